@@ -1,0 +1,15 @@
+"""CPU oracle for the forward 2-D convolution.  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg import this
+package.  It shares no code with the HIP library and never imports it.
+"""
+from .conv2d_oracle import (  # noqa: F401
+    PAD_SAME,
+    PAD_VALID,
+    build,
+    forward_f32,
+    forward_f64,
+    geometry,
+    max_threads,
+    points_f32,
+)
