@@ -1,0 +1,134 @@
+/*
+ * conv2d.h -- C ABI of the MI355X (gfx950) forward 2-D convolution library.
+ *
+ * The routine is the forward convolution that the paper (section 3,
+ * "SYCL-DNN") names as its primary optimisation target; the parameter tuple
+ * is the one in the caption of its Figure 1 (window, stride, image rows,
+ * image columns, input features, output features) plus the batch size.  The
+ * paper gives no formula, layout, padding rule or data type; the conventions
+ * below are this library's:
+ *
+ *   out[n,p,q,k] = sum_{r,s,c} X(n, p*stride_rows + r - pad_top,
+ *                                  q*stride_cols + s - pad_left, c) * filt[r,s,c,k]
+ *   X(n,h,w,c) = in[n,h,w,c] inside the image, 0 outside      (cross-correlation)
+ *
+ *   in   : [batch][in_rows][in_cols][channels]            NHWC, dense
+ *   filt : [window_rows][window_cols][channels][features] HWCF, dense
+ *   out  : [batch][out_rows][out_cols][features]          NHWC, dense
+ *
+ *   VALID: out_rows = ceil((in_rows - window_rows + 1) / stride_rows), no padding.
+ *   SAME : out_rows = ceil(in_rows / stride_rows); total padding
+ *          max((out_rows-1)*stride_rows + window_rows - in_rows, 0), of which
+ *          floor(total/2) goes before (top/left) and the rest after.
+ *   Columns alike.  Dilation 1, one group, no bias, no activation.
+ *
+ * Section 3 also says the library offers several algorithms that give the
+ * same numeric result and chooses among them (and among their parameters)
+ * per device and shape, and Figure 1's caption notes that not every
+ * algorithm supports every parameter set.  Here that is the "variant": a
+ * kernel + tile configuration.  conv2d_forward picks one from the layer
+ * shape; conv2d_forward_variant forces one and reports CONV2D_STATUS_UNSUPPORTED
+ * when it cannot run the given parameters.
+ *
+ * General rules for every call:
+ *   - All data pointers are DEVICE pointers owned by the caller; the library
+ *     never allocates, frees or keeps them.  `in` and `filt` are only read;
+ *     every element of `out` is written; `out` must not overlap the others.
+ *   - `params` and the small out-parameters are HOST pointers.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
+ *     Calls only enqueue work on it and never synchronise.
+ *   - Return value: CONV2D_STATUS_OK (0) or a negative conv2d_status_t.
+ *     Parameter validation happens before any HIP call, so it also works on a
+ *     host without a GPU.
+ *   - Element type CONV2D_F32 is IEEE binary32, CONV2D_BF16 is bfloat16
+ *     (upper 16 bits of binary32).  Accumulation is always fp32.
+ */
+#ifndef CONV2D_MI355X_H_
+#define CONV2D_MI355X_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { CONV2D_PAD_VALID = 0, CONV2D_PAD_SAME = 1 } conv2d_padding_t;
+typedef enum { CONV2D_F32 = 0, CONV2D_BF16 = 1 } conv2d_dtype_t;
+
+typedef enum {
+  CONV2D_STATUS_OK = 0,
+  CONV2D_STATUS_INVALID_ARGUMENT = -1,   /* null pointer, size <= 0, unknown enum, VALID window > image */
+  CONV2D_STATUS_UNSUPPORTED = -2,        /* forced variant / dtype pair cannot run these parameters   */
+  CONV2D_STATUS_WORKSPACE_TOO_SMALL = -3,
+  CONV2D_STATUS_LAUNCH_FAILED = -4,      /* the HIP runtime rejected a launch                          */
+  CONV2D_STATUS_TOO_LARGE = -5           /* a tensor has 2^31 or more elements                         */
+} conv2d_status_t;
+
+/* The parameter tuple of Figure 1's caption, plus batch, padding mode and
+ * element types.  All sizes are element counts. */
+typedef struct {
+  int32_t batch;        /* N >= 0 (0 = no-op) */
+  int32_t in_rows;      /* H > 0 */
+  int32_t in_cols;      /* W > 0 */
+  int32_t channels;     /* C > 0, input features  */
+  int32_t features;     /* K > 0, output features */
+  int32_t window_rows;  /* R > 0 */
+  int32_t window_cols;  /* S > 0 */
+  int32_t stride_rows;  /* > 0 */
+  int32_t stride_cols;  /* > 0 */
+  int32_t padding;      /* conv2d_padding_t */
+  int32_t in_dtype;     /* conv2d_dtype_t of `in` AND `filt` */
+  int32_t out_dtype;    /* conv2d_dtype_t of `out`; CONV2D_BF16 only with in_dtype == CONV2D_BF16 */
+} conv2d_params;
+
+typedef struct {
+  int32_t out_rows, out_cols, pad_top, pad_bottom, pad_left, pad_right;
+} conv2d_geometry;
+
+/* Output size and padding for `params` (host only, touches no GPU).
+ * INVALID_ARGUMENT if the tuple has no valid output. */
+int conv2d_get_geometry(const conv2d_params* params, conv2d_geometry* geometry);
+
+/* Bytes of device scratch that conv2d_forward may use for `params` with the
+ * variant it would select (0 for most layers; non-zero when the reduction
+ * over window and channels is split across workgroups, or the filter is
+ * repacked).  Host only. */
+int conv2d_workspace_size(const conv2d_params* params, size_t* bytes);
+
+/* Same, for a forced variant.  UNSUPPORTED if the variant cannot run `params`. */
+int conv2d_workspace_size_variant(const conv2d_params* params, int variant_id, size_t* bytes);
+
+/* Forward convolution with the variant the selector picks for the layer
+ * shape (section 3: algorithm and parameter choice per shape).
+ *   in, filt, out : device pointers, layouts above, element-aligned; the
+ *                   vectorised variants are only selected when the bases are
+ *                   16-byte aligned.
+ *   workspace     : device scratch of at least conv2d_workspace_size() bytes,
+ *                   256-byte aligned, or NULL when that size is 0.  Contents
+ *                   are undefined afterwards.
+ * Enqueues on hip_stream and returns.  batch == 0 returns OK without a launch. */
+int conv2d_forward(const conv2d_params* params, const void* in, const void* filt, void* out,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Same, with the variant forced (0 <= variant_id < conv2d_num_variants()).
+ * Every variant that supports `params` produces the same result up to the
+ * order of floating-point summation.  UNSUPPORTED if it cannot run them. */
+int conv2d_forward_variant(const conv2d_params* params, const void* in, const void* filt,
+                           void* out, void* workspace, size_t workspace_bytes, void* hip_stream,
+                           int variant_id);
+
+/* Variant introspection (host only). */
+int conv2d_num_variants(void);
+const char* conv2d_variant_name(int variant_id);            /* NULL if out of range */
+int conv2d_variant_supports(const conv2d_params* params, int variant_id); /* 1, 0, or <0 status */
+/* The variant conv2d_forward would use, assuming 16-byte-aligned pointers. */
+int conv2d_selected_variant(const conv2d_params* params, int* variant_id);
+
+const char* conv2d_status_string(int status);
+int conv2d_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONV2D_MI355X_H_ */

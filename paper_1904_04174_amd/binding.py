@@ -1,0 +1,207 @@
+"""Thin ctypes binding of the C ABI in include/conv2d.h (same names).
+
+Argument marshalling only: every step of the convolution runs in the HIP
+library.  torch is used for device memory and streams.  There is no CPU
+fallback: if the shared library is missing, loading raises.
+"""
+import ctypes
+import os
+
+PAD_VALID = 0
+PAD_SAME = 1
+F32 = 0
+BF16 = 1
+
+STATUS_OK = 0
+STATUS_INVALID_ARGUMENT = -1
+STATUS_UNSUPPORTED = -2
+STATUS_WORKSPACE_TOO_SMALL = -3
+STATUS_LAUNCH_FAILED = -4
+STATUS_TOO_LARGE = -5
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libconv2d_mi355x.so")
+
+EXPORTS = (
+    "conv2d_get_geometry", "conv2d_workspace_size", "conv2d_workspace_size_variant",
+    "conv2d_forward", "conv2d_forward_variant", "conv2d_num_variants", "conv2d_variant_name",
+    "conv2d_variant_supports", "conv2d_selected_variant", "conv2d_status_string",
+    "conv2d_version",
+)
+
+
+class Params(ctypes.Structure):
+    """conv2d_params: the parameter tuple of the paper's Figure 1 caption plus
+    batch, padding mode and element types."""
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "batch", "in_rows", "in_cols", "channels", "features", "window_rows", "window_cols",
+        "stride_rows", "stride_cols", "padding", "in_dtype", "out_dtype")]
+
+
+class Geometry(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "out_rows", "out_cols", "pad_top", "pad_bottom", "pad_left", "pad_right")]
+
+
+class Conv2dError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "%s is missing: build it with `python -m paper_1904_04174_amd.build` "
+                "(there is no CPU fallback)" % LIB_PATH)
+        l = ctypes.CDLL(LIB_PATH)
+        pp, gp = ctypes.POINTER(Params), ctypes.POINTER(Geometry)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        l.conv2d_get_geometry.argtypes = [pp, gp]
+        l.conv2d_workspace_size.argtypes = [pp, ctypes.POINTER(sz)]
+        l.conv2d_workspace_size_variant.argtypes = [pp, ctypes.c_int, ctypes.POINTER(sz)]
+        l.conv2d_forward.argtypes = [pp, vp, vp, vp, vp, sz, vp]
+        l.conv2d_forward_variant.argtypes = [pp, vp, vp, vp, vp, sz, vp, ctypes.c_int]
+        l.conv2d_num_variants.argtypes = []
+        l.conv2d_variant_name.argtypes = [ctypes.c_int]
+        l.conv2d_variant_name.restype = ctypes.c_char_p
+        l.conv2d_variant_supports.argtypes = [pp, ctypes.c_int]
+        l.conv2d_selected_variant.argtypes = [pp, ctypes.POINTER(ctypes.c_int)]
+        l.conv2d_status_string.argtypes = [ctypes.c_int]
+        l.conv2d_status_string.restype = ctypes.c_char_p
+        l.conv2d_version.argtypes = []
+        _lib = l
+    return _lib
+
+
+def make_params(batch, in_rows, in_cols, channels, features, window_rows, window_cols,
+                stride_rows=1, stride_cols=1, padding=PAD_SAME, in_dtype=F32, out_dtype=F32):
+    return Params(batch, in_rows, in_cols, channels, features, window_rows, window_cols,
+                  stride_rows, stride_cols, padding, in_dtype, out_dtype)
+
+
+def params_of_layer(layer, in_dtype=F32, out_dtype=F32, batch=None):
+    """conv2d_params for a workloads.Layer."""
+    return make_params(layer.batch if batch is None else batch, layer.in_rows, layer.in_cols,
+                       layer.channels, layer.features, layer.window_rows, layer.window_cols,
+                       layer.stride_rows, layer.stride_cols, layer.padding, in_dtype, out_dtype)
+
+
+def status_string(status):
+    return lib().conv2d_status_string(int(status)).decode()
+
+
+def conv2d_version():
+    return int(lib().conv2d_version())
+
+
+def conv2d_get_geometry(params):
+    g = Geometry()
+    rc = lib().conv2d_get_geometry(ctypes.byref(params), ctypes.byref(g))
+    if rc:
+        raise Conv2dError(rc, "conv2d_get_geometry")
+    return g
+
+
+def conv2d_workspace_size(params, variant_id=None):
+    n = ctypes.c_size_t(0)
+    if variant_id is None:
+        rc = lib().conv2d_workspace_size(ctypes.byref(params), ctypes.byref(n))
+    else:
+        rc = lib().conv2d_workspace_size_variant(ctypes.byref(params), int(variant_id),
+                                                 ctypes.byref(n))
+    if rc:
+        raise Conv2dError(rc, "conv2d_workspace_size")
+    return int(n.value)
+
+
+def conv2d_num_variants():
+    return int(lib().conv2d_num_variants())
+
+
+def conv2d_variant_name(variant_id):
+    s = lib().conv2d_variant_name(int(variant_id))
+    return None if s is None else s.decode()
+
+
+def conv2d_variant_supports(params, variant_id):
+    rc = lib().conv2d_variant_supports(ctypes.byref(params), int(variant_id))
+    if rc < 0:
+        raise Conv2dError(rc, "conv2d_variant_supports")
+    return bool(rc)
+
+
+def conv2d_selected_variant(params):
+    v = ctypes.c_int(-1)
+    rc = lib().conv2d_selected_variant(ctypes.byref(params), ctypes.byref(v))
+    if rc:
+        raise Conv2dError(rc, "conv2d_selected_variant")
+    return int(v.value)
+
+
+def variant_id_by_name(name):
+    for i in range(conv2d_num_variants()):
+        if conv2d_variant_name(i) == name:
+            return i
+    raise KeyError(name)
+
+
+def _stream_handle(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def conv2d_forward_raw(params, in_ptr, filt_ptr, out_ptr, workspace_ptr=0, workspace_bytes=0,
+                       stream_handle=0, variant_id=None):
+    """Direct pointer-level call; returns the status code without raising."""
+    l = lib()
+    if variant_id is None:
+        return l.conv2d_forward(ctypes.byref(params), in_ptr, filt_ptr, out_ptr, workspace_ptr,
+                                workspace_bytes, stream_handle)
+    return l.conv2d_forward_variant(ctypes.byref(params), in_ptr, filt_ptr, out_ptr,
+                                    workspace_ptr, workspace_bytes, stream_handle,
+                                    int(variant_id))
+
+
+def conv2d_forward(params, x, filt, out=None, workspace=None, stream=None, variant_id=None):
+    """Enqueue the forward convolution of torch device tensors.
+
+    x: NHWC, filt: HWCF, contiguous, float32 or bfloat16 matching params.in_dtype.
+    Returns `out` (allocated here if not given).  Does not synchronise.
+    """
+    import torch
+    g = conv2d_get_geometry(params)
+    want_in = torch.float32 if params.in_dtype == F32 else torch.bfloat16
+    want_out = torch.float32 if params.out_dtype == F32 else torch.bfloat16
+    if x.dtype != want_in or filt.dtype != want_in:
+        raise TypeError("input/filter dtype does not match params.in_dtype")
+    if not (x.is_cuda and filt.is_cuda and x.is_contiguous() and filt.is_contiguous()):
+        raise ValueError("input and filter must be contiguous device tensors")
+    if tuple(x.shape) != (params.batch, params.in_rows, params.in_cols, params.channels):
+        raise ValueError("input shape does not match params")
+    if tuple(filt.shape) != (params.window_rows, params.window_cols, params.channels,
+                             params.features):
+        raise ValueError("filter shape does not match params")
+    oshape = (params.batch, g.out_rows, g.out_cols, params.features)
+    if out is None:
+        out = torch.empty(oshape, dtype=want_out, device=x.device)
+    elif tuple(out.shape) != oshape or out.dtype != want_out or not out.is_contiguous():
+        raise ValueError("output tensor does not match params")
+    need = conv2d_workspace_size(params, variant_id)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else 0
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = conv2d_forward_raw(params, x.data_ptr(), filt.data_ptr(), out.data_ptr(), ws_ptr,
+                            ws_bytes, _stream_handle(stream), variant_id)
+    if rc:
+        raise Conv2dError(rc, "conv2d_forward")
+    return out

@@ -1,0 +1,47 @@
+// Internal declarations shared by the host API and the HIP kernels of the
+// forward convolution library.  Not part of the public C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace conv2d {
+
+// A fully derived problem: the public parameter tuple (Figure 1's caption in
+// the paper) plus output size and leading pads.  Implicit-GEMM view:
+//   M = N*P*Q output pixels, K output features, Kg = R*S*C reduction length
+//   ordered (r, s, c) so that the HWCF filter is the row-major [Kg][K] matrix
+//   and the NHWC output is the row-major [M][K] matrix.
+struct Problem {
+  int N, H, W, C, K;
+  int R, S, sr, sc;
+  int pt, pl;
+  int P, Q;
+  int M;        // N*P*Q
+  int Kg;       // R*S*C
+  int in_bf16;  // 0: fp32 input/filter, 1: bf16
+  int out_bf16; // 0: fp32 output, 1: bf16
+  const void* in;
+  const void* filt;
+  void* out;
+  void* workspace;
+};
+
+// Launchers (one per kernel family).  Each returns hipSuccess or the launch
+// error; none synchronises.  `tile` selects a compiled tile configuration.
+hipError_t launch_direct(const Problem& p, hipStream_t stream);
+
+// fp32 implicit GEMM on v_mfma_f32_32x32x2_f32.
+int igemm_f32_num_tiles();
+const char* igemm_f32_tile_name(int tile);
+void igemm_f32_tile_shape(int tile, int* bm, int* bn, int* bk);
+hipError_t launch_igemm_f32(const Problem& p, int tile, hipStream_t stream);
+
+// bf16 implicit GEMM on v_mfma_f32_32x32x16_bf16.
+int igemm_bf16_num_tiles();
+const char* igemm_bf16_tile_name(int tile);
+void igemm_bf16_tile_shape(int tile, int* bm, int* bn, int* bk);
+hipError_t launch_igemm_bf16(const Problem& p, int tile, hipStream_t stream);
+
+}  // namespace conv2d

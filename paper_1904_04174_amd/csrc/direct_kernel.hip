@@ -1,0 +1,85 @@
+// Direct forward convolution: one lane per output element, features fastest
+// across lanes.  This is the variant that supports every parameter set (any
+// window, stride, padding, channel count, alignment, fp32 or bf16); the
+// paper's section 3 calls its own counterpart a naive kernel that runs one
+// thread per output vector.  It is the fallback of the selector and the
+// baseline the MFMA variants must agree with.
+#include "conv2d_internal.h"
+
+namespace conv2d {
+namespace {
+
+__device__ __forceinline__ float bf16_bits_to_float(unsigned short b) {
+  return __uint_as_float(static_cast<unsigned int>(b) << 16);
+}
+
+// fp32 -> bf16, round to nearest, ties to even; NaN stays NaN.
+__device__ __forceinline__ unsigned short float_to_bf16_bits(float x) {
+  unsigned int u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<unsigned short>((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<unsigned short>(u >> 16);
+}
+
+template <bool IN_BF16, bool OUT_BF16>
+__global__ __launch_bounds__(256) void direct_kernel(Problem p) {
+  const long long total = static_cast<long long>(p.M) * p.K;
+  const long long stride = static_cast<long long>(gridDim.x) * blockDim.x;
+  for (long long idx = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x; idx < total;
+       idx += stride) {
+    const int k = static_cast<int>(idx % p.K);
+    const int m = static_cast<int>(idx / p.K);
+    const int q = m % p.Q;
+    const int t = m / p.Q;
+    const int op = t % p.P;
+    const int n = t / p.P;
+    const int h0 = op * p.sr - p.pt;
+    const int w0 = q * p.sc - p.pl;
+    float acc = 0.f;
+    for (int r = 0; r < p.R; ++r) {
+      const int h = h0 + r;
+      if (h < 0 || h >= p.H) continue;
+      for (int s = 0; s < p.S; ++s) {
+        const int w = w0 + s;
+        if (w < 0 || w >= p.W) continue;
+        const long long xoff = ((static_cast<long long>(n) * p.H + h) * p.W + w) * p.C;
+        const long long foff = (static_cast<long long>(r) * p.S + s) * p.C * p.K + k;
+        if (IN_BF16) {
+          const unsigned short* x = static_cast<const unsigned short*>(p.in) + xoff;
+          const unsigned short* f = static_cast<const unsigned short*>(p.filt) + foff;
+          for (int c = 0; c < p.C; ++c)
+            acc = fmaf(bf16_bits_to_float(x[c]), bf16_bits_to_float(f[static_cast<long long>(c) * p.K]), acc);
+        } else {
+          const float* x = static_cast<const float*>(p.in) + xoff;
+          const float* f = static_cast<const float*>(p.filt) + foff;
+          for (int c = 0; c < p.C; ++c) acc = fmaf(x[c], f[static_cast<long long>(c) * p.K], acc);
+        }
+      }
+    }
+    if (OUT_BF16)
+      static_cast<unsigned short*>(p.out)[idx] = float_to_bf16_bits(acc);
+    else
+      static_cast<float*>(p.out)[idx] = acc;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_direct(const Problem& p, hipStream_t stream) {
+  const long long total = static_cast<long long>(p.M) * p.K;
+  long long blocks = (total + 255) / 256;
+  if (blocks > 256LL * 64) blocks = 256LL * 64;  // grid-stride loop covers the rest
+  if (blocks < 1) blocks = 1;
+  dim3 grid(static_cast<unsigned>(blocks)), block(256);
+  if (p.in_bf16) {
+    if (p.out_bf16)
+      hipLaunchKernelGGL((direct_kernel<true, true>), grid, block, 0, stream, p);
+    else
+      hipLaunchKernelGGL((direct_kernel<true, false>), grid, block, 0, stream, p);
+  } else {
+    hipLaunchKernelGGL((direct_kernel<false, false>), grid, block, 0, stream, p);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace conv2d

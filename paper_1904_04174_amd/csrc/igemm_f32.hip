@@ -1,0 +1,290 @@
+// fp32 forward convolution as an implicit GEMM on the CDNA4 matrix cores
+// (v_mfma_f32_32x32x2_f32), for gfx950.
+//
+// GEMM view of the convolution of the paper's section 3:
+//   D[M][K] = A[M][Kg] * B[Kg][K],  M = N*P*Q, Kg = R*S*C ordered (r,s,c).
+//   B is the HWCF filter as it lies in memory, D is the NHWC output as it
+//   lies in memory, and row m of A is gathered on the fly from the NHWC
+//   input: R*S runs of C contiguous floats, or zeros where the window hangs
+//   over the border.
+//
+// One workgroup (4 wavefronts of 64 lanes) owns a BM x BN tile of D.  Per
+// BK-wide slice of Kg it stages the A and B tiles in LDS (k contiguous per
+// row, so one 16-byte LDS read gives a lane four consecutive k of its row),
+// and each wavefront multiplies its WM x WN sub-tile with 32x32x2 MFMAs.
+// Global loads of slice i+1 are in flight while slice i is multiplied
+// (register-staged double buffering, one barrier per slice).
+//
+// Requirements (checked by the host before launch): C % 4 == 0, K % 4 == 0,
+// 16-byte aligned in/filt, every tensor below 2^31 elements.
+#include "conv2d_internal.h"
+
+namespace conv2d {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kXcds = 8;  // workgroups are dealt round-robin over the 8 XCDs
+
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_>
+struct Tile {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_;
+  static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+  static constexpr int NT = 64 * WAVES_M * WAVES_N;
+  static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  static constexpr int TM = WM / 32, TN = WN / 32;
+  static constexpr int LD = BK + 4;  // LDS row stride in floats (16-byte reads stay conflict free)
+  static constexpr int KV = BK / 4;  // 16-byte vectors per A row
+  static constexpr int A_ROWS_PER_PASS = NT / KV;
+  static constexpr int A_ITERS = BM / A_ROWS_PER_PASS;
+  static constexpr int B_BLOCKS = (BK / 4) * (BN / 4);  // 4(k) x 4(n) blocks
+  static constexpr int B_ITERS = (B_BLOCKS + NT - 1) / NT;
+  static constexpr int LDS_FLOATS = 2 * (BM + BN) * LD;
+  static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of 32x32");
+  static_assert(BK % 8 == 0, "BK must be a multiple of 8");
+  static_assert(BM % A_ROWS_PER_PASS == 0, "A tile must divide evenly over the threads");
+};
+
+template <class T>
+__global__ __launch_bounds__(T::NT) void igemm_f32_kernel(const Problem p) {
+  constexpr int BM = T::BM, BN = T::BN, BK = T::BK, LD = T::LD, NT = T::NT;
+  extern __shared__ __align__(16) float lds[];
+  float* As = lds;                     // [2][BM][LD]
+  float* Bs = lds + 2 * BM * LD;       // [2][BN][LD]
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave / T::WAVES_N;
+  const int wn = wave % T::WAVES_N;
+  const int lr = lane & 31;   // row (A) / column (B, D) inside a 32x32 MFMA tile
+  const int lk = lane >> 5;   // which half of the k pair this lane feeds
+
+  // Tile of this workgroup.  Workgroup i runs on XCD i % 8; give each XCD a
+  // contiguous range of tiles so that neighbours share input rows in its L2,
+  // and walk feature tiles fastest so that an A tile is reused while hot.
+  const int tiles_n = (p.K + BN - 1) / BN;
+  const int nwg = gridDim.x;
+  const int xcd = blockIdx.x % kXcds;
+  const int local = blockIdx.x / kXcds;
+  const int per = nwg / kXcds, rem = nwg % kXcds;
+  const int tile = xcd * per + (xcd < rem ? xcd : rem) + local;
+  const int m0 = (tile / tiles_n) * BM;
+  const int n0 = (tile % tiles_n) * BN;
+
+  const float* __restrict__ in = static_cast<const float*>(p.in);
+  const float* __restrict__ filt = static_cast<const float*>(p.filt);
+
+  // ---- per-thread description of the A rows it gathers
+  const int a_kv = tid % T::KV;
+  const int a_row0 = tid / T::KV;
+  int a_base[T::A_ITERS], a_h0[T::A_ITERS], a_w0[T::A_ITERS];
+#pragma unroll
+  for (int i = 0; i < T::A_ITERS; ++i) {
+    const int m = m0 + a_row0 + i * T::A_ROWS_PER_PASS;
+    if (m < p.M) {
+      const int q = m % p.Q;
+      const int t = m / p.Q;
+      const int op = t % p.P;
+      const int n = t / p.P;
+      a_base[i] = n * p.H * p.W * p.C;
+      a_h0[i] = op * p.sr - p.pt;
+      a_w0[i] = q * p.sc - p.pl;
+    } else {
+      a_base[i] = 0;
+      a_h0[i] = -(1 << 28);  // every tap fails the bounds test
+      a_w0[i] = 0;
+    }
+  }
+  // (r, s, c) of this thread's 4-wide k vector in the current slice
+  int kc, ks, kr;
+  {
+    const int kg = a_kv * 4;
+    kc = kg % p.C;
+    const int t = kg / p.C;
+    ks = t % p.S;
+    kr = t / p.S;
+  }
+
+  float4 a_reg[T::A_ITERS];
+  float4 b_reg[T::B_ITERS][4];
+
+  auto load_a = [&]() {
+#pragma unroll
+    for (int i = 0; i < T::A_ITERS; ++i) {
+      const int h = a_h0[i] + kr;
+      const int w = a_w0[i] + ks;
+      const bool ok = (kr < p.R) && (static_cast<unsigned>(h) < static_cast<unsigned>(p.H)) &&
+                      (static_cast<unsigned>(w) < static_cast<unsigned>(p.W));
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (ok) v = *reinterpret_cast<const float4*>(in + a_base[i] + (h * p.W + w) * p.C + kc);
+      a_reg[i] = v;
+    }
+  };
+  auto advance_a = [&]() {
+    kc += BK;
+    while (kc >= p.C) {
+      kc -= p.C;
+      if (++ks == p.S) { ks = 0; ++kr; }
+    }
+  };
+  auto load_b = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < T::B_ITERS; ++i) {
+      const int b = tid + i * NT;
+      const int nb4 = b % (BN / 4);
+      const int kb = b / (BN / 4);
+      const int col = n0 + nb4 * 4;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int kg = k0 + kb * 4 + j;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (b < T::B_BLOCKS && kg < p.Kg && col < p.K)
+          v = *reinterpret_cast<const float4*>(filt + static_cast<size_t>(kg) * p.K + col);
+        b_reg[i][j] = v;
+      }
+    }
+  };
+  auto store_tiles = [&](int buf) {
+    float* as = As + buf * BM * LD;
+    float* bs = Bs + buf * BN * LD;
+#pragma unroll
+    for (int i = 0; i < T::A_ITERS; ++i)
+      *reinterpret_cast<float4*>(as + (a_row0 + i * T::A_ROWS_PER_PASS) * LD + a_kv * 4) = a_reg[i];
+#pragma unroll
+    for (int i = 0; i < T::B_ITERS; ++i) {
+      const int b = tid + i * NT;
+      if (b < T::B_BLOCKS) {
+        const int nb4 = b % (BN / 4);
+        const int kb = b / (BN / 4);
+        // 4x4 transpose in registers: LDS keeps B as [n][k], k contiguous
+        float* dst = bs + (nb4 * 4) * LD + kb * 4;
+        *reinterpret_cast<float4*>(dst + 0 * LD) =
+            make_float4(b_reg[i][0].x, b_reg[i][1].x, b_reg[i][2].x, b_reg[i][3].x);
+        *reinterpret_cast<float4*>(dst + 1 * LD) =
+            make_float4(b_reg[i][0].y, b_reg[i][1].y, b_reg[i][2].y, b_reg[i][3].y);
+        *reinterpret_cast<float4*>(dst + 2 * LD) =
+            make_float4(b_reg[i][0].z, b_reg[i][1].z, b_reg[i][2].z, b_reg[i][3].z);
+        *reinterpret_cast<float4*>(dst + 3 * LD) =
+            make_float4(b_reg[i][0].w, b_reg[i][1].w, b_reg[i][2].w, b_reg[i][3].w);
+      }
+    }
+  };
+
+  floatx16 acc[T::TM][T::TN];
+#pragma unroll
+  for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+    for (int j = 0; j < T::TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nslices = (p.Kg + BK - 1) / BK;
+  load_a();
+  load_b(0);
+  store_tiles(0);
+  __syncthreads();
+
+  for (int slice = 0; slice < nslices; ++slice) {
+    const int buf = slice & 1;
+    const bool more = slice + 1 < nslices;
+    if (more) {
+      advance_a();
+      load_a();
+      load_b((slice + 1) * BK);
+    }
+    const float* as = As + buf * BM * LD + (wm * T::WM + lr) * LD + lk * 4;
+    const float* bs = Bs + buf * BN * LD + (wn * T::WN + lr) * LD + lk * 4;
+#pragma unroll
+    for (int k8 = 0; k8 < BK / 8; ++k8) {
+      float4 af[T::TM], bf[T::TN];
+#pragma unroll
+      for (int i = 0; i < T::TM; ++i)
+        af[i] = *reinterpret_cast<const float4*>(as + i * 32 * LD + k8 * 8);
+#pragma unroll
+      for (int j = 0; j < T::TN; ++j)
+        bf[j] = *reinterpret_cast<const float4*>(bs + j * 32 * LD + k8 * 8);
+#pragma unroll
+      for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < T::TN; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].x, bf[j].x, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].y, bf[j].y, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].z, bf[j].z, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].w, bf[j].w, acc[i][j], 0, 0, 0);
+        }
+    }
+    if (more) store_tiles(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: D tile -> NHWC output.  In a 32x32 accumulator, lane l
+  // register v holds row 8*(v/4) + 4*(l/32) + v%4, column l%32, so each
+  // store instruction writes two 128-byte row segments.
+  float* __restrict__ out = static_cast<float*>(p.out);
+#pragma unroll
+  for (int i = 0; i < T::TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < T::TN; ++j) {
+      const int col = n0 + wn * T::WN + j * 32 + lr;
+      const int rbase = m0 + wm * T::WM + i * 32 + lk * 4;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = rbase + 8 * (v / 4) + (v % 4);
+        if (row < p.M && col < p.K) out[static_cast<size_t>(row) * p.K + col] = acc[i][j][v];
+      }
+    }
+  }
+}
+
+template <class T>
+hipError_t launch(const Problem& p, hipStream_t stream) {
+  const int tiles_m = (p.M + T::BM - 1) / T::BM;
+  const int tiles_n = (p.K + T::BN - 1) / T::BN;
+  const size_t lds_bytes = sizeof(float) * T::LDS_FLOATS;
+  static bool attr_set = false;
+  if (!attr_set && lds_bytes > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_f32_kernel<T>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       static_cast<int>(lds_bytes));
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((igemm_f32_kernel<T>), dim3(tiles_m * tiles_n), dim3(T::NT), lds_bytes, stream,
+                     p);
+  return hipGetLastError();
+}
+
+struct TileEntry {
+  const char* name;
+  int bm, bn, bk;
+  hipError_t (*fn)(const Problem&, hipStream_t);
+};
+
+#define CONV2D_F32_TILE(bm, bn, bk, wm, wn) \
+  { "igemm_f32_" #bm "x" #bn "x" #bk, bm, bn, bk, &launch<Tile<bm, bn, bk, wm, wn>> }
+
+const TileEntry kTiles[] = {
+    CONV2D_F32_TILE(256, 128, 16, 2, 2),
+    CONV2D_F32_TILE(128, 128, 16, 2, 2),
+    CONV2D_F32_TILE(256, 64, 16, 4, 1),
+    CONV2D_F32_TILE(128, 64, 16, 2, 2),
+    CONV2D_F32_TILE(64, 64, 16, 2, 2),
+    CONV2D_F32_TILE(128, 32, 16, 4, 1),
+};
+constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+
+}  // namespace
+
+int igemm_f32_num_tiles() { return kNumTiles; }
+const char* igemm_f32_tile_name(int tile) { return kTiles[tile].name; }
+void igemm_f32_tile_shape(int tile, int* bm, int* bn, int* bk) {
+  *bm = kTiles[tile].bm;
+  *bn = kTiles[tile].bn;
+  *bk = kTiles[tile].bk;
+}
+hipError_t launch_igemm_f32(const Problem& p, int tile, hipStream_t stream) {
+  return kTiles[tile].fn(p, stream);
+}
+
+}  // namespace conv2d

@@ -1,0 +1,169 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every
+declared symbol, derives the same geometry as the oracle, reports errors, and
+its selector only picks variants that support the parameters."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1904_04174_amd import binding as B
+from paper_1904_04174_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "conv2d.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(conv2d_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert len(names) >= 11
+    assert set(names) == set(B.EXPORTS)
+    raw = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert getattr(raw, n) is not None
+
+
+def test_version_and_status_strings():
+    assert B.conv2d_version() >= 100
+    assert B.status_string(0) == "ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert B.status_string(code) not in ("ok", "unknown status")
+    assert B.status_string(-99) == "unknown status"
+
+
+def test_variant_table():
+    n = B.conv2d_num_variants()
+    assert n >= 2
+    names = [B.conv2d_variant_name(i) for i in range(n)]
+    assert names[0] == "direct"
+    assert len(set(names)) == n
+    assert B.conv2d_variant_name(n) is None and B.conv2d_variant_name(-1) is None
+
+
+def test_geometry_matches_oracle(oracle):
+    rng = np.random.default_rng(5)
+    checked = 0
+    for _ in range(400):
+        h, w = int(rng.integers(1, 40)), int(rng.integers(1, 40))
+        r, s = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+        sr, sc = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        pad = int(rng.integers(0, 2))
+        p = B.make_params(2, h, w, 3, 5, r, s, sr, sc, pad)
+        try:
+            want = oracle.geometry(h, w, r, s, sr, sc, pad)
+        except ValueError:
+            with pytest.raises(B.Conv2dError) as ei:
+                B.conv2d_get_geometry(p)
+            assert ei.value.status == B.STATUS_INVALID_ARGUMENT
+            continue
+        g = B.conv2d_get_geometry(p)
+        assert (g.out_rows, g.out_cols, g.pad_top, g.pad_bottom, g.pad_left, g.pad_right) == want
+        checked += 1
+    assert checked > 200
+
+
+def test_geometry_of_named_layers():
+    want = {"R7x7": (112, 2, 3), "L-s2": (28, 0, 1), "R1x1s2": (14, 0, 0), "L-valid": (54, 0, 0),
+            "V224-N16": (224, 1, 1), "L-s2valid": (27, 0, 0)}
+    for name, (o, a, b) in want.items():
+        g = B.conv2d_get_geometry(B.params_of_layer(wl.LAYERS[name]))
+        assert (g.out_rows, g.pad_top, g.pad_bottom) == (o, a, b)
+        assert (g.out_cols, g.pad_left, g.pad_right) == (o, a, b)
+
+
+BAD = [
+    dict(batch=-1), dict(in_rows=0), dict(in_cols=-3), dict(channels=0), dict(features=0),
+    dict(window_rows=0), dict(window_cols=0), dict(stride_rows=0), dict(stride_cols=-1),
+    dict(padding=2), dict(in_dtype=5), dict(out_dtype=-1),
+    dict(padding=B.PAD_VALID, in_rows=2, window_rows=3),
+]
+
+
+@pytest.mark.parametrize("bad", BAD)
+def test_invalid_parameters_are_rejected_before_any_launch(bad):
+    kw = dict(batch=1, in_rows=8, in_cols=8, channels=4, features=4, window_rows=3, window_cols=3,
+              stride_rows=1, stride_cols=1, padding=B.PAD_SAME, in_dtype=B.F32, out_dtype=B.F32)
+    kw.update(bad)
+    p = B.make_params(**kw)
+    # non-null dummy pointers: validation must fail before they are touched
+    rc = B.conv2d_forward_raw(p, 16, 16, 16)
+    assert rc == B.STATUS_INVALID_ARGUMENT
+    rc = B.conv2d_forward_raw(p, 16, 16, 16, variant_id=0)
+    assert rc == B.STATUS_INVALID_ARGUMENT
+    with pytest.raises(B.Conv2dError):
+        B.conv2d_workspace_size(p)
+
+
+def test_null_pointers_and_bad_variant_ids():
+    p = B.make_params(1, 8, 8, 4, 4, 3, 3)
+    assert B.conv2d_forward_raw(p, 0, 16, 16) == B.STATUS_INVALID_ARGUMENT
+    assert B.conv2d_forward_raw(p, 16, 0, 16) == B.STATUS_INVALID_ARGUMENT
+    assert B.conv2d_forward_raw(p, 16, 16, 0) == B.STATUS_INVALID_ARGUMENT
+    assert B.conv2d_forward_raw(p, 16, 16, 16, variant_id=10 ** 6) == B.STATUS_INVALID_ARGUMENT
+    assert B.conv2d_forward_raw(p, 16, 16, 16, variant_id=-1) == B.STATUS_INVALID_ARGUMENT
+    assert B.lib().conv2d_get_geometry(None, None) == B.STATUS_INVALID_ARGUMENT
+    assert B.lib().conv2d_workspace_size(ctypes.byref(p), None) == B.STATUS_INVALID_ARGUMENT
+
+
+def test_empty_batch_is_a_noop_without_pointers():
+    p = B.make_params(0, 8, 8, 4, 4, 3, 3)
+    assert B.conv2d_forward_raw(p, 0, 0, 0) == B.STATUS_OK
+
+
+def test_f32_in_bf16_out_is_unsupported():
+    p = B.make_params(1, 8, 8, 8, 8, 3, 3, in_dtype=B.F32, out_dtype=B.BF16)
+    assert B.conv2d_forward_raw(p, 16, 16, 16) == B.STATUS_UNSUPPORTED
+
+
+def test_too_large_is_reported():
+    p = B.make_params(4096, 1024, 1024, 64, 64, 3, 3)
+    assert B.conv2d_forward_raw(p, 16, 16, 16) == B.STATUS_TOO_LARGE
+
+
+def test_forced_variant_that_cannot_run_is_unsupported():
+    # C = 3 cannot use the 16-byte gathers of the implicit-GEMM variants
+    p = B.make_params(1, 8, 8, 3, 8, 3, 3)
+    n = B.conv2d_num_variants()
+    unsupported = [i for i in range(n) if not B.conv2d_variant_supports(p, i)]
+    assert unsupported, "expected at least one variant to refuse C=3"
+    for i in unsupported:
+        assert B.conv2d_forward_raw(p, 16, 16, 16, variant_id=i) == B.STATUS_UNSUPPORTED
+    assert B.conv2d_variant_supports(p, 0)
+    # a misaligned pointer also makes a vectorised variant refuse
+    p = B.make_params(1, 8, 8, 8, 8, 3, 3)
+    vec = [i for i in range(1, n) if B.conv2d_variant_supports(p, i)]
+    assert vec
+    assert B.conv2d_forward_raw(p, 4, 16, 16, variant_id=vec[0]) == B.STATUS_UNSUPPORTED
+
+
+def test_selector_only_picks_supported_variants():
+    rng = np.random.default_rng(9)
+    layers = list(wl.LAYERS.values())
+    for i in range(300):
+        if i < len(layers):
+            L = layers[i]
+            shapes = [B.params_of_layer(L, dt, B.F32) for dt in (B.F32, B.BF16)]
+        else:
+            shapes = [B.make_params(int(rng.integers(1, 5)), int(rng.integers(1, 30)),
+                                    int(rng.integers(1, 30)), int(rng.integers(1, 70)),
+                                    int(rng.integers(1, 70)), int(rng.integers(1, 4)),
+                                    int(rng.integers(1, 4)), int(rng.integers(1, 3)),
+                                    int(rng.integers(1, 3)), B.PAD_SAME,
+                                    int(rng.integers(0, 2)), B.F32)]
+        for p in shapes:
+            v = B.conv2d_selected_variant(p)
+            assert 0 <= v < B.conv2d_num_variants()
+            assert B.conv2d_variant_supports(p, v)
+            assert B.conv2d_workspace_size(p) >= 0
+
+
+def test_compute_bound_layers_use_the_matrix_cores():
+    for name in wl.VGG_N16 + ["L-same", "L-valid", "L-s2", "R3x3"]:
+        v = B.conv2d_selected_variant(B.params_of_layer(wl.LAYERS[name]))
+        assert B.conv2d_variant_name(v).startswith("igemm_f32"), name

@@ -1,0 +1,244 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle,
+element by element, on the same seeded inputs.
+
+Tolerances (the paper's section 3 says all algorithms give the same numeric
+result; in floating point that means "up to summation order"):
+  fp32           : max |gpu - oracle| / (|oracle| + 1) <= 1e-4
+  bf16 in, fp32 accumulate: <= 2e-2 against the oracle run on the bf16-rounded inputs
+  integer-valued inputs   : bit-exact (every summation order gives the same fp32 sum)
+"""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_1904_04174_amd import binding as B
+from paper_1904_04174_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4
+TOL_BF16 = 2e-2
+
+
+def _say(msg):
+    sys.stdout.write("[parity] %s\n" % msg)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch
+
+
+def rel_err(got, want):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    if want.size == 0:
+        return 0.0
+    return float(np.max(np.abs(got - want) / (np.abs(want) + 1.0)))
+
+
+def run_gpu(torch, params, x, f, variant_id=None, guard=True):
+    """Runs the library on numpy inputs; returns the output as a numpy array.
+    The output buffer is poisoned with NaN and sits between two guard bands."""
+    dev = torch.device("cuda:0")
+    in_dt = torch.float32 if params.in_dtype == B.F32 else torch.bfloat16
+    out_dt = torch.float32 if params.out_dtype == B.F32 else torch.bfloat16
+    xd = torch.from_numpy(x).to(dev).to(in_dt).contiguous()
+    fd = torch.from_numpy(f).to(dev).to(in_dt).contiguous()
+    g = B.conv2d_get_geometry(params)
+    oshape = (params.batch, g.out_rows, g.out_cols, params.features)
+    n = int(np.prod(oshape))
+    band = 1024
+    buf = torch.full((n + 2 * band,), float("nan"), dtype=out_dt, device=dev)
+    out = buf[band:band + n].view(oshape)
+    B.conv2d_forward(params, xd, fd, out=out, variant_id=variant_id)
+    torch.cuda.synchronize()
+    if guard:
+        assert bool(torch.isnan(buf[:band]).all()) and bool(torch.isnan(buf[band + n:]).all()), \
+            "store outside the output tensor"
+    res = out.float().cpu().numpy()
+    assert not np.isnan(res).any(), "an output element was not written"
+    return res
+
+
+def supported_variants(params):
+    return [i for i in range(B.conv2d_num_variants()) if B.conv2d_variant_supports(params, i)]
+
+
+# (N, H, W, C, K, R, S, sr, sc, pad) -- small enough for the oracle in milliseconds, large
+# enough to span several tiles of every configuration and leave ragged tails in M, K and Kg.
+SMALL = [
+    (1, 8, 8, 4, 4, 3, 3, 1, 1, wl.PAD_SAME),          # the tiny config
+    (2, 13, 11, 8, 12, 3, 3, 1, 1, wl.PAD_SAME),
+    (3, 17, 19, 20, 36, 3, 3, 1, 1, wl.PAD_VALID),
+    (2, 23, 21, 16, 72, 3, 3, 2, 2, wl.PAD_SAME),      # pads 0/1
+    (1, 30, 30, 12, 132, 3, 3, 2, 1, wl.PAD_VALID),
+    (5, 16, 16, 64, 64, 1, 1, 1, 1, wl.PAD_SAME),
+    (3, 15, 15, 36, 40, 1, 1, 2, 2, wl.PAD_SAME),
+    (2, 20, 18, 4, 8, 7, 7, 2, 2, wl.PAD_SAME),        # pads 2/3
+    (1, 9, 12, 8, 260, 5, 3, 1, 2, wl.PAD_SAME),
+    (2, 6, 6, 24, 16, 3, 3, 3, 3, wl.PAD_SAME),        # stride == window
+    (1, 3, 3, 8, 8, 5, 5, 1, 1, wl.PAD_SAME),          # window larger than the image
+    (300, 2, 2, 8, 8, 2, 2, 1, 1, wl.PAD_SAME),        # many tiny images: tiles span images
+    (1, 40, 40, 3, 16, 7, 7, 2, 2, wl.PAD_SAME),       # C = 3 (only the general variants)
+    (2, 9, 9, 5, 7, 3, 3, 1, 1, wl.PAD_SAME),          # odd C and K
+    (1, 33, 33, 128, 128, 3, 3, 1, 1, wl.PAD_SAME),    # deep reduction, >1 tile of 256 rows
+]
+
+
+def _params(case, in_dtype=B.F32, out_dtype=B.F32):
+    n, h, w, c, k, r, s, sr, sc, pad = case
+    return B.make_params(n, h, w, c, k, r, s, sr, sc, pad, in_dtype, out_dtype)
+
+
+@pytest.mark.parametrize("case", SMALL)
+def test_every_variant_matches_oracle_fp32(torch_cuda, oracle, case):
+    n, h, w, c, k, r, s, sr, sc, pad = case
+    x, f = wl.make_case((n, h, w, c), (r, s, c, k), "uniform", 7000 + sum(case))
+    want = oracle.forward_f32(x, f, (sr, sc), pad)
+    p = _params(case)
+    ids = supported_variants(p)
+    assert 0 in ids
+    for vid in ids + [None]:
+        _say("fp32 case %s variant %s" % (case, "auto" if vid is None else B.conv2d_variant_name(vid)))
+        got = run_gpu(torch_cuda, p, x, f, vid)
+        assert got.shape == want.shape
+        err = rel_err(got, want)
+        assert err <= TOL_F32, (case, vid, err)
+
+
+@pytest.mark.parametrize("case", SMALL)
+def test_integer_inputs_are_bit_exact_fp32(torch_cuda, oracle, case):
+    n, h, w, c, k, r, s, sr, sc, pad = case
+    x, f = wl.make_case((n, h, w, c), (r, s, c, k), "ints", 8000 + sum(case))
+    want = oracle.forward_f32(x, f, (sr, sc), pad)
+    p = _params(case)
+    for vid in supported_variants(p):
+        _say("ints fp32 case %s variant %s" % (case, B.conv2d_variant_name(vid)))
+        got = run_gpu(torch_cuda, p, x, f, vid)
+        assert np.array_equal(got, want), (case, vid)
+
+
+@pytest.mark.parametrize("case", SMALL)
+def test_every_variant_matches_oracle_bf16(torch_cuda, oracle, case):
+    n, h, w, c, k, r, s, sr, sc, pad = case
+    x, f = wl.make_case((n, h, w, c), (r, s, c, k), "uniform", 9000 + sum(case))
+    x, _ = wl.round_to_bf16(x)
+    f, _ = wl.round_to_bf16(f)
+    want = oracle.forward_f32(x, f, (sr, sc), pad)
+    xi, fi = wl.make_case((n, h, w, c), (r, s, c, k), "ints", 9500 + sum(case))
+    want_i = oracle.forward_f32(xi, fi, (sr, sc), pad)
+    for out_dtype in (B.F32, B.BF16):
+        p = _params(case, B.BF16, out_dtype)
+        for vid in supported_variants(p) + [None]:
+            _say("bf16 case %s out %d variant %s" % (
+                case, out_dtype, "auto" if vid is None else B.conv2d_variant_name(vid)))
+            got = run_gpu(torch_cuda, p, x, f, vid)
+            err = rel_err(got, want)
+            assert err <= TOL_BF16, (case, vid, out_dtype, err)
+            if out_dtype == B.F32:
+                # integers in [-4,4] are exact in bf16 and their sums in fp32
+                got_i = run_gpu(torch_cuda, p, xi, fi, vid)
+                assert np.array_equal(got_i, want_i), (case, vid)
+
+
+def test_all_ones_closed_form_on_gpu(torch_cuda):
+    # count of valid taps times C, asymmetric SAME padding (pads 2 before / 3 after)
+    p = B.make_params(2, 8, 8, 8, 8, 7, 7, 2, 2, wl.PAD_SAME)
+    x = np.ones((2, 8, 8, 8), np.float32)
+    f = np.ones((7, 7, 8, 8), np.float32)
+    rows = np.array([5, 7, 6, 4], dtype=np.float32)
+    want = 8 * np.outer(rows, rows)
+    for vid in supported_variants(p):
+        got = run_gpu(torch_cuda, p, x, f, vid)
+        for n in range(2):
+            for k in range(8):
+                assert np.array_equal(got[n, :, :, k], want), B.conv2d_variant_name(vid)
+
+
+def test_same_input_twice_gives_identical_bits(torch_cuda):
+    case = (2, 23, 21, 16, 72, 3, 3, 2, 2, wl.PAD_SAME)
+    n, h, w, c, k, r, s, sr, sc, pad = case
+    x, f = wl.make_case((n, h, w, c), (r, s, c, k), "normal", 77)
+    p = _params(case)
+    for vid in supported_variants(p):
+        a = run_gpu(torch_cuda, p, x, f, vid)
+        b = run_gpu(torch_cuda, p, x, f, vid)
+        assert np.array_equal(a, b), B.conv2d_variant_name(vid)
+
+
+def test_runs_on_a_side_stream(torch_cuda, oracle):
+    torch = torch_cuda
+    L = wl.LAYERS["T1"]
+    x, f = wl.make_inputs(L)
+    want = oracle.forward_f32(x, f, 1, L.padding)
+    p = B.params_of_layer(L)
+    xd, fd = torch.from_numpy(x).cuda(), torch.from_numpy(f).cuda()
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        out = B.conv2d_forward(p, xd, fd, stream=s)
+    s.synchronize()
+    assert rel_err(out.cpu().numpy(), want) <= TOL_F32
+
+
+def test_empty_batch_on_gpu(torch_cuda):
+    torch = torch_cuda
+    p = B.make_params(0, 8, 8, 4, 4, 3, 3)
+    x = torch.empty((0, 8, 8, 4), device="cuda")
+    f = torch.ones((3, 3, 4, 4), device="cuda")
+    out = B.conv2d_forward(p, x, f)
+    assert tuple(out.shape) == (0, 8, 8, 4)
+
+
+# ------------------------------------------------------------------ full-size layers
+
+FP32_FULL = ["T1"] + wl.VGG_N1 + wl.VGG_N16 + ["R7x7", "R1x1a", "R1x1b", "R3x3", "R1x1s2",
+                                                "L-same", "L-valid", "L-s2", "L-s2valid"]
+
+
+@pytest.mark.parametrize("name", FP32_FULL)
+def test_full_size_layer_fp32(torch_cuda, oracle, name):
+    """The layer at its full size, with the variant the selector picks (the
+    launch configuration the benchmark times), against the whole oracle output."""
+    L = wl.LAYERS[name]
+    x, f = wl.make_inputs(L)
+    p = B.params_of_layer(L)
+    _say("full fp32 %s variant %s" % (name, B.conv2d_variant_name(B.conv2d_selected_variant(p))))
+    got = run_gpu(torch_cuda, p, x, f)
+    want = oracle.forward_f32(x, f, (L.stride_rows, L.stride_cols), L.padding)
+    err = rel_err(got, want)
+    _say("full fp32 %s err %.3g" % (name, err))
+    assert err <= TOL_F32, (name, err)
+
+
+@pytest.mark.parametrize("name", ["V56-N16", "R7x7", "L-s2", "R1x1s2"])
+def test_full_size_layer_integer_exact(torch_cuda, oracle, name):
+    L = wl.LAYERS[name]
+    x, f = wl.make_inputs(L, dist="ints")
+    p = B.params_of_layer(L)
+    _say("full ints %s" % name)
+    got = run_gpu(torch_cuda, p, x, f)
+    want = oracle.forward_f32(x, f, (L.stride_rows, L.stride_cols), L.padding)
+    assert np.array_equal(got, want), name
+
+
+@pytest.mark.parametrize("name", wl.BF16_LAYERS)
+@pytest.mark.parametrize("out_dtype", [B.F32, B.BF16])
+def test_full_size_layer_bf16(torch_cuda, oracle, name, out_dtype):
+    L = wl.LAYERS[name]
+    x, f = wl.make_inputs(L, dist="uniform")
+    x, _ = wl.round_to_bf16(x)
+    f, _ = wl.round_to_bf16(f)
+    p = B.params_of_layer(L, B.BF16, out_dtype)
+    _say("full bf16 %s out %d variant %s" % (
+        name, out_dtype, B.conv2d_variant_name(B.conv2d_selected_variant(p))))
+    got = run_gpu(torch_cuda, p, x, f)
+    want = oracle.forward_f32(x, f, (L.stride_rows, L.stride_cols), L.padding)
+    err = rel_err(got, want)
+    _say("full bf16 %s err %.3g" % (name, err))
+    assert err <= TOL_BF16, (name, err)
