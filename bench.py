@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the forward-convolution hot path on one MI355X.
+
+A "step" is one pass of the whole path (validate, select variant, launch)
+over the VGG-16-style 3x3 sweep at batch 16 (five layers, fp32, stride 1, SAME
+padding), inputs and filters resident in HBM before the timed region.  The
+metric is conv2d forward TFLOP/s with the direct-convolution flop count
+2*N*P*Q*K*R*S*C (padded taps count as work).
+
+Prints ONE JSON line.  Besides the contract's fields it carries
+  roofline     -- the kernel with the largest share of the step, its flop rate
+                  from HIP events on the launch stream against the fp32 MFMA peak
+  cpu_baseline -- the CPU oracle timed on a bounded sample of the same workload
+  layers       -- per-layer times (context)
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2516.6}   # MI355X dense MFMA peaks
+PEAK_HBM_GBS = 8000.0
+
+
+def layer_flops(B, p):
+    g = B.conv2d_get_geometry(p)
+    return (2.0 * p.batch * g.out_rows * g.out_cols * p.features *
+            p.window_rows * p.window_cols * p.channels)
+
+
+def layer_bytes(B, p):
+    """Algorithmic bytes: input read once + filter read once + output written once."""
+    g = B.conv2d_get_geometry(p)
+    isz = 4 if p.in_dtype == B.F32 else 2
+    osz = 4 if p.out_dtype == B.F32 else 2
+    return (isz * p.batch * p.in_rows * p.in_cols * p.channels +
+            isz * p.window_rows * p.window_cols * p.channels * p.features +
+            osz * p.batch * g.out_rows * g.out_cols * p.features)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-batch", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+                 "use --gpus 1")
+
+    import torch
+
+    from paper_1904_04174_amd import binding as B
+    from paper_1904_04174_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs the GPU")
+    dev = torch.device("cuda:0")
+    in_dtype = B.F32 if args.dtype == "f32" else B.BF16
+    tdt = torch.float32 if args.dtype == "f32" else torch.bfloat16
+
+    names = wl.VGG_N16
+    layers = []
+    for name in names:
+        L = wl.LAYERS[name]
+        x, f = wl.make_inputs(L, dist="uniform")
+        p = B.params_of_layer(L, in_dtype, B.F32)
+        xd = torch.from_numpy(x).to(dev).to(tdt).contiguous()
+        fd = torch.from_numpy(f).to(dev).to(tdt).contiguous()
+        g = B.conv2d_get_geometry(p)
+        out = torch.empty((p.batch, g.out_rows, g.out_cols, p.features), dtype=torch.float32,
+                          device=dev)
+        ws_bytes = B.conv2d_workspace_size(p)
+        ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev)
+        vid = B.conv2d_selected_variant(p)
+        layers.append(dict(name=name, layer=L, p=p, x=xd, f=fd, out=out, ws=ws, ws_bytes=ws_bytes,
+                           flops=layer_flops(B, p), bytes=layer_bytes(B, p),
+                           variant=B.conv2d_variant_name(vid)))
+        del x, f
+
+    stream = torch.cuda.Stream(device=dev)
+    handle = stream.cuda_stream
+
+    def launch(l):
+        rc = B.conv2d_forward_raw(l["p"], l["x"].data_ptr(), l["f"].data_ptr(),
+                                  l["out"].data_ptr(), l["ws"].data_ptr() if l["ws_bytes"] else 0,
+                                  l["ws_bytes"], handle)
+        if rc:
+            raise B.Conv2dError(rc, "conv2d_forward(%s)" % l["name"])
+
+    def step():
+        for l in layers:
+            launch(l)
+
+    torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        step()
+    stream.synchronize()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly --steps passes over the sweep
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    stream.synchronize()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = 1e3 * wall / args.steps
+    total_flops = sum(l["flops"] for l in layers)
+    value = total_flops / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-layer kernel time from HIP events recorded on the launch stream
+    reps = max(10, args.steps)
+    for l in layers:
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        launch(l)
+        e0.record(stream)
+        for _ in range(reps):
+            launch(l)
+        e1.record(stream)
+        stream.synchronize()
+        l["ms"] = e0.elapsed_time(e1) / reps
+    dom = max(layers, key=lambda l: l["ms"])
+    peak = PEAK_TFLOPS[args.dtype]
+    achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(achieved / peak, 4), "traffic": None,
+                "kernel": dom["variant"], "layer": dom["name"],
+                "kernel_ms": round(dom["ms"], 4),
+                "algorithmic_gflop_per_launch": round(dom["flops"] / 1e9, 3)}
+
+    result = {
+        "metric": "conv2d forward TFLOP/s (2*N*P*Q*K*R*S*C / time)",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": "VGG-16-style 3x3 sweep, stride 1, SAME, N=16: "
+                               "(224,64,64) (112,128,128) (56,256,256) (28,512,512) (14,512,512); "
+                               "NHWC/HWCF, uniform[-1,1]",
+                   "batch": 16, "layers": names},
+        "frac_of_mfma_peak": round(value / peak, 4),
+        "roofline": roofline,
+        "layers": [{"name": l["name"], "variant": l["variant"], "ms": round(l["ms"], 4),
+                    "tflops": round(l["flops"] / (l["ms"] * 1e-3) / 1e12, 2),
+                    "alg_gbs": round(l["bytes"] / (l["ms"] * 1e-3) / 1e9, 1)} for l in layers],
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        nb = args.cpu_sample_batch
+        cpu_flops, cpu_s = 0.0, 0.0
+        for l in layers:
+            L = l["layer"]
+            x, f = wl.make_inputs(L, dist="uniform", batch=nb)
+            if args.dtype == "bf16":
+                x, _ = wl.round_to_bf16(x)
+                f, _ = wl.round_to_bf16(f)
+            t = time.perf_counter()
+            oracle.forward_f32(x, f, (L.stride_rows, L.stride_cols), L.padding)
+            cpu_s += time.perf_counter() - t
+            cpu_flops += l["flops"] * nb / L.batch
+        result["cpu_baseline"] = {
+            "value": round(cpu_flops / cpu_s / 1e12, 5), "unit": "TFLOP/s",
+            "cores": oracle.max_threads(), "kind": "oracle",
+            "sample": "the same five layers at batch %d (first %d images' worth of each layer), "
+                      "%.1f GFLOP in %.2f s" % (nb, nb, cpu_flops / 1e9, cpu_s)}
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

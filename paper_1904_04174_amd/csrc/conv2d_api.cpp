@@ -112,7 +112,8 @@ bool supports(const Variant& v, const Problem& q) {
     case kDirect:
       return true;
     case kIgemmF32:
-      return !q.in_bf16 && !q.out_bf16 && q.C % 4 == 0 && q.K % 4 == 0;
+      return !q.in_bf16 && !q.out_bf16 && q.C % 4 == 0 && q.K % 4 == 0 &&
+             q.Kg <= igemm_f32_tile_max_kg(v.tile);
     case kIgemmBf16:
       return q.in_bf16 && q.C % 8 == 0 && q.K % 8 == 0;
   }
@@ -121,7 +122,7 @@ bool supports(const Variant& v, const Problem& q) {
 
 // Hand-tuned choice of tile for one device (MI355X: 256 compute units, two
 // 256-thread workgroups of these kernels resident per unit).
-int pick_tile(const Problem& q, int ntiles, void (*shape)(int, int*, int*, int*)) {
+int pick_tile(const Problem& q, Family family, int ntiles, void (*shape)(int, int*, int*, int*)) {
   // Widest feature tile that K fills, then the tallest pixel tile that still
   // gives every compute unit about two workgroups.
   const long long slots = 512;
@@ -129,6 +130,8 @@ int pick_tile(const Problem& q, int ntiles, void (*shape)(int, int*, int*, int*)
   long long best_score = -1;
   for (int t = 0; t < ntiles; ++t) {
     int bm, bn, bk;
+    const Variant cand = {family, t, ""};
+    if (!supports(cand, q)) continue;
     shape(t, &bm, &bn, &bk);
     const long long tm = ceil_div_ll(q.M, bm), tn = ceil_div_ll(q.K, bn);
     const long long wgs = tm * tn;
@@ -148,17 +151,15 @@ int select(const Problem& q, bool aligned) {
   const Table& tb = table();
   if (aligned) {
     if (!q.in_bf16 && igemm_f32_num_tiles() > 0) {
-      const Variant probe = {kIgemmF32, 0, ""};
-      if (supports(probe, q)) {
-        const int t = pick_tile(q, igemm_f32_num_tiles(), igemm_f32_tile_shape);
+      {
+        const int t = pick_tile(q, kIgemmF32, igemm_f32_num_tiles(), igemm_f32_tile_shape);
         for (int i = 0; i < tb.n; ++i)
           if (tb.v[i].family == kIgemmF32 && tb.v[i].tile == t) return i;
       }
     }
     if (q.in_bf16 && igemm_bf16_num_tiles() > 0) {
-      const Variant probe = {kIgemmBf16, 0, ""};
-      if (supports(probe, q)) {
-        const int t = pick_tile(q, igemm_bf16_num_tiles(), igemm_bf16_tile_shape);
+      {
+        const int t = pick_tile(q, kIgemmBf16, igemm_bf16_num_tiles(), igemm_bf16_tile_shape);
         for (int i = 0; i < tb.n; ++i)
           if (tb.v[i].family == kIgemmBf16 && tb.v[i].tile == t) return i;
       }

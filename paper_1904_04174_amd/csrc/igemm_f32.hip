@@ -26,9 +26,16 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kXcds = 8;  // workgroups are dealt round-robin over the 8 XCDs
 
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_>
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, bool TWO_LEVEL_, int OCC_>
 struct Tile {
+  static constexpr int OCC = OCC_;  // wavefronts per SIMD the register allocation must allow
   static constexpr int BM = BM_, BN = BN_, BK = BK_;
+  // Two-level summation: the MFMA accumulators are added into a second set
+  // of fp32 registers every `flush_slices` slices and restarted from zero.
+  // A chain of n fp32 additions has a rounding error that grows like n; the
+  // split keeps both chains near sqrt(n), which is what holds the 1e-4
+  // tolerance at Kg = 4608.  Costs one extra register per accumulator.
+  static constexpr bool TWO_LEVEL = TWO_LEVEL_;
   static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int NT = 64 * WAVES_M * WAVES_N;
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -46,7 +53,7 @@ struct Tile {
 };
 
 template <class T>
-__global__ __launch_bounds__(T::NT) void igemm_f32_kernel(const Problem p) {
+__global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem p, const int flush_slices) {
   constexpr int BM = T::BM, BN = T::BN, BK = T::BK, LD = T::LD, NT = T::NT;
   extern __shared__ __align__(16) float lds[];
   float* As = lds;                     // [2][BM][LD]
@@ -178,6 +185,16 @@ __global__ __launch_bounds__(T::NT) void igemm_f32_kernel(const Problem p) {
     for (int j = 0; j < T::TN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  floatx16 total[T::TWO_LEVEL ? T::TM : 1][T::TWO_LEVEL ? T::TN : 1];
+  if (T::TWO_LEVEL) {
+#pragma unroll
+    for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+      for (int j = 0; j < T::TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) total[i][j][v] = 0.f;
+  }
+  int until_flush = flush_slices;
 
   const int nslices = (p.Kg + BK - 1) / BK;
   load_a();
@@ -214,8 +231,30 @@ __global__ __launch_bounds__(T::NT) void igemm_f32_kernel(const Problem p) {
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].w, bf[j].w, acc[i][j], 0, 0, 0);
         }
     }
+    if (T::TWO_LEVEL) {
+      if (--until_flush == 0) {
+        until_flush = flush_slices;
+#pragma unroll
+        for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+          for (int j = 0; j < T::TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              total[i][j][v] += acc[i][j][v];
+              acc[i][j][v] = 0.f;
+            }
+      }
+    }
     if (more) store_tiles(buf ^ 1);
     __syncthreads();
+  }
+  if (T::TWO_LEVEL) {
+#pragma unroll
+    for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+      for (int j = 0; j < T::TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] += total[i][j][v];
   }
 
   // ---- epilogue: D tile -> NHWC output.  In a 32x32 accumulator, lane l
@@ -250,27 +289,40 @@ hipError_t launch(const Problem& p, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
+  // flush interval of the two-level summation: about sqrt(#slices)
+  const int nslices = (p.Kg + T::BK - 1) / T::BK;
+  int flush = 1;
+  while (flush * flush < nslices) ++flush;
   hipLaunchKernelGGL((igemm_f32_kernel<T>), dim3(tiles_m * tiles_n), dim3(T::NT), lds_bytes, stream,
-                     p);
+                     p, flush);
   return hipGetLastError();
 }
 
 struct TileEntry {
   const char* name;
   int bm, bn, bk;
+  int max_kg;  // longest reduction the tile's summation scheme keeps within tolerance
   hipError_t (*fn)(const Problem&, hipStream_t);
 };
 
-#define CONV2D_F32_TILE(bm, bn, bk, wm, wn) \
-  { "igemm_f32_" #bm "x" #bn "x" #bk, bm, bn, bk, &launch<Tile<bm, bn, bk, wm, wn>> }
+#define CONV2D_F32_TILE(bm, bn, bk, wm, wn, two, occ, tag, maxkg) \
+  { "igemm_f32_" #bm "x" #bn "x" #bk tag, bm, bn, bk, maxkg, \
+    &launch<Tile<bm, bn, bk, wm, wn, two, occ>> }
+
+constexpr int kAnyKg = 0x7fffffff;
+// A single fp32 chain over Kg/2 MFMA steps stays below the 1e-4 tolerance
+// with margin only up to about Kg = 1280 (measured 7e-5 at Kg = 2304 and
+// 1.0e-4 at Kg = 4608; the error grows in proportion to Kg).
+constexpr int kSingleChainMaxKg = 1280;
 
 const TileEntry kTiles[] = {
-    CONV2D_F32_TILE(256, 128, 16, 2, 2),
-    CONV2D_F32_TILE(128, 128, 16, 2, 2),
-    CONV2D_F32_TILE(256, 64, 16, 4, 1),
-    CONV2D_F32_TILE(128, 64, 16, 2, 2),
-    CONV2D_F32_TILE(64, 64, 16, 2, 2),
-    CONV2D_F32_TILE(128, 32, 16, 4, 1),
+    CONV2D_F32_TILE(256, 128, 16, 2, 2, false, 2, "_w128x64", kSingleChainMaxKg),
+    CONV2D_F32_TILE(256, 128, 16, 4, 2, true, 2, "", kAnyKg),
+    CONV2D_F32_TILE(128, 128, 16, 2, 2, true, 2, "", kAnyKg),
+    CONV2D_F32_TILE(256, 64, 16, 4, 1, true, 2, "", kAnyKg),
+    CONV2D_F32_TILE(128, 64, 16, 2, 2, true, 3, "", kAnyKg),
+    CONV2D_F32_TILE(64, 64, 16, 2, 2, true, 4, "", kAnyKg),
+    CONV2D_F32_TILE(128, 32, 16, 4, 1, true, 4, "", kAnyKg),
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -278,6 +330,7 @@ constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
 int igemm_f32_num_tiles() { return kNumTiles; }
 const char* igemm_f32_tile_name(int tile) { return kTiles[tile].name; }
+int igemm_f32_tile_max_kg(int tile) { return kTiles[tile].max_kg; }
 void igemm_f32_tile_shape(int tile, int* bm, int* bn, int* bk) {
   *bm = kTiles[tile].bm;
   *bn = kTiles[tile].bn;
