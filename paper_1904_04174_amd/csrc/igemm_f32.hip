@@ -8,27 +8,37 @@
 //   input: R*S runs of C contiguous floats, or zeros where the window hangs
 //   over the border.
 //
-// One workgroup (4 wavefronts of 64 lanes) owns a BM x BN tile of D.  Per
-// BK-wide slice of Kg it stages the A and B tiles in LDS (k contiguous per
-// row, so one 16-byte LDS read gives a lane four consecutive k of its row),
-// and each wavefront multiplies its WM x WN sub-tile with 32x32x2 MFMAs.
-// Global loads of slice i+1 are in flight while slice i is multiplied
-// (register-staged double buffering, one barrier per slice).
+// One workgroup owns a BM x BN tile of D.  Per BK-wide slice of Kg it stages
+// the A and B tiles in LDS (k contiguous per row, so one 16-byte LDS read
+// gives a lane four consecutive k of its row), and each wavefront multiplies
+// its WM x WN sub-tile with 32x32x2 MFMAs.
+//
+// Global loads are raw buffer loads: a tap outside the image (or a row past
+// M, or a k past Kg) gets an offset beyond the buffer and the hardware
+// returns zeros, so the gather has no branches and no selects.  Loads run PF
+// slices ahead of the MFMAs through PF register sets (HBM latency is about
+// the MFMA time of one slice, so one slice of lookahead is not always
+// enough), LDS is double buffered, one barrier per slice.
 //
 // Requirements (checked by the host before launch): C % 4 == 0, K % 4 == 0,
-// 16-byte aligned in/filt, every tensor below 2^31 elements.
+// 16-byte aligned in/filt, input and filter each below 2^31 bytes, output
+// below 2^31 elements.
+#include <type_traits>
+
 #include "conv2d_internal.h"
 
 namespace conv2d {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kXcds = 8;  // workgroups are dealt round-robin over the 8 XCDs
+constexpr int kXcds = 8;                      // workgroups are dealt round-robin over the 8 XCDs
+constexpr unsigned kRsrcFlags = 0x00020000u;  // raw buffer, 32-bit data format
+constexpr int kOutOfRange = static_cast<int>(0x80000000u);  // byte offset 2^31: past any buffer, reads 0
 
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, bool TWO_LEVEL_, int OCC_>
+template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, bool TWO_LEVEL_, int OCC_, int PF_>
 struct Tile {
-  static constexpr int OCC = OCC_;  // wavefronts per SIMD the register allocation must allow
   static constexpr int BM = BM_, BN = BN_, BK = BK_;
   // Two-level summation: the MFMA accumulators are added into a second set
   // of fp32 registers every `flush_slices` slices and restarted from zero.
@@ -36,6 +46,8 @@ struct Tile {
   // split keeps both chains near sqrt(n), which is what holds the 1e-4
   // tolerance at Kg = 4608.  Costs one extra register per accumulator.
   static constexpr bool TWO_LEVEL = TWO_LEVEL_;
+  static constexpr int OCC = OCC_;  // wavefronts per SIMD the register allocation must allow
+  static constexpr int PF = PF_;    // slices of global-load lookahead (register sets)
   static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int NT = 64 * WAVES_M * WAVES_N;
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
@@ -47,14 +59,16 @@ struct Tile {
   static constexpr int B_BLOCKS = (BK / 4) * (BN / 4);  // 4(k) x 4(n) blocks
   static constexpr int B_ITERS = (B_BLOCKS + NT - 1) / NT;
   static constexpr int LDS_FLOATS = 2 * (BM + BN) * LD;
+  static_assert(PF == 1 || PF == 2, "one or two register sets");
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of 32x32");
   static_assert(BK % 8 == 0, "BK must be a multiple of 8");
   static_assert(BM % A_ROWS_PER_PASS == 0, "A tile must divide evenly over the threads");
 };
 
 template <class T>
-__global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem p, const int flush_slices) {
-  constexpr int BM = T::BM, BN = T::BN, BK = T::BK, LD = T::LD, NT = T::NT;
+__global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem p,
+                                                                  const int flush_slices) {
+  constexpr int BM = T::BM, BN = T::BN, BK = T::BK, LD = T::LD, NT = T::NT, PF = T::PF;
   extern __shared__ __align__(16) float lds[];
   float* As = lds;                     // [2][BM][LD]
   float* Bs = lds + 2 * BM * LD;       // [2][BN][LD]
@@ -79,13 +93,16 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
   const int m0 = (tile / tiles_n) * BM;
   const int n0 = (tile % tiles_n) * BN;
 
-  const float* __restrict__ in = static_cast<const float*>(p.in);
-  const float* __restrict__ filt = static_cast<const float*>(p.filt);
+  const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void*>(p.in), 0, p.N * p.H * p.W * p.C * 4, kRsrcFlags);
+  const __amdgpu_buffer_rsrc_t filt_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void*>(p.filt), 0, p.Kg * p.K * 4, kRsrcFlags);
 
   // ---- per-thread description of the A rows it gathers
   const int a_kv = tid % T::KV;
   const int a_row0 = tid / T::KV;
-  int a_base[T::A_ITERS], a_h0[T::A_ITERS], a_w0[T::A_ITERS];
+  int a_off[T::A_ITERS];  // element offset of tap (0,0), channel 0 of the row's window
+  int a_h0[T::A_ITERS], a_w0[T::A_ITERS];
 #pragma unroll
   for (int i = 0; i < T::A_ITERS; ++i) {
     const int m = m0 + a_row0 + i * T::A_ROWS_PER_PASS;
@@ -94,16 +111,18 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
       const int t = m / p.Q;
       const int op = t % p.P;
       const int n = t / p.P;
-      a_base[i] = n * p.H * p.W * p.C;
       a_h0[i] = op * p.sr - p.pt;
       a_w0[i] = q * p.sc - p.pl;
+      a_off[i] = ((n * p.H + a_h0[i]) * p.W + a_w0[i]) * p.C;
     } else {
-      a_base[i] = 0;
       a_h0[i] = -(1 << 28);  // every tap fails the bounds test
       a_w0[i] = 0;
+      a_off[i] = 0;
     }
   }
-  // (r, s, c) of this thread's 4-wide k vector in the current slice
+  // (r, s, c) of this thread's 4-wide k vector in the next slice to load,
+  // and the per-slice advance of BK channels split into whole taps and a
+  // channel remainder so that stepping needs no division and no branch
   int kc, ks, kr;
   {
     const int kg = a_kv * 4;
@@ -112,52 +131,64 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
     ks = t % p.S;
     kr = t / p.S;
   }
+  const int step_c = BK % p.C;
+  const int step_s = (BK / p.C) % p.S;
+  const int step_r = (BK / p.C) / p.S;
+  // B: 4(k) x 4(n) blocks; the column part of the offset is fixed per thread
+  int b_col[T::B_ITERS], b_krow[T::B_ITERS];
+#pragma unroll
+  for (int i = 0; i < T::B_ITERS; ++i) {
+    const int b = tid + i * NT;
+    const int nb4 = b % (BN / 4);
+    const int kb = b / (BN / 4);
+    const int col = n0 + nb4 * 4;
+    b_krow[i] = (b < T::B_BLOCKS && col < p.K) ? kb * 4 : (1 << 30);  // first k row of the block
+    b_col[i] = col;
+  }
+  int k_next = 0;  // first k of the next slice to load
 
-  float4 a_reg[T::A_ITERS];
-  float4 b_reg[T::B_ITERS][4];
+  uintx4 a_reg[PF][T::A_ITERS];
+  uintx4 b_reg[PF][T::B_ITERS][4];
 
-  auto load_a = [&]() {
+  auto issue_loads = [&](auto set_c) {
+    constexpr int set = decltype(set_c)::value;
+    const int tap = (kr * p.W + ks) * p.C + kc;
+    // past the last window row (k >= Kg) the row test below must fail
+    const int kr_t = (kr < p.R) ? kr : (1 << 30);
 #pragma unroll
     for (int i = 0; i < T::A_ITERS; ++i) {
-      const int h = a_h0[i] + kr;
-      const int w = a_w0[i] + ks;
-      const bool ok = (kr < p.R) && (static_cast<unsigned>(h) < static_cast<unsigned>(p.H)) &&
-                      (static_cast<unsigned>(w) < static_cast<unsigned>(p.W));
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (ok) v = *reinterpret_cast<const float4*>(in + a_base[i] + (h * p.W + w) * p.C + kc);
-      a_reg[i] = v;
+      const bool ok = (static_cast<unsigned>(a_h0[i] + kr_t) < static_cast<unsigned>(p.H)) &
+                      (static_cast<unsigned>(a_w0[i] + ks) < static_cast<unsigned>(p.W));
+      const int off = ok ? (a_off[i] + tap) * 4 : kOutOfRange;
+      a_reg[set][i] = __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, off, 0, 0);
     }
-  };
-  auto advance_a = [&]() {
-    kc += BK;
-    while (kc >= p.C) {
-      kc -= p.C;
-      if (++ks == p.S) { ks = 0; ++kr; }
-    }
-  };
-  auto load_b = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < T::B_ITERS; ++i) {
-      const int b = tid + i * NT;
-      const int nb4 = b % (BN / 4);
-      const int kb = b / (BN / 4);
-      const int col = n0 + nb4 * 4;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int kg = k0 + kb * 4 + j;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (b < T::B_BLOCKS && kg < p.Kg && col < p.K)
-          v = *reinterpret_cast<const float4*>(filt + static_cast<size_t>(kg) * p.K + col);
-        b_reg[i][j] = v;
+        const int kg = k_next + b_krow[i] + j;
+        const int off = (kg < p.Kg) ? (kg * p.K + b_col[i]) * 4 : kOutOfRange;
+        b_reg[set][i][j] = __builtin_amdgcn_raw_buffer_load_b128(filt_rsrc, off, 0, 0);
       }
     }
+    // advance to the following slice
+    k_next += BK;
+    kc += step_c;
+    const int carry_c = kc >= p.C;
+    kc -= carry_c ? p.C : 0;
+    ks += step_s + carry_c;
+    const int carry_s = ks >= p.S;
+    ks -= carry_s ? p.S : 0;
+    kr += step_r + carry_s;
   };
-  auto store_tiles = [&](int buf) {
+  auto store_tiles = [&](auto set_c, int buf) {
+    constexpr int set = decltype(set_c)::value;
     float* as = As + buf * BM * LD;
     float* bs = Bs + buf * BN * LD;
 #pragma unroll
     for (int i = 0; i < T::A_ITERS; ++i)
-      *reinterpret_cast<float4*>(as + (a_row0 + i * T::A_ROWS_PER_PASS) * LD + a_kv * 4) = a_reg[i];
+      *reinterpret_cast<uintx4*>(as + (a_row0 + i * T::A_ROWS_PER_PASS) * LD + a_kv * 4) =
+          a_reg[set][i];
 #pragma unroll
     for (int i = 0; i < T::B_ITERS; ++i) {
       const int b = tid + i * NT;
@@ -165,15 +196,13 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
         const int nb4 = b % (BN / 4);
         const int kb = b / (BN / 4);
         // 4x4 transpose in registers: LDS keeps B as [n][k], k contiguous
-        float* dst = bs + (nb4 * 4) * LD + kb * 4;
-        *reinterpret_cast<float4*>(dst + 0 * LD) =
-            make_float4(b_reg[i][0].x, b_reg[i][1].x, b_reg[i][2].x, b_reg[i][3].x);
-        *reinterpret_cast<float4*>(dst + 1 * LD) =
-            make_float4(b_reg[i][0].y, b_reg[i][1].y, b_reg[i][2].y, b_reg[i][3].y);
-        *reinterpret_cast<float4*>(dst + 2 * LD) =
-            make_float4(b_reg[i][0].z, b_reg[i][1].z, b_reg[i][2].z, b_reg[i][3].z);
-        *reinterpret_cast<float4*>(dst + 3 * LD) =
-            make_float4(b_reg[i][0].w, b_reg[i][1].w, b_reg[i][2].w, b_reg[i][3].w);
+        unsigned int* dst = reinterpret_cast<unsigned int*>(bs) + (nb4 * 4) * LD + kb * 4;
+        const uintx4 r0 = b_reg[set][i][0], r1 = b_reg[set][i][1], r2 = b_reg[set][i][2],
+                     r3 = b_reg[set][i][3];
+        *reinterpret_cast<uintx4*>(dst + 0 * LD) = uintx4{r0.x, r1.x, r2.x, r3.x};
+        *reinterpret_cast<uintx4*>(dst + 1 * LD) = uintx4{r0.y, r1.y, r2.y, r3.y};
+        *reinterpret_cast<uintx4*>(dst + 2 * LD) = uintx4{r0.z, r1.z, r2.z, r3.z};
+        *reinterpret_cast<uintx4*>(dst + 3 * LD) = uintx4{r0.w, r1.w, r2.w, r3.w};
       }
     }
   };
@@ -196,20 +225,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
   }
   int until_flush = flush_slices;
 
-  const int nslices = (p.Kg + BK - 1) / BK;
-  load_a();
-  load_b(0);
-  store_tiles(0);
-  __syncthreads();
-
-  for (int slice = 0; slice < nslices; ++slice) {
-    const int buf = slice & 1;
-    const bool more = slice + 1 < nslices;
-    if (more) {
-      advance_a();
-      load_a();
-      load_b((slice + 1) * BK);
-    }
+  auto multiply = [&](int buf) {
     const float* as = As + buf * BM * LD + (wm * T::WM + lr) * LD + lk * 4;
     const float* bs = Bs + buf * BN * LD + (wn * T::WN + lr) * LD + lk * 4;
 #pragma unroll
@@ -245,7 +261,37 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
             }
       }
     }
-    if (more) store_tiles(buf ^ 1);
+  };
+
+  using Set0 = std::integral_constant<int, 0>;
+  using Set1 = std::integral_constant<int, PF - 1>;  // the same set as Set0 when PF == 1
+
+  // Slices past the end are loaded as zeros (their offsets are out of range)
+  // and multiplied by nobody, so the pipeline needs no tail special cases.
+  const int nslices = (p.Kg + BK - 1) / BK;
+  issue_loads(Set0{});
+  if (PF == 2) issue_loads(Set1{});
+  store_tiles(Set0{}, 0);
+  __syncthreads();
+
+  for (int slice = 0; slice < nslices; slice += 2) {
+    // even slice: its data is in LDS buffer 0 and register set 0 is free.
+    // The scheduling fences keep the loads ahead of the MFMAs: if the
+    // compiler sinks them, their destination registers get shared with the
+    // LDS fragments and every LDS read then waits for all loads in flight.
+    issue_loads(Set0{});
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(0);
+    __builtin_amdgcn_sched_barrier(0);
+    store_tiles(Set1{}, 1);  // PF == 1: the set just loaded; PF == 2: the one loaded a slice ago
+    __syncthreads();
+    if (slice + 1 >= nslices) break;
+    // odd slice: LDS buffer 1, register set 1 (PF == 2) is free
+    issue_loads(Set1{});
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(1);
+    __builtin_amdgcn_sched_barrier(0);
+    store_tiles(Set0{}, 0);
     __syncthreads();
   }
   if (T::TWO_LEVEL) {
@@ -281,13 +327,11 @@ hipError_t launch(const Problem& p, hipStream_t stream) {
   const int tiles_m = (p.M + T::BM - 1) / T::BM;
   const int tiles_n = (p.K + T::BN - 1) / T::BN;
   const size_t lds_bytes = sizeof(float) * T::LDS_FLOATS;
-  static bool attr_set = false;
-  if (!attr_set && lds_bytes > 64 * 1024) {
+  if (lds_bytes > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_f32_kernel<T>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        static_cast<int>(lds_bytes));
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   // flush interval of the two-level summation: about sqrt(#slices)
   const int nslices = (p.Kg + T::BK - 1) / T::BK;
@@ -305,24 +349,29 @@ struct TileEntry {
   hipError_t (*fn)(const Problem&, hipStream_t);
 };
 
-#define CONV2D_F32_TILE(bm, bn, bk, wm, wn, two, occ, tag, maxkg) \
+#define CONV2D_F32_TILE(bm, bn, bk, wm, wn, two, occ, pf, tag, maxkg) \
   { "igemm_f32_" #bm "x" #bn "x" #bk tag, bm, bn, bk, maxkg, \
-    &launch<Tile<bm, bn, bk, wm, wn, two, occ>> }
+    &launch<Tile<bm, bn, bk, wm, wn, two, occ, pf>> }
 
 constexpr int kAnyKg = 0x7fffffff;
-// A single fp32 chain over Kg/2 MFMA steps stays below the 1e-4 tolerance
-// with margin only up to about Kg = 1280 (measured 7e-5 at Kg = 2304 and
-// 1.0e-4 at Kg = 4608; the error grows in proportion to Kg).
-constexpr int kSingleChainMaxKg = 1280;
+// (A tile without the two-level summation would have to cap Kg near 1280:
+// a single fp32 chain measured 7e-5 at Kg = 2304 and 1.0e-4 at Kg = 4608.)
 
 const TileEntry kTiles[] = {
-    CONV2D_F32_TILE(256, 128, 16, 2, 2, false, 2, "_w128x64", kSingleChainMaxKg),
-    CONV2D_F32_TILE(256, 128, 16, 4, 2, true, 2, "", kAnyKg),
-    CONV2D_F32_TILE(128, 128, 16, 2, 2, true, 2, "", kAnyKg),
-    CONV2D_F32_TILE(256, 64, 16, 4, 1, true, 2, "", kAnyKg),
-    CONV2D_F32_TILE(128, 64, 16, 2, 2, true, 3, "", kAnyKg),
-    CONV2D_F32_TILE(64, 64, 16, 2, 2, true, 4, "", kAnyKg),
-    CONV2D_F32_TILE(128, 32, 16, 4, 1, true, 4, "", kAnyKg),
+    CONV2D_F32_TILE(256, 128, 16, 4, 2, true, 2, 1, "", kAnyKg),
+    CONV2D_F32_TILE(128, 128, 16, 2, 2, true, 2, 1, "", kAnyKg),
+    CONV2D_F32_TILE(256, 64, 16, 4, 1, true, 2, 1, "", kAnyKg),
+    CONV2D_F32_TILE(128, 64, 16, 2, 2, true, 3, 1, "", kAnyKg),
+    CONV2D_F32_TILE(64, 64, 16, 2, 2, true, 4, 1, "", kAnyKg),
+    CONV2D_F32_TILE(128, 32, 16, 4, 1, true, 4, 1, "", kAnyKg),
+    // two slices of lookahead
+    CONV2D_F32_TILE(256, 128, 16, 4, 2, true, 2, 2, "_pf2", kAnyKg),
+    CONV2D_F32_TILE(128, 128, 16, 2, 2, true, 2, 2, "_pf2", kAnyKg),
+    CONV2D_F32_TILE(128, 64, 16, 2, 2, true, 3, 2, "_pf2", kAnyKg),
+    // deeper slices
+    CONV2D_F32_TILE(128, 128, 32, 2, 2, true, 2, 1, "", kAnyKg),
+    CONV2D_F32_TILE(128, 64, 32, 2, 2, true, 3, 1, "", kAnyKg),
+    CONV2D_F32_TILE(128, 128, 32, 2, 2, true, 2, 2, "_pf2", kAnyKg),
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
