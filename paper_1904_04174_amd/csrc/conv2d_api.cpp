@@ -115,10 +115,10 @@ bool supports(const Variant& v, const Problem& q) {
       // 16-byte gathers need C and K in multiples of 4; buffer addressing
       // needs input and filter below 2^31 bytes
       return !q.in_bf16 && !q.out_bf16 && q.C % 4 == 0 && q.K % 4 == 0 &&
-             4LL * q.N * q.H * q.W * q.C < (1LL << 31) && 4LL * q.Kg * q.K < (1LL << 31) &&
-             q.Kg <= igemm_f32_tile_max_kg(v.tile);
+             4LL * q.N * q.H * q.W * q.C < (1LL << 31) && 4LL * q.Kg * q.K < (1LL << 31);
     case kIgemmBf16:
-      return q.in_bf16 && q.C % 8 == 0 && q.K % 8 == 0;
+      return q.in_bf16 && q.C % 8 == 0 && q.K % 8 == 0 &&
+             2LL * q.N * q.H * q.W * q.C < (1LL << 31) && 2LL * q.Kg * q.K < (1LL << 31);
   }
   return false;
 }

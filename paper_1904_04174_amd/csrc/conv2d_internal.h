@@ -36,7 +36,6 @@ hipError_t launch_direct(const Problem& p, hipStream_t stream);
 int igemm_f32_num_tiles();
 const char* igemm_f32_tile_name(int tile);
 void igemm_f32_tile_shape(int tile, int* bm, int* bn, int* bk);
-int igemm_f32_tile_max_kg(int tile);  // longest reduction the tile stays within tolerance for
 hipError_t launch_igemm_f32(const Problem& p, int tile, hipStream_t stream);
 
 // bf16 implicit GEMM on v_mfma_f32_32x32x16_bf16.

@@ -1,28 +1,30 @@
-// fp32 forward convolution as an implicit GEMM on the CDNA4 matrix cores
-// (v_mfma_f32_32x32x2_f32), for gfx950.
+// Forward convolution as an implicit GEMM on the CDNA4 matrix cores, for
+// gfx950: fp32 on v_mfma_f32_32x32x2_f32, bf16 on v_mfma_f32_32x32x16_bf16
+// (fp32 accumulation in both).
 //
 // GEMM view of the convolution of the paper's section 3:
 //   D[M][K] = A[M][Kg] * B[Kg][K],  M = N*P*Q, Kg = R*S*C ordered (r,s,c).
 //   B is the HWCF filter as it lies in memory, D is the NHWC output as it
 //   lies in memory, and row m of A is gathered on the fly from the NHWC
-//   input: R*S runs of C contiguous floats, or zeros where the window hangs
-//   over the border.
+//   input: R*S runs of C contiguous elements, or zeros where the window
+//   hangs over the border.
 //
 // One workgroup owns a BM x BN tile of D.  Per BK-wide slice of Kg it stages
-// the A and B tiles in LDS (k contiguous per row, so one 16-byte LDS read
-// gives a lane four consecutive k of its row), and each wavefront multiplies
-// its WM x WN sub-tile with 32x32x2 MFMAs.
+// the A and B tiles in LDS, both with k contiguous per row, so that one
+// 16-byte LDS read gives a lane the consecutive k of its row that the MFMA
+// wants (fp32: four k for four 32x32x2 MFMAs; bf16: the eight k of one
+// 32x32x16 MFMA).  B arrives feature-contiguous from memory and is
+// transposed in registers (VEC x VEC blocks) on its way to LDS.
 //
 // Global loads are raw buffer loads: a tap outside the image (or a row past
 // M, or a k past Kg) gets an offset beyond the buffer and the hardware
 // returns zeros, so the gather has no branches and no selects.  Loads run PF
-// slices ahead of the MFMAs through PF register sets (HBM latency is about
-// the MFMA time of one slice, so one slice of lookahead is not always
-// enough), LDS is double buffered, one barrier per slice.
+// slices ahead of the MFMAs through PF register sets, LDS is double
+// buffered, one barrier per slice.
 //
-// Requirements (checked by the host before launch): C % 4 == 0, K % 4 == 0,
-// 16-byte aligned in/filt, input and filter each below 2^31 bytes, output
-// below 2^31 elements.
+// Requirements (checked by the host before launch): C and K multiples of the
+// 16-byte vector (4 fp32 / 8 bf16), 16-byte aligned in/filt, input and
+// filter each below 2^31 bytes, output below 2^31 elements.
 #include <type_traits>
 
 #include "conv2d_internal.h"
@@ -32,46 +34,66 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kXcds = 8;                      // workgroups are dealt round-robin over the 8 XCDs
 constexpr unsigned kRsrcFlags = 0x00020000u;  // raw buffer, 32-bit data format
-constexpr int kOutOfRange = static_cast<int>(0x80000000u);  // byte offset 2^31: past any buffer, reads 0
+// byte offset 2^31: past the end of any buffer this kernel accepts, reads as zero
+constexpr int kOutOfRange = static_cast<int>(0x80000000u);
 
-template <int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, bool TWO_LEVEL_, int OCC_, int PF_>
+template <bool BF16_, int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, bool TWO_LEVEL_,
+          int OCC_, int PF_>
 struct Tile {
+  static constexpr bool BF16 = BF16_;
   static constexpr int BM = BM_, BN = BN_, BK = BK_;
-  // Two-level summation: the MFMA accumulators are added into a second set
-  // of fp32 registers every `flush_slices` slices and restarted from zero.
-  // A chain of n fp32 additions has a rounding error that grows like n; the
-  // split keeps both chains near sqrt(n), which is what holds the 1e-4
-  // tolerance at Kg = 4608.  Costs one extra register per accumulator.
+  // Two-level summation (fp32 tiles): the MFMA accumulators are added into a
+  // second set of fp32 registers every `flush_slices` slices and restarted
+  // from zero.  A chain of n fp32 additions has a rounding error that grows
+  // like n; the split keeps both chains near sqrt(n), which is what holds the
+  // 1e-4 tolerance at Kg = 4608 (a single chain measured 7e-5 at Kg = 2304
+  // and 1.0e-4 at Kg = 4608).  Costs one extra register per accumulator.
   static constexpr bool TWO_LEVEL = TWO_LEVEL_;
   static constexpr int OCC = OCC_;  // wavefronts per SIMD the register allocation must allow
   static constexpr int PF = PF_;    // slices of global-load lookahead (register sets)
+  static constexpr int ES = BF16 ? 2 : 4;   // element size in bytes
+  static constexpr int VEC = 16 / ES;       // elements per 16-byte vector
+  static constexpr int KSTEP = 2 * VEC;     // k consumed per fragment read (two lane halves)
   static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int NT = 64 * WAVES_M * WAVES_N;
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   static constexpr int TM = WM / 32, TN = WN / 32;
-  static constexpr int LD = BK + 4;  // LDS row stride in floats (16-byte reads stay conflict free)
-  static constexpr int KV = BK / 4;  // 16-byte vectors per A row
+  static constexpr int LD = BK + VEC;  // LDS row stride in elements: 16 bytes of padding keep
+                                       // the 16-byte fragment reads free of bank conflicts
+  static constexpr int KV = BK / VEC;  // 16-byte vectors per A row
   static constexpr int A_ROWS_PER_PASS = NT / KV;
   static constexpr int A_ITERS = BM / A_ROWS_PER_PASS;
-  static constexpr int B_BLOCKS = (BK / 4) * (BN / 4);  // 4(k) x 4(n) blocks
+  static constexpr int B_BLOCKS = (BK / VEC) * (BN / VEC);  // VEC(k) x VEC(n) blocks
   static constexpr int B_ITERS = (B_BLOCKS + NT - 1) / NT;
-  static constexpr int LDS_FLOATS = 2 * (BM + BN) * LD;
+  static constexpr int LDS_BYTES = 2 * (BM + BN) * LD * ES;
   static_assert(PF == 1 || PF == 2, "one or two register sets");
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of 32x32");
-  static_assert(BK % 8 == 0, "BK must be a multiple of 8");
-  static_assert(BM % A_ROWS_PER_PASS == 0, "A tile must divide evenly over the threads");
+  static_assert(BK % KSTEP == 0, "BK must be a multiple of the fragment step");
+  static_assert(NT % KV == 0 && BM % A_ROWS_PER_PASS == 0, "A tile must divide over the threads");
+  static_assert(!(BF16 && TWO_LEVEL), "two-level summation is an fp32 feature");
+  static_assert(LDS_BYTES <= 160 * 1024, "tile does not fit LDS");
 };
 
-template <class T>
-__global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem p,
-                                                                  const int flush_slices) {
+// fp32 -> bf16 bits, round to nearest even (NaN stays NaN).
+__device__ __forceinline__ unsigned short to_bf16_bits(float x) {
+  unsigned int u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<unsigned short>((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<unsigned short>(u >> 16);
+}
+
+template <class T, bool OUT_BF16>
+__global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
+                                                              const int flush_slices) {
   constexpr int BM = T::BM, BN = T::BN, BK = T::BK, LD = T::LD, NT = T::NT, PF = T::PF;
-  extern __shared__ __align__(16) float lds[];
-  float* As = lds;                     // [2][BM][LD]
-  float* Bs = lds + 2 * BM * LD;       // [2][BN][LD]
+  constexpr int ES = T::ES, VEC = T::VEC;
+  extern __shared__ __align__(16) unsigned char lds[];
+  unsigned char* As = lds;                          // [2][BM][LD] elements
+  unsigned char* Bs = lds + 2 * BM * LD * ES;       // [2][BN][LD] elements
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -79,7 +101,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
   const int wm = wave / T::WAVES_N;
   const int wn = wave % T::WAVES_N;
   const int lr = lane & 31;   // row (A) / column (B, D) inside a 32x32 MFMA tile
-  const int lk = lane >> 5;   // which half of the k pair this lane feeds
+  const int lk = lane >> 5;   // which half of the k group this lane feeds
 
   // Tile of this workgroup.  Workgroup i runs on XCD i % 8; give each XCD a
   // contiguous range of tiles so that neighbours share input rows in its L2,
@@ -94,9 +116,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
   const int n0 = (tile % tiles_n) * BN;
 
   const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<void*>(p.in), 0, p.N * p.H * p.W * p.C * 4, kRsrcFlags);
+      const_cast<void*>(p.in), 0, p.N * p.H * p.W * p.C * ES, kRsrcFlags);
   const __amdgpu_buffer_rsrc_t filt_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<void*>(p.filt), 0, p.Kg * p.K * 4, kRsrcFlags);
+      const_cast<void*>(p.filt), 0, p.Kg * p.K * ES, kRsrcFlags);
 
   // ---- per-thread description of the A rows it gathers
   const int a_kv = tid % T::KV;
@@ -120,12 +142,12 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
       a_off[i] = 0;
     }
   }
-  // (r, s, c) of this thread's 4-wide k vector in the next slice to load,
-  // and the per-slice advance of BK channels split into whole taps and a
-  // channel remainder so that stepping needs no division and no branch
+  // (r, s, c) of this thread's k vector in the next slice to load, and the
+  // per-slice advance of BK channels split into whole taps and a channel
+  // remainder so that stepping needs no division and no branch
   int kc, ks, kr;
   {
-    const int kg = a_kv * 4;
+    const int kg = a_kv * VEC;
     kc = kg % p.C;
     const int t = kg / p.C;
     ks = t % p.S;
@@ -134,21 +156,21 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
   const int step_c = BK % p.C;
   const int step_s = (BK / p.C) % p.S;
   const int step_r = (BK / p.C) / p.S;
-  // B: 4(k) x 4(n) blocks; the column part of the offset is fixed per thread
+  // B: VEC(k) x VEC(n) blocks; the column part of the offset is fixed per thread
   int b_col[T::B_ITERS], b_krow[T::B_ITERS];
 #pragma unroll
   for (int i = 0; i < T::B_ITERS; ++i) {
     const int b = tid + i * NT;
-    const int nb4 = b % (BN / 4);
-    const int kb = b / (BN / 4);
-    const int col = n0 + nb4 * 4;
-    b_krow[i] = (b < T::B_BLOCKS && col < p.K) ? kb * 4 : (1 << 30);  // first k row of the block
+    const int nbv = b % (BN / VEC);
+    const int kb = b / (BN / VEC);
+    const int col = n0 + nbv * VEC;
+    b_krow[i] = (b < T::B_BLOCKS && col < p.K) ? kb * VEC : (1 << 30);  // first k row of the block
     b_col[i] = col;
   }
   int k_next = 0;  // first k of the next slice to load
 
   uintx4 a_reg[PF][T::A_ITERS];
-  uintx4 b_reg[PF][T::B_ITERS][4];
+  uintx4 b_reg[PF][T::B_ITERS][VEC];
 
   auto issue_loads = [&](auto set_c) {
     constexpr int set = decltype(set_c)::value;
@@ -159,15 +181,15 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
     for (int i = 0; i < T::A_ITERS; ++i) {
       const bool ok = (static_cast<unsigned>(a_h0[i] + kr_t) < static_cast<unsigned>(p.H)) &
                       (static_cast<unsigned>(a_w0[i] + ks) < static_cast<unsigned>(p.W));
-      const int off = ok ? (a_off[i] + tap) * 4 : kOutOfRange;
+      const int off = ok ? (a_off[i] + tap) * ES : kOutOfRange;
       a_reg[set][i] = __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, off, 0, 0);
     }
 #pragma unroll
     for (int i = 0; i < T::B_ITERS; ++i) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < VEC; ++j) {
         const int kg = k_next + b_krow[i] + j;
-        const int off = (kg < p.Kg) ? (kg * p.K + b_col[i]) * 4 : kOutOfRange;
+        const int off = (kg < p.Kg) ? (kg * p.K + b_col[i]) * ES : kOutOfRange;
         b_reg[set][i][j] = __builtin_amdgcn_raw_buffer_load_b128(filt_rsrc, off, 0, 0);
       }
     }
@@ -183,26 +205,38 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
   };
   auto store_tiles = [&](auto set_c, int buf) {
     constexpr int set = decltype(set_c)::value;
-    float* as = As + buf * BM * LD;
-    float* bs = Bs + buf * BN * LD;
+    unsigned char* as = As + buf * BM * LD * ES;
+    unsigned char* bs = Bs + buf * BN * LD * ES;
 #pragma unroll
     for (int i = 0; i < T::A_ITERS; ++i)
-      *reinterpret_cast<uintx4*>(as + (a_row0 + i * T::A_ROWS_PER_PASS) * LD + a_kv * 4) =
+      *reinterpret_cast<uintx4*>(as + ((a_row0 + i * T::A_ROWS_PER_PASS) * LD + a_kv * VEC) * ES) =
           a_reg[set][i];
 #pragma unroll
     for (int i = 0; i < T::B_ITERS; ++i) {
       const int b = tid + i * NT;
       if (b < T::B_BLOCKS) {
-        const int nb4 = b % (BN / 4);
-        const int kb = b / (BN / 4);
-        // 4x4 transpose in registers: LDS keeps B as [n][k], k contiguous
-        unsigned int* dst = reinterpret_cast<unsigned int*>(bs) + (nb4 * 4) * LD + kb * 4;
-        const uintx4 r0 = b_reg[set][i][0], r1 = b_reg[set][i][1], r2 = b_reg[set][i][2],
-                     r3 = b_reg[set][i][3];
-        *reinterpret_cast<uintx4*>(dst + 0 * LD) = uintx4{r0.x, r1.x, r2.x, r3.x};
-        *reinterpret_cast<uintx4*>(dst + 1 * LD) = uintx4{r0.y, r1.y, r2.y, r3.y};
-        *reinterpret_cast<uintx4*>(dst + 2 * LD) = uintx4{r0.z, r1.z, r2.z, r3.z};
-        *reinterpret_cast<uintx4*>(dst + 3 * LD) = uintx4{r0.w, r1.w, r2.w, r3.w};
+        const int nbv = b % (BN / VEC);
+        const int kb = b / (BN / VEC);
+        // VEC x VEC transpose in registers: LDS keeps B as [n][k], k contiguous
+        unsigned char* dst = bs + ((nbv * VEC) * LD + kb * VEC) * ES;
+        if (T::BF16) {
+#pragma unroll
+          for (int n = 0; n < 8; ++n) {
+            const unsigned sel = (n & 1) ? 0x07060302u : 0x05040100u;  // high / low halves
+            uintx4 v;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              v[j] = __builtin_amdgcn_perm(b_reg[set][i][2 * j + 1][n >> 1],
+                                           b_reg[set][i][2 * j][n >> 1], sel);
+            *reinterpret_cast<uintx4*>(dst + n * LD * ES) = v;
+          }
+        } else {
+#pragma unroll
+          for (int n = 0; n < 4; ++n)
+            *reinterpret_cast<uintx4*>(dst + n * LD * ES) =
+                uintx4{b_reg[set][i][0][n], b_reg[set][i][1][n], b_reg[set][i][2][n],
+                       b_reg[set][i][3][n]};
+        }
       }
     }
   };
@@ -226,25 +260,31 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
   int until_flush = flush_slices;
 
   auto multiply = [&](int buf) {
-    const float* as = As + buf * BM * LD + (wm * T::WM + lr) * LD + lk * 4;
-    const float* bs = Bs + buf * BN * LD + (wn * T::WN + lr) * LD + lk * 4;
+    const unsigned char* as = As + (buf * BM * LD + (wm * T::WM + lr) * LD + lk * VEC) * ES;
+    const unsigned char* bs = Bs + (buf * BN * LD + (wn * T::WN + lr) * LD + lk * VEC) * ES;
 #pragma unroll
-    for (int k8 = 0; k8 < BK / 8; ++k8) {
-      float4 af[T::TM], bf[T::TN];
+    for (int kk = 0; kk < BK / T::KSTEP; ++kk) {
+      uintx4 af[T::TM], bf[T::TN];
 #pragma unroll
       for (int i = 0; i < T::TM; ++i)
-        af[i] = *reinterpret_cast<const float4*>(as + i * 32 * LD + k8 * 8);
+        af[i] = *reinterpret_cast<const uintx4*>(as + (i * 32 * LD + kk * T::KSTEP) * ES);
 #pragma unroll
       for (int j = 0; j < T::TN; ++j)
-        bf[j] = *reinterpret_cast<const float4*>(bs + j * 32 * LD + k8 * 8);
+        bf[j] = *reinterpret_cast<const uintx4*>(bs + (j * 32 * LD + kk * T::KSTEP) * ES);
 #pragma unroll
       for (int i = 0; i < T::TM; ++i)
 #pragma unroll
         for (int j = 0; j < T::TN; ++j) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].x, bf[j].x, acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].y, bf[j].y, acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].z, bf[j].z, acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].w, bf[j].w, acc[i][j], 0, 0, 0);
+          if (T::BF16) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(bf16x8, af[i]), __builtin_bit_cast(bf16x8, bf[j]), acc[i][j], 0,
+                0, 0);
+          } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                  __uint_as_float(af[i][t]), __uint_as_float(bf[j][t]), acc[i][j], 0, 0, 0);
+          }
         }
     }
     if (T::TWO_LEVEL) {
@@ -305,8 +345,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
 
   // ---- epilogue: D tile -> NHWC output.  In a 32x32 accumulator, lane l
   // register v holds row 8*(v/4) + 4*(l/32) + v%4, column l%32, so each
-  // store instruction writes two 128-byte row segments.
-  float* __restrict__ out = static_cast<float*>(p.out);
+  // store instruction writes two contiguous 32-element row segments.
 #pragma unroll
   for (int i = 0; i < T::TM; ++i) {
 #pragma unroll
@@ -316,19 +355,25 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_f32_kernel(const Problem 
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = rbase + 8 * (v / 4) + (v % 4);
-        if (row < p.M && col < p.K) out[static_cast<size_t>(row) * p.K + col] = acc[i][j][v];
+        if (row < p.M && col < p.K) {
+          const size_t idx = static_cast<size_t>(row) * p.K + col;
+          if (OUT_BF16)
+            static_cast<unsigned short*>(p.out)[idx] = to_bf16_bits(acc[i][j][v]);
+          else
+            static_cast<float*>(p.out)[idx] = acc[i][j][v];
+        }
       }
     }
   }
 }
 
-template <class T>
-hipError_t launch(const Problem& p, hipStream_t stream) {
+template <class T, bool OUT_BF16>
+hipError_t launch_one(const Problem& p, hipStream_t stream) {
   const int tiles_m = (p.M + T::BM - 1) / T::BM;
   const int tiles_n = (p.K + T::BN - 1) / T::BN;
-  const size_t lds_bytes = sizeof(float) * T::LDS_FLOATS;
+  const size_t lds_bytes = T::LDS_BYTES;
   if (lds_bytes > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_f32_kernel<T>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&igemm_kernel<T, OUT_BF16>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                        static_cast<int>(lds_bytes));
     if (e != hipSuccess) return e;
@@ -337,56 +382,70 @@ hipError_t launch(const Problem& p, hipStream_t stream) {
   const int nslices = (p.Kg + T::BK - 1) / T::BK;
   int flush = 1;
   while (flush * flush < nslices) ++flush;
-  hipLaunchKernelGGL((igemm_f32_kernel<T>), dim3(tiles_m * tiles_n), dim3(T::NT), lds_bytes, stream,
-                     p, flush);
+  hipLaunchKernelGGL((igemm_kernel<T, OUT_BF16>), dim3(tiles_m * tiles_n), dim3(T::NT), lds_bytes,
+                     stream, p, flush);
   return hipGetLastError();
+}
+
+template <class T>
+hipError_t launch(const Problem& p, hipStream_t stream) {
+  if (T::BF16 && p.out_bf16) return launch_one<T, T::BF16>(p, stream);
+  return launch_one<T, false>(p, stream);
 }
 
 struct TileEntry {
   const char* name;
   int bm, bn, bk;
-  int max_kg;  // longest reduction the tile's summation scheme keeps within tolerance
   hipError_t (*fn)(const Problem&, hipStream_t);
 };
 
-#define CONV2D_F32_TILE(bm, bn, bk, wm, wn, two, occ, pf, tag, maxkg) \
-  { "igemm_f32_" #bm "x" #bn "x" #bk tag, bm, bn, bk, maxkg, \
-    &launch<Tile<bm, bn, bk, wm, wn, two, occ, pf>> }
+#define CONV2D_TILE(dt, isbf, bm, bn, bk, wm, wn, two, occ, pf, tag) \
+  { "igemm_" dt "_" #bm "x" #bn "x" #bk tag, bm, bn, bk, \
+    &launch<Tile<isbf, bm, bn, bk, wm, wn, two, occ, pf>> }
 
-constexpr int kAnyKg = 0x7fffffff;
-// (A tile without the two-level summation would have to cap Kg near 1280:
-// a single fp32 chain measured 7e-5 at Kg = 2304 and 1.0e-4 at Kg = 4608.)
-
-const TileEntry kTiles[] = {
-    CONV2D_F32_TILE(256, 128, 16, 4, 2, true, 2, 1, "", kAnyKg),
-    CONV2D_F32_TILE(128, 128, 16, 2, 2, true, 2, 1, "", kAnyKg),
-    CONV2D_F32_TILE(256, 64, 16, 4, 1, true, 2, 1, "", kAnyKg),
-    CONV2D_F32_TILE(128, 64, 16, 2, 2, true, 3, 1, "", kAnyKg),
-    CONV2D_F32_TILE(64, 64, 16, 2, 2, true, 4, 1, "", kAnyKg),
-    CONV2D_F32_TILE(128, 32, 16, 4, 1, true, 4, 1, "", kAnyKg),
-    // two slices of lookahead
-    CONV2D_F32_TILE(256, 128, 16, 4, 2, true, 2, 2, "_pf2", kAnyKg),
-    CONV2D_F32_TILE(128, 128, 16, 2, 2, true, 2, 2, "_pf2", kAnyKg),
-    CONV2D_F32_TILE(128, 64, 16, 2, 2, true, 3, 2, "_pf2", kAnyKg),
-    // deeper slices
-    CONV2D_F32_TILE(128, 128, 32, 2, 2, true, 2, 1, "", kAnyKg),
-    CONV2D_F32_TILE(128, 64, 32, 2, 2, true, 3, 1, "", kAnyKg),
-    CONV2D_F32_TILE(128, 128, 32, 2, 2, true, 2, 2, "_pf2", kAnyKg),
+const TileEntry kTilesF32[] = {
+    CONV2D_TILE("f32", false, 256, 128, 16, 4, 2, true, 2, 1, ""),
+    CONV2D_TILE("f32", false, 128, 128, 16, 2, 2, true, 2, 1, ""),
+    CONV2D_TILE("f32", false, 256, 64, 16, 4, 1, true, 2, 1, ""),
+    CONV2D_TILE("f32", false, 128, 64, 16, 2, 2, true, 3, 1, ""),
+    CONV2D_TILE("f32", false, 64, 64, 16, 2, 2, true, 4, 1, ""),
+    CONV2D_TILE("f32", false, 128, 32, 16, 4, 1, true, 4, 1, ""),
+    CONV2D_TILE("f32", false, 128, 128, 32, 2, 2, true, 2, 1, ""),
+    CONV2D_TILE("f32", false, 128, 64, 32, 2, 2, true, 3, 1, ""),
+    CONV2D_TILE("f32", false, 256, 128, 32, 4, 2, true, 2, 1, ""),
 };
-constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
+const TileEntry kTilesBf16[] = {
+    CONV2D_TILE("bf16", true, 128, 128, 64, 2, 2, false, 2, 1, ""),
+    CONV2D_TILE("bf16", true, 128, 128, 32, 2, 2, false, 2, 1, ""),
+    CONV2D_TILE("bf16", true, 128, 64, 64, 2, 2, false, 3, 1, ""),
+    CONV2D_TILE("bf16", true, 128, 64, 32, 2, 2, false, 3, 1, ""),
+    CONV2D_TILE("bf16", true, 64, 64, 32, 2, 2, false, 4, 1, ""),
+};
+constexpr int kNumF32 = sizeof(kTilesF32) / sizeof(kTilesF32[0]);
+constexpr int kNumBf16 = sizeof(kTilesBf16) / sizeof(kTilesBf16[0]);
 
 }  // namespace
 
-int igemm_f32_num_tiles() { return kNumTiles; }
-const char* igemm_f32_tile_name(int tile) { return kTiles[tile].name; }
-int igemm_f32_tile_max_kg(int tile) { return kTiles[tile].max_kg; }
+int igemm_f32_num_tiles() { return kNumF32; }
+const char* igemm_f32_tile_name(int tile) { return kTilesF32[tile].name; }
 void igemm_f32_tile_shape(int tile, int* bm, int* bn, int* bk) {
-  *bm = kTiles[tile].bm;
-  *bn = kTiles[tile].bn;
-  *bk = kTiles[tile].bk;
+  *bm = kTilesF32[tile].bm;
+  *bn = kTilesF32[tile].bn;
+  *bk = kTilesF32[tile].bk;
 }
 hipError_t launch_igemm_f32(const Problem& p, int tile, hipStream_t stream) {
-  return kTiles[tile].fn(p, stream);
+  return kTilesF32[tile].fn(p, stream);
+}
+
+int igemm_bf16_num_tiles() { return kNumBf16; }
+const char* igemm_bf16_tile_name(int tile) { return kTilesBf16[tile].name; }
+void igemm_bf16_tile_shape(int tile, int* bm, int* bn, int* bk) {
+  *bm = kTilesBf16[tile].bm;
+  *bn = kTilesBf16[tile].bn;
+  *bk = kTilesBf16[tile].bk;
+}
+hipError_t launch_igemm_bf16(const Problem& p, int tile, hipStream_t stream) {
+  return kTilesBf16[tile].fn(p, stream);
 }
 
 }  // namespace conv2d
