@@ -19,7 +19,7 @@ FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
+    "-Wall", "-Wno-unused-function", "-Wno-inline-asm", "-Wno-unknown-warning-option",
 ]
 
 

@@ -19,7 +19,7 @@ namespace {
 
 constexpr long long kMaxElems = (1LL << 31) - 1;
 
-enum Family { kDirect = 0, kIgemmF32 = 1, kIgemmBf16 = 2 };
+enum Family { kDirect = 0, kIgemmF32 = 1, kIgemmBf16 = 2, kDmaF32 = 3, kDmaBf16 = 4 };
 
 struct Variant {
   Family family;
@@ -37,6 +37,8 @@ struct Table {
     for (int t = 0; t < igemm_f32_num_tiles(); ++t) v[n++] = {kIgemmF32, t, igemm_f32_tile_name(t)};
     for (int t = 0; t < igemm_bf16_num_tiles(); ++t)
       v[n++] = {kIgemmBf16, t, igemm_bf16_tile_name(t)};
+    for (int t = 0; t < igemm_dma_num_tiles(0); ++t) v[n++] = {kDmaF32, t, igemm_dma_tile_name(0, t)};
+    for (int t = 0; t < igemm_dma_num_tiles(1); ++t) v[n++] = {kDmaBf16, t, igemm_dma_tile_name(1, t)};
   }
 };
 const Table& table() {
@@ -119,6 +121,12 @@ bool supports(const Variant& v, const Problem& q) {
     case kIgemmBf16:
       return q.in_bf16 && q.C % 8 == 0 && q.K % 8 == 0 &&
              2LL * q.N * q.H * q.W * q.C < (1LL << 31) && 2LL * q.Kg * q.K < (1LL << 31);
+    case kDmaF32:  // the repacked filter rows are padded to 32 (fp32) / 64 (bf16) k
+      return !q.in_bf16 && !q.out_bf16 && q.C % 4 == 0 &&
+             4LL * q.N * q.H * q.W * q.C < (1LL << 31) && 4LL * (q.Kg + 32) * q.K < (1LL << 31);
+    case kDmaBf16:
+      return q.in_bf16 && q.C % 8 == 0 &&
+             2LL * q.N * q.H * q.W * q.C < (1LL << 31) && 2LL * (q.Kg + 64) * q.K < (1LL << 31);
   }
   return false;
 }
@@ -171,6 +179,12 @@ int select(const Problem& q, bool aligned) {
   return 0;
 }
 
+size_t workspace_bytes_for(const Variant& v, const Problem& q) {
+  if (v.family == kDmaF32) return igemm_dma_workspace_bytes(q, 0, v.tile);
+  if (v.family == kDmaBf16) return igemm_dma_workspace_bytes(q, 1, v.tile);
+  return 0;
+}
+
 bool aligned16(const void* a, const void* b, const void* c) {
   return ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) |
            reinterpret_cast<uintptr_t>(c)) & 15u) == 0;
@@ -200,8 +214,11 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     if (!supports(tb.v[id], q)) return CONV2D_STATUS_UNSUPPORTED;
     if (!al && tb.v[id].family != kDirect) return CONV2D_STATUS_UNSUPPORTED;
   }
-  (void)workspace;
-  (void)workspace_bytes;
+  const size_t need = workspace_bytes_for(tb.v[id], q);
+  if (need > 0) {
+    if (!workspace || workspace_bytes < need) return CONV2D_STATUS_WORKSPACE_TOO_SMALL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 15u) return CONV2D_STATUS_INVALID_ARGUMENT;
+  }
   q.in = in; q.filt = filt; q.out = out; q.workspace = workspace;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   hipError_t e = hipSuccess;
@@ -209,6 +226,8 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     case kDirect: e = launch_direct(q, stream); break;
     case kIgemmF32: e = launch_igemm_f32(q, tb.v[id].tile, stream); break;
     case kIgemmBf16: e = launch_igemm_bf16(q, tb.v[id].tile, stream); break;
+    case kDmaF32: e = launch_igemm_dma(q, 0, tb.v[id].tile, stream); break;
+    case kDmaBf16: e = launch_igemm_dma(q, 1, tb.v[id].tile, stream); break;
   }
   return e == hipSuccess ? CONV2D_STATUS_OK : CONV2D_STATUS_LAUNCH_FAILED;
 }
@@ -234,7 +253,7 @@ int conv2d_workspace_size(const conv2d_params* params, size_t* bytes) {
   if (!bytes) return CONV2D_STATUS_INVALID_ARGUMENT;
   int rc = derive(params, &q);
   if (rc) return rc;
-  *bytes = 0;
+  *bytes = workspace_bytes_for(table().v[select(q, true)], q);
   return CONV2D_STATUS_OK;
 }
 
@@ -246,7 +265,7 @@ int conv2d_workspace_size_variant(const conv2d_params* params, int variant_id, s
   const Table& tb = table();
   if (variant_id < 0 || variant_id >= tb.n) return CONV2D_STATUS_INVALID_ARGUMENT;
   if (!supports(tb.v[variant_id], q)) return CONV2D_STATUS_UNSUPPORTED;
-  *bytes = 0;
+  *bytes = workspace_bytes_for(tb.v[variant_id], q);
   return CONV2D_STATUS_OK;
 }
 

@@ -44,4 +44,12 @@ const char* igemm_bf16_tile_name(int tile);
 void igemm_bf16_tile_shape(int tile, int* bm, int* bn, int* bk);
 hipError_t launch_igemm_bf16(const Problem& p, int tile, hipStream_t stream);
 
+// Implicit GEMM with a multi-stage LDS ring fed by direct global->LDS loads;
+// needs the workspace for the repacked (k-contiguous) filter.
+int igemm_dma_num_tiles(int bf16);
+const char* igemm_dma_tile_name(int bf16, int tile);
+void igemm_dma_tile_shape(int bf16, int tile, int* bm, int* bn, int* bk);
+size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile);
+hipError_t launch_igemm_dma(const Problem& p, int bf16, int tile, hipStream_t stream);
+
 }  // namespace conv2d
