@@ -9,6 +9,7 @@
 // selector is a hand-tuned rule for one device (MI355X).
 #include "../../include/conv2d.h"
 
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 
@@ -19,26 +20,40 @@ namespace {
 
 constexpr long long kMaxElems = (1LL << 31) - 1;
 
-enum Family { kDirect = 0, kIgemmF32 = 1, kIgemmBf16 = 2, kDmaF32 = 3, kDmaBf16 = 4 };
+enum Family { kDirect = 0, kIgemm = 1, kDma = 2 };
 
 struct Variant {
   Family family;
-  int tile;
-  const char* name;
+  int bf16;    // element type of input and filter the variant is compiled for
+  int tile;    // index into the family's tile table
+  bool split;  // reduction split over several workgroups per output tile
+  char name[80];
 };
 
 // Variant table: id 0 is the direct kernel (supports everything), then the
-// fp32 implicit-GEMM tiles, then the bf16 ones.
+// register-staged implicit-GEMM tiles (fp32, then bf16), each followed by its
+// split-reduction twin where the tile is small enough for that to make sense,
+// then the direct-to-LDS tiles.
 struct Table {
-  Variant v[64];
+  Variant v[96];
   int n;
+  void add(Family f, int bf16, int tile, bool split, const char* base) {
+    Variant& x = v[n++];
+    x.family = f; x.bf16 = bf16; x.tile = tile; x.split = split;
+    std::snprintf(x.name, sizeof(x.name), "%s%s", base, split ? "_splitk" : "");
+  }
   Table() : n(0) {
-    v[n++] = {kDirect, 0, "direct"};
-    for (int t = 0; t < igemm_f32_num_tiles(); ++t) v[n++] = {kIgemmF32, t, igemm_f32_tile_name(t)};
-    for (int t = 0; t < igemm_bf16_num_tiles(); ++t)
-      v[n++] = {kIgemmBf16, t, igemm_bf16_tile_name(t)};
-    for (int t = 0; t < igemm_dma_num_tiles(0); ++t) v[n++] = {kDmaF32, t, igemm_dma_tile_name(0, t)};
-    for (int t = 0; t < igemm_dma_num_tiles(1); ++t) v[n++] = {kDmaBf16, t, igemm_dma_tile_name(1, t)};
+    add(kDirect, 0, 0, false, "direct");
+    for (int bf = 0; bf < 2; ++bf)
+      for (int t = 0; t < igemm_num_tiles(bf); ++t) {
+        add(kIgemm, bf, t, false, igemm_tile_name(bf, t));
+        int bm, bn, bk;
+        igemm_tile_shape(bf, t, &bm, &bn, &bk);
+        if (bm <= 128) add(kIgemm, bf, t, true, igemm_tile_name(bf, t));
+      }
+    for (int bf = 0; bf < 2; ++bf)
+      for (int t = 0; t < igemm_dma_num_tiles(bf); ++t)
+        add(kDma, bf, t, false, igemm_dma_tile_name(bf, t));
   }
 };
 const Table& table() {
@@ -109,79 +124,107 @@ int derive(const conv2d_params* p, Problem* q) {
   return CONV2D_STATUS_OK;
 }
 
-bool supports(const Variant& v, const Problem& q) {
-  switch (v.family) {
-    case kDirect:
-      return true;
-    case kIgemmF32:
-      // 16-byte gathers need C and K in multiples of 4; buffer addressing
-      // needs input and filter below 2^31 bytes
-      return !q.in_bf16 && !q.out_bf16 && q.C % 4 == 0 && q.K % 4 == 0 &&
-             4LL * q.N * q.H * q.W * q.C < (1LL << 31) && 4LL * q.Kg * q.K < (1LL << 31);
-    case kIgemmBf16:
-      return q.in_bf16 && q.C % 8 == 0 && q.K % 8 == 0 &&
-             2LL * q.N * q.H * q.W * q.C < (1LL << 31) && 2LL * q.Kg * q.K < (1LL << 31);
-    case kDmaF32:  // the repacked filter rows are padded to 32 (fp32) / 64 (bf16) k
-      return !q.in_bf16 && !q.out_bf16 && q.C % 4 == 0 &&
-             4LL * q.N * q.H * q.W * q.C < (1LL << 31) && 4LL * (q.Kg + 32) * q.K < (1LL << 31);
-    case kDmaBf16:
-      return q.in_bf16 && q.C % 8 == 0 &&
-             2LL * q.N * q.H * q.W * q.C < (1LL << 31) && 2LL * (q.Kg + 64) * q.K < (1LL << 31);
-  }
-  return false;
+void tile_shape(const Variant& v, int* bm, int* bn, int* bk) {
+  if (v.family == kIgemm) igemm_tile_shape(v.bf16, v.tile, bm, bn, bk);
+  else igemm_dma_tile_shape(v.bf16, v.tile, bm, bn, bk);
 }
 
-// Hand-tuned choice of tile for one device (MI355X: 256 compute units, two
-// 256-thread workgroups of these kernels resident per unit).
-int pick_tile(const Problem& q, Family family, int ntiles, void (*shape)(int, int*, int*, int*)) {
-  // Widest feature tile that K fills, then the tallest pixel tile that still
-  // gives every compute unit about two workgroups.
-  const long long slots = 512;
-  int best = -1;
-  long long best_score = -1;
-  for (int t = 0; t < ntiles; ++t) {
-    int bm, bn, bk;
-    const Variant cand = {family, t, ""};
-    if (!supports(cand, q)) continue;
-    shape(t, &bm, &bn, &bk);
-    const long long tm = ceil_div_ll(q.M, bm), tn = ceil_div_ll(q.K, bn);
-    const long long wgs = tm * tn;
-    // useful fraction of the launched tile area, times a machine-fill factor
-    const double useful = (1.0 * q.M * q.K) / (1.0 * tm * bm * tn * bn);
-    const long long waves = ceil_div_ll(wgs, slots);
-    const double fill = 1.0 * wgs / (1.0 * waves * slots);
-    // larger tiles reuse LDS operands better
-    const double reuse = 1.0 - 0.5 * (32.0 / bm + 32.0 / bn) * 0.5;
-    const long long score = static_cast<long long>(1e6 * useful * fill * reuse);
-    if (score > best_score) { best_score = score; best = t; }
+bool is_scalar(const Variant& v) {
+  return v.family == kIgemm && igemm_tile_is_scalar(v.bf16, v.tile);
+}
+
+bool supports(const Variant& v, const Problem& q) {
+  if (v.family == kDirect) return true;
+  const int es = q.in_bf16 ? 2 : 4, vec = 16 / es;
+  if (v.bf16 != q.in_bf16) return false;
+  if (!q.in_bf16 && q.out_bf16) return false;
+  // buffer addressing needs input and filter below 2^31 bytes
+  if (1LL * es * q.N * q.H * q.W * q.C >= (1LL << 31)) return false;
+  int bm, bn, bk;
+  tile_shape(v, &bm, &bn, &bk);
+  if (v.family == kIgemm) {
+    if (1LL * es * q.Kg * q.K >= (1LL << 31)) return false;
+    // 16-byte gathers need C and K in multiples of the vector
+    if (!is_scalar(v) && (q.C % vec != 0 || q.K % vec != 0)) return false;
+    if (v.split && (q.Kg + bk - 1) / bk < 2) return false;  // nothing to split
+    return true;
   }
-  return best;
+  // direct-to-LDS tiles: filter rows in the workspace are padded to the slice width
+  return q.C % vec == 0 && 1LL * es * (q.Kg + bk) * q.K < (1LL << 31);
+}
+
+// Number of workgroups that share one output tile in a split-reduction
+// variant: enough to give every compute unit its full set of resident
+// workgroups, at least 2, and no split shorter than 4 slices unless the
+// whole reduction is.
+int split_factor(const Variant& v, const Problem& q) {
+  if (!v.split) return 1;
+  int bm, bn, bk;
+  tile_shape(v, &bm, &bn, &bk);
+  const long long tiles = ceil_div_ll(q.M, bm) * ceil_div_ll(q.K, bn);
+  const int nslices = (q.Kg + bk - 1) / bk;
+  const long long target = 256LL * igemm_tile_occupancy(v.bf16, v.tile);
+  if (tiles == 0) return 1;  // empty batch
+  long long s = ceil_div_ll(target, tiles);
+  const long long cap = nslices / 4 > 2 ? nslices / 4 : 2;
+  if (s > cap) s = cap;
+  if (s < 2) s = 2;
+  if (s > nslices) s = nslices;
+  return static_cast<int>(s);
+}
+
+// A rough cost model, in clock cycles of a compute unit, of a variant on this
+// device (256 compute units; per unit and clock 128 fp32 or 2048 bf16
+// multiply-adds on the matrix cores; about 2000 bytes per clock of memory
+// bandwidth for the whole chip).  Each unit works through its share of the
+// workgroups; a workgroup costs its MFMA work divided by an efficiency that
+// grows with the tile (operand reuse) plus a fixed start-up and drain time
+// that co-resident workgroups overlap; a split reduction pays for writing and
+// re-reading its partial tiles and for a second launch.
+double model_cost(const Variant& v, const Problem& q) {
+  int bm, bn, bk;
+  tile_shape(v, &bm, &bn, &bk);
+  const int splits = split_factor(v, q);
+  const long long tiles = ceil_div_ll(q.M, bm) * ceil_div_ll(q.K, bn);
+  const long long wgs = tiles * splits;
+  const int nslices = (q.Kg + bk - 1) / bk;
+  const int per_split = (nslices + splits - 1) / splits;
+  const double mac_rate = q.in_bf16 ? 2048.0 : 128.0;
+  double eff = 1.0 - 0.35 * (32.0 / bm + 32.0 / bn);
+  if (is_scalar(v)) eff *= 0.8;
+  if (q.in_bf16) eff *= 0.35;  // operand delivery, not the matrix cores, bounds the bf16 tiles
+  const double wg_work = 1.0 * bm * bn * bk * per_split / mac_rate / eff;
+  const double wg_fixed = 4000.0 + bm * bn * 4 / 16.0;
+  const int occ = v.family == kIgemm ? igemm_tile_occupancy(v.bf16, v.tile) : 2;
+  const long long per_cu = ceil_div_ll(wgs, 256);
+  const long long serial_fixed = ceil_div_ll(per_cu, occ);
+  double cost = per_cu * wg_work + serial_fixed * wg_fixed;
+  if (splits > 1) cost += 4.0 * q.M * q.K * (2 * splits + 1) / 2000.0 + 7000.0;
+  return cost;
 }
 
 int select(const Problem& q, bool aligned) {
   const Table& tb = table();
-  if (aligned) {
-    if (!q.in_bf16 && igemm_f32_num_tiles() > 0) {
-      {
-        const int t = pick_tile(q, kIgemmF32, igemm_f32_num_tiles(), igemm_f32_tile_shape);
-        for (int i = 0; i < tb.n; ++i)
-          if (tb.v[i].family == kIgemmF32 && tb.v[i].tile == t) return i;
-      }
-    }
-    if (q.in_bf16 && igemm_bf16_num_tiles() > 0) {
-      {
-        const int t = pick_tile(q, kIgemmBf16, igemm_bf16_num_tiles(), igemm_bf16_tile_shape);
-        for (int i = 0; i < tb.n; ++i)
-          if (tb.v[i].family == kIgemmBf16 && tb.v[i].tile == t) return i;
-      }
-    }
+  int best = 0;
+  double best_cost = 0;
+  if (q.M == 0) return 0;  // empty batch: nothing is launched
+  for (int i = 1; i < tb.n; ++i) {
+    const Variant& v = tb.v[i];
+    if (v.family != kIgemm || !supports(v, q)) continue;
+    if (!aligned && !is_scalar(v)) continue;
+    // element-wise tiles only where the vector tiles cannot run
+    if (is_scalar(v) && aligned && q.C % (q.in_bf16 ? 8 : 4) == 0 && q.K % (q.in_bf16 ? 8 : 4) == 0)
+      continue;
+    const double c = model_cost(v, q);
+    if (best == 0 || c < best_cost) { best = i; best_cost = c; }
   }
-  return 0;
+  return best;
 }
 
 size_t workspace_bytes_for(const Variant& v, const Problem& q) {
-  if (v.family == kDmaF32) return igemm_dma_workspace_bytes(q, 0, v.tile);
-  if (v.family == kDmaBf16) return igemm_dma_workspace_bytes(q, 1, v.tile);
+  if (v.family == kDma) return igemm_dma_workspace_bytes(q, v.bf16, v.tile);
+  if (v.family == kIgemm && v.split)
+    return static_cast<size_t>(split_factor(v, q)) * q.M * q.K * sizeof(float);
   return 0;
 }
 
@@ -207,12 +250,13 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     if (env && *env) {
       const int forced = std::atoi(env);
       if (forced >= 0 && forced < tb.n && supports(tb.v[forced], q) &&
-          (al || tb.v[forced].family == kDirect))
+          (al || tb.v[forced].family == kDirect || is_scalar(tb.v[forced])))
         id = forced;
     }
   } else {
     if (!supports(tb.v[id], q)) return CONV2D_STATUS_UNSUPPORTED;
-    if (!al && tb.v[id].family != kDirect) return CONV2D_STATUS_UNSUPPORTED;
+    if (!al && tb.v[id].family != kDirect && !is_scalar(tb.v[id]))
+      return CONV2D_STATUS_UNSUPPORTED;
   }
   const size_t need = workspace_bytes_for(tb.v[id], q);
   if (need > 0) {
@@ -224,10 +268,10 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
   hipError_t e = hipSuccess;
   switch (tb.v[id].family) {
     case kDirect: e = launch_direct(q, stream); break;
-    case kIgemmF32: e = launch_igemm_f32(q, tb.v[id].tile, stream); break;
-    case kIgemmBf16: e = launch_igemm_bf16(q, tb.v[id].tile, stream); break;
-    case kDmaF32: e = launch_igemm_dma(q, 0, tb.v[id].tile, stream); break;
-    case kDmaBf16: e = launch_igemm_dma(q, 1, tb.v[id].tile, stream); break;
+    case kIgemm:
+      e = launch_igemm(q, tb.v[id].bf16, tb.v[id].tile, split_factor(tb.v[id], q), stream);
+      break;
+    case kDma: e = launch_igemm_dma(q, tb.v[id].bf16, tb.v[id].tile, stream); break;
   }
   return e == hipSuccess ? CONV2D_STATUS_OK : CONV2D_STATUS_LAUNCH_FAILED;
 }

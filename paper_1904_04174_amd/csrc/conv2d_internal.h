@@ -32,17 +32,15 @@ struct Problem {
 // error; none synchronises.  `tile` selects a compiled tile configuration.
 hipError_t launch_direct(const Problem& p, hipStream_t stream);
 
-// fp32 implicit GEMM on v_mfma_f32_32x32x2_f32.
-int igemm_f32_num_tiles();
-const char* igemm_f32_tile_name(int tile);
-void igemm_f32_tile_shape(int tile, int* bm, int* bn, int* bk);
-hipError_t launch_igemm_f32(const Problem& p, int tile, hipStream_t stream);
-
-// bf16 implicit GEMM on v_mfma_f32_32x32x16_bf16.
-int igemm_bf16_num_tiles();
-const char* igemm_bf16_tile_name(int tile);
-void igemm_bf16_tile_shape(int tile, int* bm, int* bn, int* bk);
-hipError_t launch_igemm_bf16(const Problem& p, int tile, hipStream_t stream);
+// Register-staged implicit GEMM (fp32 on v_mfma_f32_32x32x2_f32, bf16 on
+// v_mfma_f32_32x32x16_bf16).  `splits` > 1 splits the reduction over that many
+// workgroups per output tile and needs splits*M*K floats of workspace.
+int igemm_num_tiles(int bf16);
+const char* igemm_tile_name(int bf16, int tile);
+void igemm_tile_shape(int bf16, int tile, int* bm, int* bn, int* bk);
+int igemm_tile_occupancy(int bf16, int tile);   // workgroups per compute unit
+bool igemm_tile_is_scalar(int bf16, int tile);  // element-wise loads: any C, K, alignment
+hipError_t launch_igemm(const Problem& p, int bf16, int tile, int splits, hipStream_t stream);
 
 // Implicit GEMM with a multi-stage LDS ring fed by direct global->LDS loads;
 // needs the workspace for the repacked (k-contiguous) filter.

@@ -18,13 +18,24 @@
 //
 // Global loads are raw buffer loads: a tap outside the image (or a row past
 // M, or a k past Kg) gets an offset beyond the buffer and the hardware
-// returns zeros, so the gather has no branches and no selects.  Loads run PF
-// slices ahead of the MFMAs through PF register sets, LDS is double
+// returns zeros, so the gather has no branches and no selects.  Loads run one
+// slice ahead of the MFMAs through staging registers, LDS is double
 // buffered, one barrier per slice.
 //
-// Requirements (checked by the host before launch): C and K multiples of the
-// 16-byte vector (4 fp32 / 8 bf16), 16-byte aligned in/filt, input and
-// filter each below 2^31 bytes, output below 2^31 elements.
+// Two further features of the template:
+//  * SCALAR tiles (fp32) gather single elements instead of 16-byte vectors,
+//    so they take any channel and feature count (C = 3 first layers, odd K)
+//    and any 4-byte-aligned pointers.
+//  * Split reduction: gridDim.y workgroups share one output tile, each takes
+//    a contiguous range of k slices and writes an fp32 partial tile to the
+//    workspace; split_reduce_kernel adds the partials in a fixed order (so
+//    results do not depend on timing).  This is what fills the machine when
+//    M*K is small (batch-1 layers deep in a network).
+//
+// Requirements (checked by the host before launch): vector tiles need C and K
+// multiples of the 16-byte vector (4 fp32 / 8 bf16) and 16-byte aligned
+// in/filt; all tiles need input and filter each below 2^31 bytes and the
+// output below 2^31 elements.
 #include <type_traits>
 
 #include "conv2d_internal.h"
@@ -42,7 +53,7 @@ constexpr unsigned kRsrcFlags = 0x00020000u;  // raw buffer, 32-bit data format
 constexpr int kOutOfRange = static_cast<int>(0x80000000u);
 
 template <bool BF16_, int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, bool TWO_LEVEL_,
-          int OCC_, int PF_>
+          int OCC_, bool SCALAR_>
 struct Tile {
   static constexpr bool BF16 = BF16_;
   static constexpr int BM = BM_, BN = BN_, BK = BK_;
@@ -54,7 +65,7 @@ struct Tile {
   // and 1.0e-4 at Kg = 4608).  Costs one extra register per accumulator.
   static constexpr bool TWO_LEVEL = TWO_LEVEL_;
   static constexpr int OCC = OCC_;  // wavefronts per SIMD the register allocation must allow
-  static constexpr int PF = PF_;    // slices of global-load lookahead (register sets)
+  static constexpr bool SCALAR = SCALAR_;  // element-wise global loads (any C, K)
   static constexpr int ES = BF16 ? 2 : 4;   // element size in bytes
   static constexpr int VEC = 16 / ES;       // elements per 16-byte vector
   static constexpr int KSTEP = 2 * VEC;     // k consumed per fragment read (two lane halves)
@@ -64,13 +75,15 @@ struct Tile {
   static constexpr int TM = WM / 32, TN = WN / 32;
   static constexpr int LD = BK + VEC;  // LDS row stride in elements: 16 bytes of padding keep
                                        // the 16-byte fragment reads free of bank conflicts
-  static constexpr int KV = BK / VEC;  // 16-byte vectors per A row
+  static constexpr int AV = SCALAR ? 1 : VEC;  // elements per global load of A
+  static constexpr int KV = BK / AV;           // global loads per A row
   static constexpr int A_ROWS_PER_PASS = NT / KV;
   static constexpr int A_ITERS = BM / A_ROWS_PER_PASS;
-  static constexpr int B_BLOCKS = (BK / VEC) * (BN / VEC);  // VEC(k) x VEC(n) blocks
+  // B work items: VEC(k) x VEC(n) blocks, or single elements for SCALAR tiles
+  static constexpr int B_BLOCKS = SCALAR ? BK * BN : (BK / VEC) * (BN / VEC);
   static constexpr int B_ITERS = (B_BLOCKS + NT - 1) / NT;
   static constexpr int LDS_BYTES = 2 * (BM + BN) * LD * ES;
-  static_assert(PF == 1 || PF == 2, "one or two register sets");
+  static_assert(!(SCALAR && BF16), "element-wise tiles are fp32 only");
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of 32x32");
   static_assert(BK % KSTEP == 0, "BK must be a multiple of the fragment step");
   static_assert(NT % KV == 0 && BM % A_ROWS_PER_PASS == 0, "A tile must divide over the threads");
@@ -86,11 +99,48 @@ __device__ __forceinline__ unsigned short to_bf16_bits(float x) {
   return static_cast<unsigned short>(u >> 16);
 }
 
+// Sum of the `splits` fp32 partial tiles of a split reduction, in split order.
+template <bool OUT_BF16>
+__global__ __launch_bounds__(256) void split_reduce_kernel(const float* __restrict__ partial,
+                                                           void* __restrict__ out, int total,
+                                                           int splits) {
+  const int i0 = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i0 >= total) return;
+  if (i0 + 4 <= total && (total & 3) == 0) {
+    float4 acc = *reinterpret_cast<const float4*>(partial + i0);
+    for (int s = 1; s < splits; ++s) {
+      const float4 v = *reinterpret_cast<const float4*>(partial + static_cast<size_t>(s) * total + i0);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    if (OUT_BF16) {
+      ushort4 o = {to_bf16_bits(acc.x), to_bf16_bits(acc.y), to_bf16_bits(acc.z), to_bf16_bits(acc.w)};
+      *reinterpret_cast<ushort4*>(static_cast<unsigned short*>(out) + i0) = o;
+    } else {
+      *reinterpret_cast<float4*>(static_cast<float*>(out) + i0) = acc;
+    }
+  } else {
+    for (int i = i0; i < total && i < i0 + 4; ++i) {
+      float acc = partial[i];
+      for (int s = 1; s < splits; ++s) acc += partial[static_cast<size_t>(s) * total + i];
+      if (OUT_BF16)
+        static_cast<unsigned short*>(out)[i] = to_bf16_bits(acc);
+      else
+        static_cast<float*>(out)[i] = acc;
+    }
+  }
+}
+
+// gridDim.x = output tiles, gridDim.y = splits of the reduction.  With
+// gridDim.y > 1 workgroup (x, y) multiplies slices [y*slices_per_split,
+// (y+1)*slices_per_split) and stores an fp32 partial tile at
+// p.workspace + y*M*K floats; otherwise it stores the result to p.out.
 template <class T, bool OUT_BF16>
 __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
+                                                              const int slices_per_split,
                                                               const int flush_slices) {
-  constexpr int BM = T::BM, BN = T::BN, BK = T::BK, LD = T::LD, NT = T::NT, PF = T::PF;
-  constexpr int ES = T::ES, VEC = T::VEC;
+  constexpr int BM = T::BM, BN = T::BN, BK = T::BK, LD = T::LD, NT = T::NT;
+  constexpr int ES = T::ES, VEC = T::VEC, AV = T::AV;
+  constexpr bool SCALAR = T::SCALAR;
   extern __shared__ __align__(16) unsigned char lds[];
   unsigned char* As = lds;                          // [2][BM][LD] elements
   unsigned char* Bs = lds + 2 * BM * LD * ES;       // [2][BN][LD] elements
@@ -114,6 +164,11 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
   const int tile = xcd * per + (xcd < rem ? xcd : rem) + local;
   const int m0 = (tile / tiles_n) * BM;
   const int n0 = (tile % tiles_n) * BN;
+
+  // k slices of this workgroup
+  const int nslices_all = (p.Kg + BK - 1) / BK;
+  const int slice_begin = blockIdx.y * slices_per_split;
+  const int nslices = min(slices_per_split, nslices_all - slice_begin);
 
   const __amdgpu_buffer_rsrc_t in_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<void*>(p.in), 0, p.N * p.H * p.W * p.C * ES, kRsrcFlags);
@@ -142,12 +197,13 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
       a_off[i] = 0;
     }
   }
-  // (r, s, c) of this thread's k vector in the next slice to load, and the
+  // (r, s, c) of this thread's k (vector) in the next slice to load, and the
   // per-slice advance of BK channels split into whole taps and a channel
   // remainder so that stepping needs no division and no branch
+  int k_next = slice_begin * BK;  // first k of the next slice to load
   int kc, ks, kr;
   {
-    const int kg = a_kv * VEC;
+    const int kg = k_next + a_kv * AV;
     kc = kg % p.C;
     const int t = kg / p.C;
     ks = t % p.S;
@@ -156,24 +212,26 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
   const int step_c = BK % p.C;
   const int step_s = (BK / p.C) % p.S;
   const int step_r = (BK / p.C) / p.S;
-  // B: VEC(k) x VEC(n) blocks; the column part of the offset is fixed per thread
+  // B, vector tiles: VEC(k) x VEC(n) blocks, first k row and column fixed per
+  // thread.  SCALAR tiles: single elements, columns fastest over the threads.
   int b_col[T::B_ITERS], b_krow[T::B_ITERS];
 #pragma unroll
   for (int i = 0; i < T::B_ITERS; ++i) {
     const int b = tid + i * NT;
-    const int nbv = b % (BN / VEC);
-    const int kb = b / (BN / VEC);
-    const int col = n0 + nbv * VEC;
-    b_krow[i] = (b < T::B_BLOCKS && col < p.K) ? kb * VEC : (1 << 30);  // first k row of the block
+    const int per_row = SCALAR ? BN : BN / VEC;
+    const int col = n0 + (b % per_row) * (SCALAR ? 1 : VEC);
+    const int kb = b / per_row;
+    b_krow[i] = (b < T::B_BLOCKS && col < p.K) ? kb * (SCALAR ? 1 : VEC) : (1 << 30);
     b_col[i] = col;
   }
-  int k_next = 0;  // first k of the next slice to load
 
-  uintx4 a_reg[PF][T::A_ITERS];
-  uintx4 b_reg[PF][T::B_ITERS][VEC];
+  // staging registers (only the set that matches the tile kind is live)
+  uintx4 a_vec[SCALAR ? 1 : T::A_ITERS];
+  uintx4 b_vec[SCALAR ? 1 : T::B_ITERS][VEC];
+  unsigned a_elt[SCALAR ? T::A_ITERS : 1];
+  unsigned b_elt[SCALAR ? T::B_ITERS : 1];
 
-  auto issue_loads = [&](auto set_c) {
-    constexpr int set = decltype(set_c)::value;
+  auto issue_loads = [&]() {
     const int tap = (kr * p.W + ks) * p.C + kc;
     // past the last window row (k >= Kg) the row test below must fail
     const int kr_t = (kr < p.R) ? kr : (1 << 30);
@@ -182,15 +240,24 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
       const bool ok = (static_cast<unsigned>(a_h0[i] + kr_t) < static_cast<unsigned>(p.H)) &
                       (static_cast<unsigned>(a_w0[i] + ks) < static_cast<unsigned>(p.W));
       const int off = ok ? (a_off[i] + tap) * ES : kOutOfRange;
-      a_reg[set][i] = __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, off, 0, 0);
+      if constexpr (SCALAR)
+        a_elt[i] = __builtin_amdgcn_raw_buffer_load_b32(in_rsrc, off, 0, 0);
+      else
+        a_vec[i] = __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, off, 0, 0);
     }
 #pragma unroll
     for (int i = 0; i < T::B_ITERS; ++i) {
-#pragma unroll
-      for (int j = 0; j < VEC; ++j) {
-        const int kg = k_next + b_krow[i] + j;
+      if constexpr (SCALAR) {
+        const int kg = k_next + b_krow[i];
         const int off = (kg < p.Kg) ? (kg * p.K + b_col[i]) * ES : kOutOfRange;
-        b_reg[set][i][j] = __builtin_amdgcn_raw_buffer_load_b128(filt_rsrc, off, 0, 0);
+        b_elt[i] = __builtin_amdgcn_raw_buffer_load_b32(filt_rsrc, off, 0, 0);
+      } else {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          const int kg = k_next + b_krow[i] + j;
+          const int off = (kg < p.Kg) ? (kg * p.K + b_col[i]) * ES : kOutOfRange;
+          b_vec[i][j] = __builtin_amdgcn_raw_buffer_load_b128(filt_rsrc, off, 0, 0);
+        }
       }
     }
     // advance to the following slice
@@ -203,39 +270,46 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
     ks -= carry_s ? p.S : 0;
     kr += step_r + carry_s;
   };
-  auto store_tiles = [&](auto set_c, int buf) {
-    constexpr int set = decltype(set_c)::value;
+  auto store_tiles = [&](int buf) {
     unsigned char* as = As + buf * BM * LD * ES;
     unsigned char* bs = Bs + buf * BN * LD * ES;
 #pragma unroll
-    for (int i = 0; i < T::A_ITERS; ++i)
-      *reinterpret_cast<uintx4*>(as + ((a_row0 + i * T::A_ROWS_PER_PASS) * LD + a_kv * VEC) * ES) =
-          a_reg[set][i];
+    for (int i = 0; i < T::A_ITERS; ++i) {
+      unsigned char* dst = as + ((a_row0 + i * T::A_ROWS_PER_PASS) * LD + a_kv * AV) * ES;
+      if constexpr (SCALAR)
+        *reinterpret_cast<unsigned*>(dst) = a_elt[i];
+      else
+        *reinterpret_cast<uintx4*>(dst) = a_vec[i];
+    }
 #pragma unroll
     for (int i = 0; i < T::B_ITERS; ++i) {
       const int b = tid + i * NT;
       if (b < T::B_BLOCKS) {
-        const int nbv = b % (BN / VEC);
-        const int kb = b / (BN / VEC);
-        // VEC x VEC transpose in registers: LDS keeps B as [n][k], k contiguous
-        unsigned char* dst = bs + ((nbv * VEC) * LD + kb * VEC) * ES;
-        if (T::BF16) {
-#pragma unroll
-          for (int n = 0; n < 8; ++n) {
-            const unsigned sel = (n & 1) ? 0x07060302u : 0x05040100u;  // high / low halves
-            uintx4 v;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-              v[j] = __builtin_amdgcn_perm(b_reg[set][i][2 * j + 1][n >> 1],
-                                           b_reg[set][i][2 * j][n >> 1], sel);
-            *reinterpret_cast<uintx4*>(dst + n * LD * ES) = v;
-          }
+        if constexpr (SCALAR) {
+          // LDS keeps B as [n][k], k contiguous
+          *reinterpret_cast<unsigned*>(bs + ((b % BN) * LD + b / BN) * ES) = b_elt[i];
         } else {
+          const int nbv = b % (BN / VEC);
+          const int kb = b / (BN / VEC);
+          // VEC x VEC transpose in registers
+          unsigned char* dst = bs + ((nbv * VEC) * LD + kb * VEC) * ES;
+          if constexpr (T::BF16) {
 #pragma unroll
-          for (int n = 0; n < 4; ++n)
-            *reinterpret_cast<uintx4*>(dst + n * LD * ES) =
-                uintx4{b_reg[set][i][0][n], b_reg[set][i][1][n], b_reg[set][i][2][n],
-                       b_reg[set][i][3][n]};
+            for (int n = 0; n < 8; ++n) {
+              const unsigned sel = (n & 1) ? 0x07060302u : 0x05040100u;  // high / low halves
+              uintx4 v;
+#pragma unroll
+              for (int j = 0; j < 4; ++j)
+                v[j] = __builtin_amdgcn_perm(b_vec[i][2 * j + 1][n >> 1], b_vec[i][2 * j][n >> 1],
+                                             sel);
+              *reinterpret_cast<uintx4*>(dst + n * LD * ES) = v;
+            }
+          } else {
+#pragma unroll
+            for (int n = 0; n < 4; ++n)
+              *reinterpret_cast<uintx4*>(dst + n * LD * ES) =
+                  uintx4{b_vec[i][0][n], b_vec[i][1][n], b_vec[i][2][n], b_vec[i][3][n]};
+          }
         }
       }
     }
@@ -303,35 +377,30 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
     }
   };
 
-  using Set0 = std::integral_constant<int, 0>;
-  using Set1 = std::integral_constant<int, PF - 1>;  // the same set as Set0 when PF == 1
-
-  // Slices past the end are loaded as zeros (their offsets are out of range)
-  // and multiplied by nobody, so the pipeline needs no tail special cases.
-  const int nslices = (p.Kg + BK - 1) / BK;
-  issue_loads(Set0{});
-  if (PF == 2) issue_loads(Set1{});
-  store_tiles(Set0{}, 0);
+  // The slice loaded after the last one of this workgroup is multiplied by
+  // nobody, so the pipeline needs no tail special case (past Kg it reads as
+  // zeros: its offsets are out of range).
+  issue_loads();
+  store_tiles(0);
   __syncthreads();
 
   for (int slice = 0; slice < nslices; slice += 2) {
-    // even slice: its data is in LDS buffer 0 and register set 0 is free.
-    // The scheduling fences keep the loads ahead of the MFMAs: if the
+    // even slice: its data is in LDS buffer 0 and the staging registers are
+    // free.  The scheduling fences keep the loads ahead of the MFMAs: if the
     // compiler sinks them, their destination registers get shared with the
     // LDS fragments and every LDS read then waits for all loads in flight.
-    issue_loads(Set0{});
+    issue_loads();
     __builtin_amdgcn_sched_barrier(0);
     multiply(0);
     __builtin_amdgcn_sched_barrier(0);
-    store_tiles(Set1{}, 1);  // PF == 1: the set just loaded; PF == 2: the one loaded a slice ago
+    store_tiles(1);
     __syncthreads();
     if (slice + 1 >= nslices) break;
-    // odd slice: LDS buffer 1, register set 1 (PF == 2) is free
-    issue_loads(Set1{});
+    issue_loads();
     __builtin_amdgcn_sched_barrier(0);
     multiply(1);
     __builtin_amdgcn_sched_barrier(0);
-    store_tiles(Set0{}, 0);
+    store_tiles(0);
     __syncthreads();
   }
   if (T::TWO_LEVEL) {
@@ -343,9 +412,13 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
         for (int v = 0; v < 16; ++v) acc[i][j][v] += total[i][j][v];
   }
 
-  // ---- epilogue: D tile -> NHWC output.  In a 32x32 accumulator, lane l
-  // register v holds row 8*(v/4) + 4*(l/32) + v%4, column l%32, so each
-  // store instruction writes two contiguous 32-element row segments.
+  // ---- epilogue: D tile -> NHWC output (or the fp32 partial of this split).
+  // In a 32x32 accumulator, lane l register v holds row 8*(v/4) + 4*(l/32) +
+  // v%4, column l%32, so each store instruction writes two contiguous
+  // 32-element row segments.
+  const bool to_partial = gridDim.y > 1;
+  float* part = static_cast<float*>(p.workspace) +
+                static_cast<size_t>(blockIdx.y) * static_cast<size_t>(p.M) * p.K;
 #pragma unroll
   for (int i = 0; i < T::TM; ++i) {
 #pragma unroll
@@ -357,7 +430,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
         const int row = rbase + 8 * (v / 4) + (v % 4);
         if (row < p.M && col < p.K) {
           const size_t idx = static_cast<size_t>(row) * p.K + col;
-          if (OUT_BF16)
+          if (to_partial)
+            part[idx] = acc[i][j][v];
+          else if (OUT_BF16)
             static_cast<unsigned short*>(p.out)[idx] = to_bf16_bits(acc[i][j][v]);
           else
             static_cast<float*>(p.out)[idx] = acc[i][j][v];
@@ -368,7 +443,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
 }
 
 template <class T, bool OUT_BF16>
-hipError_t launch_one(const Problem& p, hipStream_t stream) {
+hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   const int tiles_m = (p.M + T::BM - 1) / T::BM;
   const int tiles_n = (p.K + T::BN - 1) / T::BN;
   const size_t lds_bytes = T::LDS_BYTES;
@@ -378,74 +453,80 @@ hipError_t launch_one(const Problem& p, hipStream_t stream) {
                                        static_cast<int>(lds_bytes));
     if (e != hipSuccess) return e;
   }
-  // flush interval of the two-level summation: about sqrt(#slices)
   const int nslices = (p.Kg + T::BK - 1) / T::BK;
+  if (splits < 1) splits = 1;
+  if (splits > nslices) splits = nslices;
+  const int per_split = (nslices + splits - 1) / splits;
+  splits = (nslices + per_split - 1) / per_split;  // no empty split
+  // flush interval of the two-level summation: about sqrt(#slices)
   int flush = 1;
-  while (flush * flush < nslices) ++flush;
-  hipLaunchKernelGGL((igemm_kernel<T, OUT_BF16>), dim3(tiles_m * tiles_n), dim3(T::NT), lds_bytes,
-                     stream, p, flush);
+  while (flush * flush < per_split) ++flush;
+  hipLaunchKernelGGL((igemm_kernel<T, OUT_BF16>), dim3(tiles_m * tiles_n, splits), dim3(T::NT),
+                     lds_bytes, stream, p, per_split, flush);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || splits == 1) return e;
+  const int total = p.M * p.K;
+  hipLaunchKernelGGL((split_reduce_kernel<OUT_BF16>), dim3((total + 1023) / 1024), dim3(256), 0,
+                     stream, static_cast<const float*>(p.workspace), p.out, total, splits);
   return hipGetLastError();
 }
 
 template <class T>
-hipError_t launch(const Problem& p, hipStream_t stream) {
-  if (T::BF16 && p.out_bf16) return launch_one<T, T::BF16>(p, stream);
-  return launch_one<T, false>(p, stream);
+hipError_t launch(const Problem& p, int splits, hipStream_t stream) {
+  if (T::BF16 && p.out_bf16) return launch_one<T, T::BF16>(p, splits, stream);
+  return launch_one<T, false>(p, splits, stream);
 }
 
 struct TileEntry {
   const char* name;
-  int bm, bn, bk;
-  hipError_t (*fn)(const Problem&, hipStream_t);
+  int bm, bn, bk, occ;
+  bool scalar;
+  hipError_t (*fn)(const Problem&, int, hipStream_t);
 };
 
-#define CONV2D_TILE(dt, isbf, bm, bn, bk, wm, wn, two, occ, pf, tag) \
-  { "igemm_" dt "_" #bm "x" #bn "x" #bk tag, bm, bn, bk, \
-    &launch<Tile<isbf, bm, bn, bk, wm, wn, two, occ, pf>> }
+#define CONV2D_TILE(dt, isbf, bm, bn, bk, wm, wn, two, occ, scalar, tag) \
+  { "igemm_" dt "_" #bm "x" #bn "x" #bk tag, bm, bn, bk, occ, scalar, \
+    &launch<Tile<isbf, bm, bn, bk, wm, wn, two, occ, scalar>> }
 
 const TileEntry kTilesF32[] = {
-    CONV2D_TILE("f32", false, 256, 128, 16, 4, 2, true, 2, 1, ""),
-    CONV2D_TILE("f32", false, 128, 128, 16, 2, 2, true, 2, 1, ""),
-    CONV2D_TILE("f32", false, 256, 64, 16, 4, 1, true, 2, 1, ""),
-    CONV2D_TILE("f32", false, 128, 64, 16, 2, 2, true, 3, 1, ""),
-    CONV2D_TILE("f32", false, 64, 64, 16, 2, 2, true, 4, 1, ""),
-    CONV2D_TILE("f32", false, 128, 32, 16, 4, 1, true, 4, 1, ""),
-    CONV2D_TILE("f32", false, 128, 128, 32, 2, 2, true, 2, 1, ""),
-    CONV2D_TILE("f32", false, 128, 64, 32, 2, 2, true, 3, 1, ""),
-    CONV2D_TILE("f32", false, 256, 128, 32, 4, 2, true, 2, 1, ""),
+    CONV2D_TILE("f32", false, 256, 128, 16, 4, 2, true, 2, false, ""),
+    CONV2D_TILE("f32", false, 128, 128, 16, 2, 2, true, 2, false, ""),
+    CONV2D_TILE("f32", false, 256, 64, 16, 4, 1, true, 2, false, ""),
+    CONV2D_TILE("f32", false, 128, 64, 16, 2, 2, true, 3, false, ""),
+    CONV2D_TILE("f32", false, 64, 64, 16, 2, 2, true, 4, false, ""),
+    CONV2D_TILE("f32", false, 128, 32, 16, 4, 1, true, 4, false, ""),
+    CONV2D_TILE("f32", false, 128, 128, 32, 2, 2, true, 2, false, ""),
+    CONV2D_TILE("f32", false, 128, 64, 32, 2, 2, true, 3, false, ""),
+    CONV2D_TILE("f32", false, 256, 128, 32, 4, 2, true, 2, false, ""),
+    CONV2D_TILE("f32", false, 128, 64, 16, 2, 2, true, 3, true, "_scalar"),
+    CONV2D_TILE("f32", false, 64, 64, 16, 2, 2, true, 4, true, "_scalar"),
+    CONV2D_TILE("f32", false, 128, 32, 16, 4, 1, true, 4, true, "_scalar"),
 };
 const TileEntry kTilesBf16[] = {
-    CONV2D_TILE("bf16", true, 128, 128, 64, 2, 2, false, 2, 1, ""),
-    CONV2D_TILE("bf16", true, 128, 128, 32, 2, 2, false, 2, 1, ""),
-    CONV2D_TILE("bf16", true, 128, 64, 64, 2, 2, false, 3, 1, ""),
-    CONV2D_TILE("bf16", true, 128, 64, 32, 2, 2, false, 3, 1, ""),
-    CONV2D_TILE("bf16", true, 64, 64, 32, 2, 2, false, 4, 1, ""),
+    CONV2D_TILE("bf16", true, 128, 128, 64, 2, 2, false, 2, false, ""),
+    CONV2D_TILE("bf16", true, 128, 128, 32, 2, 2, false, 2, false, ""),
+    CONV2D_TILE("bf16", true, 128, 64, 64, 2, 2, false, 3, false, ""),
+    CONV2D_TILE("bf16", true, 128, 64, 32, 2, 2, false, 3, false, ""),
+    CONV2D_TILE("bf16", true, 64, 64, 32, 2, 2, false, 4, false, ""),
 };
 constexpr int kNumF32 = sizeof(kTilesF32) / sizeof(kTilesF32[0]);
 constexpr int kNumBf16 = sizeof(kTilesBf16) / sizeof(kTilesBf16[0]);
 
 }  // namespace
 
-int igemm_f32_num_tiles() { return kNumF32; }
-const char* igemm_f32_tile_name(int tile) { return kTilesF32[tile].name; }
-void igemm_f32_tile_shape(int tile, int* bm, int* bn, int* bk) {
-  *bm = kTilesF32[tile].bm;
-  *bn = kTilesF32[tile].bn;
-  *bk = kTilesF32[tile].bk;
+int igemm_num_tiles(int bf16) { return bf16 ? kNumBf16 : kNumF32; }
+static const TileEntry& entry(int bf16, int tile) { return bf16 ? kTilesBf16[tile] : kTilesF32[tile]; }
+const char* igemm_tile_name(int bf16, int tile) { return entry(bf16, tile).name; }
+void igemm_tile_shape(int bf16, int tile, int* bm, int* bn, int* bk) {
+  const TileEntry& t = entry(bf16, tile);
+  *bm = t.bm;
+  *bn = t.bn;
+  *bk = t.bk;
 }
-hipError_t launch_igemm_f32(const Problem& p, int tile, hipStream_t stream) {
-  return kTilesF32[tile].fn(p, stream);
-}
-
-int igemm_bf16_num_tiles() { return kNumBf16; }
-const char* igemm_bf16_tile_name(int tile) { return kTilesBf16[tile].name; }
-void igemm_bf16_tile_shape(int tile, int* bm, int* bn, int* bk) {
-  *bm = kTilesBf16[tile].bm;
-  *bn = kTilesBf16[tile].bn;
-  *bk = kTilesBf16[tile].bk;
-}
-hipError_t launch_igemm_bf16(const Problem& p, int tile, hipStream_t stream) {
-  return kTilesBf16[tile].fn(p, stream);
+int igemm_tile_occupancy(int bf16, int tile) { return entry(bf16, tile).occ; }
+bool igemm_tile_is_scalar(int bf16, int tile) { return entry(bf16, tile).scalar; }
+hipError_t launch_igemm(const Problem& p, int bf16, int tile, int splits, hipStream_t stream) {
+  return entry(bf16, tile).fn(p, splits, stream);
 }
 
 }  // namespace conv2d

@@ -167,3 +167,29 @@ def test_compute_bound_layers_use_the_matrix_cores():
     for name in wl.VGG_N16 + ["L-same", "L-valid", "L-s2", "R3x3"]:
         v = B.conv2d_selected_variant(B.params_of_layer(wl.LAYERS[name]))
         assert B.conv2d_variant_name(v).startswith("igemm_f32"), name
+
+
+def test_empty_batch_has_a_selection_and_no_workspace():
+    for dt in (B.F32, B.BF16):
+        p = B.make_params(0, 14, 14, 512, 512, 3, 3, 1, 1, B.PAD_SAME, dt, B.F32)
+        assert B.conv2d_selected_variant(p) == 0
+        assert B.conv2d_workspace_size(p) == 0
+        for v in range(B.conv2d_num_variants()):
+            if B.conv2d_variant_supports(p, v):
+                assert B.conv2d_workspace_size(p, v) >= 0
+
+
+def test_split_reduction_variants_state_their_workspace():
+    p = B.params_of_layer(wl.LAYERS["V14-N1"])
+    names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
+    split = [v for v, n in enumerate(names) if n.endswith("_splitk") and B.conv2d_variant_supports(p, v)]
+    assert split
+    for v in split:
+        ws = B.conv2d_workspace_size(p, v)
+        # a whole number (>= 2) of fp32 partial outputs
+        assert ws % (4 * 196 * 512) == 0 and ws // (4 * 196 * 512) >= 2
+    # one slice of reduction cannot be split
+    p1 = B.make_params(1, 8, 8, 4, 8, 1, 1)
+    for v, n in enumerate(names):
+        if n.endswith("_splitk"):
+            assert not B.conv2d_variant_supports(p1, v)
