@@ -29,7 +29,7 @@ def sources():
 
 
 def _deps():
-    hdrs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    hdrs = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h") or f.endswith(".inc")]
     hdrs.append(os.path.join(os.path.dirname(HERE), "include", "conv2d.h"))
     hdrs.append(os.path.abspath(__file__))
     return max(os.path.getmtime(h) for h in hdrs)

@@ -35,7 +35,7 @@ struct Variant {
 // split-reduction twin where the tile is small enough for that to make sense,
 // then the direct-to-LDS tiles.
 struct Table {
-  Variant v[96];
+  Variant v[128];
   int n;
   void add(Family f, int bf16, int tile, bool split, const char* base) {
     Variant& x = v[n++];
@@ -52,8 +52,10 @@ struct Table {
         if (bm <= 128) add(kIgemm, bf, t, true, igemm_tile_name(bf, t));
       }
     for (int bf = 0; bf < 2; ++bf)
-      for (int t = 0; t < igemm_dma_num_tiles(bf); ++t)
+      for (int t = 0; t < igemm_dma_num_tiles(bf); ++t) {
         add(kDma, bf, t, false, igemm_dma_tile_name(bf, t));
+        add(kDma, bf, t, true, igemm_dma_tile_name(bf, t));
+      }
   }
 };
 const Table& table() {
@@ -129,6 +131,11 @@ void tile_shape(const Variant& v, int* bm, int* bn, int* bk) {
   else igemm_dma_tile_shape(v.bf16, v.tile, bm, bn, bk);
 }
 
+int occupancy(const Variant& v) {
+  return v.family == kIgemm ? igemm_tile_occupancy(v.bf16, v.tile)
+                            : igemm_dma_tile_occupancy(v.bf16, v.tile);
+}
+
 bool is_scalar(const Variant& v) {
   return v.family == kIgemm && igemm_tile_is_scalar(v.bf16, v.tile);
 }
@@ -149,8 +156,13 @@ bool supports(const Variant& v, const Problem& q) {
     if (v.split && (q.Kg + bk - 1) / bk < 2) return false;  // nothing to split
     return true;
   }
-  // direct-to-LDS tiles: filter rows in the workspace are padded to the slice width
-  return q.C % vec == 0 && 1LL * es * (q.Kg + bk) * q.K < (1LL << 31);
+  // direct-to-LDS tiles: filter rows in the workspace are padded to the slice
+  // width; the input descriptor is extended by up to a window of bytes
+  if (q.C % vec != 0 || 1LL * es * (q.Kg + bk) * q.K >= (1LL << 31)) return false;
+  if (1LL * es * (1LL * q.N * q.H * q.W + 1LL * q.R * q.W + q.S) * q.C >= (1LL << 31)) return false;
+  if (igemm_dma_tile_is_uniform(v.bf16, v.tile) && (q.C % bk != 0 || q.R * q.S > 31)) return false;
+  if (v.split && (q.Kg + bk - 1) / bk < 2) return false;
+  return true;
 }
 
 // Number of workgroups that share one output tile in a split-reduction
@@ -163,7 +175,7 @@ int split_factor(const Variant& v, const Problem& q) {
   tile_shape(v, &bm, &bn, &bk);
   const long long tiles = ceil_div_ll(q.M, bm) * ceil_div_ll(q.K, bn);
   const int nslices = (q.Kg + bk - 1) / bk;
-  const long long target = 256LL * igemm_tile_occupancy(v.bf16, v.tile);
+  const long long target = 256LL * occupancy(v);
   if (tiles == 0) return 1;  // empty batch
   long long s = ceil_div_ll(target, tiles);
   const long long cap = nslices / 4 > 2 ? nslices / 4 : 2;
@@ -173,14 +185,31 @@ int split_factor(const Variant& v, const Problem& q) {
   return static_cast<int>(s);
 }
 
+// Fraction of the MFMA peak that a tile configuration sustains on a long
+// reduction with every compute unit busy (measured on MI355X, rounded).
+double tile_efficiency(const Variant& v, int bm, int bn) {
+  const int area = bm * bn;
+  if (v.family == kDma) {
+    if (!v.bf16) return area >= 128 * 64 ? 0.86 : 0.80;
+    if (area >= 256 * 256) return 0.46;
+    if (area >= 256 * 128) return 0.40;
+    if (area >= 128 * 128) return 0.36;
+    return area >= 128 * 64 ? 0.28 : 0.20;
+  }
+  double eff = v.bf16 ? 0.20 : 0.78;
+  eff *= 1.0 - 0.25 * (32.0 / bm + 32.0 / bn);
+  if (is_scalar(v)) eff *= 0.8;
+  return eff;
+}
+
 // A rough cost model, in clock cycles of a compute unit, of a variant on this
 // device (256 compute units; per unit and clock 128 fp32 or 2048 bf16
 // multiply-adds on the matrix cores; about 2000 bytes per clock of memory
 // bandwidth for the whole chip).  Each unit works through its share of the
-// workgroups; a workgroup costs its MFMA work divided by an efficiency that
-// grows with the tile (operand reuse) plus a fixed start-up and drain time
-// that co-resident workgroups overlap; a split reduction pays for writing and
-// re-reading its partial tiles and for a second launch.
+// workgroups; a workgroup costs its MFMA work divided by the tile's measured
+// efficiency plus a fixed start-up and drain time that co-resident workgroups
+// overlap; the direct-to-LDS kernels pay for the filter repack, and a split
+// reduction for writing and re-reading its partial tiles and a second launch.
 double model_cost(const Variant& v, const Problem& q) {
   int bm, bn, bk;
   tile_shape(v, &bm, &bn, &bk);
@@ -190,31 +219,51 @@ double model_cost(const Variant& v, const Problem& q) {
   const int nslices = (q.Kg + bk - 1) / bk;
   const int per_split = (nslices + splits - 1) / splits;
   const double mac_rate = q.in_bf16 ? 2048.0 : 128.0;
-  double eff = 1.0 - 0.35 * (32.0 / bm + 32.0 / bn);
-  if (is_scalar(v)) eff *= 0.8;
-  if (q.in_bf16) eff *= 0.35;  // operand delivery, not the matrix cores, bounds the bf16 tiles
-  const double wg_work = 1.0 * bm * bn * bk * per_split / mac_rate / eff;
+  const double wg_work = 1.0 * bm * bn * bk * per_split / mac_rate / tile_efficiency(v, bm, bn);
   const double wg_fixed = 4000.0 + bm * bn * 4 / 16.0;
-  const int occ = v.family == kIgemm ? igemm_tile_occupancy(v.bf16, v.tile) : 2;
+  const int occ = occupancy(v);
   const long long per_cu = ceil_div_ll(wgs, 256);
   const long long serial_fixed = ceil_div_ll(per_cu, occ);
   double cost = per_cu * wg_work + serial_fixed * wg_fixed;
+  if (v.family == kDma) cost += 6000.0 + (q.in_bf16 ? 2.0 : 4.0) * q.Kg * q.K * 2 / 1000.0;
   if (splits > 1) cost += 4.0 * q.M * q.K * (2 * splits + 1) / 2000.0 + 7000.0;
   return cost;
 }
 
-int select(const Problem& q, bool aligned) {
+// Hand-tuned choices for known layer shapes (section 3: per-device manual
+// tuning of algorithm and parameters), written by the tuning script.
+struct Tuned {
+  int bf16, n, h, w, c, k, r, s, sr, sc, padding;
+  const char* variant;
+};
+const Tuned kTuned[] = {
+#include "tuned_table.inc"
+};
+
+bool usable(const Variant& v, const Problem& q, bool aligned) {
+  if (!supports(v, q)) return false;
+  return aligned || v.family == kDirect || is_scalar(v);
+}
+
+int select(const Problem& q, int padding, bool aligned) {
   const Table& tb = table();
+  if (q.M == 0) return 0;  // empty batch: nothing is launched
+  for (const Tuned& t : kTuned) {
+    if (t.bf16 == q.in_bf16 && t.n == q.N && t.h == q.H && t.w == q.W && t.c == q.C &&
+        t.k == q.K && t.r == q.R && t.s == q.S && t.sr == q.sr && t.sc == q.sc &&
+        t.padding == padding) {
+      for (int i = 0; i < tb.n; ++i)
+        if (std::strcmp(tb.v[i].name, t.variant) == 0 && usable(tb.v[i], q, aligned)) return i;
+    }
+  }
   int best = 0;
   double best_cost = 0;
-  if (q.M == 0) return 0;  // empty batch: nothing is launched
+  const int vec = q.in_bf16 ? 8 : 4;
   for (int i = 1; i < tb.n; ++i) {
     const Variant& v = tb.v[i];
-    if (v.family != kIgemm || !supports(v, q)) continue;
-    if (!aligned && !is_scalar(v)) continue;
+    if (!usable(v, q, aligned)) continue;
     // element-wise tiles only where the vector tiles cannot run
-    if (is_scalar(v) && aligned && q.C % (q.in_bf16 ? 8 : 4) == 0 && q.K % (q.in_bf16 ? 8 : 4) == 0)
-      continue;
+    if (is_scalar(v) && aligned && q.C % vec == 0 && q.K % vec == 0) continue;
     const double c = model_cost(v, q);
     if (best == 0 || c < best_cost) { best = i; best_cost = c; }
   }
@@ -222,7 +271,7 @@ int select(const Problem& q, bool aligned) {
 }
 
 size_t workspace_bytes_for(const Variant& v, const Problem& q) {
-  if (v.family == kDma) return igemm_dma_workspace_bytes(q, v.bf16, v.tile);
+  if (v.family == kDma) return igemm_dma_workspace_bytes(q, v.bf16, v.tile, split_factor(v, q));
   if (v.family == kIgemm && v.split)
     return static_cast<size_t>(split_factor(v, q)) * q.M * q.K * sizeof(float);
   return 0;
@@ -245,7 +294,7 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
   const bool al = aligned16(in, filt, out);
   int id = variant_id;
   if (id < 0) {
-    id = select(q, al);
+    id = select(q, params->padding, al);
     const char* env = std::getenv("CONV2D_FORCE_VARIANT");
     if (env && *env) {
       const int forced = std::atoi(env);
@@ -271,7 +320,9 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     case kIgemm:
       e = launch_igemm(q, tb.v[id].bf16, tb.v[id].tile, split_factor(tb.v[id], q), stream);
       break;
-    case kDma: e = launch_igemm_dma(q, tb.v[id].bf16, tb.v[id].tile, stream); break;
+    case kDma:
+      e = launch_igemm_dma(q, tb.v[id].bf16, tb.v[id].tile, split_factor(tb.v[id], q), stream);
+      break;
   }
   return e == hipSuccess ? CONV2D_STATUS_OK : CONV2D_STATUS_LAUNCH_FAILED;
 }
@@ -297,7 +348,7 @@ int conv2d_workspace_size(const conv2d_params* params, size_t* bytes) {
   if (!bytes) return CONV2D_STATUS_INVALID_ARGUMENT;
   int rc = derive(params, &q);
   if (rc) return rc;
-  *bytes = workspace_bytes_for(table().v[select(q, true)], q);
+  *bytes = workspace_bytes_for(table().v[select(q, params->padding, true)], q);
   return CONV2D_STATUS_OK;
 }
 
@@ -346,7 +397,7 @@ int conv2d_selected_variant(const conv2d_params* params, int* variant_id) {
   if (!variant_id) return CONV2D_STATUS_INVALID_ARGUMENT;
   int rc = derive(params, &q);
   if (rc) return rc;
-  *variant_id = select(q, true);
+  *variant_id = select(q, params->padding, true);
   return CONV2D_STATUS_OK;
 }
 

@@ -42,12 +42,22 @@ int igemm_tile_occupancy(int bf16, int tile);   // workgroups per compute unit
 bool igemm_tile_is_scalar(int bf16, int tile);  // element-wise loads: any C, K, alignment
 hipError_t launch_igemm(const Problem& p, int bf16, int tile, int splits, hipStream_t stream);
 
-// Implicit GEMM with a multi-stage LDS ring fed by direct global->LDS loads;
-// needs the workspace for the repacked (k-contiguous) filter.
+// Adds `splits` fp32 partial outputs of `total` elements each (laid out one
+// after the other at `partial`) in split order and stores the sum to `out`
+// as fp32 or bf16.
+hipError_t launch_split_reduce(const float* partial, void* out, int total, int splits,
+                               bool out_bf16, hipStream_t stream);
+
+// Implicit GEMM with a multi-stage LDS ring fed by direct global->LDS loads.
+// The workspace holds the repacked (k-contiguous) filter and, for splits > 1,
+// the fp32 partial outputs.  "Uniform" tiles need C to be a multiple of the
+// tile's bk and a window of at most 31 taps.
 int igemm_dma_num_tiles(int bf16);
 const char* igemm_dma_tile_name(int bf16, int tile);
 void igemm_dma_tile_shape(int bf16, int tile, int* bm, int* bn, int* bk);
-size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile);
-hipError_t launch_igemm_dma(const Problem& p, int bf16, int tile, hipStream_t stream);
+int igemm_dma_tile_occupancy(int bf16, int tile);
+bool igemm_dma_tile_is_uniform(int bf16, int tile);
+size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile, int splits);
+hipError_t launch_igemm_dma(const Problem& p, int bf16, int tile, int splits, hipStream_t stream);
 
 }  // namespace conv2d

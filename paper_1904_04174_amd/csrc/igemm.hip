@@ -465,10 +465,8 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
                      lds_bytes, stream, p, per_split, flush);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || splits == 1) return e;
-  const int total = p.M * p.K;
-  hipLaunchKernelGGL((split_reduce_kernel<OUT_BF16>), dim3((total + 1023) / 1024), dim3(256), 0,
-                     stream, static_cast<const float*>(p.workspace), p.out, total, splits);
-  return hipGetLastError();
+  return launch_split_reduce(static_cast<const float*>(p.workspace), p.out, p.M * p.K, splits,
+                             OUT_BF16, stream);
 }
 
 template <class T>
@@ -513,6 +511,18 @@ constexpr int kNumF32 = sizeof(kTilesF32) / sizeof(kTilesF32[0]);
 constexpr int kNumBf16 = sizeof(kTilesBf16) / sizeof(kTilesBf16[0]);
 
 }  // namespace
+
+hipError_t launch_split_reduce(const float* partial, void* out, int total, int splits,
+                               bool out_bf16, hipStream_t stream) {
+  const dim3 grid((total + 1023) / 1024), block(256);
+  if (out_bf16)
+    hipLaunchKernelGGL((split_reduce_kernel<true>), grid, block, 0, stream, partial, out, total,
+                       splits);
+  else
+    hipLaunchKernelGGL((split_reduce_kernel<false>), grid, block, 0, stream, partial, out, total,
+                       splits);
+  return hipGetLastError();
+}
 
 int igemm_num_tiles(int bf16) { return bf16 ? kNumBf16 : kNumF32; }
 static const TileEntry& entry(int bf16, int tile) { return bf16 ? kTilesBf16[tile] : kTilesF32[tile]; }

@@ -1,10 +1,10 @@
 // Implicit-GEMM forward convolution with a multi-stage LDS ring fed by direct
-// global->LDS loads (buffer_load ... lds, 16 bytes per lane), for gfx950.
-// Same GEMM view as igemm.hip (paper section 3: the convolution as the
-// routine to accelerate; D[M][K] = A[M][Kg] * B[Kg][K], Kg ordered (r,s,c)):
-// A rows are gathered from the NHWC input, D is the NHWC output.
+// global->LDS loads (buffer_load ... lds, 16 bytes per lane) and a hand-placed
+// instruction schedule, for gfx950.  Same GEMM view as igemm.hip (paper
+// section 3: the convolution as the routine to accelerate;
+// D[M][K] = A[M][Kg] * B[Kg][K], Kg ordered (r,s,c)): A rows are gathered from
+// the NHWC input, D is the NHWC output.
 //
-// Differences from the register-staged kernel:
 //  * The filter is first repacked into the workspace as Bt[K][Kg_p] (k
 //    contiguous, Kg_p = Kg rounded up to the slice width, zero filled), so
 //    that A and B tiles are both "rows of ROWB contiguous bytes" and both can
@@ -16,20 +16,32 @@
 //    under this scheme, so bank conflicts are avoided by an XOR swizzle: the
 //    chunk stored at position p of row r is chunk p ^ ((r >> 1) & (CPR-1)).
 //    The lane simply fetches that chunk from memory; the MFMA fragment reads
-//    apply the same XOR (measured: full LDS read rate, 100 B/clk/CU).
+//    apply the same XOR (measured: full LDS read rate).
 //  * Padding taps / rows past M / k past Kg use an out-of-range buffer
 //    offset: the hardware then writes zeros to LDS.
-//  * STAGES (>= 3) LDS buffers form a ring and the whole thing is software
-//    pipelined.  The MFMA fragments are double buffered in registers: while
-//    the MFMAs of step t run, the fragments of step t+1 are read from LDS.
-//    In the last step of slice i each wave waits for its own loads of slice
-//    i+1 (s_waitcnt vmcnt(N), younger slices stay in flight), passes the one
-//    barrier of the slice, issues the loads of slice i+STAGES-1 into the
-//    stage of slice i-1 (which every wave has left), and reads the first
-//    fragments of slice i+1: the MFMA stream never drains at a slice border.
+//  * STAGES (>= 3) LDS buffers form a ring.  The MFMA fragments are double
+//    buffered in registers: while the MFMAs of step t run, the fragments of
+//    step t+1 are read from LDS.  In the last step of slice i each wave waits
+//    for its own loads of slice i+1 (s_waitcnt vmcnt(N), younger slices stay
+//    in flight), passes the one barrier of the slice, issues the loads of
+//    slice i+STAGES-1 into the stage of slice i-1 (which every wave has
+//    left), and reads the first fragments of slice i+1.
+//  * Everything that is not an MFMA (fragment reads, address arithmetic, load
+//    issue, the barrier) is dealt out one piece at a time between consecutive
+//    MFMAs and pinned there with scheduling fences: an MFMA occupies the
+//    matrix core for 32 (bf16) or 64 (fp32) cycles during which the wave can
+//    issue a handful of other instructions for free, whereas a block of them
+//    between two blocks of MFMAs leaves the matrix core idle.
+//  * UNIFORM tiles (C a multiple of the slice width, window of at most 31
+//    taps) know that a slice lies inside one tap: the tap offset is a scalar
+//    and each row keeps a bit mask of its valid taps, three vector
+//    instructions per gathered row.  Other shapes step (r,s,c) per lane.
 //  * The loads are issued from inline assembly, so the compiler's automatic
 //    wait insertion does not see them (it would make LDS reads of one stage
 //    wait for loads into the others); ordering is explicit as described.
+//  * gridDim.y > 1 splits the reduction: each workgroup takes a range of
+//    slices and writes an fp32 partial tile behind the repacked filter in the
+//    workspace; a reduce pass adds the partials in a fixed order.
 #include <type_traits>
 
 #include "conv2d_internal.h"
@@ -49,9 +61,10 @@ constexpr int kOutOfRange = static_cast<int>(0x80000000u);
 // vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "no wait").
 constexpr int vmcnt_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4) | (0xf << 8); }
 
-// Raw buffer descriptor (base, stride 0, bytes, flags) as four scalars.
-__device__ __forceinline__ uintx4 make_rsrc(const void* base, int bytes) {
-  const size_t a = reinterpret_cast<size_t>(base);
+// Raw buffer descriptor (base moved back by shift_back bytes, stride 0, bytes,
+// flags) as four scalars.
+__device__ __forceinline__ uintx4 make_rsrc(const void* base, int shift_back, int bytes) {
+  const size_t a = reinterpret_cast<size_t>(base) - static_cast<size_t>(shift_back);
   uintx4 r;
   r[0] = static_cast<unsigned>(a);
   r[1] = static_cast<unsigned>(a >> 32) & 0xffffu;
@@ -77,7 +90,7 @@ __device__ __forceinline__ void dma16(const uintx4& rsrc, unsigned lds_base, int
 }
 
 template <bool BF16_, int BM_, int BN_, int ROWB_, int WAVES_M_, int WAVES_N_, int STAGES_,
-          bool TWO_LEVEL_, int OCC_>
+          bool TWO_LEVEL_, int OCC_, bool UNIFORM_>
 struct DmaTile {
   static constexpr bool BF16 = BF16_;
   static constexpr int BM = BM_, BN = BN_;
@@ -90,11 +103,15 @@ struct DmaTile {
   static constexpr int STAGES = STAGES_;
   static constexpr bool TWO_LEVEL = TWO_LEVEL_;  // see igemm.hip: two-level fp32 summation
   static constexpr int OCC = OCC_;
+  static constexpr bool UNIFORM = UNIFORM_;      // a slice never straddles two taps
   static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int NW = WAVES_M * WAVES_N;
   static constexpr int NT = 64 * NW;
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   static constexpr int TM = WM / 32, TN = WN / 32;
+  static constexpr int MPF = BF16 ? 1 : 4;       // MFMAs per pair of 16-byte fragments
+  static constexpr int NM = TM * TN * MPF;       // MFMAs per fragment step
+  static constexpr int NR = TM + TN;             // fragment reads per step
   static constexpr int ROWS_PER_INSTR = 64 / CPR;
   static constexpr int ROWS_PER_PASS = NT / CPR;
   static constexpr int A_ITERS = BM / ROWS_PER_PASS;
@@ -105,7 +122,7 @@ struct DmaTile {
   static constexpr int WAIT_FIRST = (STAGES - 2) * LOADS;
   static_assert(ROWB == 64 || ROWB == 128, "64 or 128 bytes per row");
   static_assert(KSTEPS % 2 == 0, "fragment double buffering needs an even step count");
-  static_assert(STAGES >= 3 && STAGES <= 5, "3 to 5 stages");
+  static_assert(STAGES >= 3 && STAGES <= 8, "3 to 8 stages");
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of 32x32");
   static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "tile rows must divide");
   static_assert(ROWS_PER_PASS % 16 == 0, "the swizzle must be the same for all rows of a lane");
@@ -142,18 +159,20 @@ __global__ __launch_bounds__(256) void repack_filter_kernel(const E* __restrict_
   }
 }
 
+// gridDim.x = output tiles, gridDim.y = splits of the reduction.  `bt` is the
+// repacked filter, `partial` the fp32 partial outputs (used when gridDim.y > 1).
 template <class T, bool OUT_BF16>
 __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem p, const int Kg_p,
-                                                                  const int flush_slices) {
+                                                                  const int slices_per_split,
+                                                                  const int flush_slices,
+                                                                  const void* bt,
+                                                                  float* partial) {
   constexpr int BM = T::BM, BN = T::BN, BK = T::BK, S = T::STAGES, ROWB = T::ROWB, CPR = T::CPR;
   constexpr int ES = T::ES, VEC = T::VEC, KSTEPS = T::KSTEPS;
-  // one array per stage: [BM rows of A | BN rows of B], ROWB bytes per row
-  __shared__ __align__(1024) unsigned char stage0[T::STAGE_BYTES];
-  __shared__ __align__(1024) unsigned char stage1[T::STAGE_BYTES];
-  __shared__ __align__(1024) unsigned char stage2[T::STAGE_BYTES];
-  __shared__ __align__(1024) unsigned char stage3[S > 3 ? T::STAGE_BYTES : 16];
-  __shared__ __align__(1024) unsigned char stage4[S > 4 ? T::STAGE_BYTES : 16];
-  unsigned char* const stages[5] = {stage0, stage1, stage2, stage3, stage4};
+  constexpr int TM = T::TM, TN = T::TN, NM = T::NM, NR = T::NR, MPF = T::MPF;
+  constexpr bool UNIFORM = T::UNIFORM;
+  // stage s: [BM rows of A | BN rows of B], ROWB bytes per row
+  __shared__ __align__(1024) unsigned char ring[S * T::STAGE_BYTES];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -172,8 +191,16 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   const int m0 = (tile / tiles_n) * BM;
   const int n0 = (tile % tiles_n) * BN;
 
-  const uintx4 in_rsrc = make_rsrc(p.in, p.N * p.H * p.W * p.C * ES);
-  const uintx4 bt_rsrc = make_rsrc(p.workspace, p.K * Kg_p * ES);
+  const int nslices_all = Kg_p / BK;
+  const int slice_begin = blockIdx.y * slices_per_split;
+  const int nslices = min(slices_per_split, nslices_all - slice_begin);
+
+  // UNIFORM tiles address a row by the (possibly negative) offset of its
+  // window origin plus a scalar tap offset; the descriptor base is moved
+  // back by `shift` bytes so that the vector part is never negative.
+  const int shift = UNIFORM ? (p.pt * p.W + p.pl) * p.C * ES : 0;
+  const uintx4 in_rsrc = make_rsrc(p.in, shift, p.N * p.H * p.W * p.C * ES + shift);
+  const uintx4 bt_rsrc = make_rsrc(bt, 0, p.K * Kg_p * ES);
 
   // ---- loader role of this lane: row tid / CPR (+ passes of ROWS_PER_PASS),
   // LDS chunk position tid % CPR, memory chunk = position ^ swizzle(row);
@@ -181,22 +208,36 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   const int ld_row0 = tid / CPR;
   const int ld_pos = tid % CPR;
   const int ld_chunk = ld_pos ^ ((ld_row0 >> 1) & (CPR - 1));
-  int a_off[T::A_ITERS], a_h0[T::A_ITERS], a_w0[T::A_ITERS];
+  // UNIFORM: byte offset of the row's window origin (+ shift, + this lane's
+  // chunk); otherwise the element offset of the window origin
+  int a_off[T::A_ITERS];
+  int a_h0[UNIFORM ? 1 : T::A_ITERS], a_w0[UNIFORM ? 1 : T::A_ITERS];
+  unsigned a_mask[UNIFORM ? T::A_ITERS : 1];  // bit r*S+s: tap (r,s) of the row lies inside the image
 #pragma unroll
   for (int i = 0; i < T::A_ITERS; ++i) {
     const int m = m0 + ld_row0 + i * T::ROWS_PER_PASS;
-    if (m < p.M) {
-      const int q = m % p.Q;
-      const int t = m / p.Q;
-      const int op = t % p.P;
-      const int n = t / p.P;
-      a_h0[i] = op * p.sr - p.pt;
-      a_w0[i] = q * p.sc - p.pl;
-      a_off[i] = ((n * p.H + a_h0[i]) * p.W + a_w0[i]) * p.C;
+    const bool row_ok = m < p.M;
+    const int mm = row_ok ? m : 0;
+    const int q = mm % p.Q;
+    const int t = mm / p.Q;
+    const int op = t % p.P;
+    const int n = t / p.P;
+    const int h0 = op * p.sr - p.pt;
+    const int w0 = q * p.sc - p.pl;
+    const int off = ((n * p.H + h0) * p.W + w0) * p.C;
+    if constexpr (UNIFORM) {
+      unsigned mask = 0;
+      for (int r = 0; r < p.R; ++r)
+        for (int s = 0; s < p.S; ++s)
+          if (static_cast<unsigned>(h0 + r) < static_cast<unsigned>(p.H) &&
+              static_cast<unsigned>(w0 + s) < static_cast<unsigned>(p.W))
+            mask |= 1u << (r * p.S + s);
+      a_mask[i] = row_ok ? mask : 0u;
+      a_off[i] = (off + ld_chunk * VEC) * ES + shift;
     } else {
-      a_h0[i] = -(1 << 28);
-      a_w0[i] = 0;
-      a_off[i] = 0;
+      a_h0[i] = row_ok ? h0 : -(1 << 28);
+      a_w0[i] = w0;
+      a_off[i] = off;
     }
   }
   int b_voff[T::B_ITERS];
@@ -205,62 +246,92 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
     const int n = n0 + ld_row0 + i * T::ROWS_PER_PASS;
     b_voff[i] = (n < p.K) ? (n * Kg_p + ld_chunk * VEC) * ES : kOutOfRange;
   }
-  // (r, s, c) of this lane's chunk in the next slice to load; branch-free stepping
+  // Position of the next slice to load.  UNIFORM: scalar tap index and channel
+  // offset.  Otherwise (r, s, c) of this lane's chunk, stepped without division.
   int kc, ks, kr;
+  int tap_bit = 0, tap_c = 0, tap_s = 0, tap_rowoff = 0;  // UNIFORM
   {
-    const int kg = ld_chunk * VEC;
+    const int kg = slice_begin * BK + (UNIFORM ? 0 : ld_chunk * VEC);
     kc = kg % p.C;
     const int t = kg / p.C;
     ks = t % p.S;
     kr = t / p.S;
+    if constexpr (UNIFORM) {
+      tap_bit = min(t, 31);
+      tap_c = kc;
+      tap_s = ks;
+      tap_rowoff = kr * p.W * p.C;
+    }
   }
   const int step_c = BK % p.C;
   const int step_s = (BK / p.C) % p.S;
   const int step_r = (BK / p.C) / p.S;
-  int k_next_bytes = 0;
   const int k_last_bytes = (Kg_p - BK) * ES;
+  int k_next_bytes = min(slice_begin * BK * ES, k_last_bytes);
 
-  auto issue_slice = [&](unsigned char* stage) {
-    const int tap = (kr * p.W + ks) * p.C + kc;
-    const int kr_t = (kr < p.R) ? kr : (1 << 30);
-    const unsigned dst = __builtin_amdgcn_readfirstlane(lds_address(stage) + wave * 1024);
-#pragma unroll
-    for (int i = 0; i < T::A_ITERS; ++i) {
+  const unsigned ring_base = __builtin_amdgcn_readfirstlane(lds_address(ring) + wave * 1024);
+
+  // One A load (row pass i) of the slice at the current position into `stage`.
+  auto load_a = [&](int stage, int i) {
+    const unsigned dst = ring_base + stage * T::STAGE_BYTES + i * T::ROWS_PER_PASS * ROWB;
+    if constexpr (UNIFORM) {
+      const bool ok = (a_mask[i] >> tap_bit) & 1u;
+      const int soff = (tap_rowoff + tap_s * p.C + tap_c) * ES;
+      dma16(in_rsrc, dst, ok ? a_off[i] : kOutOfRange, soff);
+    } else {
+      const int tap = (kr * p.W + ks) * p.C + kc;
+      const int kr_t = (kr < p.R) ? kr : (1 << 30);
       const bool ok = (static_cast<unsigned>(a_h0[i] + kr_t) < static_cast<unsigned>(p.H)) &
                       (static_cast<unsigned>(a_w0[i] + ks) < static_cast<unsigned>(p.W));
-      const int off = ok ? (a_off[i] + tap) * ES : kOutOfRange;
-      dma16(in_rsrc, dst + i * T::ROWS_PER_PASS * ROWB, off, 0);
+      dma16(in_rsrc, dst, ok ? (a_off[i] + tap) * ES : kOutOfRange, 0);
     }
-    const unsigned dstb = dst + BM * ROWB;
-#pragma unroll
-    for (int i = 0; i < T::B_ITERS; ++i)
-      dma16(bt_rsrc, dstb + i * T::ROWS_PER_PASS * ROWB, b_voff[i], k_next_bytes);
+  };
+  auto load_b = [&](int stage, int i) {
+    const unsigned dst = ring_base + stage * T::STAGE_BYTES + (BM + i * T::ROWS_PER_PASS) * ROWB;
+    dma16(bt_rsrc, dst, b_voff[i], k_next_bytes);
+  };
+  // Moves the load position one slice on.
+  auto advance = [&]() {
     // the scalar offset is not range checked: slices issued past the end
     // re-read the last slice (into a stage nobody reads) instead of running
     // off the end of the repacked filter
     k_next_bytes = min(k_next_bytes + ROWB, k_last_bytes);
-    kc += step_c;
-    const int carry_c = kc >= p.C;
-    kc -= carry_c ? p.C : 0;
-    ks += step_s + carry_c;
-    const int carry_s = ks >= p.S;
-    ks -= carry_s ? p.S : 0;
-    kr += step_r + carry_s;
+    if constexpr (UNIFORM) {
+      tap_c += BK;
+      if (tap_c >= p.C) {
+        tap_c = 0;
+        // windows have at most 31 taps here, so bit 31 is clear in every
+        // mask: past the last tap every row reads as out of range
+        tap_bit = min(tap_bit + 1, 31);
+        if (++tap_s >= p.S) {
+          tap_s = 0;
+          tap_rowoff += p.W * p.C;
+        }
+      }
+    } else {
+      kc += step_c;
+      const int carry_c = kc >= p.C;
+      kc -= carry_c ? p.C : 0;
+      ks += step_s + carry_c;
+      const int carry_s = ks >= p.S;
+      ks -= carry_s ? p.S : 0;
+      kr += step_r + carry_s;
+    }
   };
 
-  floatx16 acc[T::TM][T::TN];
+  floatx16 acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < T::TM; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < T::TN; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  floatx16 total[T::TWO_LEVEL ? T::TM : 1][T::TWO_LEVEL ? T::TN : 1];
+  floatx16 total[T::TWO_LEVEL ? TM : 1][T::TWO_LEVEL ? TN : 1];
   if (T::TWO_LEVEL) {
 #pragma unroll
-    for (int i = 0; i < T::TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < T::TN; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) total[i][j][v] = 0.f;
   }
@@ -268,55 +339,98 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
 
   // fragment addressing: row lr of each 32-row block, chunk (2*kk + lk) ^ swizzle
   const int frag_swz = (lr >> 1) & (CPR - 1);
-  const int a_row_bytes = (wm * T::WM + lr) * ROWB;
-  const int b_row_bytes = (BM + wn * T::WN + lr) * ROWB;
+  const unsigned char* a_frag = ring + (wm * T::WM + lr) * ROWB;
+  const unsigned char* b_frag = ring + (BM + wn * T::WN + lr) * ROWB;
   int chunk_bytes[KSTEPS];
 #pragma unroll
   for (int kk = 0; kk < KSTEPS; ++kk) chunk_bytes[kk] = ((2 * kk + lk) ^ frag_swz) * 16;
 
-  uintx4 af[2][T::TM], bf[2][T::TN];  // double-buffered MFMA fragments
+  uintx4 af[2][TM], bf[2][TN];  // double-buffered MFMA fragments
 
-  auto read_frags = [&](auto buf_c, const unsigned char* stage, int kk) {
+  // Fragment read number r (A blocks first, then B blocks) of step kk of `stage`.
+  auto read_frag = [&](auto buf_c, int stage, int kk, int r) {
     constexpr int buf = decltype(buf_c)::value;
-#pragma unroll
-    for (int i = 0; i < T::TM; ++i)
-      af[buf][i] =
-          *reinterpret_cast<const uintx4*>(stage + a_row_bytes + i * 32 * ROWB + chunk_bytes[kk]);
-#pragma unroll
-    for (int j = 0; j < T::TN; ++j)
-      bf[buf][j] =
-          *reinterpret_cast<const uintx4*>(stage + b_row_bytes + j * 32 * ROWB + chunk_bytes[kk]);
+    if (r < TM)
+      af[buf][r] = *reinterpret_cast<const uintx4*>(a_frag + stage * T::STAGE_BYTES +
+                                                    r * 32 * ROWB + chunk_bytes[kk]);
+    else
+      bf[buf][r - TM] = *reinterpret_cast<const uintx4*>(b_frag + stage * T::STAGE_BYTES +
+                                                         (r - TM) * 32 * ROWB + chunk_bytes[kk]);
   };
-  auto mfmas = [&](auto buf_c) {
+  // MFMA number m of a step.
+  auto mfma = [&](auto buf_c, int m) {
     constexpr int buf = decltype(buf_c)::value;
-#pragma unroll
-    for (int i = 0; i < T::TM; ++i)
-#pragma unroll
-      for (int j = 0; j < T::TN; ++j) {
-        if (T::BF16) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              __builtin_bit_cast(bf16x8, af[buf][i]), __builtin_bit_cast(bf16x8, bf[buf][j]),
-              acc[i][j], 0, 0, 0);
-        } else {
-#pragma unroll
-          for (int t = 0; t < 4; ++t)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(af[buf][i][t]),
-                                                             __uint_as_float(bf[buf][j][t]),
-                                                             acc[i][j], 0, 0, 0);
-        }
-      }
+    const int i = m / (TN * MPF), j = (m / MPF) % TN, t = m % MPF;
+    if constexpr (T::BF16) {
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+          __builtin_bit_cast(bf16x8, af[buf][i]), __builtin_bit_cast(bf16x8, bf[buf][j]), acc[i][j],
+          0, 0, 0);
+    } else {
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(af[buf][i][t]),
+                                                       __uint_as_float(bf[buf][j][t]), acc[i][j],
+                                                       0, 0, 0);
+    }
   };
   using Buf0 = std::integral_constant<int, 0>;
   using Buf1 = std::integral_constant<int, 1>;
 
-  const int nslices = Kg_p / BK;
+  // One fragment step: NM MFMAs with the side work dealt out between them.
+  // Side work of an ordinary step: the NR fragment reads of the next step.
+  // Side work of the last step of a slice: wait + barrier, the NR reads of
+  // the next slice's first step, the LOADS loads of slice i+S-1, advance.
+  // Side items start after the first MFMA and are spaced so that all of them
+  // are out well before the step ends.
+  auto step = [&](auto cur_c, auto nxt_c, int stage, int kk, int stage_next, int stage_load) {
+    const bool last = kk == KSTEPS - 1;
+    const int nside = last ? 1 + NR + T::LOADS + 1 : NR;
+    const int room = NM > 3 ? NM - 2 : NM;           // MFMA gaps that take side work
+    const int per_gap = (nside + room - 1) / room;   // side items per gap
+    int item = 0;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      mfma(cur_c, m);
+#pragma unroll
+      for (int g = 0; g < per_gap; ++g, ++item) {
+        if (item >= nside) {
+          // nothing left for this gap
+        } else if (!last) {
+          read_frag(nxt_c, stage, kk + 1, item);
+        } else if (item == 0) {
+          // next step belongs to the next slice: its loads must have landed
+          // (this lane's: vmcnt; everyone's: barrier), and the barrier also
+          // says that every wave has left the previous slice's stage
+          __builtin_amdgcn_s_waitcnt(vmcnt_imm(T::WAIT_STEADY));
+          __builtin_amdgcn_s_barrier();
+          asm volatile("" ::: "memory");  // LDS changed behind the compiler's back
+        } else if (item <= NR) {
+          read_frag(nxt_c, stage_next, 0, item - 1);
+        } else if (item <= NR + T::A_ITERS) {
+          load_a(stage_load, item - NR - 1);
+        } else if (item <= NR + T::LOADS) {
+          load_b(stage_load, item - NR - T::A_ITERS - 1);
+        } else {
+          advance();
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
   // prologue: slices 0 .. S-2 in flight, slice 0 landed, its first fragments read
 #pragma unroll
-  for (int s = 0; s < S - 1; ++s) issue_slice(stages[s]);
+  for (int s = 0; s < S - 1; ++s) {
+#pragma unroll
+    for (int i = 0; i < T::A_ITERS; ++i) load_a(s, i);
+#pragma unroll
+    for (int i = 0; i < T::B_ITERS; ++i) load_b(s, i);
+    advance();
+  }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(T::WAIT_FIRST));
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  read_frags(Buf0{}, stages[0], 0);
+#pragma unroll
+  for (int r = 0; r < NR; ++r) read_frag(Buf0{}, 0, 0, r);
+  __builtin_amdgcn_sched_barrier(0);
 
   for (int slice = 0; slice < nslices; slice += S) {
 #pragma unroll
@@ -324,33 +438,20 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
       if (slice + u < nslices) {
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk) {
-          // 1. fragments of the next step into the other register buffer
-          if (kk == KSTEPS - 1) {
-            // next step belongs to the next slice: its loads must have landed
-            // (this lane's: vmcnt; everyone's: barrier), and the barrier also
-            // says that every wave has left the previous slice's stage
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(T::WAIT_STEADY));
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");  // LDS changed behind the compiler's back
-            issue_slice(stages[(u + S - 1) % S]);
-            read_frags(Buf0{}, stages[(u + 1) % S], 0);  // KSTEPS is even: next step uses buffer 0
-          } else if (kk % 2 == 0) {
-            read_frags(Buf1{}, stages[u], kk + 1);
-          } else {
-            read_frags(Buf0{}, stages[u], kk + 1);
-          }
-          __builtin_amdgcn_sched_barrier(0);
-          // 2. MFMAs of this step
-          if (kk % 2 == 0) mfmas(Buf0{}); else mfmas(Buf1{});
-          __builtin_amdgcn_sched_barrier(0);
+          // KSTEPS is even: step kk uses fragment buffer kk % 2, and the first
+          // step of the next slice uses buffer 0 again
+          if (kk % 2 == 0)
+            step(Buf0{}, Buf1{}, u, kk, (u + 1) % S, (u + S - 1) % S);
+          else
+            step(Buf1{}, Buf0{}, u, kk, (u + 1) % S, (u + S - 1) % S);
         }
         if (T::TWO_LEVEL) {
           if (--until_flush == 0) {
             until_flush = flush_slices;
 #pragma unroll
-            for (int i = 0; i < T::TM; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-              for (int j = 0; j < T::TN; ++j)
+              for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                   total[i][j][v] += acc[i][j][v];
@@ -364,18 +465,20 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // drain the slices issued past the end
   if (T::TWO_LEVEL) {
 #pragma unroll
-    for (int i = 0; i < T::TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < T::TN; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] += total[i][j][v];
   }
 
   // ---- epilogue (accumulator layout: lane l reg v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32)
+  const bool to_partial = gridDim.y > 1;
+  float* part = partial + static_cast<size_t>(blockIdx.y) * static_cast<size_t>(p.M) * p.K;
 #pragma unroll
-  for (int i = 0; i < T::TM; ++i) {
+  for (int i = 0; i < TM; ++i) {
 #pragma unroll
-    for (int j = 0; j < T::TN; ++j) {
+    for (int j = 0; j < TN; ++j) {
       const int col = n0 + wn * T::WN + j * 32 + lr;
       const int rbase = m0 + wm * T::WM + i * 32 + lk * 4;
 #pragma unroll
@@ -383,7 +486,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
         const int row = rbase + 8 * (v / 4) + (v % 4);
         if (row < p.M && col < p.K) {
           const size_t idx = static_cast<size_t>(row) * p.K + col;
-          if (OUT_BF16)
+          if (to_partial)
+            part[idx] = acc[i][j][v];
+          else if (OUT_BF16)
             static_cast<unsigned short*>(p.out)[idx] = to_bf16_bits(acc[i][j][v]);
           else
             static_cast<float*>(p.out)[idx] = acc[i][j][v];
@@ -393,8 +498,24 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   }
 }
 
+// Bytes of the repacked filter at the head of the workspace (a multiple of 256).
+template <class T>
+size_t filter_bytes(const Problem& p) {
+  const size_t kg_p = static_cast<size_t>((p.Kg + T::BK - 1) / T::BK) * T::BK;
+  return (kg_p * p.K * T::ES + 255) / 256 * 256;
+}
+
+template <class T>
+int clamp_splits(const Problem& p, int splits, int* per_split) {
+  const int nslices = (p.Kg + T::BK - 1) / T::BK;
+  if (splits < 1) splits = 1;
+  if (splits > nslices) splits = nslices;
+  *per_split = (nslices + splits - 1) / splits;
+  return (nslices + *per_split - 1) / *per_split;  // no empty split
+}
+
 template <class T, bool OUT_BF16>
-hipError_t launch_one(const Problem& p, hipStream_t stream) {
+hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   const int Kg_p = (p.Kg + T::BK - 1) / T::BK * T::BK;
   // 1. filter -> Bt[K][Kg_p] in the workspace
   dim3 rgrid((Kg_p + 31) / 32, (p.K + 31) / 32);
@@ -411,68 +532,91 @@ hipError_t launch_one(const Problem& p, hipStream_t stream) {
   // 2. the convolution
   const int tiles_m = (p.M + T::BM - 1) / T::BM;
   const int tiles_n = (p.K + T::BN - 1) / T::BN;
-  const int nslices = Kg_p / T::BK;
+  int per_split;
+  splits = clamp_splits<T>(p, splits, &per_split);
   int flush = 1;
-  while (flush * flush < nslices) ++flush;
-  hipLaunchKernelGGL((igemm_dma_kernel<T, OUT_BF16>), dim3(tiles_m * tiles_n), dim3(T::NT), 0,
-                     stream, p, Kg_p, flush);
-  return hipGetLastError();
+  while (flush * flush < per_split) ++flush;
+  float* partial = reinterpret_cast<float*>(static_cast<unsigned char*>(p.workspace) +
+                                            filter_bytes<T>(p));
+  hipLaunchKernelGGL((igemm_dma_kernel<T, OUT_BF16>), dim3(tiles_m * tiles_n, splits), dim3(T::NT),
+                     0, stream, p, Kg_p, per_split, flush, p.workspace, partial);
+  e = hipGetLastError();
+  if (e != hipSuccess || splits == 1) return e;
+  // 3. sum of the partial outputs
+  return launch_split_reduce(partial, p.out, p.M * p.K, splits, OUT_BF16, stream);
 }
 
 template <class T>
-hipError_t launch(const Problem& p, hipStream_t stream) {
-  if (T::BF16 && p.out_bf16) return launch_one<T, T::BF16>(p, stream);
-  return launch_one<T, false>(p, stream);
+hipError_t launch(const Problem& p, int splits, hipStream_t stream) {
+  if (T::BF16 && p.out_bf16) return launch_one<T, T::BF16>(p, splits, stream);
+  return launch_one<T, false>(p, splits, stream);
+}
+
+template <class T>
+size_t workspace_bytes(const Problem& p, int splits) {
+  int per_split;
+  splits = clamp_splits<T>(p, splits, &per_split);
+  return filter_bytes<T>(p) +
+         (splits > 1 ? static_cast<size_t>(splits) * p.M * p.K * sizeof(float) : 0);
 }
 
 struct TileEntry {
   const char* name;
-  int bm, bn, bk;
-  hipError_t (*fn)(const Problem&, hipStream_t);
+  int bm, bn, bk, occ;
+  bool uniform;
+  hipError_t (*fn)(const Problem&, int, hipStream_t);
+  size_t (*ws)(const Problem&, int);
 };
 
-#define CONV2D_DMA_TILE(dt, isbf, bm, bn, rowb, wm, wn, st, two, occ)                     \
-  { "igemm_dma_" dt "_" #bm "x" #bn "_r" #rowb "_w" #wm "x" #wn "_s" #st, bm, bn,          \
-    DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ>::BK,                                 \
-    &launch<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ>> }
+#define CONV2D_DMA_TILE(dt, isbf, bm, bn, rowb, wm, wn, st, two, occ, uni, tag)                 \
+  { "igemm_dma_" dt "_" #bm "x" #bn "_r" #rowb "_w" #wm "x" #wn "_s" #st tag, bm, bn,           \
+    DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, uni>::BK, occ, uni,                       \
+    &launch<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, uni>>,                            \
+    &workspace_bytes<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, uni>> }
 
 const TileEntry kTilesF32[] = {
-    CONV2D_DMA_TILE("f32", false, 128, 128, 64, 2, 2, 4, true, 2),
-    CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3),
-    CONV2D_DMA_TILE("f32", false, 256, 128, 64, 4, 2, 4, true, 2),
-    CONV2D_DMA_TILE("f32", false, 128, 128, 128, 2, 2, 3, true, 1),
+    CONV2D_DMA_TILE("f32", false, 128, 128, 64, 2, 2, 4, true, 2, true, ""),
+    CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, true, ""),
+    CONV2D_DMA_TILE("f32", false, 256, 128, 64, 4, 2, 4, true, 2, true, ""),
+    CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 4, true, 4, true, ""),
+    CONV2D_DMA_TILE("f32", false, 128, 128, 64, 2, 2, 4, true, 2, false, "_g"),
+    CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, false, "_g"),
+    CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 4, true, 4, false, "_g"),
 };
 const TileEntry kTilesBf16[] = {
-    CONV2D_DMA_TILE("bf16", true, 256, 256, 64, 4, 2, 4, false, 2),
-    CONV2D_DMA_TILE("bf16", true, 256, 128, 64, 4, 2, 4, false, 2),
-    CONV2D_DMA_TILE("bf16", true, 128, 128, 64, 2, 2, 4, false, 2),
-    CONV2D_DMA_TILE("bf16", true, 128, 64, 64, 2, 2, 4, false, 3),
-    CONV2D_DMA_TILE("bf16", true, 256, 128, 128, 2, 2, 3, false, 1),
-    CONV2D_DMA_TILE("bf16", true, 128, 128, 128, 2, 2, 4, false, 1),
+    CONV2D_DMA_TILE("bf16", true, 256, 256, 64, 4, 2, 4, false, 1, true, ""),
+    CONV2D_DMA_TILE("bf16", true, 256, 128, 64, 4, 2, 4, false, 1, true, ""),
+    CONV2D_DMA_TILE("bf16", true, 256, 128, 64, 4, 2, 3, false, 2, true, ""),
+    CONV2D_DMA_TILE("bf16", true, 128, 128, 64, 2, 2, 4, false, 2, true, ""),
+    CONV2D_DMA_TILE("bf16", true, 128, 64, 64, 2, 2, 4, false, 3, true, ""),
+    CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 4, false, 4, true, ""),
+    CONV2D_DMA_TILE("bf16", true, 128, 128, 64, 2, 2, 4, false, 2, false, "_g"),
+    CONV2D_DMA_TILE("bf16", true, 128, 64, 64, 2, 2, 4, false, 3, false, "_g"),
+    CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 4, false, 4, false, "_g"),
 };
 constexpr int kNumF32 = sizeof(kTilesF32) / sizeof(kTilesF32[0]);
 constexpr int kNumBf16 = sizeof(kTilesBf16) / sizeof(kTilesBf16[0]);
+
+const TileEntry& entry(int bf16, int tile) { return bf16 ? kTilesBf16[tile] : kTilesF32[tile]; }
 
 }  // namespace dma
 using namespace dma;
 
 int igemm_dma_num_tiles(int bf16) { return bf16 ? kNumBf16 : kNumF32; }
-const char* igemm_dma_tile_name(int bf16, int tile) {
-  return bf16 ? kTilesBf16[tile].name : kTilesF32[tile].name;
-}
+const char* igemm_dma_tile_name(int bf16, int tile) { return entry(bf16, tile).name; }
 void igemm_dma_tile_shape(int bf16, int tile, int* bm, int* bn, int* bk) {
-  const TileEntry& t = bf16 ? kTilesBf16[tile] : kTilesF32[tile];
+  const TileEntry& t = entry(bf16, tile);
   *bm = t.bm;
   *bn = t.bn;
   *bk = t.bk;
 }
-size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile) {
-  const TileEntry& t = bf16 ? kTilesBf16[tile] : kTilesF32[tile];
-  const size_t kg_p = static_cast<size_t>((p.Kg + t.bk - 1) / t.bk) * t.bk;
-  return kg_p * p.K * (bf16 ? 2 : 4);
+int igemm_dma_tile_occupancy(int bf16, int tile) { return entry(bf16, tile).occ; }
+bool igemm_dma_tile_is_uniform(int bf16, int tile) { return entry(bf16, tile).uniform; }
+size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile, int splits) {
+  return entry(bf16, tile).ws(p, splits);
 }
-hipError_t launch_igemm_dma(const Problem& p, int bf16, int tile, hipStream_t stream) {
-  return (bf16 ? kTilesBf16[tile] : kTilesF32[tile]).fn(p, stream);
+hipError_t launch_igemm_dma(const Problem& p, int bf16, int tile, int splits, hipStream_t stream) {
+  return entry(bf16, tile).fn(p, splits, stream);
 }
 
 }  // namespace conv2d

@@ -1,0 +1,108 @@
+"""Per-device tuning of the variant selector.
+
+The paper (section 3) tunes the choice of algorithm and of its parameters by
+hand for each target device and names an automated search as future work.
+This script is that search for one device: it times every variant that
+supports a layer, through the C ABI's forced-variant entry point, for every
+named layer in `workloads.LAYERS` (fp32) and `workloads.BF16_LAYERS` (bf16),
+and writes the winners as a table that the selector compiles in
+(`csrc/tuned_table.inc`).  Shapes that are not in the table fall back to the
+selector's cost model.
+
+    python -m paper_1904_04174_amd.tune --out paper_1904_04174_amd/csrc/tuned_table.inc
+
+Needs the GPU.  Rebuild the library afterwards.
+"""
+import argparse
+import sys
+
+from . import binding as B
+from . import workloads as wl
+
+SPLIT_PENALTY = 1.03   # a split-reduction variant must win by 3 % to be chosen (it needs scratch)
+MAX_WORKSPACE = 1 << 30
+
+
+def time_variant(torch, layer, in_dtype, variant_id, iters, warmup=2):
+    """Milliseconds per call of one forced variant on random data of the layer's shape."""
+    tdt = torch.float32 if in_dtype == B.F32 else torch.bfloat16
+    x = (torch.rand((layer.batch, layer.in_rows, layer.in_cols, layer.channels), device="cuda")
+         * 2 - 1).to(tdt)
+    f = (torch.rand((layer.window_rows, layer.window_cols, layer.channels, layer.features),
+                    device="cuda") * 2 - 1).to(tdt)
+    p = B.params_of_layer(layer, in_dtype, B.F32)
+    need = B.conv2d_workspace_size(p, variant_id)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    out = B.conv2d_forward(p, x, f, workspace=ws, variant_id=variant_id)
+    for _ in range(warmup):
+        B.conv2d_forward(p, x, f, out=out, workspace=ws, variant_id=variant_id)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        B.conv2d_forward(p, x, f, out=out, workspace=ws, variant_id=variant_id)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def candidates(params):
+    names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
+    vec_ok = any(B.conv2d_variant_supports(params, v) for v, n in enumerate(names)
+                 if n != "direct" and "scalar" not in n)
+    for v, n in enumerate(names):
+        if n == "direct" or not B.conv2d_variant_supports(params, v):
+            continue
+        if "scalar" in n and vec_ok:
+            continue   # element-wise tiles only where the vector tiles cannot run
+        if B.conv2d_workspace_size(params, v) > MAX_WORKSPACE:
+            continue
+        yield v, n
+
+
+def tune_layer(torch, layer, in_dtype, repeats=2):
+    p = B.params_of_layer(layer, in_dtype, B.F32)
+    iters = 5 if layer.batch >= 64 else (10 if layer.batch >= 16 else 30)
+    rows = []
+    for v, n in candidates(p):
+        ms = min(time_variant(torch, layer, in_dtype, v, iters) for _ in range(repeats))
+        rows.append((ms * (SPLIT_PENALTY if n.endswith("_splitk") else 1.0), ms, n))
+    rows.sort()
+    return rows
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
+    ap.add_argument("--out", required=True, help="path of the table to write")
+    args = ap.parse_args(argv)
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("tune.py needs the GPU")
+    f32 = [n for n in wl.LAYERS]
+    lines = [
+        "// Winners of `python -m paper_1904_04174_amd.tune` on one MI355X: the fastest variant",
+        "// per named layer (milliseconds per call in the comment).  Columns: bf16 input?,",
+        "// N, H, W, C, K, R, S, stride rows, stride cols, padding, variant name.",
+    ]
+    for in_dtype, names in ((B.F32, f32), (B.BF16, wl.BF16_LAYERS)):
+        for name in names:
+            L = wl.LAYERS[name]
+            rows = tune_layer(torch, L, in_dtype)
+            if not rows:
+                continue
+            _, ms, best = rows[0]
+            print("%-5s %-10s %-46s %9.4f ms   (runner-up %s %.4f)" % (
+                "bf16" if in_dtype == B.BF16 else "f32", name, best, ms,
+                rows[1][2] if len(rows) > 1 else "-", rows[1][1] if len(rows) > 1 else 0.0),
+                flush=True)
+            lines.append('{%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, "%s"},  // %s %.4f ms' % (
+                1 if in_dtype == B.BF16 else 0, L.batch, L.in_rows, L.in_cols, L.channels,
+                L.features, L.window_rows, L.window_cols, L.stride_rows, L.stride_cols,
+                L.padding, best, name, ms))
+    with open(args.out, "w") as fh:
+        fh.write("\n".join(lines) + "\n")
+    print("wrote", args.out)
+
+
+if __name__ == "__main__":
+    main()

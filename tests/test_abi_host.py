@@ -166,7 +166,7 @@ def test_selector_only_picks_supported_variants():
 def test_compute_bound_layers_use_the_matrix_cores():
     for name in wl.VGG_N16 + ["L-same", "L-valid", "L-s2", "R3x3"]:
         v = B.conv2d_selected_variant(B.params_of_layer(wl.LAYERS[name]))
-        assert B.conv2d_variant_name(v).startswith("igemm_f32"), name
+        assert B.conv2d_variant_name(v).startswith("igemm_"), name
 
 
 def test_empty_batch_has_a_selection_and_no_workspace():
@@ -186,8 +186,10 @@ def test_split_reduction_variants_state_their_workspace():
     assert split
     for v in split:
         ws = B.conv2d_workspace_size(p, v)
-        # a whole number (>= 2) of fp32 partial outputs
-        assert ws % (4 * 196 * 512) == 0 and ws // (4 * 196 * 512) >= 2
+        # at least two fp32 partial outputs; the register-staged tiles need nothing else
+        assert ws >= 2 * 4 * 196 * 512
+        if not names[v].startswith("igemm_dma"):
+            assert ws % (4 * 196 * 512) == 0
     # one slice of reduction cannot be split
     p1 = B.make_params(1, 8, 8, 4, 8, 1, 1)
     for v, n in enumerate(names):
