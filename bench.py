@@ -50,7 +50,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-batch", type=int, default=8)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0,
+                    help="lower bound on the CPU oracle's timed work")
+    ap.add_argument("--only", default=None,
+                    help="profile mode: launch only this layer (any name in workloads.LAYERS) "
+                         "--steps times, plus one device-to-device copy of --copy-mb MiB as the "
+                         "known-size reference for memory counters; prints no JSON")
+    ap.add_argument("--copy-mb", type=int, default=256)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -67,7 +73,7 @@ def main():
     in_dtype = B.F32 if args.dtype == "f32" else B.BF16
     tdt = torch.float32 if args.dtype == "f32" else torch.bfloat16
 
-    names = wl.VGG_N16
+    names = [args.only] if args.only else wl.VGG_N16
     layers = []
     for name in names:
         L = wl.LAYERS[name]
@@ -105,6 +111,22 @@ def main():
         step()
     stream.synchronize()
     torch.cuda.synchronize()
+
+    if args.only:
+        # profile mode: the layer's kernels, then a plain copy of known size
+        for _ in range(args.steps):
+            step()
+        stream.synchronize()
+        n = args.copy_mb * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        l = layers[0]
+        print("profiled %s (%s): %.3f GFLOP, %.1f MB algorithmic; reference copy: %d MiB read + "
+              "%d MiB written" % (l["name"], l["variant"], l["flops"] / 1e9, l["bytes"] / 1e6,
+                                  args.copy_mb, args.copy_mb))
+        return
 
     # ---- timed region: exactly --steps passes over the sweep
     t0 = time.perf_counter()
@@ -156,23 +178,27 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle
-        nb = args.cpu_sample_batch
-        cpu_flops, cpu_s = 0.0, 0.0
+        cpu_in = []
         for l in layers:
             L = l["layer"]
-            x, f = wl.make_inputs(L, dist="uniform", batch=nb)
+            x, f = wl.make_inputs(L, dist="uniform")
             if args.dtype == "bf16":
                 x, _ = wl.round_to_bf16(x)
                 f, _ = wl.round_to_bf16(f)
-            t = time.perf_counter()
-            oracle.forward_f32(x, f, (L.stride_rows, L.stride_cols), L.padding)
-            cpu_s += time.perf_counter() - t
-            cpu_flops += l["flops"] * nb / L.batch
+            cpu_in.append((L, x, f))
+        cpu_flops, cpu_s, passes = 0.0, 0.0, 0
+        while cpu_s < args.cpu_seconds and passes < 64:
+            for (L, x, f), l in zip(cpu_in, layers):
+                t = time.perf_counter()
+                oracle.forward_f32(x, f, (L.stride_rows, L.stride_cols), L.padding)
+                cpu_s += time.perf_counter() - t
+                cpu_flops += l["flops"]
+            passes += 1
         result["cpu_baseline"] = {
             "value": round(cpu_flops / cpu_s / 1e12, 5), "unit": "TFLOP/s",
             "cores": oracle.max_threads(), "kind": "oracle",
-            "sample": "the same five layers at batch %d (first %d images' worth of each layer), "
-                      "%.1f GFLOP in %.2f s" % (nb, nb, cpu_flops / 1e9, cpu_s)}
+            "sample": "%d passes of the oracle over the same five layers at full batch 16, "
+                      "%.1f GFLOP in %.2f s" % (passes, cpu_flops / 1e9, cpu_s)}
 
     print(json.dumps(result))
 
