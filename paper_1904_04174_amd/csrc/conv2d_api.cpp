@@ -21,12 +21,13 @@ namespace {
 constexpr long long kMaxElems = (1LL << 31) - 1;
 
 enum Family { kDirect = 0, kIgemm = 1, kDma = 2 };
+enum Split { kWhole = 0, kSplit = 1, kTail = 2 };
 
 struct Variant {
   Family family;
   int bf16;    // element type of input and filter the variant is compiled for
   int tile;    // index into the family's tile table
-  bool split;  // reduction split over several workgroups per output tile
+  int split;   // kWhole, kSplit (reduction split uniformly over workgroups) or kTail (balanced tail)
   char name[80];
 };
 
@@ -35,26 +36,28 @@ struct Variant {
 // split-reduction twin where the tile is small enough for that to make sense,
 // then the direct-to-LDS tiles.
 struct Table {
-  Variant v[128];
+  Variant v[160];
   int n;
-  void add(Family f, int bf16, int tile, bool split, const char* base) {
+  void add(Family f, int bf16, int tile, int split, const char* base) {
     Variant& x = v[n++];
     x.family = f; x.bf16 = bf16; x.tile = tile; x.split = split;
-    std::snprintf(x.name, sizeof(x.name), "%s%s", base, split ? "_splitk" : "");
+    std::snprintf(x.name, sizeof(x.name), "%s%s", base,
+                  split == kSplit ? "_splitk" : split == kTail ? "_tail" : "");
   }
   Table() : n(0) {
-    add(kDirect, 0, 0, false, "direct");
+    add(kDirect, 0, 0, kWhole, "direct");
     for (int bf = 0; bf < 2; ++bf)
       for (int t = 0; t < igemm_num_tiles(bf); ++t) {
-        add(kIgemm, bf, t, false, igemm_tile_name(bf, t));
+        add(kIgemm, bf, t, kWhole, igemm_tile_name(bf, t));
         int bm, bn, bk;
         igemm_tile_shape(bf, t, &bm, &bn, &bk);
-        if (bm <= 128) add(kIgemm, bf, t, true, igemm_tile_name(bf, t));
+        if (bm <= 128) add(kIgemm, bf, t, kSplit, igemm_tile_name(bf, t));
       }
     for (int bf = 0; bf < 2; ++bf)
       for (int t = 0; t < igemm_dma_num_tiles(bf); ++t) {
-        add(kDma, bf, t, false, igemm_dma_tile_name(bf, t));
-        add(kDma, bf, t, true, igemm_dma_tile_name(bf, t));
+        add(kDma, bf, t, kWhole, igemm_dma_tile_name(bf, t));
+        add(kDma, bf, t, kSplit, igemm_dma_tile_name(bf, t));
+        add(kDma, bf, t, kTail, igemm_dma_tile_name(bf, t));
       }
   }
 };
@@ -153,7 +156,7 @@ bool supports(const Variant& v, const Problem& q) {
     if (1LL * es * q.Kg * q.K >= (1LL << 31)) return false;
     // 16-byte gathers need C and K in multiples of the vector
     if (!is_scalar(v) && (q.C % vec != 0 || q.K % vec != 0)) return false;
-    if (v.split && (q.Kg + bk - 1) / bk < 2) return false;  // nothing to split
+    if (v.split == kSplit && (q.Kg + bk - 1) / bk < 2) return false;  // nothing to split
     return true;
   }
   // direct-to-LDS tiles: filter rows in the workspace are padded to the slice
@@ -161,7 +164,9 @@ bool supports(const Variant& v, const Problem& q) {
   if (q.C % vec != 0 || 1LL * es * (q.Kg + bk) * q.K >= (1LL << 31)) return false;
   if (1LL * es * (1LL * q.N * q.H * q.W + 1LL * q.R * q.W + q.S) * q.C >= (1LL << 31)) return false;
   if (igemm_dma_tile_is_uniform(v.bf16, v.tile) && (q.C % bk != 0 || q.R * q.S > 31)) return false;
-  if (v.split && (q.Kg + bk - 1) / bk < 2) return false;
+  if (v.split == kSplit && (q.Kg + bk - 1) / bk < 2) return false;
+  // a balanced tail needs tiles left over after whole rounds of the 256 compute units
+  if (v.split == kTail && (ceil_div_ll(q.M, bm) * ceil_div_ll(q.K, bn)) % 256 == 0) return false;
   return true;
 }
 
@@ -170,7 +175,8 @@ bool supports(const Variant& v, const Problem& q) {
 // workgroups, at least 2, and no split shorter than 4 slices unless the
 // whole reduction is.
 int split_factor(const Variant& v, const Problem& q) {
-  if (!v.split) return 1;
+  if (v.split == kTail) return kTailBalanced;
+  if (v.split != kSplit) return 1;
   int bm, bn, bk;
   tile_shape(v, &bm, &bn, &bk);
   const long long tiles = ceil_div_ll(q.M, bm) * ceil_div_ll(q.K, bn);
@@ -213,7 +219,7 @@ double tile_efficiency(const Variant& v, int bm, int bn) {
 double model_cost(const Variant& v, const Problem& q) {
   int bm, bn, bk;
   tile_shape(v, &bm, &bn, &bk);
-  const int splits = split_factor(v, q);
+  const int splits = v.split == kTail ? 1 : split_factor(v, q);
   const long long tiles = ceil_div_ll(q.M, bm) * ceil_div_ll(q.K, bn);
   const long long wgs = tiles * splits;
   const int nslices = (q.Kg + bk - 1) / bk;
@@ -225,6 +231,12 @@ double model_cost(const Variant& v, const Problem& q) {
   const long long per_cu = ceil_div_ll(wgs, 256);
   const long long serial_fixed = ceil_div_ll(per_cu, occ);
   double cost = per_cu * wg_work + serial_fixed * wg_fixed;
+  if (v.split == kTail) {
+    // every unit gets the same share of the tail; the pieces go through memory twice
+    const long long rest = tiles % 256;
+    cost = (1.0 * tiles / 256.0) * wg_work + (serial_fixed + 1) * wg_fixed +
+           4.0 * 2.0 * (256 + rest) * bm * bn / 2000.0 + 7000.0;
+  }
   if (v.family == kDma) cost += 6000.0 + (q.in_bf16 ? 2.0 : 4.0) * q.Kg * q.K * 2 / 1000.0;
   if (splits > 1) cost += 4.0 * q.M * q.K * (2 * splits + 1) / 2000.0 + 7000.0;
   return cost;

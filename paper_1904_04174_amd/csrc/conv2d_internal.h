@@ -48,6 +48,10 @@ hipError_t launch_igemm(const Problem& p, int bf16, int tile, int splits, hipStr
 hipError_t launch_split_reduce(const float* partial, void* out, int total, int splits,
                                bool out_bf16, hipStream_t stream);
 
+// Value of `splits` that asks the direct-to-LDS kernels for whole tiles plus
+// a balanced tail instead of a uniform split.
+constexpr int kTailBalanced = -1;
+
 // Implicit GEMM with a multi-stage LDS ring fed by direct global->LDS loads.
 // The workspace holds the repacked (k-contiguous) filter and, for splits > 1,
 // the fp32 partial outputs.  "Uniform" tiles need C to be a multiple of the

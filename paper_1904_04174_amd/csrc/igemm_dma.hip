@@ -42,6 +42,14 @@
 //  * gridDim.y > 1 splits the reduction: each workgroup takes a range of
 //    slices and writes an fp32 partial tile behind the repacked filter in the
 //    workspace; a reduce pass adds the partials in a fixed order.
+//  * Tail balancing ("stream-K tail"): output tiles rarely divide evenly over
+//    the 256 compute units (every M here is 49 * 2^k).  The first n_main
+//    tiles, a multiple of 256, run as whole tiles; the slices of the remaining
+//    tiles are laid end to end and cut into equal contiguous ranges, one per
+//    tail workgroup, so that every compute unit gets the same amount of work.
+//    A range covers pieces of at most two tiles; each piece is one workgroup
+//    that stores an fp32 partial tile, and tail_reduce_kernel adds the pieces
+//    of a tile in slice order.
 #include <type_traits>
 
 #include "conv2d_internal.h"
@@ -159,14 +167,32 @@ __global__ __launch_bounds__(256) void repack_filter_kernel(const E* __restrict_
   }
 }
 
-// gridDim.x = output tiles, gridDim.y = splits of the reduction.  `bt` is the
-// repacked filter, `partial` the fp32 partial outputs (used when gridDim.y > 1).
+// How the tail tiles' slices are dealt to the tail workgroups: `units` slices
+// in all, workgroup g takes base (+1 for the first `extra` workgroups).
+struct TailPlan {
+  int n_main;   // tiles [0, n_main) are computed whole, one workgroup each
+  int wgs;      // ranges the tail is cut into (0 = no tail); two workgroups per range
+  int base, extra;
+  __host__ __device__ long long first_unit(int g) const {
+    return 1LL * g * base + (g < extra ? g : extra);
+  }
+  __host__ __device__ int owner(long long u) const {  // workgroup that holds unit u
+    const long long head = 1LL * extra * (base + 1);
+    return u < head ? static_cast<int>(u / (base + 1)) : extra + static_cast<int>((u - head) / base);
+  }
+};
+
+// gridDim.x = tail.n_main + 2 * tail.wgs workgroups, gridDim.y = splits of the
+// reduction (1 when there is a tail).  `bt` is the repacked filter, `partial`
+// the fp32 partial outputs: [split][M][K] for a split reduction, or one
+// [BM][BN] tile per tail workgroup.
 template <class T, bool OUT_BF16>
 __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem p, const int Kg_p,
                                                                   const int slices_per_split,
                                                                   const int flush_slices,
                                                                   const void* bt,
-                                                                  float* partial) {
+                                                                  float* partial,
+                                                                  const TailPlan tail) {
   constexpr int BM = T::BM, BN = T::BN, BK = T::BK, S = T::STAGES, ROWB = T::ROWB, CPR = T::CPR;
   constexpr int ES = T::ES, VEC = T::VEC, KSTEPS = T::KSTEPS;
   constexpr int TM = T::TM, TN = T::TN, NM = T::NM, NR = T::NR, MPF = T::MPF;
@@ -183,17 +209,36 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   const int lk = lane >> 5;
 
   const int tiles_n = (p.K + BN - 1) / BN;
-  const int nwg = gridDim.x;
-  const int xcd = blockIdx.x % kXcds;
-  const int local = blockIdx.x / kXcds;
-  const int per = nwg / kXcds, rem = nwg % kXcds;
-  const int tile = xcd * per + (xcd < rem ? xcd : rem) + local;
+  const int nslices_all = Kg_p / BK;
+  const bool is_tail = static_cast<int>(blockIdx.x) >= tail.n_main;
+  const unsigned ring_base = __builtin_amdgcn_readfirstlane(lds_address(ring) + wave * 1024);
+
+  int tile, slice_begin, nslices;
+  if (!is_tail) {
+    // Workgroup i runs on XCD i % 8; give each XCD a contiguous range of
+    // tiles so that neighbours share input rows in its L2
+    const int nwg = tail.n_main;
+    const int xcd = blockIdx.x % kXcds;
+    const int local = blockIdx.x / kXcds;
+    const int per = nwg / kXcds, rem = nwg % kXcds;
+    tile = xcd * per + (xcd < rem ? xcd : rem) + local;
+    slice_begin = blockIdx.y * slices_per_split;
+    nslices = min(slices_per_split, nslices_all - slice_begin);
+  } else {
+    // tail workgroups 2g and 2g+1 take the two pieces of range g of the tail
+    // tiles' slice units: the part in the range's first tile and the rest
+    const int w = blockIdx.x - tail.n_main;
+    const long long u0 = tail.first_unit(w >> 1), u1 = tail.first_unit((w >> 1) + 1);
+    const int t0 = static_cast<int>(u0 / nslices_all);
+    const long long cut = min(u1, 1LL * (t0 + 1) * nslices_all);
+    const long long b = (w & 1) ? cut : u0, e = (w & 1) ? u1 : cut;
+    if (b >= e) return;  // the range lies in one tile: no second piece
+    tile = tail.n_main + t0 + (w & 1);
+    slice_begin = static_cast<int>(b - 1LL * (t0 + (w & 1)) * nslices_all);
+    nslices = static_cast<int>(e - b);
+  }
   const int m0 = (tile / tiles_n) * BM;
   const int n0 = (tile % tiles_n) * BN;
-
-  const int nslices_all = Kg_p / BK;
-  const int slice_begin = blockIdx.y * slices_per_split;
-  const int nslices = min(slices_per_split, nslices_all - slice_begin);
 
   // UNIFORM tiles address a row by the (possibly negative) offset of its
   // window origin plus a scalar tap offset; the descriptor base is moved
@@ -268,8 +313,6 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   const int step_r = (BK / p.C) / p.S;
   const int k_last_bytes = (Kg_p - BK) * ES;
   int k_next_bytes = min(slice_begin * BK * ES, k_last_bytes);
-
-  const unsigned ring_base = __builtin_amdgcn_readfirstlane(lds_address(ring) + wave * 1024);
 
   // One A load (row pass i) of the slice at the current position into `stage`.
   auto load_a = [&](int stage, int i) {
@@ -473,6 +516,19 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   }
 
   // ---- epilogue (accumulator layout: lane l reg v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32)
+  if (is_tail) {
+    // piece of a tail tile: a whole [BM][BN] fp32 tile, no bounds
+    float* part = partial + static_cast<size_t>(blockIdx.x - tail.n_main) * (BM * BN);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          part[(wm * T::WM + i * 32 + lk * 4 + 8 * (v / 4) + (v % 4)) * BN + wn * T::WN + j * 32 +
+               lr] = acc[i][j][v];
+    return;
+  }
   const bool to_partial = gridDim.y > 1;
   float* part = partial + static_cast<size_t>(blockIdx.y) * static_cast<size_t>(p.M) * p.K;
 #pragma unroll
@@ -498,6 +554,42 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   }
 }
 
+// Sum of the pieces of each tail tile, in slice order, to the output.  One
+// workgroup per (tail tile, 16 rows); a thread adds 4 consecutive columns.
+template <int BM, int BN, bool OUT_BF16>
+__global__ __launch_bounds__(256) void tail_reduce_kernel(const float* __restrict__ partial,
+                                                          void* __restrict__ out, int M, int K,
+                                                          int nslices, const TailPlan tail) {
+  const int t = blockIdx.x;  // tail tile
+  const int tiles_n = (K + BN - 1) / BN;
+  const int tile = tail.n_main + t;
+  const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+  const int g_lo = tail.owner(1LL * t * nslices);
+  const int g_hi = tail.owner(1LL * (t + 1) * nslices - 1);
+  for (int e = (blockIdx.y * 256 + threadIdx.x) * 4; e < BM * BN; e += gridDim.y * 1024) {
+    const int row = e / BN, col = e % BN;
+    float4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int g = g_lo; g <= g_hi; ++g) {
+      // the workgroup's first piece lies in tile first_unit / nslices
+      const int piece = (tail.first_unit(g) / nslices == t) ? 0 : 1;
+      const float4 v = *reinterpret_cast<const float4*>(
+          partial + (static_cast<size_t>(g) * 2 + piece) * (BM * BN) + e);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    const int m = m0 + row, n = n0 + col;
+    if (m >= M) continue;
+    const float a[4] = {acc.x, acc.y, acc.z, acc.w};
+    for (int c = 0; c < 4; ++c) {
+      if (n + c >= K) break;
+      const size_t idx = static_cast<size_t>(m) * K + n + c;
+      if (OUT_BF16)
+        static_cast<unsigned short*>(out)[idx] = to_bf16_bits(a[c]);
+      else
+        static_cast<float*>(out)[idx] = a[c];
+    }
+  }
+}
+
 // Bytes of the repacked filter at the head of the workspace (a multiple of 256).
 template <class T>
 size_t filter_bytes(const Problem& p) {
@@ -514,6 +606,28 @@ int clamp_splits(const Problem& p, int splits, int* per_split) {
   return (nslices + *per_split - 1) / *per_split;  // no empty split
 }
 
+// Tail plan for a problem: whole rounds of 256 tiles run as they are, the
+// slices of the remaining tiles are dealt evenly to up to 256 workgroups
+// (never more than two pieces each, no piece shorter than about 4 slices).
+template <class T>
+TailPlan plan_tail(const Problem& p, bool want_tail) {
+  const int tiles = ((p.M + T::BM - 1) / T::BM) * ((p.K + T::BN - 1) / T::BN);
+  const int nslices = (p.Kg + T::BK - 1) / T::BK;
+  TailPlan t = {tiles, 0, 0, 0};
+  const int rest = tiles % 256;
+  if (!want_tail || rest == 0) return t;
+  const long long units = 1LL * rest * nslices;
+  long long wgs = units / 4 < 256 ? units / 4 : 256;
+  if (wgs < rest) wgs = rest;
+  t.n_main = tiles - rest;
+  t.wgs = static_cast<int>(wgs);
+  t.base = static_cast<int>(units / wgs);
+  t.extra = static_cast<int>(units % wgs);
+  return t;
+}
+
+// `splits` > 1: uniform split of the reduction; `splits` == kTailBalanced:
+// whole tiles plus a balanced tail; otherwise one workgroup per tile.
 template <class T, bool OUT_BF16>
 hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   const int Kg_p = (p.Kg + T::BK - 1) / T::BK * T::BK;
@@ -530,20 +644,27 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // 2. the convolution
-  const int tiles_m = (p.M + T::BM - 1) / T::BM;
-  const int tiles_n = (p.K + T::BN - 1) / T::BN;
+  const TailPlan tail = plan_tail<T>(p, splits == kTailBalanced);
   int per_split;
   splits = clamp_splits<T>(p, splits, &per_split);
   int flush = 1;
   while (flush * flush < per_split) ++flush;
   float* partial = reinterpret_cast<float*>(static_cast<unsigned char*>(p.workspace) +
                                             filter_bytes<T>(p));
-  hipLaunchKernelGGL((igemm_dma_kernel<T, OUT_BF16>), dim3(tiles_m * tiles_n, splits), dim3(T::NT),
-                     0, stream, p, Kg_p, per_split, flush, p.workspace, partial);
+  hipLaunchKernelGGL((igemm_dma_kernel<T, OUT_BF16>), dim3(tail.n_main + 2 * tail.wgs, splits),
+                     dim3(T::NT), 0, stream, p, Kg_p, per_split, flush, p.workspace, partial, tail);
   e = hipGetLastError();
-  if (e != hipSuccess || splits == 1) return e;
+  if (e != hipSuccess) return e;
   // 3. sum of the partial outputs
-  return launch_split_reduce(partial, p.out, p.M * p.K, splits, OUT_BF16, stream);
+  if (tail.wgs > 0) {
+    const int rest = ((p.M + T::BM - 1) / T::BM) * ((p.K + T::BN - 1) / T::BN) - tail.n_main;
+    hipLaunchKernelGGL((tail_reduce_kernel<T::BM, T::BN, OUT_BF16>),
+                       dim3(rest, T::BM * T::BN / 4096), dim3(256), 0, stream, partial, p.out, p.M,
+                       p.K, Kg_p / T::BK, tail);
+    return hipGetLastError();
+  }
+  if (splits > 1) return launch_split_reduce(partial, p.out, p.M * p.K, splits, OUT_BF16, stream);
+  return hipSuccess;
 }
 
 template <class T>
@@ -554,6 +675,9 @@ hipError_t launch(const Problem& p, int splits, hipStream_t stream) {
 
 template <class T>
 size_t workspace_bytes(const Problem& p, int splits) {
+  const TailPlan tail = plan_tail<T>(p, splits == kTailBalanced);
+  if (tail.wgs > 0)
+    return filter_bytes<T>(p) + static_cast<size_t>(tail.wgs) * 2 * T::BM * T::BN * sizeof(float);
   int per_split;
   splits = clamp_splits<T>(p, splits, &per_split);
   return filter_bytes<T>(p) +

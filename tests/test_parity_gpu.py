@@ -87,6 +87,7 @@ SMALL = [
     (1, 40, 40, 3, 16, 7, 7, 2, 2, wl.PAD_SAME),       # C = 3 (only the general variants)
     (2, 9, 9, 5, 7, 3, 3, 1, 1, wl.PAD_SAME),          # odd C and K
     (1, 33, 33, 128, 128, 3, 3, 1, 1, wl.PAD_SAME),    # deep reduction, >1 tile of 256 rows
+    (8, 48, 48, 16, 64, 3, 3, 1, 1, wl.PAD_SAME),      # 288 tiles of 64x64: whole rounds + a tail
 ]
 
 
