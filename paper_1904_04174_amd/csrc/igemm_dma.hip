@@ -5,11 +5,12 @@
 // D[M][K] = A[M][Kg] * B[Kg][K], Kg ordered (r,s,c)): A rows are gathered from
 // the NHWC input, D is the NHWC output.
 //
-//  * The filter is first repacked into the workspace as Bt[K][Kg_p] (k
-//    contiguous, Kg_p = Kg rounded up to the slice width, zero filled), so
-//    that A and B tiles are both "rows of ROWB contiguous bytes" and both can
-//    be written to LDS by the load instruction itself: no staging registers,
-//    no transposes, and as many slices in flight as LDS has room for.
+//  * The filter is first repacked into the workspace as Bt[slice][K][BK]
+//    (k contiguous within a slice of BK, Kg rounded up to whole slices, zero
+//    filled), so that A and B tiles are both "rows of ROWB contiguous bytes"
+//    and both can be written to LDS by the load instruction itself: no
+//    staging registers, no transposes, and as many slices in flight as LDS
+//    has room for.  A slice's B tile is one contiguous block of memory.
 //  * A slice is ROWB = 64 or 128 bytes of k per row.  One load instruction
 //    of a wavefront fills 1 KiB of LDS: lane l -> row l / CPR, 16-byte chunk
 //    position l % CPR (CPR = ROWB/16 chunks per row).  LDS cannot be padded
@@ -146,24 +147,37 @@ __device__ __forceinline__ unsigned short to_bf16_bits(float x) {
   return static_cast<unsigned short>(u >> 16);
 }
 
-// Bt[n][k] = filt[k][n] for k < Kg, 0 for Kg <= k < Kg_p.  32x32 tiles through LDS.
+// Bt[k' / bk][n][k' % bk] = filt[k][n], 0 for Kg <= k' < Kg_p: one slice of bk
+// consecutive k' for all features is contiguous, so a B tile of a slice is
+// one contiguous block and its loads fetch whole cache lines.  With
+// block == 0, k' = k (the (r,s,c) order).  With block > 0 (a divisor of C) the reduction is reordered
+// channel block by channel block: k' = ((c / block) * taps + tap) * block +
+// c % block for k = tap * C + c.  32x32 tiles through LDS.
 template <typename E>
 __global__ __launch_bounds__(256) void repack_filter_kernel(const E* __restrict__ filt,
                                                             E* __restrict__ bt, int Kg, int K,
-                                                            int Kg_p) {
+                                                            int Kg_p, int C, int taps, int block,
+                                                            int bk) {
   __shared__ E tile[32][33];
   const int k0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int k = k0 + ty + 8 * j, n = n0 + tx;
-    tile[ty + 8 * j][tx] = (k < Kg && n < K) ? filt[static_cast<size_t>(k) * K + n] : E(0);
+    const int kp = k0 + ty + 8 * j, n = n0 + tx;
+    int k = kp;
+    if (block > 0 && kp < Kg) {
+      const int per = taps * block;
+      const int rem = kp % per;
+      k = (rem / block) * C + (kp / per) * block + rem % block;
+    }
+    tile[ty + 8 * j][tx] = (kp < Kg && n < K) ? filt[static_cast<size_t>(k) * K + n] : E(0);
   }
   __syncthreads();
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int n = n0 + ty + 8 * j, k = k0 + tx;
-    if (n < K && k < Kg_p) bt[static_cast<size_t>(n) * Kg_p + k] = tile[tx][ty + 8 * j];
+    if (n < K && k < Kg_p)
+      bt[(static_cast<size_t>(k / bk) * K + n) * bk + k % bk] = tile[tx][ty + 8 * j];
   }
 }
 
@@ -289,12 +303,12 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
 #pragma unroll
   for (int i = 0; i < T::B_ITERS; ++i) {
     const int n = n0 + ld_row0 + i * T::ROWS_PER_PASS;
-    b_voff[i] = (n < p.K) ? (n * Kg_p + ld_chunk * VEC) * ES : kOutOfRange;
+    b_voff[i] = (n < p.K) ? (n * BK + ld_chunk * VEC) * ES : kOutOfRange;
   }
   // Position of the next slice to load.  UNIFORM: scalar tap index and channel
   // offset.  Otherwise (r, s, c) of this lane's chunk, stepped without division.
   int kc, ks, kr;
-  int tap_bit = 0, tap_c = 0, tap_s = 0, tap_rowoff = 0;  // UNIFORM
+  int tap_bit = 0, tap_idx = 0, tap_c = 0, tap_s = 0, tap_rowoff = 0;  // UNIFORM
   {
     const int kg = slice_begin * BK + (UNIFORM ? 0 : ld_chunk * VEC);
     kc = kg % p.C;
@@ -302,17 +316,26 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
     ks = t % p.S;
     kr = t / p.S;
     if constexpr (UNIFORM) {
-      tap_bit = min(t, 31);
-      tap_c = kc;
-      tap_s = ks;
-      tap_rowoff = kr * p.W * p.C;
+      // UNIFORM tiles walk the reduction channel block by channel block, all
+      // taps of a block of BK channels before the next block: the taps of
+      // one block re-read the same input pixels within a few slices, while
+      // they are still in L2 (the filter is repacked in the same order)
+      const int taps = p.R * p.S;
+      const int tap = slice_begin % taps;
+      tap_c = (slice_begin / taps) * BK;
+      tap_s = tap % p.S;
+      tap_rowoff = (tap / p.S) * p.W * p.C;
+      tap_idx = tap;
+      tap_bit = tap_c < p.C ? tap : 31;
     }
   }
   const int step_c = BK % p.C;
   const int step_s = (BK / p.C) % p.S;
   const int step_r = (BK / p.C) / p.S;
-  const int k_last_bytes = (Kg_p - BK) * ES;
-  int k_next_bytes = min(slice_begin * BK * ES, k_last_bytes);
+  // byte offset of a slice of the repacked filter: slices of K rows of ROWB bytes
+  const int k_slice_bytes = p.K * ROWB;
+  const int k_last_bytes = (nslices_all - 1) * k_slice_bytes;
+  int k_next_bytes = min(slice_begin * k_slice_bytes, k_last_bytes);
 
   // One A load (row pass i) of the slice at the current position into `stage`.
   auto load_a = [&](int stage, int i) {
@@ -338,19 +361,21 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
     // the scalar offset is not range checked: slices issued past the end
     // re-read the last slice (into a stage nobody reads) instead of running
     // off the end of the repacked filter
-    k_next_bytes = min(k_next_bytes + ROWB, k_last_bytes);
+    k_next_bytes = min(k_next_bytes + k_slice_bytes, k_last_bytes);
     if constexpr (UNIFORM) {
-      tap_c += BK;
-      if (tap_c >= p.C) {
-        tap_c = 0;
-        // windows have at most 31 taps here, so bit 31 is clear in every
-        // mask: past the last tap every row reads as out of range
-        tap_bit = min(tap_bit + 1, 31);
-        if (++tap_s >= p.S) {
-          tap_s = 0;
-          tap_rowoff += p.W * p.C;
-        }
+      ++tap_idx;
+      if (++tap_s >= p.S) {
+        tap_s = 0;
+        tap_rowoff += p.W * p.C;
       }
+      if (tap_idx >= p.R * p.S) {
+        tap_idx = 0;
+        tap_rowoff = 0;
+        tap_c += BK;
+      }
+      // windows have at most 31 taps here, so bit 31 is clear in every mask:
+      // past the last channel block every row reads as out of range
+      tap_bit = tap_c < p.C ? tap_idx : 31;
     } else {
       kc += step_c;
       const int carry_c = kc >= p.C;
@@ -554,8 +579,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   }
 }
 
-// Sum of the pieces of each tail tile, in slice order, to the output.  One
-// workgroup per (tail tile, 16 rows); a thread adds 4 consecutive columns.
+// Sum of the pieces of each tail tile, in slice order, to the output.
+// gridDim.x = tail tiles, gridDim.y * 1024 = BM * BN: a thread adds 4
+// consecutive columns of one row.
 template <int BM, int BN, bool OUT_BF16>
 __global__ __launch_bounds__(256) void tail_reduce_kernel(const float* __restrict__ partial,
                                                           void* __restrict__ out, int M, int K,
@@ -564,23 +590,27 @@ __global__ __launch_bounds__(256) void tail_reduce_kernel(const float* __restric
   const int tiles_n = (K + BN - 1) / BN;
   const int tile = tail.n_main + t;
   const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
-  const int g_lo = tail.owner(1LL * t * nslices);
-  const int g_hi = tail.owner(1LL * (t + 1) * nslices - 1);
-  for (int e = (blockIdx.y * 256 + threadIdx.x) * 4; e < BM * BN; e += gridDim.y * 1024) {
-    const int row = e / BN, col = e % BN;
-    float4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int g = g_lo; g <= g_hi; ++g) {
-      // the workgroup's first piece lies in tile first_unit / nslices
-      const int piece = (tail.first_unit(g) / nslices == t) ? 0 : 1;
-      const float4 v = *reinterpret_cast<const float4*>(
-          partial + (static_cast<size_t>(g) * 2 + piece) * (BM * BN) + e);
-      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-    }
-    const int m = m0 + row, n = n0 + col;
-    if (m >= M) continue;
-    const float a[4] = {acc.x, acc.y, acc.z, acc.w};
-    for (int c = 0; c < 4; ++c) {
-      if (n + c >= K) break;
+  const long long first = 1LL * t * nslices;
+  const int g_lo = tail.owner(first);
+  const int g_hi = tail.owner(first + nslices - 1);
+  const int e = (blockIdx.y * 256 + threadIdx.x) * 4;
+  const int row = e / BN, col = e % BN;
+  // range g_lo holds the tile's first slice: as its first piece if the range
+  // starts there, else as its second; every later range starts inside the tile
+  const float* src = partial + (static_cast<size_t>(g_lo) * 2 +
+                                (tail.first_unit(g_lo) == first ? 0 : 1)) * (BM * BN) + e;
+  float4 acc = *reinterpret_cast<const float4*>(src);
+  for (int g = g_lo + 1; g <= g_hi; ++g) {
+    const float4 v =
+        *reinterpret_cast<const float4*>(partial + static_cast<size_t>(g) * 2 * (BM * BN) + e);
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  const int m = m0 + row, n = n0 + col;
+  if (m >= M) return;
+  const float a[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    if (n + c < K) {
       const size_t idx = static_cast<size_t>(m) * K + n + c;
       if (OUT_BF16)
         static_cast<unsigned short*>(out)[idx] = to_bf16_bits(a[c]);
@@ -606,18 +636,24 @@ int clamp_splits(const Problem& p, int splits, int* per_split) {
   return (nslices + *per_split - 1) / *per_split;  // no empty split
 }
 
-// Tail plan for a problem: whole rounds of 256 tiles run as they are, the
-// slices of the remaining tiles are dealt evenly to up to 256 workgroups
-// (never more than two pieces each, no piece shorter than about 4 slices).
+// Tail plan for a problem.  Whole rounds of 256 tiles (one per compute unit)
+// run as they are; the slices of the remaining tiles are dealt evenly to up
+// to 256 ranges (never more than two pieces each, no piece shorter than about
+// 4 slices).  The dispatcher fills all workgroup slots of a compute unit
+// before it moves to the next, so fewer whole tiles than one workgroup per
+// slot would leave units idle while others hold two tiles: then every tile
+// goes to the tail.
 template <class T>
 TailPlan plan_tail(const Problem& p, bool want_tail) {
   const int tiles = ((p.M + T::BM - 1) / T::BM) * ((p.K + T::BN - 1) / T::BN);
   const int nslices = (p.Kg + T::BK - 1) / T::BK;
   TailPlan t = {tiles, 0, 0, 0};
-  const int rest = tiles % 256;
+  int rest = tiles % 256;
   if (!want_tail || rest == 0) return t;
+  if (tiles - rest < 256 * T::OCC) rest = tiles;
   const long long units = 1LL * rest * nslices;
-  long long wgs = units / 4 < 256 ? units / 4 : 256;
+  const long long most = rest > 256 ? 256LL * ((rest + 255) / 256) : 256;
+  long long wgs = units / 4 < most ? units / 4 : most;
   if (wgs < rest) wgs = rest;
   t.n_main = tiles - rest;
   t.wgs = static_cast<int>(wgs);
@@ -636,11 +672,12 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   if (T::BF16)
     hipLaunchKernelGGL((repack_filter_kernel<unsigned short>), rgrid, dim3(256), 0, stream,
                        static_cast<const unsigned short*>(p.filt),
-                       static_cast<unsigned short*>(p.workspace), p.Kg, p.K, Kg_p);
+                       static_cast<unsigned short*>(p.workspace), p.Kg, p.K, Kg_p, p.C,
+                       p.R * p.S, T::UNIFORM ? T::BK : 0, T::BK);
   else
     hipLaunchKernelGGL((repack_filter_kernel<float>), rgrid, dim3(256), 0, stream,
                        static_cast<const float*>(p.filt), static_cast<float*>(p.workspace), p.Kg,
-                       p.K, Kg_p);
+                       p.K, Kg_p, p.C, p.R * p.S, T::UNIFORM ? T::BK : 0, T::BK);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // 2. the convolution
@@ -659,7 +696,7 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   if (tail.wgs > 0) {
     const int rest = ((p.M + T::BM - 1) / T::BM) * ((p.K + T::BN - 1) / T::BN) - tail.n_main;
     hipLaunchKernelGGL((tail_reduce_kernel<T::BM, T::BN, OUT_BF16>),
-                       dim3(rest, T::BM * T::BN / 4096), dim3(256), 0, stream, partial, p.out, p.M,
+                       dim3(rest, T::BM * T::BN / 1024), dim3(256), 0, stream, partial, p.out, p.M,
                        p.K, Kg_p / T::BK, tail);
     return hipGetLastError();
   }
