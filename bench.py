@@ -26,6 +26,16 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2516.6}   # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of the selected fp32 variant (convolution kernel), from two rocprofv3 --pmc
+# runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, factors calibrated on a 256 MiB copy); source:
+# profiles/igemm_dma_counters_per_layer.md.  Not measurable inside this process.
+MEASURED_TRAFFIC_MB = {
+    ("f32", "V224-N16"): 213.1 + 209.7, ("f32", "V112-N16"): 115.0 + 109.1,
+    ("f32", "V56-N16"): 97.9 + 67.1, ("f32", "V28-N16"): 214.0 + 33.6,
+    ("f32", "V14-N16"): 110.1 + 19.3 + 6.4,
+    ("bf16", "V56-N16"): 35.8 + 51.4, ("bf16", "V28-N16"): 55.5 + 25.7,
+}
+
 
 def layer_flops(B, p):
     g = B.conv2d_get_geometry(p)
@@ -155,7 +165,11 @@ def main():
     peak = PEAK_TFLOPS[args.dtype]
     achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(achieved / peak, 4), "traffic": None,
+                "frac": round(achieved / peak, 4),
+                "traffic": (round(MEASURED_TRAFFIC_MB[(args.dtype, dom["name"])] * 1e6)
+                            if (args.dtype, dom["name"]) in MEASURED_TRAFFIC_MB else None),
+                "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled)",
+                "algorithmic_bytes_per_launch": dom["bytes"],
                 "kernel": dom["variant"], "layer": dom["name"],
                 "kernel_ms": round(dom["ms"], 4),
                 "algorithmic_gflop_per_launch": round(dom["flops"] / 1e9, 3)}

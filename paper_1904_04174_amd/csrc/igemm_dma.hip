@@ -740,6 +740,7 @@ const TileEntry kTilesF32[] = {
     CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, true, ""),
     CONV2D_DMA_TILE("f32", false, 256, 128, 64, 4, 2, 4, true, 2, true, ""),
     CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 4, true, 4, true, ""),
+    CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 3, true, 6, true, ""),
     CONV2D_DMA_TILE("f32", false, 128, 128, 64, 2, 2, 4, true, 2, false, "_g"),
     CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, false, "_g"),
     CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 4, true, 4, false, "_g"),
@@ -751,6 +752,7 @@ const TileEntry kTilesBf16[] = {
     CONV2D_DMA_TILE("bf16", true, 128, 128, 64, 2, 2, 4, false, 2, true, ""),
     CONV2D_DMA_TILE("bf16", true, 128, 64, 64, 2, 2, 4, false, 3, true, ""),
     CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 4, false, 4, true, ""),
+    CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 3, false, 6, true, ""),
     CONV2D_DMA_TILE("bf16", true, 128, 128, 64, 2, 2, 4, false, 2, false, "_g"),
     CONV2D_DMA_TILE("bf16", true, 128, 64, 64, 2, 2, 4, false, 3, false, "_g"),
     CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 4, false, 4, false, "_g"),

@@ -195,3 +195,41 @@ def test_split_reduction_variants_state_their_workspace():
     for v, n in enumerate(names):
         if n.endswith("_splitk"):
             assert not B.conv2d_variant_supports(p1, v)
+
+
+def test_workspace_is_checked_before_any_launch():
+    # a variant that needs scratch: too little of it, or a misaligned pointer, is an error status
+    p = B.params_of_layer(wl.LAYERS["V14-N1"])
+    names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
+    v = next(i for i, n in enumerate(names)
+             if n.startswith("igemm_dma_f32") and B.conv2d_variant_supports(p, i))
+    need = B.conv2d_workspace_size(p, v)
+    assert need > 0
+    assert B.conv2d_forward_raw(p, 256, 512, 768, 0, 0, variant_id=v) == B.STATUS_WORKSPACE_TOO_SMALL
+    assert B.conv2d_forward_raw(p, 256, 512, 768, 1024, need - 1,
+                                variant_id=v) == B.STATUS_WORKSPACE_TOO_SMALL
+    assert B.conv2d_forward_raw(p, 256, 512, 768, 1028, need,
+                                variant_id=v) == B.STATUS_INVALID_ARGUMENT
+
+
+def test_tuned_table_names_existing_variants():
+    # every named layer has a tuned choice; it must resolve to a variant that supports the layer
+    names = {B.conv2d_variant_name(v): v for v in range(B.conv2d_num_variants())}
+    import os
+    table = os.path.join(os.path.dirname(B.__file__), "csrc", "tuned_table.inc")
+    rows = [l for l in open(table) if l.startswith("{")]
+    assert len(rows) >= len(wl.LAYERS)
+    for l in rows:
+        fields = l[1:l.index("}")].split(",")
+        name = fields[-1].strip().strip('"')
+        bf16, n, h, w, c, k, r, s_, sr, sc, pad = (int(f) for f in fields[:-1])
+        p = B.make_params(n, h, w, c, k, r, s_, sr, sc, pad, B.BF16 if bf16 else B.F32, B.F32)
+        assert name in names, name
+        assert B.conv2d_variant_supports(p, names[name]), l
+        assert B.conv2d_selected_variant(p) == names[name], l
+
+
+def test_variant_names_are_unique():
+    names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
+    assert len(set(names)) == len(names)
+    assert B.conv2d_variant_name(-1) is None and B.conv2d_variant_name(len(names)) is None

@@ -187,6 +187,41 @@ def test_runs_on_a_side_stream(torch_cuda, oracle):
     assert rel_err(out.cpu().numpy(), want) <= TOL_F32
 
 
+def test_unaligned_pointers_take_the_element_wise_path(torch_cuda, oracle):
+    # input, filter and output all start 4 bytes past a 16-byte boundary: the
+    # vector variants refuse, the selector falls back to a variant that can run
+    torch = torch_cuda
+    case = (2, 13, 11, 8, 12, 3, 3, 1, 1, wl.PAD_SAME)
+    n, h, w, c, k, r, s, sr, sc, pad = case
+    x, f = wl.make_case((n, h, w, c), (r, s, c, k), "uniform", 4242)
+    want = oracle.forward_f32(x, f, (sr, sc), pad)
+    p = _params(case)
+    def shifted(a):
+        buf = torch.empty(a.size + 1, dtype=torch.float32, device="cuda")
+        v = buf[1:].view(a.shape)
+        v.copy_(torch.from_numpy(a))
+        return v
+    xd, fd = shifted(x), shifted(f)
+    out = shifted(np.full(want.shape, np.nan, np.float32))
+    assert xd.data_ptr() % 16 == 4 and out.data_ptr() % 16 == 4
+    B.conv2d_forward(p, xd, fd, out=out)
+    torch.cuda.synchronize()
+    assert rel_err(out.cpu().numpy(), want) <= TOL_F32
+    names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
+    for v, name in enumerate(names):
+        if not B.conv2d_variant_supports(p, v):
+            continue
+        ws = torch.empty(max(B.conv2d_workspace_size(p, v), 16), dtype=torch.uint8, device="cuda")
+        rc = B.conv2d_forward_raw(p, xd.data_ptr(), fd.data_ptr(), out.data_ptr(), ws.data_ptr(),
+                                  ws.numel(), 0, v)
+        torch.cuda.synchronize()
+        if name == "direct" or "scalar" in name:
+            assert rc == B.STATUS_OK, name
+            assert rel_err(out.cpu().numpy(), want) <= TOL_F32, name
+        else:
+            assert rc == B.STATUS_UNSUPPORTED, name
+
+
 def test_empty_batch_on_gpu(torch_cuda):
     torch = torch_cuda
     p = B.make_params(0, 8, 8, 4, 4, 3, 3)
