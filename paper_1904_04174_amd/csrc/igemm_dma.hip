@@ -20,13 +20,15 @@
 //    apply the same XOR (measured: full LDS read rate).
 //  * Padding taps / rows past M / k past Kg use an out-of-range buffer
 //    offset: the hardware then writes zeros to LDS.
-//  * STAGES (>= 3) LDS buffers form a ring.  The MFMA fragments are double
+//  * STAGES (>= 2) LDS buffers form a ring.  The MFMA fragments are double
 //    buffered in registers: while the MFMAs of step t run, the fragments of
-//    step t+1 are read from LDS.  In the last step of slice i each wave waits
-//    for its own loads of slice i+1 (s_waitcnt vmcnt(N), younger slices stay
-//    in flight), passes the one barrier of the slice, issues the loads of
-//    slice i+STAGES-1 into the stage of slice i-1 (which every wave has
-//    left), and reads the first fragments of slice i+1.
+//    step t+1 are read from LDS, so during the last step of slice i nothing
+//    of its stage is needed any more.  In that step each wave waits for its
+//    own loads of slice i+1 (s_waitcnt vmcnt(N), younger slices stay in
+//    flight) and for its own LDS reads, passes the one barrier of the slice,
+//    issues the loads of slice i+STAGES into the stage of slice i (which
+//    every wave has now read completely), and reads the first fragments of
+//    slice i+1: loads run STAGES-1 slices ahead of the MFMAs.
 //  * Everything that is not an MFMA (fragment reads, address arithmetic, load
 //    issue, the barrier) is dealt out one piece at a time between consecutive
 //    MFMAs and pinned there with scheduling fences: an MFMA occupies the
@@ -69,6 +71,8 @@ constexpr int kOutOfRange = static_cast<int>(0x80000000u);
 // s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding:
 // vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "no wait").
 constexpr int vmcnt_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4) | (0xf << 8); }
+// the same, and all of this wave's LDS reads complete as well (lgkmcnt == 0)
+constexpr int vmcnt_lds_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4); }
 
 // Raw buffer descriptor (base moved back by shift_back bytes, stride 0, bytes,
 // flags) as four scalars.
@@ -127,11 +131,11 @@ struct DmaTile {
   static constexpr int B_ITERS = BN / ROWS_PER_PASS;
   static constexpr int LOADS = A_ITERS + B_ITERS;  // load instructions per slice per lane
   static constexpr int STAGE_BYTES = (BM + BN) * ROWB;
-  static constexpr int WAIT_STEADY = (STAGES - 3) * LOADS;  // loads that may stay in flight
-  static constexpr int WAIT_FIRST = (STAGES - 2) * LOADS;
+  static constexpr int WAIT_STEADY = (STAGES - 2) * LOADS;  // loads that may stay in flight
+  static constexpr int WAIT_FIRST = (STAGES - 1) * LOADS;
   static_assert(ROWB == 64 || ROWB == 128, "64 or 128 bytes per row");
   static_assert(KSTEPS % 2 == 0, "fragment double buffering needs an even step count");
-  static_assert(STAGES >= 3 && STAGES <= 8, "3 to 8 stages");
+  static_assert(STAGES >= 2 && STAGES <= 8, "2 to 8 stages");
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of 32x32");
   static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "tile rows must divide");
   static_assert(ROWS_PER_PASS % 16 == 0, "the swizzle must be the same for all rows of a lane");
@@ -445,7 +449,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   // One fragment step: NM MFMAs with the side work dealt out between them.
   // Side work of an ordinary step: the NR fragment reads of the next step.
   // Side work of the last step of a slice: wait + barrier, the NR reads of
-  // the next slice's first step, the LOADS loads of slice i+S-1, advance.
+  // the next slice's first step, the LOADS loads of slice i+S, advance.
   // Side items start after the first MFMA and are spaced so that all of them
   // are out well before the step ends.
   auto step = [&](auto cur_c, auto nxt_c, int stage, int kk, int stage_next, int stage_load) {
@@ -466,8 +470,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
         } else if (item == 0) {
           // next step belongs to the next slice: its loads must have landed
           // (this lane's: vmcnt; everyone's: barrier), and the barrier also
-          // says that every wave has left the previous slice's stage
-          __builtin_amdgcn_s_waitcnt(vmcnt_imm(T::WAIT_STEADY));
+          // says that every wave's reads of this slice's stage are complete
+          // (lgkmcnt), so the loads below may overwrite it
+          __builtin_amdgcn_s_waitcnt(vmcnt_lds_imm(T::WAIT_STEADY));
           __builtin_amdgcn_s_barrier();
           asm volatile("" ::: "memory");  // LDS changed behind the compiler's back
         } else if (item <= NR) {
@@ -484,9 +489,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
     }
   };
 
-  // prologue: slices 0 .. S-2 in flight, slice 0 landed, its first fragments read
+  // prologue: slices 0 .. S-1 in flight, slice 0 landed, its first fragments read
 #pragma unroll
-  for (int s = 0; s < S - 1; ++s) {
+  for (int s = 0; s < S; ++s) {
 #pragma unroll
     for (int i = 0; i < T::A_ITERS; ++i) load_a(s, i);
 #pragma unroll
@@ -509,9 +514,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
           // KSTEPS is even: step kk uses fragment buffer kk % 2, and the first
           // step of the next slice uses buffer 0 again
           if (kk % 2 == 0)
-            step(Buf0{}, Buf1{}, u, kk, (u + 1) % S, (u + S - 1) % S);
+            step(Buf0{}, Buf1{}, u, kk, (u + 1) % S, u);
           else
-            step(Buf1{}, Buf0{}, u, kk, (u + 1) % S, (u + S - 1) % S);
+            step(Buf1{}, Buf0{}, u, kk, (u + 1) % S, u);
         }
         if (T::TWO_LEVEL) {
           if (--until_flush == 0) {
@@ -747,6 +752,7 @@ const TileEntry kTilesF32[] = {
 };
 const TileEntry kTilesBf16[] = {
     CONV2D_DMA_TILE("bf16", true, 256, 256, 64, 4, 2, 4, false, 1, true, ""),
+    CONV2D_DMA_TILE("bf16", true, 256, 256, 128, 4, 2, 2, false, 1, true, ""),
     CONV2D_DMA_TILE("bf16", true, 256, 128, 64, 4, 2, 4, false, 1, true, ""),
     CONV2D_DMA_TILE("bf16", true, 256, 128, 64, 4, 2, 3, false, 2, true, ""),
     CONV2D_DMA_TILE("bf16", true, 128, 128, 64, 2, 2, 4, false, 2, true, ""),
