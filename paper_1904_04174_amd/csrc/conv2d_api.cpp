@@ -139,8 +139,10 @@ int occupancy(const Variant& v) {
                             : igemm_dma_tile_occupancy(v.bf16, v.tile);
 }
 
+// Element-wise tiles: any C and K, pointers only 4-byte aligned.
 bool is_scalar(const Variant& v) {
-  return v.family == kIgemm && igemm_tile_is_scalar(v.bf16, v.tile);
+  if (v.family == kIgemm) return igemm_tile_is_scalar(v.bf16, v.tile);
+  return v.family == kDma && igemm_dma_tile_addressing(v.bf16, v.tile) == 2;
 }
 
 bool supports(const Variant& v, const Problem& q) {
@@ -161,9 +163,9 @@ bool supports(const Variant& v, const Problem& q) {
   }
   // direct-to-LDS tiles: filter rows in the workspace are padded to the slice
   // width; the input descriptor is extended by up to a window of bytes
-  if (q.C % vec != 0 || 1LL * es * (q.Kg + bk) * q.K >= (1LL << 31)) return false;
+  if ((!is_scalar(v) && q.C % vec != 0) || 1LL * es * (q.Kg + bk) * q.K >= (1LL << 31)) return false;
   if (1LL * es * (1LL * q.N * q.H * q.W + 1LL * q.R * q.W + q.S) * q.C >= (1LL << 31)) return false;
-  if (igemm_dma_tile_is_uniform(v.bf16, v.tile) && (q.C % bk != 0 || q.R * q.S > 31)) return false;
+  if (igemm_dma_tile_addressing(v.bf16, v.tile) == 0 && (q.C % bk != 0 || q.R * q.S > 31)) return false;
   if (v.split == kSplit && (q.Kg + bk - 1) / bk < 2) return false;
   // a balanced tail needs tiles left over after whole rounds of the 256 compute units
   if (v.split == kTail && (ceil_div_ll(q.M, bm) * ceil_div_ll(q.K, bn)) % 256 == 0) return false;

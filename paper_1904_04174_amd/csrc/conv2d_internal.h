@@ -54,13 +54,15 @@ constexpr int kTailBalanced = -1;
 
 // Implicit GEMM with a multi-stage LDS ring fed by direct global->LDS loads.
 // The workspace holds the repacked (k-contiguous) filter and, for splits > 1,
-// the fp32 partial outputs.  "Uniform" tiles need C to be a multiple of the
-// tile's bk and a window of at most 31 taps.
+// the fp32 partial outputs.  Addressing kinds of a tile: 0 = "uniform" (C a
+// multiple of the tile's bk and a window of at most 31 taps), 1 = vector (C a
+// multiple of the 16-byte vector), 2 = element-wise (fp32, any C and K, any
+// 4-byte alignment of input, filter and output).
 int igemm_dma_num_tiles(int bf16);
 const char* igemm_dma_tile_name(int bf16, int tile);
 void igemm_dma_tile_shape(int bf16, int tile, int* bm, int* bn, int* bk);
 int igemm_dma_tile_occupancy(int bf16, int tile);
-bool igemm_dma_tile_is_uniform(int bf16, int tile);
+int igemm_dma_tile_addressing(int bf16, int tile);
 size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile, int splits);
 hipError_t launch_igemm_dma(const Problem& p, int bf16, int tile, int splits, hipStream_t stream);
 

@@ -102,8 +102,24 @@ __device__ __forceinline__ void dma16(const uintx4& rsrc, unsigned lds_base, int
                : "memory", "m0");
 }
 
+// The same with 4 bytes per lane: lane l's dword lands at lds_base + 4*l.
+__device__ __forceinline__ void dma4(const uintx4& rsrc, unsigned lds_base, int voffset,
+                                     int soffset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+               :
+               : "s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset)
+               : "memory", "m0");
+}
+
+// ADDR: how the gathered A rows are addressed.
+//   kUniform  a slice lies inside one tap (C a multiple of the slice width, at
+//             most 31 taps): scalar tap offset + per-row tap masks, 16-byte loads
+//   kVector   any C that is a multiple of the 16-byte vector: (r,s,c) per lane
+//   kElement  any C (fp32 only): 4-byte loads, (r,s,c) per lane and element
+constexpr int kUniform = 0, kVector = 1, kElement = 2;
+
 template <bool BF16_, int BM_, int BN_, int ROWB_, int WAVES_M_, int WAVES_N_, int STAGES_,
-          bool TWO_LEVEL_, int OCC_, bool UNIFORM_>
+          bool TWO_LEVEL_, int OCC_, int ADDR_>
 struct DmaTile {
   static constexpr bool BF16 = BF16_;
   static constexpr int BM = BM_, BN = BN_;
@@ -116,7 +132,9 @@ struct DmaTile {
   static constexpr int STAGES = STAGES_;
   static constexpr bool TWO_LEVEL = TWO_LEVEL_;  // see igemm.hip: two-level fp32 summation
   static constexpr int OCC = OCC_;
-  static constexpr bool UNIFORM = UNIFORM_;      // a slice never straddles two taps
+  static constexpr int ADDR = ADDR_;
+  static constexpr bool UNIFORM = ADDR_ == kUniform;  // a slice never straddles two taps
+  static constexpr bool ELEMENT = ADDR_ == kElement;  // A gathered element by element
   static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int NW = WAVES_M * WAVES_N;
   static constexpr int NT = 64 * NW;
@@ -127,7 +145,10 @@ struct DmaTile {
   static constexpr int NR = TM + TN;             // fragment reads per step
   static constexpr int ROWS_PER_INSTR = 64 / CPR;
   static constexpr int ROWS_PER_PASS = NT / CPR;
-  static constexpr int A_ITERS = BM / ROWS_PER_PASS;
+  static constexpr int A_VEC = ELEMENT ? 1 : VEC;          // elements per A load
+  static constexpr int A_LPR = (ROWB / ES) / A_VEC;        // A loads per row
+  static constexpr int A_ROWS_PER_PASS = NT / A_LPR;
+  static constexpr int A_ITERS = BM / A_ROWS_PER_PASS;
   static constexpr int B_ITERS = BN / ROWS_PER_PASS;
   static constexpr int LOADS = A_ITERS + B_ITERS;  // load instructions per slice per lane
   static constexpr int STAGE_BYTES = (BM + BN) * ROWB;
@@ -137,7 +158,9 @@ struct DmaTile {
   static_assert(KSTEPS % 2 == 0, "fragment double buffering needs an even step count");
   static_assert(STAGES >= 2 && STAGES <= 8, "2 to 8 stages");
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of 32x32");
-  static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "tile rows must divide");
+  static_assert(BM % A_ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "tile rows must divide");
+  static_assert(A_ROWS_PER_PASS % 16 == 0, "the swizzle must be the same for all rows of a lane");
+  static_assert(!(ELEMENT && BF16), "element-wise gathers are fp32 only");
   static_assert(ROWS_PER_PASS % 16 == 0, "the swizzle must be the same for all rows of a lane");
   static_assert(WAIT_FIRST <= 63, "vmcnt has 6 bits");
   static_assert(STAGES * STAGE_BYTES <= 160 * 1024, "stages do not fit LDS");
@@ -214,7 +237,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   constexpr int BM = T::BM, BN = T::BN, BK = T::BK, S = T::STAGES, ROWB = T::ROWB, CPR = T::CPR;
   constexpr int ES = T::ES, VEC = T::VEC, KSTEPS = T::KSTEPS;
   constexpr int TM = T::TM, TN = T::TN, NM = T::NM, NR = T::NR, MPF = T::MPF;
-  constexpr bool UNIFORM = T::UNIFORM;
+  constexpr bool UNIFORM = T::UNIFORM, ELEMENT = T::ELEMENT;
   // stage s: [BM rows of A | BN rows of B], ROWB bytes per row
   __shared__ __align__(1024) unsigned char ring[S * T::STAGE_BYTES];
 
@@ -230,6 +253,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   const int nslices_all = Kg_p / BK;
   const bool is_tail = static_cast<int>(blockIdx.x) >= tail.n_main;
   const unsigned ring_base = __builtin_amdgcn_readfirstlane(lds_address(ring) + wave * 1024);
+  const unsigned ring_base_elt = __builtin_amdgcn_readfirstlane(lds_address(ring) + wave * 256);
 
   int tile, slice_begin, nslices;
   if (!is_tail) {
@@ -271,6 +295,13 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   const int ld_row0 = tid / CPR;
   const int ld_pos = tid % CPR;
   const int ld_chunk = ld_pos ^ ((ld_row0 >> 1) & (CPR - 1));
+  // A loads of ELEMENT tiles move one element per lane: row tid / A_LPR,
+  // element position tid % A_LPR inside the LDS row, memory element =
+  // (chunk position ^ swizzle) * VEC + element within the chunk
+  const int a_row0 = ELEMENT ? tid / T::A_LPR : ld_row0;
+  const int a_k0 = ELEMENT ? ((((tid % T::A_LPR) / VEC) ^ ((a_row0 >> 1) & (CPR - 1))) * VEC +
+                              (tid % T::A_LPR) % VEC)
+                           : ld_chunk * VEC;
   // UNIFORM: byte offset of the row's window origin (+ shift, + this lane's
   // chunk); otherwise the element offset of the window origin
   int a_off[T::A_ITERS];
@@ -278,7 +309,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   unsigned a_mask[UNIFORM ? T::A_ITERS : 1];  // bit r*S+s: tap (r,s) of the row lies inside the image
 #pragma unroll
   for (int i = 0; i < T::A_ITERS; ++i) {
-    const int m = m0 + ld_row0 + i * T::ROWS_PER_PASS;
+    const int m = m0 + a_row0 + i * T::A_ROWS_PER_PASS;
     const bool row_ok = m < p.M;
     const int mm = row_ok ? m : 0;
     const int q = mm % p.Q;
@@ -314,7 +345,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   int kc, ks, kr;
   int tap_bit = 0, tap_idx = 0, tap_c = 0, tap_s = 0, tap_rowoff = 0;  // UNIFORM
   {
-    const int kg = slice_begin * BK + (UNIFORM ? 0 : ld_chunk * VEC);
+    const int kg = slice_begin * BK + (UNIFORM ? 0 : a_k0);
     kc = kg % p.C;
     const int t = kg / p.C;
     ks = t % p.S;
@@ -343,7 +374,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
 
   // One A load (row pass i) of the slice at the current position into `stage`.
   auto load_a = [&](int stage, int i) {
-    const unsigned dst = ring_base + stage * T::STAGE_BYTES + i * T::ROWS_PER_PASS * ROWB;
+    // a wave's load fills 1 KiB (16-byte loads) or 256 bytes (4-byte loads) of the stage
+    const unsigned dst = (ELEMENT ? ring_base_elt : ring_base) + stage * T::STAGE_BYTES +
+                         i * T::A_ROWS_PER_PASS * ROWB;
     if constexpr (UNIFORM) {
       const bool ok = (a_mask[i] >> tap_bit) & 1u;
       const int soff = (tap_rowoff + tap_s * p.C + tap_c) * ES;
@@ -353,7 +386,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
       const int kr_t = (kr < p.R) ? kr : (1 << 30);
       const bool ok = (static_cast<unsigned>(a_h0[i] + kr_t) < static_cast<unsigned>(p.H)) &
                       (static_cast<unsigned>(a_w0[i] + ks) < static_cast<unsigned>(p.W));
-      dma16(in_rsrc, dst, ok ? (a_off[i] + tap) * ES : kOutOfRange, 0);
+      if constexpr (T::ELEMENT)
+        dma4(in_rsrc, dst, ok ? (a_off[i] + tap) * ES : kOutOfRange, 0);
+      else
+        dma16(in_rsrc, dst, ok ? (a_off[i] + tap) * ES : kOutOfRange, 0);
     }
   };
   auto load_b = [&](int stage, int i) {
@@ -729,39 +765,41 @@ size_t workspace_bytes(const Problem& p, int splits) {
 struct TileEntry {
   const char* name;
   int bm, bn, bk, occ;
-  bool uniform;
+  int addr;
   hipError_t (*fn)(const Problem&, int, hipStream_t);
   size_t (*ws)(const Problem&, int);
 };
 
-#define CONV2D_DMA_TILE(dt, isbf, bm, bn, rowb, wm, wn, st, two, occ, uni, tag)                 \
+#define CONV2D_DMA_TILE(dt, isbf, bm, bn, rowb, wm, wn, st, two, occ, addr, tag)                \
   { "igemm_dma_" dt "_" #bm "x" #bn "_r" #rowb "_w" #wm "x" #wn "_s" #st tag, bm, bn,           \
-    DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, uni>::BK, occ, uni,                       \
-    &launch<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, uni>>,                            \
-    &workspace_bytes<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, uni>> }
+    DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>::BK, occ, addr,                     \
+    &launch<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>>,                           \
+    &workspace_bytes<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>> }
 
 const TileEntry kTilesF32[] = {
-    CONV2D_DMA_TILE("f32", false, 128, 128, 64, 2, 2, 4, true, 2, true, ""),
-    CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, true, ""),
-    CONV2D_DMA_TILE("f32", false, 256, 128, 64, 4, 2, 4, true, 2, true, ""),
-    CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 4, true, 4, true, ""),
-    CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 3, true, 6, true, ""),
-    CONV2D_DMA_TILE("f32", false, 128, 128, 64, 2, 2, 4, true, 2, false, "_g"),
-    CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, false, "_g"),
-    CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 4, true, 4, false, "_g"),
+    CONV2D_DMA_TILE("f32", false, 128, 128, 64, 2, 2, 4, true, 2, kUniform, ""),
+    CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, kUniform, ""),
+    CONV2D_DMA_TILE("f32", false, 256, 128, 64, 4, 2, 4, true, 2, kUniform, ""),
+    CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 4, true, 4, kUniform, ""),
+    CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 3, true, 6, kUniform, ""),
+    CONV2D_DMA_TILE("f32", false, 128, 128, 64, 2, 2, 4, true, 2, kVector, "_g"),
+    CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, kVector, "_g"),
+    CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 4, true, 4, kVector, "_g"),
+    CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, kElement, "_e"),
+    CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 4, true, 4, kElement, "_e"),
 };
 const TileEntry kTilesBf16[] = {
-    CONV2D_DMA_TILE("bf16", true, 256, 256, 64, 4, 2, 4, false, 1, true, ""),
-    CONV2D_DMA_TILE("bf16", true, 256, 256, 128, 4, 2, 2, false, 1, true, ""),
-    CONV2D_DMA_TILE("bf16", true, 256, 128, 64, 4, 2, 4, false, 1, true, ""),
-    CONV2D_DMA_TILE("bf16", true, 256, 128, 64, 4, 2, 3, false, 2, true, ""),
-    CONV2D_DMA_TILE("bf16", true, 128, 128, 64, 2, 2, 4, false, 2, true, ""),
-    CONV2D_DMA_TILE("bf16", true, 128, 64, 64, 2, 2, 4, false, 3, true, ""),
-    CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 4, false, 4, true, ""),
-    CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 3, false, 6, true, ""),
-    CONV2D_DMA_TILE("bf16", true, 128, 128, 64, 2, 2, 4, false, 2, false, "_g"),
-    CONV2D_DMA_TILE("bf16", true, 128, 64, 64, 2, 2, 4, false, 3, false, "_g"),
-    CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 4, false, 4, false, "_g"),
+    CONV2D_DMA_TILE("bf16", true, 256, 256, 64, 4, 2, 4, false, 1, kUniform, ""),
+    CONV2D_DMA_TILE("bf16", true, 256, 256, 128, 4, 2, 2, false, 1, kUniform, ""),
+    CONV2D_DMA_TILE("bf16", true, 256, 128, 64, 4, 2, 4, false, 1, kUniform, ""),
+    CONV2D_DMA_TILE("bf16", true, 256, 128, 64, 4, 2, 3, false, 2, kUniform, ""),
+    CONV2D_DMA_TILE("bf16", true, 128, 128, 64, 2, 2, 4, false, 2, kUniform, ""),
+    CONV2D_DMA_TILE("bf16", true, 128, 64, 64, 2, 2, 4, false, 3, kUniform, ""),
+    CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 4, false, 4, kUniform, ""),
+    CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 3, false, 6, kUniform, ""),
+    CONV2D_DMA_TILE("bf16", true, 128, 128, 64, 2, 2, 4, false, 2, kVector, "_g"),
+    CONV2D_DMA_TILE("bf16", true, 128, 64, 64, 2, 2, 4, false, 3, kVector, "_g"),
+    CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 4, false, 4, kVector, "_g"),
 };
 constexpr int kNumF32 = sizeof(kTilesF32) / sizeof(kTilesF32[0]);
 constexpr int kNumBf16 = sizeof(kTilesBf16) / sizeof(kTilesBf16[0]);
@@ -780,7 +818,7 @@ void igemm_dma_tile_shape(int bf16, int tile, int* bm, int* bn, int* bk) {
   *bk = t.bk;
 }
 int igemm_dma_tile_occupancy(int bf16, int tile) { return entry(bf16, tile).occ; }
-bool igemm_dma_tile_is_uniform(int bf16, int tile) { return entry(bf16, tile).uniform; }
+int igemm_dma_tile_addressing(int bf16, int tile) { return entry(bf16, tile).addr; }
 size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile, int splits) {
   return entry(bf16, tile).ws(p, splits);
 }

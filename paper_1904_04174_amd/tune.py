@@ -48,12 +48,14 @@ def time_variant(torch, layer, in_dtype, variant_id, iters, warmup=2):
 
 def candidates(params):
     names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
+    def elementwise(n):
+        return "scalar" in n or n.endswith("_e") or "_e_" in n
     vec_ok = any(B.conv2d_variant_supports(params, v) for v, n in enumerate(names)
-                 if n != "direct" and "scalar" not in n)
+                 if n != "direct" and not elementwise(n))
     for v, n in enumerate(names):
         if n == "direct" or not B.conv2d_variant_supports(params, v):
             continue
-        if "scalar" in n and vec_ok:
+        if elementwise(n) and vec_ok:
             continue   # element-wise tiles only where the vector tiles cannot run
         if B.conv2d_workspace_size(params, v) > MAX_WORKSPACE:
             continue

@@ -215,7 +215,7 @@ def test_unaligned_pointers_take_the_element_wise_path(torch_cuda, oracle):
         rc = B.conv2d_forward_raw(p, xd.data_ptr(), fd.data_ptr(), out.data_ptr(), ws.data_ptr(),
                                   ws.numel(), 0, v)
         torch.cuda.synchronize()
-        if name == "direct" or "scalar" in name:
+        if name == "direct" or "scalar" in name or name.endswith("_e") or "_e_" in name:
             assert rc == B.STATUS_OK, name
             assert rel_err(out.cpu().numpy(), want) <= TOL_F32, name
         else:
