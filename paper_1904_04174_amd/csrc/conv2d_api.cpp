@@ -166,6 +166,9 @@ bool supports(const Variant& v, const Problem& q) {
   if ((!is_scalar(v) && q.C % vec != 0) || 1LL * es * (q.Kg + bk) * q.K >= (1LL << 31)) return false;
   if (1LL * es * (1LL * q.N * q.H * q.W + 1LL * q.R * q.W + q.S) * q.C >= (1LL << 31)) return false;
   if (igemm_dma_tile_addressing(v.bf16, v.tile) == 0 && (q.C % bk != 0 || q.R * q.S > 31)) return false;
+  if (igemm_dma_tile_addressing(v.bf16, v.tile) == 3 &&
+      (v.split != kWhole || !igemm_dma_tile_fits(q, v.bf16, v.tile)))
+    return false;
   if (v.split == kSplit && (q.Kg + bk - 1) / bk < 2) return false;
   // a balanced tail needs tiles left over after whole rounds of the 256 compute units
   if (v.split == kTail && (ceil_div_ll(q.M, bm) * ceil_div_ll(q.K, bn)) % 256 == 0) return false;

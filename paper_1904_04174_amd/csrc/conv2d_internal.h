@@ -57,12 +57,15 @@ constexpr int kTailBalanced = -1;
 // the fp32 partial outputs.  Addressing kinds of a tile: 0 = "uniform" (C a
 // multiple of the tile's bk and a window of at most 31 taps), 1 = vector (C a
 // multiple of the 16-byte vector), 2 = element-wise (fp32, any C and K, any
-// 4-byte alignment of input, filter and output).
+// 4-byte alignment of input, filter and output), 3 = LDS-resident input
+// patch (3x3 window, stride 1, C a multiple of bk, tiles whose patch fits;
+// whole tiles only).
 int igemm_dma_num_tiles(int bf16);
 const char* igemm_dma_tile_name(int bf16, int tile);
 void igemm_dma_tile_shape(int bf16, int tile, int* bm, int* bn, int* bk);
 int igemm_dma_tile_occupancy(int bf16, int tile);
 int igemm_dma_tile_addressing(int bf16, int tile);
+bool igemm_dma_tile_fits(const Problem& p, int bf16, int tile);  // extra shape condition (kind 3)
 size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile, int splits);
 hipError_t launch_igemm_dma(const Problem& p, int bf16, int tile, int splits, hipStream_t stream);
 

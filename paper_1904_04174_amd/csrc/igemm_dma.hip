@@ -153,7 +153,8 @@ struct DmaTile {
   static constexpr int LOADS = A_ITERS + B_ITERS;  // load instructions per slice per lane
   static constexpr int STAGE_BYTES = (BM + BN) * ROWB;
   static constexpr int WAIT_STEADY = (STAGES - 2) * LOADS;  // loads that may stay in flight
-  static constexpr int WAIT_FIRST = (STAGES - 1) * LOADS;
+  // after the prologue: slices 1 .. S-2 and the first share of slice S-1
+  static constexpr int WAIT_FIRST = (STAGES - 2) * LOADS + LOADS / KSTEPS;
   static_assert(ROWB == 64 || ROWB == 128, "64 or 128 bytes per row");
   static_assert(KSTEPS % 2 == 0, "fragment double buffering needs an even step count");
   static_assert(STAGES >= 2 && STAGES <= 8, "2 to 8 stages");
@@ -483,14 +484,26 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   using Buf1 = std::integral_constant<int, 1>;
 
   // One fragment step: NM MFMAs with the side work dealt out between them.
-  // Side work of an ordinary step: the NR fragment reads of the next step.
+  // The loads of slice i+S may start once the barrier in the last step of
+  // slice i has released that slice's stage, and must all be out before the
+  // barrier of slice i+1: they are dealt over the KSTEPS steps in between
+  // (load number l in step l * KSTEPS / LOADS of that period), because a
+  // burst of them right after the barrier backs up the load unit and stalls
+  // the wave's MFMA issue behind it.
   // Side work of the last step of a slice: wait + barrier, the NR reads of
-  // the next slice's first step, the LOADS loads of slice i+S, advance.
-  // Side items start after the first MFMA and are spaced so that all of them
-  // are out well before the step ends.
-  auto step = [&](auto cur_c, auto nxt_c, int stage, int kk, int stage_next, int stage_load) {
+  // the next slice's first step, the first share of the loads of slice i+S.
+  // Side work of any other step kk of slice i+1: the NR reads of its next
+  // step and share kk+1 of those loads (into the stage of slice i); the
+  // load position advances after the last share.
+  auto load_one = [&](int stage, int l) {
+    if (l < T::A_ITERS) load_a(stage, l); else load_b(stage, l - T::A_ITERS);
+  };
+  auto step = [&](auto cur_c, auto nxt_c, int stage, int kk, int stage_next, int stage_prev) {
     const bool last = kk == KSTEPS - 1;
-    const int nside = last ? 1 + NR + T::LOADS + 1 : NR;
+    const int share = last ? 0 : kk + 1;                      // which share of the loads
+    const int l0 = share * T::LOADS / KSTEPS, l1 = (share + 1) * T::LOADS / KSTEPS;
+    const bool adv = share == KSTEPS - 1;
+    const int nside = (last ? 1 : 0) + NR + (l1 - l0) + (adv ? 1 : 0);
     const int room = NM > 3 ? NM - 2 : NM;           // MFMA gaps that take side work
     const int per_gap = (nside + room - 1) / room;   // side items per gap
     int item = 0;
@@ -499,24 +512,21 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
       mfma(cur_c, m);
 #pragma unroll
       for (int g = 0; g < per_gap; ++g, ++item) {
+        const int it = last ? item - 1 : item;       // item number after the barrier
         if (item >= nside) {
           // nothing left for this gap
-        } else if (!last) {
-          read_frag(nxt_c, stage, kk + 1, item);
-        } else if (item == 0) {
+        } else if (last && item == 0) {
           // next step belongs to the next slice: its loads must have landed
           // (this lane's: vmcnt; everyone's: barrier), and the barrier also
           // says that every wave's reads of this slice's stage are complete
-          // (lgkmcnt), so the loads below may overwrite it
+          // (lgkmcnt), so the loads that follow may overwrite it
           __builtin_amdgcn_s_waitcnt(vmcnt_lds_imm(T::WAIT_STEADY));
           __builtin_amdgcn_s_barrier();
           asm volatile("" ::: "memory");  // LDS changed behind the compiler's back
-        } else if (item <= NR) {
-          read_frag(nxt_c, stage_next, 0, item - 1);
-        } else if (item <= NR + T::A_ITERS) {
-          load_a(stage_load, item - NR - 1);
-        } else if (item <= NR + T::LOADS) {
-          load_b(stage_load, item - NR - T::A_ITERS - 1);
+        } else if (it < NR) {
+          if (last) read_frag(nxt_c, stage_next, 0, it); else read_frag(nxt_c, stage, kk + 1, it);
+        } else if (it < NR + (l1 - l0)) {
+          load_one(last ? stage : stage_prev, l0 + it - NR);
         } else {
           advance();
         }
@@ -525,14 +535,14 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
     }
   };
 
-  // prologue: slices 0 .. S-1 in flight, slice 0 landed, its first fragments read
+  // prologue: slices 0 .. S-2 and the first share of slice S-1 in flight
+  // (the steps of slice 0 issue its other shares), slice 0 landed, its first
+  // fragments read
 #pragma unroll
   for (int s = 0; s < S; ++s) {
 #pragma unroll
-    for (int i = 0; i < T::A_ITERS; ++i) load_a(s, i);
-#pragma unroll
-    for (int i = 0; i < T::B_ITERS; ++i) load_b(s, i);
-    advance();
+    for (int l = 0; l < (s < S - 1 ? T::LOADS : T::LOADS / KSTEPS); ++l) load_one(s, l);
+    if (s < S - 1) advance();
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(T::WAIT_FIRST));
   __builtin_amdgcn_s_barrier();
@@ -550,9 +560,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
           // KSTEPS is even: step kk uses fragment buffer kk % 2, and the first
           // step of the next slice uses buffer 0 again
           if (kk % 2 == 0)
-            step(Buf0{}, Buf1{}, u, kk, (u + 1) % S, u);
+            step(Buf0{}, Buf1{}, u, kk, (u + 1) % S, (u + S - 1) % S);
           else
-            step(Buf1{}, Buf0{}, u, kk, (u + 1) % S, u);
+            step(Buf1{}, Buf0{}, u, kk, (u + 1) % S, (u + S - 1) % S);
         }
         if (T::TWO_LEVEL) {
           if (--until_flush == 0) {
@@ -762,21 +772,424 @@ size_t workspace_bytes(const Problem& p, int splits) {
          (splits > 1 ? static_cast<size_t>(splits) * p.M * p.K * sizeof(float) : 0);
 }
 
+// ---------------------------------------------------------------------------
+// LDS-resident input patch for 3x3 (any R x S), stride-1 layers.
+//
+// The gather kernel above fetches every input element once per tap: nine
+// times for a 3x3 window, and at 64 bytes per pixel row per slice that
+// request stream, not the matrix cores, is what bounds the bf16 tiles (the L2
+// of an XCD is ~83 % busy).  Here a workgroup loads, per block of BK
+// channels, the whole patch of input pixels that its BM consecutive output
+// pixels touch, once, and the MFMA fragment reads of all R*S taps address
+// into it: with the input laid out as a zero-padded image of width
+// Wp = W + pad_left + pad_right, output pixel m with window origin index
+// base(m) = (n*Hp + p)*Wp + q reads, for tap (r,s), patch entry
+// base(m) + r*Wp + s.  The patch of a tile is the contiguous range of such
+// indices from base(m0) on; entries that fall into the padding frame (or
+// past the last image) are loaded with an out-of-range offset and read zero.
+//
+// LDS layout of a patch: CPR planes of PATCH_ROWS x 16 bytes (plane c holds
+// 16-byte chunk c of every entry), so one load instruction fills 64
+// consecutive entries of a plane and a fragment read (32 consecutive entries
+// of one plane per lane half) is conflict free without a swizzle.  Two patch
+// buffers alternate between channel blocks; the filter slices go through a
+// three-stage ring exactly as above (same repacked, channel-block-major
+// filter).  The nine taps of a 3x3 window are unrolled, one barrier per tap
+// slice; the patch of the next channel block is loaded during the first six
+// tap slices of the current one.
+template <bool BF16_, int BM_, int BN_, int WAVES_M_, int WAVES_N_, int PATCH_ROWS_,
+          bool TWO_LEVEL_, int OCC_>
+struct PatchTile {
+  static constexpr bool BF16 = BF16_;
+  static constexpr int BM = BM_, BN = BN_;
+  static constexpr int ROWB = 64, CPR = 4, KSTEPS = 2;
+  static constexpr int ES = BF16 ? 2 : 4;
+  static constexpr int VEC = 16 / ES;
+  static constexpr int BK = ROWB / ES;
+  static constexpr int SB = 3;                   // filter ring stages
+  static constexpr bool TWO_LEVEL = TWO_LEVEL_;
+  static constexpr int OCC = OCC_;
+  static constexpr int ADDR = 3;
+  static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+  static constexpr int NW = WAVES_M * WAVES_N;
+  static constexpr int NT = 64 * NW;
+  static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  static constexpr int TM = WM / 32, TN = WN / 32;
+  static constexpr int MPF = BF16 ? 1 : 4;
+  static constexpr int NM = TM * TN * MPF;
+  static constexpr int NR = TM + TN;
+  static constexpr int PATCH_ROWS = PATCH_ROWS_;
+  static constexpr int PLANE_BYTES = PATCH_ROWS * 16;
+  static constexpr int PATCH_BYTES = CPR * PLANE_BYTES;
+  static constexpr int A_PASSES = PATCH_ROWS / (64 * NW);
+  static constexpr int A_LOADS = A_PASSES * CPR;  // patch loads per lane per channel block
+  static constexpr int A_SLICES = 6;              // dealt over the first 6 tap slices of a block
+  static constexpr int B_ROWS_PER_PASS = NT / CPR;
+  static constexpr int B_ITERS = BN / B_ROWS_PER_PASS;
+  static constexpr int B_STAGE_BYTES = BN * ROWB;
+  static constexpr int LDS_BYTES = 2 * PATCH_BYTES + SB * B_STAGE_BYTES;
+  static_assert(PATCH_ROWS % (64 * NW) == 0, "patch rows must divide over the waves");
+  static_assert(BN % B_ROWS_PER_PASS == 0 && B_ROWS_PER_PASS % 16 == 0, "filter tile rows");
+  static_assert(LDS_BYTES <= 160 * 1024, "does not fit LDS");
+  static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of 32x32");
+  static_assert(!(BF16 && TWO_LEVEL), "two-level summation is an fp32 feature");
+  // patch loads issued at the end of tap slice t of a block
+  static constexpr int a_first(int t) { return t >= A_SLICES ? A_LOADS : t * A_LOADS / A_SLICES; }
+  static constexpr int a_count(int t) { return t < 0 ? 0 : a_first(t + 1) - a_first(t); }
+};
+
+// Patch entries that the tile starting at output pixel m0 needs.
+__host__ __device__ inline long long patch_base(const Problem& p, int Hp, int Wp, int m) {
+  const int q = m % p.Q, t = m / p.Q;
+  return (1LL * (t / p.P) * Hp + t % p.P) * Wp + q;
+}
+
+template <class T, bool OUT_BF16>
+__global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Problem p, const int Hp,
+                                                                    const int Wp,
+                                                                    const int flush_slices,
+                                                                    const void* bt) {
+  constexpr int BM = T::BM, BN = T::BN, BK = T::BK, ROWB = T::ROWB, CPR = T::CPR, SB = T::SB;
+  constexpr int ES = T::ES, VEC = T::VEC, KSTEPS = T::KSTEPS;
+  constexpr int TM = T::TM, TN = T::TN, NM = T::NM, NR = T::NR, MPF = T::MPF;
+  __shared__ __align__(1024) unsigned char ring[T::LDS_BYTES];
+  constexpr int B_REGION = 2 * T::PATCH_BYTES;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave / T::WAVES_N;
+  const int wn = wave % T::WAVES_N;
+  const int lr = lane & 31;
+  const int lk = lane >> 5;
+
+  const int tiles_n = (p.K + BN - 1) / BN;
+  const int nwg = gridDim.x;
+  const int xcd = blockIdx.x % kXcds;
+  const int local = blockIdx.x / kXcds;
+  const int per = nwg / kXcds, rem = nwg % kXcds;
+  const int tile = xcd * per + (xcd < rem ? xcd : rem) + local;
+  const int m0 = (tile / tiles_n) * BM;
+  const int n0 = (tile % tiles_n) * BN;
+  constexpr int taps = 9;
+  const int nblocks = p.C / BK;      // channel blocks
+  const int Kg_p = p.Kg;             // C is a multiple of BK
+
+  const uintx4 in_rsrc = make_rsrc(p.in, 0, p.N * p.H * p.W * p.C * ES);
+  const uintx4 bt_rsrc = make_rsrc(bt, 0, p.K * Kg_p * ES);
+  const unsigned ring_base = __builtin_amdgcn_readfirstlane(lds_address(ring) + wave * 1024);
+
+  // ---- patch loader role: entries (pass*NW + wave)*64 + lane of the patch
+  const long long v0 = patch_base(p, Hp, Wp, m0);
+  int a_voff[T::A_PASSES];
+#pragma unroll
+  for (int i = 0; i < T::A_PASSES; ++i) {
+    const long long v = v0 + (i * T::NW + wave) * 64 + lane;
+    const int w = static_cast<int>(v % Wp) - p.pl;
+    const long long t = v / Wp;
+    const int h = static_cast<int>(t % Hp) - p.pt;
+    const long long n = t / Hp;
+    const bool ok = n < p.N && static_cast<unsigned>(h) < static_cast<unsigned>(p.H) &&
+                    static_cast<unsigned>(w) < static_cast<unsigned>(p.W);
+    a_voff[i] = ok ? static_cast<int>(((n * p.H + h) * p.W + w) * p.C * ES) : kOutOfRange;
+  }
+  // ---- filter loader role (as in the gather kernel)
+  const int ld_row0 = tid / CPR;
+  const int ld_chunk = (tid % CPR) ^ ((ld_row0 >> 1) & (CPR - 1));
+  int b_voff[T::B_ITERS];
+#pragma unroll
+  for (int i = 0; i < T::B_ITERS; ++i) {
+    const int n = n0 + ld_row0 + i * T::B_ROWS_PER_PASS;
+    b_voff[i] = (n < p.K) ? (n * BK + ld_chunk * VEC) * ES : kOutOfRange;
+  }
+  const int k_slice_bytes = p.K * ROWB;
+  const int k_last_bytes = (nblocks * taps - 1) * k_slice_bytes;
+  int k_next_bytes = 0;
+  int a_next_block_bytes = 0;   // channel offset (bytes) of the patch being loaded
+  const int a_last_block_bytes = (nblocks - 1) * ROWB;
+
+  auto load_b = [&](int stage, int i) {
+    dma16(bt_rsrc, ring_base + B_REGION + stage * T::B_STAGE_BYTES + i * T::B_ROWS_PER_PASS * ROWB,
+          b_voff[i], k_next_bytes);
+  };
+  // patch load number j (pass j / CPR, plane j % CPR) into patch buffer `buf`
+  auto load_a = [&](int buf, int j) {
+    const int i = j / CPR, c = j % CPR;
+    dma16(in_rsrc, ring_base + buf * T::PATCH_BYTES + c * T::PLANE_BYTES + i * T::NW * 1024,
+          a_voff[i], a_next_block_bytes + c * 16);
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  floatx16 total[T::TWO_LEVEL ? TM : 1][T::TWO_LEVEL ? TN : 1];
+  if (T::TWO_LEVEL) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) total[i][j][v] = 0.f;
+  }
+  int until_flush = flush_slices;
+
+  // ---- fragment addressing.  A: patch entry of the lane's output pixel in
+  // each 32-row block (pixels past M repeat the last one; they are not
+  // stored), plane lk (+2 per step).  B: as in the gather kernel.
+  int a_frag[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = min(m0 + wm * T::WM + i * 32 + lr, p.M - 1);
+    a_frag[i] = static_cast<int>(patch_base(p, Hp, Wp, m) - v0) * 16 + lk * T::PLANE_BYTES;
+  }
+  const int frag_swz = (lr >> 1) & (CPR - 1);
+  const unsigned char* b_frag = ring + B_REGION + (wn * T::WN + lr) * ROWB;
+  int chunk_bytes[KSTEPS];
+#pragma unroll
+  for (int kk = 0; kk < KSTEPS; ++kk) chunk_bytes[kk] = ((2 * kk + lk) ^ frag_swz) * 16;
+
+  uintx4 af[2][TM], bf[2][TN];
+  int a_buf_off = 0;  // byte offset of the patch buffer being read (0 or PATCH_BYTES)
+
+  // Fragment read r (A blocks, then B blocks) of step kk; A from the patch at
+  // byte offset a_off (buffer + tap), B from filter stage `bstage`.
+  auto read_frag = [&](auto buf_c, int a_off, int bstage, int kk, int r) {
+    constexpr int buf = decltype(buf_c)::value;
+    if (r < TM)
+      af[buf][r] = *reinterpret_cast<const uintx4*>(ring + a_frag[r] + a_off +
+                                                    2 * kk * T::PLANE_BYTES);
+    else
+      bf[buf][r - TM] = *reinterpret_cast<const uintx4*>(
+          b_frag + bstage * T::B_STAGE_BYTES + (r - TM) * 32 * ROWB + chunk_bytes[kk]);
+  };
+  auto mfma = [&](auto buf_c, int m) {
+    constexpr int buf = decltype(buf_c)::value;
+    const int i = m / (TN * MPF), j = (m / MPF) % TN, t = m % MPF;
+    if constexpr (T::BF16) {
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+          __builtin_bit_cast(bf16x8, af[buf][i]), __builtin_bit_cast(bf16x8, bf[buf][j]), acc[i][j],
+          0, 0, 0);
+    } else {
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(af[buf][i][t]),
+                                                       __uint_as_float(bf[buf][j][t]), acc[i][j],
+                                                       0, 0, 0);
+    }
+  };
+  using Buf0 = std::integral_constant<int, 0>;
+  using Buf1 = std::integral_constant<int, 1>;
+  // NM MFMAs of one step with `nside` side items dealt out between them
+  // (pinned by scheduling fences, none after the last two MFMAs).
+  auto run_step = [&](auto cur_c, int nside, auto side) {
+    const int room = NM > 3 ? NM - 2 : NM;
+    const int per_gap = (nside + room - 1) / room;
+    int item = 0;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      mfma(cur_c, m);
+#pragma unroll
+      for (int g = 0; g < per_gap; ++g, ++item)
+        if (item < nside) side(item);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  // Tap slice t of a channel block: filter stage t % SB.  Step 0 reads the
+  // fragments of step 1.  Step 1: wait for the next slice's filter tile (and
+  // this wave's LDS reads), barrier, read the next slice's first fragments,
+  // load the filter slice SB ahead into the stage just released, and this
+  // slice's share of the next block's patch.
+  auto tap_slice = [&](auto t_c) {
+    constexpr int t = decltype(t_c)::value;
+    constexpr int bstage = t % SB;
+    constexpr int tn = (t + 1) % taps;
+    const int a_cur = a_buf_off + ((t / 3) * Wp + t % 3) * 16;
+    const int a_nxt = (t == taps - 1 ? (a_buf_off ^ T::PATCH_BYTES) : a_buf_off) +
+                      ((tn / 3) * Wp + tn % 3) * 16;
+    const int a_load_buf = (a_buf_off ^ T::PATCH_BYTES) / T::PATCH_BYTES;
+    constexpr int a_from = T::a_first(t), a_n = T::a_count(t);
+    // loads younger than the next slice's filter tile: the filter tile after
+    // it and the patch loads of the two slices before this one
+    constexpr int wait_n = T::B_ITERS + T::a_count(t - 2) + T::a_count(t - 1);
+    run_step(Buf0{}, NR, [&](int item) { read_frag(Buf1{}, a_cur, bstage, 1, item); });
+    run_step(Buf1{}, 1 + NR + T::B_ITERS + a_n + 1, [&](int item) {
+      if (item == 0) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_lds_imm(wait_n));
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");  // LDS changed behind the compiler's back
+      } else if (item <= NR) {
+        read_frag(Buf0{}, a_nxt, (bstage + 1) % SB, 0, item - 1);
+      } else if (item <= NR + T::B_ITERS) {
+        load_b(bstage, item - NR - 1);
+      } else if (item <= NR + T::B_ITERS + a_n) {
+        load_a(a_load_buf, a_from + item - NR - T::B_ITERS - 1);
+      } else {
+        k_next_bytes = min(k_next_bytes + k_slice_bytes, k_last_bytes);
+      }
+    });
+    if (T::TWO_LEVEL) {
+      if (--until_flush == 0) {
+        until_flush = flush_slices;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              total[i][j][v] += acc[i][j][v];
+              acc[i][j][v] = 0.f;
+            }
+      }
+    }
+  };
+
+  // prologue: the first block's patch and the first SB filter slices in
+  // flight; patch and slice 0 landed; first fragments read
+#pragma unroll
+  for (int j = 0; j < T::A_LOADS; ++j) load_a(0, j);
+#pragma unroll
+  for (int s = 0; s < SB; ++s) {
+#pragma unroll
+    for (int i = 0; i < T::B_ITERS; ++i) load_b(s, i);
+    k_next_bytes = min(k_next_bytes + k_slice_bytes, k_last_bytes);
+  }
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm((SB - 1) * T::B_ITERS));
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+#pragma unroll
+  for (int r = 0; r < NR; ++r) read_frag(Buf0{}, 0, 0, 0, r);
+  __builtin_amdgcn_sched_barrier(0);
+
+  for (int block = 0; block < nblocks; ++block) {
+    // the patch loaded during this block is the next block's (past the end:
+    // the last one again, into the buffer nobody reads)
+    a_next_block_bytes = min((block + 1) * ROWB, a_last_block_bytes);
+    tap_slice(std::integral_constant<int, 0>{});
+    tap_slice(std::integral_constant<int, 1>{});
+    tap_slice(std::integral_constant<int, 2>{});
+    tap_slice(std::integral_constant<int, 3>{});
+    tap_slice(std::integral_constant<int, 4>{});
+    tap_slice(std::integral_constant<int, 5>{});
+    tap_slice(std::integral_constant<int, 6>{});
+    tap_slice(std::integral_constant<int, 7>{});
+    tap_slice(std::integral_constant<int, 8>{});
+    a_buf_off ^= T::PATCH_BYTES;
+  }
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // drain the loads issued past the end
+  if (T::TWO_LEVEL) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] += total[i][j][v];
+  }
+
+  // ---- epilogue (accumulator layout: lane l reg v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32)
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + wn * T::WN + j * 32 + lr;
+      const int rbase = m0 + wm * T::WM + i * 32 + lk * 4;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = rbase + 8 * (v / 4) + (v % 4);
+        if (row < p.M && col < p.K) {
+          const size_t idx = static_cast<size_t>(row) * p.K + col;
+          if (OUT_BF16)
+            static_cast<unsigned short*>(p.out)[idx] = to_bf16_bits(acc[i][j][v]);
+          else
+            static_cast<float*>(p.out)[idx] = acc[i][j][v];
+        }
+      }
+    }
+  }
+}
+
+// Largest number of patch entries any tile of the problem needs.
+template <class T>
+long long patch_rows_needed(const Problem& p) {
+  const int Hp = p.P + p.R - 1, Wp = p.Q + p.S - 1;  // stride 1: padded extent
+  long long worst = 0;
+  for (int m0 = 0; m0 < p.M; m0 += T::BM) {
+    const int m1 = (m0 + T::BM - 1 < p.M - 1) ? m0 + T::BM - 1 : p.M - 1;
+    const long long span = patch_base(p, Hp, Wp, m1) - patch_base(p, Hp, Wp, m0);
+    if (span > worst) worst = span;
+  }
+  return worst + 1LL * (p.R - 1) * Wp + (p.S - 1) + 1;
+}
+
+template <class T>
+bool patch_fits(const Problem& p) {
+  return p.R == 3 && p.S == 3 && p.sr == 1 && p.sc == 1 && p.C % T::BK == 0 &&
+         patch_rows_needed<T>(p) <= T::PATCH_ROWS;
+}
+
+template <class T, bool OUT_BF16>
+hipError_t launch_patch_one(const Problem& p, hipStream_t stream) {
+  // 1. filter -> Bt[slice][K][BK], channel block by channel block
+  dim3 rgrid((p.Kg + 31) / 32, (p.K + 31) / 32);
+  if (T::BF16)
+    hipLaunchKernelGGL((repack_filter_kernel<unsigned short>), rgrid, dim3(256), 0, stream,
+                       static_cast<const unsigned short*>(p.filt),
+                       static_cast<unsigned short*>(p.workspace), p.Kg, p.K, p.Kg, p.C,
+                       p.R * p.S, T::BK, T::BK);
+  else
+    hipLaunchKernelGGL((repack_filter_kernel<float>), rgrid, dim3(256), 0, stream,
+                       static_cast<const float*>(p.filt), static_cast<float*>(p.workspace), p.Kg,
+                       p.K, p.Kg, p.C, p.R * p.S, T::BK, T::BK);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // 2. the convolution
+  const int tiles = ((p.M + T::BM - 1) / T::BM) * ((p.K + T::BN - 1) / T::BN);
+  const int nslices = p.Kg / T::BK;
+  int flush = 1;
+  while (flush * flush < nslices) ++flush;
+  hipLaunchKernelGGL((igemm_patch_kernel<T, OUT_BF16>), dim3(tiles), dim3(T::NT), 0, stream, p,
+                     p.P + p.R - 1, p.Q + p.S - 1, flush, p.workspace);
+  return hipGetLastError();
+}
+
+template <class T>
+hipError_t launch_patch(const Problem& p, int, hipStream_t stream) {
+  if (!patch_fits<T>(p)) return hipErrorInvalidValue;
+  if (T::BF16 && p.out_bf16) return launch_patch_one<T, T::BF16>(p, stream);
+  return launch_patch_one<T, false>(p, stream);
+}
+
+template <class T>
+size_t workspace_bytes_patch(const Problem& p, int) {
+  return (static_cast<size_t>(p.Kg) * p.K * T::ES + 255) / 256 * 256;
+}
+
 struct TileEntry {
   const char* name;
   int bm, bn, bk, occ;
   int addr;
   hipError_t (*fn)(const Problem&, int, hipStream_t);
   size_t (*ws)(const Problem&, int);
+  bool (*fits)(const Problem&);  // extra shape condition of a tile, or null
 };
+
+#define CONV2D_PATCH_TILE(dt, isbf, bm, bn, wm, wn, rows, two, occ)                              \
+  { "igemm_patch_" dt "_" #bm "x" #bn "_w" #wm "x" #wn "_p" #rows, bm, bn,                       \
+    PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>::BK, occ, 3,                                 \
+    &launch_patch<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>>,                              \
+    &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>>,                     \
+    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>> }
 
 #define CONV2D_DMA_TILE(dt, isbf, bm, bn, rowb, wm, wn, st, two, occ, addr, tag)                \
   { "igemm_dma_" dt "_" #bm "x" #bn "_r" #rowb "_w" #wm "x" #wn "_s" #st tag, bm, bn,           \
     DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>::BK, occ, addr,                     \
     &launch<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>>,                           \
-    &workspace_bytes<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>> }
+    &workspace_bytes<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>>, nullptr }
 
 const TileEntry kTilesF32[] = {
+    CONV2D_PATCH_TILE("f32", false, 128, 128, 2, 2, 512, true, 1),
     CONV2D_DMA_TILE("f32", false, 128, 128, 64, 2, 2, 4, true, 2, kUniform, ""),
     CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, kUniform, ""),
     CONV2D_DMA_TILE("f32", false, 256, 128, 64, 4, 2, 4, true, 2, kUniform, ""),
@@ -789,6 +1202,9 @@ const TileEntry kTilesF32[] = {
     CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 4, true, 4, kElement, "_e"),
 };
 const TileEntry kTilesBf16[] = {
+    CONV2D_PATCH_TILE("bf16", true, 256, 256, 4, 2, 512, false, 1),
+    CONV2D_PATCH_TILE("bf16", true, 256, 256, 2, 2, 512, false, 1),
+    CONV2D_PATCH_TILE("bf16", true, 256, 128, 4, 2, 512, false, 1),
     CONV2D_DMA_TILE("bf16", true, 256, 256, 64, 4, 2, 4, false, 1, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 256, 256, 128, 4, 2, 2, false, 1, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 256, 128, 64, 4, 2, 4, false, 1, kUniform, ""),
@@ -819,6 +1235,10 @@ void igemm_dma_tile_shape(int bf16, int tile, int* bm, int* bn, int* bk) {
 }
 int igemm_dma_tile_occupancy(int bf16, int tile) { return entry(bf16, tile).occ; }
 int igemm_dma_tile_addressing(int bf16, int tile) { return entry(bf16, tile).addr; }
+bool igemm_dma_tile_fits(const Problem& p, int bf16, int tile) {
+  const TileEntry& t = entry(bf16, tile);
+  return t.fits == nullptr || t.fits(p);
+}
 size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile, int splits) {
   return entry(bf16, tile).ws(p, splits);
 }
