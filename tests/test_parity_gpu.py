@@ -88,6 +88,8 @@ SMALL = [
     (2, 9, 9, 5, 7, 3, 3, 1, 1, wl.PAD_SAME),          # odd C and K
     (1, 33, 33, 128, 128, 3, 3, 1, 1, wl.PAD_SAME),    # deep reduction, >1 tile of 256 rows
     (8, 48, 48, 16, 64, 3, 3, 1, 1, wl.PAD_SAME),      # 288 tiles of 64x64: whole rounds + a tail
+    (5, 10, 10, 32, 64, 3, 3, 1, 1, wl.PAD_SAME),      # tiles span several small images (patch tiles)
+    (3, 12, 13, 32, 40, 3, 3, 1, 1, wl.PAD_VALID),     # the same without padding, H != W
 ]
 
 
