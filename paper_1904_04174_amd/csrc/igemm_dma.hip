@@ -178,34 +178,50 @@ __device__ __forceinline__ unsigned short to_bf16_bits(float x) {
 // Bt[k' / bk][n][k' % bk] = filt[k][n], 0 for Kg <= k' < Kg_p: one slice of bk
 // consecutive k' for all features is contiguous, so a B tile of a slice is
 // one contiguous block and its loads fetch whole cache lines.  With
-// block == 0, k' = k (the (r,s,c) order).  With block > 0 (a divisor of C) the reduction is reordered
-// channel block by channel block: k' = ((c / block) * taps + tap) * block +
-// c % block for k = tap * C + c.  32x32 tiles through LDS.
+// block == 0, k' = k (the (r,s,c) order).  With block > 0 (a divisor of C)
+// the reduction is reordered channel block by channel block:
+// k' = ((c / block) * taps + tap) * block + c % block for k = tap * C + c.
+// One workgroup transposes one slice x 64 features through LDS: 16-byte
+// loads along the features, 16-byte stores along k (a contiguous 64*bk block).
 template <typename E>
 __global__ __launch_bounds__(256) void repack_filter_kernel(const E* __restrict__ filt,
                                                             E* __restrict__ bt, int Kg, int K,
                                                             int Kg_p, int C, int taps, int block,
                                                             int bk) {
-  __shared__ E tile[32][33];
-  const int k0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int kp = k0 + ty + 8 * j, n = n0 + tx;
+  constexpr int V = 16 / sizeof(E);          // elements per 16-byte vector
+  __shared__ __align__(16) E tile[64][128 + V];  // [n][k of the slice], bk <= 128
+  const int slice = blockIdx.x, n0 = blockIdx.y * 64;
+  const bool vec_ok = (K % V == 0) && ((reinterpret_cast<size_t>(filt) & 15) == 0);
+  // load: thread -> (k of the slice, vector of V features)
+  for (int idx = threadIdx.x; idx < bk * (64 / V); idx += 256) {
+    const int kk = idx / (64 / V), nv = (idx % (64 / V)) * V;
+    const int kp = slice * bk + kk;
     int k = kp;
     if (block > 0 && kp < Kg) {
       const int per = taps * block;
       const int rem = kp % per;
       k = (rem / block) * C + (kp / per) * block + rem % block;
     }
-    tile[ty + 8 * j][tx] = (kp < Kg && n < K) ? filt[static_cast<size_t>(k) * K + n] : E(0);
+    E v[V];
+    const int n = n0 + nv;
+    if (kp < Kg && vec_ok && n + V <= K) {
+      *reinterpret_cast<uint4*>(v) =
+          *reinterpret_cast<const uint4*>(filt + static_cast<size_t>(k) * K + n);
+    } else {
+#pragma unroll
+      for (int j = 0; j < V; ++j)
+        v[j] = (kp < Kg && n + j < K) ? filt[static_cast<size_t>(k) * K + n + j] : E(0);
+    }
+#pragma unroll
+    for (int j = 0; j < V; ++j) tile[nv + j][kk] = v[j];
   }
   __syncthreads();
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int n = n0 + ty + 8 * j, k = k0 + tx;
-    if (n < K && k < Kg_p)
-      bt[(static_cast<size_t>(k / bk) * K + n) * bk + k % bk] = tile[tx][ty + 8 * j];
+  // store: thread -> (feature, vector of V consecutive k)
+  for (int idx = threadIdx.x; idx < 64 * (bk / V); idx += 256) {
+    const int n = idx / (bk / V), kv = (idx % (bk / V)) * V;
+    if (n0 + n < K)
+      *reinterpret_cast<uint4*>(bt + (static_cast<size_t>(slice) * K + n0 + n) * bk + kv) =
+          *reinterpret_cast<const uint4*>(&tile[n][kv]);
   }
 }
 
@@ -719,7 +735,7 @@ template <class T, bool OUT_BF16>
 hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   const int Kg_p = (p.Kg + T::BK - 1) / T::BK * T::BK;
   // 1. filter -> Bt[K][Kg_p] in the workspace
-  dim3 rgrid((Kg_p + 31) / 32, (p.K + 31) / 32);
+  dim3 rgrid(Kg_p / T::BK, (p.K + 63) / 64);
   if (T::BF16)
     hipLaunchKernelGGL((repack_filter_kernel<unsigned short>), rgrid, dim3(256), 0, stream,
                        static_cast<const unsigned short*>(p.filt),
@@ -1132,7 +1148,7 @@ bool patch_fits(const Problem& p) {
 template <class T, bool OUT_BF16>
 hipError_t launch_patch_one(const Problem& p, hipStream_t stream) {
   // 1. filter -> Bt[slice][K][BK], channel block by channel block
-  dim3 rgrid((p.Kg + 31) / 32, (p.K + 31) / 32);
+  dim3 rgrid(p.Kg / T::BK, (p.K + 63) / 64);
   if (T::BF16)
     hipLaunchKernelGGL((repack_filter_kernel<unsigned short>), rgrid, dim3(256), 0, stream,
                        static_cast<const unsigned short*>(p.filt),
