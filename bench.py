@@ -60,6 +60,10 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
+    ap.add_argument("--workload", choices=["vgg16", "resnet50"], default="vgg16",
+                    help="vgg16: the five VGG-style 3x3 layers at batch 16 (the headline workload); "
+                         "resnet50: the 26 distinct ResNet-50 convolution shapes at batch 32 "
+                         "(the workload of the paper's Figure 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="lower bound on the CPU oracle's timed work")
@@ -84,10 +88,15 @@ def main():
     in_dtype = B.F32 if args.dtype == "f32" else B.BF16
     tdt = torch.float32 if args.dtype == "f32" else torch.bfloat16
 
-    names = [args.only] if args.only else wl.VGG_N16
+    if args.only:
+        names = [args.only]
+    elif args.workload == "resnet50":
+        names = list(wl.RESNET50)
+    else:
+        names = wl.VGG_N16
     layers = []
     for name in names:
-        L = wl.LAYERS[name]
+        L = wl.ALL_LAYERS[name]
         x, f = wl.make_inputs(L, dist="uniform")
         p = B.params_of_layer(L, in_dtype, B.F32)
         xd = torch.from_numpy(x).to(dev).to(tdt).contiguous()
@@ -180,10 +189,14 @@ def main():
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": "VGG-16-style 3x3 sweep, stride 1, SAME, N=16: "
-                               "(224,64,64) (112,128,128) (56,256,256) (28,512,512) (14,512,512); "
-                               "NHWC/HWCF, uniform[-1,1]",
-                   "batch": 16, "layers": names},
+        "config": ({"workload": "VGG-16-style 3x3 sweep, stride 1, SAME, N=16: "
+                                "(224,64,64) (112,128,128) (56,256,256) (28,512,512) (14,512,512); "
+                                "NHWC/HWCF, uniform[-1,1]",
+                    "batch": 16, "layers": names} if args.workload == "vgg16" else
+                   {"workload": "the 26 distinct ResNet-50 convolution shapes (7x7 stem, 1x1 and "
+                                "3x3 bottleneck layers, stride 1 and 2), SAME, N=32; NHWC/HWCF, "
+                                "uniform[-1,1]",
+                    "batch": 32, "layers": names}),
         "frac_of_mfma_peak": round(value / peak, 4),
         "roofline": roofline,
         "layers": [{"name": l["name"], "variant": l["variant"], "ms": round(l["ms"], 4),
@@ -212,8 +225,8 @@ def main():
         result["cpu_baseline"] = {
             "value": round(cpu_flops / cpu_s / 1e12, 5), "unit": "TFLOP/s",
             "cores": oracle.max_threads(), "kind": "oracle",
-            "sample": "%d passes of the oracle over the same five layers at full batch 16, "
-                      "%.1f GFLOP in %.2f s" % (passes, cpu_flops / 1e9, cpu_s)}
+            "sample": "%d passes of the oracle over the same %d layers at full batch, "
+                      "%.1f GFLOP in %.2f s" % (passes, len(layers), cpu_flops / 1e9, cpu_s)}
 
     print(json.dumps(result))
 

@@ -4,7 +4,8 @@ The paper (section 3) tunes the choice of algorithm and of its parameters by
 hand for each target device and names an automated search as future work.
 This script is that search for one device: it times every variant that
 supports a layer, through the C ABI's forced-variant entry point, for every
-named layer in `workloads.LAYERS` (fp32) and `workloads.BF16_LAYERS` (bf16),
+named layer in `workloads.LAYERS` and the ResNet-50 shapes `workloads.RESNET50` (fp32 and bf16;
+of `LAYERS` only `workloads.BF16_LAYERS` in bf16),
 and writes the winners as a table that the selector compiles in
 (`csrc/tuned_table.inc`).  Shapes that are not in the table fall back to the
 selector's cost model.
@@ -80,15 +81,21 @@ def main(argv=None):
     import torch
     if not torch.cuda.is_available():
         sys.exit("tune.py needs the GPU")
-    f32 = [n for n in wl.LAYERS]
+    f32 = list(wl.LAYERS) + list(wl.RESNET50)
+    bf16 = list(wl.BF16_LAYERS) + list(wl.RESNET50)
     lines = [
         "// Winners of `python -m paper_1904_04174_amd.tune` on one MI355X: the fastest variant",
         "// per named layer (milliseconds per call in the comment).  Columns: bf16 input?,",
         "// N, H, W, C, K, R, S, stride rows, stride cols, padding, variant name.",
     ]
-    for in_dtype, names in ((B.F32, f32), (B.BF16, wl.BF16_LAYERS)):
+    seen = set()
+    for in_dtype, names in ((B.F32, f32), (B.BF16, bf16)):
         for name in names:
-            L = wl.LAYERS[name]
+            L = wl.ALL_LAYERS[name]
+            key = (in_dtype,) + tuple(L[1:11])   # the same shape under two names is tuned once
+            if key in seen:
+                continue
+            seen.add(key)
             rows = tune_layer(torch, L, in_dtype)
             if not rows:
                 continue

@@ -60,12 +60,40 @@ BF16_LAYERS = ["V224-N16", "V112-N16", "V56-N16", "V28-N16", "V14-N16",
                "R3x3", "R1x1a", "R1x1b", "R1x1s2"]
 
 VGG_N16 = ["V224-N16", "V112-N16", "V56-N16", "V28-N16", "V14-N16"]
+
+# Group 5: the distinct convolution shapes of ResNet-50 at batch 32 (the workload of the paper's
+# Figure 1), derived from the architecture's published definition: a 7x7 stride-2 stem and four
+# stages of bottleneck blocks (1x1 reduce, 3x3, 1x1 expand, 1x1 projection shortcuts) at 56, 28,
+# 14 and 7 pixels with 64/128/256/512 bottleneck channels.  Both common placements of the
+# stage's stride 2 are listed (on the first 1x1, or on the 3x3): 20 + 6 = 26 shapes.
+# (image size, C, K, window, stride)
+_RN50 = [
+    (224, 3, 64, 7, 2),
+    (56, 64, 64, 1, 1), (56, 64, 64, 3, 1), (56, 64, 256, 1, 1), (56, 256, 64, 1, 1),
+    (56, 256, 128, 1, 2), (28, 128, 128, 3, 1), (28, 128, 512, 1, 1), (56, 256, 512, 1, 2),
+    (28, 512, 128, 1, 1),
+    (28, 512, 256, 1, 2), (14, 256, 256, 3, 1), (14, 256, 1024, 1, 1), (28, 512, 1024, 1, 2),
+    (14, 1024, 256, 1, 1),
+    (14, 1024, 512, 1, 2), (7, 512, 512, 3, 1), (7, 512, 2048, 1, 1), (14, 1024, 2048, 1, 2),
+    (7, 2048, 512, 1, 1),
+    # stride on the 3x3 instead of the first 1x1
+    (56, 256, 128, 1, 1), (56, 128, 128, 3, 2), (28, 512, 256, 1, 1), (28, 256, 256, 3, 2),
+    (14, 1024, 512, 1, 1), (14, 512, 512, 3, 2),
+]
+RESNET50 = {}
+for _i, (_hw, _c, _k, _win, _st) in enumerate(_RN50):
+    _name = "RN50-%02d-%dx%d-%dto%d-%dx%ds%d" % (_i + 1, _hw, _hw, _c, _k, _win, _win, _st)
+    RESNET50[_name] = _layer(_name, 32, _hw, _c, _k, _win, _st, PAD_SAME, "normal", 5)
+ALL_LAYERS = dict(LAYERS)
+ALL_LAYERS.update(RESNET50)
 VGG_N1 = ["V224-N1", "V112-N1", "V56-N1", "V28-N1", "V14-N1"]
 
 
 def layer_seed(layer):
     """Seed of a layer's generator: base seed + group, then a per-name offset."""
-    return BASE_SEED + layer.group * 1000 + sorted(LAYERS).index(layer.name)
+    if layer.name in LAYERS:
+        return BASE_SEED + layer.group * 1000 + sorted(LAYERS).index(layer.name)
+    return BASE_SEED + layer.group * 1000 + sorted(RESNET50).index(layer.name)
 
 
 def round_to_bf16(x):

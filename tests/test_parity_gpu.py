@@ -280,3 +280,27 @@ def test_full_size_layer_bf16(torch_cuda, oracle, name, out_dtype):
     err = rel_err(got, want)
     _say("full bf16 %s err %.3g" % (name, err))
     assert err <= TOL_BF16, (name, err)
+
+
+# ------------------------------------------------------------------ ResNet-50 shapes (Figure 1's workload)
+
+@pytest.mark.parametrize("name", list(wl.RESNET50))
+def test_resnet50_layer_fp32_and_bf16(torch_cuda, oracle, name):
+    """Every distinct ResNet-50 convolution shape at batch 32 with the selected variant, fp32
+    against the whole oracle output; bf16 inputs (fp32 accumulate) against the oracle on the
+    rounded inputs."""
+    L = wl.RESNET50[name]
+    x, f = wl.make_inputs(L)
+    strides = (L.stride_rows, L.stride_cols)
+    p = B.params_of_layer(L)
+    _say("resnet50 fp32 %s variant %s" % (name, B.conv2d_variant_name(B.conv2d_selected_variant(p))))
+    err = rel_err(run_gpu(torch_cuda, p, x, f), oracle.forward_f32(x, f, strides, L.padding))
+    assert err <= TOL_F32, (name, err)
+    if L.channels % 8 == 0:
+        xb, _ = wl.round_to_bf16(x)
+        fb, _ = wl.round_to_bf16(f)
+        pb = B.params_of_layer(L, B.BF16, B.F32)
+        _say("resnet50 bf16 %s variant %s" % (
+            name, B.conv2d_variant_name(B.conv2d_selected_variant(pb))))
+        err = rel_err(run_gpu(torch_cuda, pb, xb, fb), oracle.forward_f32(xb, fb, strides, L.padding))
+        assert err <= TOL_BF16, (name, err)
