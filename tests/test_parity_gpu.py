@@ -282,6 +282,24 @@ def test_full_size_layer_bf16(torch_cuda, oracle, name, out_dtype):
     assert err <= TOL_BF16, (name, err)
 
 
+@pytest.mark.parametrize("batch,expect_direct", [(63, False), (64, True)])
+def test_tensors_around_two_gib(torch_cuda, oracle, batch, expect_direct):
+    """Input of just under / exactly 2^31 bytes: the MFMA variants address with 32-bit byte
+    offsets and must still be right at the top of that range; at 2^31 bytes they are not
+    supported and the selector falls back to the direct kernel."""
+    n, h, w, c, k = batch, 128, 128, 512, 8
+    p = B.make_params(n, h, w, c, k, 1, 1)
+    name = B.conv2d_variant_name(B.conv2d_selected_variant(p))
+    assert (name == "direct") == expect_direct, name
+    rng = np.random.default_rng(31 + batch)
+    x = rng.integers(-4, 5, size=(n, h, w, c)).astype(np.float32)
+    f = rng.integers(-4, 5, size=(1, 1, c, k)).astype(np.float32)
+    _say("2 GiB case batch %d variant %s" % (batch, name))
+    got = run_gpu(torch_cuda, p, x, f)
+    want = oracle.forward_f32(x, f, 1, wl.PAD_SAME)
+    assert np.array_equal(got, want)
+
+
 # ------------------------------------------------------------------ ResNet-50 shapes (Figure 1's workload)
 
 @pytest.mark.parametrize("name", list(wl.RESNET50))
