@@ -170,8 +170,17 @@ bool supports(const Variant& v, const Problem& q) {
       (v.split != kWhole || !igemm_dma_tile_fits(q, v.bf16, v.tile)))
     return false;
   if (v.split == kSplit && (q.Kg + bk - 1) / bk < 2) return false;
-  // a balanced tail needs tiles left over after whole rounds of the 256 compute units
-  if (v.split == kTail && (ceil_div_ll(q.M, bm) * ceil_div_ll(q.K, bn)) % 256 == 0) return false;
+  if (v.split == kTail) {
+    // A balanced tail needs tiles left over after whole rounds of the 256
+    // compute units.  With fewer whole tiles than resident workgroups every
+    // tile would go to the tail: fine for a handful of tiles (the tail then
+    // spreads their slices over the chip), but from one round of tiles on the
+    // uneven pieces land on the units unbalanced and a uniform split is faster.
+    const long long tiles = ceil_div_ll(q.M, bm) * ceil_div_ll(q.K, bn);
+    const long long rest = tiles % 256;
+    if (rest == 0) return false;
+    if (tiles >= 256 && tiles - rest < 256LL * occupancy(v)) return false;
+  }
   return true;
 }
 

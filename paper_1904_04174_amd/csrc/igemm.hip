@@ -99,33 +99,58 @@ __device__ __forceinline__ unsigned short to_bf16_bits(float x) {
   return static_cast<unsigned short>(u >> 16);
 }
 
-// Sum of the `splits` fp32 partial tiles of a split reduction, in split order.
+// Sum of the `splits` fp32 partial tiles of a split reduction, in a fixed
+// order.  A workgroup covers 256 / groups vectors of 4 consecutive outputs;
+// thread (vector o, group g) adds the partials g, g + groups, g + 2 groups ...
+// in that order, and group 0 then adds the group sums in group order from LDS.
+// `groups` is a power of two up to 16: with few outputs and many splits it
+// spreads the otherwise serial chain of dependent loads over more threads.
 template <bool OUT_BF16>
 __global__ __launch_bounds__(256) void split_reduce_kernel(const float* __restrict__ partial,
                                                            void* __restrict__ out, int total,
-                                                           int splits) {
-  const int i0 = (blockIdx.x * 256 + threadIdx.x) * 4;
-  if (i0 >= total) return;
-  if (i0 + 4 <= total && (total & 3) == 0) {
-    float4 acc = *reinterpret_cast<const float4*>(partial + i0);
-    for (int s = 1; s < splits; ++s) {
-      const float4 v = *reinterpret_cast<const float4*>(partial + static_cast<size_t>(s) * total + i0);
+                                                           int splits, int groups) {
+  __shared__ float4 sums[256];
+  const int per_wg = 256 / groups;
+  const int o = threadIdx.x % per_wg, g = threadIdx.x / per_wg;
+  const int i0 = (blockIdx.x * per_wg + o) * 4;
+  const bool vec = (total & 3) == 0;  // then every partial vector is 16-byte aligned and whole
+  float4 acc = {0.f, 0.f, 0.f, 0.f};
+  if (i0 < total) {
+    for (int s = g; s < splits; s += groups) {
+      const float* src = partial + static_cast<size_t>(s) * total + i0;
+      float4 v = {0.f, 0.f, 0.f, 0.f};
+      if (vec) {
+        v = *reinterpret_cast<const float4*>(src);
+      } else {
+        v.x = src[0];
+        if (i0 + 1 < total) v.y = src[1];
+        if (i0 + 2 < total) v.z = src[2];
+        if (i0 + 3 < total) v.w = src[3];
+      }
       acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
+  }
+  sums[threadIdx.x] = acc;
+  __syncthreads();
+  if (g != 0 || i0 >= total) return;
+  for (int j = 1; j < groups; ++j) {
+    const float4 v = sums[j * per_wg + o];
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  const float a[4] = {acc.x, acc.y, acc.z, acc.w};
+  if (vec) {
     if (OUT_BF16) {
-      ushort4 o = {to_bf16_bits(acc.x), to_bf16_bits(acc.y), to_bf16_bits(acc.z), to_bf16_bits(acc.w)};
-      *reinterpret_cast<ushort4*>(static_cast<unsigned short*>(out) + i0) = o;
+      ushort4 r = {to_bf16_bits(a[0]), to_bf16_bits(a[1]), to_bf16_bits(a[2]), to_bf16_bits(a[3])};
+      *reinterpret_cast<ushort4*>(static_cast<unsigned short*>(out) + i0) = r;
     } else {
       *reinterpret_cast<float4*>(static_cast<float*>(out) + i0) = acc;
     }
   } else {
-    for (int i = i0; i < total && i < i0 + 4; ++i) {
-      float acc = partial[i];
-      for (int s = 1; s < splits; ++s) acc += partial[static_cast<size_t>(s) * total + i];
+    for (int c = 0; c < 4 && i0 + c < total; ++c) {
       if (OUT_BF16)
-        static_cast<unsigned short*>(out)[i] = to_bf16_bits(acc);
+        static_cast<unsigned short*>(out)[i0 + c] = to_bf16_bits(a[c]);
       else
-        static_cast<float*>(out)[i] = acc;
+        static_cast<float*>(out)[i0 + c] = a[c];
     }
   }
 }
@@ -514,13 +539,19 @@ constexpr int kNumBf16 = sizeof(kTilesBf16) / sizeof(kTilesBf16[0]);
 
 hipError_t launch_split_reduce(const float* partial, void* out, int total, int splits,
                                bool out_bf16, hipStream_t stream) {
-  const dim3 grid((total + 1023) / 1024), block(256);
+  // more groups while the grid would stay under two workgroups per compute unit
+  const int vecs = (total + 3) / 4;
+  int groups = 1;
+  while (groups < 16 && groups * 2 <= splits && (vecs + 256 / groups - 1) / (256 / groups) < 512)
+    groups *= 2;
+  const int per_wg = 256 / groups;
+  const dim3 grid((vecs + per_wg - 1) / per_wg), block(256);
   if (out_bf16)
     hipLaunchKernelGGL((split_reduce_kernel<true>), grid, block, 0, stream, partial, out, total,
-                       splits);
+                       splits, groups);
   else
     hipLaunchKernelGGL((split_reduce_kernel<false>), grid, block, 0, stream, partial, out, total,
-                       splits);
+                       splits, groups);
   return hipGetLastError();
 }
 

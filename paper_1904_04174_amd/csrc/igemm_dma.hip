@@ -273,6 +273,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   const unsigned ring_base_elt = __builtin_amdgcn_readfirstlane(lds_address(ring) + wave * 256);
 
   int tile, slice_begin, nslices;
+  int piece = 0;  // tail: index of this workgroup's piece (two per range)
   if (!is_tail) {
     // Workgroup i runs on XCD i % 8; give each XCD a contiguous range of
     // tiles so that neighbours share input rows in its L2
@@ -286,7 +287,14 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   } else {
     // tail workgroups 2g and 2g+1 take the two pieces of range g of the tail
     // tiles' slice units: the part in the range's first tile and the rest
-    const int w = blockIdx.x - tail.n_main;
+    // (n_main is a multiple of 8, so tail workgroup j also runs on XCD j % 8;
+    // as above each XCD takes a contiguous run of pieces)
+    const int j = blockIdx.x - tail.n_main;
+    const int nwg = 2 * tail.wgs;
+    const int per = nwg / kXcds, rem = nwg % kXcds;
+    const int xcd = j % kXcds;
+    const int w = xcd * per + (xcd < rem ? xcd : rem) + j / kXcds;
+    piece = w;
     const long long u0 = tail.first_unit(w >> 1), u1 = tail.first_unit((w >> 1) + 1);
     const int t0 = static_cast<int>(u0 / nslices_all);
     const long long cut = min(u1, 1LL * (t0 + 1) * nslices_all);
@@ -610,7 +618,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   // ---- epilogue (accumulator layout: lane l reg v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32)
   if (is_tail) {
     // piece of a tail tile: a whole [BM][BN] fp32 tile, no bounds
-    float* part = partial + static_cast<size_t>(blockIdx.x - tail.n_main) * (BM * BN);
+    float* part = partial + static_cast<size_t>(piece) * (BM * BN);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
