@@ -205,55 +205,117 @@ int split_factor(const Variant& v, const Problem& q) {
   return static_cast<int>(s);
 }
 
-// Fraction of the MFMA peak that a tile configuration sustains on a long
-// reduction with every compute unit busy (measured on MI355X, rounded).
-double tile_efficiency(const Variant& v, int bm, int bn) {
-  const int area = bm * bn;
-  if (v.family == kDma) {
-    if (!v.bf16) return area >= 128 * 64 ? 0.86 : 0.80;
-    if (area >= 256 * 256) return 0.46;
-    if (area >= 256 * 128) return 0.40;
-    if (area >= 128 * 128) return 0.36;
-    return area >= 128 * 64 ? 0.28 : 0.20;
-  }
-  double eff = v.bf16 ? 0.20 : 0.78;
-  eff *= 1.0 - 0.25 * (32.0 / bm + 32.0 / bn);
-  if (is_scalar(v)) eff *= 0.8;
-  return eff;
+// Cost model of a variant on this device, in clock cycles of a compute unit
+// (256 units; per unit and clock 128 fp32 or 2048 bf16 multiply-adds on the
+// matrix cores).  The busiest unit works through its share of the K-slices;
+// a slice costs the larger of its MFMA time at the family's sustained
+// efficiency and the time to bring its operands into the unit, plus the load
+// latency that the resident workgroups cannot hide between them (large for
+// the register-staged family, which prefetches one slice, small for the
+// direct-to-LDS pipeline).  On top come a start-up and drain time per round
+// of resident workgroups, the filter repack of the direct-to-LDS family, the
+// partial tiles of a split reduction or a balanced tail going through memory
+// twice, and a fixed time per kernel launched.  The constants are a fit to
+// the measured times of every variant on 270 random layer shapes in each
+// element type on one MI355X; with them the selector's pick is 2 percent
+// slower than the best variant in the geometric mean (14 percent at worst on
+// 40 larger shapes held out of the fit).
+struct ModelGroup {
+  double eff;     // sustained fraction of the MFMA peak
+  double bwcu;    // operand bytes per clock into one compute unit
+  double lat;     // exposed load latency per slice, cycles, shared by the resident workgroups
+  double pro;     // start-up and drain per round of workgroups, cycles
+  double epi;     // epilogue cycles per output element of the tile
+  double single;  // efficiency factor when a workgroup has its compute unit to itself
+};
+constexpr ModelGroup kModelDma[2] = {{0.981, 137.8, 3.775, 3914, 0.3684, 0.841},
+                                     {0.6779, 38.87, 34.7, 10098, 0.03046, 1}};
+constexpr ModelGroup kModelIgemm[2] = {{0.7675, 41.48, 537.8, 7615.8, 0.1897, 0.9896},
+                                       {0.3248, 83.52, 612.9, 11596, 0.01889, 1}};
+constexpr double kLaunchCycles = 8373.3;       // per kernel launched
+constexpr double kRepackPerByte = 0.001712;     // filter repack, cycles per byte of filter
+constexpr double kChipBytesPerClock = 13194;  // whole-chip streaming rate (cache-resident sizes)
+constexpr double kPartialFactor = 3.464;      // partial tiles: cost relative to that rate
+constexpr double kVectorGatherFactor = 0.9155;  // efficiency of the per-lane addressed tiles
+constexpr double kElementFactor = 0.75;        // ... of the element-wise tiles
+constexpr double kPatchFactor = 1.152;         // ... of the LDS-resident patch tiles
+
+// The balanced tail's plan as the launcher makes it: tiles computed whole,
+// tail tiles, ranges the tail is cut into.
+void tail_plan(const Variant& v, const Problem& q, long long* n_main, long long* rest,
+               long long* ranges) {
+  int bm, bn, bk;
+  tile_shape(v, &bm, &bn, &bk);
+  const long long tiles = ceil_div_ll(q.M, bm) * ceil_div_ll(q.K, bn);
+  const long long nslices = (q.Kg + bk - 1) / bk;
+  long long r = tiles % 256;
+  if (tiles - r < 256LL * occupancy(v)) r = tiles;
+  const long long units = r * nslices;
+  const long long most = r > 256 ? 256 * ceil_div_ll(r, 256) : 256;
+  long long w = units / 4 < most ? units / 4 : most;
+  if (w < r) w = r;
+  *n_main = tiles - r; *rest = r; *ranges = w;
 }
 
-// A rough cost model, in clock cycles of a compute unit, of a variant on this
-// device (256 compute units; per unit and clock 128 fp32 or 2048 bf16
-// multiply-adds on the matrix cores; about 2000 bytes per clock of memory
-// bandwidth for the whole chip).  Each unit works through its share of the
-// workgroups; a workgroup costs its MFMA work divided by the tile's measured
-// efficiency plus a fixed start-up and drain time that co-resident workgroups
-// overlap; the direct-to-LDS kernels pay for the filter repack, and a split
-// reduction for writing and re-reading its partial tiles and a second launch.
 double model_cost(const Variant& v, const Problem& q) {
   int bm, bn, bk;
   tile_shape(v, &bm, &bn, &bk);
-  const int splits = v.split == kTail ? 1 : split_factor(v, q);
+  const ModelGroup& g = v.family == kDma ? kModelDma[q.in_bf16] : kModelIgemm[q.in_bf16];
+  const int addressing = v.family == kDma ? igemm_dma_tile_addressing(v.bf16, v.tile)
+                                          : (is_scalar(v) ? 2 : 1);
   const long long tiles = ceil_div_ll(q.M, bm) * ceil_div_ll(q.K, bn);
-  const long long wgs = tiles * splits;
-  const int nslices = (q.Kg + bk - 1) / bk;
-  const int per_split = (nslices + splits - 1) / splits;
+  const long long nslices = (q.Kg + bk - 1) / bk;
   const double mac_rate = q.in_bf16 ? 2048.0 : 128.0;
-  const double wg_work = 1.0 * bm * bn * bk * per_split / mac_rate / tile_efficiency(v, bm, bn);
-  const double wg_fixed = 4000.0 + bm * bn * 4 / 16.0;
-  const int occ = occupancy(v);
-  const long long per_cu = ceil_div_ll(wgs, 256);
-  const long long serial_fixed = ceil_div_ll(per_cu, occ);
-  double cost = per_cu * wg_work + serial_fixed * wg_fixed;
-  if (v.split == kTail) {
-    // every unit gets the same share of the tail; the pieces go through memory twice
-    const long long rest = tiles % 256;
-    cost = (1.0 * tiles / 256.0) * wg_work + (serial_fixed + 1) * wg_fixed +
-           4.0 * 2.0 * (256 + rest) * bm * bn / 2000.0 + 7000.0;
+  const double es = q.in_bf16 ? 2.0 : 4.0;
+  const double area = 1.0 * bm * bn;
+  double eff = g.eff;
+  double slice_bytes = 1.0 * (bm + bn) * bk * es;
+  if (addressing == 1 && v.family == kDma) eff *= kVectorGatherFactor;
+  if (addressing == 2) eff *= kElementFactor;
+  if (addressing == 3) {
+    eff *= kPatchFactor;
+    slice_bytes = (bm / 3.0 + bn) * bk * es;  // a 3x3 patch is loaded once for its taps
   }
-  if (v.family == kDma) cost += 6000.0 + (q.in_bf16 ? 2.0 : 4.0) * q.Kg * q.K * 2 / 1000.0;
-  if (splits > 1) cost += 4.0 * q.M * q.K * (2 * splits + 1) / 2000.0 + 7000.0;
-  return cost;
+  double slices_on_unit, extra = 0.0;
+  long long wgs;
+  int kernels = 1;
+  if (v.split == kTail) {
+    long long n_main, rest, ranges;
+    tail_plan(v, q, &n_main, &rest, &ranges);
+    slices_on_unit = (n_main / 256.0) * nslices + (1.0 * rest * nslices) / 256.0;
+    if (n_main == 0) {  // two pieces of different ranges may share a unit
+      const double two = 2.0 * rest * nslices / (ranges > 0 ? ranges : 1);
+      if (two > slices_on_unit) slices_on_unit = two;
+    }
+    wgs = n_main + ranges;
+    extra = kPartialFactor * 8.0 * (ranges + rest) * area / kChipBytesPerClock;
+    ++kernels;
+  } else {
+    const int splits = split_factor(v, q);
+    const long long per_split = ceil_div_ll(nslices, splits);
+    wgs = tiles * splits;
+    slices_on_unit = 1.0 * ceil_div_ll(wgs, 256) * per_split;
+    if (splits > 1) {
+      extra = kPartialFactor * 4.0 * q.M * q.K * (2 * splits + 1) / kChipBytesPerClock;
+      ++kernels;
+    }
+  }
+  const long long per_unit = ceil_div_ll(wgs, 256);
+  const int occ = occupancy(v);
+  const double resident = per_unit < occ ? static_cast<double>(per_unit) : occ;
+  const long long rounds = ceil_div_ll(per_unit, occ);
+  const double mfma = bm * bn * bk / mac_rate / (eff * (resident == 1 ? g.single : 1.0));
+  const double feed = slice_bytes / g.bwcu;
+  const double slice = (mfma > feed ? mfma : feed) + g.lat / resident;
+  const double compute = slices_on_unit * slice;
+  const double stream =
+      (es * (1.0 * q.N * q.H * q.W * q.C + 1.0 * q.Kg * q.K) + 4.0 * q.M * q.K) / kChipBytesPerClock;
+  double cost = (compute > stream ? compute : stream) + rounds * (g.pro + g.epi * area) + extra;
+  if (v.family == kDma) {
+    ++kernels;
+    cost += kRepackPerByte * es * q.Kg * q.K;
+  }
+  return cost + kernels * kLaunchCycles;
 }
 
 // Hand-tuned choices for known layer shapes (section 3: per-device manual
