@@ -62,8 +62,10 @@ def main():
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32")
     ap.add_argument("--workload", choices=["vgg16", "resnet50"], default="vgg16",
                     help="vgg16: the five VGG-style 3x3 layers at batch 16 (the headline workload); "
-                         "resnet50: the 26 distinct ResNet-50 convolution shapes at batch 32 "
+                         "resnet50: the 26 distinct ResNet-50 convolution shapes (--batch 1, 4 or 32) "
                          "(the workload of the paper's Figure 1)")
+    ap.add_argument("--batch", type=int, choices=[1, 4, 32], default=32,
+                    help="batch size of the resnet50 workload (the paper's Figures 1-3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="lower bound on the CPU oracle's timed work")
@@ -91,7 +93,7 @@ def main():
     if args.only:
         names = [args.only]
     elif args.workload == "resnet50":
-        names = list(wl.RESNET50)
+        names = list(wl.RESNET50_BY_BATCH[args.batch])
     else:
         names = wl.VGG_N16
     layers = []
@@ -194,9 +196,9 @@ def main():
                                 "NHWC/HWCF, uniform[-1,1]",
                     "batch": 16, "layers": names} if args.workload == "vgg16" else
                    {"workload": "the 26 distinct ResNet-50 convolution shapes (7x7 stem, 1x1 and "
-                                "3x3 bottleneck layers, stride 1 and 2), SAME, N=32; NHWC/HWCF, "
+                                "3x3 bottleneck layers, stride 1 and 2), SAME, N=%d; NHWC/HWCF, " % args.batch +
                                 "uniform[-1,1]",
-                    "batch": 32, "layers": names}),
+                    "batch": args.batch, "layers": names}),
         "frac_of_mfma_peak": round(value / peak, 4),
         "roofline": roofline,
         "layers": [{"name": l["name"], "variant": l["variant"], "ms": round(l["ms"], 4),

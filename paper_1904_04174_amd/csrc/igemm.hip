@@ -23,9 +23,9 @@
 // buffered, one barrier per slice.
 //
 // Two further features of the template:
-//  * SCALAR tiles (fp32) gather single elements instead of 16-byte vectors,
+//  * SCALAR tiles gather single elements instead of 16-byte vectors,
 //    so they take any channel and feature count (C = 3 first layers, odd K)
-//    and any 4-byte-aligned pointers.
+//    and pointers aligned to one element.
 //  * Split reduction: gridDim.y workgroups share one output tile, each takes
 //    a contiguous range of k slices and writes an fp32 partial tile to the
 //    workspace; split_reduce_kernel adds the partials in a fixed order (so
@@ -83,7 +83,6 @@ struct Tile {
   static constexpr int B_BLOCKS = SCALAR ? BK * BN : (BK / VEC) * (BN / VEC);
   static constexpr int B_ITERS = (B_BLOCKS + NT - 1) / NT;
   static constexpr int LDS_BYTES = 2 * (BM + BN) * LD * ES;
-  static_assert(!(SCALAR && BF16), "element-wise tiles are fp32 only");
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of 32x32");
   static_assert(BK % KSTEP == 0, "BK must be a multiple of the fragment step");
   static_assert(NT % KV == 0 && BM % A_ROWS_PER_PASS == 0, "A tile must divide over the threads");
@@ -265,7 +264,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
       const bool ok = (static_cast<unsigned>(a_h0[i] + kr_t) < static_cast<unsigned>(p.H)) &
                       (static_cast<unsigned>(a_w0[i] + ks) < static_cast<unsigned>(p.W));
       const int off = ok ? (a_off[i] + tap) * ES : kOutOfRange;
-      if constexpr (SCALAR)
+      if constexpr (SCALAR && T::BF16)
+        a_elt[i] = static_cast<unsigned short>(__builtin_amdgcn_raw_buffer_load_b16(in_rsrc, off, 0, 0));
+      else if constexpr (SCALAR)
         a_elt[i] = __builtin_amdgcn_raw_buffer_load_b32(in_rsrc, off, 0, 0);
       else
         a_vec[i] = __builtin_amdgcn_raw_buffer_load_b128(in_rsrc, off, 0, 0);
@@ -275,7 +276,11 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
       if constexpr (SCALAR) {
         const int kg = k_next + b_krow[i];
         const int off = (kg < p.Kg) ? (kg * p.K + b_col[i]) * ES : kOutOfRange;
-        b_elt[i] = __builtin_amdgcn_raw_buffer_load_b32(filt_rsrc, off, 0, 0);
+        if constexpr (T::BF16)
+          b_elt[i] = static_cast<unsigned short>(
+              __builtin_amdgcn_raw_buffer_load_b16(filt_rsrc, off, 0, 0));
+        else
+          b_elt[i] = __builtin_amdgcn_raw_buffer_load_b32(filt_rsrc, off, 0, 0);
       } else {
 #pragma unroll
         for (int j = 0; j < VEC; ++j) {
@@ -301,7 +306,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
 #pragma unroll
     for (int i = 0; i < T::A_ITERS; ++i) {
       unsigned char* dst = as + ((a_row0 + i * T::A_ROWS_PER_PASS) * LD + a_kv * AV) * ES;
-      if constexpr (SCALAR)
+      if constexpr (SCALAR && T::BF16)
+        *reinterpret_cast<unsigned short*>(dst) = static_cast<unsigned short>(a_elt[i]);
+      else if constexpr (SCALAR)
         *reinterpret_cast<unsigned*>(dst) = a_elt[i];
       else
         *reinterpret_cast<uintx4*>(dst) = a_vec[i];
@@ -312,7 +319,11 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
       if (b < T::B_BLOCKS) {
         if constexpr (SCALAR) {
           // LDS keeps B as [n][k], k contiguous
-          *reinterpret_cast<unsigned*>(bs + ((b % BN) * LD + b / BN) * ES) = b_elt[i];
+          unsigned char* dst = bs + ((b % BN) * LD + b / BN) * ES;
+          if constexpr (T::BF16)
+            *reinterpret_cast<unsigned short*>(dst) = static_cast<unsigned short>(b_elt[i]);
+          else
+            *reinterpret_cast<unsigned*>(dst) = b_elt[i];
         } else {
           const int nbv = b % (BN / VEC);
           const int kb = b / (BN / VEC);
@@ -531,6 +542,9 @@ const TileEntry kTilesBf16[] = {
     CONV2D_TILE("bf16", true, 128, 64, 64, 2, 2, false, 3, false, ""),
     CONV2D_TILE("bf16", true, 128, 64, 32, 2, 2, false, 3, false, ""),
     CONV2D_TILE("bf16", true, 64, 64, 32, 2, 2, false, 4, false, ""),
+    // element-wise gathers: any C and K (a 3-channel stem in bf16), 2-byte alignment
+    CONV2D_TILE("bf16", true, 128, 64, 32, 2, 2, false, 3, true, "_scalar"),
+    CONV2D_TILE("bf16", true, 64, 64, 32, 2, 2, false, 4, true, "_scalar"),
 };
 constexpr int kNumF32 = sizeof(kTilesF32) / sizeof(kTilesF32[0]);
 constexpr int kNumBf16 = sizeof(kTilesBf16) / sizeof(kTilesBf16[0]);

@@ -4,7 +4,7 @@ The paper (section 3) tunes the choice of algorithm and of its parameters by
 hand for each target device and names an automated search as future work.
 This script is that search for one device: it times every variant that
 supports a layer, through the C ABI's forced-variant entry point, for every
-named layer in `workloads.LAYERS` and the ResNet-50 shapes `workloads.RESNET50` (fp32 and bf16;
+named layer in `workloads.LAYERS` and the ResNet-50 shapes at batch 1, 4 and 32 (fp32 and bf16;
 of `LAYERS` only `workloads.BF16_LAYERS` in bf16),
 and writes the winners as a table that the selector compiles in
 (`csrc/tuned_table.inc`).  Shapes that are not in the table fall back to the
@@ -81,8 +81,9 @@ def main(argv=None):
     import torch
     if not torch.cuda.is_available():
         sys.exit("tune.py needs the GPU")
-    f32 = list(wl.LAYERS) + list(wl.RESNET50)
-    bf16 = list(wl.BF16_LAYERS) + list(wl.RESNET50)
+    rn50 = [name for n in wl.RESNET50_BATCHES for name in wl.RESNET50_BY_BATCH[n]]
+    f32 = list(wl.LAYERS) + rn50
+    bf16 = list(wl.BF16_LAYERS) + rn50
     lines = [
         "// Winners of `python -m paper_1904_04174_amd.tune` on one MI355X: the fastest variant",
         "// per named layer (milliseconds per call in the comment).  Columns: bf16 input?,",

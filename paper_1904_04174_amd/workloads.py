@@ -62,7 +62,7 @@ BF16_LAYERS = ["V224-N16", "V112-N16", "V56-N16", "V28-N16", "V14-N16",
 VGG_N16 = ["V224-N16", "V112-N16", "V56-N16", "V28-N16", "V14-N16"]
 
 # Group 5: the distinct convolution shapes of ResNet-50 at batch 32 (the workload of the paper's
-# Figure 1), derived from the architecture's published definition: a 7x7 stride-2 stem and four
+# Figure 1; batch 1 and 4 below), derived from the architecture's published definition: a 7x7 stride-2 stem and four
 # stages of bottleneck blocks (1x1 reduce, 3x3, 1x1 expand, 1x1 projection shortcuts) at 56, 28,
 # 14 and 7 pixels with 64/128/256/512 bottleneck channels.  Both common placements of the
 # stage's stride 2 are listed (on the first 1x1, or on the 3x3): 20 + 6 = 26 shapes.
@@ -84,8 +84,17 @@ RESNET50 = {}
 for _i, (_hw, _c, _k, _win, _st) in enumerate(_RN50):
     _name = "RN50-%02d-%dx%d-%dto%d-%dx%ds%d" % (_i + 1, _hw, _hw, _c, _k, _win, _win, _st)
     RESNET50[_name] = _layer(_name, 32, _hw, _c, _k, _win, _st, PAD_SAME, "normal", 5)
+# The same 26 shapes at the two other batch sizes of the paper's Figures 2 and 3.
+RESNET50_BATCHES = (1, 4, 32)
+RESNET50_BY_BATCH = {32: RESNET50}
+for _n in (1, 4):
+    RESNET50_BY_BATCH[_n] = {}
+    for _name, _l in RESNET50.items():
+        _nm = "%s-N%d" % (_name, _n)
+        RESNET50_BY_BATCH[_n][_nm] = _l._replace(name=_nm, batch=_n)
 ALL_LAYERS = dict(LAYERS)
-ALL_LAYERS.update(RESNET50)
+for _n in RESNET50_BATCHES:
+    ALL_LAYERS.update(RESNET50_BY_BATCH[_n])
 VGG_N1 = ["V224-N1", "V112-N1", "V56-N1", "V28-N1", "V14-N1"]
 
 
@@ -93,7 +102,9 @@ def layer_seed(layer):
     """Seed of a layer's generator: base seed + group, then a per-name offset."""
     if layer.name in LAYERS:
         return BASE_SEED + layer.group * 1000 + sorted(LAYERS).index(layer.name)
-    return BASE_SEED + layer.group * 1000 + sorted(RESNET50).index(layer.name)
+    base = layer.name.rsplit("-N", 1)[0] if layer.batch != 32 else layer.name
+    offset = 0 if layer.batch == 32 else 100 * layer.batch
+    return BASE_SEED + layer.group * 1000 + offset + sorted(RESNET50).index(base)
 
 
 def round_to_bf16(x):
