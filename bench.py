@@ -64,6 +64,11 @@ def main():
                     help="vgg16: the five VGG-style 3x3 layers at batch 16 (the headline workload); "
                          "resnet50: the 26 distinct ResNet-50 convolution shapes (--batch 1, 4 or 32) "
                          "(the workload of the paper's Figure 1)")
+    ap.add_argument("--algorithms", choices=["direct", "all"], default="direct",
+                    help="direct: the selector's pick among the variants that sum the window "
+                         "directly, so that the executed multiply-adds are the metric's (default); "
+                         "all: also the Winograd variants, which execute 2.25x fewer and can "
+                         "therefore exceed the MFMA peak in the metric's terms")
     ap.add_argument("--batch", type=int, choices=[1, 4, 32], default=32,
                     help="batch size of the resnet50 workload (the paper's Figures 1-3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -106,11 +111,12 @@ def main():
         g = B.conv2d_get_geometry(p)
         out = torch.empty((p.batch, g.out_rows, g.out_cols, p.features), dtype=torch.float32,
                           device=dev)
-        ws_bytes = B.conv2d_workspace_size(p)
+        vid = B.conv2d_select_variant(
+            p, B.SELECT_DIRECT_SUM_ONLY if args.algorithms == "direct" else 0)
+        ws_bytes = B.conv2d_workspace_size(p, vid)
         ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev)
-        vid = B.conv2d_selected_variant(p)
         layers.append(dict(name=name, layer=L, p=p, x=xd, f=fd, out=out, ws=ws, ws_bytes=ws_bytes,
-                           flops=layer_flops(B, p), bytes=layer_bytes(B, p),
+                           vid=vid, flops=layer_flops(B, p), bytes=layer_bytes(B, p),
                            variant=B.conv2d_variant_name(vid)))
         del x, f
 
@@ -120,7 +126,7 @@ def main():
     def launch(l):
         rc = B.conv2d_forward_raw(l["p"], l["x"].data_ptr(), l["f"].data_ptr(),
                                   l["out"].data_ptr(), l["ws"].data_ptr() if l["ws_bytes"] else 0,
-                                  l["ws_bytes"], handle)
+                                  l["ws_bytes"], handle, l["vid"])
         if rc:
             raise B.Conv2dError(rc, "conv2d_forward(%s)" % l["name"])
 

@@ -113,7 +113,8 @@ int conv2d_forward(const conv2d_params* params, const void* in, const void* filt
 
 /* Same, with the variant forced (0 <= variant_id < conv2d_num_variants()).
  * Every variant that supports `params` produces the same result up to the
- * order of floating-point summation.  UNSUPPORTED if it cannot run them. */
+ * order of floating-point summation (the Winograd variants: up to the
+ * rounding of their transforms, within the same tolerance).  UNSUPPORTED if it cannot run them. */
 int conv2d_forward_variant(const conv2d_params* params, const void* in, const void* filt,
                            void* out, void* workspace, size_t workspace_bytes, void* hip_stream,
                            int variant_id);
@@ -124,6 +125,18 @@ const char* conv2d_variant_name(int variant_id);            /* NULL if out of ra
 int conv2d_variant_supports(const conv2d_params* params, int variant_id); /* 1, 0, or <0 status */
 /* The variant conv2d_forward would use, assuming 16-byte-aligned pointers. */
 int conv2d_selected_variant(const conv2d_params* params, int* variant_id);
+
+/* Selection with a restriction.  The paper's library holds, next to the
+ * algorithms that sum the window directly, a Winograd algorithm that reaches
+ * the same result through data transforms with fewer multiplications
+ * (section 3); here those are the "winograd2x2_*" variants (fp32, 3x3 window,
+ * stride 1; they need a workspace several times the size of the input).
+ * flags = 0 selects among all variants, exactly as conv2d_selected_variant;
+ * CONV2D_SELECT_DIRECT_SUM_ONLY leaves the transform variants out, for a
+ * caller that wants a small workspace or counts the executed multiplications.
+ * INVALID_ARGUMENT for unknown flag bits.  Host only. */
+#define CONV2D_SELECT_DIRECT_SUM_ONLY 1u
+int conv2d_select_variant(const conv2d_params* params, uint32_t flags, int* variant_id);
 
 const char* conv2d_status_string(int status);
 int conv2d_version(void);

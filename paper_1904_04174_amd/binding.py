@@ -25,8 +25,8 @@ LIB_PATH = os.path.join(_HERE, "libconv2d_mi355x.so")
 EXPORTS = (
     "conv2d_get_geometry", "conv2d_workspace_size", "conv2d_workspace_size_variant",
     "conv2d_forward", "conv2d_forward_variant", "conv2d_num_variants", "conv2d_variant_name",
-    "conv2d_variant_supports", "conv2d_selected_variant", "conv2d_status_string",
-    "conv2d_version",
+    "conv2d_variant_supports", "conv2d_selected_variant", "conv2d_select_variant",
+    "conv2d_status_string", "conv2d_version",
 )
 
 
@@ -73,6 +73,7 @@ def lib():
         l.conv2d_variant_name.restype = ctypes.c_char_p
         l.conv2d_variant_supports.argtypes = [pp, ctypes.c_int]
         l.conv2d_selected_variant.argtypes = [pp, ctypes.POINTER(ctypes.c_int)]
+        l.conv2d_select_variant.argtypes = [pp, ctypes.c_uint32, ctypes.POINTER(ctypes.c_int)]
         l.conv2d_status_string.argtypes = [ctypes.c_int]
         l.conv2d_status_string.restype = ctypes.c_char_p
         l.conv2d_version.argtypes = []
@@ -142,6 +143,17 @@ def conv2d_selected_variant(params):
     rc = lib().conv2d_selected_variant(ctypes.byref(params), ctypes.byref(v))
     if rc:
         raise Conv2dError(rc, "conv2d_selected_variant")
+    return int(v.value)
+
+
+SELECT_DIRECT_SUM_ONLY = 1
+
+
+def conv2d_select_variant(params, flags=0):
+    v = ctypes.c_int(-1)
+    rc = lib().conv2d_select_variant(ctypes.byref(params), flags, ctypes.byref(v))
+    if rc:
+        raise Conv2dError(rc, "conv2d_select_variant")
     return int(v.value)
 
 

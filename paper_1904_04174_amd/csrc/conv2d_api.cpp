@@ -20,7 +20,7 @@ namespace {
 
 constexpr long long kMaxElems = (1LL << 31) - 1;
 
-enum Family { kDirect = 0, kIgemm = 1, kDma = 2 };
+enum Family { kDirect = 0, kIgemm = 1, kDma = 2, kWinograd = 3 };
 enum Split { kWhole = 0, kSplit = 1, kTail = 2 };
 
 struct Variant {
@@ -34,7 +34,7 @@ struct Variant {
 // Variant table: id 0 is the direct kernel (supports everything), then the
 // register-staged implicit-GEMM tiles (fp32, then bf16), each followed by its
 // split-reduction twin where the tile is small enough for that to make sense,
-// then the direct-to-LDS tiles.
+// then the direct-to-LDS tiles, then the Winograd variants.
 struct Table {
   Variant v[160];
   int n;
@@ -59,6 +59,15 @@ struct Table {
         add(kDma, bf, t, kSplit, igemm_dma_tile_name(bf, t));
         add(kDma, bf, t, kTail, igemm_dma_tile_name(bf, t));
       }
+    // Winograd F(2x2, 3x3), fp32: one variant per gather tile that can run its products
+    for (int t = 0; t < igemm_dma_num_tiles(0); ++t) {
+      const int addressing = igemm_dma_tile_addressing(0, t);
+      if (addressing != 0 && addressing != 1) continue;
+      char base[80];
+      // "igemm_dma_f32_64x64_..." -> "winograd2x2_f32_64x64_..."
+      std::snprintf(base, sizeof(base), "winograd2x2_%s", igemm_dma_tile_name(0, t) + 10);
+      add(kWinograd, 0, t, kWhole, base);
+    }
   }
 };
 const Table& table() {
@@ -152,6 +161,7 @@ bool supports(const Variant& v, const Problem& q) {
   if (!q.in_bf16 && q.out_bf16) return false;
   // buffer addressing needs input and filter below 2^31 bytes
   if (1LL * es * q.N * q.H * q.W * q.C >= (1LL << 31)) return false;
+  if (v.family == kWinograd) return winograd_supports(q, v.tile);
   int bm, bn, bk;
   tile_shape(v, &bm, &bn, &bk);
   if (v.family == kIgemm) {
@@ -257,7 +267,32 @@ void tail_plan(const Variant& v, const Problem& q, long long* n_main, long long*
   *n_main = tiles - r; *rest = r; *ranges = w;
 }
 
+double model_cost(const Variant& v, const Problem& q);
+
+// Winograd F(2x2, 3x3): the 16 point-wise products cost what the gather tile
+// costs on a 1x1 convolution over all 16 * tiles rows (at least the time to
+// stream the transformed input and the products through memory, which do not
+// fit the caches), plus the transform kernels' traffic and three more launches.
+double winograd_cost(const Variant& v, const Problem& q) {
+  const long long tiles = 1LL * q.N * ((q.P + 1) / 2) * ((q.Q + 1) / 2);
+  Problem g = {};
+  g.N = 1; g.H = 1; g.W = static_cast<int>(16 * tiles < 0x7fffffff ? 16 * tiles : 0x7fffffff);
+  g.C = q.C; g.K = q.K; g.R = 1; g.S = 1; g.sr = 1; g.sc = 1; g.P = 1; g.Q = g.W; g.M = g.W;
+  g.Kg = q.C;
+  Variant inner = v;
+  inner.family = kDma;
+  const double memory_rate = 2000.0;  // bytes per clock from HBM
+  const double v_bytes = 4.0 * 16 * tiles * q.C, m_bytes = 4.0 * 16 * tiles * q.K;
+  double product = model_cost(inner, g);
+  const double product_stream = (v_bytes + m_bytes) / memory_rate;
+  if (product < product_stream) product = product_stream;
+  const double transforms =
+      (4.0 * q.N * q.H * q.W * q.C + v_bytes + m_bytes + 4.0 * q.M * q.K) / memory_rate;
+  return product + transforms + 3 * kLaunchCycles;
+}
+
 double model_cost(const Variant& v, const Problem& q) {
+  if (v.family == kWinograd) return winograd_cost(v, q);
   int bm, bn, bk;
   tile_shape(v, &bm, &bn, &bk);
   const ModelGroup& g = v.family == kDma ? kModelDma[q.in_bf16] : kModelIgemm[q.in_bf16];
@@ -333,7 +368,36 @@ bool usable(const Variant& v, const Problem& q, bool aligned) {
   return aligned || v.family == kDirect || is_scalar(v);
 }
 
-int select(const Problem& q, int padding, bool aligned) {
+// `direct_sum_only` leaves out the variants that reach the result through a
+// transform (Winograd): fewer multiplications, a large workspace.  A shape
+// may have two rows in the tuned table, the transform variant first.
+int select_uncached(const Problem& q, int padding, bool aligned, bool direct_sum_only);
+
+// The model path evaluates every variant (about 10 us of host time), which a
+// layer of a few microseconds cannot afford on every call: each thread keeps
+// its last selections in a small direct-mapped cache keyed on the parameters.
+int select(const Problem& q, int padding, bool aligned, bool direct_sum_only) {
+  struct Entry {
+    int key[14];
+    int variant;
+    bool valid;
+  };
+  constexpr int kEntries = 64;
+  thread_local Entry cache[kEntries] = {};
+  const int key[14] = {q.N, q.H, q.W, q.C, q.K, q.R, q.S, q.sr, q.sc, padding, q.in_bf16,
+                       q.out_bf16, aligned ? 1 : 0, direct_sum_only ? 1 : 0};
+  unsigned h = 2166136261u;
+  for (int v : key) h = (h ^ static_cast<unsigned>(v)) * 16777619u;
+  Entry& e = cache[h % kEntries];
+  if (e.valid && std::memcmp(e.key, key, sizeof(key)) == 0) return e.variant;
+  const int id = select_uncached(q, padding, aligned, direct_sum_only);
+  std::memcpy(e.key, key, sizeof(key));
+  e.variant = id;
+  e.valid = true;
+  return id;
+}
+
+int select_uncached(const Problem& q, int padding, bool aligned, bool direct_sum_only) {
   const Table& tb = table();
   if (q.M == 0) return 0;  // empty batch: nothing is launched
   for (const Tuned& t : kTuned) {
@@ -341,7 +405,9 @@ int select(const Problem& q, int padding, bool aligned) {
         t.k == q.K && t.r == q.R && t.s == q.S && t.sr == q.sr && t.sc == q.sc &&
         t.padding == padding) {
       for (int i = 0; i < tb.n; ++i)
-        if (std::strcmp(tb.v[i].name, t.variant) == 0 && usable(tb.v[i], q, aligned)) return i;
+        if (std::strcmp(tb.v[i].name, t.variant) == 0 && usable(tb.v[i], q, aligned) &&
+            !(direct_sum_only && tb.v[i].family == kWinograd))
+          return i;
     }
   }
   int best = 0;
@@ -350,6 +416,7 @@ int select(const Problem& q, int padding, bool aligned) {
   for (int i = 1; i < tb.n; ++i) {
     const Variant& v = tb.v[i];
     if (!usable(v, q, aligned)) continue;
+    if (direct_sum_only && v.family == kWinograd) continue;
     // element-wise tiles only where the vector tiles cannot run
     if (is_scalar(v) && aligned && q.C % vec == 0 && q.K % vec == 0) continue;
     const double c = model_cost(v, q);
@@ -359,6 +426,7 @@ int select(const Problem& q, int padding, bool aligned) {
 }
 
 size_t workspace_bytes_for(const Variant& v, const Problem& q) {
+  if (v.family == kWinograd) return winograd_workspace_bytes(q, v.tile);
   if (v.family == kDma) return igemm_dma_workspace_bytes(q, v.bf16, v.tile, split_factor(v, q));
   if (v.family == kIgemm && v.split)
     return static_cast<size_t>(split_factor(v, q)) * q.M * q.K * sizeof(float);
@@ -382,7 +450,7 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
   const bool al = aligned16(in, filt, out);
   int id = variant_id;
   if (id < 0) {
-    id = select(q, params->padding, al);
+    id = select(q, params->padding, al, false);
     const char* env = std::getenv("CONV2D_FORCE_VARIANT");
     if (env && *env) {
       const int forced = std::atoi(env);
@@ -411,6 +479,7 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     case kDma:
       e = launch_igemm_dma(q, tb.v[id].bf16, tb.v[id].tile, split_factor(tb.v[id], q), stream);
       break;
+    case kWinograd: e = launch_winograd(q, tb.v[id].tile, stream); break;
   }
   return e == hipSuccess ? CONV2D_STATUS_OK : CONV2D_STATUS_LAUNCH_FAILED;
 }
@@ -436,7 +505,7 @@ int conv2d_workspace_size(const conv2d_params* params, size_t* bytes) {
   if (!bytes) return CONV2D_STATUS_INVALID_ARGUMENT;
   int rc = derive(params, &q);
   if (rc) return rc;
-  *bytes = workspace_bytes_for(table().v[select(q, params->padding, true)], q);
+  *bytes = workspace_bytes_for(table().v[select(q, params->padding, true, false)], q);
   return CONV2D_STATUS_OK;
 }
 
@@ -485,7 +554,17 @@ int conv2d_selected_variant(const conv2d_params* params, int* variant_id) {
   if (!variant_id) return CONV2D_STATUS_INVALID_ARGUMENT;
   int rc = derive(params, &q);
   if (rc) return rc;
-  *variant_id = select(q, params->padding, true);
+  *variant_id = select(q, params->padding, true, false);
+  return CONV2D_STATUS_OK;
+}
+
+int conv2d_select_variant(const conv2d_params* params, uint32_t flags, int* variant_id) {
+  Problem q;
+  if (!variant_id || (flags & ~static_cast<uint32_t>(CONV2D_SELECT_DIRECT_SUM_ONLY)))
+    return CONV2D_STATUS_INVALID_ARGUMENT;
+  int rc = derive(params, &q);
+  if (rc) return rc;
+  *variant_id = select(q, params->padding, true, (flags & CONV2D_SELECT_DIRECT_SUM_ONLY) != 0);
   return CONV2D_STATUS_OK;
 }
 

@@ -26,6 +26,11 @@ struct Problem {
   const void* filt;
   void* out;
   void* workspace;
+  // Batched launch of the direct-to-LDS gather kernels (used by the Winograd
+  // path for its per-point matrix products): `batches` > 1 problems of this
+  // shape whose input, filter and output start `*_stride` elements apart.
+  int batches;
+  long long in_stride, filt_stride, out_stride;
 };
 
 // Launchers (one per kernel family).  Each returns hipSuccess or the launch
@@ -66,7 +71,17 @@ void igemm_dma_tile_shape(int bf16, int tile, int* bm, int* bn, int* bk);
 int igemm_dma_tile_occupancy(int bf16, int tile);
 int igemm_dma_tile_addressing(int bf16, int tile);
 bool igemm_dma_tile_fits(const Problem& p, int bf16, int tile);  // extra shape condition (kind 3)
+// (a batched problem holds one repacked filter per batch and takes whole tiles only)
 size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile, int splits);
 hipError_t launch_igemm_dma(const Problem& p, int bf16, int tile, int splits, hipStream_t stream);
+
+// Winograd F(2x2, 3x3), fp32, stride 1: filter, input and output transforms
+// around one batched launch of direct-to-LDS tile `gemm_tile` (addressing kind
+// 0 or 1) for the 16 point-wise matrix products.  The workspace holds the
+// transformed filter, input and products and the batched launch's own
+// workspace.
+bool winograd_supports(const Problem& p, int gemm_tile);
+size_t winograd_workspace_bytes(const Problem& p, int gemm_tile);
+hipError_t launch_winograd(const Problem& p, int gemm_tile, hipStream_t stream);
 
 }  // namespace conv2d

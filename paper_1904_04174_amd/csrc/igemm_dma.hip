@@ -187,8 +187,11 @@ template <typename E>
 __global__ __launch_bounds__(256) void repack_filter_kernel(const E* __restrict__ filt,
                                                             E* __restrict__ bt, int Kg, int K,
                                                             int Kg_p, int C, int taps, int block,
-                                                            int bk) {
+                                                            int bk, long long filt_stride,
+                                                            long long bt_stride) {
   constexpr int V = 16 / sizeof(E);          // elements per 16-byte vector
+  filt += blockIdx.z * filt_stride;          // batched: one filter per blockIdx.z
+  bt += blockIdx.z * bt_stride;
   __shared__ __align__(16) E tile[64][128 + V];  // [n][k of the slice], bk <= 128
   const int slice = blockIdx.x, n0 = blockIdx.y * 64;
   const bool vec_ok = (K % V == 0) && ((reinterpret_cast<size_t>(filt) & 15) == 0);
@@ -311,8 +314,14 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   // window origin plus a scalar tap offset; the descriptor base is moved
   // back by `shift` bytes so that the vector part is never negative.
   const int shift = UNIFORM ? (p.pt * p.W + p.pl) * p.C * ES : 0;
-  const uintx4 in_rsrc = make_rsrc(p.in, shift, p.N * p.H * p.W * p.C * ES + shift);
-  const uintx4 bt_rsrc = make_rsrc(bt, 0, p.K * Kg_p * ES);
+  // batched launch: problem blockIdx.z of p.batches
+  const size_t bz = blockIdx.z;
+  const size_t bt_bytes = (static_cast<size_t>(Kg_p) * p.K * ES + 255) / 256 * 256;
+  const uintx4 in_rsrc =
+      make_rsrc(static_cast<const unsigned char*>(p.in) + bz * p.in_stride * ES, shift,
+                p.N * p.H * p.W * p.C * ES + shift);
+  const uintx4 bt_rsrc =
+      make_rsrc(static_cast<const unsigned char*>(bt) + bz * bt_bytes, 0, p.K * Kg_p * ES);
 
   // ---- loader role of this lane: row tid / CPR (+ passes of ROWS_PER_PASS),
   // LDS chunk position tid % CPR, memory chunk = position ^ swizzle(row);
@@ -645,9 +654,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
           if (to_partial)
             part[idx] = acc[i][j][v];
           else if (OUT_BF16)
-            static_cast<unsigned short*>(p.out)[idx] = to_bf16_bits(acc[i][j][v]);
+            static_cast<unsigned short*>(p.out)[bz * p.out_stride + idx] =
+                to_bf16_bits(acc[i][j][v]);
           else
-            static_cast<float*>(p.out)[idx] = acc[i][j][v];
+            static_cast<float*>(p.out)[bz * p.out_stride + idx] = acc[i][j][v];
         }
       }
     }
@@ -742,17 +752,21 @@ TailPlan plan_tail(const Problem& p, bool want_tail) {
 template <class T, bool OUT_BF16>
 hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   const int Kg_p = (p.Kg + T::BK - 1) / T::BK * T::BK;
-  // 1. filter -> Bt[K][Kg_p] in the workspace
-  dim3 rgrid(Kg_p / T::BK, (p.K + 63) / 64);
+  const int batches = p.batches > 1 ? p.batches : 1;
+  if (batches > 1 && splits != 1) return hipErrorInvalidValue;  // batched: whole tiles only
+  // 1. filter -> Bt[K][Kg_p] in the workspace (one per batch)
+  dim3 rgrid(Kg_p / T::BK, (p.K + 63) / 64, batches);
+  const long long bt_stride = static_cast<long long>(filter_bytes<T>(p) / T::ES);
   if (T::BF16)
     hipLaunchKernelGGL((repack_filter_kernel<unsigned short>), rgrid, dim3(256), 0, stream,
                        static_cast<const unsigned short*>(p.filt),
                        static_cast<unsigned short*>(p.workspace), p.Kg, p.K, Kg_p, p.C,
-                       p.R * p.S, T::UNIFORM ? T::BK : 0, T::BK);
+                       p.R * p.S, T::UNIFORM ? T::BK : 0, T::BK, p.filt_stride, bt_stride);
   else
     hipLaunchKernelGGL((repack_filter_kernel<float>), rgrid, dim3(256), 0, stream,
                        static_cast<const float*>(p.filt), static_cast<float*>(p.workspace), p.Kg,
-                       p.K, Kg_p, p.C, p.R * p.S, T::UNIFORM ? T::BK : 0, T::BK);
+                       p.K, Kg_p, p.C, p.R * p.S, T::UNIFORM ? T::BK : 0, T::BK, p.filt_stride,
+                       bt_stride);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // 2. the convolution
@@ -763,8 +777,9 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   while (flush * flush < per_split) ++flush;
   float* partial = reinterpret_cast<float*>(static_cast<unsigned char*>(p.workspace) +
                                             filter_bytes<T>(p));
-  hipLaunchKernelGGL((igemm_dma_kernel<T, OUT_BF16>), dim3(tail.n_main + 2 * tail.wgs, splits),
-                     dim3(T::NT), 0, stream, p, Kg_p, per_split, flush, p.workspace, partial, tail);
+  hipLaunchKernelGGL((igemm_dma_kernel<T, OUT_BF16>),
+                     dim3(tail.n_main + 2 * tail.wgs, splits, batches), dim3(T::NT), 0, stream, p,
+                     Kg_p, per_split, flush, p.workspace, partial, tail);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   // 3. sum of the partial outputs
@@ -787,6 +802,7 @@ hipError_t launch(const Problem& p, int splits, hipStream_t stream) {
 
 template <class T>
 size_t workspace_bytes(const Problem& p, int splits) {
+  if (p.batches > 1) return filter_bytes<T>(p) * p.batches;
   const TailPlan tail = plan_tail<T>(p, splits == kTailBalanced);
   if (tail.wgs > 0)
     return filter_bytes<T>(p) + static_cast<size_t>(tail.wgs) * 2 * T::BM * T::BN * sizeof(float);
@@ -1161,11 +1177,11 @@ hipError_t launch_patch_one(const Problem& p, hipStream_t stream) {
     hipLaunchKernelGGL((repack_filter_kernel<unsigned short>), rgrid, dim3(256), 0, stream,
                        static_cast<const unsigned short*>(p.filt),
                        static_cast<unsigned short*>(p.workspace), p.Kg, p.K, p.Kg, p.C,
-                       p.R * p.S, T::BK, T::BK);
+                       p.R * p.S, T::BK, T::BK, 0LL, 0LL);
   else
     hipLaunchKernelGGL((repack_filter_kernel<float>), rgrid, dim3(256), 0, stream,
                        static_cast<const float*>(p.filt), static_cast<float*>(p.workspace), p.Kg,
-                       p.K, p.Kg, p.C, p.R * p.S, T::BK, T::BK);
+                       p.K, p.Kg, p.C, p.R * p.S, T::BK, T::BK, 0LL, 0LL);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // 2. the convolution

@@ -21,6 +21,7 @@ from . import binding as B
 from . import workloads as wl
 
 SPLIT_PENALTY = 1.03   # a split-reduction variant must win by 3 % to be chosen (it needs scratch)
+WINOGRAD_MARGIN = 1.05  # a Winograd variant must win by 5 % (its workspace is several inputs large)
 MAX_WORKSPACE = 1 << 30
 
 
@@ -87,7 +88,8 @@ def main(argv=None):
     lines = [
         "// Winners of `python -m paper_1904_04174_amd.tune` on one MI355X: the fastest variant",
         "// per named layer (milliseconds per call in the comment).  Columns: bf16 input?,",
-        "// N, H, W, C, K, R, S, stride rows, stride cols, padding, variant name.",
+        "// N, H, W, C, K, R, S, stride rows, stride cols, padding, variant name.  A shape whose",
+        "// fastest variant is a Winograd one has that row first, then its best direct-sum variant.",
     ]
     seen = set()
     for in_dtype, names in ((B.F32, f32), (B.BF16, bf16)):
@@ -100,15 +102,22 @@ def main(argv=None):
             rows = tune_layer(torch, L, in_dtype)
             if not rows:
                 continue
-            _, ms, best = rows[0]
-            print("%-5s %-10s %-46s %9.4f ms   (runner-up %s %.4f)" % (
-                "bf16" if in_dtype == B.BF16 else "f32", name, best, ms,
-                rows[1][2] if len(rows) > 1 else "-", rows[1][1] if len(rows) > 1 else 0.0),
-                flush=True)
-            lines.append('{%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, "%s"},  // %s %.4f ms' % (
-                1 if in_dtype == B.BF16 else 0, L.batch, L.in_rows, L.in_cols, L.channels,
-                L.features, L.window_rows, L.window_cols, L.stride_rows, L.stride_cols,
-                L.padding, best, name, ms))
+            # the best variant overall goes first if it is a transform (Winograd) variant and
+            # wins by the margin; the best direct-sum variant always gets a row
+            direct = [r for r in rows if not r[2].startswith("winograd")]
+            chosen = []
+            if rows[0][2].startswith("winograd") and (
+                    not direct or rows[0][0] * WINOGRAD_MARGIN < direct[0][0]):
+                chosen.append(rows[0])
+            if direct:
+                chosen.append(direct[0])
+            for _, ms, best in chosen:
+                print("%-5s %-10s %-46s %9.4f ms" % (
+                    "bf16" if in_dtype == B.BF16 else "f32", name, best, ms), flush=True)
+                lines.append('{%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d, "%s"},  // %s %.4f ms'
+                             % (1 if in_dtype == B.BF16 else 0, L.batch, L.in_rows, L.in_cols,
+                                L.channels, L.features, L.window_rows, L.window_cols,
+                                L.stride_rows, L.stride_cols, L.padding, best, name, ms))
     with open(args.out, "w") as fh:
         fh.write("\n".join(lines) + "\n")
     print("wrote", args.out)

@@ -165,7 +165,10 @@ def test_selector_only_picks_supported_variants():
 
 def test_compute_bound_layers_use_the_matrix_cores():
     for name in wl.VGG_N16 + ["L-same", "L-valid", "L-s2", "R3x3"]:
-        v = B.conv2d_selected_variant(B.params_of_layer(wl.LAYERS[name]))
+        p = B.params_of_layer(wl.LAYERS[name])
+        v = B.conv2d_selected_variant(p)
+        assert B.conv2d_variant_name(v).startswith(("igemm_", "winograd2x2_")), name
+        v = B.conv2d_select_variant(p, B.SELECT_DIRECT_SUM_ONLY)
         assert B.conv2d_variant_name(v).startswith("igemm_"), name
 
 
@@ -219,6 +222,7 @@ def test_tuned_table_names_existing_variants():
     table = os.path.join(os.path.dirname(B.__file__), "csrc", "tuned_table.inc")
     rows = [l for l in open(table) if l.startswith("{")]
     assert len(rows) >= len(wl.LAYERS)
+    seen = {}
     for l in rows:
         fields = l[1:l.index("}")].split(",")
         name = fields[-1].strip().strip('"')
@@ -226,7 +230,39 @@ def test_tuned_table_names_existing_variants():
         p = B.make_params(n, h, w, c, k, r, s_, sr, sc, pad, B.BF16 if bf16 else B.F32, B.F32)
         assert name in names, name
         assert B.conv2d_variant_supports(p, names[name]), l
-        assert B.conv2d_selected_variant(p) == names[name], l
+        # a shape has at most two rows, the transform (Winograd) variant first: that one is the
+        # unrestricted choice, the other the choice among the direct-sum variants
+        key = tuple(fields[:-1])
+        seen.setdefault(key, []).append(name)
+        if name.startswith("winograd"):
+            assert len(seen[key]) == 1, l
+            assert B.conv2d_selected_variant(p) == names[name], l
+        else:
+            assert len(seen[key]) <= 2, l
+            assert B.conv2d_select_variant(p, B.SELECT_DIRECT_SUM_ONLY) == names[name], l
+            if len(seen[key]) == 1:
+                assert B.conv2d_selected_variant(p) == names[name], l
+
+
+def test_select_variant_flags():
+    p = B.make_params(16, 56, 56, 256, 256, 3, 3)
+    names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
+    assert any(n.startswith("winograd2x2_") for n in names)
+    assert B.conv2d_select_variant(p, 0) == B.conv2d_selected_variant(p)
+    assert not names[B.conv2d_select_variant(p, B.SELECT_DIRECT_SUM_ONLY)].startswith("winograd")
+    with pytest.raises(B.Conv2dError):
+        B.conv2d_select_variant(p, 2)
+    # Winograd runs fp32 3x3 stride-1 layers with C and K multiples of 4 only
+    wino = [i for i, n in enumerate(names) if n.startswith("winograd2x2_") and n.endswith("_g")]
+    assert B.conv2d_variant_supports(p, wino[0])
+    for bad in (B.make_params(16, 56, 56, 256, 256, 3, 3, 2, 2),
+                B.make_params(16, 56, 56, 256, 256, 5, 5),
+                B.make_params(16, 56, 56, 254, 256, 3, 3),
+                B.make_params(16, 56, 56, 256, 256, 3, 3, in_dtype=B.BF16)):
+        assert not B.conv2d_variant_supports(bad, wino[0])
+    # its workspace holds the transformed filter, input and products
+    tiles = 16 * 28 * 28
+    assert B.conv2d_workspace_size(p, wino[0]) >= 4 * 16 * (256 * 256 + 2 * tiles * 256)
 
 
 def test_variant_names_are_unique():

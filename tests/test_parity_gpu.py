@@ -336,3 +336,53 @@ def test_resnet50_small_batches_fp32(torch_cuda, oracle, batch):
         err = rel_err(run_gpu(torch_cuda, p, x, f),
                       oracle.forward_f32(x, f, (L.stride_rows, L.stride_cols), L.padding))
         assert err <= TOL_F32, (name, err)
+
+
+# ------------------------------------------------------------------ Winograd F(2x2, 3x3) (section 3)
+
+def _winograd_variants(p):
+    return [v for v in supported_variants(p) if B.conv2d_variant_name(v).startswith("winograd2x2_")]
+
+
+def test_winograd_variants_are_among_the_small_cases():
+    """The all-variants tests above must really reach the Winograd path: odd output sizes (a
+    2x2 block hanging over the edge), VALID padding, several images."""
+    reached = [c for c in SMALL if _winograd_variants(_params(c))]
+    assert any(c[9] == wl.PAD_VALID for c in reached)
+    assert any(c[1] % 2 == 1 or c[2] % 2 == 1 for c in reached)
+    assert len(reached) >= 4, reached
+
+
+@pytest.mark.parametrize("name", ["V56-N16", "V28-N16", "V14-N16", "V14-N1", "R3x3"])
+def test_winograd_full_size_fp32(torch_cuda, oracle, name):
+    """Forced Winograd variants (one with scalar-offset addressing, one with per-lane addressing
+    of the batched products) at full layer size against the whole oracle output, to the same
+    fp32 tolerance as the direct-sum variants."""
+    L = wl.LAYERS[name]
+    x, f = wl.make_inputs(L)
+    p = B.params_of_layer(L)
+    want = oracle.forward_f32(x, f, (1, 1), L.padding)
+    ids = _winograd_variants(p)
+    names = [B.conv2d_variant_name(v) for v in ids]
+    picks = [ids[0]] + [v for v, n in zip(ids, names) if n.endswith("_g")][:1]
+    assert len(picks) == 2, names
+    for vid in picks:
+        _say("winograd %s variant %s" % (name, B.conv2d_variant_name(vid)))
+        err = rel_err(run_gpu(torch_cuda, p, x, f, vid), want)
+        assert err <= TOL_F32, (name, B.conv2d_variant_name(vid), err)
+
+
+@pytest.mark.parametrize("pad", [wl.PAD_SAME, wl.PAD_VALID])
+def test_winograd_integer_inputs_bit_exact(torch_cuda, oracle, pad):
+    """The transform matrices hold only 0, +-1 and +-1/2: with small integer inputs every
+    intermediate is a multiple of 1/4 below 2^22, so the result is exact."""
+    case = (4, 19, 23, 64, 32, 3, 3, 1, 1, pad)
+    n, h, w, c, k, r, s, sr, sc, _ = case
+    x, f = wl.make_case((n, h, w, c), (r, s, c, k), "ints", 9100 + pad)
+    want = oracle.forward_f32(x, f, (1, 1), pad)
+    p = _params(case)
+    ids = _winograd_variants(p)
+    assert ids
+    for vid in ids:
+        _say("winograd ints %s variant %s" % (case, B.conv2d_variant_name(vid)))
+        assert np.array_equal(run_gpu(torch_cuda, p, x, f, vid), want), B.conv2d_variant_name(vid)
