@@ -20,7 +20,8 @@
  *   SAME : out_rows = ceil(in_rows / stride_rows); total padding
  *          max((out_rows-1)*stride_rows + window_rows - in_rows, 0), of which
  *          floor(total/2) goes before (top/left) and the rest after.
- *   Columns alike.  Dilation 1, one group, no bias, no activation.
+ *   Columns alike.  Dilation 1, one group; bias and activation only through
+ *   conv2d_forward_bias_act.
  *
  * Section 3 also says the library offers several algorithms that give the
  * same numeric result and chooses among them (and among their parameters)
@@ -118,6 +119,23 @@ int conv2d_forward(const conv2d_params* params, const void* in, const void* filt
 int conv2d_forward_variant(const conv2d_params* params, const void* in, const void* filt,
                            void* out, void* workspace, size_t workspace_bytes, void* hip_stream,
                            int variant_id);
+
+/* Forward convolution with a fused epilogue:
+ *   out[n,p,q,k] = act( conv(in, filt)[n,p,q,k] + bias[k] )
+ * Section 3 of the paper names the layers that sit between the convolutions
+ * of a network only in passing; folding the bias and the activation into the
+ * store of the convolution saves one round trip of the output through memory
+ * (on the 1x1 layers the output is most of the traffic).
+ *   bias       : device pointer to `features` fp32 values, or NULL for none
+ *   activation : CONV2D_ACT_NONE or CONV2D_ACT_RELU (max(x, 0); NaN stays NaN)
+ * The sum is formed in fp32 exactly as by conv2d_forward, the bias is added
+ * in fp32 and the result is rounded once to out_dtype.  Same variant
+ * selection, workspace and other rules as conv2d_forward; INVALID_ARGUMENT
+ * for an unknown activation or a misaligned bias pointer. */
+typedef enum { CONV2D_ACT_NONE = 0, CONV2D_ACT_RELU = 1 } conv2d_activation_t;
+int conv2d_forward_bias_act(const conv2d_params* params, const void* in, const void* filt,
+                            const float* bias, int activation, void* out, void* workspace,
+                            size_t workspace_bytes, void* hip_stream);
 
 /* Variant introspection (host only). */
 int conv2d_num_variants(void);

@@ -7,6 +7,7 @@ from .conv2d_oracle import (  # noqa: F401
     PAD_SAME,
     PAD_VALID,
     build,
+    forward_bias_act_f32,
     forward_f32,
     forward_f64,
     geometry,

@@ -127,3 +127,22 @@ def points_f32(x, f, flat_index, stride=1, padding=PAD_SAME, num_threads=0):
     if rc:
         raise RuntimeError("conv2d_oracle_points_f32 failed with status %d" % rc)
     return vals
+
+
+def forward_bias_act_f32(x, f, bias=None, relu=False, stride=1, padding=PAD_SAME, num_threads=0):
+    """The fused epilogue written out from its definition:
+    out = act(conv(x, f) + bias[k]), conv in fp64 on the float32 data, bias added in fp64,
+    act = max(., 0) if `relu`, one rounding to float32 at the end.  (Section 3 of the paper
+    names the layers between the convolutions only in passing; bias and ReLU are the usual
+    ones, and this is their plain definition.)"""
+    y = forward_f64(np.asarray(x, dtype=np.float32).astype(np.float64),
+                    np.asarray(f, dtype=np.float32).astype(np.float64), stride, padding,
+                    num_threads)
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float32).astype(np.float64)
+        if b.shape != (y.shape[3],):
+            raise ValueError("bias must have one value per output feature")
+        y = y + b
+    if relu:
+        y = np.maximum(y, 0.0)
+    return y.astype(np.float32)

@@ -24,7 +24,8 @@ LIB_PATH = os.path.join(_HERE, "libconv2d_mi355x.so")
 
 EXPORTS = (
     "conv2d_get_geometry", "conv2d_workspace_size", "conv2d_workspace_size_variant",
-    "conv2d_forward", "conv2d_forward_variant", "conv2d_num_variants", "conv2d_variant_name",
+    "conv2d_forward", "conv2d_forward_variant", "conv2d_forward_bias_act", "conv2d_num_variants",
+    "conv2d_variant_name",
     "conv2d_variant_supports", "conv2d_selected_variant", "conv2d_select_variant",
     "conv2d_status_string", "conv2d_version",
 )
@@ -73,6 +74,8 @@ def lib():
         l.conv2d_variant_name.restype = ctypes.c_char_p
         l.conv2d_variant_supports.argtypes = [pp, ctypes.c_int]
         l.conv2d_selected_variant.argtypes = [pp, ctypes.POINTER(ctypes.c_int)]
+        l.conv2d_forward_bias_act.argtypes = [pp, vp, vp, vp, ctypes.c_int, vp, vp, ctypes.c_size_t,
+                                              vp]
         l.conv2d_select_variant.argtypes = [pp, ctypes.c_uint32, ctypes.POINTER(ctypes.c_int)]
         l.conv2d_status_string.argtypes = [ctypes.c_int]
         l.conv2d_status_string.restype = ctypes.c_char_p
@@ -183,7 +186,19 @@ def conv2d_forward_raw(params, in_ptr, filt_ptr, out_ptr, workspace_ptr=0, works
                                     int(variant_id))
 
 
-def conv2d_forward(params, x, filt, out=None, workspace=None, stream=None, variant_id=None):
+ACT_NONE = 0
+ACT_RELU = 1
+
+
+def conv2d_forward_bias_act(params, x, filt, bias, activation, out=None, workspace=None,
+                            stream=None):
+    """out = act(conv(x, filt) + bias): `bias` a float32 device tensor of `features` values or
+    None, `activation` ACT_NONE or ACT_RELU.  Otherwise as conv2d_forward."""
+    return conv2d_forward(params, x, filt, out, workspace, stream, None, bias, activation, True)
+
+
+def conv2d_forward(params, x, filt, out=None, workspace=None, stream=None, variant_id=None,
+                   bias=None, activation=ACT_NONE, fused=False):
     """Enqueue the forward convolution of torch device tensors.
 
     x: NHWC, filt: HWCF, contiguous, float32 or bfloat16 matching params.in_dtype.
@@ -212,6 +227,19 @@ def conv2d_forward(params, x, filt, out=None, workspace=None, stream=None, varia
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else 0
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    if fused:
+        if variant_id is not None:
+            raise ValueError("the fused entry point selects the variant itself")
+        if bias is not None and not (bias.is_cuda and bias.dtype == torch.float32 and
+                                     bias.is_contiguous() and bias.numel() == params.features):
+            raise ValueError("bias must be a contiguous float32 device tensor of `features` values")
+        rc = lib().conv2d_forward_bias_act(
+            ctypes.byref(params), x.data_ptr(), filt.data_ptr(),
+            bias.data_ptr() if bias is not None else 0, int(activation), out.data_ptr(), ws_ptr,
+            ws_bytes, _stream_handle(stream))
+        if rc:
+            raise Conv2dError(rc, "conv2d_forward_bias_act")
+        return out
     rc = conv2d_forward_raw(params, x.data_ptr(), filt.data_ptr(), out.data_ptr(), ws_ptr,
                             ws_bytes, _stream_handle(stream), variant_id)
     if rc:

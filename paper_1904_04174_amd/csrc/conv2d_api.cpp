@@ -439,7 +439,8 @@ bool aligned16(const void* a, const void* b, const void* c) {
 }
 
 int run(const conv2d_params* params, const void* in, const void* filt, void* out, void* workspace,
-        size_t workspace_bytes, void* hip_stream, int variant_id) {
+        size_t workspace_bytes, void* hip_stream, int variant_id, const float* bias = nullptr,
+        int activation = CONV2D_ACT_NONE) {
   Problem q;
   int rc = derive(params, &q);
   if (rc) return rc;
@@ -469,6 +470,8 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     if (reinterpret_cast<uintptr_t>(workspace) & 15u) return CONV2D_STATUS_INVALID_ARGUMENT;
   }
   q.in = in; q.filt = filt; q.out = out; q.workspace = workspace;
+  q.bias = bias;
+  q.relu = activation == CONV2D_ACT_RELU;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   hipError_t e = hipSuccess;
   switch (tb.v[id].family) {
@@ -531,6 +534,15 @@ int conv2d_forward_variant(const conv2d_params* params, const void* in, const vo
                            int variant_id) {
   if (variant_id < 0) return CONV2D_STATUS_INVALID_ARGUMENT;
   return run(params, in, filt, out, workspace, workspace_bytes, hip_stream, variant_id);
+}
+
+int conv2d_forward_bias_act(const conv2d_params* params, const void* in, const void* filt,
+                            const float* bias, int activation, void* out, void* workspace,
+                            size_t workspace_bytes, void* hip_stream) {
+  if (activation != CONV2D_ACT_NONE && activation != CONV2D_ACT_RELU)
+    return CONV2D_STATUS_INVALID_ARGUMENT;
+  if (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)) return CONV2D_STATUS_INVALID_ARGUMENT;
+  return run(params, in, filt, out, workspace, workspace_bytes, hip_stream, -1, bias, activation);
 }
 
 int conv2d_num_variants(void) { return table().n; }

@@ -26,12 +26,23 @@ struct Problem {
   const void* filt;
   void* out;
   void* workspace;
+  // Fused epilogue: out = act(sum + bias[k]).  bias: K fp32 values on the
+  // device, or null; relu: 0 or 1.
+  const float* bias;
+  int relu;
   // Batched launch of the direct-to-LDS gather kernels (used by the Winograd
   // path for its per-point matrix products): `batches` > 1 problems of this
   // shape whose input, filter and output start `*_stride` elements apart.
   int batches;
   long long in_stride, filt_stride, out_stride;
 };
+
+// The fused epilogue on one finished sum (feature index `col`).  A NaN sum stays NaN.
+__device__ __forceinline__ float finish(float v, const float* __restrict__ bias, int relu, int col) {
+  if (bias) v += bias[col];
+  if (relu) v = v < 0.f ? 0.f : v;
+  return v;
+}
 
 // Launchers (one per kernel family).  Each returns hipSuccess or the launch
 // error; none synchronises.  `tile` selects a compiled tile configuration.
@@ -48,10 +59,11 @@ bool igemm_tile_is_scalar(int bf16, int tile);  // element-wise loads: any C, K,
 hipError_t launch_igemm(const Problem& p, int bf16, int tile, int splits, hipStream_t stream);
 
 // Adds `splits` fp32 partial outputs of `total` elements each (laid out one
-// after the other at `partial`) in split order and stores the sum to `out`
-// as fp32 or bf16.
+// after the other at `partial`) in a fixed order, applies the fused epilogue
+// (feature = index % K) and stores the result to `out` as fp32 or bf16.
 hipError_t launch_split_reduce(const float* partial, void* out, int total, int splits,
-                               bool out_bf16, hipStream_t stream);
+                               bool out_bf16, const float* bias, int relu, int K,
+                               hipStream_t stream);
 
 // Value of `splits` that asks the direct-to-LDS kernels for whole tiles plus
 // a balanced tail instead of a uniform split.

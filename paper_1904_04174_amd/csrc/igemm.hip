@@ -107,7 +107,9 @@ __device__ __forceinline__ unsigned short to_bf16_bits(float x) {
 template <bool OUT_BF16>
 __global__ __launch_bounds__(256) void split_reduce_kernel(const float* __restrict__ partial,
                                                            void* __restrict__ out, int total,
-                                                           int splits, int groups) {
+                                                           int splits, int groups,
+                                                           const float* __restrict__ bias, int relu,
+                                                           int K) {
   __shared__ float4 sums[256];
   const int per_wg = 256 / groups;
   const int o = threadIdx.x % per_wg, g = threadIdx.x / per_wg;
@@ -136,7 +138,12 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(const float* __restri
     const float4 v = sums[j * per_wg + o];
     acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
   }
-  const float a[4] = {acc.x, acc.y, acc.z, acc.w};
+  // fused epilogue: the feature of flat output index i is i % K
+  const int col = i0 % K;
+  float a[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+  for (int c = 0; c < 4; ++c) a[c] = finish(a[c], bias, relu, (col + c) % K);
+  acc = float4{a[0], a[1], a[2], a[3]};
   if (vec) {
     if (OUT_BF16) {
       ushort4 r = {to_bf16_bits(a[0]), to_bf16_bits(a[1]), to_bf16_bits(a[2]), to_bf16_bits(a[3])};
@@ -469,9 +476,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
           if (to_partial)
             part[idx] = acc[i][j][v];
           else if (OUT_BF16)
-            static_cast<unsigned short*>(p.out)[idx] = to_bf16_bits(acc[i][j][v]);
+            static_cast<unsigned short*>(p.out)[idx] =
+                to_bf16_bits(finish(acc[i][j][v], p.bias, p.relu, col));
           else
-            static_cast<float*>(p.out)[idx] = acc[i][j][v];
+            static_cast<float*>(p.out)[idx] = finish(acc[i][j][v], p.bias, p.relu, col);
         }
       }
     }
@@ -502,7 +510,7 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || splits == 1) return e;
   return launch_split_reduce(static_cast<const float*>(p.workspace), p.out, p.M * p.K, splits,
-                             OUT_BF16, stream);
+                             OUT_BF16, p.bias, p.relu, p.K, stream);
 }
 
 template <class T>
@@ -552,7 +560,8 @@ constexpr int kNumBf16 = sizeof(kTilesBf16) / sizeof(kTilesBf16[0]);
 }  // namespace
 
 hipError_t launch_split_reduce(const float* partial, void* out, int total, int splits,
-                               bool out_bf16, hipStream_t stream) {
+                               bool out_bf16, const float* bias, int relu, int K,
+                               hipStream_t stream) {
   // more groups while the grid would stay under two workgroups per compute unit
   const int vecs = (total + 3) / 4;
   int groups = 1;
@@ -562,10 +571,10 @@ hipError_t launch_split_reduce(const float* partial, void* out, int total, int s
   const dim3 grid((vecs + per_wg - 1) / per_wg), block(256);
   if (out_bf16)
     hipLaunchKernelGGL((split_reduce_kernel<true>), grid, block, 0, stream, partial, out, total,
-                       splits, groups);
+                       splits, groups, bias, relu, K);
   else
     hipLaunchKernelGGL((split_reduce_kernel<false>), grid, block, 0, stream, partial, out, total,
-                       splits, groups);
+                       splits, groups, bias, relu, K);
   return hipGetLastError();
 }
 

@@ -655,9 +655,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
             part[idx] = acc[i][j][v];
           else if (OUT_BF16)
             static_cast<unsigned short*>(p.out)[bz * p.out_stride + idx] =
-                to_bf16_bits(acc[i][j][v]);
+                to_bf16_bits(finish(acc[i][j][v], p.bias, p.relu, col));
           else
-            static_cast<float*>(p.out)[bz * p.out_stride + idx] = acc[i][j][v];
+            static_cast<float*>(p.out)[bz * p.out_stride + idx] =
+                finish(acc[i][j][v], p.bias, p.relu, col);
         }
       }
     }
@@ -670,7 +671,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
 template <int BM, int BN, bool OUT_BF16>
 __global__ __launch_bounds__(256) void tail_reduce_kernel(const float* __restrict__ partial,
                                                           void* __restrict__ out, int M, int K,
-                                                          int nslices, const TailPlan tail) {
+                                                          int nslices, const TailPlan tail,
+                                                          const float* __restrict__ bias,
+                                                          int relu) {
   const int t = blockIdx.x;  // tail tile
   const int tiles_n = (K + BN - 1) / BN;
   const int tile = tail.n_main + t;
@@ -697,10 +700,11 @@ __global__ __launch_bounds__(256) void tail_reduce_kernel(const float* __restric
   for (int c = 0; c < 4; ++c) {
     if (n + c < K) {
       const size_t idx = static_cast<size_t>(m) * K + n + c;
+      const float r = finish(a[c], bias, relu, n + c);
       if (OUT_BF16)
-        static_cast<unsigned short*>(out)[idx] = to_bf16_bits(a[c]);
+        static_cast<unsigned short*>(out)[idx] = to_bf16_bits(r);
       else
-        static_cast<float*>(out)[idx] = a[c];
+        static_cast<float*>(out)[idx] = r;
     }
   }
 }
@@ -787,10 +791,12 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
     const int rest = ((p.M + T::BM - 1) / T::BM) * ((p.K + T::BN - 1) / T::BN) - tail.n_main;
     hipLaunchKernelGGL((tail_reduce_kernel<T::BM, T::BN, OUT_BF16>),
                        dim3(rest, T::BM * T::BN / 1024), dim3(256), 0, stream, partial, p.out, p.M,
-                       p.K, Kg_p / T::BK, tail);
+                       p.K, Kg_p / T::BK, tail, p.bias, p.relu);
     return hipGetLastError();
   }
-  if (splits > 1) return launch_split_reduce(partial, p.out, p.M * p.K, splits, OUT_BF16, stream);
+  if (splits > 1)
+    return launch_split_reduce(partial, p.out, p.M * p.K, splits, OUT_BF16, p.bias, p.relu, p.K,
+                               stream);
   return hipSuccess;
 }
 
@@ -1141,9 +1147,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
         if (row < p.M && col < p.K) {
           const size_t idx = static_cast<size_t>(row) * p.K + col;
           if (OUT_BF16)
-            static_cast<unsigned short*>(p.out)[idx] = to_bf16_bits(acc[i][j][v]);
+            static_cast<unsigned short*>(p.out)[idx] =
+                to_bf16_bits(finish(acc[i][j][v], p.bias, p.relu, col));
           else
-            static_cast<float*>(p.out)[idx] = acc[i][j][v];
+            static_cast<float*>(p.out)[idx] = finish(acc[i][j][v], p.bias, p.relu, col);
         }
       }
     }

@@ -140,7 +140,9 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
 __global__ __launch_bounds__(256) void output_transform_kernel(const float* __restrict__ mt,
                                                                float* __restrict__ out, int N,
                                                                int P, int Q, int K, int TH,
-                                                               int TW) {
+                                                               int TW,
+                                                               const float* __restrict__ bias,
+                                                               int relu) {
   const int kv = K / 4;
   const long long tiles = static_cast<long long>(N) * TH * TW;
   const long long idx = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
@@ -168,8 +170,12 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
   for (int i = 0; i < 2; ++i) {
     const int op = 2 * th + i;
     if (op >= P) continue;
-    const float4 y0 = add4(add4(t[i][0], t[i][1]), t[i][2]);
-    const float4 y1 = sub4(sub4(t[i][1], t[i][2]), t[i][3]);
+    float4 y0 = add4(add4(t[i][0], t[i][1]), t[i][2]);
+    float4 y1 = sub4(sub4(t[i][1], t[i][2]), t[i][3]);
+    y0 = float4{finish(y0.x, bias, relu, k), finish(y0.y, bias, relu, k + 1),
+                finish(y0.z, bias, relu, k + 2), finish(y0.w, bias, relu, k + 3)};
+    y1 = float4{finish(y1.x, bias, relu, k), finish(y1.y, bias, relu, k + 1),
+                finish(y1.z, bias, relu, k + 2), finish(y1.w, bias, relu, k + 3)};
     float* row = out + ((static_cast<size_t>(n) * P + op) * Q) * K + k;
     const int oq = 2 * tw;
     *reinterpret_cast<float4*>(row + static_cast<size_t>(oq) * K) = y0;
@@ -260,7 +266,7 @@ hipError_t launch_winograd(const Problem& p, int gemm_tile, hipStream_t stream) 
   const long long othreads = pl.tiles * (p.K / 4);
   hipLaunchKernelGGL(output_transform_kernel, dim3(static_cast<unsigned>((othreads + 255) / 256)),
                      dim3(256), 0, stream, mt, static_cast<float*>(p.out), p.N, p.P, p.Q, p.K,
-                     pl.TH, pl.TW);
+                     pl.TH, pl.TW, p.bias, p.relu);
   return hipGetLastError();
 }
 

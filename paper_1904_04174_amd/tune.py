@@ -75,9 +75,36 @@ def tune_layer(torch, layer, in_dtype, repeats=2):
     return rows
 
 
+FAMILIES = (
+    ("register-staged implicit GEMM", lambda n: n.startswith("igemm_") and not n.startswith(
+        ("igemm_dma_", "igemm_patch_"))),
+    ("direct-to-LDS implicit GEMM", lambda n: n.startswith("igemm_dma_")),
+    ("LDS-resident patch", lambda n: n.startswith("igemm_patch_")),
+    ("Winograd F(2x2,3x3)", lambda n: n.startswith("winograd2x2_")),
+)
+
+
+def family_report(results):
+    """Markdown table: per layer the best time of each kernel family (the per-layer algorithm
+    comparison of the paper's Figure 1, for this library's families)."""
+    lines = ["dtype | layer | GFLOP | " + " | ".join(f for f, _ in FAMILIES) + " | best variant",
+             "---|---|---|" + "---|" * len(FAMILIES) + "---"]
+    for dt, name, gflop, rows in results:
+        cells = []
+        for _, pred in FAMILIES:
+            mine = [ms for _, ms, n in rows if pred(n)]
+            cells.append("%.1f us (%.1f TFLOP/s)" % (min(mine) * 1e3, gflop / min(mine))
+                         if mine else "-")
+        best = min(rows, key=lambda r: r[1])
+        lines.append("%s | %s | %.2f | %s | %s" % (dt, name, gflop, " | ".join(cells), best[2]))
+    return "\n".join(lines) + "\n"
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
     ap.add_argument("--out", required=True, help="path of the table to write")
+    ap.add_argument("--report", default=None,
+                    help="also write a markdown table of the best time per kernel family and layer")
     args = ap.parse_args(argv)
     import torch
     if not torch.cuda.is_available():
@@ -92,6 +119,7 @@ def main(argv=None):
         "// fastest variant is a Winograd one has that row first, then its best direct-sum variant.",
     ]
     seen = set()
+    results = []
     for in_dtype, names in ((B.F32, f32), (B.BF16, bf16)):
         for name in names:
             L = wl.ALL_LAYERS[name]
@@ -102,6 +130,10 @@ def main(argv=None):
             rows = tune_layer(torch, L, in_dtype)
             if not rows:
                 continue
+            g = B.conv2d_get_geometry(B.params_of_layer(L, in_dtype, B.F32))
+            gflop = 2e-9 * L.batch * g.out_rows * g.out_cols * L.features * L.window_rows * \
+                L.window_cols * L.channels
+            results.append(("bf16" if in_dtype == B.BF16 else "f32", name, gflop, rows))
             # the best variant overall goes first if it is a transform (Winograd) variant and
             # wins by the margin; the best direct-sum variant always gets a row
             direct = [r for r in rows if not r[2].startswith("winograd")]
@@ -121,6 +153,10 @@ def main(argv=None):
     with open(args.out, "w") as fh:
         fh.write("\n".join(lines) + "\n")
     print("wrote", args.out)
+    if args.report:
+        with open(args.report, "w") as fh:
+            fh.write(family_report(results))
+        print("wrote", args.report)
 
 
 if __name__ == "__main__":

@@ -269,3 +269,16 @@ def test_variant_names_are_unique():
     names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
     assert len(set(names)) == len(names)
     assert B.conv2d_variant_name(-1) is None and B.conv2d_variant_name(len(names)) is None
+
+
+def test_bias_act_arguments_are_validated_before_any_launch():
+    p = B.make_params(1, 8, 8, 4, 4, 3, 3)
+    l = B.lib()
+    call = lambda bias, act, x=16: l.conv2d_forward_bias_act(ctypes.byref(p), x, 16, bias, act, 16,
+                                                             0, 0, 0)
+    assert call(0, 2) == B.STATUS_INVALID_ARGUMENT       # unknown activation
+    assert call(0, -1) == B.STATUS_INVALID_ARGUMENT
+    assert call(18, B.ACT_RELU) == B.STATUS_INVALID_ARGUMENT   # bias not 4-byte aligned
+    assert call(16, B.ACT_RELU, x=0) == B.STATUS_INVALID_ARGUMENT  # null input
+    empty = B.make_params(0, 8, 8, 4, 4, 3, 3)
+    assert l.conv2d_forward_bias_act(ctypes.byref(empty), 0, 0, 0, B.ACT_RELU, 0, 0, 0, 0) == 0

@@ -331,3 +331,51 @@ def test_generators_are_seeded():
     assert np.all(np.abs(a[0]) <= 1.0)
     ints = wl.make_inputs(layer, dist="ints")[0]
     assert np.array_equal(ints, np.round(ints)) and ints.min() >= -4 and ints.max() <= 4
+
+
+# ------------------------------------------------------------------ fused bias + activation
+
+def test_bias_act_hand_example(oracle):
+    # 1x1 window, one channel, weight 2: out = max(2*x + bias, 0)
+    x = np.array([-1.0, 3.0, 0.25, -0.5], np.float32).reshape(1, 2, 2, 1)
+    f = np.array([2.0], np.float32).reshape(1, 1, 1, 1)
+    b = np.array([-1.0], np.float32)
+    got = oracle.forward_bias_act_f32(x, f, b, relu=True)
+    assert got.reshape(-1).tolist() == [0.0, 5.0, 0.0, 0.0]
+    got = oracle.forward_bias_act_f32(x, f, b, relu=False)
+    assert got.reshape(-1).tolist() == [-3.0, 5.0, -0.5, -2.0]
+
+
+def test_bias_act_reduces_to_the_plain_convolution(oracle):
+    x, f = wl.make_case((2, 7, 6, 5), (3, 3, 5, 4), "uniform", 31)
+    plain = oracle.forward_f32(x, f, 1, wl.PAD_SAME)
+    assert np.array_equal(oracle.forward_bias_act_f32(x, f, None, False, 1, wl.PAD_SAME), plain)
+    zero = np.zeros(4, np.float32)
+    assert np.array_equal(oracle.forward_bias_act_f32(x, f, zero, False, 1, wl.PAD_SAME), plain)
+
+
+def test_bias_act_zero_filter_broadcasts_the_bias(oracle):
+    x, f = wl.make_case((1, 5, 5, 3), (3, 3, 3, 6), "uniform", 32)
+    b = np.array([-2.0, -0.5, 0.0, 0.5, 1.0, 3.0], np.float32)
+    got = oracle.forward_bias_act_f32(x, np.zeros_like(f), b, True, 2, wl.PAD_SAME)
+    assert got.shape == (1, 3, 3, 6)
+    assert np.array_equal(got, np.broadcast_to(np.maximum(b, 0), got.shape))
+
+
+def test_bias_act_against_brute_force(oracle):
+    rng = np.random.default_rng(33)
+    x = rng.integers(-3, 4, (1, 4, 5, 2)).astype(np.float32)
+    f = rng.integers(-3, 4, (2, 3, 2, 3)).astype(np.float32)
+    b = rng.integers(-5, 6, 3).astype(np.float32)
+    got = oracle.forward_bias_act_f32(x, f, b, True, 1, wl.PAD_VALID)
+    want = np.zeros((1, 3, 3, 3))
+    for p in range(3):
+        for q in range(3):
+            for k in range(3):
+                acc = float(b[k])
+                for r in range(2):
+                    for s in range(3):
+                        for c in range(2):
+                            acc += float(x[0, p + r, q + s, c]) * float(f[r, s, c, k])
+                want[0, p, q, k] = max(acc, 0.0)
+    assert np.array_equal(got, want.astype(np.float32))

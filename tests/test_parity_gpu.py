@@ -386,3 +386,80 @@ def test_winograd_integer_inputs_bit_exact(torch_cuda, oracle, pad):
     for vid in ids:
         _say("winograd ints %s variant %s" % (case, B.conv2d_variant_name(vid)))
         assert np.array_equal(run_gpu(torch_cuda, p, x, f, vid), want), B.conv2d_variant_name(vid)
+
+
+# ------------------------------------------------------------------ fused bias + activation
+
+def run_gpu_fused(torch, params, x, f, bias, activation, force=None):
+    """conv2d_forward_bias_act on numpy inputs.  `force`: variant id put into the library's
+    CONV2D_FORCE_VARIANT environment switch for the call (the fused entry point has no
+    forced-variant twin)."""
+    import os
+    dev = torch.device("cuda:0")
+    in_dt = torch.float32 if params.in_dtype == B.F32 else torch.bfloat16
+    xd = torch.from_numpy(x).to(dev).to(in_dt).contiguous()
+    fd = torch.from_numpy(f).to(dev).to(in_dt).contiguous()
+    bd = None if bias is None else torch.from_numpy(bias).to(dev)
+    ws = None
+    if force is not None:
+        need = B.conv2d_workspace_size(params, force)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+        os.environ["CONV2D_FORCE_VARIANT"] = str(force)
+    try:
+        out = B.conv2d_forward_bias_act(params, xd, fd, bd, activation, workspace=ws)
+        torch.cuda.synchronize()
+    finally:
+        os.environ.pop("CONV2D_FORCE_VARIANT", None)
+    return out.float().cpu().numpy()
+
+
+FUSED_SMALL = [SMALL[1], SMALL[3], SMALL[5], SMALL[7], SMALL[13], SMALL[14], SMALL[15], SMALL[17]]
+
+
+@pytest.mark.parametrize("case", FUSED_SMALL)
+def test_bias_relu_every_variant_fp32(torch_cuda, oracle, case):
+    """out = max(conv + bias, 0) through every variant that supports the case (split-reduction,
+    balanced-tail and Winograd variants apply the epilogue in their last kernel)."""
+    n, h, w, c, k, r, s, sr, sc, pad = case
+    x, f = wl.make_case((n, h, w, c), (r, s, c, k), "uniform", 9500 + sum(case))
+    bias = np.random.default_rng(9600 + sum(case)).uniform(-2, 2, k).astype(np.float32)
+    want = oracle.forward_bias_act_f32(x, f, bias, True, (sr, sc), pad)
+    want_lin = oracle.forward_bias_act_f32(x, f, bias, False, (sr, sc), pad)
+    assert (want == 0).any() and (want > 0).any()
+    p = _params(case)
+    for vid in supported_variants(p):
+        _say("bias+relu case %s variant %s" % (case, B.conv2d_variant_name(vid)))
+        got = run_gpu_fused(torch_cuda, p, x, f, bias, B.ACT_RELU, vid)
+        # where the pre-activation is within the tolerance of zero either side of the clamp is right
+        err = np.abs(got.astype(np.float64) - want) / (np.abs(want) + 1.0)
+        near_zero = np.abs(want_lin) <= 2 * TOL_F32
+        assert float(err[~near_zero].max()) <= TOL_F32, (case, B.conv2d_variant_name(vid))
+        assert float(np.abs(got[near_zero]).max(initial=0.0)) <= 4 * TOL_F32
+        assert (got >= 0).all()
+    got = run_gpu_fused(torch_cuda, p, x, f, bias, B.ACT_NONE)
+    assert rel_err(got, want_lin) <= TOL_F32
+    got = run_gpu_fused(torch_cuda, p, x, f, None, B.ACT_NONE)
+    assert rel_err(got, oracle.forward_f32(x, f, (sr, sc), pad)) <= TOL_F32
+
+
+@pytest.mark.parametrize("name", ["V56-N16", "V28-N16", "V14-N1", "R1x1a", "R7x7"])
+def test_bias_relu_full_size(torch_cuda, oracle, name):
+    """Full-size layers with the automatic selection (Winograd on the deep 3x3 layers) and with
+    the best direct-sum variant; bf16 inputs with bf16 output for the layers in that list."""
+    L = wl.LAYERS[name]
+    x, f = wl.make_inputs(L)
+    bias = np.random.default_rng(9700).normal(0, 1, L.features).astype(np.float32)
+    strides = (L.stride_rows, L.stride_cols)
+    want = oracle.forward_bias_act_f32(x, f, bias, True, strides, L.padding)
+    p = B.params_of_layer(L)
+    for vid in (None, B.conv2d_select_variant(p, B.SELECT_DIRECT_SUM_ONLY)):
+        _say("bias+relu %s variant %s" % (name, "auto" if vid is None else B.conv2d_variant_name(vid)))
+        got = run_gpu_fused(torch_cuda, p, x, f, bias, B.ACT_RELU, vid)
+        assert rel_err(got, want) <= 2 * TOL_F32, name   # clamp decided by an fp32 sum near zero
+    if name in wl.BF16_LAYERS:
+        xb, _ = wl.round_to_bf16(x)
+        fb, _ = wl.round_to_bf16(f)
+        pb = B.params_of_layer(L, B.BF16, B.BF16)
+        want = oracle.forward_bias_act_f32(xb, fb, bias, True, strides, L.padding)
+        got = run_gpu_fused(torch_cuda, pb, xb, fb, bias, B.ACT_RELU)
+        assert rel_err(got, want) <= TOL_BF16, name
