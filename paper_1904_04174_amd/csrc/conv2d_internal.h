@@ -37,9 +37,16 @@ struct Problem {
   long long in_stride, filt_stride, out_stride;
 };
 
-// The fused epilogue on one finished sum (feature index `col`).  A NaN sum stays NaN.
-__device__ __forceinline__ float finish(float v, const float* __restrict__ bias, int relu, int col) {
-  if (bias) v += bias[col];
+// The fused epilogue on one finished sum of feature `col`.  A NaN sum stays
+// NaN.  Tile epilogues fetch the bias of their column once (bias_of) and
+// apply it to all rows (finish with the value): the output stores in between
+// may alias the bias as far as the compiler knows, so a load per element
+// would not be hoisted.
+__device__ __forceinline__ float bias_of(const float* __restrict__ bias, int col, int K) {
+  return (bias && col < K) ? bias[col] : 0.f;
+}
+__device__ __forceinline__ float finish(float v, float bias_value, int relu) {
+  v += bias_value;
   if (relu) v = v < 0.f ? 0.f : v;
   return v;
 }

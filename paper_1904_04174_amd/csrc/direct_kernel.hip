@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void direct_kernel(Problem p) {
         }
       }
     }
-    acc = finish(acc, p.bias, p.relu, k);
+    acc = finish(acc, bias_of(p.bias, k, p.K), p.relu);
     if (OUT_BF16)
       static_cast<unsigned short*>(p.out)[idx] = float_to_bf16_bits(acc);
     else

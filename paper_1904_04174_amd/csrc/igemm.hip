@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(const float* __restri
   const int col = i0 % K;
   float a[4] = {acc.x, acc.y, acc.z, acc.w};
 #pragma unroll
-  for (int c = 0; c < 4; ++c) a[c] = finish(a[c], bias, relu, (col + c) % K);
+  for (int c = 0; c < 4; ++c) a[c] = finish(a[c], bias_of(bias, (col + c) % K, K), relu);
   acc = float4{a[0], a[1], a[2], a[3]};
   if (vec) {
     if (OUT_BF16) {
@@ -468,6 +468,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
     for (int j = 0; j < T::TN; ++j) {
       const int col = n0 + wn * T::WN + j * 32 + lr;
       const int rbase = m0 + wm * T::WM + i * 32 + lk * 4;
+      const float bcol = bias_of(p.bias, col, p.K);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = rbase + 8 * (v / 4) + (v % 4);
@@ -477,9 +478,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
             part[idx] = acc[i][j][v];
           else if (OUT_BF16)
             static_cast<unsigned short*>(p.out)[idx] =
-                to_bf16_bits(finish(acc[i][j][v], p.bias, p.relu, col));
+                to_bf16_bits(finish(acc[i][j][v], bcol, p.relu));
           else
-            static_cast<float*>(p.out)[idx] = finish(acc[i][j][v], p.bias, p.relu, col);
+            static_cast<float*>(p.out)[idx] = finish(acc[i][j][v], bcol, p.relu);
         }
       }
     }

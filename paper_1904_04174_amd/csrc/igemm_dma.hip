@@ -646,6 +646,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
     for (int j = 0; j < TN; ++j) {
       const int col = n0 + wn * T::WN + j * 32 + lr;
       const int rbase = m0 + wm * T::WM + i * 32 + lk * 4;
+      const float bcol = bias_of(p.bias, col, p.K);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = rbase + 8 * (v / 4) + (v % 4);
@@ -655,10 +656,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
             part[idx] = acc[i][j][v];
           else if (OUT_BF16)
             static_cast<unsigned short*>(p.out)[bz * p.out_stride + idx] =
-                to_bf16_bits(finish(acc[i][j][v], p.bias, p.relu, col));
+                to_bf16_bits(finish(acc[i][j][v], bcol, p.relu));
           else
             static_cast<float*>(p.out)[bz * p.out_stride + idx] =
-                finish(acc[i][j][v], p.bias, p.relu, col);
+                finish(acc[i][j][v], bcol, p.relu);
         }
       }
     }
@@ -700,7 +701,7 @@ __global__ __launch_bounds__(256) void tail_reduce_kernel(const float* __restric
   for (int c = 0; c < 4; ++c) {
     if (n + c < K) {
       const size_t idx = static_cast<size_t>(m) * K + n + c;
-      const float r = finish(a[c], bias, relu, n + c);
+      const float r = finish(a[c], bias_of(bias, n + c, K), relu);
       if (OUT_BF16)
         static_cast<unsigned short*>(out)[idx] = to_bf16_bits(r);
       else
@@ -1141,6 +1142,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
     for (int j = 0; j < TN; ++j) {
       const int col = n0 + wn * T::WN + j * 32 + lr;
       const int rbase = m0 + wm * T::WM + i * 32 + lk * 4;
+      const float bcol = bias_of(p.bias, col, p.K);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = rbase + 8 * (v / 4) + (v % 4);
@@ -1148,9 +1150,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
           const size_t idx = static_cast<size_t>(row) * p.K + col;
           if (OUT_BF16)
             static_cast<unsigned short*>(p.out)[idx] =
-                to_bf16_bits(finish(acc[i][j][v], p.bias, p.relu, col));
+                to_bf16_bits(finish(acc[i][j][v], bcol, p.relu));
           else
-            static_cast<float*>(p.out)[idx] = finish(acc[i][j][v], p.bias, p.relu, col);
+            static_cast<float*>(p.out)[idx] = finish(acc[i][j][v], bcol, p.relu);
         }
       }
     }

@@ -166,16 +166,18 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
     t[0][b] = add4(add4(m[0][b], m[1][b]), m[2][b]);
     t[1][b] = sub4(sub4(m[1][b], m[2][b]), m[3][b]);
   }
+  const float4 b = bias ? float4{bias[k], bias[k + 1], bias[k + 2], bias[k + 3]}
+                        : float4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int op = 2 * th + i;
     if (op >= P) continue;
     float4 y0 = add4(add4(t[i][0], t[i][1]), t[i][2]);
     float4 y1 = sub4(sub4(t[i][1], t[i][2]), t[i][3]);
-    y0 = float4{finish(y0.x, bias, relu, k), finish(y0.y, bias, relu, k + 1),
-                finish(y0.z, bias, relu, k + 2), finish(y0.w, bias, relu, k + 3)};
-    y1 = float4{finish(y1.x, bias, relu, k), finish(y1.y, bias, relu, k + 1),
-                finish(y1.z, bias, relu, k + 2), finish(y1.w, bias, relu, k + 3)};
+    y0 = float4{finish(y0.x, b.x, relu), finish(y0.y, b.y, relu), finish(y0.z, b.z, relu),
+                finish(y0.w, b.w, relu)};
+    y1 = float4{finish(y1.x, b.x, relu), finish(y1.y, b.y, relu), finish(y1.z, b.z, relu),
+                finish(y1.w, b.w, relu)};
     float* row = out + ((static_cast<size_t>(n) * P + op) * Q) * K + k;
     const int oq = 2 * tw;
     *reinterpret_cast<float4*>(row + static_cast<size_t>(oq) * K) = y0;
