@@ -54,6 +54,9 @@
 extern "C" {
 #endif
 
+/* The library is built with hidden visibility; these are its only exports. */
+#define CONV2D_API __attribute__((visibility("default")))
+
 typedef enum { CONV2D_PAD_VALID = 0, CONV2D_PAD_SAME = 1 } conv2d_padding_t;
 typedef enum { CONV2D_F32 = 0, CONV2D_BF16 = 1 } conv2d_dtype_t;
 
@@ -89,16 +92,16 @@ typedef struct {
 
 /* Output size and padding for `params` (host only, touches no GPU).
  * INVALID_ARGUMENT if the tuple has no valid output. */
-int conv2d_get_geometry(const conv2d_params* params, conv2d_geometry* geometry);
+CONV2D_API int conv2d_get_geometry(const conv2d_params* params, conv2d_geometry* geometry);
 
 /* Bytes of device scratch that conv2d_forward may use for `params` with the
  * variant it would select (0 for most layers; non-zero when the reduction
  * over window and channels is split across workgroups, or the filter is
  * repacked).  Host only. */
-int conv2d_workspace_size(const conv2d_params* params, size_t* bytes);
+CONV2D_API int conv2d_workspace_size(const conv2d_params* params, size_t* bytes);
 
 /* Same, for a forced variant.  UNSUPPORTED if the variant cannot run `params`. */
-int conv2d_workspace_size_variant(const conv2d_params* params, int variant_id, size_t* bytes);
+CONV2D_API int conv2d_workspace_size_variant(const conv2d_params* params, int variant_id, size_t* bytes);
 
 /* Forward convolution with the variant the selector picks for the layer
  * shape (section 3: algorithm and parameter choice per shape).
@@ -109,14 +112,14 @@ int conv2d_workspace_size_variant(const conv2d_params* params, int variant_id, s
  *                   256-byte aligned, or NULL when that size is 0.  Contents
  *                   are undefined afterwards.
  * Enqueues on hip_stream and returns.  batch == 0 returns OK without a launch. */
-int conv2d_forward(const conv2d_params* params, const void* in, const void* filt, void* out,
+CONV2D_API int conv2d_forward(const conv2d_params* params, const void* in, const void* filt, void* out,
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Same, with the variant forced (0 <= variant_id < conv2d_num_variants()).
  * Every variant that supports `params` produces the same result up to the
  * order of floating-point summation (the Winograd variants: up to the
  * rounding of their transforms, within the same tolerance).  UNSUPPORTED if it cannot run them. */
-int conv2d_forward_variant(const conv2d_params* params, const void* in, const void* filt,
+CONV2D_API int conv2d_forward_variant(const conv2d_params* params, const void* in, const void* filt,
                            void* out, void* workspace, size_t workspace_bytes, void* hip_stream,
                            int variant_id);
 
@@ -133,16 +136,16 @@ int conv2d_forward_variant(const conv2d_params* params, const void* in, const vo
  * selection, workspace and other rules as conv2d_forward; INVALID_ARGUMENT
  * for an unknown activation or a misaligned bias pointer. */
 typedef enum { CONV2D_ACT_NONE = 0, CONV2D_ACT_RELU = 1 } conv2d_activation_t;
-int conv2d_forward_bias_act(const conv2d_params* params, const void* in, const void* filt,
+CONV2D_API int conv2d_forward_bias_act(const conv2d_params* params, const void* in, const void* filt,
                             const float* bias, int activation, void* out, void* workspace,
                             size_t workspace_bytes, void* hip_stream);
 
 /* Variant introspection (host only). */
-int conv2d_num_variants(void);
-const char* conv2d_variant_name(int variant_id);            /* NULL if out of range */
-int conv2d_variant_supports(const conv2d_params* params, int variant_id); /* 1, 0, or <0 status */
+CONV2D_API int conv2d_num_variants(void);
+CONV2D_API const char* conv2d_variant_name(int variant_id);            /* NULL if out of range */
+CONV2D_API int conv2d_variant_supports(const conv2d_params* params, int variant_id); /* 1, 0, or <0 status */
 /* The variant conv2d_forward would use, assuming 16-byte-aligned pointers. */
-int conv2d_selected_variant(const conv2d_params* params, int* variant_id);
+CONV2D_API int conv2d_selected_variant(const conv2d_params* params, int* variant_id);
 
 /* Selection with a restriction.  The paper's library holds, next to the
  * algorithms that sum the window directly, a Winograd algorithm that reaches
@@ -154,10 +157,10 @@ int conv2d_selected_variant(const conv2d_params* params, int* variant_id);
  * caller that wants a small workspace or counts the executed multiplications.
  * INVALID_ARGUMENT for unknown flag bits.  Host only. */
 #define CONV2D_SELECT_DIRECT_SUM_ONLY 1u
-int conv2d_select_variant(const conv2d_params* params, uint32_t flags, int* variant_id);
+CONV2D_API int conv2d_select_variant(const conv2d_params* params, uint32_t flags, int* variant_id);
 
-const char* conv2d_status_string(int status);
-int conv2d_version(void);
+CONV2D_API const char* conv2d_status_string(int status);
+CONV2D_API int conv2d_version(void);
 
 #ifdef __cplusplus
 }
