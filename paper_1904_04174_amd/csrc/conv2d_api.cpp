@@ -21,7 +21,7 @@ namespace {
 constexpr long long kMaxElems = (1LL << 31) - 1;
 
 enum Family { kDirect = 0, kIgemm = 1, kDma = 2, kWinograd = 3 };
-enum Split { kWhole = 0, kSplit = 1, kTail = 2 };
+enum Split { kWhole = 0, kSplit = 1, kTail = 2, kFused = 3 };
 
 struct Variant {
   Family family;
@@ -67,6 +67,12 @@ struct Table {
       // "igemm_dma_f32_64x64_..." -> "winograd2x2_f32_64x64_..."
       std::snprintf(base, sizeof(base), "winograd2x2_%s", igemm_dma_tile_name(0, t) + 10);
       add(kWinograd, 0, t, kWhole, base);
+      if (igemm_dma_tile_has_wino(0, t)) {
+        // products and output transform fused in one launch (the split field marks it)
+        std::snprintf(base, sizeof(base), "winograd2x2_fused_%s", igemm_dma_tile_name(0, t) + 10);
+        add(kWinograd, 0, t, kWhole, base);
+        v[n - 1].split = kFused;
+      }
     }
   }
 };
@@ -161,7 +167,7 @@ bool supports(const Variant& v, const Problem& q) {
   if (!q.in_bf16 && q.out_bf16) return false;
   // buffer addressing needs input and filter below 2^31 bytes
   if (1LL * es * q.N * q.H * q.W * q.C >= (1LL << 31)) return false;
-  if (v.family == kWinograd) return winograd_supports(q, v.tile);
+  if (v.family == kWinograd) return winograd_supports(q, v.tile, v.split == kFused);
   int bm, bn, bk;
   tile_shape(v, &bm, &bn, &bk);
   if (v.family == kIgemm) {
@@ -281,14 +287,17 @@ double winograd_cost(const Variant& v, const Problem& q) {
   g.Kg = q.C;
   Variant inner = v;
   inner.family = kDma;
+  inner.split = kWhole;
+  const bool fused = v.split == kFused;  // products folded into the output: no Mt
   const double memory_rate = 2000.0;  // bytes per clock from HBM
-  const double v_bytes = 4.0 * 16 * tiles * q.C, m_bytes = 4.0 * 16 * tiles * q.K;
+  const double v_bytes = 4.0 * 16 * tiles * q.C;
+  const double m_bytes = fused ? 0.0 : 4.0 * 16 * tiles * q.K;
   double product = model_cost(inner, g);
   const double product_stream = (v_bytes + m_bytes) / memory_rate;
   if (product < product_stream) product = product_stream;
   const double transforms =
       (4.0 * q.N * q.H * q.W * q.C + v_bytes + m_bytes + 4.0 * q.M * q.K) / memory_rate;
-  return product + transforms + 3 * kLaunchCycles;
+  return product + transforms + (fused ? 2 : 3) * kLaunchCycles;
 }
 
 double model_cost(const Variant& v, const Problem& q) {
@@ -426,7 +435,7 @@ int select_uncached(const Problem& q, int padding, bool aligned, bool direct_sum
 }
 
 size_t workspace_bytes_for(const Variant& v, const Problem& q) {
-  if (v.family == kWinograd) return winograd_workspace_bytes(q, v.tile);
+  if (v.family == kWinograd) return winograd_workspace_bytes(q, v.tile, v.split == kFused);
   if (v.family == kDma) return igemm_dma_workspace_bytes(q, v.bf16, v.tile, split_factor(v, q));
   if (v.family == kIgemm && v.split)
     return static_cast<size_t>(split_factor(v, q)) * q.M * q.K * sizeof(float);
@@ -482,7 +491,9 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     case kDma:
       e = launch_igemm_dma(q, tb.v[id].bf16, tb.v[id].tile, split_factor(tb.v[id], q), stream);
       break;
-    case kWinograd: e = launch_winograd(q, tb.v[id].tile, stream); break;
+    case kWinograd:
+      e = launch_winograd(q, tb.v[id].tile, tb.v[id].split == kFused, stream);
+      break;
   }
   return e == hipSuccess ? CONV2D_STATUS_OK : CONV2D_STATUS_LAUNCH_FAILED;
 }

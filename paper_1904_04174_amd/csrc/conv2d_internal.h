@@ -35,6 +35,9 @@ struct Problem {
   // shape whose input, filter and output start `*_stride` elements apart.
   int batches;
   long long in_stride, filt_stride, out_stride;
+  // Winograd product with fused output transform (see launch_igemm_dma_wino):
+  // tiles per image column and row, and the real output size.
+  int wino_th, wino_tw, wino_p, wino_q;
 };
 
 // The fused epilogue on one finished sum of feature `col`.  A NaN sum stays
@@ -94,13 +97,28 @@ bool igemm_dma_tile_fits(const Problem& p, int bf16, int tile);  // extra shape 
 size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile, int splits);
 hipError_t launch_igemm_dma(const Problem& p, int bf16, int tile, int splits, hipStream_t stream);
 
+// The Winograd F(2x2, 3x3) point products with the output transform folded
+// in, on a direct-to-LDS tile that has such an instantiation
+// (igemm_dma_tile_has_wino).  `p` describes the transformed input V as an
+// image of 16 rows (the points) by `tiles` columns and the transformed
+// filter U as a 16x1 window (VALID, stride 1), so that the reduction runs
+// point by point over the channels; every C / bk slices the kernel folds the
+// finished point product into the four output pixels of each tile with the
+// signs of A^T (x) A^T, and the epilogue stores those (p.wino_* give the
+// tiling and the real output size, p.out the NHWC output).  Needs C a
+// multiple of bk.  Workspace: the repacked U (igemm_dma_workspace_bytes(p, ..., 1)).
+bool igemm_dma_tile_has_wino(int bf16, int tile);
+hipError_t launch_igemm_dma_wino(const Problem& p, int bf16, int tile, hipStream_t stream);
+
 // Winograd F(2x2, 3x3), fp32, stride 1: filter, input and output transforms
 // around one batched launch of direct-to-LDS tile `gemm_tile` (addressing kind
 // 0 or 1) for the 16 point-wise matrix products.  The workspace holds the
 // transformed filter, input and products and the batched launch's own
 // workspace.
-bool winograd_supports(const Problem& p, int gemm_tile);
-size_t winograd_workspace_bytes(const Problem& p, int gemm_tile);
-hipError_t launch_winograd(const Problem& p, int gemm_tile, hipStream_t stream);
+// `fused`: products and output transform in one launch (no Mt); needs a tile
+// with igemm_dma_tile_has_wino and C a multiple of its bk.
+bool winograd_supports(const Problem& p, int gemm_tile, bool fused);
+size_t winograd_workspace_bytes(const Problem& p, int gemm_tile, bool fused);
+hipError_t launch_winograd(const Problem& p, int gemm_tile, bool fused, hipStream_t stream);
 
 }  // namespace conv2d

@@ -247,7 +247,19 @@ struct TailPlan {
 // reduction (1 when there is a tail).  `bt` is the repacked filter, `partial`
 // the fp32 partial outputs: [split][M][K] for a split reduction, or one
 // [BM][BN] tile per tail workgroup.
-template <class T, bool OUT_BF16>
+// Signs of A^T (x) A^T for Winograd F(2x2, 3x3): contribution of point
+// t = 4a + b to output pixel 2i + j of a tile is A^T[i][a] * A^T[j][b] with
+// A^T = [[1, 1, 1, 0], [0, 1, -1, -1]].
+__constant__ float kWinoFold[16][4] = {
+    {1, 0, 0, 0},  {1, 1, 0, 0},   {1, -1, 0, 0},  {0, -1, 0, 0},
+    {1, 0, 1, 0},  {1, 1, 1, 1},   {1, -1, 1, -1}, {0, -1, 0, -1},
+    {1, 0, -1, 0}, {1, 1, -1, -1}, {1, -1, -1, 1}, {0, -1, 0, 1},
+    {0, 0, -1, 0}, {0, 0, -1, -1}, {0, 0, -1, 1},  {0, 0, 0, 1}};
+
+// WINO: the reduction is the 16 Winograd point products laid end to end
+// (flush_slices slices each); each finished product is folded into the four
+// output pixels of the tile's rows and the epilogue stores those.
+template <class T, bool OUT_BF16, bool WINO = false>
 __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem p, const int Kg_p,
                                                                   const int slices_per_split,
                                                                   const int flush_slices,
@@ -468,8 +480,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  floatx16 total[T::TWO_LEVEL ? TM : 1][T::TWO_LEVEL ? TN : 1];
-  if (T::TWO_LEVEL) {
+  constexpr bool TWO_LEVEL = T::TWO_LEVEL && !WINO;
+  floatx16 total[TWO_LEVEL ? TM : 1][TWO_LEVEL ? TN : 1];
+  if (TWO_LEVEL) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -477,6 +490,18 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
 #pragma unroll
         for (int v = 0; v < 16; ++v) total[i][j][v] = 0.f;
   }
+  floatx16 pixel[WINO ? 4 : 1][WINO ? TM : 1][WINO ? TN : 1];  // WINO: the 2x2 outputs of a tile row
+  if (WINO) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) pixel[q][i][j][v] = 0.f;
+  }
+  int wino_point = 0;
   int until_flush = flush_slices;
 
   // fragment addressing: row lr of each 32-row block, chunk (2*kk + lk) ^ swizzle
@@ -597,7 +622,31 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
           else
             step(Buf1{}, Buf0{}, u, kk, (u + 1) % S, (u + S - 1) % S);
         }
-        if (T::TWO_LEVEL) {
+        if (WINO) {
+          if (--until_flush == 0) {
+            until_flush = flush_slices;
+            const int pt = min(wino_point, 15);
+            ++wino_point;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const float sign = kWinoFold[pt][q];
+#pragma unroll
+              for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                  for (int v = 0; v < 16; ++v)
+                    pixel[q][i][j][v] = fmaf(sign, acc[i][j][v], pixel[q][i][j][v]);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+              for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+          }
+        }
+        if (TWO_LEVEL) {
           if (--until_flush == 0) {
             until_flush = flush_slices;
 #pragma unroll
@@ -615,7 +664,38 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
     }
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // drain the slices issued past the end
-  if (T::TWO_LEVEL) {
+  if (WINO) {
+    // the tile's rows are Winograd tiles (n, th, tw): four output pixels each
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn * T::WN + j * 32 + lr;
+        const int rbase = m0 + wm * T::WM + i * 32 + lk * 4;
+        const float bcol = bias_of(p.bias, col, p.K);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = rbase + 8 * (v / 4) + (v % 4);
+          if (row < p.M && col < p.K) {
+            const int tw = row % p.wino_tw;
+            const int tr = row / p.wino_tw;
+            const int th = tr % p.wino_th;
+            const int n = tr / p.wino_th;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int op = 2 * th + (q >> 1), oq = 2 * tw + (q & 1);
+              if (op < p.wino_p && oq < p.wino_q)
+                static_cast<float*>(p.out)[((static_cast<size_t>(n) * p.wino_p + op) * p.wino_q +
+                                            oq) * p.K + col] =
+                    finish(pixel[q][i][j][v], bcol, p.relu);
+            }
+          }
+        }
+      }
+    }
+    return;
+  }
+  if (TWO_LEVEL) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -805,6 +885,26 @@ template <class T>
 hipError_t launch(const Problem& p, int splits, hipStream_t stream) {
   if (T::BF16 && p.out_bf16) return launch_one<T, T::BF16>(p, splits, stream);
   return launch_one<T, false>(p, splits, stream);
+}
+
+// Winograd point products with the output transform folded in: repack of U,
+// then one workgroup per (BM Winograd tiles) x (BN features).
+template <class T>
+hipError_t launch_wino(const Problem& p, hipStream_t stream) {
+  if (p.C % T::BK != 0 || p.R != 16 || p.S != 1 || p.out_bf16) return hipErrorInvalidValue;
+  const int Kg_p = p.Kg;
+  dim3 rgrid(Kg_p / T::BK, (p.K + 63) / 64, 1);
+  hipLaunchKernelGGL((repack_filter_kernel<float>), rgrid, dim3(256), 0, stream,
+                     static_cast<const float*>(p.filt), static_cast<float*>(p.workspace), p.Kg,
+                     p.K, Kg_p, p.C, p.R * p.S, 0, T::BK, 0LL, 0LL);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int tiles = ((p.M + T::BM - 1) / T::BM) * ((p.K + T::BN - 1) / T::BN);
+  const TailPlan none = {tiles, 0, 0, 0};
+  hipLaunchKernelGGL((igemm_dma_kernel<T, false, true>), dim3(tiles, 1, 1), dim3(T::NT), 0, stream,
+                     p, Kg_p, Kg_p / T::BK, p.C / T::BK, p.workspace,
+                     static_cast<float*>(nullptr), none);
+  return hipGetLastError();
 }
 
 template <class T>
@@ -1222,6 +1322,7 @@ struct TileEntry {
   hipError_t (*fn)(const Problem&, int, hipStream_t);
   size_t (*ws)(const Problem&, int);
   bool (*fits)(const Problem&);  // extra shape condition of a tile, or null
+  hipError_t (*wino)(const Problem&, hipStream_t);  // fused Winograd products, or null
 };
 
 #define CONV2D_PATCH_TILE(dt, isbf, bm, bn, wm, wn, rows, two, occ)                              \
@@ -1229,13 +1330,21 @@ struct TileEntry {
     PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>::BK, occ, 3,                                 \
     &launch_patch<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>>,                              \
     &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>>,                     \
-    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>> }
+    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>>, nullptr }
 
 #define CONV2D_DMA_TILE(dt, isbf, bm, bn, rowb, wm, wn, st, two, occ, addr, tag)                \
   { "igemm_dma_" dt "_" #bm "x" #bn "_r" #rowb "_w" #wm "x" #wn "_s" #st tag, bm, bn,           \
     DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>::BK, occ, addr,                     \
     &launch<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>>,                           \
-    &workspace_bytes<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>>, nullptr }
+    &workspace_bytes<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>>, nullptr, nullptr }
+
+// the same with an instantiation for the fused Winograd products
+#define CONV2D_DMA_TILE_W(dt, isbf, bm, bn, rowb, wm, wn, st, two, occ, addr, tag)              \
+  { "igemm_dma_" dt "_" #bm "x" #bn "_r" #rowb "_w" #wm "x" #wn "_s" #st tag, bm, bn,           \
+    DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>::BK, occ, addr,                     \
+    &launch<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>>,                           \
+    &workspace_bytes<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>>, nullptr,         \
+    &launch_wino<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>> }
 
 const TileEntry kTilesF32[] = {
     CONV2D_PATCH_TILE("f32", false, 128, 128, 2, 2, 512, true, 1),
@@ -1246,7 +1355,7 @@ const TileEntry kTilesF32[] = {
     CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 3, true, 6, kUniform, ""),
     CONV2D_DMA_TILE("f32", false, 128, 128, 64, 2, 2, 4, true, 2, kVector, "_g"),
     CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, kVector, "_g"),
-    CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 4, true, 4, kVector, "_g"),
+    CONV2D_DMA_TILE_W("f32", false, 64, 64, 64, 2, 2, 4, true, 4, kVector, "_g"),
     CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, kElement, "_e"),
     CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 4, true, 4, kElement, "_e"),
 };
@@ -1287,6 +1396,11 @@ int igemm_dma_tile_addressing(int bf16, int tile) { return entry(bf16, tile).add
 bool igemm_dma_tile_fits(const Problem& p, int bf16, int tile) {
   const TileEntry& t = entry(bf16, tile);
   return t.fits == nullptr || t.fits(p);
+}
+bool igemm_dma_tile_has_wino(int bf16, int tile) { return entry(bf16, tile).wino != nullptr; }
+hipError_t launch_igemm_dma_wino(const Problem& p, int bf16, int tile, hipStream_t stream) {
+  const TileEntry& t = entry(bf16, tile);
+  return t.wino ? t.wino(p, stream) : hipErrorInvalidValue;
 }
 size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile, int splits) {
   return entry(bf16, tile).ws(p, splits);

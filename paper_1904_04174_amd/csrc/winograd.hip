@@ -23,6 +23,11 @@
 //      kernel (a 1x1 convolution over a 1 x tiles "image" per point)
 //   4. output_transform_kernel   Mt[16][tiles][K]   -> out[N][P][Q][K]
 //
+// "Fused" variants replace 3 and 4 by one launch of the gather kernel in its
+// Winograd mode: a workgroup runs the 16 products of its block of tiles one
+// after the other and folds each into the four output pixels with the signs
+// of A^T (x) A^T, so Mt (4x the output) never goes through memory.
+//
 // All transform entries are 0, +-1 or +-1/2, so the transforms add no
 // rounding error beyond a few ulp of their inputs; the measured error against
 // the fp64 oracle stays within the fp32 tolerance of the direct kernels
@@ -191,54 +196,67 @@ struct Plan {
   int TH, TW;
   long long tiles;
   size_t u_bytes, v_bytes, m_bytes;
-  Problem gemm;  // the batched point-wise products as a 1x1 convolution over a 1 x tiles image
+  Problem gemm;  // the point products as a problem of the direct-to-LDS gather kernel
 };
 
-Plan make_plan(const Problem& p) {
+// `fused`: the products run point after point inside one workgroup per tile
+// block, which folds each into the output pixels (no Mt): V is then an image
+// of 16 rows (points) x tiles columns and U a 16x1 window.  Otherwise: 16
+// batched 1x1 convolutions over a 1 x tiles image that write Mt.
+Plan make_plan(const Problem& p, bool fused) {
   Plan pl;
   pl.TH = (p.P + 1) / 2;
   pl.TW = (p.Q + 1) / 2;
   pl.tiles = static_cast<long long>(p.N) * pl.TH * pl.TW;
   pl.u_bytes = align256(sizeof(float) * kPoints * static_cast<size_t>(p.C) * p.K);
   pl.v_bytes = align256(sizeof(float) * kPoints * static_cast<size_t>(pl.tiles) * p.C);
-  pl.m_bytes = align256(sizeof(float) * kPoints * static_cast<size_t>(pl.tiles) * p.K);
+  pl.m_bytes = fused ? 0 : align256(sizeof(float) * kPoints * static_cast<size_t>(pl.tiles) * p.K);
   Problem g = {};
-  g.N = 1; g.H = 1; g.W = static_cast<int>(pl.tiles); g.C = p.C; g.K = p.K;
-  g.R = 1; g.S = 1; g.sr = 1; g.sc = 1; g.pt = 0; g.pl = 0;
-  g.P = 1; g.Q = g.W; g.M = g.W; g.Kg = p.C;
+  g.N = 1; g.W = static_cast<int>(pl.tiles); g.C = p.C; g.K = p.K;
+  g.sr = 1; g.sc = 1; g.pt = 0; g.pl = 0;
+  g.P = 1; g.Q = g.W; g.M = g.W;
   g.in_bf16 = 0; g.out_bf16 = 0;
-  g.batches = kPoints;
-  g.in_stride = pl.tiles * p.C;
-  g.filt_stride = static_cast<long long>(p.C) * p.K;
-  g.out_stride = pl.tiles * p.K;
+  if (fused) {
+    g.H = kPoints; g.R = kPoints; g.S = 1; g.Kg = kPoints * p.C;
+    g.wino_th = pl.TH; g.wino_tw = pl.TW; g.wino_p = p.P; g.wino_q = p.Q;
+    g.bias = p.bias; g.relu = p.relu;
+  } else {
+    g.H = 1; g.R = 1; g.S = 1; g.Kg = p.C;
+    g.batches = kPoints;
+    g.in_stride = pl.tiles * p.C;
+    g.filt_stride = static_cast<long long>(p.C) * p.K;
+    g.out_stride = pl.tiles * p.K;
+  }
   pl.gemm = g;
   return pl;
 }
 
 }  // namespace
 
-bool winograd_supports(const Problem& p, int gemm_tile) {
+bool winograd_supports(const Problem& p, int gemm_tile, bool fused) {
   if (p.in_bf16 || p.out_bf16) return false;
   if (p.R != 3 || p.S != 3 || p.sr != 1 || p.sc != 1) return false;
   if (p.C % 4 != 0 || p.K % 4 != 0 || p.M == 0) return false;
-  const Plan pl = make_plan(p);
-  // one point's matrices must fit the 31-bit byte offsets of the product kernel
-  if (pl.tiles * p.C * 4 >= (1LL << 31) || pl.tiles * p.K * 4 >= (1LL << 31)) return false;
-  if (4LL * (p.C + 64) * p.K >= (1LL << 31)) return false;
+  const Plan pl = make_plan(p, fused);
   const int addressing = igemm_dma_tile_addressing(0, gemm_tile);
   int bm, bn, bk;
   igemm_dma_tile_shape(0, gemm_tile, &bm, &bn, &bk);
+  // the products' operands must fit the 31-bit byte offsets of the gather kernel
+  const long long points = fused ? kPoints : 1;
+  if (points * pl.tiles * p.C * 4 >= (1LL << 31) || pl.tiles * p.K * 4 >= (1LL << 31)) return false;
+  if (4LL * (points * p.C + bk) * p.K >= (1LL << 31)) return false;
+  if (fused) return igemm_dma_tile_has_wino(0, gemm_tile) && p.C % bk == 0;
   if (addressing == 0) return p.C % bk == 0;
   return addressing == 1;
 }
 
-size_t winograd_workspace_bytes(const Problem& p, int gemm_tile) {
-  const Plan pl = make_plan(p);
+size_t winograd_workspace_bytes(const Problem& p, int gemm_tile, bool fused) {
+  const Plan pl = make_plan(p, fused);
   return pl.u_bytes + pl.v_bytes + pl.m_bytes + igemm_dma_workspace_bytes(pl.gemm, 0, gemm_tile, 1);
 }
 
-hipError_t launch_winograd(const Problem& p, int gemm_tile, hipStream_t stream) {
-  Plan pl = make_plan(p);
+hipError_t launch_winograd(const Problem& p, int gemm_tile, bool fused, hipStream_t stream) {
+  Plan pl = make_plan(p, fused);
   unsigned char* ws = static_cast<unsigned char*>(p.workspace);
   float* u = reinterpret_cast<float*>(ws);
   float* v = reinterpret_cast<float*>(ws + pl.u_bytes);
@@ -260,8 +278,12 @@ hipError_t launch_winograd(const Problem& p, int gemm_tile, hipStream_t stream) 
 
   pl.gemm.in = v;
   pl.gemm.filt = u;
-  pl.gemm.out = mt;
   pl.gemm.workspace = gemm_ws;
+  if (fused) {
+    pl.gemm.out = p.out;
+    return launch_igemm_dma_wino(pl.gemm, 0, gemm_tile, stream);
+  }
+  pl.gemm.out = mt;
   e = launch_igemm_dma(pl.gemm, 0, gemm_tile, 1, stream);
   if (e != hipSuccess) return e;
 
