@@ -465,3 +465,54 @@ def test_bias_relu_full_size(torch_cuda, oracle, name):
         want = oracle.forward_bias_act_f32(xb, fb, bias, True, strides, L.padding)
         got = run_gpu_fused(torch_cuda, pb, xb, fb, bias, B.ACT_RELU)
         assert rel_err(got, want) <= TOL_BF16, name
+
+
+# ------------------------------------------------------------------ HIP graph capture
+
+def test_calls_can_be_captured_in_a_hip_graph(torch_cuda, oracle):
+    """The library only enqueues kernels (no allocation, no memset, no synchronisation), so a
+    sequence of calls can be captured into a HIP graph.  Several replays, with eager work and
+    synchronisations in between, must all reproduce the eager result: a split-reduction layer,
+    a balanced-tail layer, a Winograd layer and a fused-epilogue call."""
+    torch = torch_cuda
+    dev = torch.device("cuda:0")
+    cases = [(1, 14, 14, 512, 512, 3, 3), (16, 28, 28, 128, 128, 3, 3), (4, 56, 56, 64, 64, 3, 3),
+             (8, 28, 28, 64, 256, 1, 1)]
+    jobs = []
+    for i, (n, hw, _, c, k, r, s) in enumerate(cases):
+        p = B.make_params(n, hw, hw, c, k, r, s)
+        x, f = wl.make_case((n, hw, hw, c), (r, s, c, k), "uniform", 9900 + i)
+        xd, fd = torch.from_numpy(x).to(dev), torch.from_numpy(f).to(dev)
+        vid = B.conv2d_selected_variant(p)
+        ws = torch.empty(max(B.conv2d_workspace_size(p, vid), 16), dtype=torch.uint8, device=dev)
+        g = B.conv2d_get_geometry(p)
+        out = torch.empty((n, g.out_rows, g.out_cols, k), dtype=torch.float32, device=dev)
+        bias = torch.linspace(-1, 1, k, device=dev) if i == 3 else None
+        jobs.append((p, xd, fd, out, ws, bias, x, f))
+
+    def run_all():
+        for p, xd, fd, out, ws, bias, _, _ in jobs:
+            if bias is None:
+                B.conv2d_forward(p, xd, fd, out=out, workspace=ws)
+            else:
+                B.conv2d_forward_bias_act(p, xd, fd, bias, B.ACT_RELU, out=out, workspace=ws)
+
+    run_all()
+    torch.cuda.synchronize()
+    eager = [j[3].clone() for j in jobs]
+    for (p, _, _, out, _, bias, x, f), e in zip(jobs, eager):
+        want = oracle.forward_bias_act_f32(x, f, None if bias is None else bias.cpu().numpy(),
+                                           bias is not None, 1, wl.PAD_SAME)
+        assert rel_err(e.cpu().numpy(), want) <= 2 * TOL_F32
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run_all()
+    for _ in range(4):
+        for j in jobs:
+            j[3].fill_(float("nan"))          # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for j, e in zip(jobs, eager):
+            assert torch.equal(j[3], e)
