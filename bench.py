@@ -69,6 +69,9 @@ def main():
                          "directly, so that the executed multiply-adds are the metric's (default); "
                          "all: also the Winograd variants, which execute 2.25x fewer and can "
                          "therefore exceed the MFMA peak in the metric's terms")
+    ap.add_argument("--skip-all-algorithms-leg", action="store_true",
+                    help="with --algorithms direct: do not also time the unrestricted selection "
+                         "(keeps a profile of the run to the direct-sum kernels)")
     ap.add_argument("--batch", type=int, choices=[1, 4, 32], default=32,
                     help="batch size of the resnet50 workload (the paper's Figures 1-3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -195,7 +198,7 @@ def main():
     # ---- the same sweep with the unrestricted selection (Winograd variants allowed), reported
     # beside the headline value: they execute 2.25x fewer multiply-adds than the metric counts
     with_transforms = None
-    if args.algorithms == "direct":
+    if args.algorithms == "direct" and not args.skip_all_algorithms_leg:
         changed = False
         for l in layers:
             vid = B.conv2d_select_variant(l["p"], 0)
