@@ -53,7 +53,7 @@ constexpr unsigned kRsrcFlags = 0x00020000u;  // raw buffer, 32-bit data format
 constexpr int kOutOfRange = static_cast<int>(0x80000000u);
 
 template <bool BF16_, int BM_, int BN_, int BK_, int WAVES_M_, int WAVES_N_, bool TWO_LEVEL_,
-          int OCC_, bool SCALAR_>
+          int OCC_, bool SCALAR_, int WAVES_K_ = 1>
 struct Tile {
   static constexpr bool BF16 = BF16_;
   static constexpr int BM = BM_, BN = BN_, BK = BK_;
@@ -70,7 +70,13 @@ struct Tile {
   static constexpr int VEC = 16 / ES;       // elements per 16-byte vector
   static constexpr int KSTEP = 2 * VEC;     // k consumed per fragment read (two lane halves)
   static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
-  static constexpr int NT = 64 * WAVES_M * WAVES_N;
+  // WAVES_K > 1: that many groups of waves share an output tile, each group
+  // multiplies its own part of every slice's k range, and the groups' sums
+  // are added through LDS in group order at the end (a split of the
+  // reduction inside the workgroup: small tiles for small layers without a
+  // second launch for the reduce)
+  static constexpr int WAVES_K = WAVES_K_;
+  static constexpr int NT = 64 * WAVES_M * WAVES_N * WAVES_K;
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   static constexpr int TM = WM / 32, TN = WN / 32;
   static constexpr int LD = BK + VEC;  // LDS row stride in elements: 16 bytes of padding keep
@@ -85,6 +91,10 @@ struct Tile {
   static constexpr int LDS_BYTES = 2 * (BM + BN) * LD * ES;
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of 32x32");
   static_assert(BK % KSTEP == 0, "BK must be a multiple of the fragment step");
+  static_assert((BK / KSTEP) % WAVES_K == 0, "fragment steps must divide over the k groups");
+  static_assert((WAVES_K - 1) * (BM / WAVES_M / 32) * (BN / WAVES_N / 32) * 4096 * WAVES_M *
+                        WAVES_N <= 2 * (BM + BN) * (BK + 16 / (BF16_ ? 2 : 4)) * (BF16_ ? 2 : 4),
+                "the k groups' sums must fit the tile buffers");
   static_assert(NT % KV == 0 && BM % A_ROWS_PER_PASS == 0, "A tile must divide over the threads");
   static_assert(!(BF16 && TWO_LEVEL), "two-level summation is an fp32 feature");
   static_assert(LDS_BYTES <= 160 * 1024, "tile does not fit LDS");
@@ -179,8 +189,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int wm = wave / T::WAVES_N;
-  const int wn = wave % T::WAVES_N;
+  const int wk = wave / (T::WAVES_M * T::WAVES_N);           // k group of this wave
+  const int wmn = wave % (T::WAVES_M * T::WAVES_N);
+  const int wm = wmn / T::WAVES_N;
+  const int wn = wmn % T::WAVES_N;
   const int lr = lane & 31;   // row (A) / column (B, D) inside a 32x32 MFMA tile
   const int lk = lane >> 5;   // which half of the k group this lane feeds
 
@@ -379,8 +391,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
   auto multiply = [&](int buf) {
     const unsigned char* as = As + (buf * BM * LD + (wm * T::WM + lr) * LD + lk * VEC) * ES;
     const unsigned char* bs = Bs + (buf * BN * LD + (wn * T::WN + lr) * LD + lk * VEC) * ES;
+    constexpr int KK = BK / T::KSTEP / T::WAVES_K;  // fragment steps of one k group
 #pragma unroll
-    for (int kk = 0; kk < BK / T::KSTEP; ++kk) {
+    for (int k0 = 0; k0 < KK; ++k0) {
+      const int kk = wk * KK + k0;
       uintx4 af[T::TM], bf[T::TN];
 #pragma unroll
       for (int i = 0; i < T::TM; ++i)
@@ -455,10 +469,50 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
         for (int v = 0; v < 16; ++v) acc[i][j][v] += total[i][j][v];
   }
 
+  if constexpr (T::WAVES_K > 1) {
+    // sum of the k groups, in group order, through LDS (the tile buffers are free now)
+    float* red = reinterpret_cast<float*>(lds);
+    const int slot = wmn * 64 + lane;  // one float per (wave position, lane) and accumulator register
+    constexpr int PER_GROUP = T::WAVES_M * T::WAVES_N * 64 * T::TM * T::TN * 16;
+    __syncthreads();
+    if (wk > 0) {
+#pragma unroll
+      for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < T::TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            red[(wk - 1) * PER_GROUP + ((i * T::TN + j) * 16 + v) * (T::WAVES_M * T::WAVES_N * 64) +
+                slot] = acc[i][j][v];
+    }
+    __syncthreads();
+    if (wk > 0) return;
+#pragma unroll
+    for (int g = 0; g < T::WAVES_K - 1; ++g)
+#pragma unroll
+      for (int i = 0; i < T::TM; ++i)
+#pragma unroll
+        for (int j = 0; j < T::TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            acc[i][j][v] += red[g * PER_GROUP + ((i * T::TN + j) * 16 + v) *
+                                                    (T::WAVES_M * T::WAVES_N * 64) + slot];
+  }
+
   // ---- epilogue: D tile -> NHWC output (or the fp32 partial of this split).
   // In a 32x32 accumulator, lane l register v holds row 8*(v/4) + 4*(l/32) +
   // v%4, column l%32, so each store instruction writes two contiguous
   // 32-element row segments.
+  // The bias of this lane's columns, fetched before the first store.  The empty asm makes the
+  // values "arrive" here, in uniform control flow: left to itself the compiler waits for the
+  // loads inside every bounds-checked store block, and that wait (the counter covers loads
+  // and stores alike) drains all earlier stores each time, one round trip per store.
+  float bias_col[T::TN];
+#pragma unroll
+  for (int j = 0; j < T::TN; ++j)
+    bias_col[j] = bias_of(p.bias, n0 + wn * T::WN + j * 32 + lr, p.K);
+#pragma unroll
+  for (int j = 0; j < T::TN; ++j) asm volatile("" : "+v"(bias_col[j]));
   const bool to_partial = gridDim.y > 1;
   float* part = static_cast<float*>(p.workspace) +
                 static_cast<size_t>(blockIdx.y) * static_cast<size_t>(p.M) * p.K;
@@ -468,7 +522,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
     for (int j = 0; j < T::TN; ++j) {
       const int col = n0 + wn * T::WN + j * 32 + lr;
       const int rbase = m0 + wm * T::WM + i * 32 + lk * 4;
-      const float bcol = bias_of(p.bias, col, p.K);
+      const float bcol = bias_col[j];
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = rbase + 8 * (v / 4) + (v % 4);
@@ -530,6 +584,10 @@ struct TileEntry {
 #define CONV2D_TILE(dt, isbf, bm, bn, bk, wm, wn, two, occ, scalar, tag) \
   { "igemm_" dt "_" #bm "x" #bn "x" #bk tag, bm, bn, bk, occ, scalar, \
     &launch<Tile<isbf, bm, bn, bk, wm, wn, two, occ, scalar>> }
+// tiles whose waves also split the k range of a slice (see Tile::WAVES_K)
+#define CONV2D_TILE_K(dt, isbf, bm, bn, bk, wm, wn, wk, two, occ)     \
+  { "igemm_" dt "_" #bm "x" #bn "x" #bk "_k" #wk, bm, bn, bk, occ, false, \
+    &launch<Tile<isbf, bm, bn, bk, wm, wn, two, occ, false, wk>> }
 
 const TileEntry kTilesF32[] = {
     CONV2D_TILE("f32", false, 256, 128, 16, 4, 2, true, 2, false, ""),
@@ -541,6 +599,8 @@ const TileEntry kTilesF32[] = {
     CONV2D_TILE("f32", false, 128, 128, 32, 2, 2, true, 2, false, ""),
     CONV2D_TILE("f32", false, 128, 64, 32, 2, 2, true, 3, false, ""),
     CONV2D_TILE("f32", false, 256, 128, 32, 4, 2, true, 2, false, ""),
+    CONV2D_TILE_K("f32", false, 32, 32, 64, 1, 1, 4, true, 4),
+    CONV2D_TILE_K("f32", false, 64, 32, 32, 2, 1, 2, true, 4),
     CONV2D_TILE("f32", false, 128, 64, 16, 2, 2, true, 3, true, "_scalar"),
     CONV2D_TILE("f32", false, 64, 64, 16, 2, 2, true, 4, true, "_scalar"),
     CONV2D_TILE("f32", false, 128, 32, 16, 4, 1, true, 4, true, "_scalar"),
@@ -551,6 +611,8 @@ const TileEntry kTilesBf16[] = {
     CONV2D_TILE("bf16", true, 128, 64, 64, 2, 2, false, 3, false, ""),
     CONV2D_TILE("bf16", true, 128, 64, 32, 2, 2, false, 3, false, ""),
     CONV2D_TILE("bf16", true, 64, 64, 32, 2, 2, false, 4, false, ""),
+    CONV2D_TILE_K("bf16", true, 32, 32, 128, 1, 1, 4, false, 4),
+    CONV2D_TILE_K("bf16", true, 64, 32, 64, 2, 1, 2, false, 4),
     // element-wise gathers: any C and K (a 3-channel stem in bf16), 2-byte alignment
     CONV2D_TILE("bf16", true, 128, 64, 32, 2, 2, false, 3, true, "_scalar"),
     CONV2D_TILE("bf16", true, 64, 64, 32, 2, 2, false, 4, true, "_scalar"),

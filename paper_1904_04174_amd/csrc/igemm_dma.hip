@@ -664,6 +664,16 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
     }
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // drain the slices issued past the end
+  // The bias of this lane's columns, fetched before the first store.  The empty asm makes the
+  // values "arrive" here, in uniform control flow: left to itself the compiler waits for the
+  // loads inside every bounds-checked store block, and that wait (the counter covers loads
+  // and stores alike) drains all earlier stores each time, one round trip per store.
+  float bias_col[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+    bias_col[j] = bias_of(p.bias, n0 + wn * T::WN + j * 32 + lr, p.K);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(bias_col[j]));
   if (WINO) {
     // the tile's rows are Winograd tiles (n, th, tw): four output pixels each
 #pragma unroll
@@ -672,7 +682,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
       for (int j = 0; j < TN; ++j) {
         const int col = n0 + wn * T::WN + j * 32 + lr;
         const int rbase = m0 + wm * T::WM + i * 32 + lk * 4;
-        const float bcol = bias_of(p.bias, col, p.K);
+        const float bcol = bias_col[j];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = rbase + 8 * (v / 4) + (v % 4);
@@ -726,7 +736,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
     for (int j = 0; j < TN; ++j) {
       const int col = n0 + wn * T::WN + j * 32 + lr;
       const int rbase = m0 + wm * T::WM + i * 32 + lk * 4;
-      const float bcol = bias_of(p.bias, col, p.K);
+      const float bcol = bias_col[j];
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = rbase + 8 * (v / 4) + (v % 4);
@@ -1235,6 +1245,16 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
         for (int v = 0; v < 16; ++v) acc[i][j][v] += total[i][j][v];
   }
 
+  // The bias of this lane's columns, fetched before the first store.  The empty asm makes the
+  // values "arrive" here, in uniform control flow: left to itself the compiler waits for the
+  // loads inside every bounds-checked store block, and that wait (the counter covers loads
+  // and stores alike) drains all earlier stores each time, one round trip per store.
+  float bias_col[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+    bias_col[j] = bias_of(p.bias, n0 + wn * T::WN + j * 32 + lr, p.K);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(bias_col[j]));
   // ---- epilogue (accumulator layout: lane l reg v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32)
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -1242,7 +1262,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
     for (int j = 0; j < TN; ++j) {
       const int col = n0 + wn * T::WN + j * 32 + lr;
       const int rbase = m0 + wm * T::WM + i * 32 + lk * 4;
-      const float bcol = bias_of(p.bias, col, p.K);
+      const float bcol = bias_col[j];
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = rbase + 8 * (v / 4) + (v % 4);
