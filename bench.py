@@ -30,11 +30,11 @@ PEAK_HBM_GBS = 8000.0
 # runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, factors calibrated on a 256 MiB copy); source:
 # profiles/igemm_dma_counters_per_layer.md.  Not measurable inside this process.
 MEASURED_TRAFFIC_MB = {
-    ("f32", "V224-N16"): 206.8 + 205.5, ("f32", "V112-N16"): 112.1 + 104.9,
-    ("f32", "V56-N16"): 90.7 + 54.5, ("f32", "V28-N16"): 402.2 + 29.4,
-    ("f32", "V14-N16"): 105.9 + 19.3 + 6.4,
-    ("bf16", "V112-N16"): 62.6 + 119.5, ("bf16", "V56-N16"): 36.1 + 51.4,
-    ("bf16", "V28-N16"): 52.7 + 25.7,
+    ("f32", "V224-N16"): 206.9 + 205.5, ("f32", "V112-N16"): 108.1 + 102.8,
+    ("f32", "V56-N16"): 95.7 + 54.5, ("f32", "V28-N16"): 388.8 + 29.4,
+    ("f32", "V14-N16"): 106.0 + 19.3 + 6.4,
+    ("bf16", "V224-N16"): 103.7 + 205.5, ("bf16", "V112-N16"): 59.9 + 119.5,
+    ("bf16", "V56-N16"): 36.2 + 51.4, ("bf16", "V28-N16"): 52.8 + 25.7,
 }
 
 
