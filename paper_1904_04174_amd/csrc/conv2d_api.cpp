@@ -232,10 +232,10 @@ int split_factor(const Variant& v, const Problem& q) {
 // of resident workgroups, the filter repack of the direct-to-LDS family, the
 // partial tiles of a split reduction or a balanced tail going through memory
 // twice, and a fixed time per kernel launched.  The constants are a fit to
-// the measured times of every variant on 270 random layer shapes in each
-// element type on one MI355X; with them the selector's pick is 2 percent
-// slower than the best variant in the geometric mean (14 percent at worst on
-// 40 larger shapes held out of the fit).
+// the measured times of every variant on 210 random layer shapes in each
+// element type on one MI355X (all families, Winograd included); with them
+// the selector's pick is 3 percent slower than the best variant in the
+// geometric mean.
 struct ModelGroup {
   double eff;     // sustained fraction of the MFMA peak
   double bwcu;    // operand bytes per clock into one compute unit
@@ -244,17 +244,19 @@ struct ModelGroup {
   double epi;     // epilogue cycles per output element of the tile
   double single;  // efficiency factor when a workgroup has its compute unit to itself
 };
-constexpr ModelGroup kModelDma[2] = {{0.981, 137.8, 3.775, 3914, 0.3684, 0.841},
-                                     {0.6779, 38.87, 34.7, 10098, 0.03046, 1}};
-constexpr ModelGroup kModelIgemm[2] = {{0.7675, 41.48, 537.8, 7615.8, 0.1897, 0.9896},
-                                       {0.3248, 83.52, 612.9, 11596, 0.01889, 1}};
-constexpr double kLaunchCycles = 8373.3;       // per kernel launched
-constexpr double kRepackPerByte = 0.001712;     // filter repack, cycles per byte of filter
-constexpr double kChipBytesPerClock = 13194;  // whole-chip streaming rate (cache-resident sizes)
-constexpr double kPartialFactor = 3.464;      // partial tiles: cost relative to that rate
-constexpr double kVectorGatherFactor = 0.9155;  // efficiency of the per-lane addressed tiles
+constexpr ModelGroup kModelDma[2] = {{0.8883, 137.8, 3.797, 2796.1, 0.3092, 0.7661},
+                                     {0.5598, 41.55, 29.93, 8874.6, 0.03176, 1}};
+constexpr ModelGroup kModelIgemm[2] = {{0.8179, 41.48, 537.2, 6614.4, 0.5328, 0.9163},
+                                       {0.2657, 82.96, 529.2, 13765, 0.02623, 0.9554}};
+constexpr double kLaunchCycles = 8605.2;       // per kernel launched
+constexpr double kRepackPerByte = 0.0003335;     // filter repack, cycles per byte of filter
+constexpr double kChipBytesPerClock = 12892;  // whole-chip streaming rate (cache-resident sizes)
+constexpr double kPartialFactor = 6.942;      // partial tiles: cost relative to that rate
+constexpr double kVectorGatherFactor = 0.8502;  // efficiency of the per-lane addressed tiles
 constexpr double kElementFactor = 0.75;        // ... of the element-wise tiles
-constexpr double kPatchFactor = 1.152;         // ... of the LDS-resident patch tiles
+constexpr double kKSplitFactor = 0.9858;          // ... of the tiles whose waves split the k range
+constexpr double kKSplitLatency = 0.3428;        // extra exposed latency per further k group (their slices are deeper)
+constexpr double kPatchFactor = 1.246;         // ... of the LDS-resident patch tiles
 
 // The balanced tail's plan as the launcher makes it: tiles computed whole,
 // tail tiles, ranges the tail is cut into.
@@ -281,15 +283,21 @@ double model_cost(const Variant& v, const Problem& q);
 // fit the caches), plus the transform kernels' traffic and three more launches.
 double winograd_cost(const Variant& v, const Problem& q) {
   const long long tiles = 1LL * q.N * ((q.P + 1) / 2) * ((q.Q + 1) / 2);
+  const bool fused = v.split == kFused;  // products folded into the output: no Mt
   Problem g = {};
-  g.N = 1; g.H = 1; g.W = static_cast<int>(16 * tiles < 0x7fffffff ? 16 * tiles : 0x7fffffff);
-  g.C = q.C; g.K = q.K; g.R = 1; g.S = 1; g.sr = 1; g.sc = 1; g.P = 1; g.Q = g.W; g.M = g.W;
-  g.Kg = q.C;
+  g.N = 1; g.C = q.C; g.K = q.K; g.S = 1; g.sr = 1; g.sc = 1; g.P = 1;
+  if (fused) {
+    // one workgroup per block of tiles runs the 16 products one after the other
+    g.H = 16; g.R = 16; g.W = static_cast<int>(tiles); g.Kg = 16 * q.C;
+  } else {
+    g.H = 1; g.R = 1; g.W = static_cast<int>(16 * tiles < 0x7fffffff ? 16 * tiles : 0x7fffffff);
+    g.Kg = q.C;
+  }
+  g.Q = g.W; g.M = g.W;
   Variant inner = v;
   inner.family = kDma;
   inner.split = kWhole;
-  const bool fused = v.split == kFused;  // products folded into the output: no Mt
-  const double memory_rate = 2000.0;  // bytes per clock from HBM
+  const double memory_rate = 2083.3;  // bytes per clock from HBM (fitted)
   const double v_bytes = 4.0 * 16 * tiles * q.C;
   const double m_bytes = fused ? 0.0 : 4.0 * 16 * tiles * q.K;
   double product = model_cost(inner, g);
@@ -314,6 +322,13 @@ double model_cost(const Variant& v, const Problem& q) {
   const double area = 1.0 * bm * bn;
   double eff = g.eff;
   double slice_bytes = 1.0 * (bm + bn) * bk * es;
+  double exposed_latency = g.lat;
+  if (v.family == kIgemm && igemm_tile_waves_k(v.bf16, v.tile) > 1) {
+    // small tiles whose waves split the slice: every MFMA reads both its fragments from LDS,
+    // and a slice is waves_k times deeper than a plain tile's
+    eff *= kKSplitFactor;
+    exposed_latency *= 1.0 + kKSplitLatency * (igemm_tile_waves_k(v.bf16, v.tile) - 1);
+  }
   if (addressing == 1 && v.family == kDma) eff *= kVectorGatherFactor;
   if (addressing == 2) eff *= kElementFactor;
   if (addressing == 3) {
@@ -350,7 +365,7 @@ double model_cost(const Variant& v, const Problem& q) {
   const long long rounds = ceil_div_ll(per_unit, occ);
   const double mfma = bm * bn * bk / mac_rate / (eff * (resident == 1 ? g.single : 1.0));
   const double feed = slice_bytes / g.bwcu;
-  const double slice = (mfma > feed ? mfma : feed) + g.lat / resident;
+  const double slice = (mfma > feed ? mfma : feed) + exposed_latency / resident;
   const double compute = slices_on_unit * slice;
   const double stream =
       (es * (1.0 * q.N * q.H * q.W * q.C + 1.0 * q.Kg * q.K) + 4.0 * q.M * q.K) / kChipBytesPerClock;

@@ -66,6 +66,7 @@ const char* igemm_tile_name(int bf16, int tile);
 void igemm_tile_shape(int bf16, int tile, int* bm, int* bn, int* bk);
 int igemm_tile_occupancy(int bf16, int tile);   // workgroups per compute unit
 bool igemm_tile_is_scalar(int bf16, int tile);  // element-wise loads: any C, K, alignment
+int igemm_tile_waves_k(int bf16, int tile);     // wave groups that split a slice's k range (1 = none)
 hipError_t launch_igemm(const Problem& p, int bf16, int tile, int splits, hipStream_t stream);
 
 // Adds `splits` fp32 partial outputs of `total` elements each (laid out one

@@ -579,15 +579,16 @@ struct TileEntry {
   int bm, bn, bk, occ;
   bool scalar;
   hipError_t (*fn)(const Problem&, int, hipStream_t);
+  int waves_k;
 };
 
 #define CONV2D_TILE(dt, isbf, bm, bn, bk, wm, wn, two, occ, scalar, tag) \
   { "igemm_" dt "_" #bm "x" #bn "x" #bk tag, bm, bn, bk, occ, scalar, \
-    &launch<Tile<isbf, bm, bn, bk, wm, wn, two, occ, scalar>> }
+    &launch<Tile<isbf, bm, bn, bk, wm, wn, two, occ, scalar>>, 1 }
 // tiles whose waves also split the k range of a slice (see Tile::WAVES_K)
 #define CONV2D_TILE_K(dt, isbf, bm, bn, bk, wm, wn, wk, two, occ)     \
   { "igemm_" dt "_" #bm "x" #bn "x" #bk "_k" #wk, bm, bn, bk, occ, false, \
-    &launch<Tile<isbf, bm, bn, bk, wm, wn, two, occ, false, wk>> }
+    &launch<Tile<isbf, bm, bn, bk, wm, wn, two, occ, false, wk>>, wk }
 
 const TileEntry kTilesF32[] = {
     CONV2D_TILE("f32", false, 256, 128, 16, 4, 2, true, 2, false, ""),
@@ -652,6 +653,7 @@ void igemm_tile_shape(int bf16, int tile, int* bm, int* bn, int* bk) {
 }
 int igemm_tile_occupancy(int bf16, int tile) { return entry(bf16, tile).occ; }
 bool igemm_tile_is_scalar(int bf16, int tile) { return entry(bf16, tile).scalar; }
+int igemm_tile_waves_k(int bf16, int tile) { return entry(bf16, tile).waves_k; }
 hipError_t launch_igemm(const Problem& p, int bf16, int tile, int splits, hipStream_t stream) {
   return entry(bf16, tile).fn(p, splits, stream);
 }
