@@ -954,11 +954,22 @@ size_t workspace_bytes(const Problem& p, int splits) {
 // filter).  The nine taps of a 3x3 window are unrolled, one barrier per tap
 // slice; the patch of the next channel block is loaded during the first six
 // tap slices of the current one.
+//
+// Blocked tiles (BW > 0) take a BH x BW block of output pixels of one image
+// (BH = BM / BW) instead of BM consecutive ones: their patch is the
+// (BH + 2) x (BW + 2) block of input pixels around it, stored row by row with
+// its own width, so wide images, whose consecutive-pixel patch would span
+// several whole image rows, fit as well.
 template <bool BF16_, int BM_, int BN_, int WAVES_M_, int WAVES_N_, int PATCH_ROWS_,
-          bool TWO_LEVEL_, int OCC_>
+          bool TWO_LEVEL_, int OCC_, int BW_ = 0>
 struct PatchTile {
   static constexpr bool BF16 = BF16_;
   static constexpr int BM = BM_, BN = BN_;
+  static constexpr int BW = BW_;                       // 0: BM consecutive output pixels
+  static constexpr int BH = BW_ > 0 ? BM_ / BW_ : 0;
+  static constexpr int PW = BW_ + 2;                   // patch width of a blocked tile
+  static_assert(BW_ == 0 || (BM_ % BW_ == 0 && (BM_ / BW_ + 2) * (BW_ + 2) <= PATCH_ROWS_),
+                "blocked tile: BM = BH * BW and its patch must fit");
   static constexpr int ROWB = 64, CPR = 4, KSTEPS = 2;
   static constexpr int ES = BF16 ? 2 : 4;
   static constexpr int VEC = 16 / ES;
@@ -1026,8 +1037,17 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   const int local = blockIdx.x / kXcds;
   const int per = nwg / kXcds, rem = nwg % kXcds;
   const int tile = xcd * per + (xcd < rem ? xcd : rem) + local;
-  const int m0 = (tile / tiles_n) * BM;
+  const int m0 = (tile / tiles_n) * BM;   // consecutive-pixel tiles: first output pixel
   const int n0 = (tile % tiles_n) * BN;
+  // blocked tiles: image and top-left output pixel of the block
+  int blk_n = 0, blk_p = 0, blk_q = 0;
+  if constexpr (T::BW > 0) {
+    const int nbx = (p.Q + T::BW - 1) / T::BW, nby = (p.P + T::BH - 1) / T::BH;
+    const int tm = tile / tiles_n;
+    blk_q = (tm % nbx) * T::BW;
+    blk_p = ((tm / nbx) % nby) * T::BH;
+    blk_n = tm / (nbx * nby);
+  }
   constexpr int taps = 9;
   const int nblocks = p.C / BK;      // channel blocks
   const int Kg_p = p.Kg;             // C is a multiple of BK
@@ -1037,18 +1057,28 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   const unsigned ring_base = __builtin_amdgcn_readfirstlane(lds_address(ring) + wave * 1024);
 
   // ---- patch loader role: entries (pass*NW + wave)*64 + lane of the patch
-  const long long v0 = patch_base(p, Hp, Wp, m0);
+  const long long v0 = T::BW > 0 ? 0 : patch_base(p, Hp, Wp, m0);
   int a_voff[T::A_PASSES];
 #pragma unroll
   for (int i = 0; i < T::A_PASSES; ++i) {
-    const long long v = v0 + (i * T::NW + wave) * 64 + lane;
-    const int w = static_cast<int>(v % Wp) - p.pl;
-    const long long t = v / Wp;
-    const int h = static_cast<int>(t % Hp) - p.pt;
-    const long long n = t / Hp;
-    const bool ok = n < p.N && static_cast<unsigned>(h) < static_cast<unsigned>(p.H) &&
-                    static_cast<unsigned>(w) < static_cast<unsigned>(p.W);
-    a_voff[i] = ok ? static_cast<int>(((n * p.H + h) * p.W + w) * p.C * ES) : kOutOfRange;
+    if constexpr (T::BW > 0) {
+      // entry e of the patch: row e / PW, column e % PW of the input block
+      const int e = (i * T::NW + wave) * 64 + lane;
+      const int dy = e / T::PW, dx = e % T::PW;
+      const int h = blk_p - p.pt + dy, w = blk_q - p.pl + dx;
+      const bool ok = dy < T::BH + 2 && static_cast<unsigned>(h) < static_cast<unsigned>(p.H) &&
+                      static_cast<unsigned>(w) < static_cast<unsigned>(p.W);
+      a_voff[i] = ok ? ((blk_n * p.H + h) * p.W + w) * p.C * ES : kOutOfRange;
+    } else {
+      const long long v = v0 + (i * T::NW + wave) * 64 + lane;
+      const int w = static_cast<int>(v % Wp) - p.pl;
+      const long long t = v / Wp;
+      const int h = static_cast<int>(t % Hp) - p.pt;
+      const long long n = t / Hp;
+      const bool ok = n < p.N && static_cast<unsigned>(h) < static_cast<unsigned>(p.H) &&
+                      static_cast<unsigned>(w) < static_cast<unsigned>(p.W);
+      a_voff[i] = ok ? static_cast<int>(((n * p.H + h) * p.W + w) * p.C * ES) : kOutOfRange;
+    }
   }
   // ---- filter loader role (as in the gather kernel)
   const int ld_row0 = tid / CPR;
@@ -1100,8 +1130,13 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   int a_frag[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-    const int m = min(m0 + wm * T::WM + i * 32 + lr, p.M - 1);
-    a_frag[i] = static_cast<int>(patch_base(p, Hp, Wp, m) - v0) * 16 + lk * T::PLANE_BYTES;
+    if constexpr (T::BW > 0) {
+      const int ml = wm * T::WM + i * 32 + lr;  // pixel (ml / BW, ml % BW) of the block
+      a_frag[i] = ((ml / T::BW) * T::PW + ml % T::BW) * 16 + lk * T::PLANE_BYTES;
+    } else {
+      const int m = min(m0 + wm * T::WM + i * 32 + lr, p.M - 1);
+      a_frag[i] = static_cast<int>(patch_base(p, Hp, Wp, m) - v0) * 16 + lk * T::PLANE_BYTES;
+    }
   }
   const int frag_swz = (lr >> 1) & (CPR - 1);
   const unsigned char* b_frag = ring + B_REGION + (wn * T::WN + lr) * ROWB;
@@ -1265,8 +1300,15 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
       const float bcol = bias_col[j];
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int row = rbase + 8 * (v / 4) + (v % 4);
-        if (row < p.M && col < p.K) {
+        int row = rbase + 8 * (v / 4) + (v % 4);
+        bool row_ok = row < p.M;
+        if constexpr (T::BW > 0) {
+          const int ml = row - m0;  // position in the block
+          const int op = blk_p + ml / T::BW, oq = blk_q + ml % T::BW;
+          row_ok = op < p.P && oq < p.Q;
+          row = (blk_n * p.P + op) * p.Q + oq;
+        }
+        if (row_ok && col < p.K) {
           const size_t idx = static_cast<size_t>(row) * p.K + col;
           if (OUT_BF16)
             static_cast<unsigned short*>(p.out)[idx] =
@@ -1294,8 +1336,16 @@ long long patch_rows_needed(const Problem& p) {
 
 template <class T>
 bool patch_fits(const Problem& p) {
-  return p.R == 3 && p.S == 3 && p.sr == 1 && p.sc == 1 && p.C % T::BK == 0 &&
-         patch_rows_needed<T>(p) <= T::PATCH_ROWS;
+  if (!(p.R == 3 && p.S == 3 && p.sr == 1 && p.sc == 1 && p.C % T::BK == 0)) return false;
+  if (T::BW > 0) return true;  // a block's patch always fits
+  return patch_rows_needed<T>(p) <= T::PATCH_ROWS;
+}
+
+// Output tiles along M: blocks of BH x BW pixels per image, or runs of BM pixels.
+template <class T>
+int patch_tiles_m(const Problem& p) {
+  if (T::BW > 0) return p.N * ((p.P + T::BH - 1) / T::BH) * ((p.Q + T::BW - 1) / T::BW);
+  return (p.M + T::BM - 1) / T::BM;
 }
 
 template <class T, bool OUT_BF16>
@@ -1314,12 +1364,14 @@ hipError_t launch_patch_one(const Problem& p, hipStream_t stream) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // 2. the convolution
-  const int tiles = ((p.M + T::BM - 1) / T::BM) * ((p.K + T::BN - 1) / T::BN);
+  const int tiles = patch_tiles_m<T>(p) * ((p.K + T::BN - 1) / T::BN);
   const int nslices = p.Kg / T::BK;
   int flush = 1;
   while (flush * flush < nslices) ++flush;
+  // width of the patch rows: the padded image's, or the block's own
+  const int patch_width = T::BW > 0 ? T::PW : p.Q + p.S - 1;
   hipLaunchKernelGGL((igemm_patch_kernel<T, OUT_BF16>), dim3(tiles), dim3(T::NT), 0, stream, p,
-                     p.P + p.R - 1, p.Q + p.S - 1, flush, p.workspace);
+                     p.P + p.R - 1, patch_width, flush, p.workspace);
   return hipGetLastError();
 }
 
@@ -1352,6 +1404,14 @@ struct TileEntry {
     &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>>,                     \
     &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>>, nullptr }
 
+// blocked patch tiles: bm / bw x bw output pixels of one image
+#define CONV2D_PATCH_TILE_B(dt, isbf, bm, bn, wm, wn, rows, two, occ, bw)                        \
+  { "igemm_patch_" dt "_" #bm "x" #bn "_w" #wm "x" #wn "_p" #rows "_b" #bw, bm, bn,              \
+    PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw>::BK, occ, 3,                             \
+    &launch_patch<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw>>,                          \
+    &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw>>,                 \
+    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw>>, nullptr }
+
 #define CONV2D_DMA_TILE(dt, isbf, bm, bn, rowb, wm, wn, st, two, occ, addr, tag)                \
   { "igemm_dma_" dt "_" #bm "x" #bn "_r" #rowb "_w" #wm "x" #wn "_s" #st tag, bm, bn,           \
     DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>::BK, occ, addr,                     \
@@ -1368,6 +1428,7 @@ struct TileEntry {
 
 const TileEntry kTilesF32[] = {
     CONV2D_PATCH_TILE("f32", false, 128, 128, 2, 2, 512, true, 1),
+    CONV2D_PATCH_TILE_B("f32", false, 128, 128, 2, 2, 256, true, 2, 16),
     CONV2D_DMA_TILE("f32", false, 128, 128, 64, 2, 2, 4, true, 2, kUniform, ""),
     CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, kUniform, ""),
     CONV2D_DMA_TILE("f32", false, 256, 128, 64, 4, 2, 4, true, 2, kUniform, ""),
@@ -1383,6 +1444,9 @@ const TileEntry kTilesBf16[] = {
     CONV2D_PATCH_TILE("bf16", true, 256, 256, 4, 2, 512, false, 1),
     CONV2D_PATCH_TILE("bf16", true, 256, 256, 2, 2, 512, false, 1),
     CONV2D_PATCH_TILE("bf16", true, 256, 128, 4, 2, 512, false, 1),
+    CONV2D_PATCH_TILE_B("bf16", true, 256, 256, 4, 2, 512, false, 1, 16),
+    CONV2D_PATCH_TILE_B("bf16", true, 256, 128, 4, 2, 512, false, 1, 16),
+    CONV2D_PATCH_TILE_B("bf16", true, 256, 64, 4, 1, 512, false, 2, 16),
     CONV2D_DMA_TILE("bf16", true, 256, 256, 64, 4, 2, 4, false, 1, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 256, 256, 128, 4, 2, 2, false, 1, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 256, 128, 64, 4, 2, 4, false, 1, kUniform, ""),
