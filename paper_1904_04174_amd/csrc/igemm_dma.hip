@@ -1455,6 +1455,7 @@ const TileEntry kTilesBf16[] = {
     CONV2D_DMA_TILE("bf16", true, 128, 64, 64, 2, 2, 4, false, 3, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 4, false, 4, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 3, false, 6, kUniform, ""),
+    CONV2D_DMA_TILE("bf16", true, 64, 64, 128, 2, 2, 4, false, 2, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 128, 128, 64, 2, 2, 4, false, 2, kVector, "_g"),
     CONV2D_DMA_TILE("bf16", true, 128, 64, 64, 2, 2, 4, false, 3, kVector, "_g"),
     CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 4, false, 4, kVector, "_g"),
