@@ -1447,6 +1447,8 @@ const TileEntry kTilesBf16[] = {
     CONV2D_PATCH_TILE_B("bf16", true, 256, 256, 4, 2, 512, false, 1, 16),
     CONV2D_PATCH_TILE_B("bf16", true, 256, 128, 4, 2, 512, false, 1, 16),
     CONV2D_PATCH_TILE_B("bf16", true, 256, 64, 4, 1, 512, false, 2, 16),
+    CONV2D_PATCH_TILE_B("bf16", true, 128, 64, 2, 2, 256, false, 3, 16),
+    CONV2D_PATCH_TILE_B("bf16", true, 128, 128, 2, 2, 256, false, 2, 16),
     CONV2D_DMA_TILE("bf16", true, 256, 256, 64, 4, 2, 4, false, 1, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 256, 256, 128, 4, 2, 2, false, 1, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 256, 128, 64, 4, 2, 4, false, 1, kUniform, ""),
