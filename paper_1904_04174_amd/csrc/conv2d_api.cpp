@@ -36,7 +36,7 @@ struct Variant {
 // split-reduction twin where the tile is small enough for that to make sense,
 // then the direct-to-LDS tiles, then the Winograd variants.
 struct Table {
-  Variant v[160];
+  Variant v[256];
   int n;
   void add(Family f, int bf16, int tile, int split, const char* base) {
     Variant& x = v[n++];

@@ -1444,6 +1444,7 @@ const TileEntry kTilesBf16[] = {
     CONV2D_PATCH_TILE("bf16", true, 256, 256, 4, 2, 512, false, 1),
     CONV2D_PATCH_TILE("bf16", true, 256, 256, 2, 2, 512, false, 1),
     CONV2D_PATCH_TILE("bf16", true, 256, 128, 4, 2, 512, false, 1),
+    CONV2D_PATCH_TILE("bf16", true, 224, 256, 1, 4, 512, false, 1),
     CONV2D_PATCH_TILE_B("bf16", true, 256, 256, 4, 2, 512, false, 1, 16),
     CONV2D_PATCH_TILE_B("bf16", true, 256, 128, 4, 2, 512, false, 1, 16),
     CONV2D_PATCH_TILE_B("bf16", true, 256, 64, 4, 1, 512, false, 2, 16),
