@@ -33,7 +33,7 @@ MEASURED_TRAFFIC_MB = {
     ("f32", "V224-N16"): 206.9 + 205.5, ("f32", "V112-N16"): 108.1 + 102.8,
     ("f32", "V56-N16"): 95.7 + 54.5, ("f32", "V28-N16"): 388.8 + 29.4,
     ("f32", "V14-N16"): 106.0 + 19.3 + 6.4,
-    ("bf16", "V224-N16"): 103.7 + 205.5, ("bf16", "V112-N16"): 59.9 + 119.5,
+    ("bf16", "V224-N16"): 104.7 + 205.5, ("bf16", "V112-N16"): 61.0 + 102.8,
     ("bf16", "V56-N16"): 36.2 + 51.4, ("bf16", "V28-N16"): 52.8 + 25.7,
 }
 
