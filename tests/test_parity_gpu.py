@@ -224,6 +224,47 @@ def test_unaligned_pointers_take_the_element_wise_path(torch_cuda, oracle):
             assert rc == B.STATUS_UNSUPPORTED, name
 
 
+def test_unaligned_bf16_pointers_and_odd_channels(torch_cuda, oracle):
+    """bf16 input and filter that start 2 bytes past a 16-byte boundary, and a layer with
+    C = 3 and K = 10 (no 16-byte vector along either): the element-wise bf16 MFMA tiles run
+    them, the vector variants refuse."""
+    torch = torch_cuda
+    for case, shift in (((2, 13, 11, 8, 16, 3, 3, 1, 1, wl.PAD_SAME), 1),
+                        ((2, 17, 15, 3, 10, 5, 5, 2, 2, wl.PAD_SAME), 0)):
+        n, h, w, c, k, r, s, sr, sc, pad = case
+        x, f = wl.make_case((n, h, w, c), (r, s, c, k), "uniform", 4343 + shift)
+        xb, _ = wl.round_to_bf16(x)
+        fb, _ = wl.round_to_bf16(f)
+        want = oracle.forward_f32(xb, fb, (sr, sc), pad)
+        p = _params(case, B.BF16, B.F32)
+
+        def shifted(a):
+            buf = torch.empty(a.size + 8, dtype=torch.bfloat16, device="cuda")
+            v = buf[shift:shift + a.size].view(a.shape)
+            v.copy_(torch.from_numpy(a).to(torch.bfloat16))
+            return v
+        xd, fd = shifted(xb), shifted(fb)
+        assert xd.data_ptr() % 16 == 2 * shift
+        out = B.conv2d_forward(p, xd, fd)
+        torch.cuda.synchronize()
+        assert rel_err(out.cpu().numpy(), want) <= TOL_BF16
+        ran = []
+        for v in supported_variants(p):
+            name = B.conv2d_variant_name(v)
+            ws = torch.empty(max(B.conv2d_workspace_size(p, v), 16), dtype=torch.uint8,
+                             device="cuda")
+            rc = B.conv2d_forward_raw(p, xd.data_ptr(), fd.data_ptr(), out.data_ptr(),
+                                      ws.data_ptr(), ws.numel(), 0, v)
+            torch.cuda.synchronize()
+            if name == "direct" or "scalar" in name:
+                assert rc == B.STATUS_OK, name
+                assert rel_err(out.cpu().numpy(), want) <= TOL_BF16, name
+                ran.append(name)
+            else:
+                assert shift and rc == B.STATUS_UNSUPPORTED, name
+        assert any("scalar" in n for n in ran), ran
+
+
 def test_empty_batch_on_gpu(torch_cuda):
     torch = torch_cuda
     p = B.make_params(0, 8, 8, 4, 4, 3, 3)
