@@ -20,7 +20,7 @@ namespace {
 
 constexpr long long kMaxElems = (1LL << 31) - 1;
 
-enum Family { kDirect = 0, kIgemm = 1, kDma = 2, kWinograd = 3 };
+enum Family { kDirect = 0, kIgemm = 1, kDma = 2, kWinograd = 3, kPadded = 4 };
 enum Split { kWhole = 0, kSplit = 1, kTail = 2, kFused = 3 };
 
 struct Variant {
@@ -58,6 +58,15 @@ struct Table {
         add(kDma, bf, t, kWhole, igemm_dma_tile_name(bf, t));
         add(kDma, bf, t, kSplit, igemm_dma_tile_name(bf, t));
         add(kDma, bf, t, kTail, igemm_dma_tile_name(bf, t));
+      }
+    // zero-padded channels for small C: one variant per per-lane addressed gather tile
+    for (int bf = 0; bf < 2; ++bf)
+      for (int t = 0; t < igemm_dma_num_tiles(bf); ++t) {
+        if (igemm_dma_tile_addressing(bf, t) != 1) continue;
+        char base[80];
+        // "igemm_dma_bf16_64x64_..._g" -> "padc_bf16_64x64_..._g"
+        std::snprintf(base, sizeof(base), "padc_%s", igemm_dma_tile_name(bf, t) + 10);
+        add(kPadded, bf, t, kWhole, base);
       }
     // Winograd F(2x2, 3x3), fp32: one variant per gather tile that can run its products
     for (int t = 0; t < igemm_dma_num_tiles(0); ++t) {
@@ -168,6 +177,10 @@ bool supports(const Variant& v, const Problem& q) {
   // buffer addressing needs input and filter below 2^31 bytes
   if (1LL * es * q.N * q.H * q.W * q.C >= (1LL << 31)) return false;
   if (v.family == kWinograd) return winograd_supports(q, v.tile, v.split == kFused);
+  if (v.family == kPadded) {
+    if (v.bf16 != q.in_bf16 || (!q.in_bf16 && q.out_bf16)) return false;
+    return padded_supports(q, v.tile);
+  }
   int bm, bn, bk;
   tile_shape(v, &bm, &bn, &bk);
   if (v.family == kIgemm) {
@@ -310,6 +323,18 @@ double winograd_cost(const Variant& v, const Problem& q) {
 
 double model_cost(const Variant& v, const Problem& q) {
   if (v.family == kWinograd) return winograd_cost(v, q);
+  if (v.family == kPadded) {
+    // the gather tile on the padded problem, the padding passes' traffic, two more launches
+    const int vec = q.in_bf16 ? 8 : 4;
+    Problem g = q;
+    g.C = (q.C + vec - 1) / vec * vec;
+    g.Kg = q.R * q.S * g.C;
+    Variant inner = v;
+    inner.family = kDma;
+    const double es = q.in_bf16 ? 2.0 : 4.0;
+    const double pad_bytes = es * q.N * q.H * q.W * (q.C + g.C);
+    return model_cost(inner, g) + pad_bytes / 2083.3 + 2 * kLaunchCycles;
+  }
   int bm, bn, bk;
   tile_shape(v, &bm, &bn, &bk);
   const ModelGroup& g = v.family == kDma ? kModelDma[q.in_bf16] : kModelIgemm[q.in_bf16];
@@ -451,6 +476,7 @@ int select_uncached(const Problem& q, int padding, bool aligned, bool direct_sum
 
 size_t workspace_bytes_for(const Variant& v, const Problem& q) {
   if (v.family == kWinograd) return winograd_workspace_bytes(q, v.tile, v.split == kFused);
+  if (v.family == kPadded) return padded_workspace_bytes(q, v.tile);
   if (v.family == kDma) return igemm_dma_workspace_bytes(q, v.bf16, v.tile, split_factor(v, q));
   if (v.family == kIgemm && v.split)
     return static_cast<size_t>(split_factor(v, q)) * q.M * q.K * sizeof(float);
@@ -506,6 +532,7 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     case kDma:
       e = launch_igemm_dma(q, tb.v[id].bf16, tb.v[id].tile, split_factor(tb.v[id], q), stream);
       break;
+    case kPadded: e = launch_padded(q, tb.v[id].tile, stream); break;
     case kWinograd:
       e = launch_winograd(q, tb.v[id].tile, tb.v[id].split == kFused, stream);
       break;

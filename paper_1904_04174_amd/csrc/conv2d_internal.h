@@ -122,4 +122,13 @@ bool winograd_supports(const Problem& p, int gemm_tile, bool fused);
 size_t winograd_workspace_bytes(const Problem& p, int gemm_tile, bool fused);
 hipError_t launch_winograd(const Problem& p, int gemm_tile, bool fused, hipStream_t stream);
 
+// Small channel counts that are no multiple of the 16-byte vector (a 3-channel
+// first layer): input and filter are zero-padded to the vector width in the
+// workspace and per-lane addressed direct-to-LDS tile `gemm_tile` runs on the
+// padded tensors.  The workspace holds the padded input and filter and the
+// tile's own workspace.
+bool padded_supports(const Problem& p, int gemm_tile);
+size_t padded_workspace_bytes(const Problem& p, int gemm_tile);
+hipError_t launch_padded(const Problem& p, int gemm_tile, hipStream_t stream);
+
 }  // namespace conv2d

@@ -57,8 +57,10 @@ def candidates(params):
     names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
     def elementwise(n):
         return "scalar" in n or n.endswith("_e") or "_e_" in n
+    # (the zero-padded-channel variants run exactly where the vector tiles cannot: they do not
+    # count as "vector tiles can run")
     vec_ok = any(B.conv2d_variant_supports(params, v) for v, n in enumerate(names)
-                 if n != "direct" and not elementwise(n))
+                 if n != "direct" and not elementwise(n) and not n.startswith("padc_"))
     for v, n in enumerate(names):
         if n == "direct" or not B.conv2d_variant_supports(params, v):
             continue
@@ -83,7 +85,7 @@ def tune_layer(torch, layer, in_dtype, repeats=2):
 FAMILIES = (
     ("register-staged implicit GEMM", lambda n: n.startswith("igemm_") and not n.startswith(
         ("igemm_dma_", "igemm_patch_"))),
-    ("direct-to-LDS implicit GEMM", lambda n: n.startswith("igemm_dma_")),
+    ("direct-to-LDS implicit GEMM", lambda n: n.startswith(("igemm_dma_", "padc_"))),
     ("LDS-resident patch", lambda n: n.startswith("igemm_patch_")),
     ("Winograd F(2x2,3x3)", lambda n: n.startswith("winograd2x2_")),
 )
