@@ -44,16 +44,27 @@ __global__ __launch_bounds__(256) void direct_kernel(Problem p) {
         if (w < 0 || w >= p.W) continue;
         const long long xoff = ((static_cast<long long>(n) * p.H + h) * p.W + w) * p.C;
         const long long foff = (static_cast<long long>(r) * p.S + s) * p.C * p.K + k;
-        if (IN_BF16) {
-          const unsigned short* x = static_cast<const unsigned short*>(p.in) + xoff;
-          const unsigned short* f = static_cast<const unsigned short*>(p.filt) + foff;
-          for (int c = 0; c < p.C; ++c)
-            acc = fmaf(bf16_bits_to_float(x[c]), bf16_bits_to_float(f[static_cast<long long>(c) * p.K]), acc);
-        } else {
-          const float* x = static_cast<const float*>(p.in) + xoff;
-          const float* f = static_cast<const float*>(p.filt) + foff;
-          for (int c = 0; c < p.C; ++c) acc = fmaf(x[c], f[static_cast<long long>(c) * p.K], acc);
+        // Three-level sum (blocks of 64 channels, taps, total): a single fp32 chain over a
+        // long reduction (6400 terms for a 5x5 window on 256 channels) drifts past the 1e-4
+        // tolerance; chains of at most 64, C / 64 and R * S terms do not.
+        float tap = 0.f;
+        for (int c0 = 0; c0 < p.C; c0 += 64) {
+          const int c1 = min(c0 + 64, p.C);
+          float blk = 0.f;
+          if (IN_BF16) {
+            const unsigned short* x = static_cast<const unsigned short*>(p.in) + xoff;
+            const unsigned short* f = static_cast<const unsigned short*>(p.filt) + foff;
+            for (int c = c0; c < c1; ++c)
+              blk = fmaf(bf16_bits_to_float(x[c]),
+                         bf16_bits_to_float(f[static_cast<long long>(c) * p.K]), blk);
+          } else {
+            const float* x = static_cast<const float*>(p.in) + xoff;
+            const float* f = static_cast<const float*>(p.filt) + foff;
+            for (int c = c0; c < c1; ++c) blk = fmaf(x[c], f[static_cast<long long>(c) * p.K], blk);
+          }
+          tap += blk;
         }
+        acc += tap;
       }
     }
     acc = finish(acc, bias_of(p.bias, k, p.K), p.relu);
