@@ -61,6 +61,7 @@ namespace conv2d {
 namespace dma {  // named namespace: the kernels' host stubs need external linkage
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
@@ -960,8 +961,16 @@ size_t workspace_bytes(const Problem& p, int splits) {
 // (BH + 2) x (BW + 2) block of input pixels around it, stored row by row with
 // its own width, so wide images, whose consecutive-pixel patch would span
 // several whole image rows, fit as well.
+//
+// 16-row tiles (MF16, bf16): 16x16x32 MFMA blocks, one per 64-byte row (a
+// single step per slice), so that a wave tile can be 112 rows high: the
+// output pixel counts of these workloads are 49 * 2^k, which tiles of 224 or
+// 448 rows divide and tiles of 128 or 256 rows do not (a last round that is
+// 77 % full against 87.5 %).  The blocks are computed transposed (filter
+// fragment as the first operand), so a lane ends up with four consecutive
+// features of one pixel and stores them as one 16-byte vector.
 template <bool BF16_, int BM_, int BN_, int WAVES_M_, int WAVES_N_, int PATCH_ROWS_,
-          bool TWO_LEVEL_, int OCC_, int BW_ = 0>
+          bool TWO_LEVEL_, int OCC_, int BW_ = 0, bool MF16_ = false>
 struct PatchTile {
   static constexpr bool BF16 = BF16_;
   static constexpr int BM = BM_, BN = BN_;
@@ -970,7 +979,11 @@ struct PatchTile {
   static constexpr int PW = BW_ + 2;                   // patch width of a blocked tile
   static_assert(BW_ == 0 || (BM_ % BW_ == 0 && (BM_ / BW_ + 2) * (BW_ + 2) <= PATCH_ROWS_),
                 "blocked tile: BM = BH * BW and its patch must fit");
-  static constexpr int ROWB = 64, CPR = 4, KSTEPS = 2;
+  static constexpr bool MF16 = MF16_;
+  static_assert(!MF16_ || BF16_, "16-row blocks are a bf16 feature");
+  static constexpr int BLK = MF16 ? 16 : 32;        // rows / columns of an MFMA block
+  static constexpr int ACC = MF16 ? 4 : 16;         // accumulator registers of a block
+  static constexpr int ROWB = 64, CPR = 4, KSTEPS = MF16 ? 1 : 2;
   static constexpr int ES = BF16 ? 2 : 4;
   static constexpr int VEC = 16 / ES;
   static constexpr int BK = ROWB / ES;
@@ -982,24 +995,28 @@ struct PatchTile {
   static constexpr int NW = WAVES_M * WAVES_N;
   static constexpr int NT = 64 * NW;
   static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
-  static constexpr int TM = WM / 32, TN = WN / 32;
+  static constexpr int TM = WM / BLK, TN = WN / BLK;
   static constexpr int MPF = BF16 ? 1 : 4;
   static constexpr int NM = TM * TN * MPF;
   static constexpr int NR = TM + TN;
   static constexpr int PATCH_ROWS = PATCH_ROWS_;
   static constexpr int PLANE_BYTES = PATCH_ROWS * 16;
   static constexpr int PATCH_BYTES = CPR * PLANE_BYTES;
-  static constexpr int A_PASSES = PATCH_ROWS / (64 * NW);
-  static constexpr int A_LOADS = A_PASSES * CPR;  // patch loads per lane per channel block
+  // Patch loads: a wave takes 64 consecutive entries of every plane per pass
+  // (A_PASSES passes); a patch that is no multiple of 64 * NW entries is dealt
+  // by plane instead (BY_PLANE: wave w loads plane w of every 64-entry chunk).
+  static constexpr bool BY_PLANE = PATCH_ROWS % (64 * NW) != 0;
+  static_assert(!BY_PLANE || (NW == CPR && PATCH_ROWS % 64 == 0), "patch rows over the waves");
+  static constexpr int A_PASSES = BY_PLANE ? PATCH_ROWS / 64 : PATCH_ROWS / (64 * NW);
+  static constexpr int A_LOADS = BY_PLANE ? A_PASSES : A_PASSES * CPR;  // per lane and block
   static constexpr int A_SLICES = 6;              // dealt over the first 6 tap slices of a block
   static constexpr int B_ROWS_PER_PASS = NT / CPR;
   static constexpr int B_ITERS = BN / B_ROWS_PER_PASS;
   static constexpr int B_STAGE_BYTES = BN * ROWB;
   static constexpr int LDS_BYTES = 2 * PATCH_BYTES + SB * B_STAGE_BYTES;
-  static_assert(PATCH_ROWS % (64 * NW) == 0, "patch rows must divide over the waves");
   static_assert(BN % B_ROWS_PER_PASS == 0 && B_ROWS_PER_PASS % 16 == 0, "filter tile rows");
   static_assert(LDS_BYTES <= 160 * 1024, "does not fit LDS");
-  static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of 32x32");
+  static_assert(WM % BLK == 0 && WN % BLK == 0, "wave tile must be a multiple of the MFMA block");
   static_assert(!(BF16 && TWO_LEVEL), "two-level summation is an fp32 feature");
   // patch loads issued at the end of tap slice t of a block
   static constexpr int a_first(int t) { return t >= A_SLICES ? A_LOADS : t * A_LOADS / A_SLICES; }
@@ -1020,6 +1037,8 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   constexpr int BM = T::BM, BN = T::BN, BK = T::BK, ROWB = T::ROWB, CPR = T::CPR, SB = T::SB;
   constexpr int ES = T::ES, VEC = T::VEC, KSTEPS = T::KSTEPS;
   constexpr int TM = T::TM, TN = T::TN, NM = T::NM, NR = T::NR, MPF = T::MPF;
+  constexpr int BLK = T::BLK, ACC = T::ACC;
+  using Acc = std::conditional_t<T::MF16, floatx4, floatx16>;
   __shared__ __align__(1024) unsigned char ring[T::LDS_BYTES];
   constexpr int B_REGION = 2 * T::PATCH_BYTES;
 
@@ -1028,8 +1047,8 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   const int wave = tid >> 6;
   const int wm = wave / T::WAVES_N;
   const int wn = wave % T::WAVES_N;
-  const int lr = lane & 31;
-  const int lk = lane >> 5;
+  const int lr = lane & (BLK - 1);   // row / column of the lane inside an MFMA block
+  const int lk = lane / BLK;         // its group of 8 (bf16) / 4 (fp32) k values
 
   const int tiles_n = (p.K + BN - 1) / BN;
   const int nwg = gridDim.x;
@@ -1063,14 +1082,14 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   for (int i = 0; i < T::A_PASSES; ++i) {
     if constexpr (T::BW > 0) {
       // entry e of the patch: row e / PW, column e % PW of the input block
-      const int e = (i * T::NW + wave) * 64 + lane;
+      const int e = (T::BY_PLANE ? i : i * T::NW + wave) * 64 + lane;
       const int dy = e / T::PW, dx = e % T::PW;
       const int h = blk_p - p.pt + dy, w = blk_q - p.pl + dx;
       const bool ok = dy < T::BH + 2 && static_cast<unsigned>(h) < static_cast<unsigned>(p.H) &&
                       static_cast<unsigned>(w) < static_cast<unsigned>(p.W);
       a_voff[i] = ok ? ((blk_n * p.H + h) * p.W + w) * p.C * ES : kOutOfRange;
     } else {
-      const long long v = v0 + (i * T::NW + wave) * 64 + lane;
+      const long long v = v0 + (T::BY_PLANE ? i : i * T::NW + wave) * 64 + lane;
       const int w = static_cast<int>(v % Wp) - p.pl;
       const long long t = v / Wp;
       const int h = static_cast<int>(t % Hp) - p.pt;
@@ -1101,26 +1120,33 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   };
   // patch load number j (pass j / CPR, plane j % CPR) into patch buffer `buf`
   auto load_a = [&](int buf, int j) {
-    const int i = j / CPR, c = j % CPR;
-    dma16(in_rsrc, ring_base + buf * T::PATCH_BYTES + c * T::PLANE_BYTES + i * T::NW * 1024,
-          a_voff[i], a_next_block_bytes + c * 16);
+    if constexpr (T::BY_PLANE) {
+      // chunk j of plane `wave` (ring_base - wave * 1024 is the start of the ring)
+      const int w = __builtin_amdgcn_readfirstlane(wave);
+      dma16(in_rsrc, ring_base + buf * T::PATCH_BYTES + w * (T::PLANE_BYTES - 1024) + j * 1024,
+            a_voff[j], a_next_block_bytes + w * 16);
+    } else {
+      const int i = j / CPR, c = j % CPR;
+      dma16(in_rsrc, ring_base + buf * T::PATCH_BYTES + c * T::PLANE_BYTES + i * T::NW * 1024,
+            a_voff[i], a_next_block_bytes + c * 16);
+    }
   };
 
-  floatx16 acc[TM][TN];
+  Acc acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  floatx16 total[T::TWO_LEVEL ? TM : 1][T::TWO_LEVEL ? TN : 1];
+      for (int v = 0; v < ACC; ++v) acc[i][j][v] = 0.f;
+  Acc total[T::TWO_LEVEL ? TM : 1][T::TWO_LEVEL ? TN : 1];
   if (T::TWO_LEVEL) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) total[i][j][v] = 0.f;
+        for (int v = 0; v < ACC; ++v) total[i][j][v] = 0.f;
   }
   int until_flush = flush_slices;
 
@@ -1131,10 +1157,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     if constexpr (T::BW > 0) {
-      const int ml = wm * T::WM + i * 32 + lr;  // pixel (ml / BW, ml % BW) of the block
+      const int ml = wm * T::WM + i * BLK + lr;  // pixel (ml / BW, ml % BW) of the block
       a_frag[i] = ((ml / T::BW) * T::PW + ml % T::BW) * 16 + lk * T::PLANE_BYTES;
     } else {
-      const int m = min(m0 + wm * T::WM + i * 32 + lr, p.M - 1);
+      const int m = min(m0 + wm * T::WM + i * BLK + lr, p.M - 1);
       a_frag[i] = static_cast<int>(patch_base(p, Hp, Wp, m) - v0) * 16 + lk * T::PLANE_BYTES;
     }
   }
@@ -1151,17 +1177,23 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   // byte offset a_off (buffer + tap), B from filter stage `bstage`.
   auto read_frag = [&](auto buf_c, int a_off, int bstage, int kk, int r) {
     constexpr int buf = decltype(buf_c)::value;
+    // (16-row blocks: one buffer for the A fragments, two only for the last)
     if (r < TM)
-      af[buf][r] = *reinterpret_cast<const uintx4*>(ring + a_frag[r] + a_off +
-                                                    2 * kk * T::PLANE_BYTES);
+      af[T::MF16 && r < TM - 1 ? 0 : buf][r] = *reinterpret_cast<const uintx4*>(
+          ring + a_frag[r] + a_off + 2 * kk * T::PLANE_BYTES);
     else
       bf[buf][r - TM] = *reinterpret_cast<const uintx4*>(
-          b_frag + bstage * T::B_STAGE_BYTES + (r - TM) * 32 * ROWB + chunk_bytes[kk]);
+          b_frag + bstage * T::B_STAGE_BYTES + (r - TM) * BLK * ROWB + chunk_bytes[kk]);
   };
   auto mfma = [&](auto buf_c, int m) {
     constexpr int buf = decltype(buf_c)::value;
     const int i = m / (TN * MPF), j = (m / MPF) % TN, t = m % MPF;
-    if constexpr (T::BF16) {
+    if constexpr (T::MF16) {
+      // transposed block: features x pixels
+      acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+          __builtin_bit_cast(bf16x8, bf[buf][j]),
+          __builtin_bit_cast(bf16x8, af[i < TM - 1 ? 0 : buf][i]), acc[i][j], 0, 0, 0);
+    } else if constexpr (T::BF16) {
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
           __builtin_bit_cast(bf16x8, af[buf][i]), __builtin_bit_cast(bf16x8, bf[buf][j]), acc[i][j],
           0, 0, 0);
@@ -1194,8 +1226,34 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   // this wave's LDS reads), barrier, read the next slice's first fragments,
   // load the filter slice SB ahead into the stage just released, and this
   // slice's share of the next block's patch.
-  auto tap_slice = [&](auto t_c) {
+  // The same for 16-row blocks, where the A fragments have a single buffer (registers): the
+  // next slice's A fragment i is read right after the last MFMA that uses this slice's
+  // (MFMAs run A block by A block), everything else fills the other gaps in order.  The last
+  // A fragment would be read after the slice's last MFMA, right before the next slice's wait
+  // for all LDS reads; it has two buffers and is read early, as one of the other items.
+  auto run_step16 = [&](auto cur_c, int nside, auto side, auto read_a) {
+    int item = 0;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      mfma(cur_c, m);
+      if (m % TN == TN - 1 && m / TN < TM - 1) {
+        read_a(m / TN);
+      } else if (item < nside) {
+        side(item);
+        ++item;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  static_assert(!T::MF16 || 3 + TN + T::B_ITERS + T::A_LOADS <= NM - TM, "side items need gaps");
+
+  // With one step per slice (16-row blocks) the B fragment buffers alternate per slice: `par`
+  // is the buffer that holds this slice's.
+  auto tap_slice = [&](auto t_c, auto par_c) {
     constexpr int t = decltype(t_c)::value;
+    constexpr int par = decltype(par_c)::value;
+    using Cur = std::integral_constant<int, KSTEPS == 2 ? 1 : par>;
+    using Nxt = std::integral_constant<int, KSTEPS == 2 ? 0 : (par ^ 1)>;
     constexpr int bstage = t % SB;
     constexpr int tn = (t + 1) % taps;
     const int a_cur = a_buf_off + ((t / 3) * Wp + t % 3) * 16;
@@ -1206,14 +1264,37 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
     // loads younger than the next slice's filter tile: the filter tile after
     // it and the patch loads of the two slices before this one
     constexpr int wait_n = T::B_ITERS + T::a_count(t - 2) + T::a_count(t - 1);
-    run_step(Buf0{}, NR, [&](int item) { read_frag(Buf1{}, a_cur, bstage, 1, item); });
-    run_step(Buf1{}, 1 + NR + T::B_ITERS + a_n + 1, [&](int item) {
+    if constexpr (T::MF16) {
+      run_step16(
+          Cur{}, 2 + TN + T::B_ITERS + a_n + 1,
+          [&](int item) {
+            if (item == 0) {
+              __builtin_amdgcn_s_waitcnt(vmcnt_lds_imm(wait_n));
+              __builtin_amdgcn_s_barrier();
+              asm volatile("" ::: "memory");  // LDS changed behind the compiler's back
+            } else if (item <= TN) {
+              read_frag(Nxt{}, a_nxt, (bstage + 1) % SB, 0, TM + item - 1);
+            } else if (item == TN + 1) {
+              read_frag(Nxt{}, a_nxt, (bstage + 1) % SB, 0, TM - 1);
+            } else if (item <= 1 + TN + T::B_ITERS) {
+              load_b(bstage, item - TN - 2);
+            } else if (item <= 1 + TN + T::B_ITERS + a_n) {
+              load_a(a_load_buf, a_from + item - TN - T::B_ITERS - 2);
+            } else {
+              k_next_bytes = min(k_next_bytes + k_slice_bytes, k_last_bytes);
+            }
+          },
+          [&](int i) { read_frag(Nxt{}, a_nxt, (bstage + 1) % SB, 0, i); });
+    } else {
+    if constexpr (KSTEPS == 2)
+      run_step(Buf0{}, NR, [&](int item) { read_frag(Buf1{}, a_cur, bstage, 1, item); });
+    run_step(Cur{}, 1 + NR + T::B_ITERS + a_n + 1, [&](int item) {
       if (item == 0) {
         __builtin_amdgcn_s_waitcnt(vmcnt_lds_imm(wait_n));
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");  // LDS changed behind the compiler's back
       } else if (item <= NR) {
-        read_frag(Buf0{}, a_nxt, (bstage + 1) % SB, 0, item - 1);
+        read_frag(Nxt{}, a_nxt, (bstage + 1) % SB, 0, item - 1);
       } else if (item <= NR + T::B_ITERS) {
         load_b(bstage, item - NR - 1);
       } else if (item <= NR + T::B_ITERS + a_n) {
@@ -1222,6 +1303,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
         k_next_bytes = min(k_next_bytes + k_slice_bytes, k_last_bytes);
       }
     });
+    }
     if (T::TWO_LEVEL) {
       if (--until_flush == 0) {
         until_flush = flush_slices;
@@ -1230,12 +1312,25 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
 #pragma unroll
           for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
+            for (int v = 0; v < ACC; ++v) {
               total[i][j][v] += acc[i][j][v];
               acc[i][j][v] = 0.f;
             }
       }
     }
+  };
+  // the nine tap slices of a channel block whose first slice's fragments are in buffer `bp`
+  auto channel_block = [&](auto bp_c) {
+    constexpr int bp = decltype(bp_c)::value;
+    tap_slice(std::integral_constant<int, 0>{}, std::integral_constant<int, bp>{});
+    tap_slice(std::integral_constant<int, 1>{}, std::integral_constant<int, bp ^ 1>{});
+    tap_slice(std::integral_constant<int, 2>{}, std::integral_constant<int, bp>{});
+    tap_slice(std::integral_constant<int, 3>{}, std::integral_constant<int, bp ^ 1>{});
+    tap_slice(std::integral_constant<int, 4>{}, std::integral_constant<int, bp>{});
+    tap_slice(std::integral_constant<int, 5>{}, std::integral_constant<int, bp ^ 1>{});
+    tap_slice(std::integral_constant<int, 6>{}, std::integral_constant<int, bp>{});
+    tap_slice(std::integral_constant<int, 7>{}, std::integral_constant<int, bp ^ 1>{});
+    tap_slice(std::integral_constant<int, 8>{}, std::integral_constant<int, bp>{});
   };
 
   // prologue: the first block's patch and the first SB filter slices in
@@ -1255,20 +1350,31 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   for (int r = 0; r < NR; ++r) read_frag(Buf0{}, 0, 0, 0, r);
   __builtin_amdgcn_sched_barrier(0);
 
-  for (int block = 0; block < nblocks; ++block) {
-    // the patch loaded during this block is the next block's (past the end:
-    // the last one again, into the buffer nobody reads)
-    a_next_block_bytes = min((block + 1) * ROWB, a_last_block_bytes);
-    tap_slice(std::integral_constant<int, 0>{});
-    tap_slice(std::integral_constant<int, 1>{});
-    tap_slice(std::integral_constant<int, 2>{});
-    tap_slice(std::integral_constant<int, 3>{});
-    tap_slice(std::integral_constant<int, 4>{});
-    tap_slice(std::integral_constant<int, 5>{});
-    tap_slice(std::integral_constant<int, 6>{});
-    tap_slice(std::integral_constant<int, 7>{});
-    tap_slice(std::integral_constant<int, 8>{});
-    a_buf_off ^= T::PATCH_BYTES;
+  // the patch loaded during a block is the next block's (past the end: the last one again,
+  // into the buffer nobody reads)
+  if constexpr (KSTEPS == 2) {
+    for (int block = 0; block < nblocks; ++block) {
+      a_next_block_bytes = min((block + 1) * ROWB, a_last_block_bytes);
+      channel_block(Buf0{});
+      a_buf_off ^= T::PATCH_BYTES;
+    }
+  } else {
+    // nine slices per block and one step per slice: the fragment buffer parity flips from
+    // block to block, so the loop body is a pair of blocks
+    int block = 0;
+    for (; block + 1 < nblocks; block += 2) {
+      a_next_block_bytes = min((block + 1) * ROWB, a_last_block_bytes);
+      channel_block(Buf0{});
+      a_buf_off ^= T::PATCH_BYTES;
+      a_next_block_bytes = min((block + 2) * ROWB, a_last_block_bytes);
+      channel_block(Buf1{});
+      a_buf_off ^= T::PATCH_BYTES;
+    }
+    if (block < nblocks) {
+      a_next_block_bytes = a_last_block_bytes;
+      channel_block(Buf0{});
+      a_buf_off ^= T::PATCH_BYTES;
+    }
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // drain the loads issued past the end
   if (T::TWO_LEVEL) {
@@ -1277,9 +1383,65 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][j][v] += total[i][j][v];
+        for (int v = 0; v < ACC; ++v) acc[i][j][v] += total[i][j][v];
   }
 
+  if constexpr (T::MF16) {
+    // ---- epilogue of the transposed 16x16 blocks: lane l, register v -> pixel l % 16,
+    // feature 4 * (l / 16) + v of the block: four consecutive features per lane
+    float bias4[TN][4];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        bias4[j][v] = bias_of(p.bias, n0 + wn * T::WN + j * BLK + lk * 4 + v, p.K);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) asm volatile("" : "+v"(bias4[j][v]));
+    const bool vec_ok = (p.K & 3) == 0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      int row = m0 + wm * T::WM + i * BLK + lr;
+      bool row_ok = row < p.M;
+      if constexpr (T::BW > 0) {
+        const int ml = row - m0;  // position in the block
+        const int op = blk_p + ml / T::BW, oq = blk_q + ml % T::BW;
+        row_ok = op < p.P && oq < p.Q;
+        row = (blk_n * p.P + op) * p.Q + oq;
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn * T::WN + j * BLK + lk * 4;
+        float r[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) r[v] = finish(acc[i][j][v], bias4[j][v], p.relu);
+        if (row_ok) {
+          const size_t idx = static_cast<size_t>(row) * p.K + col;
+          if (vec_ok && col + 3 < p.K) {
+            if (OUT_BF16) {
+              uint2 packed;
+              packed.x = to_bf16_bits(r[0]) | (static_cast<unsigned>(to_bf16_bits(r[1])) << 16);
+              packed.y = to_bf16_bits(r[2]) | (static_cast<unsigned>(to_bf16_bits(r[3])) << 16);
+              *reinterpret_cast<uint2*>(static_cast<unsigned short*>(p.out) + idx) = packed;
+            } else {
+              *reinterpret_cast<float4*>(static_cast<float*>(p.out) + idx) =
+                  make_float4(r[0], r[1], r[2], r[3]);
+            }
+          } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              if (col + v < p.K) {
+                if (OUT_BF16)
+                  static_cast<unsigned short*>(p.out)[idx + v] = to_bf16_bits(r[v]);
+                else
+                  static_cast<float*>(p.out)[idx + v] = r[v];
+              }
+          }
+        }
+      }
+    }
+  } else {
   // The bias of this lane's columns, fetched before the first store.  The empty asm makes the
   // values "arrive" here, in uniform control flow: left to itself the compiler waits for the
   // loads inside every bounds-checked store block, and that wait (the counter covers loads
@@ -1319,6 +1481,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
       }
     }
   }
+  }  // 32-row blocks
 }
 
 // Largest number of patch entries any tile of the problem needs.
@@ -1404,6 +1567,21 @@ struct TileEntry {
     &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>>,                     \
     &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>>, nullptr }
 
+// 16-row MFMA blocks (tile heights that are multiples of 7 * 32)
+#define CONV2D_PATCH_TILE_M16(dt, isbf, bm, bn, wm, wn, rows, occ)                               \
+  { "igemm_patch_" dt "_" #bm "x" #bn "_w" #wm "x" #wn "_p" #rows "_m16", bm, bn,               \
+    PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, 0, true>::BK, occ, 3,                      \
+    &launch_patch<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, 0, true>>,                   \
+    &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, 0, true>>,          \
+    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, 0, true>>, nullptr }
+
+#define CONV2D_PATCH_TILE_M16B(dt, isbf, bm, bn, wm, wn, rows, occ, bw)                          \
+  { "igemm_patch_" dt "_" #bm "x" #bn "_w" #wm "x" #wn "_p" #rows "_b" #bw "_m16", bm, bn,      \
+    PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true>::BK, occ, 3,                     \
+    &launch_patch<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true>>,                  \
+    &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true>>,         \
+    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true>>, nullptr }
+
 // blocked patch tiles: bm / bw x bw output pixels of one image
 #define CONV2D_PATCH_TILE_B(dt, isbf, bm, bn, wm, wn, rows, two, occ, bw)                        \
   { "igemm_patch_" dt "_" #bm "x" #bn "_w" #wm "x" #wn "_p" #rows "_b" #bw, bm, bn,              \
@@ -1445,6 +1623,8 @@ const TileEntry kTilesBf16[] = {
     CONV2D_PATCH_TILE("bf16", true, 256, 256, 2, 2, 512, false, 1),
     CONV2D_PATCH_TILE("bf16", true, 256, 128, 4, 2, 512, false, 1),
     CONV2D_PATCH_TILE("bf16", true, 224, 256, 1, 4, 512, false, 1),
+    CONV2D_PATCH_TILE_M16("bf16", true, 224, 128, 2, 2, 384, 2),
+    CONV2D_PATCH_TILE_M16B("bf16", true, 224, 128, 2, 2, 384, 2, 16),
     CONV2D_PATCH_TILE_B("bf16", true, 256, 256, 4, 2, 512, false, 1, 16),
     CONV2D_PATCH_TILE_B("bf16", true, 256, 128, 4, 2, 512, false, 1, 16),
     CONV2D_PATCH_TILE_B("bf16", true, 256, 64, 4, 1, 512, false, 2, 16),
