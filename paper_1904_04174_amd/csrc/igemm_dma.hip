@@ -66,6 +66,7 @@ typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kXcds = 8;
+constexpr int kComputeUnits = 256;
 constexpr unsigned kRsrcFlags = 0x00020000u;
 constexpr int kOutOfRange = static_cast<int>(0x80000000u);
 
@@ -991,6 +992,9 @@ struct PatchTile {
   static constexpr bool TWO_LEVEL = TWO_LEVEL_;
   static constexpr int OCC = OCC_;
   static constexpr int ADDR = 3;
+  // blocked tiles of 32-row blocks: a workgroup takes several tiles, one after the other (the
+  // 16-row tiles were slower that way: 71.9 -> 81.0 us on a 112x112x128 layer at batch 16)
+  static constexpr bool PERSIST = BW_ > 0 && !MF16_;
   static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int NW = WAVES_M * WAVES_N;
   static constexpr int NT = 64 * NW;
@@ -1033,7 +1037,8 @@ template <class T, bool OUT_BF16>
 __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Problem p, const int Hp,
                                                                     const int Wp,
                                                                     const int flush_slices,
-                                                                    const void* bt) {
+                                                                    const void* bt,
+                                                                    const int ntiles) {
   constexpr int BM = T::BM, BN = T::BN, BK = T::BK, ROWB = T::ROWB, CPR = T::CPR, SB = T::SB;
   constexpr int ES = T::ES, VEC = T::VEC, KSTEPS = T::KSTEPS;
   constexpr int TM = T::TM, TN = T::TN, NM = T::NM, NR = T::NR, MPF = T::MPF;
@@ -1050,23 +1055,32 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   const int lr = lane & (BLK - 1);   // row / column of the lane inside an MFMA block
   const int lk = lane / BLK;         // its group of 8 (bf16) / 4 (fp32) k values
 
+  // Tiles of this workgroup.  Each XCD owns a contiguous range of tiles (feature tiles
+  // fastest); workgroup i runs on XCD i % 8.  Persistent tiles (blocked, 32-row blocks) are
+  // launched with at most OCC workgroups per compute unit, and a workgroup walks its XCD's
+  // range with the stride of that XCD's workgroup count, loading the next tile's patch and
+  // first filter slices while it finishes the current one; all others get one tile each.
+  constexpr bool PERSIST = T::PERSIST;
   const int tiles_n = (p.K + BN - 1) / BN;
   const int nwg = gridDim.x;
   const int xcd = blockIdx.x % kXcds;
   const int local = blockIdx.x / kXcds;
-  const int per = nwg / kXcds, rem = nwg % kXcds;
-  const int tile = xcd * per + (xcd < rem ? xcd : rem) + local;
-  const int m0 = (tile / tiles_n) * BM;   // consecutive-pixel tiles: first output pixel
-  const int n0 = (tile % tiles_n) * BN;
+  const int per = ntiles / kXcds, rem = ntiles % kXcds;
+  const int tile_end = xcd * per + (xcd < rem ? xcd : rem) + per + (xcd < rem ? 1 : 0);
+  const int tile_step = nwg / kXcds + (xcd < nwg % kXcds ? 1 : 0);
+  int tile = tile_end - (per + (xcd < rem ? 1 : 0)) + local;
+  int m0 = (tile / tiles_n) * BM;   // consecutive-pixel tiles: first output pixel
+  int n0 = (tile % tiles_n) * BN;
   // blocked tiles: image and top-left output pixel of the block
   int blk_n = 0, blk_p = 0, blk_q = 0;
-  if constexpr (T::BW > 0) {
+  auto block_of = [&](int t, int& bn, int& bp, int& bq) {
     const int nbx = (p.Q + T::BW - 1) / T::BW, nby = (p.P + T::BH - 1) / T::BH;
-    const int tm = tile / tiles_n;
-    blk_q = (tm % nbx) * T::BW;
-    blk_p = ((tm / nbx) % nby) * T::BH;
-    blk_n = tm / (nbx * nby);
-  }
+    const int tm = t / tiles_n;
+    bq = (tm % nbx) * T::BW;
+    bp = ((tm / nbx) % nby) * T::BH;
+    bn = tm / (nbx * nby);
+  };
+  if constexpr (T::BW > 0) block_of(tile, blk_n, blk_p, blk_q);
   constexpr int taps = 9;
   const int nblocks = p.C / BK;      // channel blocks
   const int Kg_p = p.Kg;             // C is a multiple of BK
@@ -1078,17 +1092,23 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   // ---- patch loader role: entries (pass*NW + wave)*64 + lane of the patch
   const long long v0 = T::BW > 0 ? 0 : patch_base(p, Hp, Wp, m0);
   int a_voff[T::A_PASSES];
+  // blocked tiles: the patch offsets of the block at (bn, bp, bq)
+  auto block_patch_offsets = [&](int bn, int bp, int bq, int (&voff)[T::A_PASSES]) {
 #pragma unroll
-  for (int i = 0; i < T::A_PASSES; ++i) {
-    if constexpr (T::BW > 0) {
+    for (int i = 0; i < T::A_PASSES; ++i) {
       // entry e of the patch: row e / PW, column e % PW of the input block
       const int e = (T::BY_PLANE ? i : i * T::NW + wave) * 64 + lane;
       const int dy = e / T::PW, dx = e % T::PW;
-      const int h = blk_p - p.pt + dy, w = blk_q - p.pl + dx;
+      const int h = bp - p.pt + dy, w = bq - p.pl + dx;
       const bool ok = dy < T::BH + 2 && static_cast<unsigned>(h) < static_cast<unsigned>(p.H) &&
                       static_cast<unsigned>(w) < static_cast<unsigned>(p.W);
-      a_voff[i] = ok ? ((blk_n * p.H + h) * p.W + w) * p.C * ES : kOutOfRange;
-    } else {
+      voff[i] = ok ? ((bn * p.H + h) * p.W + w) * p.C * ES : kOutOfRange;
+    }
+  };
+  if constexpr (T::BW > 0) block_patch_offsets(blk_n, blk_p, blk_q, a_voff);
+#pragma unroll
+  for (int i = 0; i < T::A_PASSES; ++i) {
+    if constexpr (T::BW == 0) {
       const long long v = v0 + (T::BY_PLANE ? i : i * T::NW + wave) * 64 + lane;
       const int w = static_cast<int>(v % Wp) - p.pl;
       const long long t = v / Wp;
@@ -1103,16 +1123,24 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   const int ld_row0 = tid / CPR;
   const int ld_chunk = (tid % CPR) ^ ((ld_row0 >> 1) & (CPR - 1));
   int b_voff[T::B_ITERS];
+  auto filter_offsets = [&](int col0, int (&voff)[T::B_ITERS]) {
 #pragma unroll
-  for (int i = 0; i < T::B_ITERS; ++i) {
-    const int n = n0 + ld_row0 + i * T::B_ROWS_PER_PASS;
-    b_voff[i] = (n < p.K) ? (n * BK + ld_chunk * VEC) * ES : kOutOfRange;
-  }
+    for (int i = 0; i < T::B_ITERS; ++i) {
+      const int n = col0 + ld_row0 + i * T::B_ROWS_PER_PASS;
+      voff[i] = (n < p.K) ? (n * BK + ld_chunk * VEC) * ES : kOutOfRange;
+    }
+  };
+  filter_offsets(n0, b_voff);
   const int k_slice_bytes = p.K * ROWB;
   const int k_last_bytes = (nblocks * taps - 1) * k_slice_bytes;
-  int k_next_bytes = 0;
+  int k_next_bytes = 0;         // filter slice to load next; wraps into the next tile's
   int a_next_block_bytes = 0;   // channel offset (bytes) of the patch being loaded
-  const int a_last_block_bytes = (nblocks - 1) * ROWB;
+  // Persistent tiles: the loads of a tile's last channel block (patch) and last SB slices
+  // (filter) fetch the workgroup's next tile's (or nothing: out-of-range offsets); the loader
+  // offsets are switched at those points.
+  bool last_block = false;
+  int tile_next = 0, n0_next = 0, next_n = 0, next_p = 0, next_q = 0;
+  bool has_next = false;
 
   auto load_b = [&](int stage, int i) {
     dma16(bt_rsrc, ring_base + B_REGION + stage * T::B_STAGE_BYTES + i * T::B_ROWS_PER_PASS * ROWB,
@@ -1133,21 +1161,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   };
 
   Acc acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < ACC; ++v) acc[i][j][v] = 0.f;
   Acc total[T::TWO_LEVEL ? TM : 1][T::TWO_LEVEL ? TN : 1];
-  if (T::TWO_LEVEL) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int v = 0; v < ACC; ++v) total[i][j][v] = 0.f;
-  }
   int until_flush = flush_slices;
 
   // ---- fragment addressing.  A: patch entry of the lane's output pixel in
@@ -1264,6 +1278,17 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
     // loads younger than the next slice's filter tile: the filter tile after
     // it and the patch loads of the two slices before this one
     constexpr int wait_n = T::B_ITERS + T::a_count(t - 2) + T::a_count(t - 1);
+    // the filter loads of a tile's last SB slices fetch the next tile's first slices
+    // (a tile without a successor loads its own first slices again, into stages nobody reads)
+    if constexpr (PERSIST && t == taps - SB) {
+      if (last_block) {
+        filter_offsets(n0_next, b_voff);
+        if (!has_next) {
+#pragma unroll
+          for (int i = 0; i < T::B_ITERS; ++i) b_voff[i] = kOutOfRange;
+        }
+      }
+    }
     if constexpr (T::MF16) {
       run_step16(
           Cur{}, 2 + TN + T::B_ITERS + a_n + 1,
@@ -1281,7 +1306,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
             } else if (item <= 1 + TN + T::B_ITERS + a_n) {
               load_a(a_load_buf, a_from + item - TN - T::B_ITERS - 2);
             } else {
-              k_next_bytes = min(k_next_bytes + k_slice_bytes, k_last_bytes);
+              k_next_bytes = k_next_bytes >= k_last_bytes ? 0 : k_next_bytes + k_slice_bytes;
             }
           },
           [&](int i) { read_frag(Nxt{}, a_nxt, (bstage + 1) % SB, 0, i); });
@@ -1300,7 +1325,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
       } else if (item <= NR + T::B_ITERS + a_n) {
         load_a(a_load_buf, a_from + item - NR - T::B_ITERS - 1);
       } else {
-        k_next_bytes = min(k_next_bytes + k_slice_bytes, k_last_bytes);
+        k_next_bytes = k_next_bytes >= k_last_bytes ? 0 : k_next_bytes + k_slice_bytes;
       }
     });
     }
@@ -1341,7 +1366,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   for (int s = 0; s < SB; ++s) {
 #pragma unroll
     for (int i = 0; i < T::B_ITERS; ++i) load_b(s, i);
-    k_next_bytes = min(k_next_bytes + k_slice_bytes, k_last_bytes);
+    k_next_bytes = k_next_bytes >= k_last_bytes ? 0 : k_next_bytes + k_slice_bytes;
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm((SB - 1) * T::B_ITERS));
   __builtin_amdgcn_s_barrier();
@@ -1350,11 +1375,67 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   for (int r = 0; r < NR; ++r) read_frag(Buf0{}, 0, 0, 0, r);
   __builtin_amdgcn_sched_barrier(0);
 
-  // the patch loaded during a block is the next block's (past the end: the last one again,
-  // into the buffer nobody reads)
+  // The patch loaded during a channel block is the next block's; during a tile's last block it
+  // is the first block of the workgroup's next tile (or nothing).
+  auto begin_block = [&](int block) {
+    if constexpr (PERSIST) {
+      last_block = block == nblocks - 1;
+      a_next_block_bytes = last_block ? 0 : (block + 1) * ROWB;
+      if (last_block) {
+        block_patch_offsets(next_n, next_p, next_q, a_voff);
+        if (!has_next) {
+#pragma unroll
+          for (int i = 0; i < T::A_PASSES; ++i) a_voff[i] = kOutOfRange;
+        }
+      }
+    } else {
+      // (past the end: the last block again, into the buffer nobody reads)
+      a_next_block_bytes = min(block + 1, nblocks - 1) * ROWB;
+    }
+  };
+
+  for (;;) {
+  // ---- the workgroup's next tile, if any
+  tile_next = tile + tile_step;
+  has_next = PERSIST && tile_next < tile_end;
+  if constexpr (PERSIST) {
+    if (has_next) {
+      block_of(tile_next, next_n, next_p, next_q);
+      n0_next = (tile_next % tiles_n) * BN;
+    }
+  }
+  // The bias of this lane's columns (32-row blocks), fetched before the tile's loop.  The empty
+  // asm makes the values "arrive" here, in uniform control flow: left to itself the compiler
+  // waits for the loads inside every bounds-checked store block, and that wait (the counter
+  // covers loads and stores alike) drains all earlier stores each time, one round trip per
+  // store.  At this point it only waits for loads that the first slice needs anyway.
+  float bias_col[TN];
+  if constexpr (!T::MF16) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      bias_col[j] = bias_of(p.bias, n0 + wn * T::WN + j * 32 + lr, p.K);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(bias_col[j]));
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < ACC; ++v) acc[i][j][v] = 0.f;
+  if (T::TWO_LEVEL) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < ACC; ++v) total[i][j][v] = 0.f;
+    until_flush = flush_slices;
+  }
+
   if constexpr (KSTEPS == 2) {
     for (int block = 0; block < nblocks; ++block) {
-      a_next_block_bytes = min((block + 1) * ROWB, a_last_block_bytes);
+      begin_block(block);
       channel_block(Buf0{});
       a_buf_off ^= T::PATCH_BYTES;
     }
@@ -1363,20 +1444,19 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
     // block to block, so the loop body is a pair of blocks
     int block = 0;
     for (; block + 1 < nblocks; block += 2) {
-      a_next_block_bytes = min((block + 1) * ROWB, a_last_block_bytes);
+      begin_block(block);
       channel_block(Buf0{});
       a_buf_off ^= T::PATCH_BYTES;
-      a_next_block_bytes = min((block + 2) * ROWB, a_last_block_bytes);
+      begin_block(block + 1);
       channel_block(Buf1{});
       a_buf_off ^= T::PATCH_BYTES;
     }
     if (block < nblocks) {
-      a_next_block_bytes = a_last_block_bytes;
+      begin_block(block);
       channel_block(Buf0{});
       a_buf_off ^= T::PATCH_BYTES;
     }
   }
-  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // drain the loads issued past the end
   if (T::TWO_LEVEL) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -1442,16 +1522,6 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
       }
     }
   } else {
-  // The bias of this lane's columns, fetched before the first store.  The empty asm makes the
-  // values "arrive" here, in uniform control flow: left to itself the compiler waits for the
-  // loads inside every bounds-checked store block, and that wait (the counter covers loads
-  // and stores alike) drains all earlier stores each time, one round trip per store.
-  float bias_col[TN];
-#pragma unroll
-  for (int j = 0; j < TN; ++j)
-    bias_col[j] = bias_of(p.bias, n0 + wn * T::WN + j * 32 + lr, p.K);
-#pragma unroll
-  for (int j = 0; j < TN; ++j) asm volatile("" : "+v"(bias_col[j]));
   // ---- epilogue (accumulator layout: lane l reg v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32)
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -1482,6 +1552,18 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
     }
   }
   }  // 32-row blocks
+
+  if (!has_next) break;
+  // on to the next tile: its patch and first filter slices are in flight or landed, its first
+  // fragments are in registers, the loader offsets were switched during the last block
+  tile = tile_next;
+  n0 = n0_next;
+  m0 = (tile / tiles_n) * BM;
+  blk_n = next_n;
+  blk_p = next_p;
+  blk_q = next_q;
+  }  // tiles of this workgroup
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // drain the loads issued past the end
 }
 
 // Largest number of patch entries any tile of the problem needs.
@@ -1533,8 +1615,10 @@ hipError_t launch_patch_one(const Problem& p, hipStream_t stream) {
   while (flush * flush < nslices) ++flush;
   // width of the patch rows: the padded image's, or the block's own
   const int patch_width = T::BW > 0 ? T::PW : p.Q + p.S - 1;
-  hipLaunchKernelGGL((igemm_patch_kernel<T, OUT_BF16>), dim3(tiles), dim3(T::NT), 0, stream, p,
-                     p.P + p.R - 1, patch_width, flush, p.workspace);
+  const int resident = kComputeUnits * T::OCC;
+  const int grid = T::PERSIST && tiles > resident ? resident : tiles;
+  hipLaunchKernelGGL((igemm_patch_kernel<T, OUT_BF16>), dim3(grid), dim3(T::NT), 0, stream, p,
+                     p.P + p.R - 1, patch_width, flush, p.workspace, tiles);
   return hipGetLastError();
 }
 

@@ -532,6 +532,37 @@ def test_bias_relu_full_size(torch_cuda, oracle, name):
 
 # ------------------------------------------------------------------ HIP graph capture
 
+@pytest.mark.parametrize("shape", [(32, 70, 70, 64, 80), (24, 50, 83, 96, 200)])
+def test_patch_tiles_with_more_tiles_than_resident_workgroups(torch_cuda, oracle, shape):
+    """The blocked patch tiles run persistently (a workgroup takes several tiles and loads the
+    next tile's patch and filter slices while it finishes the current one) once a layer has more
+    tiles than resident workgroups; the 224-row tiles are checked on the same shapes.  Ragged
+    blocks at the image edge, two and three channel blocks, feature tiles that change from tile
+    to tile.  Integer inputs: bit-exact, also through the fused bias + ReLU epilogue."""
+    n, h, w, c, k = shape
+    rng = np.random.default_rng(sum(shape))
+    x = rng.integers(-4, 5, size=(n, h, w, c)).astype(np.float32)
+    f = rng.integers(-4, 5, size=(3, 3, c, k)).astype(np.float32)
+    bias = rng.integers(-4, 5, size=k).astype(np.float32)
+    want = oracle.forward_f32(x, f, 1, wl.PAD_SAME)
+    want_fused = oracle.forward_bias_act_f32(x, f, bias, True, 1, wl.PAD_SAME)
+    ran = 0
+    for dt in (B.F32, B.BF16):
+        p = B.make_params(n, h, w, c, k, 3, 3, 1, 1, wl.PAD_SAME, dt, B.F32)
+        for v in range(B.conv2d_num_variants()):
+            name = B.conv2d_variant_name(v)
+            if not (name.startswith("igemm_patch_") and ("_b16" in name or "_m16" in name)):
+                continue
+            if name.endswith(("_splitk", "_tail")) or not B.conv2d_variant_supports(p, v):
+                continue
+            _say("persistent patch %s %s" % (shape, name))
+            assert np.array_equal(run_gpu(torch_cuda, p, x, f, variant_id=v), want), name
+            got = run_gpu_fused(torch_cuda, p, x, f, bias, B.ACT_RELU, force=v)
+            assert np.array_equal(got, want_fused), name
+            ran += 1
+    assert ran >= 5, ran
+
+
 def test_calls_can_be_captured_in_a_hip_graph(torch_cuda, oracle):
     """The library only enqueues kernels (no allocation, no memset, no synchronisation), so a
     sequence of calls can be captured into a HIP graph.  Several replays, with eager work and
