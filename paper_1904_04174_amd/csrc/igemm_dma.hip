@@ -1691,6 +1691,7 @@ struct TileEntry {
 const TileEntry kTilesF32[] = {
     CONV2D_PATCH_TILE("f32", false, 128, 128, 2, 2, 512, true, 1),
     CONV2D_PATCH_TILE_B("f32", false, 128, 128, 2, 2, 256, true, 2, 16),
+    CONV2D_PATCH_TILE_B("f32", false, 128, 64, 2, 2, 256, true, 3, 16),
     CONV2D_DMA_TILE("f32", false, 128, 128, 64, 2, 2, 4, true, 2, kUniform, ""),
     CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, kUniform, ""),
     CONV2D_DMA_TILE("f32", false, 256, 128, 64, 4, 2, 4, true, 2, kUniform, ""),
