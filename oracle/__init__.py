@@ -8,9 +8,11 @@ from .conv2d_oracle import (  # noqa: F401
     PAD_VALID,
     build,
     forward_bias_act_f32,
+    forward_bias_act_pool_f32,
     forward_f32,
     forward_f64,
     geometry,
+    max_pool_2x2,
     max_threads,
     points_f32,
 )

@@ -146,3 +146,37 @@ def forward_bias_act_f32(x, f, bias=None, relu=False, stride=1, padding=PAD_SAME
     if relu:
         y = np.maximum(y, 0.0)
     return y.astype(np.float32)
+
+
+def max_pool_2x2(y):
+    """2x2 max pooling with stride 2 and no padding over an NHWC array, written out as loops
+    over the four window positions: out[n, i, j, k] = max over a, b in {0, 1} of
+    y[n, 2 i + a, 2 j + b, k]; a trailing odd row or column is dropped.  (The pooling layer
+    that section 3 of the paper names next to the convolutions, in its usual VGG form.)"""
+    y = np.asarray(y)
+    n, h, w, k = y.shape
+    ph, pw = h // 2, w // 2
+    out = np.full((n, ph, pw, k), -np.inf, dtype=y.dtype)
+    for a in range(2):
+        for b in range(2):
+            out = np.maximum(out, y[:, a:2 * ph:2, b:2 * pw:2, :])
+    return out
+
+
+def forward_bias_act_pool_f32(x, f, bias=None, relu=False, stride=1, padding=PAD_SAME,
+                              num_threads=0):
+    """Convolution, bias, activation, then 2x2 max pooling: the plain composition
+    max_pool_2x2(act(conv(x, f) + bias)), everything in fp64 on the float32 data, one rounding
+    to float32 at the end."""
+    y = forward_f64(np.asarray(x, dtype=np.float32).astype(np.float64),
+                    np.asarray(f, dtype=np.float32).astype(np.float64), stride, padding,
+                    num_threads)
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float32).astype(np.float64)
+        if b.shape != (y.shape[3],):
+            raise ValueError("bias must have one value per output feature")
+        y = y + b
+    if relu:
+        y = np.maximum(y, 0.0)
+    return max_pool_2x2(y).astype(np.float32)
+

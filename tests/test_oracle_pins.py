@@ -379,3 +379,58 @@ def test_bias_act_against_brute_force(oracle):
                             acc += float(x[0, p + r, q + s, c]) * float(f[r, s, c, k])
                 want[0, p, q, k] = max(acc, 0.0)
     assert np.array_equal(got, want.astype(np.float32))
+
+
+# ------------------------------------------------------------------ fused 2x2 max pooling
+
+def test_pool_hand_example(oracle):
+    # the worked 4x4 example above (input 0..15, filter 1..9, stride 1, SAME) gives
+    # [[83,139,178,121],[198,303,348,225],[330,483,528,333],[181,253,274,163]]:
+    # its 2x2 windows have the maxima 303, 348 / 483, 528
+    x = np.arange(16, dtype=np.float32).reshape(1, 4, 4, 1)
+    f = np.arange(1, 10, dtype=np.float32).reshape(3, 3, 1, 1)
+    got = oracle.forward_bias_act_pool_f32(x, f, None, False, 1, wl.PAD_SAME)
+    assert got.reshape(2, 2).tolist() == [[303.0, 348.0], [483.0, 528.0]]
+    # a bias of -400 and the ReLU zero the first row of windows
+    got = oracle.forward_bias_act_pool_f32(x, f, np.array([-400.0], np.float32), True, 1,
+                                           wl.PAD_SAME)
+    assert got.reshape(2, 2).tolist() == [[0.0, 0.0], [83.0, 128.0]]
+
+
+def test_pool_drops_a_trailing_odd_row_and_column(oracle):
+    y = np.arange(2 * 5 * 7 * 3, dtype=np.float64).reshape(2, 5, 7, 3)
+    got = oracle.max_pool_2x2(y)
+    assert got.shape == (2, 2, 3, 3)
+    # values grow along every axis: the maximum of a window is its bottom-right element
+    assert np.array_equal(got, y[:, 1:4:2, 1:6:2, :])
+    assert oracle.max_pool_2x2(np.zeros((1, 1, 4, 2))).shape == (1, 0, 2, 2)
+
+
+def test_pool_against_explicit_windows(oracle):
+    rng = np.random.default_rng(41)
+    x = rng.integers(-3, 4, (2, 7, 6, 3)).astype(np.float32)
+    f = rng.integers(-3, 4, (3, 3, 3, 4)).astype(np.float32)
+    b = rng.integers(-5, 6, 4).astype(np.float32)
+    full = oracle.forward_bias_act_f32(x, f, b, True, 1, wl.PAD_SAME)      # 2 x 7 x 6 x 4
+    got = oracle.forward_bias_act_pool_f32(x, f, b, True, 1, wl.PAD_SAME)  # 2 x 3 x 3 x 4
+    assert got.shape == (2, 3, 3, 4)
+    for n in range(2):
+        for i in range(3):
+            for j in range(3):
+                for k in range(4):
+                    window = [full[n, 2 * i + a, 2 * j + c, k] for a in (0, 1) for c in (0, 1)]
+                    assert got[n, i, j, k] == max(window)
+
+
+def test_pool_of_all_ones_closed_form(oracle):
+    # all-ones input and filter: the unpooled output counts the taps inside the image, so every
+    # 2x2 window of an 8x8 image holds an interior pixel (9 taps x 2 channels = 18) except none:
+    # corners of the pooled map see the pixels (1,1) etc., which are interior as well
+    x = np.ones((1, 8, 8, 2), np.float32)
+    f = np.ones((3, 3, 2, 3), np.float32)
+    got = oracle.forward_bias_act_pool_f32(x, f, None, False, 1, wl.PAD_SAME)
+    assert got.shape == (1, 4, 4, 3) and np.all(got == 18.0)
+    # 2x2 image: every output pixel sees 4 taps x 2 channels
+    got = oracle.forward_bias_act_pool_f32(np.ones((1, 2, 2, 2), np.float32), f, None, False, 1,
+                                           wl.PAD_SAME)
+    assert got.shape == (1, 1, 1, 3) and np.all(got == 8.0)
