@@ -140,6 +140,34 @@ CONV2D_API int conv2d_forward_bias_act(const conv2d_params* params, const void* 
                             const float* bias, int activation, void* out, void* workspace,
                             size_t workspace_bytes, void* hip_stream);
 
+/* Convolution + bias + activation + 2x2 max pooling (stride 2, no padding) in
+ * one call:
+ *   out[n,i,j,k] = max over a, b in {0,1} of
+ *                  act( conv(in, filt)[n, 2i+a, 2j+b, k] + bias[k] )
+ *   out : [batch][out_rows/2][out_cols/2][features], NHWC, dense, out_dtype;
+ *         a trailing odd row or column of the convolution's output is dropped
+ *         (nothing is written if out_rows or out_cols is below 2).
+ * Section 3 of the paper names pooling among the layers that sit between the
+ * convolutions; the 3x3 layers of a VGG-style network that precede a pooling
+ * layer are exactly the ones whose output traffic this removes (a quarter of
+ * the unpooled tensor is written and nothing of it is read back).
+ * Variants whose tiles are even-sized blocks of output pixels of one image
+ * (the blocked patch tiles: 3x3 window, stride 1) take the maximum of the
+ * four sums in registers and write only the pooled tensor.  Every other
+ * variant writes the unpooled tensor into the workspace, behind its own
+ * scratch, and a second kernel pools it; the result is the same.
+ * The maximum is taken with fmaxf: a NaN among the four is dropped unless all
+ * four are NaN.  conv2d_pool_workspace_size (host only) gives the bytes this
+ * entry point needs for the variant it would select, the _variant form for a
+ * given variant (UNSUPPORTED if that variant cannot run the parameters); all
+ * other rules are those of conv2d_forward_bias_act. */
+CONV2D_API int conv2d_pool_workspace_size(const conv2d_params* params, size_t* bytes);
+CONV2D_API int conv2d_pool_workspace_size_variant(const conv2d_params* params, int variant_id,
+                                       size_t* bytes);
+CONV2D_API int conv2d_forward_bias_act_pool(const conv2d_params* params, const void* in,
+                                 const void* filt, const float* bias, int activation, void* out,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Variant introspection (host only). */
 CONV2D_API int conv2d_num_variants(void);
 CONV2D_API const char* conv2d_variant_name(int variant_id);            /* NULL if out of range */

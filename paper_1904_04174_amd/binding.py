@@ -24,7 +24,9 @@ LIB_PATH = os.path.join(_HERE, "libconv2d_mi355x.so")
 
 EXPORTS = (
     "conv2d_get_geometry", "conv2d_workspace_size", "conv2d_workspace_size_variant",
-    "conv2d_forward", "conv2d_forward_variant", "conv2d_forward_bias_act", "conv2d_num_variants",
+    "conv2d_forward", "conv2d_forward_variant", "conv2d_forward_bias_act",
+    "conv2d_forward_bias_act_pool", "conv2d_pool_workspace_size",
+    "conv2d_pool_workspace_size_variant", "conv2d_num_variants",
     "conv2d_variant_name",
     "conv2d_variant_supports", "conv2d_selected_variant", "conv2d_select_variant",
     "conv2d_status_string", "conv2d_version",
@@ -76,6 +78,10 @@ def lib():
         l.conv2d_selected_variant.argtypes = [pp, ctypes.POINTER(ctypes.c_int)]
         l.conv2d_forward_bias_act.argtypes = [pp, vp, vp, vp, ctypes.c_int, vp, vp, ctypes.c_size_t,
                                               vp]
+        l.conv2d_forward_bias_act_pool.argtypes = [pp, vp, vp, vp, ctypes.c_int, vp, vp,
+                                                   ctypes.c_size_t, vp]
+        l.conv2d_pool_workspace_size.argtypes = [pp, ctypes.POINTER(sz)]
+        l.conv2d_pool_workspace_size_variant.argtypes = [pp, ctypes.c_int, ctypes.POINTER(sz)]
         l.conv2d_select_variant.argtypes = [pp, ctypes.c_uint32, ctypes.POINTER(ctypes.c_int)]
         l.conv2d_status_string.argtypes = [ctypes.c_int]
         l.conv2d_status_string.restype = ctypes.c_char_p
@@ -195,6 +201,57 @@ def conv2d_forward_bias_act(params, x, filt, bias, activation, out=None, workspa
     """out = act(conv(x, filt) + bias): `bias` a float32 device tensor of `features` values or
     None, `activation` ACT_NONE or ACT_RELU.  Otherwise as conv2d_forward."""
     return conv2d_forward(params, x, filt, out, workspace, stream, None, bias, activation, True)
+
+
+def conv2d_pool_workspace_size(params, variant_id=None):
+    n = ctypes.c_size_t(0)
+    if variant_id is None:
+        rc = lib().conv2d_pool_workspace_size(ctypes.byref(params), ctypes.byref(n))
+    else:
+        rc = lib().conv2d_pool_workspace_size_variant(ctypes.byref(params), int(variant_id),
+                                                      ctypes.byref(n))
+    if rc:
+        raise Conv2dError(rc, "conv2d_pool_workspace_size")
+    return int(n.value)
+
+
+def conv2d_forward_bias_act_pool(params, x, filt, bias, activation, out=None, workspace=None,
+                                 stream=None):
+    """out = max_pool_2x2(act(conv(x, filt) + bias)); `out` is [batch, out_rows // 2,
+    out_cols // 2, features].  Otherwise as conv2d_forward_bias_act."""
+    import torch
+    g = conv2d_get_geometry(params)
+    want_in = torch.float32 if params.in_dtype == F32 else torch.bfloat16
+    want_out = torch.float32 if params.out_dtype == F32 else torch.bfloat16
+    if x.dtype != want_in or filt.dtype != want_in:
+        raise TypeError("input/filter dtype does not match params.in_dtype")
+    if not (x.is_cuda and filt.is_cuda and x.is_contiguous() and filt.is_contiguous()):
+        raise ValueError("input and filter must be contiguous device tensors")
+    if tuple(x.shape) != (params.batch, params.in_rows, params.in_cols, params.channels):
+        raise ValueError("input shape does not match params")
+    if tuple(filt.shape) != (params.window_rows, params.window_cols, params.channels,
+                             params.features):
+        raise ValueError("filter shape does not match params")
+    if bias is not None and not (bias.is_cuda and bias.dtype == torch.float32 and
+                                 bias.is_contiguous() and bias.numel() == params.features):
+        raise ValueError("bias must be a contiguous float32 device tensor of `features` values")
+    oshape = (params.batch, g.out_rows // 2, g.out_cols // 2, params.features)
+    if out is None:
+        out = torch.empty(oshape, dtype=want_out, device=x.device)
+    elif tuple(out.shape) != oshape or out.dtype != want_out or not out.is_contiguous():
+        raise ValueError("output tensor does not match params")
+    need = conv2d_pool_workspace_size(params)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else 0
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = lib().conv2d_forward_bias_act_pool(
+        ctypes.byref(params), x.data_ptr(), filt.data_ptr(),
+        bias.data_ptr() if bias is not None else 0, int(activation), out.data_ptr(), ws_ptr,
+        ws_bytes, _stream_handle(stream))
+    if rc:
+        raise Conv2dError(rc, "conv2d_forward_bias_act_pool")
+    return out
 
 
 def conv2d_forward(params, x, filt, out=None, workspace=None, stream=None, variant_id=None,

@@ -483,6 +483,21 @@ size_t workspace_bytes_for(const Variant& v, const Problem& q) {
   return 0;
 }
 
+// 2x2 pooling in the epilogue: whole blocked patch tiles.
+bool pools_in_epilogue(const Variant& v) {
+  return v.family == kDma && v.split == kWhole && igemm_dma_tile_pools(v.bf16, v.tile);
+}
+
+size_t align256(size_t bytes) { return (bytes + 255) / 256 * 256; }
+
+// Workspace of the pooled entry point with variant `v`: the variant's own, then (unless the
+// variant pools in its epilogue) the unpooled output tensor.
+size_t pooled_workspace_bytes_for(const Variant& v, const Problem& q) {
+  const size_t own = workspace_bytes_for(v, q);
+  if (pools_in_epilogue(v)) return own;
+  return align256(own) + static_cast<size_t>(q.M) * q.K * (q.out_bf16 ? 2 : 4);
+}
+
 bool aligned16(const void* a, const void* b, const void* c) {
   return ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) |
            reinterpret_cast<uintptr_t>(c)) & 15u) == 0;
@@ -490,7 +505,7 @@ bool aligned16(const void* a, const void* b, const void* c) {
 
 int run(const conv2d_params* params, const void* in, const void* filt, void* out, void* workspace,
         size_t workspace_bytes, void* hip_stream, int variant_id, const float* bias = nullptr,
-        int activation = CONV2D_ACT_NONE) {
+        int activation = CONV2D_ACT_NONE, bool pool = false) {
   Problem q;
   int rc = derive(params, &q);
   if (rc) return rc;
@@ -514,7 +529,9 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     if (!al && tb.v[id].family != kDirect && !is_scalar(tb.v[id]))
       return CONV2D_STATUS_UNSUPPORTED;
   }
-  const size_t need = workspace_bytes_for(tb.v[id], q);
+  if (pool && (q.P < 2 || q.Q < 2)) return CONV2D_STATUS_OK;  // empty pooled tensor
+  const bool fused_pool = pool && pools_in_epilogue(tb.v[id]);
+  const size_t need = pool ? pooled_workspace_bytes_for(tb.v[id], q) : workspace_bytes_for(tb.v[id], q);
   if (need > 0) {
     if (!workspace || workspace_bytes < need) return CONV2D_STATUS_WORKSPACE_TOO_SMALL;
     if (reinterpret_cast<uintptr_t>(workspace) & 15u) return CONV2D_STATUS_INVALID_ARGUMENT;
@@ -522,6 +539,13 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
   q.in = in; q.filt = filt; q.out = out; q.workspace = workspace;
   q.bias = bias;
   q.relu = activation == CONV2D_ACT_RELU;
+  q.pool = fused_pool ? 1 : 0;
+  // (a variant that cannot pool writes the unpooled tensor behind its own workspace)
+  void* unpooled = nullptr;
+  if (pool && !fused_pool) {
+    unpooled = static_cast<char*>(workspace) + align256(workspace_bytes_for(tb.v[id], q));
+    q.out = unpooled;
+  }
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   hipError_t e = hipSuccess;
   switch (tb.v[id].family) {
@@ -537,6 +561,8 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
       e = launch_winograd(q, tb.v[id].tile, tb.v[id].split == kFused, stream);
       break;
   }
+  if (e == hipSuccess && unpooled)
+    e = launch_max_pool_2x2(unpooled, out, q.N, q.P, q.Q, q.K, q.out_bf16 != 0, stream);
   return e == hipSuccess ? CONV2D_STATUS_OK : CONV2D_STATUS_LAUNCH_FAILED;
 }
 
@@ -596,6 +622,38 @@ int conv2d_forward_bias_act(const conv2d_params* params, const void* in, const v
     return CONV2D_STATUS_INVALID_ARGUMENT;
   if (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)) return CONV2D_STATUS_INVALID_ARGUMENT;
   return run(params, in, filt, out, workspace, workspace_bytes, hip_stream, -1, bias, activation);
+}
+
+int conv2d_pool_workspace_size(const conv2d_params* params, size_t* bytes) {
+  Problem q;
+  if (!bytes) return CONV2D_STATUS_INVALID_ARGUMENT;
+  int rc = derive(params, &q);
+  if (rc) return rc;
+  *bytes = pooled_workspace_bytes_for(table().v[select(q, params->padding, true, false)], q);
+  return CONV2D_STATUS_OK;
+}
+
+int conv2d_pool_workspace_size_variant(const conv2d_params* params, int variant_id,
+                                       size_t* bytes) {
+  Problem q;
+  if (!bytes) return CONV2D_STATUS_INVALID_ARGUMENT;
+  int rc = derive(params, &q);
+  if (rc) return rc;
+  const Table& tb = table();
+  if (variant_id < 0 || variant_id >= tb.n) return CONV2D_STATUS_INVALID_ARGUMENT;
+  if (!supports(tb.v[variant_id], q)) return CONV2D_STATUS_UNSUPPORTED;
+  *bytes = pooled_workspace_bytes_for(tb.v[variant_id], q);
+  return CONV2D_STATUS_OK;
+}
+
+int conv2d_forward_bias_act_pool(const conv2d_params* params, const void* in, const void* filt,
+                                 const float* bias, int activation, void* out, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+  if (activation != CONV2D_ACT_NONE && activation != CONV2D_ACT_RELU)
+    return CONV2D_STATUS_INVALID_ARGUMENT;
+  if (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)) return CONV2D_STATUS_INVALID_ARGUMENT;
+  return run(params, in, filt, out, workspace, workspace_bytes, hip_stream, -1, bias, activation,
+             true);
 }
 
 int conv2d_num_variants(void) { return table().n; }

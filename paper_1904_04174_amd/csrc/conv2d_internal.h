@@ -30,6 +30,9 @@ struct Problem {
   // device, or null; relu: 0 or 1.
   const float* bias;
   int relu;
+  // Fused 2x2 max pooling (stride 2, trailing odd row / column dropped): only
+  // for tiles with igemm_dma_tile_pools; `out` is then [N][P/2][Q/2][K].
+  int pool;
   // Batched launch of the direct-to-LDS gather kernels (used by the Winograd
   // path for its per-point matrix products): `batches` > 1 problems of this
   // shape whose input, filter and output start `*_stride` elements apart.
@@ -94,6 +97,12 @@ void igemm_dma_tile_shape(int bf16, int tile, int* bm, int* bn, int* bk);
 int igemm_dma_tile_occupancy(int bf16, int tile);
 int igemm_dma_tile_addressing(int bf16, int tile);
 bool igemm_dma_tile_fits(const Problem& p, int bf16, int tile);  // extra shape condition (kind 3)
+// Tiles that are blocks of output pixels of one image with an even number of
+// rows and columns: a 2x2 pooling window never leaves the tile, and with
+// Problem::pool the epilogue reduces the four sums in registers (bias and
+// activation after the maximum: both are monotone) and stores the pooled
+// tensor only.
+bool igemm_dma_tile_pools(int bf16, int tile);
 // (a batched problem holds one repacked filter per batch and takes whole tiles only)
 size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile, int splits);
 hipError_t launch_igemm_dma(const Problem& p, int bf16, int tile, int splits, hipStream_t stream);
@@ -121,6 +130,12 @@ hipError_t launch_igemm_dma_wino(const Problem& p, int bf16, int tile, hipStream
 bool winograd_supports(const Problem& p, int gemm_tile, bool fused);
 size_t winograd_workspace_bytes(const Problem& p, int gemm_tile, bool fused);
 hipError_t launch_winograd(const Problem& p, int gemm_tile, bool fused, hipStream_t stream);
+
+// 2x2 max pooling, stride 2, of the NHWC tensor `in` [N][P][Q][K] (fp32 or bf16)
+// into `out` [N][P/2][Q/2][K] of the same type: the second step of the pooled
+// entry point for variants that cannot pool in their epilogue.
+hipError_t launch_max_pool_2x2(const void* in, void* out, int N, int P, int Q, int K, bool bf16,
+                               hipStream_t stream);
 
 // Small channel counts that are no multiple of the 16-byte vector (a 3-channel
 // first layer): input and filter are zero-padded to the vector width in the

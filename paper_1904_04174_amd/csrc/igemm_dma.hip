@@ -995,6 +995,8 @@ struct PatchTile {
   // blocked tiles of 32-row blocks: a workgroup takes several tiles, one after the other (the
   // 16-row tiles were slower that way: 71.9 -> 81.0 us on a 112x112x128 layer at batch 16)
   static constexpr bool PERSIST = BW_ > 0 && !MF16_;
+  // 2x2 pooling in the epilogue: blocks of 16 columns and an even number of rows, 32-row blocks
+  static constexpr bool POOLS = BW_ == 16 && !MF16_ && (BM_ / 16) % 2 == 0;
   static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int NW = WAVES_M * WAVES_N;
   static constexpr int NT = 64 * NW;
@@ -1522,6 +1524,40 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
       }
     }
   } else {
+  bool pooled = false;
+  if constexpr (T::POOLS) {
+    if (p.pool) {
+      // ---- pooled epilogue.  A 32-row block is two rows of the 16-pixel-wide tile; with the
+      // accumulator layout below, the 2x2 window of pooled column x of that row pair is
+      // registers v, v + 1 (pixel pair along the row) and v + 8, v + 9 (the row below) of one
+      // lane, v = 0, 2, 4, 6.
+      const int P2 = p.P / 2, Q2 = p.Q / 2;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int py = (blk_p + (wm * T::WM + i * 32) / T::BW) / 2;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int col = n0 + wn * T::WN + j * 32 + lr;
+          const float bcol = bias_col[j];
+#pragma unroll
+          for (int v = 0; v < 8; v += 2) {
+            const int px = (blk_q + 8 * (v / 4) + 4 * lk + v % 4) / 2;
+            const float m = fmaxf(fmaxf(acc[i][j][v], acc[i][j][v + 1]),
+                                  fmaxf(acc[i][j][v + 8], acc[i][j][v + 9]));
+            if (py < P2 && px < Q2 && col < p.K) {
+              const size_t idx = (static_cast<size_t>(blk_n * P2 + py) * Q2 + px) * p.K + col;
+              if (OUT_BF16)
+                static_cast<unsigned short*>(p.out)[idx] = to_bf16_bits(finish(m, bcol, p.relu));
+              else
+                static_cast<float*>(p.out)[idx] = finish(m, bcol, p.relu);
+            }
+          }
+        }
+      }
+      pooled = true;
+    }
+  }
+  if (!pooled) {
   // ---- epilogue (accumulator layout: lane l reg v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32)
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -1551,6 +1587,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
       }
     }
   }
+  }  // unpooled
   }  // 32-row blocks
 
   if (!has_next) break;
@@ -1642,6 +1679,7 @@ struct TileEntry {
   size_t (*ws)(const Problem&, int);
   bool (*fits)(const Problem&);  // extra shape condition of a tile, or null
   hipError_t (*wino)(const Problem&, hipStream_t);  // fused Winograd products, or null
+  bool pools = false;                               // 2x2 pooling in the epilogue
 };
 
 #define CONV2D_PATCH_TILE(dt, isbf, bm, bn, wm, wn, rows, two, occ)                              \
@@ -1672,7 +1710,8 @@ struct TileEntry {
     PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw>::BK, occ, 3,                             \
     &launch_patch<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw>>,                          \
     &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw>>,                 \
-    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw>>, nullptr }
+    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw>>, nullptr,                   \
+    PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw>::POOLS }
 
 #define CONV2D_DMA_TILE(dt, isbf, bm, bn, rowb, wm, wn, st, two, occ, addr, tag)                \
   { "igemm_dma_" dt "_" #bm "x" #bn "_r" #rowb "_w" #wm "x" #wn "_s" #st tag, bm, bn,           \
@@ -1751,6 +1790,7 @@ bool igemm_dma_tile_fits(const Problem& p, int bf16, int tile) {
   return t.fits == nullptr || t.fits(p);
 }
 bool igemm_dma_tile_has_wino(int bf16, int tile) { return entry(bf16, tile).wino != nullptr; }
+bool igemm_dma_tile_pools(int bf16, int tile) { return entry(bf16, tile).pools; }
 hipError_t launch_igemm_dma_wino(const Problem& p, int bf16, int tile, hipStream_t stream) {
   const TileEntry& t = entry(bf16, tile);
   return t.wino ? t.wino(p, stream) : hipErrorInvalidValue;

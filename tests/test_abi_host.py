@@ -282,3 +282,36 @@ def test_bias_act_arguments_are_validated_before_any_launch():
     assert call(16, B.ACT_RELU, x=0) == B.STATUS_INVALID_ARGUMENT  # null input
     empty = B.make_params(0, 8, 8, 4, 4, 3, 3)
     assert l.conv2d_forward_bias_act(ctypes.byref(empty), 0, 0, 0, B.ACT_RELU, 0, 0, 0, 0) == 0
+
+
+def test_pool_arguments_and_workspace_sizes_on_the_host():
+    p = B.make_params(1, 8, 8, 4, 4, 3, 3)
+    l = B.lib()
+    call = lambda bias, act, x=16: l.conv2d_forward_bias_act_pool(ctypes.byref(p), x, 16, bias, act,
+                                                                  16, 0, 0, 0)
+    assert call(0, 2) == B.STATUS_INVALID_ARGUMENT       # unknown activation
+    assert call(18, B.ACT_RELU) == B.STATUS_INVALID_ARGUMENT   # bias not 4-byte aligned
+    assert call(16, B.ACT_RELU, x=0) == B.STATUS_INVALID_ARGUMENT  # null input
+    empty = B.make_params(0, 8, 8, 4, 4, 3, 3)
+    assert l.conv2d_forward_bias_act_pool(ctypes.byref(empty), 0, 0, 0, B.ACT_RELU, 0, 0, 0, 0) == 0
+    # an output of one row has no 2x2 window: nothing to do, no workspace asked for
+    thin = B.make_params(2, 1, 9, 4, 4, 1, 1)
+    assert l.conv2d_forward_bias_act_pool(ctypes.byref(thin), 16, 16, 0, B.ACT_NONE, 16, 0, 0, 0) == 0
+    # a variant that pools in its epilogue needs its own workspace only; any other also the
+    # unpooled tensor behind it
+    big = B.make_params(16, 224, 224, 64, 64, 3, 3, in_dtype=B.BF16, out_dtype=B.BF16)
+    unpooled = 16 * 224 * 224 * 64 * 2
+    for v in range(B.conv2d_num_variants()):
+        if not B.conv2d_variant_supports(big, v):
+            continue
+        own = B.conv2d_workspace_size(big, v)
+        pooled = B.conv2d_pool_workspace_size(big, v)
+        name = B.conv2d_variant_name(v)
+        if name.startswith("igemm_patch_") and name.endswith("_b16"):
+            assert pooled == own, name
+        else:
+            assert pooled == (own + 255) // 256 * 256 + unpooled, name
+    sel = B.conv2d_selected_variant(big)
+    assert B.conv2d_pool_workspace_size(big) == B.conv2d_pool_workspace_size(big, sel)
+    with pytest.raises(B.Conv2dError):
+        B.conv2d_pool_workspace_size(big, B.conv2d_num_variants())

@@ -563,6 +563,107 @@ def test_patch_tiles_with_more_tiles_than_resident_workgroups(torch_cuda, oracle
     assert ran >= 5, ran
 
 
+# ------------------------------------------------------------------ fused 2x2 max pooling
+
+def run_gpu_pooled(torch, params, x, f, bias, activation, force=None):
+    """conv2d_forward_bias_act_pool on numpy inputs; `force` as in run_gpu_fused."""
+    import os
+    dev = torch.device("cuda:0")
+    in_dt = torch.float32 if params.in_dtype == B.F32 else torch.bfloat16
+    xd = torch.from_numpy(x).to(dev).to(in_dt).contiguous()
+    fd = torch.from_numpy(f).to(dev).to(in_dt).contiguous()
+    bd = None if bias is None else torch.from_numpy(bias).to(dev)
+    ws = None
+    if force is not None:
+        need = B.conv2d_pool_workspace_size(params, force)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+        os.environ["CONV2D_FORCE_VARIANT"] = str(force)
+    try:
+        g = B.conv2d_get_geometry(params)
+        out = torch.full((params.batch, g.out_rows // 2, g.out_cols // 2, params.features),
+                         float("nan"), device=dev,
+                         dtype=torch.float32 if params.out_dtype == B.F32 else torch.bfloat16)
+        B.conv2d_forward_bias_act_pool(params, xd, fd, bd, activation, out=out, workspace=ws)
+        torch.cuda.synchronize()
+    finally:
+        os.environ.pop("CONV2D_FORCE_VARIANT", None)
+    return out.float().cpu().numpy()
+
+
+@pytest.mark.parametrize("case", FUSED_SMALL)
+def test_pool_every_variant_fp32(torch_cuda, oracle, case):
+    """Convolution + bias + ReLU + 2x2 max pooling with every variant that supports the case
+    (most write the unpooled tensor into the workspace and pool it with the second kernel),
+    against the oracle's plain composition; odd output sizes drop the last row / column."""
+    (n, h, w, c, k, r, s_, sr, sc, pad) = case
+    x, f = wl.make_case((n, h, w, c), (r, s_, c, k), "uniform", 777)
+    bias = np.random.default_rng(778).uniform(-1, 1, k).astype(np.float32)
+    p = _params(case)
+    want = oracle.forward_bias_act_pool_f32(x, f, bias, True, (sr, sc), pad)
+    for v in [None] + supported_variants(p):
+        _say("pool case %s variant %s" % (case, "auto" if v is None else B.conv2d_variant_name(v)))
+        got = run_gpu_pooled(torch_cuda, p, x, f, bias, B.ACT_RELU, force=v)
+        assert got.shape == want.shape
+        if want.size:
+            assert rel_err(got, want) <= TOL_F32, (case, v)
+
+
+@pytest.mark.parametrize("shape", [(32, 70, 70, 64, 80), (24, 51, 83, 96, 200)])
+def test_pool_in_the_epilogue_of_blocked_tiles(torch_cuda, oracle, shape):
+    """The blocked patch tiles take the maximum of the four sums in registers and store only the
+    pooled tensor (run persistently here: more tiles than resident workgroups).  Even and odd
+    image sizes, ragged blocks, integer inputs: bit-exact, fp32 and bf16, with and without the
+    bias + ReLU."""
+    n, h, w, c, k = shape
+    rng = np.random.default_rng(sum(shape) + 1)
+    x = rng.integers(-4, 5, size=(n, h, w, c)).astype(np.float32)
+    f = rng.integers(-4, 5, size=(3, 3, c, k)).astype(np.float32)
+    bias = rng.integers(-4, 5, size=k).astype(np.float32)
+    want_plain = oracle.forward_bias_act_pool_f32(x, f, None, False, 1, wl.PAD_SAME)
+    want_fused = oracle.forward_bias_act_pool_f32(x, f, bias, True, 1, wl.PAD_SAME)
+    ran = 0
+    for dt in (B.F32, B.BF16):
+        p = B.make_params(n, h, w, c, k, 3, 3, 1, 1, wl.PAD_SAME, dt, B.F32)
+        for v in range(B.conv2d_num_variants()):
+            name = B.conv2d_variant_name(v)
+            if not (name.startswith("igemm_patch_") and name.endswith("_b16")):
+                continue
+            if not B.conv2d_variant_supports(p, v):
+                continue
+            # pooling in the epilogue needs no room for the unpooled tensor
+            assert B.conv2d_pool_workspace_size(p, v) == B.conv2d_workspace_size(p, v), name
+            _say("pool in epilogue %s %s" % (shape, name))
+            got = run_gpu_pooled(torch_cuda, p, x, f, None, B.ACT_NONE, force=v)
+            assert np.array_equal(got, want_plain), name
+            got = run_gpu_pooled(torch_cuda, p, x, f, bias, B.ACT_RELU, force=v)
+            assert np.array_equal(got, want_fused), name
+            ran += 1
+    assert ran >= 5, ran
+
+
+@pytest.mark.parametrize("name,in_dtype,out_dtype", [
+    ("V224-N16", B.F32, B.F32), ("V224-N16", B.BF16, B.BF16), ("V112-N16", B.BF16, B.F32),
+    ("V14-N16", B.F32, B.F32), ("R7x7", B.F32, B.F32)])
+def test_pool_full_size(torch_cuda, oracle, name, in_dtype, out_dtype):
+    """The pooled entry point on full-size layers with the selected variant (pooling in the
+    epilogue on the 224 and 112 layers, the second kernel elsewhere), against the whole pooled
+    oracle output."""
+    L = wl.LAYERS[name]
+    x, f = wl.make_inputs(L)
+    if in_dtype == B.BF16:
+        x, _ = wl.round_to_bf16(x)
+        f, _ = wl.round_to_bf16(f)
+    bias = np.random.default_rng(5).uniform(-1, 1, L.features).astype(np.float32)
+    p = B.params_of_layer(L, in_dtype, out_dtype)
+    _say("pool full %s variant %s" % (name, B.conv2d_variant_name(B.conv2d_selected_variant(p))))
+    got = run_gpu_pooled(torch_cuda, p, x, f, bias, B.ACT_RELU)
+    want = oracle.forward_bias_act_pool_f32(x, f, bias, True, (L.stride_rows, L.stride_cols),
+                                            L.padding)
+    err = rel_err(got, want)
+    _say("pool full %s err %.3g" % (name, err))
+    assert err <= (TOL_F32 if in_dtype == B.F32 else TOL_BF16), (name, err)
+
+
 def test_calls_can_be_captured_in_a_hip_graph(torch_cuda, oracle):
     """The library only enqueues kernels (no allocation, no memset, no synchronisation), so a
     sequence of calls can be captured into a HIP graph.  Several replays, with eager work and
