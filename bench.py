@@ -76,7 +76,8 @@ def main():
                          "therefore exceed the MFMA peak in the metric's terms")
     ap.add_argument("--skip-all-algorithms-leg", action="store_true",
                     help="with --algorithms direct: do not also time the unrestricted selection "
-                         "(keeps a profile of the run to the direct-sum kernels)")
+                         "and the packed-filter leg (keeps a profile of the run to the headline's "
+                         "kernels)")
     ap.add_argument("--batch", type=int, choices=[1, 4, 32], default=32,
                     help="batch size of the resnet50 workload (the paper's Figures 1-3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -266,6 +267,50 @@ def main():
         for l in layers:
             l["vid"], l["variant"] = l["direct_vid"], l["direct_variant"]
 
+    # ---- the same sweep (direct-sum selection) with the filters packed ahead of time
+    # (conv2d_pack_filter once, outside the timed region; conv2d_forward_packed in it): what an
+    # inference loop with constant filters runs.  Reported beside the headline value, which packs
+    # the filter inside every call.
+    packed_leg = None
+    if args.algorithms == "direct" and not args.skip_all_algorithms_leg:
+        calls = []
+        for l in layers:
+            try:
+                packed = B.conv2d_pack_filter(l["p"], l["vid"], l["f"])
+            except B.Conv2dError:      # a variant that transforms the filter another way
+                packed = None
+            l["packed"] = packed
+            ws_ptr = l["ws"].data_ptr() if l["ws_bytes"] else 0
+            if packed is None:
+                calls.append((False, (l["p"], l["x"].data_ptr(), l["f"].data_ptr(),
+                                      l["out"].data_ptr(), ws_ptr, l["ws_bytes"], handle,
+                                      l["vid"])))
+            else:
+                calls.append((True, (l["p"], l["vid"], l["x"].data_ptr(), packed.data_ptr(), 0, 0,
+                                     l["out"].data_ptr(), ws_ptr, l["ws_bytes"], handle)))
+
+        def packed_step():
+            for is_packed, a in calls:
+                rc = B.conv2d_forward_packed_raw(*a) if is_packed else B.conv2d_forward_raw(*a)
+                if rc:
+                    raise B.Conv2dError(rc, "conv2d_forward_packed")
+        torch.cuda.synchronize()
+        for _ in range(args.warmup):
+            packed_step()
+        stream.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            packed_step()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        ms_packed = 1e3 * (time.perf_counter() - t0) / args.steps
+        packed_leg = {
+            "value": round(total_flops / (ms_packed * 1e-3) / 1e12, 3), "unit": "TFLOP/s",
+            "ms_per_step": round(ms_packed, 4),
+            "layers_packed": sum(1 for is_packed, _ in calls if is_packed),
+            "note": "filters packed once outside the timed region (conv2d_pack_filter), "
+                    "conv2d_forward_packed inside it; the headline value repacks in every call"}
+
     result = {
         "metric": "conv2d forward TFLOP/s (2*N*P*Q*K*R*S*C / time)",
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -283,6 +328,7 @@ def main():
         "frac_of_mfma_peak": round(value / peak, 4),
         "roofline": roofline,
         "all_algorithms": with_transforms,
+        "packed_filters": packed_leg,
         "layers": [{"name": l["name"], "variant": l["variant"], "ms": round(l["ms"], 4),
                     "tflops": round(l["flops"] / (l["ms"] * 1e-3) / 1e12, 2),
                     "alg_gbs": round(l["bytes"] / (l["ms"] * 1e-3) / 1e9, 1),

@@ -168,6 +168,35 @@ CONV2D_API int conv2d_forward_bias_act_pool(const conv2d_params* params, const v
                                  const void* filt, const float* bias, int activation, void* out,
                                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Filters packed ahead of time.  The matrix-core kernels read the filter in a
+ * layout of their own (reduction index contiguous, cut into the tile's
+ * slices), which conv2d_forward writes into the workspace on every call: a
+ * small kernel of its own, ~5 us, a tenth to a third of a whole call on the
+ * small layers of a network at batch 1-4.  A caller whose filters do not
+ * change (inference) packs them once:
+ *   conv2d_packed_filter_size  bytes of the packed filter of `variant_id` for
+ *                              these parameters (host only)
+ *   conv2d_pack_filter         writes it (device to device, on the stream)
+ *   conv2d_forward_packed      conv2d_forward_bias_act with that variant on
+ *                              the packed filter; same workspace as
+ *                              conv2d_workspace_size_variant gives
+ * The packed filter belongs to the variant and the parameters it was packed
+ * for (take the id from conv2d_select_variant with
+ * CONV2D_SELECT_DIRECT_SUM_ONLY); using it with others gives wrong results,
+ * not an error.  The variants that transform the filter per call in another
+ * way (winograd2x2_*, padc_*) return UNSUPPORTED from all three; for the
+ * direct and the register-staged variants the packed filter is a plain copy.
+ * Results are bit-identical to conv2d_forward_variant / _bias_act with the
+ * same variant.  Pointer alignment rules as for conv2d_forward. */
+CONV2D_API int conv2d_packed_filter_size(const conv2d_params* params, int variant_id,
+                                         size_t* bytes);
+CONV2D_API int conv2d_pack_filter(const conv2d_params* params, int variant_id, const void* filt,
+                                  void* packed, size_t packed_bytes, void* hip_stream);
+CONV2D_API int conv2d_forward_packed(const conv2d_params* params, int variant_id, const void* in,
+                                     const void* packed_filt, const float* bias, int activation,
+                                     void* out, void* workspace, size_t workspace_bytes,
+                                     void* hip_stream);
+
 /* Variant introspection (host only). */
 CONV2D_API int conv2d_num_variants(void);
 CONV2D_API const char* conv2d_variant_name(int variant_id);            /* NULL if out of range */

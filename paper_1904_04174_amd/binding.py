@@ -26,7 +26,8 @@ EXPORTS = (
     "conv2d_get_geometry", "conv2d_workspace_size", "conv2d_workspace_size_variant",
     "conv2d_forward", "conv2d_forward_variant", "conv2d_forward_bias_act",
     "conv2d_forward_bias_act_pool", "conv2d_pool_workspace_size",
-    "conv2d_pool_workspace_size_variant", "conv2d_num_variants",
+    "conv2d_pool_workspace_size_variant", "conv2d_packed_filter_size", "conv2d_pack_filter",
+    "conv2d_forward_packed", "conv2d_num_variants",
     "conv2d_variant_name",
     "conv2d_variant_supports", "conv2d_selected_variant", "conv2d_select_variant",
     "conv2d_status_string", "conv2d_version",
@@ -82,6 +83,10 @@ def lib():
                                                    ctypes.c_size_t, vp]
         l.conv2d_pool_workspace_size.argtypes = [pp, ctypes.POINTER(sz)]
         l.conv2d_pool_workspace_size_variant.argtypes = [pp, ctypes.c_int, ctypes.POINTER(sz)]
+        l.conv2d_packed_filter_size.argtypes = [pp, ctypes.c_int, ctypes.POINTER(sz)]
+        l.conv2d_pack_filter.argtypes = [pp, ctypes.c_int, vp, vp, sz, vp]
+        l.conv2d_forward_packed.argtypes = [pp, ctypes.c_int, vp, vp, vp, ctypes.c_int, vp, vp, sz,
+                                            vp]
         l.conv2d_select_variant.argtypes = [pp, ctypes.c_uint32, ctypes.POINTER(ctypes.c_int)]
         l.conv2d_status_string.argtypes = [ctypes.c_int]
         l.conv2d_status_string.restype = ctypes.c_char_p
@@ -201,6 +206,64 @@ def conv2d_forward_bias_act(params, x, filt, bias, activation, out=None, workspa
     """out = act(conv(x, filt) + bias): `bias` a float32 device tensor of `features` values or
     None, `activation` ACT_NONE or ACT_RELU.  Otherwise as conv2d_forward."""
     return conv2d_forward(params, x, filt, out, workspace, stream, None, bias, activation, True)
+
+
+def conv2d_packed_filter_size(params, variant_id):
+    n = ctypes.c_size_t(0)
+    rc = lib().conv2d_packed_filter_size(ctypes.byref(params), int(variant_id), ctypes.byref(n))
+    if rc:
+        raise Conv2dError(rc, "conv2d_packed_filter_size")
+    return int(n.value)
+
+
+def conv2d_pack_filter(params, variant_id, filt, stream=None):
+    """The filter (a contiguous HWCF device tensor) packed for `variant_id`: a uint8 device
+    tensor to hand to conv2d_forward_packed."""
+    import torch
+    need = conv2d_packed_filter_size(params, variant_id)
+    packed = torch.empty(max(need, 16), dtype=torch.uint8, device=filt.device)
+    rc = lib().conv2d_pack_filter(ctypes.byref(params), int(variant_id), filt.data_ptr(),
+                                  packed.data_ptr(), need, _stream_handle(stream))
+    if rc:
+        raise Conv2dError(rc, "conv2d_pack_filter")
+    return packed
+
+
+def conv2d_forward_packed_raw(params, variant_id, in_ptr, packed_ptr, bias_ptr, activation, out_ptr,
+                              ws_ptr, ws_bytes, stream_handle):
+    """The C call itself on raw device pointers; returns the status."""
+    return lib().conv2d_forward_packed(ctypes.byref(params), int(variant_id), in_ptr, packed_ptr,
+                                       bias_ptr, int(activation), out_ptr, ws_ptr, ws_bytes,
+                                       stream_handle)
+
+
+def conv2d_forward_packed(params, variant_id, x, packed, bias=None, activation=ACT_NONE, out=None,
+                          workspace=None, stream=None):
+    """out = act(conv(x, filter) + bias) with `variant_id` on a filter packed by
+    conv2d_pack_filter for the same variant and parameters."""
+    import torch
+    g = conv2d_get_geometry(params)
+    want_out = torch.float32 if params.out_dtype == F32 else torch.bfloat16
+    if tuple(x.shape) != (params.batch, params.in_rows, params.in_cols, params.channels) or \
+            not (x.is_cuda and x.is_contiguous()):
+        raise ValueError("input does not match params")
+    oshape = (params.batch, g.out_rows, g.out_cols, params.features)
+    if out is None:
+        out = torch.empty(oshape, dtype=want_out, device=x.device)
+    elif tuple(out.shape) != oshape or out.dtype != want_out or not out.is_contiguous():
+        raise ValueError("output tensor does not match params")
+    need = conv2d_workspace_size(params, variant_id)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    rc = conv2d_forward_packed_raw(
+        params, variant_id, x.data_ptr(), packed.data_ptr(),
+        bias.data_ptr() if bias is not None else 0, activation, out.data_ptr(),
+        workspace.data_ptr() if workspace is not None else 0,
+        workspace.numel() * workspace.element_size() if workspace is not None else 0,
+        _stream_handle(stream))
+    if rc:
+        raise Conv2dError(rc, "conv2d_forward_packed")
+    return out
 
 
 def conv2d_pool_workspace_size(params, variant_id=None):

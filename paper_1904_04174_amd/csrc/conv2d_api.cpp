@@ -483,12 +483,24 @@ size_t workspace_bytes_for(const Variant& v, const Problem& q) {
   return 0;
 }
 
+size_t align256(size_t bytes) { return (bytes + 255) / 256 * 256; }
+
+// Bytes of variant `v`'s packed filter; 0 with *ok = false for the variants that transform the
+// filter per call in another way (Winograd, zero-padded channels).
+size_t packed_filter_bytes_for(const Variant& v, const Problem& q, bool* ok) {
+  *ok = true;
+  if (v.family == kDma) return igemm_dma_packed_filter_bytes(q, v.bf16, v.tile);
+  if (v.family == kDirect || v.family == kIgemm)  // these read the filter as it is: a copy
+    return align256(static_cast<size_t>(q.Kg) * q.K * (q.in_bf16 ? 2 : 4));
+  *ok = false;
+  return 0;
+}
+
 // 2x2 pooling in the epilogue: whole blocked patch tiles.
 bool pools_in_epilogue(const Variant& v) {
   return v.family == kDma && v.split == kWhole && igemm_dma_tile_pools(v.bf16, v.tile);
 }
 
-size_t align256(size_t bytes) { return (bytes + 255) / 256 * 256; }
 
 // Workspace of the pooled entry point with variant `v`: the variant's own, then (unless the
 // variant pools in its epilogue) the unpooled output tensor.
@@ -505,7 +517,7 @@ bool aligned16(const void* a, const void* b, const void* c) {
 
 int run(const conv2d_params* params, const void* in, const void* filt, void* out, void* workspace,
         size_t workspace_bytes, void* hip_stream, int variant_id, const float* bias = nullptr,
-        int activation = CONV2D_ACT_NONE, bool pool = false) {
+        int activation = CONV2D_ACT_NONE, bool pool = false, bool filt_is_packed = false) {
   Problem q;
   int rc = derive(params, &q);
   if (rc) return rc;
@@ -537,6 +549,8 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     if (reinterpret_cast<uintptr_t>(workspace) & 15u) return CONV2D_STATUS_INVALID_ARGUMENT;
   }
   q.in = in; q.filt = filt; q.out = out; q.workspace = workspace;
+  // (a packed filter of the direct and register-staged variants is a plain copy)
+  if (filt_is_packed && tb.v[id].family == kDma) q.packed_filt = filt;
   q.bias = bias;
   q.relu = activation == CONV2D_ACT_RELU;
   q.pool = fused_pool ? 1 : 0;
@@ -654,6 +668,69 @@ int conv2d_forward_bias_act_pool(const conv2d_params* params, const void* in, co
   if (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)) return CONV2D_STATUS_INVALID_ARGUMENT;
   return run(params, in, filt, out, workspace, workspace_bytes, hip_stream, -1, bias, activation,
              true);
+}
+
+int conv2d_packed_filter_size(const conv2d_params* params, int variant_id, size_t* bytes) {
+  Problem q;
+  if (!bytes) return CONV2D_STATUS_INVALID_ARGUMENT;
+  int rc = derive(params, &q);
+  if (rc) return rc;
+  const Table& tb = table();
+  if (variant_id < 0 || variant_id >= tb.n) return CONV2D_STATUS_INVALID_ARGUMENT;
+  if (!supports(tb.v[variant_id], q)) return CONV2D_STATUS_UNSUPPORTED;
+  bool ok;
+  *bytes = packed_filter_bytes_for(tb.v[variant_id], q, &ok);
+  return ok ? CONV2D_STATUS_OK : CONV2D_STATUS_UNSUPPORTED;
+}
+
+int conv2d_pack_filter(const conv2d_params* params, int variant_id, const void* filt, void* packed,
+                       size_t packed_bytes, void* hip_stream) {
+  Problem q;
+  int rc = derive(params, &q);
+  if (rc) return rc;
+  const Table& tb = table();
+  if (variant_id < 0 || variant_id >= tb.n) return CONV2D_STATUS_INVALID_ARGUMENT;
+  const Variant& v = tb.v[variant_id];
+  if (!supports(v, q)) return CONV2D_STATUS_UNSUPPORTED;
+  bool ok;
+  const size_t need = packed_filter_bytes_for(v, q, &ok);
+  if (!ok) return CONV2D_STATUS_UNSUPPORTED;
+  if (!filt || !packed) return CONV2D_STATUS_INVALID_ARGUMENT;
+  if (packed_bytes < need) return CONV2D_STATUS_WORKSPACE_TOO_SMALL;
+  if (!is_scalar(v) && v.family != kDirect &&
+      ((reinterpret_cast<uintptr_t>(filt) | reinterpret_cast<uintptr_t>(packed)) & 15u))
+    return CONV2D_STATUS_UNSUPPORTED;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (v.family == kDma) {
+    q.filt = filt;
+    e = igemm_dma_pack_filter(q, v.bf16, v.tile, packed, stream);
+  } else {
+    e = hipMemcpyAsync(packed, filt, static_cast<size_t>(q.Kg) * q.K * (q.in_bf16 ? 2 : 4),
+                       hipMemcpyDeviceToDevice, stream);
+  }
+  return e == hipSuccess ? CONV2D_STATUS_OK : CONV2D_STATUS_LAUNCH_FAILED;
+}
+
+int conv2d_forward_packed(const conv2d_params* params, int variant_id, const void* in,
+                          const void* packed_filt, const float* bias, int activation, void* out,
+                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (variant_id < 0) return CONV2D_STATUS_INVALID_ARGUMENT;
+  if (activation != CONV2D_ACT_NONE && activation != CONV2D_ACT_RELU)
+    return CONV2D_STATUS_INVALID_ARGUMENT;
+  if (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)) return CONV2D_STATUS_INVALID_ARGUMENT;
+  {
+    Problem q;
+    int rc = derive(params, &q);
+    if (rc) return rc;
+    const Table& tb = table();
+    if (variant_id >= tb.n) return CONV2D_STATUS_INVALID_ARGUMENT;
+    bool ok;
+    packed_filter_bytes_for(tb.v[variant_id], q, &ok);
+    if (!ok) return CONV2D_STATUS_UNSUPPORTED;
+  }
+  return run(params, in, packed_filt, out, workspace, workspace_bytes, hip_stream, variant_id, bias,
+             activation, false, true);
 }
 
 int conv2d_num_variants(void) { return table().n; }

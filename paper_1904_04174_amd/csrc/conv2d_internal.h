@@ -26,6 +26,10 @@ struct Problem {
   const void* filt;
   void* out;
   void* workspace;
+  // The filter already in the repacked form of the direct-to-LDS tile that runs (written by
+  // igemm_dma_pack_filter for the same tile and parameters), or null: the launch repacks
+  // `filt` into the head of the workspace first.  Not for batched launches.
+  const void* packed_filt;
   // Fused epilogue: out = act(sum + bias[k]).  bias: K fp32 values on the
   // device, or null; relu: 0 or 1.
   const float* bias;
@@ -103,6 +107,12 @@ bool igemm_dma_tile_fits(const Problem& p, int bf16, int tile);  // extra shape 
 // activation after the maximum: both are monotone) and stores the pooled
 // tensor only.
 bool igemm_dma_tile_pools(int bf16, int tile);
+// The repacked filter of a tile (slice-major, k contiguous, zero padded to whole slices) as a
+// tensor of its own: its size and the kernel that writes it from p.filt.  A launch with
+// Problem::packed_filt set to it skips its own repack.
+size_t igemm_dma_packed_filter_bytes(const Problem& p, int bf16, int tile);
+hipError_t igemm_dma_pack_filter(const Problem& p, int bf16, int tile, void* packed,
+                                 hipStream_t stream);
 // (a batched problem holds one repacked filter per batch and takes whole tiles only)
 size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile, int splits);
 hipError_t launch_igemm_dma(const Problem& p, int bf16, int tile, int splits, hipStream_t stream);

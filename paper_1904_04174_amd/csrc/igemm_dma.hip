@@ -851,21 +851,26 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   const int Kg_p = (p.Kg + T::BK - 1) / T::BK * T::BK;
   const int batches = p.batches > 1 ? p.batches : 1;
   if (batches > 1 && splits != 1) return hipErrorInvalidValue;  // batched: whole tiles only
-  // 1. filter -> Bt[K][Kg_p] in the workspace (one per batch)
-  dim3 rgrid(Kg_p / T::BK, (p.K + 63) / 64, batches);
-  const long long bt_stride = static_cast<long long>(filter_bytes<T>(p) / T::ES);
-  if (T::BF16)
-    hipLaunchKernelGGL((repack_filter_kernel<unsigned short>), rgrid, dim3(256), 0, stream,
-                       static_cast<const unsigned short*>(p.filt),
-                       static_cast<unsigned short*>(p.workspace), p.Kg, p.K, Kg_p, p.C,
-                       p.R * p.S, T::UNIFORM ? T::BK : 0, T::BK, p.filt_stride, bt_stride);
-  else
-    hipLaunchKernelGGL((repack_filter_kernel<float>), rgrid, dim3(256), 0, stream,
-                       static_cast<const float*>(p.filt), static_cast<float*>(p.workspace), p.Kg,
-                       p.K, Kg_p, p.C, p.R * p.S, T::UNIFORM ? T::BK : 0, T::BK, p.filt_stride,
-                       bt_stride);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  // 1. filter -> Bt[K][Kg_p] in the workspace (one per batch), unless the caller packed it before
+  if (p.packed_filt && batches > 1) return hipErrorInvalidValue;
+  const void* bt = p.packed_filt ? p.packed_filt : p.workspace;
+  hipError_t e = hipSuccess;
+  if (!p.packed_filt) {
+    dim3 rgrid(Kg_p / T::BK, (p.K + 63) / 64, batches);
+    const long long bt_stride = static_cast<long long>(filter_bytes<T>(p) / T::ES);
+    if (T::BF16)
+      hipLaunchKernelGGL((repack_filter_kernel<unsigned short>), rgrid, dim3(256), 0, stream,
+                         static_cast<const unsigned short*>(p.filt),
+                         static_cast<unsigned short*>(p.workspace), p.Kg, p.K, Kg_p, p.C,
+                         p.R * p.S, T::UNIFORM ? T::BK : 0, T::BK, p.filt_stride, bt_stride);
+    else
+      hipLaunchKernelGGL((repack_filter_kernel<float>), rgrid, dim3(256), 0, stream,
+                         static_cast<const float*>(p.filt), static_cast<float*>(p.workspace),
+                         p.Kg, p.K, Kg_p, p.C, p.R * p.S, T::UNIFORM ? T::BK : 0, T::BK,
+                         p.filt_stride, bt_stride);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   // 2. the convolution
   const TailPlan tail = plan_tail<T>(p, splits == kTailBalanced);
   int per_split;
@@ -876,7 +881,7 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
                                             filter_bytes<T>(p));
   hipLaunchKernelGGL((igemm_dma_kernel<T, OUT_BF16>),
                      dim3(tail.n_main + 2 * tail.wgs, splits, batches), dim3(T::NT), 0, stream, p,
-                     Kg_p, per_split, flush, p.workspace, partial, tail);
+                     Kg_p, per_split, flush, bt, partial, tail);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   // 3. sum of the partial outputs
@@ -1632,19 +1637,23 @@ int patch_tiles_m(const Problem& p) {
 
 template <class T, bool OUT_BF16>
 hipError_t launch_patch_one(const Problem& p, hipStream_t stream) {
-  // 1. filter -> Bt[slice][K][BK], channel block by channel block
-  dim3 rgrid(p.Kg / T::BK, (p.K + 63) / 64);
-  if (T::BF16)
-    hipLaunchKernelGGL((repack_filter_kernel<unsigned short>), rgrid, dim3(256), 0, stream,
-                       static_cast<const unsigned short*>(p.filt),
-                       static_cast<unsigned short*>(p.workspace), p.Kg, p.K, p.Kg, p.C,
-                       p.R * p.S, T::BK, T::BK, 0LL, 0LL);
-  else
-    hipLaunchKernelGGL((repack_filter_kernel<float>), rgrid, dim3(256), 0, stream,
-                       static_cast<const float*>(p.filt), static_cast<float*>(p.workspace), p.Kg,
-                       p.K, p.Kg, p.C, p.R * p.S, T::BK, T::BK, 0LL, 0LL);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  // 1. filter -> Bt[slice][K][BK], channel block by channel block, unless packed before
+  const void* bt = p.packed_filt ? p.packed_filt : p.workspace;
+  hipError_t e = hipSuccess;
+  if (!p.packed_filt) {
+    dim3 rgrid(p.Kg / T::BK, (p.K + 63) / 64);
+    if (T::BF16)
+      hipLaunchKernelGGL((repack_filter_kernel<unsigned short>), rgrid, dim3(256), 0, stream,
+                         static_cast<const unsigned short*>(p.filt),
+                         static_cast<unsigned short*>(p.workspace), p.Kg, p.K, p.Kg, p.C,
+                         p.R * p.S, T::BK, T::BK, 0LL, 0LL);
+    else
+      hipLaunchKernelGGL((repack_filter_kernel<float>), rgrid, dim3(256), 0, stream,
+                         static_cast<const float*>(p.filt), static_cast<float*>(p.workspace),
+                         p.Kg, p.K, p.Kg, p.C, p.R * p.S, T::BK, T::BK, 0LL, 0LL);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   // 2. the convolution
   const int tiles = patch_tiles_m<T>(p) * ((p.K + T::BN - 1) / T::BN);
   const int nslices = p.Kg / T::BK;
@@ -1655,7 +1664,7 @@ hipError_t launch_patch_one(const Problem& p, hipStream_t stream) {
   const int resident = kComputeUnits * T::OCC;
   const int grid = T::PERSIST && tiles > resident ? resident : tiles;
   hipLaunchKernelGGL((igemm_patch_kernel<T, OUT_BF16>), dim3(grid), dim3(T::NT), 0, stream, p,
-                     p.P + p.R - 1, patch_width, flush, p.workspace, tiles);
+                     p.P + p.R - 1, patch_width, flush, bt, tiles);
   return hipGetLastError();
 }
 
@@ -1791,6 +1800,29 @@ bool igemm_dma_tile_fits(const Problem& p, int bf16, int tile) {
 }
 bool igemm_dma_tile_has_wino(int bf16, int tile) { return entry(bf16, tile).wino != nullptr; }
 bool igemm_dma_tile_pools(int bf16, int tile) { return entry(bf16, tile).pools; }
+size_t igemm_dma_packed_filter_bytes(const Problem& p, int bf16, int tile) {
+  const TileEntry& t = entry(bf16, tile);
+  const size_t kg_p = static_cast<size_t>((p.Kg + t.bk - 1) / t.bk) * t.bk;
+  return (kg_p * p.K * (bf16 ? 2 : 4) + 255) / 256 * 256;
+}
+hipError_t igemm_dma_pack_filter(const Problem& p, int bf16, int tile, void* packed,
+                                 hipStream_t stream) {
+  const TileEntry& t = entry(bf16, tile);
+  const int Kg_p = (p.Kg + t.bk - 1) / t.bk * t.bk;
+  // uniform and patch tiles walk the reduction channel block by channel block
+  const int block = (t.addr == kUniform || t.addr == 3) ? t.bk : 0;
+  dim3 rgrid(Kg_p / t.bk, (p.K + 63) / 64, 1);
+  if (bf16)
+    hipLaunchKernelGGL((repack_filter_kernel<unsigned short>), rgrid, dim3(256), 0, stream,
+                       static_cast<const unsigned short*>(p.filt),
+                       static_cast<unsigned short*>(packed), p.Kg, p.K, Kg_p, p.C, p.R * p.S,
+                       block, t.bk, 0LL, 0LL);
+  else
+    hipLaunchKernelGGL((repack_filter_kernel<float>), rgrid, dim3(256), 0, stream,
+                       static_cast<const float*>(p.filt), static_cast<float*>(packed), p.Kg, p.K,
+                       Kg_p, p.C, p.R * p.S, block, t.bk, 0LL, 0LL);
+  return hipGetLastError();
+}
 hipError_t launch_igemm_dma_wino(const Problem& p, int bf16, int tile, hipStream_t stream) {
   const TileEntry& t = entry(bf16, tile);
   return t.wino ? t.wino(p, stream) : hipErrorInvalidValue;

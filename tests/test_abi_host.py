@@ -315,3 +315,44 @@ def test_pool_arguments_and_workspace_sizes_on_the_host():
     assert B.conv2d_pool_workspace_size(big) == B.conv2d_pool_workspace_size(big, sel)
     with pytest.raises(B.Conv2dError):
         B.conv2d_pool_workspace_size(big, B.conv2d_num_variants())
+
+
+def test_packed_filter_sizes_and_argument_checks():
+    p = B.make_params(2, 14, 14, 40, 24, 3, 3)       # Kg = 360: no multiple of a 16-wide slice
+    l = B.lib()
+    names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
+    seen = set()
+    for v, name in enumerate(names):
+        if not B.conv2d_variant_supports(p, v):
+            continue
+        n = ctypes.c_size_t(0)
+        rc = l.conv2d_packed_filter_size(ctypes.byref(p), v, ctypes.byref(n))
+        if name.startswith(("winograd2x2_", "padc_")):
+            assert rc == B.STATUS_UNSUPPORTED, name
+            assert l.conv2d_pack_filter(ctypes.byref(p), v, 16, 16, 1 << 30, 0) == B.STATUS_UNSUPPORTED
+            assert l.conv2d_forward_packed(ctypes.byref(p), v, 16, 16, 0, 0, 16, 0, 0, 0) == \
+                B.STATUS_UNSUPPORTED
+            continue
+        assert rc == 0, name
+        if name.startswith("igemm_dma_f32_") and "_r64_" in name:
+            # slices of 16 fp32 values: 360 -> 368 rows of 24 features
+            assert n.value == (368 * 24 * 4 + 255) // 256 * 256, name
+            seen.add("dma")
+        elif name == "direct" or name.startswith("igemm_f32_"):
+            assert n.value == (360 * 24 * 4 + 255) // 256 * 256, name
+            seen.add("copy")
+        # a buffer that is too small, null pointers: rejected before any device call
+        assert l.conv2d_pack_filter(ctypes.byref(p), v, 16, 16, n.value - 1, 0) == \
+            B.STATUS_WORKSPACE_TOO_SMALL
+        assert l.conv2d_pack_filter(ctypes.byref(p), v, 0, 16, n.value, 0) == B.STATUS_INVALID_ARGUMENT
+        assert l.conv2d_pack_filter(ctypes.byref(p), v, 16, 0, n.value, 0) == B.STATUS_INVALID_ARGUMENT
+    assert seen == {"dma", "copy"}
+    n = ctypes.c_size_t(0)
+    assert l.conv2d_packed_filter_size(ctypes.byref(p), -1, ctypes.byref(n)) == B.STATUS_INVALID_ARGUMENT
+    assert l.conv2d_packed_filter_size(ctypes.byref(p), len(names), ctypes.byref(n)) == \
+        B.STATUS_INVALID_ARGUMENT
+    assert l.conv2d_packed_filter_size(ctypes.byref(p), 0, None) == B.STATUS_INVALID_ARGUMENT
+    assert l.conv2d_forward_packed(ctypes.byref(p), -1, 16, 16, 0, 0, 16, 0, 0, 0) == \
+        B.STATUS_INVALID_ARGUMENT
+    assert l.conv2d_forward_packed(ctypes.byref(p), 0, 16, 16, 0, 7, 16, 0, 0, 0) == \
+        B.STATUS_INVALID_ARGUMENT   # unknown activation

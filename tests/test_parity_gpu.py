@@ -664,6 +664,75 @@ def test_pool_full_size(torch_cuda, oracle, name, in_dtype, out_dtype):
     assert err <= (TOL_F32 if in_dtype == B.F32 else TOL_BF16), (name, err)
 
 
+# ------------------------------------------------------------------ filters packed ahead of time
+
+PACKED_CASES = [SMALL[1], SMALL[3], SMALL[5], SMALL[7], SMALL[13], SMALL[14], SMALL[16]]
+
+
+@pytest.mark.parametrize("case", PACKED_CASES)
+@pytest.mark.parametrize("in_dtype", [B.F32, B.BF16])
+def test_packed_filter_gives_the_same_bits(torch_cuda, oracle, case, in_dtype):
+    """conv2d_pack_filter + conv2d_forward_packed against conv2d_forward_variant with the same
+    variant: the same kernel on the same packed values, so the outputs are bit-identical; the
+    first variant of every case is also checked against the oracle, with bias and ReLU."""
+    torch = torch_cuda
+    (n, h, w, c, k, r, s_, sr, sc, pad) = case
+    x, f = wl.make_case((n, h, w, c), (r, s_, c, k), "uniform", 4242)
+    if in_dtype == B.BF16:
+        x, _ = wl.round_to_bf16(x)
+        f, _ = wl.round_to_bf16(f)
+    bias = np.random.default_rng(4243).uniform(-1, 1, k).astype(np.float32)
+    p = _params(case, in_dtype, B.F32)
+    tdt = torch.float32 if in_dtype == B.F32 else torch.bfloat16
+    xd = torch.from_numpy(x).cuda().to(tdt)
+    fd = torch.from_numpy(f).cuda().to(tdt)
+    bd = torch.from_numpy(bias).cuda()
+    want = oracle.forward_bias_act_f32(x, f, bias, True, (sr, sc), pad)
+    ran = 0
+    for v in supported_variants(p):
+        name = B.conv2d_variant_name(v)
+        if name.startswith(("winograd2x2_", "padc_")):
+            with pytest.raises(B.Conv2dError):
+                B.conv2d_packed_filter_size(p, v)
+            continue
+        _say("packed %s %s" % (case, name))
+        packed = B.conv2d_pack_filter(p, v, fd)
+        plain = B.conv2d_forward(p, xd, fd, variant_id=v)
+        got = B.conv2d_forward_packed(p, v, xd, packed)
+        torch.cuda.synchronize()
+        assert torch.equal(got, plain), name
+        if ran == 0:
+            fused = B.conv2d_forward_packed(p, v, xd, packed, bd, B.ACT_RELU)
+            err = rel_err(fused.cpu().numpy(), want)
+            assert err <= (TOL_F32 if in_dtype == B.F32 else TOL_BF16), (name, err)
+        ran += 1
+    assert ran >= 2
+
+
+@pytest.mark.parametrize("name,in_dtype", [("V56-N16", B.F32), ("V28-N16", B.BF16),
+                                           ("R1x1a", B.BF16), ("V14-N1", B.F32)])
+def test_packed_filter_full_size(torch_cuda, oracle, name, in_dtype):
+    """The selected direct-sum variant on a packed filter, full-size layers, against the oracle."""
+    torch = torch_cuda
+    L = wl.LAYERS[name]
+    x, f = wl.make_inputs(L)
+    if in_dtype == B.BF16:
+        x, _ = wl.round_to_bf16(x)
+        f, _ = wl.round_to_bf16(f)
+    p = B.params_of_layer(L, in_dtype, B.F32)
+    v = B.conv2d_select_variant(p, B.SELECT_DIRECT_SUM_ONLY)
+    _say("packed full %s variant %s" % (name, B.conv2d_variant_name(v)))
+    tdt = torch.float32 if in_dtype == B.F32 else torch.bfloat16
+    xd = torch.from_numpy(x).cuda().to(tdt)
+    fd = torch.from_numpy(f).cuda().to(tdt)
+    packed = B.conv2d_pack_filter(p, v, fd)
+    del fd
+    got = B.conv2d_forward_packed(p, v, xd, packed).cpu().numpy()
+    want = oracle.forward_f32(x, f, (L.stride_rows, L.stride_cols), L.padding)
+    err = rel_err(got, want)
+    assert err <= (TOL_F32 if in_dtype == B.F32 else TOL_BF16), (name, err)
+
+
 def test_calls_can_be_captured_in_a_hip_graph(torch_cuda, oracle):
     """The library only enqueues kernels (no allocation, no memset, no synchronisation), so a
     sequence of calls can be captured into a HIP graph.  Several replays, with eager work and
