@@ -27,15 +27,23 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2516.6}   # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the selected fp32 variant (convolution kernel), from two rocprofv3 --pmc
-# runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, factors calibrated on a 256 MiB copy); source:
-# profiles/igemm_dma_counters_per_layer.md.  Not measurable inside this process.
+# HBM bytes per launch of a layer's selected variant (convolution kernel plus its reduce kernel),
+# from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, factors calibrated on a
+# 256 MiB copy); source: profiles/igemm_dma_counters_per_layer.md.  Not measurable inside this
+# process; keyed by the variant as well, so that another selection reports null, not a wrong figure.
 MEASURED_TRAFFIC_MB = {
-    ("f32", "V224-N16"): 206.9 + 205.5, ("f32", "V112-N16"): 108.1 + 102.8,
-    ("f32", "V56-N16"): 95.7 + 54.5, ("f32", "V28-N16"): 388.8 + 29.4,
-    ("f32", "V14-N16"): 106.0 + 19.3 + 6.4,
-    ("bf16", "V224-N16"): 104.7 + 205.5, ("bf16", "V112-N16"): 61.0 + 102.8,
-    ("bf16", "V56-N16"): 36.2 + 51.4, ("bf16", "V28-N16"): 52.8 + 25.7,
+    ("f32", "V224-N16", "igemm_patch_f32_128x64_w2x2_p256_b16"): 277.6 + 205.5,
+    ("f32", "V224-N16", "igemm_dma_f32_64x64_r64_w2x2_s3"): 206.9 + 205.5,
+    ("f32", "V112-N16", "igemm_patch_f32_128x64_w2x2_p256_b16"): 122.7 + 102.8,
+    ("f32", "V112-N16", "igemm_dma_f32_64x64_r64_w2x2_s3"): 108.1 + 102.8,
+    ("f32", "V56-N16", "igemm_dma_f32_128x128_r64_w2x2_s4_tail"): 100.6 + 67.1 + 16.8 + 1.0,
+    ("f32", "V56-N16", "igemm_dma_f32_64x64_r64_w2x2_s3_tail"): 95.7 + 54.5 + 4.3 + 1.0,
+    ("f32", "V28-N16", "igemm_dma_f32_64x64_r64_w2x2_s3_tail"): 390.4 + 29.4 + 4.3 + 0.5,
+    ("f32", "V14-N16", "igemm_dma_f32_64x64_r64_w2x2_s4_splitk"): 107.0 + 19.3 + 19.3 + 6.4,
+    ("bf16", "V224-N16", "igemm_patch_bf16_256x64_w4x1_p512_b16"): 189.9 + 205.5,
+    ("bf16", "V112-N16", "igemm_patch_bf16_256x64_w4x1_p512_b16"): 71.1 + 102.8,
+    ("bf16", "V56-N16", "igemm_patch_bf16_224x128_w2x2_p384_b16_m16"): 40.5 + 51.4,
+    ("bf16", "V28-N16", "igemm_patch_bf16_224x128_w2x2_p384_m16"): 52.2 + 25.7,
 }
 
 
@@ -225,8 +233,9 @@ def main():
     achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(achieved / peak, 4),
-                "traffic": (round(MEASURED_TRAFFIC_MB[(args.dtype, dom["name"])] * 1e6)
-                            if (args.dtype, dom["name"]) in MEASURED_TRAFFIC_MB else None),
+                "traffic": (round(MEASURED_TRAFFIC_MB[(args.dtype, dom["name"], dom["variant"])] * 1e6)
+                            if (args.dtype, dom["name"], dom["variant"]) in MEASURED_TRAFFIC_MB
+                            else None),
                 "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled)",
                 "algorithmic_bytes_per_launch": dom["bytes"],
                 "kernel": dom["variant"], "layer": dom["name"],
