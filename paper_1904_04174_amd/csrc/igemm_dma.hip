@@ -177,6 +177,15 @@ __device__ __forceinline__ unsigned short to_bf16_bits(float x) {
   return static_cast<unsigned short>(u >> 16);
 }
 
+// Final outputs are stored non-temporally: nothing in the call reads them back, and as ordinary
+// stores they take L2 lines from the input rows that neighbouring tiles are about to re-use
+// (measured on a 224x224x64 bf16 layer, persistent patch tile: 189.5 MB fetched from beyond L2
+// with ordinary stores, 103.6 MB with the stores switched off; the input is 102.8 MB).
+template <class V>
+__device__ __forceinline__ void store_out(V* ptr, V value) {
+  __builtin_nontemporal_store(value, ptr);
+}
+
 // Bt[k' / bk][n][k' % bk] = filt[k][n], 0 for Kg <= k' < Kg_p: one slice of bk
 // consecutive k' for all features is contiguous, so a B tile of a slice is
 // one contiguous block and its loads fetch whole cache lines.  With
@@ -747,11 +756,11 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
           if (to_partial)
             part[idx] = acc[i][j][v];
           else if (OUT_BF16)
-            static_cast<unsigned short*>(p.out)[bz * p.out_stride + idx] =
-                to_bf16_bits(finish(acc[i][j][v], bcol, p.relu));
+            store_out(static_cast<unsigned short*>(p.out) + bz * p.out_stride + idx,
+                      to_bf16_bits(finish(acc[i][j][v], bcol, p.relu)));
           else
-            static_cast<float*>(p.out)[bz * p.out_stride + idx] =
-                finish(acc[i][j][v], bcol, p.relu);
+            store_out(static_cast<float*>(p.out) + bz * p.out_stride + idx,
+                      finish(acc[i][j][v], bcol, p.relu));
         }
       }
     }
@@ -1081,11 +1090,13 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   // blocked tiles: image and top-left output pixel of the block
   int blk_n = 0, blk_p = 0, blk_q = 0;
   auto block_of = [&](int t, int& bn, int& bp, int& bq) {
-    const int nbx = (p.Q + T::BW - 1) / T::BW, nby = (p.P + T::BH - 1) / T::BH;
-    const int tm = t / tiles_n;
-    bq = (tm % nbx) * T::BW;
-    bp = ((tm / nbx) % nby) * T::BH;
-    bn = tm / (nbx * nby);
+    if constexpr (T::BW > 0) {
+      const int nbx = (p.Q + T::BW - 1) / T::BW, nby = (p.P + T::BH - 1) / T::BH;
+      const int tm = t / tiles_n;
+      bq = (tm % nbx) * T::BW;
+      bp = ((tm / nbx) % nby) * T::BH;
+      bn = tm / (nbx * nby);
+    }
   };
   if constexpr (T::BW > 0) block_of(tile, blk_n, blk_p, blk_q);
   constexpr int taps = 9;
@@ -1507,13 +1518,15 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
           const size_t idx = static_cast<size_t>(row) * p.K + col;
           if (vec_ok && col + 3 < p.K) {
             if (OUT_BF16) {
-              uint2 packed;
+              typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+              uintx2 packed;
               packed.x = to_bf16_bits(r[0]) | (static_cast<unsigned>(to_bf16_bits(r[1])) << 16);
               packed.y = to_bf16_bits(r[2]) | (static_cast<unsigned>(to_bf16_bits(r[3])) << 16);
-              *reinterpret_cast<uint2*>(static_cast<unsigned short*>(p.out) + idx) = packed;
+              store_out(reinterpret_cast<uintx2*>(static_cast<unsigned short*>(p.out) + idx),
+                        packed);
             } else {
-              *reinterpret_cast<float4*>(static_cast<float*>(p.out) + idx) =
-                  make_float4(r[0], r[1], r[2], r[3]);
+              floatx4 quad = {r[0], r[1], r[2], r[3]};
+              store_out(reinterpret_cast<floatx4*>(static_cast<float*>(p.out) + idx), quad);
             }
           } else {
 #pragma unroll
@@ -1552,9 +1565,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
             if (py < P2 && px < Q2 && col < p.K) {
               const size_t idx = (static_cast<size_t>(blk_n * P2 + py) * Q2 + px) * p.K + col;
               if (OUT_BF16)
-                static_cast<unsigned short*>(p.out)[idx] = to_bf16_bits(finish(m, bcol, p.relu));
+                store_out(static_cast<unsigned short*>(p.out) + idx,
+                          to_bf16_bits(finish(m, bcol, p.relu)));
               else
-                static_cast<float*>(p.out)[idx] = finish(m, bcol, p.relu);
+                store_out(static_cast<float*>(p.out) + idx, finish(m, bcol, p.relu));
             }
           }
         }
@@ -1584,10 +1598,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
         if (row_ok && col < p.K) {
           const size_t idx = static_cast<size_t>(row) * p.K + col;
           if (OUT_BF16)
-            static_cast<unsigned short*>(p.out)[idx] =
-                to_bf16_bits(finish(acc[i][j][v], bcol, p.relu));
+            store_out(static_cast<unsigned short*>(p.out) + idx,
+                      to_bf16_bits(finish(acc[i][j][v], bcol, p.relu)));
           else
-            static_cast<float*>(p.out)[idx] = finish(acc[i][j][v], bcol, p.relu);
+            store_out(static_cast<float*>(p.out) + idx, finish(acc[i][j][v], bcol, p.relu));
         }
       }
     }
