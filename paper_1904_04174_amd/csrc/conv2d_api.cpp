@@ -561,6 +561,9 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     q.out = unpooled;
   }
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  // (an error that some earlier, unrelated runtime call of the process left behind is not
+  // this call's: the launchers below report through hipGetLastError)
+  (void)hipGetLastError();
   hipError_t e = hipSuccess;
   switch (tb.v[id].family) {
     case kDirect: e = launch_direct(q, stream); break;
@@ -701,6 +704,7 @@ int conv2d_pack_filter(const conv2d_params* params, int variant_id, const void* 
       ((reinterpret_cast<uintptr_t>(filt) | reinterpret_cast<uintptr_t>(packed)) & 15u))
     return CONV2D_STATUS_UNSUPPORTED;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  (void)hipGetLastError();  // not this call's
   hipError_t e;
   if (v.family == kDma) {
     q.filt = filt;

@@ -758,6 +758,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
           else if (OUT_BF16)
             store_out(static_cast<unsigned short*>(p.out) + bz * p.out_stride + idx,
                       to_bf16_bits(finish(acc[i][j][v], bcol, p.relu)));
+          else if (p.batches > 1)  // an intermediate that the next kernel reads: keep it cached
+            static_cast<float*>(p.out)[bz * p.out_stride + idx] =
+                finish(acc[i][j][v], bcol, p.relu);
           else
             store_out(static_cast<float*>(p.out) + bz * p.out_stride + idx,
                       finish(acc[i][j][v], bcol, p.relu));
@@ -1498,9 +1501,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
 #pragma unroll
       for (int v = 0; v < 4; ++v) asm volatile("" : "+v"(bias4[j][v]));
     const bool vec_ok = (p.K & 3) == 0;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      int row = m0 + wm * T::WM + i * BLK + lr;
+    // output row of pixel `px` of 16-row block i, or -1 if it is not stored
+    auto out_row = [&](int i, int px) {
+      int row = m0 + wm * T::WM + i * BLK + px;
       bool row_ok = row < p.M;
       if constexpr (T::BW > 0) {
         const int ml = row - m0;  // position in the block
@@ -1508,6 +1511,51 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
         row_ok = op < p.P && oq < p.Q;
         row = (blk_n * p.P + op) * p.Q + oq;
       }
+      return row_ok ? row : -1;
+    };
+    // fp32 output with whole 32-feature groups: two feature blocks are stored together so that
+    // one store instruction writes whole 128-byte lines (8 pixels x 32 features) instead of
+    // 64-byte halves (16 pixels x 16 features), which as non-temporal stores cost ~1.45x the
+    // write traffic.  Lanes px and px ^ 8 swap one of their two quads (a rotate by 8 inside
+    // the row of 16 lanes); then the first store covers the pixels with px & 8 == 0, the second
+    // the others.
+    if (!OUT_BF16 && TN % 2 == 0 && (p.K & 31) == 0) {
+      const bool hi = (lr & 8) != 0;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row_own = out_row(i, lr), row_other = out_row(i, lr ^ 8);
+#pragma unroll
+        for (int j = 0; j < TN; j += 2) {
+          const int col = n0 + wn * T::WN + (hi ? j + 1 : j) * BLK + lk * 4;
+          floatx4 lo, up, sent, got;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            lo[v] = finish(acc[i][j][v], bias4[j][v], p.relu);
+            up[v] = finish(acc[i][j + 1][v], bias4[j + 1][v], p.relu);
+          }
+          sent = hi ? lo : up;
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            got[v] = __int_as_float(__builtin_amdgcn_update_dpp(
+                0, __float_as_int(sent[v]), 0x128 /* row_ror:8 */, 0xf, 0xf, false));
+          // pixels with px & 8 == 0: their own lower quad, the partner's upper quad
+          const int row_a = hi ? row_other : row_own;
+          if (row_a >= 0 && col + 3 < p.K)
+            store_out(reinterpret_cast<floatx4*>(static_cast<float*>(p.out) +
+                                                 static_cast<size_t>(row_a) * p.K + col),
+                      hi ? got : lo);
+          const int row_b = hi ? row_own : row_other;
+          if (row_b >= 0 && col + 3 < p.K)
+            store_out(reinterpret_cast<floatx4*>(static_cast<float*>(p.out) +
+                                                 static_cast<size_t>(row_b) * p.K + col),
+                      hi ? up : got);
+        }
+      }
+    } else {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int row = out_row(i, lr);
+      const bool row_ok = row >= 0;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int col = n0 + wn * T::WN + j * BLK + lk * 4;
@@ -1541,6 +1589,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
         }
       }
     }
+    }  // one feature block per store
   } else {
   bool pooled = false;
   if constexpr (T::POOLS) {
