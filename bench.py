@@ -32,17 +32,14 @@ PEAK_HBM_GBS = 8000.0
 # 256 MiB copy); source: profiles/igemm_dma_counters_per_layer.md.  Not measurable inside this
 # process; keyed by the variant as well, so that another selection reports null, not a wrong figure.
 MEASURED_TRAFFIC_MB = {
-    ("f32", "V224-N16", "igemm_patch_f32_128x64_w2x2_p256_b16"): 277.6 + 205.5,
-    ("f32", "V224-N16", "igemm_dma_f32_64x64_r64_w2x2_s3"): 206.9 + 205.5,
-    ("f32", "V112-N16", "igemm_patch_f32_128x64_w2x2_p256_b16"): 122.7 + 102.8,
-    ("f32", "V112-N16", "igemm_dma_f32_64x64_r64_w2x2_s3"): 108.1 + 102.8,
-    ("f32", "V56-N16", "igemm_dma_f32_128x128_r64_w2x2_s4_tail"): 100.6 + 67.1 + 16.8 + 1.0,
-    ("f32", "V56-N16", "igemm_dma_f32_64x64_r64_w2x2_s3_tail"): 95.7 + 54.5 + 4.3 + 1.0,
-    ("f32", "V28-N16", "igemm_dma_f32_64x64_r64_w2x2_s3_tail"): 390.4 + 29.4 + 4.3 + 0.5,
-    ("f32", "V14-N16", "igemm_dma_f32_64x64_r64_w2x2_s4_splitk"): 107.0 + 19.3 + 19.3 + 6.4,
-    ("bf16", "V224-N16", "igemm_patch_bf16_256x64_w4x1_p512_b16"): 189.9 + 205.5,
-    ("bf16", "V112-N16", "igemm_patch_bf16_256x64_w4x1_p512_b16"): 71.1 + 102.8,
-    ("bf16", "V56-N16", "igemm_patch_bf16_224x128_w2x2_p384_b16_m16"): 40.5 + 51.4,
+    ("f32", "V224-N16", "igemm_patch_f32_128x64_w2x2_p256_b16"): 223.6 + 205.5,
+    ("f32", "V112-N16", "igemm_dma_f32_64x64_r64_w2x2_s3_tail"): 109.3 + 104.9 + 4.3 + 2.1,
+    ("f32", "V56-N16", "igemm_dma_f32_64x64_r64_w2x2_s3_tail"): 78.2 + 54.5 + 4.3 + 1.0,
+    ("f32", "V28-N16", "igemm_dma_f32_64x64_r64_w2x2_s3_tail"): 388.0 + 29.4 + 4.3 + 0.5,
+    ("f32", "V14-N16", "igemm_dma_f32_64x64_r64_w2x2_s4_splitk"): 106.2 + 19.3 + 19.3 + 6.4,
+    ("bf16", "V224-N16", "igemm_patch_bf16_256x64_w4x1_p512_b16"): 105.0 + 205.5,
+    ("bf16", "V112-N16", "igemm_patch_bf16_224x128_w2x2_p384_b16_m16"): 54.1 + 102.8,
+    ("bf16", "V56-N16", "igemm_patch_bf16_224x128_w2x2_p384_b16_m16"): 35.4 + 51.4,
     ("bf16", "V28-N16", "igemm_patch_bf16_224x128_w2x2_p384_m16"): 52.2 + 25.7,
 }
 
