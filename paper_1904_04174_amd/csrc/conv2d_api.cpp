@@ -524,6 +524,7 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
   const Table& tb = table();
   if (variant_id >= tb.n) return CONV2D_STATUS_INVALID_ARGUMENT;
   if (q.N == 0) return CONV2D_STATUS_OK;
+  if (pool && (q.P < 2 || q.Q < 2)) return CONV2D_STATUS_OK;  // empty pooled tensor: nothing to do
   if (!in || !filt || !out) return CONV2D_STATUS_INVALID_ARGUMENT;
   const bool al = aligned16(in, filt, out);
   int id = variant_id;
@@ -541,7 +542,6 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     if (!al && tb.v[id].family != kDirect && !is_scalar(tb.v[id]))
       return CONV2D_STATUS_UNSUPPORTED;
   }
-  if (pool && (q.P < 2 || q.Q < 2)) return CONV2D_STATUS_OK;  // empty pooled tensor
   const bool fused_pool = pool && pools_in_epilogue(tb.v[id]);
   const size_t need = pool ? pooled_workspace_bytes_for(tb.v[id], q) : workspace_bytes_for(tb.v[id], q);
   if (need > 0) {

@@ -297,6 +297,8 @@ def test_pool_arguments_and_workspace_sizes_on_the_host():
     # an output of one row has no 2x2 window: nothing to do, no workspace asked for
     thin = B.make_params(2, 1, 9, 4, 4, 1, 1)
     assert l.conv2d_forward_bias_act_pool(ctypes.byref(thin), 16, 16, 0, B.ACT_NONE, 16, 0, 0, 0) == 0
+    # (the empty output tensor may well have a null pointer)
+    assert l.conv2d_forward_bias_act_pool(ctypes.byref(thin), 16, 16, 0, B.ACT_NONE, 0, 0, 0, 0) == 0
     # a variant that pools in its epilogue needs its own workspace only; any other also the
     # unpooled tensor behind it
     big = B.make_params(16, 224, 224, 64, 64, 3, 3, in_dtype=B.BF16, out_dtype=B.BF16)
