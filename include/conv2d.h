@@ -197,6 +197,11 @@ CONV2D_API int conv2d_forward_packed(const conv2d_params* params, int variant_id
                                      void* out, void* workspace, size_t workspace_bytes,
                                      void* hip_stream);
 
+/* The runtime's description of the error behind the calling thread's last
+ * CONV2D_STATUS_LAUNCH_FAILED ("" if there was none).  The string is the
+ * runtime's and stays valid. */
+CONV2D_API const char* conv2d_last_launch_error(void);
+
 /* Variant introspection (host only). */
 CONV2D_API int conv2d_num_variants(void);
 CONV2D_API const char* conv2d_variant_name(int variant_id);            /* NULL if out of range */

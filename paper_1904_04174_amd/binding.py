@@ -27,7 +27,7 @@ EXPORTS = (
     "conv2d_forward", "conv2d_forward_variant", "conv2d_forward_bias_act",
     "conv2d_forward_bias_act_pool", "conv2d_pool_workspace_size",
     "conv2d_pool_workspace_size_variant", "conv2d_packed_filter_size", "conv2d_pack_filter",
-    "conv2d_forward_packed", "conv2d_num_variants",
+    "conv2d_forward_packed", "conv2d_last_launch_error", "conv2d_num_variants",
     "conv2d_variant_name",
     "conv2d_variant_supports", "conv2d_selected_variant", "conv2d_select_variant",
     "conv2d_status_string", "conv2d_version",
@@ -50,7 +50,10 @@ class Geometry(ctypes.Structure):
 class Conv2dError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
-        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+        detail = ""
+        if status == STATUS_LAUNCH_FAILED:
+            detail = ": " + lib().conv2d_last_launch_error().decode()
+        super().__init__("%s: %s%s (status %d)" % (where, status_string(status), detail, status))
 
 
 _lib = None
@@ -64,6 +67,15 @@ def lib():
             raise ImportError(
                 "%s is missing: build it with `python -m paper_1904_04174_amd.build` "
                 "(there is no CPU fallback)" % LIB_PATH)
+        # torch ships a HIP runtime of its own and loads it by path.  Loaded after this
+        # library (which would then have pulled in the system's runtime), it is a second
+        # runtime in the process, and this library's launches fail on device pointers of the
+        # other one ("no ROCm-capable device is detected").  Loaded first, it is the one this
+        # library binds to (same soname).
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         l = ctypes.CDLL(LIB_PATH)
         pp, gp = ctypes.POINTER(Params), ctypes.POINTER(Geometry)
         vp, sz = ctypes.c_void_p, ctypes.c_size_t
@@ -87,6 +99,8 @@ def lib():
         l.conv2d_pack_filter.argtypes = [pp, ctypes.c_int, vp, vp, sz, vp]
         l.conv2d_forward_packed.argtypes = [pp, ctypes.c_int, vp, vp, vp, ctypes.c_int, vp, vp, sz,
                                             vp]
+        l.conv2d_last_launch_error.argtypes = []
+        l.conv2d_last_launch_error.restype = ctypes.c_char_p
         l.conv2d_select_variant.argtypes = [pp, ctypes.c_uint32, ctypes.POINTER(ctypes.c_int)]
         l.conv2d_status_string.argtypes = [ctypes.c_int]
         l.conv2d_status_string.restype = ctypes.c_char_p

@@ -496,6 +496,9 @@ size_t packed_filter_bytes_for(const Variant& v, const Problem& q, bool* ok) {
   return 0;
 }
 
+// The runtime's error code behind this thread's last LAUNCH_FAILED status.
+thread_local hipError_t last_launch_error = hipSuccess;
+
 // 2x2 pooling in the epilogue: whole blocked patch tiles.
 bool pools_in_epilogue(const Variant& v) {
   return v.family == kDma && v.split == kWhole && igemm_dma_tile_pools(v.bf16, v.tile);
@@ -580,6 +583,7 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
   }
   if (e == hipSuccess && unpooled)
     e = launch_max_pool_2x2(unpooled, out, q.N, q.P, q.Q, q.K, q.out_bf16 != 0, stream);
+  if (e != hipSuccess) last_launch_error = e;
   return e == hipSuccess ? CONV2D_STATUS_OK : CONV2D_STATUS_LAUNCH_FAILED;
 }
 
@@ -713,6 +717,7 @@ int conv2d_pack_filter(const conv2d_params* params, int variant_id, const void* 
     e = hipMemcpyAsync(packed, filt, static_cast<size_t>(q.Kg) * q.K * (q.in_bf16 ? 2 : 4),
                        hipMemcpyDeviceToDevice, stream);
   }
+  if (e != hipSuccess) last_launch_error = e;
   return e == hipSuccess ? CONV2D_STATUS_OK : CONV2D_STATUS_LAUNCH_FAILED;
 }
 
@@ -782,6 +787,10 @@ const char* conv2d_status_string(int status) {
     case CONV2D_STATUS_TOO_LARGE: return "tensor too large for 31-bit indexing";
   }
   return "unknown status";
+}
+
+const char* conv2d_last_launch_error(void) {
+  return last_launch_error == hipSuccess ? "" : hipGetErrorString(last_launch_error);
 }
 
 int conv2d_version(void) { return 100; }

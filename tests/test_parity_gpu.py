@@ -7,6 +7,7 @@ result; in floating point that means "up to summation order"):
   bf16 in, fp32 accumulate: <= 2e-2 against the oracle run on the bf16-rounded inputs
   integer-valued inputs   : bit-exact (every summation order gives the same fp32 sum)
 """
+import os
 import sys
 
 import numpy as np
@@ -731,6 +732,27 @@ def test_packed_filter_full_size(torch_cuda, oracle, name, in_dtype):
     want = oracle.forward_f32(x, f, (L.stride_rows, L.stride_cols), L.padding)
     err = rel_err(got, want)
     assert err <= (TOL_F32 if in_dtype == B.F32 else TOL_BF16), (name, err)
+
+
+def test_library_loaded_before_torch(torch_cuda):
+    """A process that touches the library before it imports torch must not end up with two HIP
+    runtimes (torch ships its own): the binding loads torch's first.  Run in a child process,
+    where the order is under control."""
+    import subprocess
+    import sys
+    code = (
+        "from paper_1904_04174_amd import binding as B\n"
+        "n = B.conv2d_num_variants()\n"
+        "import torch\n"
+        "x = torch.ones((2, 16, 16, 32), device='cuda'); f = torch.ones((3, 3, 32, 32), device='cuda')\n"
+        "out = B.conv2d_forward(B.make_params(2, 16, 16, 32, 32, 3, 3), x, f)\n"
+        "torch.cuda.synchronize()\n"
+        "assert float(out[0, 8, 8, 0]) == 288.0, float(out[0, 8, 8, 0])\n"
+        "print('ok', n)\n")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True,
+                       timeout=240)
+    assert r.returncode == 0 and "ok" in r.stdout, (r.stdout[-500:], r.stderr[-1500:])
 
 
 def test_calls_can_be_captured_in_a_hip_graph(torch_cuda, oracle):
