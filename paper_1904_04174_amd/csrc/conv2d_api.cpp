@@ -420,12 +420,16 @@ bool usable(const Variant& v, const Problem& q, bool aligned) {
 // `direct_sum_only` leaves out the variants that reach the result through a
 // transform (Winograd): fewer multiplications, a large workspace.  A shape
 // may have two rows in the tuned table, the transform variant first.
-int select_uncached(const Problem& q, int padding, bool aligned, bool direct_sum_only);
+// What a selection is for: any algorithm, the direct-sum variants only, or the pooled entry
+// point (see select_uncached).
+enum SelectMode { kAny = 0, kDirectSumOnly = 1, kForPooling = 2 };
+int select_uncached(const Problem& q, int padding, bool aligned, int mode);
+bool pools_in_epilogue(const Variant& v);
 
 // The model path evaluates every variant (about 10 us of host time), which a
 // layer of a few microseconds cannot afford on every call: each thread keeps
 // its last selections in a small direct-mapped cache keyed on the parameters.
-int select(const Problem& q, int padding, bool aligned, bool direct_sum_only) {
+int select(const Problem& q, int padding, bool aligned, int mode) {
   struct Entry {
     int key[14];
     int variant;
@@ -434,21 +438,45 @@ int select(const Problem& q, int padding, bool aligned, bool direct_sum_only) {
   constexpr int kEntries = 64;
   thread_local Entry cache[kEntries] = {};
   const int key[14] = {q.N, q.H, q.W, q.C, q.K, q.R, q.S, q.sr, q.sc, padding, q.in_bf16,
-                       q.out_bf16, aligned ? 1 : 0, direct_sum_only ? 1 : 0};
+                       q.out_bf16, aligned ? 1 : 0, mode};
   unsigned h = 2166136261u;
   for (int v : key) h = (h ^ static_cast<unsigned>(v)) * 16777619u;
   Entry& e = cache[h % kEntries];
   if (e.valid && std::memcmp(e.key, key, sizeof(key)) == 0) return e.variant;
-  const int id = select_uncached(q, padding, aligned, direct_sum_only);
+  const int id = select_uncached(q, padding, aligned, mode);
   std::memcpy(e.key, key, sizeof(key));
   e.variant = id;
   e.valid = true;
   return id;
 }
 
-int select_uncached(const Problem& q, int padding, bool aligned, bool direct_sum_only) {
+int select_uncached(const Problem& q, int padding, bool aligned, int mode) {
   const Table& tb = table();
   if (q.M == 0) return 0;  // empty batch: nothing is launched
+  if (mode == kForPooling) {
+    // The unrestricted pick, unless that is a patch tile that cannot pool (the 16-row tiles)
+    // while a blocked patch tile that can is priced within 30 % of it and the layer is short
+    // enough in the reduction for the second kernel to matter: measured on 3x3 layers at batch
+    // 16 in bf16, 128 -> 128 channels 84.7 us with the second kernel against 64.5 us on a
+    // pooling tile, 256 -> 256 69.2 against 60.7, but 512 -> 512 64.3 against 68.8 (the
+    // unpooled tensor is small there and the 16-row tile is that much faster).  Other picks
+    // (Winograd, gather tiles) keep the two-kernel path: the model is not sharp enough to
+    // trade them against the pooling epilogue.
+    const int any = select_uncached(q, padding, aligned, kAny);
+    const Variant& a = tb.v[any];
+    if (pools_in_epilogue(a) || a.family != kDma || igemm_dma_tile_addressing(a.bf16, a.tile) != 3)
+      return any;
+    if (q.Kg > 3000) return any;
+    int best = any;
+    double best_cost = 1.3 * model_cost(a, q);
+    for (int i = 1; i < tb.n; ++i) {
+      if (!usable(tb.v[i], q, aligned) || !pools_in_epilogue(tb.v[i])) continue;
+      const double c = model_cost(tb.v[i], q);
+      if (c < best_cost) { best = i; best_cost = c; }
+    }
+    return best;
+  }
+  const bool direct_sum_only = mode == kDirectSumOnly;
   for (const Tuned& t : kTuned) {
     if (t.bf16 == q.in_bf16 && t.n == q.N && t.h == q.H && t.w == q.W && t.c == q.C &&
         t.k == q.K && t.r == q.R && t.s == q.S && t.sr == q.sr && t.sc == q.sc &&
@@ -532,7 +560,7 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
   const bool al = aligned16(in, filt, out);
   int id = variant_id;
   if (id < 0) {
-    id = select(q, params->padding, al, false);
+    id = select(q, params->padding, al, pool ? kForPooling : kAny);
     const char* env = std::getenv("CONV2D_FORCE_VARIANT");
     if (env && *env) {
       const int forced = std::atoi(env);
@@ -608,7 +636,7 @@ int conv2d_workspace_size(const conv2d_params* params, size_t* bytes) {
   if (!bytes) return CONV2D_STATUS_INVALID_ARGUMENT;
   int rc = derive(params, &q);
   if (rc) return rc;
-  *bytes = workspace_bytes_for(table().v[select(q, params->padding, true, false)], q);
+  *bytes = workspace_bytes_for(table().v[select(q, params->padding, true, kAny)], q);
   return CONV2D_STATUS_OK;
 }
 
@@ -650,7 +678,7 @@ int conv2d_pool_workspace_size(const conv2d_params* params, size_t* bytes) {
   if (!bytes) return CONV2D_STATUS_INVALID_ARGUMENT;
   int rc = derive(params, &q);
   if (rc) return rc;
-  *bytes = pooled_workspace_bytes_for(table().v[select(q, params->padding, true, false)], q);
+  *bytes = pooled_workspace_bytes_for(table().v[select(q, params->padding, true, kForPooling)], q);
   return CONV2D_STATUS_OK;
 }
 
@@ -763,7 +791,7 @@ int conv2d_selected_variant(const conv2d_params* params, int* variant_id) {
   if (!variant_id) return CONV2D_STATUS_INVALID_ARGUMENT;
   int rc = derive(params, &q);
   if (rc) return rc;
-  *variant_id = select(q, params->padding, true, false);
+  *variant_id = select(q, params->padding, true, kAny);
   return CONV2D_STATUS_OK;
 }
 
@@ -773,7 +801,8 @@ int conv2d_select_variant(const conv2d_params* params, uint32_t flags, int* vari
     return CONV2D_STATUS_INVALID_ARGUMENT;
   int rc = derive(params, &q);
   if (rc) return rc;
-  *variant_id = select(q, params->padding, true, (flags & CONV2D_SELECT_DIRECT_SUM_ONLY) != 0);
+  *variant_id = select(q, params->padding, true,
+                       (flags & CONV2D_SELECT_DIRECT_SUM_ONLY) ? kDirectSumOnly : kAny);
   return CONV2D_STATUS_OK;
 }
 

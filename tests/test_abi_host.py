@@ -315,6 +315,12 @@ def test_pool_arguments_and_workspace_sizes_on_the_host():
             assert pooled == (own + 255) // 256 * 256 + unpooled, name
     sel = B.conv2d_selected_variant(big)
     assert B.conv2d_pool_workspace_size(big) == B.conv2d_pool_workspace_size(big, sel)
+    # where conv2d_forward's pick cannot pool (a 16-row tile here), the pooled entry point takes a
+    # variant that can, if the model prices it below that pick plus the second kernel: no room
+    # for the unpooled tensor is asked for
+    mid = B.make_params(16, 112, 112, 128, 128, 3, 3, in_dtype=B.BF16, out_dtype=B.F32)
+    assert "_m16" in B.conv2d_variant_name(B.conv2d_selected_variant(mid))
+    assert B.conv2d_pool_workspace_size(mid) < 16 * 112 * 112 * 128 * 4
     with pytest.raises(B.Conv2dError):
         B.conv2d_pool_workspace_size(big, B.conv2d_num_variants())
 
