@@ -11,7 +11,8 @@ Prints ONE JSON line.  Besides the contract's fields it carries
   roofline     -- the kernel with the largest share of the step, its flop rate
                   from HIP events on the launch stream against the fp32 MFMA peak
   cpu_baseline -- the CPU oracle timed on a bounded sample of the same workload
-  layers       -- per-layer times (context): back to back on one buffer set (`ms`) and rotating
+  layers       -- per-layer times (context): back to back on one buffer set (`ms`: mean;
+                  `median_ms`, `min_ms`: per launch, from an event between launches) and rotating
                   over more than 1 GiB of buffer sets (`cold_ms`, large layers only)
 """
 import argparse
@@ -196,6 +197,20 @@ def main():
         e1.record(stream)
         stream.synchronize()
         l["ms"] = e0.elapsed_time(e1) / reps
+    # ---- per launch: an event between consecutive launches (20 of them, 200 for layers under
+    # 0.1 ms); median and minimum of the intervals
+    for l in layers:
+        n = 200 if l["ms"] < 0.1 else 20
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        launch(l)
+        for i in range(n):
+            evs[i].record(stream)
+            launch(l)
+        evs[n].record(stream)
+        stream.synchronize()
+        times = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(n))
+        l["median_ms"], l["min_ms"] = times[n // 2], times[0]
+
     # ---- the same per-layer time with cold caches: the launches rotate over enough distinct
     # input/output buffers (over 1 GiB together) that no launch finds its tensors in the 256 MB
     # last-level cache; only for layers large enough to get there with at most 16 buffer sets
@@ -337,6 +352,7 @@ def main():
         "packed_filters": packed_leg,
         "layers": [{"name": l["name"], "variant": l["variant"], "ms": round(l["ms"], 4),
                     "tflops": round(l["flops"] / (l["ms"] * 1e-3) / 1e12, 2),
+                    "median_ms": round(l["median_ms"], 4), "min_ms": round(l["min_ms"], 4),
                     "alg_gbs": round(l["bytes"] / (l["ms"] * 1e-3) / 1e9, 1),
                     "cold_ms": None if l["cold_ms"] is None else round(l["cold_ms"], 4),
                     "cold_alg_gbs": None if l["cold_ms"] is None else
