@@ -802,3 +802,62 @@ def test_calls_can_be_captured_in_a_hip_graph(torch_cuda, oracle):
         torch.cuda.synchronize()
         for j, e in zip(jobs, eager):
             assert torch.equal(j[3], e)
+
+
+def test_pooled_and_packed_calls_in_a_hip_graph(torch_cuda, oracle):
+    """The pooled entry point (pooling epilogue of a persistent blocked tile, and the two-kernel
+    path behind a gather tile) and the packed-filter entry point captured into a HIP graph:
+    every replay reproduces the eager result."""
+    torch = torch_cuda
+    dev = torch.device("cuda:0")
+    bias_np = np.linspace(-1, 1, 64).astype(np.float32)
+    bias = torch.from_numpy(bias_np).to(dev)
+    # persistent blocked patch tile (bf16, 1440 tiles), pooled in the epilogue
+    pa = B.make_params(32, 70, 70, 64, 64, 3, 3, in_dtype=B.BF16, out_dtype=B.F32)
+    xa, fa = wl.make_case((32, 70, 70, 64), (3, 3, 64, 64), "ints", 9950)
+    # strided 3x3: a gather tile, pooled by the second kernel
+    pb = B.make_params(4, 30, 30, 32, 64, 3, 3, 2, 2)
+    xb, fb = wl.make_case((4, 30, 30, 32), (3, 3, 32, 64), "uniform", 9951)
+    # packed filter on the direct-sum pick
+    pc = B.make_params(8, 28, 28, 64, 64, 1, 1)
+    xc, fc = wl.make_case((8, 28, 28, 64), (1, 1, 64, 64), "uniform", 9952)
+    xa_d = torch.from_numpy(xa).to(dev).bfloat16()
+    fa_d = torch.from_numpy(fa).to(dev).bfloat16()
+    xb_d, fb_d = torch.from_numpy(xb).to(dev), torch.from_numpy(fb).to(dev)
+    xc_d, fc_d = torch.from_numpy(xc).to(dev), torch.from_numpy(fc).to(dev)
+    vc = B.conv2d_select_variant(pc, B.SELECT_DIRECT_SUM_ONLY)
+    packed = B.conv2d_pack_filter(pc, vc, fc_d)
+    wsa = torch.empty(max(B.conv2d_pool_workspace_size(pa), 16), dtype=torch.uint8, device=dev)
+    wsb = torch.empty(max(B.conv2d_pool_workspace_size(pb), 16), dtype=torch.uint8, device=dev)
+    wsc = torch.empty(max(B.conv2d_workspace_size(pc, vc), 16), dtype=torch.uint8, device=dev)
+    oa = torch.empty((32, 35, 35, 64), dtype=torch.float32, device=dev)
+    ob = torch.empty((4, 7, 7, 64), dtype=torch.float32, device=dev)
+    oc = torch.empty((8, 28, 28, 64), dtype=torch.float32, device=dev)
+    outs = [oa, ob, oc]
+
+    def run_all():
+        B.conv2d_forward_bias_act_pool(pa, xa_d, fa_d, bias, B.ACT_RELU, out=oa, workspace=wsa)
+        B.conv2d_forward_bias_act_pool(pb, xb_d, fb_d, bias, B.ACT_RELU, out=ob, workspace=wsb)
+        B.conv2d_forward_packed(pc, vc, xc_d, packed, bias, B.ACT_RELU, out=oc, workspace=wsc)
+
+    run_all()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    want_a = oracle.forward_bias_act_pool_f32(xa, fa, bias_np, True, 1, wl.PAD_SAME)
+    assert np.array_equal(eager[0].cpu().numpy(), want_a)      # integer inputs: exact
+    want_b = oracle.forward_bias_act_pool_f32(xb, fb, bias_np, True, 2, wl.PAD_SAME)
+    assert rel_err(eager[1].cpu().numpy(), want_b) <= 2 * TOL_F32
+    want_c = oracle.forward_bias_act_f32(xc, fc, bias_np, True, 1, wl.PAD_SAME)
+    assert rel_err(eager[2].cpu().numpy(), want_c) <= 2 * TOL_F32
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run_all()
+    for _ in range(3):
+        for o in outs:
+            o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, e in zip(outs, eager):
+            assert torch.equal(o, e)
