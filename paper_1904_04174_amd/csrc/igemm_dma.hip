@@ -706,9 +706,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
             for (int q = 0; q < 4; ++q) {
               const int op = 2 * th + (q >> 1), oq = 2 * tw + (q & 1);
               if (op < p.wino_p && oq < p.wino_q)
-                static_cast<float*>(p.out)[((static_cast<size_t>(n) * p.wino_p + op) * p.wino_q +
-                                            oq) * p.K + col] =
-                    finish(pixel[q][i][j][v], bcol, p.relu);
+                store_out(static_cast<float*>(p.out) +
+                              ((static_cast<size_t>(n) * p.wino_p + op) * p.wino_q + oq) * p.K + col,
+                          finish(pixel[q][i][j][v], bcol, p.relu));
             }
           }
         }
