@@ -8,8 +8,10 @@ metric is conv2d forward TFLOP/s with the direct-convolution flop count
 2*N*P*Q*K*R*S*C (padded taps count as work).
 
 Prints ONE JSON line.  Besides the contract's fields it carries
-  roofline     -- the kernel with the largest share of the step, its flop rate
-                  from HIP events on the launch stream against the fp32 MFMA peak
+  roofline     -- the layer with the largest share of the step, from HIP events on the launch
+                  stream: its flop rate against the MFMA peak of the element type, or, for a
+                  layer whose flop per algorithmic byte lies under the ridge, its algorithmic
+                  bytes per second against the HBM peak
   cpu_baseline -- the CPU oracle timed on a bounded sample of the same workload
   layers       -- per-layer times (context): back to back on one buffer set (`ms`: mean;
                   `median_ms`, `min_ms`: per launch, from an event between launches) and rotating
@@ -243,7 +245,15 @@ def main():
     dom = max(layers, key=lambda l: l["ms"])
     peak = PEAK_TFLOPS[args.dtype]
     achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
+    # the layer is bound by the matrix cores unless its flop per algorithmic byte lies under the
+    # ridge of the two peaks (fp32: 19.7 flop/B, bf16: 315): then by HBM
+    ridge = peak * 1e12 / (PEAK_HBM_GBS * 1e9)
+    hbm_bound = dom["flops"] / dom["bytes"] < ridge
+    if hbm_bound:
+        achieved = dom["bytes"] / (dom["ms"] * 1e-3) / 1e9
+        peak = PEAK_HBM_GBS
+    roofline = {"bound": "hbm" if hbm_bound else "mfma", "achieved": round(achieved, 3),
+                "peak": peak, "unit": "GB/s" if hbm_bound else "TFLOP/s",
                 "frac": round(achieved / peak, 4),
                 "traffic": (round(MEASURED_TRAFFIC_MB[(args.dtype, dom["name"], dom["variant"])] * 1e6)
                             if (args.dtype, dom["name"], dom["variant"]) in MEASURED_TRAFFIC_MB
@@ -346,7 +356,7 @@ def main():
                                 "3x3 bottleneck layers, stride 1 and 2), SAME, N=%d; NHWC/HWCF, " % args.batch +
                                 "uniform[-1,1]",
                     "batch": args.batch, "layers": names, "algorithms": args.algorithms}),
-        "frac_of_mfma_peak": round(value / peak, 4),
+        "frac_of_mfma_peak": round(value / PEAK_TFLOPS[args.dtype], 4),
         "roofline": roofline,
         "all_algorithms": with_transforms,
         "packed_filters": packed_leg,
