@@ -186,6 +186,7 @@ __device__ __forceinline__ void store_out(V* ptr, V value) {
   __builtin_nontemporal_store(value, ptr);
 }
 
+
 // Bt[k' / bk][n][k' % bk] = filt[k][n], 0 for Kg <= k' < Kg_p: one slice of bk
 // consecutive k' for all features is contiguous, so a B tile of a slice is
 // one contiguous block and its loads fetch whole cache lines.  With
@@ -1570,8 +1571,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
               uintx2 packed;
               packed.x = to_bf16_bits(r[0]) | (static_cast<unsigned>(to_bf16_bits(r[1])) << 16);
               packed.y = to_bf16_bits(r[2]) | (static_cast<unsigned>(to_bf16_bits(r[3])) << 16);
-              store_out(reinterpret_cast<uintx2*>(static_cast<unsigned short*>(p.out) + idx),
-                        packed);
+              // (32 bytes per pixel and instruction: as non-temporal stores such pieces cost more
+              // write traffic than they save in L2: 72.5 us against 60.2 us on a 112x112x128
+              // layer at batch 16; ordinary stores, which L2 merges)
+              *reinterpret_cast<uintx2*>(static_cast<unsigned short*>(p.out) + idx) = packed;
             } else {
               floatx4 quad = {r[0], r[1], r[2], r[3]};
               store_out(reinterpret_cast<floatx4*>(static_cast<float*>(p.out) + idx), quad);
