@@ -1520,7 +1520,47 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
     // write traffic.  Lanes px and px ^ 8 swap one of their two quads (a rotate by 8 inside
     // the row of 16 lanes); then the first store covers the pixels with px & 8 == 0, the second
     // the others.
-    if (!OUT_BF16 && TN % 2 == 0 && (p.K & 31) == 0) {
+    constexpr int kStageRow = T::WN * 2 + 16;  // bytes of a staged pixel: its features + a pad
+    if (OUT_BF16 && T::WN == 64 && (p.K & 7) == 0 &&
+        T::NW * T::WM * kStageRow <= T::LDS_BYTES) {
+      // bf16 output: a lane's 8-byte pieces (four features of a pixel) are gathered through LDS
+      // into whole 128-byte lines (64 features of a pixel), 8 pixels per store instruction.  The
+      // ring is free: every wave has its last fragments in registers (the reads issued during
+      // the last slice are the dummy ones past the end), once the loads that every wave issued
+      // past the end have landed (they write all over the ring).  Each wave stages its own rows.
+      typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      unsigned char* stage = ring + wave * (T::WM * kStageRow);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          float r[4];
+#pragma unroll
+          for (int v = 0; v < 4; ++v) r[v] = finish(acc[i][j][v], bias4[j][v], p.relu);
+          uintx2 packed;
+          packed.x = to_bf16_bits(r[0]) | (static_cast<unsigned>(to_bf16_bits(r[1])) << 16);
+          packed.y = to_bf16_bits(r[2]) | (static_cast<unsigned>(to_bf16_bits(r[3])) << 16);
+          *reinterpret_cast<uintx2*>(stage + (i * BLK + lr) * kStageRow + (j * BLK + lk * 4) * 2) =
+              packed;
+        }
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave's staged rows are written
+      asm volatile("" ::: "memory");
+      const int chunk = lane & 7;           // 16 bytes = 8 features
+      const int col = n0 + wn * T::WN + chunk * 8;
+#pragma unroll
+      for (int t = 0; t < T::WM / 8; ++t) {
+        const int pw = t * 8 + (lane >> 3);  // pixel of the wave's rows
+        const uintx4 line = *reinterpret_cast<const uintx4*>(stage + pw * kStageRow + chunk * 16);
+        const int row = out_row(pw / BLK, pw % BLK);
+        if (row >= 0 && col + 7 < p.K)
+          store_out(reinterpret_cast<uintx4*>(static_cast<unsigned short*>(p.out) +
+                                              static_cast<size_t>(row) * p.K + col),
+                    line);
+      }
+    } else if (!OUT_BF16 && TN % 2 == 0 && (p.K & 31) == 0) {
       const bool hi = (lr & 8) != 0;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
@@ -1572,8 +1612,8 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
               packed.x = to_bf16_bits(r[0]) | (static_cast<unsigned>(to_bf16_bits(r[1])) << 16);
               packed.y = to_bf16_bits(r[2]) | (static_cast<unsigned>(to_bf16_bits(r[3])) << 16);
               // (32 bytes per pixel and instruction: as non-temporal stores such pieces cost more
-              // write traffic than they save in L2: 72.5 us against 60.2 us on a 112x112x128
-              // layer at batch 16; ordinary stores, which L2 merges)
+              // write traffic than they save in L2; ordinary stores, which L2 merges.  Only for
+              // shapes that the staged path above does not take.)
               *reinterpret_cast<uintx2*>(static_cast<unsigned short*>(p.out) + idx) = packed;
             } else {
               floatx4 quad = {r[0], r[1], r[2], r[3]};
