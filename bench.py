@@ -264,6 +264,44 @@ def main():
                 "kernel_ms": round(dom["ms"], 4),
                 "algorithmic_gflop_per_launch": round(dom["flops"] / 1e9, 3)}
 
+    def time_packed():
+        """ms per step of the sweep with every layer's filter packed ahead of time for its
+        current variant (the few variants that cannot be packed take the ordinary call), and
+        the number of layers that were packed."""
+        calls = []
+        keep = []
+        for l in layers:
+            try:
+                packed = B.conv2d_pack_filter(l["p"], l["vid"], l["f"])
+            except B.Conv2dError:      # the zero-padded-channel variants
+                packed = None
+            keep.append(packed)
+            ws_ptr = l["ws"].data_ptr() if l["ws_bytes"] else 0
+            if packed is None:
+                calls.append((False, (l["p"], l["x"].data_ptr(), l["f"].data_ptr(),
+                                      l["out"].data_ptr(), ws_ptr, l["ws_bytes"], handle,
+                                      l["vid"])))
+            else:
+                calls.append((True, (l["p"], l["vid"], l["x"].data_ptr(), packed.data_ptr(), 0, 0,
+                                     l["out"].data_ptr(), ws_ptr, l["ws_bytes"], handle)))
+
+        def packed_step():
+            for is_packed, a in calls:
+                rc = B.conv2d_forward_packed_raw(*a) if is_packed else B.conv2d_forward_raw(*a)
+                if rc:
+                    raise B.Conv2dError(rc, "conv2d_forward_packed")
+        torch.cuda.synchronize()
+        for _ in range(args.warmup):
+            packed_step()
+        stream.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            packed_step()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        return (1e3 * (time.perf_counter() - t0) / args.steps,
+                sum(1 for is_packed, _ in calls if is_packed))
+
     # ---- the same sweep with the unrestricted selection (Winograd variants allowed), reported
     # beside the headline value: they execute 2.25x fewer multiply-adds than the metric counts
     with_transforms = None
@@ -295,6 +333,10 @@ def main():
                 "note": "conv2d_forward's own selection; the Winograd variants execute 2.25x "
                         "fewer multiply-adds than the metric counts, so this is not a fraction "
                         "of the MFMA peak"}
+            ms_all_packed, _ = time_packed()
+            with_transforms["packed_filters_value"] = round(
+                total_flops / (ms_all_packed * 1e-3) / 1e12, 3)
+            with_transforms["packed_filters_ms_per_step"] = round(ms_all_packed, 4)
         for l in layers:
             l["vid"], l["variant"] = l["direct_vid"], l["direct_variant"]
 
@@ -304,41 +346,11 @@ def main():
     # the filter inside every call.
     packed_leg = None
     if args.algorithms == "direct" and not args.skip_all_algorithms_leg:
-        calls = []
-        for l in layers:
-            try:
-                packed = B.conv2d_pack_filter(l["p"], l["vid"], l["f"])
-            except B.Conv2dError:      # a variant that transforms the filter another way
-                packed = None
-            l["packed"] = packed
-            ws_ptr = l["ws"].data_ptr() if l["ws_bytes"] else 0
-            if packed is None:
-                calls.append((False, (l["p"], l["x"].data_ptr(), l["f"].data_ptr(),
-                                      l["out"].data_ptr(), ws_ptr, l["ws_bytes"], handle,
-                                      l["vid"])))
-            else:
-                calls.append((True, (l["p"], l["vid"], l["x"].data_ptr(), packed.data_ptr(), 0, 0,
-                                     l["out"].data_ptr(), ws_ptr, l["ws_bytes"], handle)))
-
-        def packed_step():
-            for is_packed, a in calls:
-                rc = B.conv2d_forward_packed_raw(*a) if is_packed else B.conv2d_forward_raw(*a)
-                if rc:
-                    raise B.Conv2dError(rc, "conv2d_forward_packed")
-        torch.cuda.synchronize()
-        for _ in range(args.warmup):
-            packed_step()
-        stream.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            packed_step()
-        stream.synchronize()
-        torch.cuda.synchronize()
-        ms_packed = 1e3 * (time.perf_counter() - t0) / args.steps
+        ms_packed, n_packed = time_packed()
         packed_leg = {
             "value": round(total_flops / (ms_packed * 1e-3) / 1e12, 3), "unit": "TFLOP/s",
             "ms_per_step": round(ms_packed, 4),
-            "layers_packed": sum(1 for is_packed, _ in calls if is_packed),
+            "layers_packed": n_packed,
             "note": "filters packed once outside the timed region (conv2d_pack_filter), "
                     "conv2d_forward_packed inside it; the headline value repacks in every call"}
 

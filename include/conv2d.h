@@ -181,11 +181,13 @@ CONV2D_API int conv2d_forward_bias_act_pool(const conv2d_params* params, const v
  *                              the packed filter; same workspace as
  *                              conv2d_workspace_size_variant gives
  * The packed filter belongs to the variant and the parameters it was packed
- * for (take the id from conv2d_select_variant with
- * CONV2D_SELECT_DIRECT_SUM_ONLY); using it with others gives wrong results,
- * not an error.  The variants that transform the filter per call in another
- * way (winograd2x2_*, padc_*) return UNSUPPORTED from all three; for the
- * direct and the register-staged variants the packed filter is a plain copy.
+ * for (take the id from conv2d_select_variant or conv2d_selected_variant);
+ * using it with others gives wrong results, not an error.  For the Winograd
+ * variants it holds the transformed filter (16 points, 16/9 of the filter's
+ * size, twice: transformed and repacked); for the direct and the
+ * register-staged variants it is a plain copy.  The zero-padded-channel
+ * variants (padc_*), whose input is padded per call as well, return
+ * UNSUPPORTED from all three.
  * Results are bit-identical to conv2d_forward_variant / _bias_act with the
  * same variant.  Pointer alignment rules as for conv2d_forward. */
 CONV2D_API int conv2d_packed_filter_size(const conv2d_params* params, int variant_id,

@@ -513,13 +513,14 @@ size_t workspace_bytes_for(const Variant& v, const Problem& q) {
 
 size_t align256(size_t bytes) { return (bytes + 255) / 256 * 256; }
 
-// Bytes of variant `v`'s packed filter; 0 with *ok = false for the variants that transform the
-// filter per call in another way (Winograd, zero-padded channels).
+// Bytes of variant `v`'s packed filter; 0 with *ok = false for the zero-padded-channel variants
+// (their input is padded per call as well).
 size_t packed_filter_bytes_for(const Variant& v, const Problem& q, bool* ok) {
   *ok = true;
   if (v.family == kDma) return igemm_dma_packed_filter_bytes(q, v.bf16, v.tile);
   if (v.family == kDirect || v.family == kIgemm)  // these read the filter as it is: a copy
     return align256(static_cast<size_t>(q.Kg) * q.K * (q.in_bf16 ? 2 : 4));
+  if (v.family == kWinograd) return winograd_packed_filter_bytes(q, v.tile, v.split == kFused);
   *ok = false;
   return 0;
 }
@@ -581,7 +582,8 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
   }
   q.in = in; q.filt = filt; q.out = out; q.workspace = workspace;
   // (a packed filter of the direct and register-staged variants is a plain copy)
-  if (filt_is_packed && tb.v[id].family == kDma) q.packed_filt = filt;
+  if (filt_is_packed && (tb.v[id].family == kDma || tb.v[id].family == kWinograd))
+    q.packed_filt = filt;
   q.bias = bias;
   q.relu = activation == CONV2D_ACT_RELU;
   q.pool = fused_pool ? 1 : 0;
@@ -741,6 +743,9 @@ int conv2d_pack_filter(const conv2d_params* params, int variant_id, const void* 
   if (v.family == kDma) {
     q.filt = filt;
     e = igemm_dma_pack_filter(q, v.bf16, v.tile, packed, stream);
+  } else if (v.family == kWinograd) {
+    q.filt = filt;
+    e = winograd_pack_filter(q, v.tile, v.split == kFused, packed, stream);
   } else {
     e = hipMemcpyAsync(packed, filt, static_cast<size_t>(q.Kg) * q.K * (q.in_bf16 ? 2 : 4),
                        hipMemcpyDeviceToDevice, stream);

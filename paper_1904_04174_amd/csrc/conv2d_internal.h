@@ -27,8 +27,8 @@ struct Problem {
   void* out;
   void* workspace;
   // The filter already in the repacked form of the direct-to-LDS tile that runs (written by
-  // igemm_dma_pack_filter for the same tile and parameters), or null: the launch repacks
-  // `filt` into the head of the workspace first.  Not for batched launches.
+  // igemm_dma_pack_filter / winograd_pack_filter for the same tile and parameters), or null:
+  // the launch transforms and repacks `filt` into the workspace first.
   const void* packed_filt;
   // Fused epilogue: out = act(sum + bias[k]).  bias: K fp32 values on the
   // device, or null; relu: 0 or 1.
@@ -140,6 +140,10 @@ hipError_t launch_igemm_dma_wino(const Problem& p, int bf16, int tile, hipStream
 bool winograd_supports(const Problem& p, int gemm_tile, bool fused);
 size_t winograd_workspace_bytes(const Problem& p, int gemm_tile, bool fused);
 hipError_t launch_winograd(const Problem& p, int gemm_tile, bool fused, hipStream_t stream);
+// The filter transformed and repacked ahead of time (Problem::packed_filt of a later launch).
+size_t winograd_packed_filter_bytes(const Problem& p, int gemm_tile, bool fused);
+hipError_t winograd_pack_filter(const Problem& p, int gemm_tile, bool fused, void* packed,
+                                hipStream_t stream);
 
 // 2x2 max pooling, stride 2, of the NHWC tensor `in` [N][P][Q][K] (fp32 or bf16)
 // into `out` [N][P/2][Q/2][K] of the same type: the second step of the pooled

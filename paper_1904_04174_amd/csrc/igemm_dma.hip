@@ -865,7 +865,6 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   const int batches = p.batches > 1 ? p.batches : 1;
   if (batches > 1 && splits != 1) return hipErrorInvalidValue;  // batched: whole tiles only
   // 1. filter -> Bt[K][Kg_p] in the workspace (one per batch), unless the caller packed it before
-  if (p.packed_filt && batches > 1) return hipErrorInvalidValue;
   const void* bt = p.packed_filt ? p.packed_filt : p.workspace;
   hipError_t e = hipSuccess;
   if (!p.packed_filt) {
@@ -923,17 +922,20 @@ template <class T>
 hipError_t launch_wino(const Problem& p, hipStream_t stream) {
   if (p.C % T::BK != 0 || p.R != 16 || p.S != 1 || p.out_bf16) return hipErrorInvalidValue;
   const int Kg_p = p.Kg;
-  dim3 rgrid(Kg_p / T::BK, (p.K + 63) / 64, 1);
-  hipLaunchKernelGGL((repack_filter_kernel<float>), rgrid, dim3(256), 0, stream,
-                     static_cast<const float*>(p.filt), static_cast<float*>(p.workspace), p.Kg,
-                     p.K, Kg_p, p.C, p.R * p.S, 0, T::BK, 0LL, 0LL);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  const void* bt = p.packed_filt ? p.packed_filt : p.workspace;
+  hipError_t e = hipSuccess;
+  if (!p.packed_filt) {
+    dim3 rgrid(Kg_p / T::BK, (p.K + 63) / 64, 1);
+    hipLaunchKernelGGL((repack_filter_kernel<float>), rgrid, dim3(256), 0, stream,
+                       static_cast<const float*>(p.filt), static_cast<float*>(p.workspace), p.Kg,
+                       p.K, Kg_p, p.C, p.R * p.S, 0, T::BK, 0LL, 0LL);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   const int tiles = ((p.M + T::BM - 1) / T::BM) * ((p.K + T::BN - 1) / T::BN);
   const TailPlan none = {tiles, 0, 0, 0};
   hipLaunchKernelGGL((igemm_dma_kernel<T, false, true>), dim3(tiles, 1, 1), dim3(T::NT), 0, stream,
-                     p, Kg_p, Kg_p / T::BK, p.C / T::BK, p.workspace,
-                     static_cast<float*>(nullptr), none);
+                     p, Kg_p, Kg_p / T::BK, p.C / T::BK, bt, static_cast<float*>(nullptr), none);
   return hipGetLastError();
 }
 
@@ -1909,7 +1911,7 @@ bool igemm_dma_tile_pools(int bf16, int tile) { return entry(bf16, tile).pools; 
 size_t igemm_dma_packed_filter_bytes(const Problem& p, int bf16, int tile) {
   const TileEntry& t = entry(bf16, tile);
   const size_t kg_p = static_cast<size_t>((p.Kg + t.bk - 1) / t.bk) * t.bk;
-  return (kg_p * p.K * (bf16 ? 2 : 4) + 255) / 256 * 256;
+  return (kg_p * p.K * (bf16 ? 2 : 4) + 255) / 256 * 256 * (p.batches > 1 ? p.batches : 1);
 }
 hipError_t igemm_dma_pack_filter(const Problem& p, int bf16, int tile, void* packed,
                                  hipStream_t stream) {
@@ -1917,16 +1919,20 @@ hipError_t igemm_dma_pack_filter(const Problem& p, int bf16, int tile, void* pac
   const int Kg_p = (p.Kg + t.bk - 1) / t.bk * t.bk;
   // uniform and patch tiles walk the reduction channel block by channel block
   const int block = (t.addr == kUniform || t.addr == 3) ? t.bk : 0;
-  dim3 rgrid(Kg_p / t.bk, (p.K + 63) / 64, 1);
+  // (a batched problem: one packed filter per batch, one after the other)
+  const int batches = p.batches > 1 ? p.batches : 1;
+  const long long bt_stride = static_cast<long long>(
+      igemm_dma_packed_filter_bytes(p, bf16, tile) / batches / (bf16 ? 2 : 4));
+  dim3 rgrid(Kg_p / t.bk, (p.K + 63) / 64, batches);
   if (bf16)
     hipLaunchKernelGGL((repack_filter_kernel<unsigned short>), rgrid, dim3(256), 0, stream,
                        static_cast<const unsigned short*>(p.filt),
                        static_cast<unsigned short*>(packed), p.Kg, p.K, Kg_p, p.C, p.R * p.S,
-                       block, t.bk, 0LL, 0LL);
+                       block, t.bk, p.filt_stride, bt_stride);
   else
     hipLaunchKernelGGL((repack_filter_kernel<float>), rgrid, dim3(256), 0, stream,
                        static_cast<const float*>(p.filt), static_cast<float*>(packed), p.Kg, p.K,
-                       Kg_p, p.C, p.R * p.S, block, t.bk, 0LL, 0LL);
+                       Kg_p, p.C, p.R * p.S, block, t.bk, p.filt_stride, bt_stride);
   return hipGetLastError();
 }
 hipError_t launch_igemm_dma_wino(const Problem& p, int bf16, int tile, hipStream_t stream) {

@@ -255,6 +255,28 @@ size_t winograd_workspace_bytes(const Problem& p, int gemm_tile, bool fused) {
   return pl.u_bytes + pl.v_bytes + pl.m_bytes + igemm_dma_workspace_bytes(pl.gemm, 0, gemm_tile, 1);
 }
 
+// The filter packed ahead of time: the transformed filter U, then U repacked for the products'
+// tile (one per point, or the 16-point-long one of the fused variant).  Only the second part is
+// read by a launch; U is the packing's intermediate.
+size_t winograd_packed_filter_bytes(const Problem& p, int gemm_tile, bool fused) {
+  const Plan pl = make_plan(p, fused);
+  return pl.u_bytes + igemm_dma_packed_filter_bytes(pl.gemm, 0, gemm_tile);
+}
+
+hipError_t winograd_pack_filter(const Problem& p, int gemm_tile, bool fused, void* packed,
+                                hipStream_t stream) {
+  Plan pl = make_plan(p, fused);
+  float* u = static_cast<float*>(packed);
+  const long long fthreads = static_cast<long long>(p.C) * (p.K / 4);
+  hipLaunchKernelGGL(filter_transform_kernel, dim3(static_cast<unsigned>((fthreads + 255) / 256)),
+                     dim3(256), 0, stream, static_cast<const float*>(p.filt), u, p.C, p.K);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  pl.gemm.filt = u;
+  return igemm_dma_pack_filter(pl.gemm, 0, gemm_tile, static_cast<unsigned char*>(packed) + pl.u_bytes,
+                               stream);
+}
+
 hipError_t launch_winograd(const Problem& p, int gemm_tile, bool fused, hipStream_t stream) {
   Plan pl = make_plan(p, fused);
   unsigned char* ws = static_cast<unsigned char*>(p.workspace);
@@ -263,11 +285,17 @@ hipError_t launch_winograd(const Problem& p, int gemm_tile, bool fused, hipStrea
   float* mt = reinterpret_cast<float*>(ws + pl.u_bytes + pl.v_bytes);
   void* gemm_ws = ws + pl.u_bytes + pl.v_bytes + pl.m_bytes;
 
-  const long long fthreads = static_cast<long long>(p.C) * (p.K / 4);
-  hipLaunchKernelGGL(filter_transform_kernel, dim3(static_cast<unsigned>((fthreads + 255) / 256)),
-                     dim3(256), 0, stream, static_cast<const float*>(p.filt), u, p.C, p.K);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  hipError_t e = hipSuccess;
+  if (p.packed_filt) {
+    pl.gemm.packed_filt = static_cast<const unsigned char*>(p.packed_filt) + pl.u_bytes;
+  } else {
+    const long long fthreads = static_cast<long long>(p.C) * (p.K / 4);
+    hipLaunchKernelGGL(filter_transform_kernel,
+                       dim3(static_cast<unsigned>((fthreads + 255) / 256)), dim3(256), 0, stream,
+                       static_cast<const float*>(p.filt), u, p.C, p.K);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
 
   const long long ithreads = pl.tiles * (p.C / 4);
   hipLaunchKernelGGL(input_transform_kernel, dim3(static_cast<unsigned>((ithreads + 255) / 256)),

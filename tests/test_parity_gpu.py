@@ -692,7 +692,7 @@ def test_packed_filter_gives_the_same_bits(torch_cuda, oracle, case, in_dtype):
     ran = 0
     for v in supported_variants(p):
         name = B.conv2d_variant_name(v)
-        if name.startswith(("winograd2x2_", "padc_")):
+        if name.startswith("padc_"):
             with pytest.raises(B.Conv2dError):
                 B.conv2d_packed_filter_size(p, v)
             continue
