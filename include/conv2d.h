@@ -153,7 +153,8 @@ CONV2D_API int conv2d_forward_bias_act(const conv2d_params* params, const void* 
  * the unpooled tensor is written and nothing of it is read back).
  * Variants whose tiles are even-sized blocks of output pixels of one image
  * (the blocked patch tiles: 3x3 window, stride 1) take the maximum of the
- * four sums in registers and write only the pooled tensor.  Every other
+ * four sums in registers and write only the pooled tensor; so do the Winograd
+ * variants, whose tiles of 2x2 outputs are exactly the pooling windows.  Every other
  * variant writes the unpooled tensor into the workspace, behind its own
  * scratch, and a second kernel pools it; the result is the same.
  * The maximum is taken with fmaxf: a NaN among the four is dropped unless all

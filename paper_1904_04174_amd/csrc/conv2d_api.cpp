@@ -530,6 +530,9 @@ thread_local hipError_t last_launch_error = hipSuccess;
 
 // 2x2 pooling in the epilogue: whole blocked patch tiles.
 bool pools_in_epilogue(const Variant& v) {
+  // (the four outputs of a Winograd F(2x2, 3x3) tile are one pooling window: the output
+  // transform, or the fused variant's epilogue, takes their maximum)
+  if (v.family == kWinograd) return true;
   return v.family == kDma && v.split == kWhole && igemm_dma_tile_pools(v.bf16, v.tile);
 }
 

@@ -35,7 +35,8 @@ struct Problem {
   const float* bias;
   int relu;
   // Fused 2x2 max pooling (stride 2, trailing odd row / column dropped): only
-  // for tiles with igemm_dma_tile_pools; `out` is then [N][P/2][Q/2][K].
+  // for tiles with igemm_dma_tile_pools and for the Winograd variants (a tile's
+  // four outputs are one window); `out` is then [N][P/2][Q/2][K].
   int pool;
   // Batched launch of the direct-to-LDS gather kernels (used by the Winograd
   // path for its per-point matrix products): `batches` > 1 problems of this

@@ -703,6 +703,18 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
             const int tr = row / p.wino_tw;
             const int th = tr % p.wino_th;
             const int n = tr / p.wino_th;
+            if (p.pool) {
+              // the four outputs of a Winograd tile are one 2x2 pooling window
+              const int P2 = p.wino_p / 2, Q2 = p.wino_q / 2;
+              if (th < P2 && tw < Q2) {
+                const float m = fmaxf(fmaxf(pixel[0][i][j][v], pixel[1][i][j][v]),
+                                      fmaxf(pixel[2][i][j][v], pixel[3][i][j][v]));
+                store_out(static_cast<float*>(p.out) +
+                              ((static_cast<size_t>(n) * P2 + th) * Q2 + tw) * p.K + col,
+                          finish(m, bcol, p.relu));
+              }
+              continue;
+            }
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
               const int op = 2 * th + (q >> 1), oq = 2 * tw + (q & 1);

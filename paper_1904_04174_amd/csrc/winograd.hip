@@ -147,7 +147,7 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
                                                                int P, int Q, int K, int TH,
                                                                int TW,
                                                                const float* __restrict__ bias,
-                                                               int relu) {
+                                                               int relu, int pool) {
   const int kv = K / 4;
   const long long tiles = static_cast<long long>(N) * TH * TW;
   const long long idx = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
@@ -173,6 +173,26 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
   }
   const float4 b = bias ? float4{bias[k], bias[k + 1], bias[k + 2], bias[k + 3]}
                         : float4{0.f, 0.f, 0.f, 0.f};
+  if (pool) {
+    // 2x2 max pooling: the four outputs of a Winograd tile are one pooling window; bias and
+    // activation after the maximum (both monotone); windows past P/2 or Q/2 are dropped
+    if (th >= P / 2 || tw >= Q / 2) return;
+    float4 best;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const float4 y0 = add4(add4(t[i][0], t[i][1]), t[i][2]);
+      const float4 y1 = sub4(sub4(t[i][1], t[i][2]), t[i][3]);
+      const float4 m = float4{fmaxf(y0.x, y1.x), fmaxf(y0.y, y1.y), fmaxf(y0.z, y1.z),
+                              fmaxf(y0.w, y1.w)};
+      best = i == 0 ? m : float4{fmaxf(best.x, m.x), fmaxf(best.y, m.y), fmaxf(best.z, m.z),
+                                 fmaxf(best.w, m.w)};
+    }
+    best = float4{finish(best.x, b.x, relu), finish(best.y, b.y, relu), finish(best.z, b.z, relu),
+                  finish(best.w, b.w, relu)};
+    *reinterpret_cast<float4*>(out + ((static_cast<size_t>(n) * (P / 2) + th) * (Q / 2) + tw) * K +
+                               k) = best;
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int op = 2 * th + i;
@@ -309,6 +329,7 @@ hipError_t launch_winograd(const Problem& p, int gemm_tile, bool fused, hipStrea
   pl.gemm.workspace = gemm_ws;
   if (fused) {
     pl.gemm.out = p.out;
+    pl.gemm.pool = p.pool;
     return launch_igemm_dma_wino(pl.gemm, 0, gemm_tile, stream);
   }
   pl.gemm.out = mt;
@@ -318,7 +339,7 @@ hipError_t launch_winograd(const Problem& p, int gemm_tile, bool fused, hipStrea
   const long long othreads = pl.tiles * (p.K / 4);
   hipLaunchKernelGGL(output_transform_kernel, dim3(static_cast<unsigned>((othreads + 255) / 256)),
                      dim3(256), 0, stream, mt, static_cast<float*>(p.out), p.N, p.P, p.Q, p.K,
-                     pl.TH, pl.TW, p.bias, p.relu);
+                     pl.TH, pl.TW, p.bias, p.relu, p.pool);
   return hipGetLastError();
 }
 
