@@ -53,6 +53,14 @@
 //    A range covers pieces of at most two tiles; each piece is one workgroup
 //    that stores an fp32 partial tile, and tail_reduce_kernel adds the pieces
 //    of a tile in slice order.
+//  * Final outputs are stored non-temporally (store_out); partial tiles and
+//    the batched launches' outputs, which another kernel reads next, are not.
+//  * A filter packed ahead of time (Problem::packed_filt) is the repacked
+//    Bt as a tensor of its own; the launch then skips the repack.
+//
+// The second half of the file is the LDS-resident patch kernel for 3x3,
+// stride-1 layers (consecutive-pixel and blocked tiles, persistent launch of
+// the blocked tiles, 16-row MFMA tiles, pooling epilogue); see there.
 #include <type_traits>
 
 #include "conv2d_internal.h"
