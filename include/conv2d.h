@@ -185,10 +185,10 @@ CONV2D_API int conv2d_forward_bias_act_pool(const conv2d_params* params, const v
  * for (take the id from conv2d_select_variant or conv2d_selected_variant);
  * using it with others gives wrong results, not an error.  For the Winograd
  * variants it holds the transformed filter (16 points, 16/9 of the filter's
- * size, twice: transformed and repacked); for the direct and the
- * register-staged variants it is a plain copy.  The zero-padded-channel
- * variants (padc_*), whose input is padded per call as well, return
- * UNSUPPORTED from all three.
+ * size, twice: transformed and repacked); for the zero-padded-channel
+ * variants (padc_*) the padded and repacked filter (their input is still
+ * padded in every call); for the direct and the register-staged variants it
+ * is a plain copy.
  * Results are bit-identical to conv2d_forward_variant / _bias_act with the
  * same variant.  Pointer alignment rules as for conv2d_forward. */
 CONV2D_API int conv2d_packed_filter_size(const conv2d_params* params, int variant_id,

@@ -513,10 +513,10 @@ size_t workspace_bytes_for(const Variant& v, const Problem& q) {
 
 size_t align256(size_t bytes) { return (bytes + 255) / 256 * 256; }
 
-// Bytes of variant `v`'s packed filter; 0 with *ok = false for the zero-padded-channel variants
-// (their input is padded per call as well).
+// Bytes of variant `v`'s packed filter (every family has one; *ok stays for a family without).
 size_t packed_filter_bytes_for(const Variant& v, const Problem& q, bool* ok) {
   *ok = true;
+  if (v.family == kPadded) return padded_packed_filter_bytes(q, v.tile);
   if (v.family == kDma) return igemm_dma_packed_filter_bytes(q, v.bf16, v.tile);
   if (v.family == kDirect || v.family == kIgemm)  // these read the filter as it is: a copy
     return align256(static_cast<size_t>(q.Kg) * q.K * (q.in_bf16 ? 2 : 4));
@@ -585,7 +585,8 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
   }
   q.in = in; q.filt = filt; q.out = out; q.workspace = workspace;
   // (a packed filter of the direct and register-staged variants is a plain copy)
-  if (filt_is_packed && (tb.v[id].family == kDma || tb.v[id].family == kWinograd))
+  if (filt_is_packed && (tb.v[id].family == kDma || tb.v[id].family == kWinograd ||
+                         tb.v[id].family == kPadded))
     q.packed_filt = filt;
   q.bias = bias;
   q.relu = activation == CONV2D_ACT_RELU;
@@ -749,6 +750,9 @@ int conv2d_pack_filter(const conv2d_params* params, int variant_id, const void* 
   } else if (v.family == kWinograd) {
     q.filt = filt;
     e = winograd_pack_filter(q, v.tile, v.split == kFused, packed, stream);
+  } else if (v.family == kPadded) {
+    q.filt = filt;
+    e = padded_pack_filter(q, v.tile, packed, stream);
   } else {
     e = hipMemcpyAsync(packed, filt, static_cast<size_t>(q.Kg) * q.K * (q.in_bf16 ? 2 : 4),
                        hipMemcpyDeviceToDevice, stream);

@@ -160,5 +160,8 @@ hipError_t launch_max_pool_2x2(const void* in, void* out, int N, int P, int Q, i
 bool padded_supports(const Problem& p, int gemm_tile);
 size_t padded_workspace_bytes(const Problem& p, int gemm_tile);
 hipError_t launch_padded(const Problem& p, int gemm_tile, hipStream_t stream);
+// The filter padded and repacked ahead of time (Problem::packed_filt of a later launch).
+size_t padded_packed_filter_bytes(const Problem& p, int gemm_tile);
+hipError_t padded_pack_filter(const Problem& p, int gemm_tile, void* packed, hipStream_t stream);
 
 }  // namespace conv2d

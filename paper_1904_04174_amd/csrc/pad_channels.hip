@@ -87,6 +87,40 @@ size_t padded_workspace_bytes(const Problem& p, int gemm_tile) {
   return pl.in_bytes + pl.filt_bytes + igemm_dma_workspace_bytes(pl.inner, p.in_bf16, gemm_tile, 1);
 }
 
+namespace {
+
+hipError_t pad_filter(const Problem& p, const Plan& pl, void* filt_p, hipStream_t stream) {
+  const long long felems = static_cast<long long>(p.R) * p.S * pl.Cp * p.K;
+  const dim3 fgrid(static_cast<unsigned>((felems + 255) / 256));
+  if (p.in_bf16)
+    hipLaunchKernelGGL((pad_filter_kernel<unsigned short>), fgrid, dim3(256), 0, stream,
+                       static_cast<const unsigned short*>(p.filt),
+                       static_cast<unsigned short*>(filt_p), p.R * p.S, p.C, pl.Cp, p.K);
+  else
+    hipLaunchKernelGGL((pad_filter_kernel<float>), fgrid, dim3(256), 0, stream,
+                       static_cast<const float*>(p.filt), static_cast<float*>(filt_p), p.R * p.S,
+                       p.C, pl.Cp, p.K);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// The filter packed ahead of time: the zero-padded filter, then that repacked for the tile.
+// Only the second part is read by a launch.
+size_t padded_packed_filter_bytes(const Problem& p, int gemm_tile) {
+  const Plan pl = make_plan(p);
+  return pl.filt_bytes + igemm_dma_packed_filter_bytes(pl.inner, p.in_bf16, gemm_tile);
+}
+
+hipError_t padded_pack_filter(const Problem& p, int gemm_tile, void* packed, hipStream_t stream) {
+  Plan pl = make_plan(p);
+  hipError_t e = pad_filter(p, pl, packed, stream);
+  if (e != hipSuccess) return e;
+  pl.inner.filt = packed;
+  return igemm_dma_pack_filter(pl.inner, p.in_bf16, gemm_tile,
+                               static_cast<unsigned char*>(packed) + pl.filt_bytes, stream);
+}
+
 hipError_t launch_padded(const Problem& p, int gemm_tile, hipStream_t stream) {
   Plan pl = make_plan(p);
   unsigned char* ws = static_cast<unsigned char*>(p.workspace);
@@ -94,25 +128,22 @@ hipError_t launch_padded(const Problem& p, int gemm_tile, hipStream_t stream) {
   void* filt_p = ws + pl.in_bytes;
   const int vec = p.in_bf16 ? 8 : 4;
   const long long vectors = static_cast<long long>(p.N) * p.H * p.W * (pl.Cp / vec);
-  const long long felems = static_cast<long long>(p.R) * p.S * pl.Cp * p.K;
   const dim3 igrid(static_cast<unsigned>((vectors + 255) / 256));
-  const dim3 fgrid(static_cast<unsigned>((felems + 255) / 256));
-  if (p.in_bf16) {
+  if (p.in_bf16)
     hipLaunchKernelGGL((pad_input_kernel<unsigned short, 8>), igrid, dim3(256), 0, stream,
                        static_cast<const unsigned short*>(p.in),
                        static_cast<unsigned short*>(in_p), vectors, p.C);
-    hipLaunchKernelGGL((pad_filter_kernel<unsigned short>), fgrid, dim3(256), 0, stream,
-                       static_cast<const unsigned short*>(p.filt),
-                       static_cast<unsigned short*>(filt_p), p.R * p.S, p.C, pl.Cp, p.K);
-  } else {
+  else
     hipLaunchKernelGGL((pad_input_kernel<float, 4>), igrid, dim3(256), 0, stream,
                        static_cast<const float*>(p.in), static_cast<float*>(in_p), vectors, p.C);
-    hipLaunchKernelGGL((pad_filter_kernel<float>), fgrid, dim3(256), 0, stream,
-                       static_cast<const float*>(p.filt), static_cast<float*>(filt_p), p.R * p.S,
-                       p.C, pl.Cp, p.K);
-  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (p.packed_filt) {
+    pl.inner.packed_filt = static_cast<const unsigned char*>(p.packed_filt) + pl.filt_bytes;
+  } else {
+    e = pad_filter(p, pl, filt_p, stream);
+    if (e != hipSuccess) return e;
+  }
   pl.inner.in = in_p;
   pl.inner.filt = filt_p;
   pl.inner.workspace = ws + pl.in_bytes + pl.filt_bytes;

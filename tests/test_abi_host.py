@@ -335,12 +335,6 @@ def test_packed_filter_sizes_and_argument_checks():
             continue
         n = ctypes.c_size_t(0)
         rc = l.conv2d_packed_filter_size(ctypes.byref(p), v, ctypes.byref(n))
-        if name.startswith("padc_"):
-            assert rc == B.STATUS_UNSUPPORTED, name
-            assert l.conv2d_pack_filter(ctypes.byref(p), v, 16, 16, 1 << 30, 0) == B.STATUS_UNSUPPORTED
-            assert l.conv2d_forward_packed(ctypes.byref(p), v, 16, 16, 0, 0, 16, 0, 0, 0) == \
-                B.STATUS_UNSUPPORTED
-            continue
         assert rc == 0, name
         if name.startswith("igemm_dma_f32_") and "_r64_" in name:
             # slices of 16 fp32 values: 360 -> 368 rows of 24 features

@@ -692,10 +692,6 @@ def test_packed_filter_gives_the_same_bits(torch_cuda, oracle, case, in_dtype):
     ran = 0
     for v in supported_variants(p):
         name = B.conv2d_variant_name(v)
-        if name.startswith("padc_"):
-            with pytest.raises(B.Conv2dError):
-                B.conv2d_packed_filter_size(p, v)
-            continue
         _say("packed %s %s" % (case, name))
         packed = B.conv2d_pack_filter(p, v, fd)
         plain = B.conv2d_forward(p, xd, fd, variant_id=v)
