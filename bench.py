@@ -266,28 +266,19 @@ def main():
 
     def time_packed():
         """ms per step of the sweep with every layer's filter packed ahead of time for its
-        current variant (the few variants that cannot be packed take the ordinary call), and
-        the number of layers that were packed."""
+        current variant, and the ms per call of each layer."""
         calls = []
         keep = []
         for l in layers:
-            try:
-                packed = B.conv2d_pack_filter(l["p"], l["vid"], l["f"])
-            except B.Conv2dError:      # the zero-padded-channel variants
-                packed = None
+            packed = B.conv2d_pack_filter(l["p"], l["vid"], l["f"])
             keep.append(packed)
             ws_ptr = l["ws"].data_ptr() if l["ws_bytes"] else 0
-            if packed is None:
-                calls.append((False, (l["p"], l["x"].data_ptr(), l["f"].data_ptr(),
-                                      l["out"].data_ptr(), ws_ptr, l["ws_bytes"], handle,
-                                      l["vid"])))
-            else:
-                calls.append((True, (l["p"], l["vid"], l["x"].data_ptr(), packed.data_ptr(), 0, 0,
-                                     l["out"].data_ptr(), ws_ptr, l["ws_bytes"], handle)))
+            calls.append((l["p"], l["vid"], l["x"].data_ptr(), packed.data_ptr(), 0, 0,
+                          l["out"].data_ptr(), ws_ptr, l["ws_bytes"], handle))
 
         def packed_step():
-            for is_packed, a in calls:
-                rc = B.conv2d_forward_packed_raw(*a) if is_packed else B.conv2d_forward_raw(*a)
+            for a in calls:
+                rc = B.conv2d_forward_packed_raw(*a)
                 if rc:
                     raise B.Conv2dError(rc, "conv2d_forward_packed")
         torch.cuda.synchronize()
@@ -299,8 +290,20 @@ def main():
             packed_step()
         stream.synchronize()
         torch.cuda.synchronize()
-        return (1e3 * (time.perf_counter() - t0) / args.steps,
-                sum(1 for is_packed, _ in calls if is_packed))
+        ms_sweep = 1e3 * (time.perf_counter() - t0) / args.steps
+        # per layer, from HIP events on the launch stream (as for the ordinary calls)
+        per_layer = []
+        for a in calls:
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            B.conv2d_forward_packed_raw(*a)
+            e0.record(stream)
+            for _ in range(reps):
+                B.conv2d_forward_packed_raw(*a)
+            e1.record(stream)
+            stream.synchronize()
+            per_layer.append(e0.elapsed_time(e1) / reps)
+        return ms_sweep, per_layer
 
     # ---- the same sweep with the unrestricted selection (Winograd variants allowed), reported
     # beside the headline value: they execute 2.25x fewer multiply-adds than the metric counts
@@ -346,11 +349,15 @@ def main():
     # the filter inside every call.
     packed_leg = None
     if args.algorithms == "direct" and not args.skip_all_algorithms_leg:
-        ms_packed, n_packed = time_packed()
+        ms_packed, ms_layers = time_packed()
         packed_leg = {
             "value": round(total_flops / (ms_packed * 1e-3) / 1e12, 3), "unit": "TFLOP/s",
             "ms_per_step": round(ms_packed, 4),
-            "layers_packed": n_packed,
+            "layers": [{"name": l["name"], "ms": round(ms, 4),
+                        "tflops": round(l["flops"] / (ms * 1e-3) / 1e12, 2),
+                        "frac_of_mfma_peak": round(l["flops"] / (ms * 1e-3) / 1e12 /
+                                                   PEAK_TFLOPS[args.dtype], 4)}
+                       for l, ms in zip(layers, ms_layers)],
             "note": "filters packed once outside the timed region (conv2d_pack_filter), "
                     "conv2d_forward_packed inside it; the headline value repacks in every call"}
 
