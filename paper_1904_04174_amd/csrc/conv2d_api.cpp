@@ -20,7 +20,7 @@ namespace {
 
 constexpr long long kMaxElems = (1LL << 31) - 1;
 
-enum Family { kDirect = 0, kIgemm = 1, kDma = 2, kWinograd = 3, kPadded = 4 };
+enum Family { kDirect = 0, kIgemm = 1, kDma = 2, kWinograd = 3, kPadded = 4, kRowGather = 5 };
 enum Split { kWhole = 0, kSplit = 1, kTail = 2, kFused = 3 };
 
 struct Variant {
@@ -34,7 +34,8 @@ struct Variant {
 // Variant table: id 0 is the direct kernel (supports everything), then the
 // register-staged implicit-GEMM tiles (fp32, then bf16), each followed by its
 // split-reduction twin where the tile is small enough for that to make sense,
-// then the direct-to-LDS tiles, then the Winograd variants.
+// then the direct-to-LDS tiles, then the Winograd variants, then the window-row gather kernel
+// for very few channels.
 struct Table {
   Variant v[256];
   int n;
@@ -83,6 +84,7 @@ struct Table {
         v[n - 1].split = kFused;
       }
     }
+    add(kRowGather, 0, 0, kWhole, "rowgather_f32_128x64");
   }
 };
 const Table& table() {
@@ -165,6 +167,7 @@ int occupancy(const Variant& v) {
 
 // Element-wise tiles: any C and K, pointers only 4-byte aligned.
 bool is_scalar(const Variant& v) {
+  if (v.family == kRowGather) return true;
   if (v.family == kIgemm) return igemm_tile_is_scalar(v.bf16, v.tile);
   return v.family == kDma && igemm_dma_tile_addressing(v.bf16, v.tile) == 2;
 }
@@ -177,6 +180,7 @@ bool supports(const Variant& v, const Problem& q) {
   // buffer addressing needs input and filter below 2^31 bytes
   if (1LL * es * q.N * q.H * q.W * q.C >= (1LL << 31)) return false;
   if (v.family == kWinograd) return winograd_supports(q, v.tile, v.split == kFused);
+  if (v.family == kRowGather) return row_gather_supports(q);
   if (v.family == kPadded) {
     if (v.bf16 != q.in_bf16 || (!q.in_bf16 && q.out_bf16)) return false;
     return padded_supports(q, v.tile);
@@ -323,6 +327,7 @@ double winograd_cost(const Variant& v, const Problem& q) {
 
 double model_cost(const Variant& v, const Problem& q) {
   if (v.family == kWinograd) return winograd_cost(v, q);
+  if (v.family == kRowGather) return row_gather_cost(q);
   if (v.family == kPadded) {
     // the gather tile on the padded problem, the padding passes' traffic, two more launches
     const int vec = q.in_bf16 ? 8 : 4;
@@ -495,6 +500,7 @@ int select_uncached(const Problem& q, int padding, bool aligned, int mode) {
     if (!usable(v, q, aligned)) continue;
     if (direct_sum_only && v.family == kWinograd) continue;
     // element-wise tiles only where the vector tiles cannot run
+    if (v.family == kRowGather && q.C % vec == 0) continue;
     if (is_scalar(v) && aligned && q.C % vec == 0 && q.K % vec == 0) continue;
     const double c = model_cost(v, q);
     if (best == 0 || c < best_cost) { best = i; best_cost = c; }
@@ -518,7 +524,7 @@ size_t packed_filter_bytes_for(const Variant& v, const Problem& q, bool* ok) {
   *ok = true;
   if (v.family == kPadded) return padded_packed_filter_bytes(q, v.tile);
   if (v.family == kDma) return igemm_dma_packed_filter_bytes(q, v.bf16, v.tile);
-  if (v.family == kDirect || v.family == kIgemm)  // these read the filter as it is: a copy
+  if (v.family == kDirect || v.family == kIgemm || v.family == kRowGather)  // these read the filter as it is: a copy
     return align256(static_cast<size_t>(q.Kg) * q.K * (q.in_bf16 ? 2 : 4));
   if (v.family == kWinograd) return winograd_packed_filter_bytes(q, v.tile, v.split == kFused);
   *ok = false;
@@ -611,6 +617,7 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
       e = launch_igemm_dma(q, tb.v[id].bf16, tb.v[id].tile, split_factor(tb.v[id], q), stream);
       break;
     case kPadded: e = launch_padded(q, tb.v[id].tile, stream); break;
+    case kRowGather: e = launch_row_gather(q, stream); break;
     case kWinograd:
       e = launch_winograd(q, tb.v[id].tile, tb.v[id].split == kFused, stream);
       break;

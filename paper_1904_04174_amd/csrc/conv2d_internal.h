@@ -62,6 +62,12 @@ __device__ __forceinline__ float finish(float v, float bias_value, int relu) {
   return v;
 }
 
+// Window-row gather kernel for fp32 layers of at most 4 channels (row_gather.hip): supported
+// problems, modelled cost in clock cycles, launch.  No workspace; reads the filter as it is.
+bool row_gather_supports(const Problem& p);
+double row_gather_cost(const Problem& p);
+hipError_t launch_row_gather(const Problem& p, hipStream_t stream);
+
 // Launchers (one per kernel family).  Each returns hipSuccess or the launch
 // error; none synchronises.  `tile` selects a compiled tile configuration.
 hipError_t launch_direct(const Problem& p, hipStream_t stream);

@@ -1,0 +1,298 @@
+// Window-row gather kernel for layers with very few input channels (fp32),
+// such as the 7x7 stride-2 first layer of a ResNet on a 3-channel image
+// (Figure 1's caption gives the parameter tuple; section 3 asks for a choice
+// of algorithm per layer).
+//
+// With C <= 4 a 16-byte gather vector covers a pixel and a quarter, so the
+// vector tiles cannot run and the element-wise tiles issue one load per
+// multiply operand.  Here the reduction index k = (r, s, c) is read as
+// (r, j) with j = s * C + c: the S * C values of one window row are
+// consecutive in the NHWC input, and k itself is the row index of the HWCF
+// filter, so nothing is repacked and only a window row of odd length is
+// padded by one value (7x7x3: 154 reduction indices instead of 196 with the
+// channels padded to 4).
+//
+// A workgroup (4 waves) computes an 8 x 16 block of output pixels of one
+// image times 64 features.  It keeps the filter tile in LDS (loaded once:
+// workgroups are persistent and walk the tiles with the grid's stride) and
+// loads the block's input patch, (7 * sr + R) rows of (15 * sc + S) * C
+// consecutive values, zero outside the image (fetched into registers while the
+// previous tile is computed).  Wave w owns block rows 2w and
+// 2w + 1 (32 pixels) and all 64 features: two 32x32x2 fp32 MFMA accumulators.
+// Per step of two reduction indices (both in one window row) a lane reads one
+// patch value (its pixel, value 2 * jj + lane / 32 of the row) and two filter
+// values; fragments are fetched one step ahead.  The patch's row pitch is chosen so that the 32 pixels of a wave
+// fall into distinct LDS banks.
+#include "conv2d_internal.h"
+
+namespace conv2d {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kBH = 8, kBW = 16, kBN = 64, kThreads = 256;
+constexpr int kMaxLds = 64 * 1024;
+constexpr int kFilterLoads = 16; // filter values per thread and pass
+constexpr int kPatchLoads = 12;  // patch values per thread: patches of up to 12 * 256 values
+
+struct RowPlan {
+  int PH, PWE, pitch;   // patch rows, values per row, LDS row pitch (floats)
+  int steps;            // pairs of reduction indices
+  int frows;            // filter rows kept in LDS (2 * steps + 2, zero past Kg)
+  int tiles_x, tiles_y, tiles_n;
+  int tiles_m;          // N * tiles_y * tiles_x
+  long long tiles;
+  int lds_bytes;
+  int grid;
+};
+
+RowPlan make_plan(const Problem& p) {
+  RowPlan pl;
+  pl.PH = (kBH - 1) * p.sr + p.R;
+  pl.PWE = ((kBW - 1) * p.sc + p.S) * p.C;
+  // a wave's second block row lies sr * pitch floats after the first: half a turn of the 64
+  // banks apart when the pixels of a row are an even number of floats apart (else any pitch)
+  pl.pitch = pl.PWE;
+  if ((p.sc * p.C) % 2 == 0)
+    while ((1LL * p.sr * pl.pitch) % 64 != 32 && pl.pitch < pl.PWE + 64) ++pl.pitch;
+  if ((1LL * p.sr * pl.pitch) % 64 != 32) pl.pitch = pl.PWE | 1;
+  pl.steps = p.R * ((p.S * p.C + 1) / 2);  // window rows padded to an even length
+  pl.frows = 2 * pl.steps + 2;
+  pl.tiles_x = (p.Q + kBW - 1) / kBW;
+  pl.tiles_y = (p.P + kBH - 1) / kBH;
+  pl.tiles_n = (p.K + kBN - 1) / kBN;
+  pl.tiles_m = p.N * pl.tiles_y * pl.tiles_x;
+  pl.tiles = 1LL * pl.tiles_m * pl.tiles_n;
+  // (+4: the pad value of an odd window row may lie one past the last patch row)
+  const long long lds = 4LL * (1LL * pl.frows * kBN + 1LL * pl.PH * pl.pitch + 4);
+  pl.lds_bytes = lds > (1LL << 30) ? (1 << 30) : static_cast<int>(lds);
+  int occ = pl.lds_bytes > 0 ? (160 * 1024) / pl.lds_bytes : 1;
+  occ = occ < 1 ? 1 : (occ > 3 ? 3 : occ);
+  const long long resident = 256LL * occ;
+  pl.grid = static_cast<int>(pl.tiles < resident ? pl.tiles : resident);
+  return pl;
+}
+
+// LDS position of filter value (k, col) of the tile: the two reduction indices of a step side
+// by side, so that the lanes of both halves of a wave read distinct banks.
+__device__ __forceinline__ int filter_slot(int k, int col) {
+  return (k >> 1) * 128 + (k & 1) * 32 + (col & 31) + (col >> 5) * 64;
+}
+
+// Workgroup barrier that orders LDS accesses only.  (__syncthreads also waits for the wave's
+// global stores: every tile would then wait for its own output stores to be acknowledged.)
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+__global__ __launch_bounds__(kThreads, 2) void row_gather_kernel(const Problem p,
+                                                                 const RowPlan pl) {
+  extern __shared__ __align__(16) float lds[];
+  float* lds_f = lds;
+  float* lds_p = lds + pl.frows * kBN;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int l32 = lane & 31;
+  const int kh = lane >> 5;
+
+  const float* __restrict__ in = static_cast<const float*>(p.in);
+  const float* __restrict__ filt = static_cast<const float*>(p.filt);
+  float* __restrict__ out = static_cast<float*>(p.out);
+
+  const int row_len = p.S * p.C;
+  // the lane's pixel of the block: wave's rows 2w, 2w + 1
+  const int py = 2 * wave + (l32 >> 4), px = l32 & 15;
+  const int a_lane = py * p.sr * pl.pitch + px * p.sc * p.C + kh;
+  const int row_steps = (row_len + 1) / 2;
+  const bool odd_pad = (row_len & 1) && kh == 1;
+  const int b_base = kh * 32 + l32;
+
+  // ---- patch loader role: values tid + i * 256 of the patch (row y, value e of the row); the
+  // same for every tile, so the positions are worked out once.  A tile's values are fetched
+  // into registers while the previous tile is computed and stored to LDS after it.  (All of
+  // this in 32-bit integer arithmetic with as few instructions per tile as possible: they are
+  // issued by the same SIMDs that issue the products.)
+  int ye[kPatchLoads], p_slot[kPatchLoads], g_rel[kPatchLoads];
+#pragma unroll
+  for (int i = 0; i < kPatchLoads; ++i) {
+    const int idx = tid + i * kThreads;
+    const int y = idx / pl.PWE, e = idx - y * pl.PWE;
+    ye[i] = y < pl.PH ? (y << 16 | e) : -1;
+    p_slot[i] = y * pl.pitch + e;
+    g_rel[i] = y * p.W * p.C + e;   // input offset relative to the patch's first value
+  }
+  float pv[kPatchLoads];
+  unsigned pmask = 0;               // bit i: value i lies inside the image
+  // tile t -> feature tile, image, block row and column
+  auto tile_of = [&](unsigned t, int& tn, int& n, int& by, int& bx) {
+    const unsigned tiles_m = static_cast<unsigned>(pl.tiles_m);
+    tn = static_cast<int>(t / tiles_m);
+    const unsigned tm = t - static_cast<unsigned>(tn) * tiles_m;
+    const unsigned per_image = static_cast<unsigned>(pl.tiles_x * pl.tiles_y);
+    n = static_cast<int>(tm / per_image);
+    const unsigned tb = tm - static_cast<unsigned>(n) * per_image;
+    by = static_cast<int>(tb / static_cast<unsigned>(pl.tiles_x));
+    bx = static_cast<int>(tb) - by * pl.tiles_x;
+  };
+  auto fetch_patch = [&](int n, int by, int bx) {
+    // rows from h0, values from column w0 on; zero outside the image
+    const int h0 = by * kBH * p.sr - p.pt;
+    const int w0 = bx * kBW * p.sc - p.pl;
+    const int lo_e = (w0 < 0 ? -w0 : 0) * p.C;
+    const int hi_w = p.W - w0;  // columns of the image from w0 on
+    const int hi_e = hi_w <= 0 ? 0 : (1LL * hi_w * p.C < pl.PWE ? hi_w * p.C : pl.PWE);
+    const int src0 = ((n * p.H + h0) * p.W + w0) * p.C;
+    pmask = 0;
+#pragma unroll
+    for (int i = 0; i < kPatchLoads; ++i) {
+      const int y = ye[i] >> 16, e = ye[i] & 0xffff;
+      const bool ok = ye[i] >= 0 && static_cast<unsigned>(h0 + y) < static_cast<unsigned>(p.H) &&
+                      e >= lo_e && e < hi_e;
+      // (an unconditional load from a safe address, the select when the value is stored to LDS:
+      // loads under a branch would each be waited for, one after the other)
+      pv[i] = in[ok ? src0 + g_rel[i] : 0];
+      pmask |= ok ? 1u << i : 0u;
+    }
+  };
+
+  // ---- filter loader role: column tid % 64 of rows tid / 64 + 4 * i of the padded filter
+  const int f_col = tid & 63;
+  const int row2 = 2 * row_steps;   // padded window row
+
+  int loaded_tn = -1;
+  const unsigned ntiles = static_cast<unsigned>(pl.tiles);
+  int tn = 0, n = 0, by = 0, bx = 0;
+  if (blockIdx.x < ntiles) {
+    tile_of(blockIdx.x, tn, n, by, bx);
+    fetch_patch(n, by, bx);
+  }
+  for (unsigned t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const int n0 = tn * kBN;
+
+    lds_barrier();  // the previous tile's fragment reads are done
+    if (tn != loaded_tn) {
+      // padded row kp = (fr, fj) with rows of row2 values; zero for the pads and past the end.
+      // Sixteen loads in flight per thread: one at a time their latencies would add up to more
+      // than a tile's products.
+      int kp = tid >> 6, fr = 0, fj = kp;
+      if (fj >= row2) { fj -= row2; ++fr; }
+      if (fj >= row2) { fj -= row2; ++fr; }
+      const bool col_ok = n0 + f_col < p.K;
+      for (int base = 0; base < pl.frows; base += 4 * kFilterLoads) {
+        float fv[kFilterLoads];
+        unsigned fmask = 0;
+        int slot[kFilterLoads];
+#pragma unroll
+        for (int u = 0; u < kFilterLoads; ++u) {
+          const bool ok = kp < pl.frows && fr < p.R && fj < row_len && col_ok;
+          fv[u] = filt[ok ? (fr * row_len + fj) * p.K + n0 + f_col : 0];
+          fmask |= ok ? 1u << u : 0u;
+          slot[u] = kp < pl.frows ? filter_slot(kp, f_col) : -1;
+          kp += 4; fj += 4;
+          if (fj >= row2) { fj -= row2; ++fr; }
+          if (fj >= row2) { fj -= row2; ++fr; }
+        }
+#pragma unroll
+        for (int u = 0; u < kFilterLoads; ++u)
+          if (slot[u] >= 0) lds_f[slot[u]] = (fmask >> u & 1) ? fv[u] : 0.f;
+      }
+      loaded_tn = tn;
+    }
+#pragma unroll
+    for (int i = 0; i < kPatchLoads; ++i)
+      if (ye[i] >= 0) lds_p[p_slot[i]] = (pmask >> i & 1) ? pv[i] : 0.f;
+    lds_barrier();
+    float bias0 = bias_of(p.bias, n0 + l32, p.K);
+    float bias1 = bias_of(p.bias, n0 + 32 + l32, p.K);
+    const bool col0_ok = n0 + l32 < p.K, col1_ok = n0 + 32 + l32 < p.K;
+    // this tile's output position; then the next tile's patch, in flight during the products
+    const int op0 = by * kBH + 2 * wave, oq0 = bx * kBW + 4 * kh;
+    float* tile_out = out + ((static_cast<size_t>(n) * p.P + op0) * p.Q + oq0) * p.K + n0 + l32;
+    if (t + gridDim.x < ntiles) {
+      tile_of(t + gridDim.x, tn, n, by, bx);
+      fetch_patch(n, by, bx);
+    }
+
+    floatx16 acc0 = {}, acc1 = {};
+    // Step (r, jj) multiplies values j = 2 * jj + kh of window row r (both halves of the wave in
+    // the same row, so the patch offset of a step is the same for all lanes); with an odd row
+    // length the upper half's last value of a row is a pad: zero filter row, value forced to 0.
+    int r = 0, jj = 0;
+    float a_cur = (odd_pad && row_steps == 1) ? 0.f : lds_p[a_lane];
+    float b0_cur = lds_f[b_base], b1_cur = lds_f[b_base + 64];
+    for (int s = 0; s < pl.steps; ++s) {
+      // fragments of the next step (past the end: zero rows of the filter, the first patch value)
+      if (++jj == row_steps) { jj = 0; ++r; }
+      const int off = s + 1 < pl.steps ? r * pl.pitch + 2 * jj : 0;
+      const bool pad = odd_pad && jj == row_steps - 1;
+      const float a_ld = lds_p[a_lane + off];
+      const float b0_nxt = lds_f[b_base + (s + 1) * 128];
+      const float b1_nxt = lds_f[b_base + (s + 1) * 128 + 64];
+      __builtin_amdgcn_sched_barrier(0);  // the reads above are issued before this step's products
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur, b0_cur, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur, b1_cur, acc1, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);  // and waited for only after them
+      a_cur = pad ? 0.f : a_ld; b0_cur = b0_nxt; b1_cur = b1_nxt;
+    }
+
+    // ---- epilogue: register v of a lane is row 8 * (v / 4) + 4 * kh + v % 4 of the wave's 32
+    // pixels (block row v / 8, column 8 * (v / 4 % 2) + 4 * kh + v % 4), column l32 of the
+    // feature block: a store instruction writes two pixels' 32 consecutive features (whole
+    // 128-byte lines; non-temporal: the output is not read again).  The bias values are made to
+    // arrive before the first store: a wait for them between the stores would also wait for
+    // the stores before it, one after the other.
+    asm volatile("" : "+v"(bias0), "+v"(bias1));
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int dy = v >> 3, dx = 8 * ((v >> 2) & 1) + (v & 3);
+      if (op0 + dy < p.P && oq0 + dx < p.Q) {
+        float* dst = tile_out + (dy * p.Q + dx) * p.K;
+        if (col0_ok) __builtin_nontemporal_store(finish(acc0[v], bias0, p.relu), dst);
+        if (col1_ok) __builtin_nontemporal_store(finish(acc1[v], bias1, p.relu), dst + 32);
+      }
+    }
+  }
+}
+
+}  // namespace
+
+bool row_gather_supports(const Problem& p) {
+  if (p.in_bf16 || p.out_bf16 || p.M == 0) return false;
+  if (p.C > 4) return false;   // wider pixels: the 16-byte gather tiles
+  if (p.R > 16 || p.S > 16 || p.sr > 4 || p.sc > 4) return false;
+  const RowPlan pl = make_plan(p);
+  if (pl.PWE >= (1 << 16) || 1LL * pl.PH * pl.PWE > kPatchLoads * kThreads) return false;
+  if (pl.tiles >= (1LL << 31) || 1LL * p.Kg * p.K >= (1LL << 31)) return false;
+  return pl.lds_bytes <= kMaxLds;
+}
+
+// Modelled cost in clock cycles (for the selector), from measurements on 224x224x3 -> 64
+// layers with 1x1 to 7x7 windows at stride 2: a workgroup alone on its compute unit takes about
+// 390 cycles per step (the fragment reads' latency is exposed), three resident ones about 170
+// each; the fixed part is the output stream or, for a few tiles, about 15000 cycles of launch,
+// filter and patch loads.  Priced 15 % up: chosen only where it wins clearly.
+double row_gather_cost(const Problem& p) {
+  const RowPlan pl = make_plan(p);
+  int occ = (160 * 1024) / pl.lds_bytes;
+  occ = occ < 1 ? 1 : (occ > 3 ? 3 : occ);
+  const double per_unit = static_cast<double>((pl.tiles + 255) / 256);
+  const double resident = per_unit < occ ? per_unit : occ;
+  const double rounds = static_cast<double>((pl.tiles + 256LL * occ - 1) / (256LL * occ));
+  const double step = 170.0 * resident > 390.0 ? 170.0 * resident : 390.0;
+  const double stream = (4.0 * p.N * p.H * p.W * p.C + 4.0 * p.M * p.K) / 2083.3;
+  return 1.15 * (rounds * pl.steps * step + (stream > 15000.0 ? stream : 15000.0));
+}
+
+hipError_t launch_row_gather(const Problem& p, hipStream_t stream) {
+  const RowPlan pl = make_plan(p);
+  if (!row_gather_supports(p) || pl.grid <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(row_gather_kernel, dim3(pl.grid), dim3(kThreads), pl.lds_bytes, stream, p, pl);
+  return hipGetLastError();
+}
+
+}  // namespace conv2d

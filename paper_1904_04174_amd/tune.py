@@ -57,10 +57,11 @@ def candidates(params):
     names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
     def elementwise(n):
         return "scalar" in n or n.endswith("_e") or "_e_" in n
-    # (the zero-padded-channel variants run exactly where the vector tiles cannot: they do not
-    # count as "vector tiles can run")
+    # (the zero-padded-channel variants and the window-row gather kernel run exactly where the
+    # vector tiles cannot: they do not count as "vector tiles can run")
     vec_ok = any(B.conv2d_variant_supports(params, v) for v, n in enumerate(names)
-                 if n != "direct" and not elementwise(n) and not n.startswith("padc_"))
+                 if n != "direct" and not elementwise(n)
+                 and not n.startswith(("padc_", "rowgather_")))
     for v, n in enumerate(names):
         if n == "direct" or not B.conv2d_variant_supports(params, v):
             continue
@@ -88,6 +89,7 @@ FAMILIES = (
     ("direct-to-LDS implicit GEMM", lambda n: n.startswith(("igemm_dma_", "padc_"))),
     ("LDS-resident patch", lambda n: n.startswith("igemm_patch_")),
     ("Winograd F(2x2,3x3)", lambda n: n.startswith("winograd2x2_")),
+    ("window-row gather", lambda n: n.startswith("rowgather_")),
 )
 
 

@@ -358,3 +358,23 @@ def test_packed_filter_sizes_and_argument_checks():
         B.STATUS_INVALID_ARGUMENT
     assert l.conv2d_forward_packed(ctypes.byref(p), 0, 16, 16, 0, 7, 16, 0, 0, 0) == \
         B.STATUS_INVALID_ARGUMENT   # unknown activation
+
+
+def test_window_row_gather_kernel_support_rules():
+    """The kernel for very few channels: fp32 only, at most 4 channels, a patch of at most 3072
+    values and LDS within 64 KiB; no workspace; chosen for the 7x7 stride-2 layer on a 3-channel
+    image at batch 32."""
+    names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
+    vid = names.index("rowgather_f32_128x64")
+    stem = B.make_params(32, 224, 224, 3, 64, 7, 7, 2, 2, wl.PAD_SAME, B.F32, B.F32)
+    assert B.conv2d_variant_supports(stem, vid)
+    assert B.conv2d_workspace_size(stem, vid) == 0
+    assert B.conv2d_variant_name(B.conv2d_selected_variant(stem)) == "rowgather_f32_128x64"
+    for bad in (B.make_params(32, 224, 224, 3, 64, 7, 7, 2, 2, wl.PAD_SAME, B.BF16, B.F32),
+                B.make_params(4, 56, 56, 8, 64, 3, 3, 1, 1, wl.PAD_SAME, B.F32, B.F32),
+                # 11x11 stride 4: the block's patch has 39 x 213 values
+                B.make_params(2, 50, 50, 3, 96, 11, 11, 4, 4, wl.PAD_SAME, B.F32, B.F32)):
+        assert not B.conv2d_variant_supports(bad, vid)
+    # a single channel, a 1x1 window: supported (one padded reduction step)
+    assert B.conv2d_variant_supports(
+        B.make_params(2, 19, 23, 1, 5, 1, 1, 1, 1, wl.PAD_SAME, B.F32, B.F32), vid)

@@ -665,6 +665,49 @@ def test_pool_full_size(torch_cuda, oracle, name, in_dtype, out_dtype):
     assert err <= (TOL_F32 if in_dtype == B.F32 else TOL_BF16), (name, err)
 
 
+# ------------------------------------------------------------------ window-row gather kernel
+
+ROW_GATHER_CASES = [
+    (2, 20, 18, 4, 8, 5, 5, 2, 2, wl.PAD_SAME),
+    (3, 33, 47, 3, 70, 7, 7, 2, 2, wl.PAD_SAME),     # two feature tiles, ragged blocks
+    (2, 19, 23, 1, 5, 1, 1, 1, 1, wl.PAD_SAME),      # a single reduction index (one padded step)
+    (2, 19, 23, 2, 130, 3, 5, 1, 2, wl.PAD_VALID),   # three feature tiles, even window rows
+    (5, 30, 17, 3, 64, 5, 5, 3, 1, wl.PAD_SAME),     # different strides
+    (40, 9, 9, 1, 33, 3, 3, 2, 2, wl.PAD_VALID),     # blocks larger than the image
+    (36, 100, 100, 3, 64, 7, 7, 2, 2, wl.PAD_SAME),  # more tiles than resident workgroups
+]
+
+
+@pytest.mark.parametrize("case", ROW_GATHER_CASES)
+def test_window_row_gather_kernel(torch_cuda, oracle, case):
+    """The kernel for fp32 layers of at most 4 channels against the oracle: random inputs within
+    the tolerance, integer inputs bit-exact, also through the fused bias + ReLU epilogue, the
+    pooled entry point and a filter packed ahead of time (a plain copy for this kernel)."""
+    n, h, w, c, k, r, s, sr, sc, pad = case
+    names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
+    vid = names.index("rowgather_f32_128x64")
+    p = _params(case)
+    assert B.conv2d_variant_supports(p, vid)
+    x, f = wl.make_case((n, h, w, c), (r, s, c, k), "uniform", 31 + sum(case))
+    _say("row gather %s uniform" % (case,))
+    err = rel_err(run_gpu(torch_cuda, p, x, f, vid), oracle.forward_f32(x, f, (sr, sc), pad))
+    assert err <= TOL_F32, (case, err)
+    x, f = wl.make_case((n, h, w, c), (r, s, c, k), "ints", 32 + sum(case))
+    bias = np.random.default_rng(33).integers(-4, 5, size=k).astype(np.float32)
+    _say("row gather %s ints" % (case,))
+    assert np.array_equal(run_gpu(torch_cuda, p, x, f, vid), oracle.forward_f32(x, f, (sr, sc), pad))
+    want = oracle.forward_bias_act_f32(x, f, bias, True, (sr, sc), pad)
+    torch = torch_cuda
+    xd, fd, bd = (torch.from_numpy(a).cuda() for a in (x, f, bias))
+    assert np.array_equal(run_gpu_fused(torch_cuda, p, x, f, bias, B.ACT_RELU, force=vid), want)
+    packed = B.conv2d_pack_filter(p, vid, fd)
+    got = B.conv2d_forward_packed(p, vid, xd, packed, bd, B.ACT_RELU)
+    assert np.array_equal(got.cpu().numpy(), want)
+    want_pool = oracle.forward_bias_act_pool_f32(x, f, bias, True, (sr, sc), pad)
+    got = run_gpu_pooled(torch_cuda, p, x, f, bias, B.ACT_RELU, force=vid)
+    assert np.array_equal(got, want_pool)
+
+
 # ------------------------------------------------------------------ filters packed ahead of time
 
 PACKED_CASES = [SMALL[1], SMALL[3], SMALL[5], SMALL[7], SMALL[13], SMALL[14], SMALL[16]]
