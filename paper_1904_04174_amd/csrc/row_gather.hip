@@ -17,7 +17,7 @@
 // workgroups are persistent and walk the tiles with the grid's stride) and
 // loads the block's input patch, (7 * sr + R) rows of (15 * sc + S) * C
 // consecutive values, zero outside the image (fetched into registers while the
-// previous tile is computed).  Wave w owns block rows 2w and
+// previous tile is computed, stored to LDS before that tile's output stores).  Wave w owns block rows 2w and
 // 2w + 1 (32 pixels) and all 64 features: two 32x32x2 fp32 MFMA accumulators.
 // Per step of two reduction indices (both in one window row) a lane reads one
 // patch value (its pixel, value 2 * jj + lane / 32 of the row) and two filter
@@ -63,8 +63,9 @@ RowPlan make_plan(const Problem& p) {
   pl.tiles_n = (p.K + kBN - 1) / kBN;
   pl.tiles_m = p.N * pl.tiles_y * pl.tiles_x;
   pl.tiles = 1LL * pl.tiles_m * pl.tiles_n;
-  // (+4: the pad value of an odd window row may lie one past the last patch row)
-  const long long lds = 4LL * (1LL * pl.frows * kBN + 1LL * pl.PH * pl.pitch + 4);
+  // (one more patch row: the fragment fetched after the last step lies in the row after the
+  // window; +4: the pad value of an odd window row may lie one past the last value of a row)
+  const long long lds = 4LL * (1LL * pl.frows * kBN + 1LL * (pl.PH + 1) * pl.pitch + 4);
   pl.lds_bytes = lds > (1LL << 30) ? (1 << 30) : static_cast<int>(lds);
   int occ = pl.lds_bytes > 0 ? (160 * 1024) / pl.lds_bytes : 1;
   occ = occ < 1 ? 1 : (occ > 3 ? 3 : occ);
@@ -163,58 +164,68 @@ __global__ __launch_bounds__(kThreads, 2) void row_gather_kernel(const Problem p
   // ---- filter loader role: column tid % 64 of rows tid / 64 + 4 * i of the padded filter
   const int f_col = tid & 63;
   const int row2 = 2 * row_steps;   // padded window row
+  const int row_skip = pl.pitch - row2;  // from the end of a window row to the start of the next
 
-  int loaded_tn = -1;
-  const unsigned ntiles = static_cast<unsigned>(pl.tiles);
-  int tn = 0, n = 0, by = 0, bx = 0;
-  if (blockIdx.x < ntiles) {
-    tile_of(blockIdx.x, tn, n, by, bx);
-    fetch_patch(n, by, bx);
-  }
-  for (unsigned t = blockIdx.x; t < ntiles; t += gridDim.x) {
-    const int n0 = tn * kBN;
-
-    lds_barrier();  // the previous tile's fragment reads are done
-    if (tn != loaded_tn) {
-      // padded row kp = (fr, fj) with rows of row2 values; zero for the pads and past the end.
-      // Sixteen loads in flight per thread: one at a time their latencies would add up to more
-      // than a tile's products.
-      int kp = tid >> 6, fr = 0, fj = kp;
-      if (fj >= row2) { fj -= row2; ++fr; }
-      if (fj >= row2) { fj -= row2; ++fr; }
-      const bool col_ok = n0 + f_col < p.K;
-      for (int base = 0; base < pl.frows; base += 4 * kFilterLoads) {
-        float fv[kFilterLoads];
-        unsigned fmask = 0;
-        int slot[kFilterLoads];
+  auto load_filter = [&](int n0) {
+    // padded row kp = (fr, fj) with rows of row2 values; zero for the pads and past the end.
+    // Sixteen loads in flight per thread: one at a time their latencies would add up to more
+    // than a tile's products.
+    int kp = tid >> 6, fr = 0, fj = kp;
+    if (fj >= row2) { fj -= row2; ++fr; }
+    if (fj >= row2) { fj -= row2; ++fr; }
+    const bool col_ok = n0 + f_col < p.K;
+    for (int base = 0; base < pl.frows; base += 4 * kFilterLoads) {
+      float fv[kFilterLoads];
+      unsigned fmask = 0;
+      int slot[kFilterLoads];
 #pragma unroll
-        for (int u = 0; u < kFilterLoads; ++u) {
-          const bool ok = kp < pl.frows && fr < p.R && fj < row_len && col_ok;
-          fv[u] = filt[ok ? (fr * row_len + fj) * p.K + n0 + f_col : 0];
-          fmask |= ok ? 1u << u : 0u;
-          slot[u] = kp < pl.frows ? filter_slot(kp, f_col) : -1;
-          kp += 4; fj += 4;
-          if (fj >= row2) { fj -= row2; ++fr; }
-          if (fj >= row2) { fj -= row2; ++fr; }
-        }
-#pragma unroll
-        for (int u = 0; u < kFilterLoads; ++u)
-          if (slot[u] >= 0) lds_f[slot[u]] = (fmask >> u & 1) ? fv[u] : 0.f;
+      for (int u = 0; u < kFilterLoads; ++u) {
+        const bool ok = kp < pl.frows && fr < p.R && fj < row_len && col_ok;
+        fv[u] = filt[ok ? (fr * row_len + fj) * p.K + n0 + f_col : 0];
+        fmask |= ok ? 1u << u : 0u;
+        slot[u] = kp < pl.frows ? filter_slot(kp, f_col) : -1;
+        kp += 4; fj += 4;
+        if (fj >= row2) { fj -= row2; ++fr; }
+        if (fj >= row2) { fj -= row2; ++fr; }
       }
-      loaded_tn = tn;
+#pragma unroll
+      for (int u = 0; u < kFilterLoads; ++u)
+        if (slot[u] >= 0) lds_f[slot[u]] = (fmask >> u & 1) ? fv[u] : 0.f;
     }
+  };
+  auto stash_patch = [&]() {
 #pragma unroll
     for (int i = 0; i < kPatchLoads; ++i)
       if (ye[i] >= 0) lds_p[p_slot[i]] = (pmask >> i & 1) ? pv[i] : 0.f;
-    lds_barrier();
-    float bias0 = bias_of(p.bias, n0 + l32, p.K);
-    float bias1 = bias_of(p.bias, n0 + 32 + l32, p.K);
+  };
+
+  // Order of a tile's phases: products; barrier; the NEXT tile's patch from registers to LDS;
+  // this tile's output stores; barrier; loads of the tile after next.  The wait for the patch
+  // loads thus comes a whole tile of products after the previous stores were issued: the one
+  // counter of outstanding memory operations covers stores too, and straight after the stores
+  // it would wait for all of them to be acknowledged.
+  const unsigned ntiles = static_cast<unsigned>(pl.tiles);
+  unsigned t = blockIdx.x;
+  if (t >= ntiles) return;
+  int tn = 0, n = 0, by = 0, bx = 0;
+  tile_of(t, tn, n, by, bx);
+  fetch_patch(n, by, bx);
+  load_filter(tn * kBN);
+  float bias0 = bias_of(p.bias, tn * kBN + l32, p.K);
+  float bias1 = bias_of(p.bias, tn * kBN + 32 + l32, p.K);
+  stash_patch();
+  lds_barrier();
+  for (;;) {
+    const int n0 = tn * kBN;
     const bool col0_ok = n0 + l32 < p.K, col1_ok = n0 + 32 + l32 < p.K;
     // this tile's output position; then the next tile's patch, in flight during the products
     const int op0 = by * kBH + 2 * wave, oq0 = bx * kBW + 4 * kh;
     float* tile_out = out + ((static_cast<size_t>(n) * p.P + op0) * p.Q + oq0) * p.K + n0 + l32;
-    if (t + gridDim.x < ntiles) {
-      tile_of(t + gridDim.x, tn, n, by, bx);
+    const unsigned t_next = t + gridDim.x;
+    const bool has_next = t_next < ntiles;
+    int tn_next = tn;
+    if (has_next) {
+      tile_of(t_next, tn_next, n, by, bx);
       fetch_patch(n, by, bx);
     }
 
@@ -222,13 +233,16 @@ __global__ __launch_bounds__(kThreads, 2) void row_gather_kernel(const Problem p
     // Step (r, jj) multiplies values j = 2 * jj + kh of window row r (both halves of the wave in
     // the same row, so the patch offset of a step is the same for all lanes); with an odd row
     // length the upper half's last value of a row is a pad: zero filter row, value forced to 0.
-    int r = 0, jj = 0;
+    // (The scalar bookkeeping of a step is kept to a few dependent instructions: a wave issues
+    // them one after the other between its products.)
+    int jj = 0, off = 0;
     float a_cur = (odd_pad && row_steps == 1) ? 0.f : lds_p[a_lane];
     float b0_cur = lds_f[b_base], b1_cur = lds_f[b_base + 64];
     for (int s = 0; s < pl.steps; ++s) {
-      // fragments of the next step (past the end: zero rows of the filter, the first patch value)
-      if (++jj == row_steps) { jj = 0; ++r; }
-      const int off = s + 1 < pl.steps ? r * pl.pitch + 2 * jj : 0;
+      // fragments of the next step (past the end: zero rows of the filter and the patch row
+      // after the window, which LDS has room for)
+      ++jj; off += 2;
+      if (jj == row_steps) { jj = 0; off += row_skip; }
       const bool pad = odd_pad && jj == row_steps - 1;
       const float a_ld = lds_p[a_lane + off];
       const float b0_nxt = lds_f[b_base + (s + 1) * 128];
@@ -240,12 +254,18 @@ __global__ __launch_bounds__(kThreads, 2) void row_gather_kernel(const Problem p
       a_cur = pad ? 0.f : a_ld; b0_cur = b0_nxt; b1_cur = b1_nxt;
     }
 
+    lds_barrier();  // every wave has read this tile's patch and filter
+    if (has_next) {
+      if (tn_next != tn) load_filter(tn_next * kBN);
+      stash_patch();
+    }
+
     // ---- epilogue: register v of a lane is row 8 * (v / 4) + 4 * kh + v % 4 of the wave's 32
     // pixels (block row v / 8, column 8 * (v / 4 % 2) + 4 * kh + v % 4), column l32 of the
     // feature block: a store instruction writes two pixels' 32 consecutive features (whole
-    // 128-byte lines; non-temporal: the output is not read again).  The bias values are made to
-    // arrive before the first store: a wait for them between the stores would also wait for
-    // the stores before it, one after the other.
+    // 128-byte lines; non-temporal: the output is not read again).  The bias values are in
+    // registers before the first store (a wait for them between the stores would also wait for
+    // the stores before it, one after the other).
     asm volatile("" : "+v"(bias0), "+v"(bias1));
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -256,6 +276,14 @@ __global__ __launch_bounds__(kThreads, 2) void row_gather_kernel(const Problem p
         if (col1_ok) __builtin_nontemporal_store(finish(acc1[v], bias1, p.relu), dst + 32);
       }
     }
+    if (!has_next) break;
+    if (tn_next != tn) {
+      bias0 = bias_of(p.bias, tn_next * kBN + l32, p.K);
+      bias1 = bias_of(p.bias, tn_next * kBN + 32 + l32, p.K);
+    }
+    lds_barrier();  // the next tile's patch (and filter) are in LDS
+    t = t_next;
+    tn = tn_next;
   }
 }
 
