@@ -23,8 +23,9 @@ __global__ __launch_bounds__(256) void pad_input_kernel(const E* __restrict__ sr
   const long long i = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
   if (i >= vectors) return;
   const int per_pixel = (C + CP - 1) / CP;        // vectors per pixel
-  const long long pixel = i / per_pixel;
-  const int c0 = static_cast<int>(i % per_pixel) * CP;
+  // (one vector per pixel, the usual case of 3 channels: no 64-bit division per thread)
+  const long long pixel = per_pixel == 1 ? i : i / per_pixel;
+  const int c0 = per_pixel == 1 ? 0 : static_cast<int>(i % per_pixel) * CP;
   E v[CP];
 #pragma unroll
   for (int j = 0; j < CP; ++j) v[j] = (c0 + j < C) ? src[pixel * C + c0 + j] : E(0);
