@@ -187,8 +187,8 @@ CONV2D_API int conv2d_forward_bias_act_pool(const conv2d_params* params, const v
  * variants it holds the transformed filter (16 points, 16/9 of the filter's
  * size, twice: transformed and repacked); for the zero-padded-channel
  * variants (padc_*) the padded and repacked filter (their input is still
- * padded in every call); for the direct and the register-staged variants it
- * is a plain copy.
+ * padded in every call); for the direct, the register-staged and the
+ * window-row gather (rowgather_*) variants it is a plain copy.
  * Results are bit-identical to conv2d_forward_variant / _bias_act with the
  * same variant.  Pointer alignment rules as for conv2d_forward. */
 CONV2D_API int conv2d_packed_filter_size(const conv2d_params* params, int variant_id,
