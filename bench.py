@@ -13,6 +13,14 @@ Prints ONE JSON line.  Besides the contract's fields it carries
                   layer whose flop per algorithmic byte lies under the ridge, its algorithmic
                   bytes per second against the HBM peak
   cpu_baseline -- the CPU oracle timed on a bounded sample of the same workload
+  groups       -- every other configuration group (bf16 VGG sweep, VGG at batch 1, ResNet-style
+                  layers at batch 32 in fp32 and bf16, the large-batch layer and its VALID /
+                  stride-2 forms, the tiny case): per layer ms, TFLOP/s and the fraction of the
+                  layer's own bound (the larger of flop / MFMA peak and algorithmic bytes / HBM
+                  peak, over the measured time; cold caches where rotating buffers are feasible)
+  ceilings     -- the reachable rates of this GPU measured in the same process (register-only
+                  MFMA loop, LDS fragment reads, streaming copy); roofline.achievable_peak is
+                  the one that belongs to the roofline's bound
   layers       -- per-layer times (context): back to back on one buffer set (`ms`: mean;
                   `median_ms`, `min_ms`: per launch, from an event between launches) and rotating
                   over more than 1 GiB of buffer sets (`cold_ms`, large layers only)
@@ -67,6 +75,121 @@ def layer_bytes(B, p):
             osz * p.batch * g.out_rows * g.out_cols * p.features)
 
 
+def measure_ceilings():
+    """{name: (value, unit)} from the ceilings helper library (register-only MFMA loops, LDS
+    read loops, streaming copies), or None if it is not built."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_1904_04174_amd", "libconv2d_ceilings.so")
+    if not os.path.exists(path):
+        return None
+
+    class Record(ctypes.Structure):
+        _fields_ = [("name", ctypes.c_char * 64), ("value", ctypes.c_double),
+                    ("unit", ctypes.c_char * 16)]
+    lib = ctypes.CDLL(path)
+    buf = (Record * 64)()
+    n = lib.conv2d_ceilings_measure(buf, 64)
+    if n < 0:
+        return None
+    return {buf[i].name.decode(): (round(buf[i].value, 2), buf[i].unit.decode()) for i in range(n)}
+
+
+# The configuration groups beside the headline sweep: (key, dtype, layer names).
+def config_groups(wl):
+    return [
+        ("vgg_n16_bf16", "bf16", wl.VGG_N16),
+        ("vgg_n1_f32", "f32", wl.VGG_N1),
+        ("resnet_n32_f32", "f32", ["R7x7", "R1x1a", "R1x1b", "R3x3", "R1x1s2"]),
+        ("resnet_n32_bf16", "bf16", ["R3x3", "R1x1a", "R1x1b", "R1x1s2"]),
+        ("large_batch_f32", "f32", ["L-same", "L-valid", "L-s2"]),
+        ("tiny_f32", "f32", ["T1"]),
+    ]
+
+
+def time_group(torch, B, wl, stream, dtype, names, reps=20):
+    """Per layer of a group: mean ms of back-to-back calls of conv2d_forward's direct-sum
+    selection (repack and reduce kernels included), a cold-cache ms where at most 64 rotating
+    buffer sets exceed 1.25 GiB, TFLOP/s, and the fraction of the layer's own bound."""
+    dev = torch.device("cuda:0")
+    in_dtype = B.F32 if dtype == "f32" else B.BF16
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    handle = stream.cuda_stream
+    rows = []
+    for name in names:
+        L = wl.ALL_LAYERS[name]
+        x, f = wl.make_inputs(L)
+        p = B.params_of_layer(L, in_dtype, B.F32)
+        xd = torch.from_numpy(x).to(dev).to(tdt).contiguous()
+        fd = torch.from_numpy(f).to(dev).to(tdt).contiguous()
+        del x, f
+        g = B.conv2d_get_geometry(p)
+        out = torch.empty((p.batch, g.out_rows, g.out_cols, p.features), dtype=torch.float32,
+                          device=dev)
+        vid = B.conv2d_select_variant(p, B.SELECT_DIRECT_SUM_ONLY)
+        ws_bytes = B.conv2d_workspace_size(p, vid)
+        ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev)
+        ws_ptr = ws.data_ptr() if ws_bytes else 0
+        flops, nbytes = layer_flops(B, p), layer_bytes(B, p)
+
+        def call(xp, op):
+            rc = B.conv2d_forward_raw(p, xp, fd.data_ptr(), op, ws_ptr, ws_bytes, handle, vid)
+            if rc:
+                raise B.Conv2dError(rc, "conv2d_forward(%s)" % name)
+        n = reps if flops > 2e9 else 10 * reps
+        for _ in range(3):
+            call(xd.data_ptr(), out.data_ptr())
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(n):
+            call(xd.data_ptr(), out.data_ptr())
+        e1.record(stream)
+        stream.synchronize()
+        ms = e0.elapsed_time(e1) / n
+        cold_ms = None
+        per_set = xd.numel() * xd.element_size() + out.numel() * 4
+        sets = -(-(5 << 28) // per_set)
+        if 2 <= sets <= 64:
+            xs = [xd] + [xd.clone() for _ in range(sets - 1)]
+            outs = [out] + [torch.empty_like(out) for _ in range(sets - 1)]
+            torch.cuda.synchronize()
+            for xx, oo in zip(xs, outs):
+                call(xx.data_ptr(), oo.data_ptr())
+            rounds = max(2, -(-n // sets))
+            e0.record(stream)
+            for _ in range(rounds):
+                for xx, oo in zip(xs, outs):
+                    call(xx.data_ptr(), oo.data_ptr())
+            e1.record(stream)
+            stream.synchronize()
+            cold_ms = e0.elapsed_time(e1) / (rounds * sets)
+            del xs, outs
+        t_mfma = flops / (PEAK_TFLOPS[dtype] * 1e12) * 1e3
+        t_hbm = nbytes / (PEAK_HBM_GBS * 1e9) * 1e3
+        bound_ms = max(t_mfma, t_hbm)
+        rows.append({"name": name, "variant": B.conv2d_variant_name(vid), "ms": round(ms, 5),
+                     "cold_ms": None if cold_ms is None else round(cold_ms, 5),
+                     "tflops": round(flops / (ms * 1e-3) / 1e12, 2),
+                     "cold_tflops": None if cold_ms is None else
+                     round(flops / (cold_ms * 1e-3) / 1e12, 2),
+                     "alg_gbs": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                     "cold_alg_gbs": None if cold_ms is None else
+                     round(nbytes / (cold_ms * 1e-3) / 1e9, 1),
+                     "bound": "mfma" if t_mfma >= t_hbm else "hbm",
+                     "bound_ms": round(bound_ms, 5),
+                     "frac_of_bound": round(bound_ms / ms, 4),
+                     "frac_of_bound_cold": None if cold_ms is None else
+                     round(bound_ms / cold_ms, 4)})
+        del xd, fd, out, ws
+    total_flops = sum(layer_flops(B, B.params_of_layer(wl.ALL_LAYERS[n_], in_dtype, B.F32))
+                      for n_ in names)
+    total_ms = sum(r["ms"] for r in rows)
+    return {"dtype": dtype, "tflops": round(total_flops / (total_ms * 1e-3) / 1e12, 2),
+            "ms": round(total_ms, 5),
+            "note": "ms: back-to-back calls on one buffer set; cold_ms: rotating over more than "
+                    "1.25 GiB of buffer sets (null where that takes more than 64 sets)",
+            "layers": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -99,6 +222,11 @@ def main():
                          "--steps times, plus one device-to-device copy of --copy-mb MiB as the "
                          "known-size reference for memory counters; prints no JSON")
     ap.add_argument("--copy-mb", type=int, default=256)
+    ap.add_argument("--ceilings", action="store_true",
+                    help="only measure this GPU's reachable rates (register-only MFMA loops, LDS "
+                         "fragment reads, streaming copies) and print them, one per line")
+    ap.add_argument("--no-groups", action="store_true",
+                    help="skip the other configuration groups (the `groups` key)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -111,6 +239,15 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs the GPU")
+    if args.ceilings:
+        torch.cuda.init()
+        torch.zeros(1, device="cuda:0")
+        c = measure_ceilings()
+        if c is None:
+            sys.exit("bench.py --ceilings: libconv2d_ceilings.so is not built or failed")
+        for k, (v, u) in c.items():
+            print("%-48s %12.2f %s" % (k, v, u))
+        return
     dev = torch.device("cuda:0")
     in_dtype = B.F32 if args.dtype == "f32" else B.BF16
     tdt = torch.float32 if args.dtype == "f32" else torch.bfloat16
@@ -361,6 +498,21 @@ def main():
             "note": "filters packed once outside the timed region (conv2d_pack_filter), "
                     "conv2d_forward_packed inside it; the headline value repacks in every call"}
 
+    # ---- this GPU's reachable rates, measured now (a second or two), and the other groups
+    ceilings = None if args.skip_all_algorithms_leg else measure_ceilings()
+    if ceilings:
+        key = ({"f32": "mfma_f32_32x32x2 x4acc", "bf16": "mfma_bf16_16x16x32 x8acc"}[args.dtype]
+               if not hbm_bound else "hbm_copy (read+write)")
+        roofline["achievable_peak"] = ceilings[key][0]
+        roofline["achievable_peak_source"] = key + " (measured in this run)"
+        roofline["frac_of_achievable"] = round(roofline["achieved"] / ceilings[key][0], 4)
+    groups = None
+    if (args.workload == "vgg16" and args.dtype == "f32" and args.algorithms == "direct"
+            and not args.no_groups and not args.skip_all_algorithms_leg):
+        groups = {}
+        for key, dt, group_names in config_groups(wl):
+            groups[key] = time_group(torch, B, wl, stream, dt, group_names)
+
     result = {
         "metric": "conv2d forward TFLOP/s (2*N*P*Q*K*R*S*C / time)",
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -379,6 +531,9 @@ def main():
         "roofline": roofline,
         "all_algorithms": with_transforms,
         "packed_filters": packed_leg,
+        "groups": groups,
+        "ceilings": ({k: {"value": v, "unit": u} for k, (v, u) in ceilings.items()}
+                     if ceilings else None),
         "layers": [{"name": l["name"], "variant": l["variant"], "ms": round(l["ms"], 4),
                     "tflops": round(l["flops"] / (l["ms"] * 1e-3) / 1e12, 2),
                     "median_ms": round(l["median_ms"], 4), "min_ms": round(l["min_ms"], 4),

@@ -12,6 +12,10 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libconv2d_mi355x.so")
+# the ceilings helper (register-only MFMA loop, LDS read loop, copy kernels): a library of its
+# own, outside the convolution library's C ABI, loaded only by bench.py --ceilings
+CEILINGS_SRC = os.path.join(HERE, "ceilings", "ceilings.hip")
+CEILINGS_LIB = os.path.join(HERE, "libconv2d_ceilings.so")
 BUILD_DIR = os.path.join(HERE, "_build")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -55,6 +59,11 @@ def build(force=False, jobs=None):
     tmp = LIB + ".tmp%d" % os.getpid()
     subprocess.check_call([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs)
     os.replace(tmp, LIB)
+    if (force or not os.path.exists(CEILINGS_LIB)
+            or os.path.getmtime(CEILINGS_LIB) < os.path.getmtime(CEILINGS_SRC)):
+        tmp = CEILINGS_LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call([HIPCC] + FLAGS + ["-shared", CEILINGS_SRC, "-o", tmp])
+        os.replace(tmp, CEILINGS_LIB)
     return LIB
 
 

@@ -15,7 +15,7 @@
 //    of a wavefront fills 1 KiB of LDS: lane l -> row l / CPR, 16-byte chunk
 //    position l % CPR (CPR = ROWB/16 chunks per row).  LDS cannot be padded
 //    under this scheme, so bank conflicts are avoided by an XOR swizzle: the
-//    chunk stored at position p of row r is chunk p ^ ((r >> 1) & (CPR-1)).
+//    chunk stored at position p of row r is chunk p ^ ((r >> SWZ_SHIFT) & (CPR-1)).
 //    The lane simply fetches that chunk from memory; the MFMA fragment reads
 //    apply the same XOR (measured: full LDS read rate).
 //  * Padding taps / rows past M / k past Kg use an out-of-range buffer
@@ -139,6 +139,11 @@ struct DmaTile {
   static constexpr int VEC = 16 / ES;
   static constexpr int BK = ROWB / ES;
   static constexpr int KSTEPS = CPR / 2;         // a fragment step eats two chunks (two lane halves)
+  // XOR swizzle of the chunk position: (row >> SWZ_SHIFT) & (CPR - 1).  A fragment read of a
+  // 32-row block must spread over all 64 banks: with 64-byte rows four rows share a quarter of
+  // the banks, so rows r, r+4, r+8, r+12 need four different positions (shift 2; measured
+  // 246 bytes per clock and compute unit against 127 with shift 1); 128-byte rows: shift 1.
+  static constexpr int SWZ_SHIFT = CPR == 4 ? 2 : 1;
   static constexpr int STAGES = STAGES_;
   static constexpr bool TWO_LEVEL = TWO_LEVEL_;  // see igemm.hip: two-level fp32 summation
   static constexpr int OCC = OCC_;
@@ -360,12 +365,12 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   // passes step by a multiple of 16 rows, so the swizzle is the same in all
   const int ld_row0 = tid / CPR;
   const int ld_pos = tid % CPR;
-  const int ld_chunk = ld_pos ^ ((ld_row0 >> 1) & (CPR - 1));
+  const int ld_chunk = ld_pos ^ ((ld_row0 >> T::SWZ_SHIFT) & (CPR - 1));
   // A loads of ELEMENT tiles move one element per lane: row tid / A_LPR,
   // element position tid % A_LPR inside the LDS row, memory element =
   // (chunk position ^ swizzle) * VEC + element within the chunk
   const int a_row0 = ELEMENT ? tid / T::A_LPR : ld_row0;
-  const int a_k0 = ELEMENT ? ((((tid % T::A_LPR) / VEC) ^ ((a_row0 >> 1) & (CPR - 1))) * VEC +
+  const int a_k0 = ELEMENT ? ((((tid % T::A_LPR) / VEC) ^ ((a_row0 >> T::SWZ_SHIFT) & (CPR - 1))) * VEC +
                               (tid % T::A_LPR) % VEC)
                            : ld_chunk * VEC;
   // UNIFORM: byte offset of the row's window origin (+ shift, + this lane's
@@ -525,7 +530,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   int until_flush = flush_slices;
 
   // fragment addressing: row lr of each 32-row block, chunk (2*kk + lk) ^ swizzle
-  const int frag_swz = (lr >> 1) & (CPR - 1);
+  const int frag_swz = (lr >> T::SWZ_SHIFT) & (CPR - 1);
   const unsigned char* a_frag = ring + (wm * T::WM + lr) * ROWB;
   const unsigned char* b_frag = ring + (BM + wn * T::WN + lr) * ROWB;
   int chunk_bytes[KSTEPS];
@@ -1025,6 +1030,9 @@ struct PatchTile {
   static constexpr int BLK = MF16 ? 16 : 32;        // rows / columns of an MFMA block
   static constexpr int ACC = MF16 ? 4 : 16;         // accumulator registers of a block
   static constexpr int ROWB = 64, CPR = 4, KSTEPS = MF16 ? 1 : 2;
+  // swizzle of the filter rows (see DmaTile): a 16-row block's read (row = lane % 16, chunk =
+  // lane / 16) is conflict free with shift 1, a 32-row block's with shift 2
+  static constexpr int SWZ_SHIFT = MF16 ? 1 : 2;
   static constexpr int ES = BF16 ? 2 : 4;
   static constexpr int VEC = 16 / ES;
   static constexpr int BK = ROWB / ES;
@@ -1165,7 +1173,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   }
   // ---- filter loader role (as in the gather kernel)
   const int ld_row0 = tid / CPR;
-  const int ld_chunk = (tid % CPR) ^ ((ld_row0 >> 1) & (CPR - 1));
+  const int ld_chunk = (tid % CPR) ^ ((ld_row0 >> T::SWZ_SHIFT) & (CPR - 1));
   int b_voff[T::B_ITERS];
   auto filter_offsets = [&](int col0, int (&voff)[T::B_ITERS]) {
 #pragma unroll
@@ -1222,7 +1230,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
       a_frag[i] = static_cast<int>(patch_base(p, Hp, Wp, m) - v0) * 16 + lk * T::PLANE_BYTES;
     }
   }
-  const int frag_swz = (lr >> 1) & (CPR - 1);
+  const int frag_swz = (lr >> T::SWZ_SHIFT) & (CPR - 1);
   const unsigned char* b_frag = ring + B_REGION + (wn * T::WN + lr) * ROWB;
   int chunk_bytes[KSTEPS];
 #pragma unroll
