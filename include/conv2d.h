@@ -94,10 +94,15 @@ typedef struct {
  * INVALID_ARGUMENT if the tuple has no valid output. */
 CONV2D_API int conv2d_get_geometry(const conv2d_params* params, conv2d_geometry* geometry);
 
-/* Bytes of device scratch that conv2d_forward may use for `params` with the
- * variant it would select (0 for most layers; non-zero when the reduction
- * over window and channels is split across workgroups, or the filter is
- * repacked).  Host only. */
+/* Bytes of device scratch that conv2d_forward may use for `params` (section 3:
+ * the library chooses the algorithm, so it also says what that algorithm
+ * needs) with the variant it selects for 16-byte-aligned pointers (0 for some
+ * layers; non-zero when the filter is repacked or the reduction over window
+ * and channels is split across workgroups).  The query sees no pointers; with
+ * pointers that are only element-aligned conv2d_forward selects among the
+ * element-wise variants, and if its pick there needs more than the workspace
+ * it is given, it runs the cheapest variant that fits (the direct kernel
+ * needs none), so a workspace of this size is always enough.  Host only. */
 CONV2D_API int conv2d_workspace_size(const conv2d_params* params, size_t* bytes);
 
 /* Same, for a forced variant.  UNSUPPORTED if the variant cannot run `params`. */
@@ -109,7 +114,7 @@ CONV2D_API int conv2d_workspace_size_variant(const conv2d_params* params, int va
  *                   vectorised variants are only selected when the bases are
  *                   16-byte aligned.
  *   workspace     : device scratch of at least conv2d_workspace_size() bytes,
- *                   256-byte aligned, or NULL when that size is 0.  Contents
+ *                   16-byte aligned, or NULL when that size is 0.  Contents
  *                   are undefined afterwards.
  * Enqueues on hip_stream and returns.  batch == 0 returns OK without a launch. */
 CONV2D_API int conv2d_forward(const conv2d_params* params, const void* in, const void* filt, void* out,
@@ -159,9 +164,13 @@ CONV2D_API int conv2d_forward_bias_act(const conv2d_params* params, const void* 
  * scratch, and a second kernel pools it; the result is the same.
  * The maximum is taken with fmaxf: a NaN among the four is dropped unless all
  * four are NaN.  conv2d_pool_workspace_size (host only) gives the bytes this
- * entry point needs for the variant it would select, the _variant form for a
- * given variant (UNSUPPORTED if that variant cannot run the parameters); all
- * other rules are those of conv2d_forward_bias_act. */
+ * entry point needs for the variant it would select for 16-byte-aligned
+ * pointers, the _variant form for a given variant (UNSUPPORTED if that variant
+ * cannot run the parameters).  With pointers that are only element-aligned no
+ * variant pools in its epilogue, so the workspace must also hold the unpooled
+ * tensor: conv2d_pool_workspace_size_variant(params, 0, ...) (the direct
+ * kernel's size) is then enough, less is WORKSPACE_TOO_SMALL.  All other
+ * rules are those of conv2d_forward_bias_act. */
 CONV2D_API int conv2d_pool_workspace_size(const conv2d_params* params, size_t* bytes);
 CONV2D_API int conv2d_pool_workspace_size_variant(const conv2d_params* params, int variant_id,
                                        size_t* bytes);
@@ -209,6 +218,17 @@ CONV2D_API const char* conv2d_last_launch_error(void);
 CONV2D_API int conv2d_num_variants(void);
 CONV2D_API const char* conv2d_variant_name(int variant_id);            /* NULL if out of range */
 CONV2D_API int conv2d_variant_supports(const conv2d_params* params, int variant_id); /* 1, 0, or <0 status */
+/* Debugging aid for the entry points that select a variant themselves and have
+ * no forced-variant form (conv2d_forward_bias_act, conv2d_forward_bias_act_pool,
+ * and conv2d_forward): from now on the calling
+ * thread's calls run `variant_id` wherever it supports the parameters and the
+ * pointers' alignment, and their own pick elsewhere; -1 switches it off.  The
+ * size queries of the same thread follow.  A thread starts with the value of
+ * the CONV2D_FORCE_VARIANT environment variable (read once per process), -1
+ * without it.  It is how the tests check section 3's statement that every
+ * algorithm gives the same result through these entry points too.
+ * INVALID_ARGUMENT for an id outside [-1, conv2d_num_variants()). */
+CONV2D_API int conv2d_debug_force_variant(int variant_id);
 /* The variant conv2d_forward would use, assuming 16-byte-aligned pointers. */
 CONV2D_API int conv2d_selected_variant(const conv2d_params* params, int* variant_id);
 

@@ -27,7 +27,8 @@ EXPORTS = (
     "conv2d_forward", "conv2d_forward_variant", "conv2d_forward_bias_act",
     "conv2d_forward_bias_act_pool", "conv2d_pool_workspace_size",
     "conv2d_pool_workspace_size_variant", "conv2d_packed_filter_size", "conv2d_pack_filter",
-    "conv2d_forward_packed", "conv2d_last_launch_error", "conv2d_num_variants",
+    "conv2d_forward_packed", "conv2d_last_launch_error", "conv2d_debug_force_variant",
+    "conv2d_num_variants",
     "conv2d_variant_name",
     "conv2d_variant_supports", "conv2d_selected_variant", "conv2d_select_variant",
     "conv2d_status_string", "conv2d_version",
@@ -84,6 +85,7 @@ def lib():
         l.conv2d_workspace_size_variant.argtypes = [pp, ctypes.c_int, ctypes.POINTER(sz)]
         l.conv2d_forward.argtypes = [pp, vp, vp, vp, vp, sz, vp]
         l.conv2d_forward_variant.argtypes = [pp, vp, vp, vp, vp, sz, vp, ctypes.c_int]
+        l.conv2d_debug_force_variant.argtypes = [ctypes.c_int]
         l.conv2d_num_variants.argtypes = []
         l.conv2d_variant_name.argtypes = [ctypes.c_int]
         l.conv2d_variant_name.restype = ctypes.c_char_p
@@ -209,6 +211,13 @@ def conv2d_forward_raw(params, in_ptr, filt_ptr, out_ptr, workspace_ptr=0, works
     return l.conv2d_forward_variant(ctypes.byref(params), in_ptr, filt_ptr, out_ptr,
                                     workspace_ptr, workspace_bytes, stream_handle,
                                     int(variant_id))
+
+
+def conv2d_debug_force_variant(variant_id):
+    """Forces `variant_id` (None or -1: off) for the calling thread's selecting entry points."""
+    rc = lib().conv2d_debug_force_variant(-1 if variant_id is None else int(variant_id))
+    if rc:
+        raise Conv2dError(rc, "conv2d_debug_force_variant")
 
 
 ACT_NONE = 0

@@ -556,9 +556,32 @@ bool aligned16(const void* a, const void* b, const void* c) {
            reinterpret_cast<uintptr_t>(c)) & 15u) == 0;
 }
 
+// Variant that the selecting entry points of the calling thread are told to run, or -1
+// (conv2d_debug_force_variant).  The thread's first call takes the CONV2D_FORCE_VARIANT
+// environment variable (a variant id) as its initial value, read once per process.
+int& forced_variant_of_thread() {
+  static const int from_environment = [] {
+    const char* env = std::getenv("CONV2D_FORCE_VARIANT");
+    return (env && *env) ? std::atoi(env) : -1;
+  }();
+  thread_local int forced = from_environment;
+  return forced;
+}
+int forced_variant_from_environment() { return forced_variant_of_thread(); }
+
+// The variant a selecting entry point runs for pointers of the given alignment.
+int pick(const Problem& q, int padding, bool aligned, int mode) {
+  const Table& tb = table();
+  int id = select(q, padding, aligned, mode);
+  const int forced = forced_variant_from_environment();
+  if (forced >= 0 && forced < tb.n && usable(tb.v[forced], q, aligned)) id = forced;
+  return id;
+}
+
 int run(const conv2d_params* params, const void* in, const void* filt, void* out, void* workspace,
         size_t workspace_bytes, void* hip_stream, int variant_id, const float* bias = nullptr,
-        int activation = CONV2D_ACT_NONE, bool pool = false, bool filt_is_packed = false) {
+        int activation = CONV2D_ACT_NONE, bool pool = false, bool filt_is_packed = false,
+        int select_mode_override = -1) {
   Problem q;
   int rc = derive(params, &q);
   if (rc) return rc;
@@ -570,13 +593,27 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
   const bool al = aligned16(in, filt, out);
   int id = variant_id;
   if (id < 0) {
-    id = select(q, params->padding, al, pool ? kForPooling : kAny);
-    const char* env = std::getenv("CONV2D_FORCE_VARIANT");
-    if (env && *env) {
-      const int forced = std::atoi(env);
-      if (forced >= 0 && forced < tb.n && supports(tb.v[forced], q) &&
-          (al || tb.v[forced].family == kDirect || is_scalar(tb.v[forced])))
-        id = forced;
+    const int mode = select_mode_override >= 0 ? select_mode_override : (pool ? kForPooling : kAny);
+    id = pick(q, params->padding, al, mode);
+    if (!al) {
+      // The size queries see no pointers and answer for 16-byte-aligned ones.  Pointers that are
+      // only element-aligned get another pick, which may need more scratch than the caller was
+      // told: then the cheapest usable variant that fits what the caller brought (the direct
+      // kernel needs none).
+      const size_t need0 = pool ? pooled_workspace_bytes_for(tb.v[id], q) : workspace_bytes_for(tb.v[id], q);
+      if (need0 > 0 && (!workspace || workspace_bytes < need0)) {
+        int best = -1;
+        double best_cost = 0;
+        for (int i = 0; i < tb.n; ++i) {
+          if (!usable(tb.v[i], q, false)) continue;
+          if (mode == kDirectSumOnly && tb.v[i].family == kWinograd) continue;
+          const size_t n = pool ? pooled_workspace_bytes_for(tb.v[i], q) : workspace_bytes_for(tb.v[i], q);
+          if (n > 0 && (!workspace || workspace_bytes < n)) continue;
+          const double c = tb.v[i].family == kDirect ? 1e300 : model_cost(tb.v[i], q);
+          if (best < 0 || c < best_cost) { best = i; best_cost = c; }
+        }
+        if (best >= 0) id = best;
+      }
     }
   } else {
     if (!supports(tb.v[id], q)) return CONV2D_STATUS_UNSUPPORTED;
@@ -649,7 +686,7 @@ int conv2d_workspace_size(const conv2d_params* params, size_t* bytes) {
   if (!bytes) return CONV2D_STATUS_INVALID_ARGUMENT;
   int rc = derive(params, &q);
   if (rc) return rc;
-  *bytes = workspace_bytes_for(table().v[select(q, params->padding, true, kAny)], q);
+  *bytes = workspace_bytes_for(table().v[pick(q, params->padding, true, kAny)], q);
   return CONV2D_STATUS_OK;
 }
 
@@ -691,7 +728,7 @@ int conv2d_pool_workspace_size(const conv2d_params* params, size_t* bytes) {
   if (!bytes) return CONV2D_STATUS_INVALID_ARGUMENT;
   int rc = derive(params, &q);
   if (rc) return rc;
-  *bytes = pooled_workspace_bytes_for(table().v[select(q, params->padding, true, kForPooling)], q);
+  *bytes = pooled_workspace_bytes_for(table().v[pick(q, params->padding, true, kForPooling)], q);
   return CONV2D_STATUS_OK;
 }
 
@@ -787,6 +824,12 @@ int conv2d_forward_packed(const conv2d_params* params, int variant_id, const voi
   }
   return run(params, in, packed_filt, out, workspace, workspace_bytes, hip_stream, variant_id, bias,
              activation, false, true);
+}
+
+int conv2d_debug_force_variant(int variant_id) {
+  if (variant_id < -1 || variant_id >= table().n) return CONV2D_STATUS_INVALID_ARGUMENT;
+  forced_variant_of_thread() = variant_id;
+  return CONV2D_STATUS_OK;
 }
 
 int conv2d_num_variants(void) { return table().n; }

@@ -225,6 +225,42 @@ def test_unaligned_pointers_take_the_element_wise_path(torch_cuda, oracle):
             assert rc == B.STATUS_UNSUPPORTED, name
 
 
+def test_unaligned_pointers_with_the_reported_workspace(torch_cuda, oracle):
+    """conv2d_workspace_size answers for 16-byte-aligned pointers.  With pointers 4 bytes past a
+    16-byte boundary conv2d_forward picks among the element-wise variants, and if that pick
+    needs more scratch than the reported size it must run a variant that fits: never
+    WORKSPACE_TOO_SMALL, always the right result (random shapes, and the two that showed it:
+    a deep 3x3 layer on a 14x14 image and a 1x1 layer on a 7x7 image)."""
+    torch = torch_cuda
+    rng = np.random.default_rng(31337)
+    shapes = [(1, 14, 14, 512, 512, 3, 3, 1), (8, 7, 7, 512, 2048, 1, 1, 1)]
+    for _ in range(10):
+        r = int(rng.choice([1, 3, 5]))
+        shapes.append((int(rng.integers(1, 5)), int(rng.integers(5, 20)), int(rng.integers(5, 20)),
+                       int(rng.choice([8, 16, 64, 256, 512])), int(rng.choice([8, 24, 64, 512])),
+                       r, r, int(rng.choice([1, 2]))))
+
+    def shifted(a):
+        buf = torch.empty(a.size + 1, dtype=torch.float32, device="cuda")
+        v = buf[1:].view(a.shape)
+        v.copy_(torch.from_numpy(a))
+        return v
+    for i, (n, h, w, c, k, r, s_, st) in enumerate(shapes):
+        x, f = wl.make_case((n, h, w, c), (r, s_, c, k), "uniform", 500 + i)
+        want = oracle.forward_f32(x, f, (st, st), wl.PAD_SAME)
+        p = B.make_params(n, h, w, c, k, r, s_, st, st, B.PAD_SAME)
+        need = B.conv2d_workspace_size(p)
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        xd, fd = shifted(x), shifted(f)
+        out = shifted(np.full(want.shape, np.nan, np.float32))
+        _say("unaligned pointers, reported workspace %d bytes: %s" % (need, (n, h, w, c, k, r, st)))
+        rc = B.conv2d_forward_raw(p, xd.data_ptr(), fd.data_ptr(), out.data_ptr(),
+                                  ws.data_ptr() if need else 0, need, 0)
+        torch.cuda.synchronize()
+        assert rc == B.STATUS_OK, (shapes[i], B.status_string(rc))
+        assert rel_err(out.cpu().numpy(), want) <= TOL_F32, shapes[i]
+
+
 def test_unaligned_bf16_pointers_and_odd_channels(torch_cuda, oracle):
     """bf16 input and filter that start 2 bytes past a 16-byte boundary, and a layer with
     C = 3 and K = 10 (no 16-byte vector along either): the element-wise bf16 MFMA tiles run
@@ -402,6 +438,23 @@ def test_resnet50_small_batches_fp32(torch_cuda, oracle, batch):
         assert err <= TOL_F32, (name, err)
 
 
+@pytest.mark.parametrize("batch", [1, 4])
+def test_resnet50_small_batches_bf16(torch_cuda, oracle, batch):
+    """The same 26 shapes at batch 4 and 1 with bf16 inputs and fp32 output (the tuned table
+    holds bf16 rows for them), with the selected variant, against the oracle on the bf16-rounded
+    inputs."""
+    for name, L in wl.RESNET50_BY_BATCH[batch].items():
+        x, f = wl.make_inputs(L)
+        xb, _ = wl.round_to_bf16(x)
+        fb, _ = wl.round_to_bf16(f)
+        p = B.params_of_layer(L, B.BF16, B.F32)
+        _say("resnet50 N=%d bf16 %s variant %s" % (
+            batch, name, B.conv2d_variant_name(B.conv2d_selected_variant(p))))
+        err = rel_err(run_gpu(torch_cuda, p, xb, fb),
+                      oracle.forward_f32(xb, fb, (L.stride_rows, L.stride_cols), L.padding))
+        assert err <= TOL_BF16, (name, err)
+
+
 # ------------------------------------------------------------------ Winograd F(2x2, 3x3) (section 3)
 
 def _winograd_variants(p):
@@ -457,10 +510,8 @@ def test_winograd_integer_inputs_bit_exact(torch_cuda, oracle, pad):
 # ------------------------------------------------------------------ fused bias + activation
 
 def run_gpu_fused(torch, params, x, f, bias, activation, force=None):
-    """conv2d_forward_bias_act on numpy inputs.  `force`: variant id put into the library's
-    CONV2D_FORCE_VARIANT environment switch for the call (the fused entry point has no
-    forced-variant twin)."""
-    import os
+    """conv2d_forward_bias_act on numpy inputs.  `force`: variant id forced for the call through
+    conv2d_debug_force_variant (the fused entry point has no forced-variant twin)."""
     dev = torch.device("cuda:0")
     in_dt = torch.float32 if params.in_dtype == B.F32 else torch.bfloat16
     xd = torch.from_numpy(x).to(dev).to(in_dt).contiguous()
@@ -470,12 +521,12 @@ def run_gpu_fused(torch, params, x, f, bias, activation, force=None):
     if force is not None:
         need = B.conv2d_workspace_size(params, force)
         ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
-        os.environ["CONV2D_FORCE_VARIANT"] = str(force)
+        B.conv2d_debug_force_variant(force)
     try:
         out = B.conv2d_forward_bias_act(params, xd, fd, bd, activation, workspace=ws)
         torch.cuda.synchronize()
     finally:
-        os.environ.pop("CONV2D_FORCE_VARIANT", None)
+        B.conv2d_debug_force_variant(None)
     return out.float().cpu().numpy()
 
 
@@ -496,11 +547,8 @@ def test_bias_relu_every_variant_fp32(torch_cuda, oracle, case):
     for vid in supported_variants(p):
         _say("bias+relu case %s variant %s" % (case, B.conv2d_variant_name(vid)))
         got = run_gpu_fused(torch_cuda, p, x, f, bias, B.ACT_RELU, vid)
-        # where the pre-activation is within the tolerance of zero either side of the clamp is right
-        err = np.abs(got.astype(np.float64) - want) / (np.abs(want) + 1.0)
-        near_zero = np.abs(want_lin) <= 2 * TOL_F32
-        assert float(err[~near_zero].max()) <= TOL_F32, (case, B.conv2d_variant_name(vid))
-        assert float(np.abs(got[near_zero]).max(initial=0.0)) <= 4 * TOL_F32
+        # (the clamp is 1-Lipschitz: it cannot widen the error of the sum)
+        assert rel_err(got, want) <= TOL_F32, (case, B.conv2d_variant_name(vid))
         assert (got >= 0).all()
     got = run_gpu_fused(torch_cuda, p, x, f, bias, B.ACT_NONE)
     assert rel_err(got, want_lin) <= TOL_F32
@@ -521,7 +569,7 @@ def test_bias_relu_full_size(torch_cuda, oracle, name):
     for vid in (None, B.conv2d_select_variant(p, B.SELECT_DIRECT_SUM_ONLY)):
         _say("bias+relu %s variant %s" % (name, "auto" if vid is None else B.conv2d_variant_name(vid)))
         got = run_gpu_fused(torch_cuda, p, x, f, bias, B.ACT_RELU, vid)
-        assert rel_err(got, want) <= 2 * TOL_F32, name   # clamp decided by an fp32 sum near zero
+        assert rel_err(got, want) <= TOL_F32, name
     if name in wl.BF16_LAYERS:
         xb, _ = wl.round_to_bf16(x)
         fb, _ = wl.round_to_bf16(f)
@@ -568,7 +616,6 @@ def test_patch_tiles_with_more_tiles_than_resident_workgroups(torch_cuda, oracle
 
 def run_gpu_pooled(torch, params, x, f, bias, activation, force=None):
     """conv2d_forward_bias_act_pool on numpy inputs; `force` as in run_gpu_fused."""
-    import os
     dev = torch.device("cuda:0")
     in_dt = torch.float32 if params.in_dtype == B.F32 else torch.bfloat16
     xd = torch.from_numpy(x).to(dev).to(in_dt).contiguous()
@@ -578,7 +625,7 @@ def run_gpu_pooled(torch, params, x, f, bias, activation, force=None):
     if force is not None:
         need = B.conv2d_pool_workspace_size(params, force)
         ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
-        os.environ["CONV2D_FORCE_VARIANT"] = str(force)
+        B.conv2d_debug_force_variant(force)
     try:
         g = B.conv2d_get_geometry(params)
         out = torch.full((params.batch, g.out_rows // 2, g.out_cols // 2, params.features),
@@ -587,7 +634,7 @@ def run_gpu_pooled(torch, params, x, f, bias, activation, force=None):
         B.conv2d_forward_bias_act_pool(params, xd, fd, bd, activation, out=out, workspace=ws)
         torch.cuda.synchronize()
     finally:
-        os.environ.pop("CONV2D_FORCE_VARIANT", None)
+        B.conv2d_debug_force_variant(None)
     return out.float().cpu().numpy()
 
 
@@ -607,6 +654,26 @@ def test_pool_every_variant_fp32(torch_cuda, oracle, case):
         assert got.shape == want.shape
         if want.size:
             assert rel_err(got, want) <= TOL_F32, (case, v)
+
+
+@pytest.mark.parametrize("case", FUSED_SMALL)
+@pytest.mark.parametrize("out_dtype", [B.F32, B.BF16])
+def test_pool_every_variant_bf16(torch_cuda, oracle, case, out_dtype):
+    """The same with bf16 inputs (fp32 and bf16 output): every bf16 variant that supports the
+    case, against the oracle's composition on the bf16-rounded inputs."""
+    (n, h, w, c, k, r, s_, sr, sc, pad) = case
+    x, f = wl.make_case((n, h, w, c), (r, s_, c, k), "uniform", 779)
+    xb, _ = wl.round_to_bf16(x)
+    fb, _ = wl.round_to_bf16(f)
+    bias = np.random.default_rng(780).uniform(-1, 1, k).astype(np.float32)
+    p = _params(case, B.BF16, out_dtype)
+    want = oracle.forward_bias_act_pool_f32(xb, fb, bias, True, (sr, sc), pad)
+    for v in [None] + supported_variants(p):
+        _say("pool bf16 case %s variant %s" % (case, "auto" if v is None else B.conv2d_variant_name(v)))
+        got = run_gpu_pooled(torch_cuda, p, xb, fb, bias, B.ACT_RELU, force=v)
+        assert got.shape == want.shape
+        if want.size:
+            assert rel_err(got, want) <= TOL_BF16, (case, v)
 
 
 @pytest.mark.parametrize("shape", [(32, 70, 70, 64, 80), (24, 51, 83, 96, 200)])
@@ -828,7 +895,7 @@ def test_calls_can_be_captured_in_a_hip_graph(torch_cuda, oracle):
     for (p, _, _, out, _, bias, x, f), e in zip(jobs, eager):
         want = oracle.forward_bias_act_f32(x, f, None if bias is None else bias.cpu().numpy(),
                                            bias is not None, 1, wl.PAD_SAME)
-        assert rel_err(e.cpu().numpy(), want) <= 2 * TOL_F32
+        assert rel_err(e.cpu().numpy(), want) <= TOL_F32
     side = torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=side):
@@ -885,9 +952,9 @@ def test_pooled_and_packed_calls_in_a_hip_graph(torch_cuda, oracle):
     want_a = oracle.forward_bias_act_pool_f32(xa, fa, bias_np, True, 1, wl.PAD_SAME)
     assert np.array_equal(eager[0].cpu().numpy(), want_a)      # integer inputs: exact
     want_b = oracle.forward_bias_act_pool_f32(xb, fb, bias_np, True, 2, wl.PAD_SAME)
-    assert rel_err(eager[1].cpu().numpy(), want_b) <= 2 * TOL_F32
+    assert rel_err(eager[1].cpu().numpy(), want_b) <= TOL_F32
     want_c = oracle.forward_bias_act_f32(xc, fc, bias_np, True, 1, wl.PAD_SAME)
-    assert rel_err(eager[2].cpu().numpy(), want_c) <= 2 * TOL_F32
+    assert rel_err(eager[2].cpu().numpy(), want_c) <= TOL_F32
     side = torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=side):
