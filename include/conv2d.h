@@ -66,7 +66,9 @@ typedef enum {
   CONV2D_STATUS_UNSUPPORTED = -2,        /* forced variant / dtype pair cannot run these parameters   */
   CONV2D_STATUS_WORKSPACE_TOO_SMALL = -3,
   CONV2D_STATUS_LAUNCH_FAILED = -4,      /* the HIP runtime rejected a launch                          */
-  CONV2D_STATUS_TOO_LARGE = -5           /* a tensor has 2^31 or more elements                         */
+  CONV2D_STATUS_TOO_LARGE = -5,          /* a tensor has 2^31 or more elements                         */
+  CONV2D_STATUS_SCRATCH_EXCEEDED = -6    /* conv2d_forward_static_scratch: layer needs more scratch
+                                            than CONV2D_STATIC_SCRATCH_BYTES                           */
 } conv2d_status_t;
 
 /* The parameter tuple of Figure 1's caption, plus batch, padding mode and
@@ -119,6 +121,31 @@ CONV2D_API int conv2d_workspace_size_variant(const conv2d_params* params, int va
  * Enqueues on hip_stream and returns.  batch == 0 returns OK without a launch. */
 CONV2D_API int conv2d_forward(const conv2d_params* params, const void* in, const void* filt, void* out,
                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* conv2d_forward for callers that cannot allocate or pass scratch memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  (It follows no passage of the paper; it exists for those callers.)
+ * It runs the variant that conv2d_select_variant(params,
+ * CONV2D_SELECT_DIRECT_SUM_ONLY) names for pointers of this alignment, with
+ * that variant's scratch (repacked filter, partial sums of a split reduction)
+ * in an array of CONV2D_STATIC_SCRATCH_BYTES that the library itself holds in
+ * device memory, one copy on every GPU that loads the library, until the
+ * process ends.  The result is bit-identical to conv2d_forward_variant with
+ * that variant.  The call allocates and frees nothing and calls no allocating
+ * routine; it looks the array's address up once per device, at its first call
+ * on that device (make that call outside a stream capture).
+ *   - A layer whose variant needs more than CONV2D_STATIC_SCRATCH_BYTES
+ *     returns CONV2D_STATUS_SCRATCH_EXCEEDED and launches nothing (use
+ *     conv2d_forward with a workspace).  Every layer of this library's
+ *     workloads up to 3x3x512x512 filters fits.
+ *   - All calls on one GPU share that GPU's array, which keeps the previous
+ *     call's contents; no kernel relies on its initial contents.  Two calls
+ *     that may overlap on one GPU (different streams, or different threads
+ *     without ordering between their streams) race on it: order them.
+ *   - in, filt, out, hip_stream and the return value: as conv2d_forward. */
+#define CONV2D_STATIC_SCRATCH_BYTES (32u << 20)
+CONV2D_API int conv2d_forward_static_scratch(const conv2d_params* params, const void* in,
+                                             const void* filt, void* out, void* hip_stream);
 
 /* Same, with the variant forced (0 <= variant_id < conv2d_num_variants()).
  * Every variant that supports `params` produces the same result up to the
@@ -220,7 +247,7 @@ CONV2D_API const char* conv2d_variant_name(int variant_id);            /* NULL i
 CONV2D_API int conv2d_variant_supports(const conv2d_params* params, int variant_id); /* 1, 0, or <0 status */
 /* Debugging aid for the entry points that select a variant themselves and have
  * no forced-variant form (conv2d_forward_bias_act, conv2d_forward_bias_act_pool,
- * and conv2d_forward): from now on the calling
+ * conv2d_forward_static_scratch, and conv2d_forward): from now on the calling
  * thread's calls run `variant_id` wherever it supports the parameters and the
  * pointers' alignment, and their own pick elsewhere; -1 switches it off.  The
  * size queries of the same thread follow.  A thread starts with the value of

@@ -24,7 +24,8 @@ LIB_PATH = os.path.join(_HERE, "libconv2d_mi355x.so")
 
 EXPORTS = (
     "conv2d_get_geometry", "conv2d_workspace_size", "conv2d_workspace_size_variant",
-    "conv2d_forward", "conv2d_forward_variant", "conv2d_forward_bias_act",
+    "conv2d_forward", "conv2d_forward_static_scratch", "conv2d_forward_variant",
+    "conv2d_forward_bias_act",
     "conv2d_forward_bias_act_pool", "conv2d_pool_workspace_size",
     "conv2d_pool_workspace_size_variant", "conv2d_packed_filter_size", "conv2d_pack_filter",
     "conv2d_forward_packed", "conv2d_last_launch_error", "conv2d_debug_force_variant",
@@ -85,6 +86,7 @@ def lib():
         l.conv2d_workspace_size_variant.argtypes = [pp, ctypes.c_int, ctypes.POINTER(sz)]
         l.conv2d_forward.argtypes = [pp, vp, vp, vp, vp, sz, vp]
         l.conv2d_forward_variant.argtypes = [pp, vp, vp, vp, vp, sz, vp, ctypes.c_int]
+        l.conv2d_forward_static_scratch.argtypes = [pp, vp, vp, vp, vp]
         l.conv2d_debug_force_variant.argtypes = [ctypes.c_int]
         l.conv2d_num_variants.argtypes = []
         l.conv2d_variant_name.argtypes = [ctypes.c_int]
@@ -218,6 +220,17 @@ def conv2d_debug_force_variant(variant_id):
     rc = lib().conv2d_debug_force_variant(-1 if variant_id is None else int(variant_id))
     if rc:
         raise Conv2dError(rc, "conv2d_debug_force_variant")
+
+
+STATIC_SCRATCH_BYTES = 32 << 20   # CONV2D_STATIC_SCRATCH_BYTES
+STATUS_SCRATCH_EXCEEDED = -6
+
+
+def conv2d_forward_static_scratch_raw(params, in_ptr, filt_ptr, out_ptr, stream_handle=0):
+    """conv2d_forward_static_scratch on raw device pointers: no workspace argument, nothing is
+    allocated (the caller owns `out`); returns the status code without raising."""
+    return lib().conv2d_forward_static_scratch(ctypes.byref(params), in_ptr, filt_ptr, out_ptr,
+                                               stream_handle)
 
 
 ACT_NONE = 0

@@ -12,6 +12,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "conv2d_internal.h"
 
@@ -670,6 +671,41 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
 
 using namespace conv2d;
 
+// ---- scratch memory of the entry point that allocates nothing -------------------------------
+// conv2d_forward_static_scratch runs conv2d_forward's kernels with the repacked filter and the
+// partial sums of a split reduction in this array instead of a caller's workspace.  Every GPU
+// that loads the library holds its own copy until the process ends.  In host code the array's
+// name is only a handle for hipGetSymbolAddress; the device address is looked up once per
+// device and that pointer is what the kernels get.
+namespace {
+constexpr size_t kStaticScratchBytes = CONV2D_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+namespace {
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices] = {};
+
+// The current device's copy of `scratch`; null (and *err set) if the runtime refuses.
+void* static_scratch_of_current_device(hipError_t* err) {
+  int dev = 0;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kMaxDevices) {
+    *err = hipErrorInvalidDevice;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    *err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess) return nullptr;
+    scratch_ptr[dev] = ptr;
+  }
+  return scratch_ptr[dev];
+}
+}  // namespace
+
 extern "C" {
 
 int conv2d_get_geometry(const conv2d_params* params, conv2d_geometry* geometry) {
@@ -705,6 +741,30 @@ int conv2d_workspace_size_variant(const conv2d_params* params, int variant_id, s
 int conv2d_forward(const conv2d_params* params, const void* in, const void* filt, void* out,
                    void* workspace, size_t workspace_bytes, void* hip_stream) {
   return run(params, in, filt, out, workspace, workspace_bytes, hip_stream, -1);
+}
+
+int conv2d_forward_static_scratch(const conv2d_params* params, const void* in, const void* filt,
+                                  void* out, void* hip_stream) {
+  Problem q;
+  int rc = derive(params, &q);
+  if (rc) return rc;
+  if (q.N == 0) return CONV2D_STATUS_OK;
+  if (!in || !filt || !out) return CONV2D_STATUS_INVALID_ARGUMENT;
+  // conv2d_forward's pick among the direct-sum variants (the transform variants need several
+  // times the input as scratch), then the same kernels on the library's own array
+  const int id = pick(q, params->padding, aligned16(in, filt, out), kDirectSumOnly);
+  const size_t need = workspace_bytes_for(table().v[id], q);
+  if (need > kStaticScratchBytes) return CONV2D_STATUS_SCRATCH_EXCEEDED;
+  void* ws = nullptr;
+  if (need > 0) {
+    hipError_t e = hipSuccess;
+    ws = static_scratch_of_current_device(&e);
+    if (!ws) {
+      last_launch_error = e;
+      return CONV2D_STATUS_LAUNCH_FAILED;
+    }
+  }
+  return run(params, in, filt, out, ws, need, hip_stream, id);
 }
 
 int conv2d_forward_variant(const conv2d_params* params, const void* in, const void* filt, void* out,
@@ -876,6 +936,8 @@ const char* conv2d_status_string(int status) {
     case CONV2D_STATUS_WORKSPACE_TOO_SMALL: return "workspace too small";
     case CONV2D_STATUS_LAUNCH_FAILED: return "kernel launch failed";
     case CONV2D_STATUS_TOO_LARGE: return "tensor too large for 31-bit indexing";
+    case CONV2D_STATUS_SCRATCH_EXCEEDED:
+      return "layer needs more scratch than the library's static array holds";
   }
   return "unknown status";
 }

@@ -32,7 +32,7 @@ def test_library_exports_every_declared_symbol():
 def test_version_and_status_strings():
     assert B.conv2d_version() >= 100
     assert B.status_string(0) == "ok"
-    for code in (-1, -2, -3, -4, -5):
+    for code in (-1, -2, -3, -4, -5, -6):
         assert B.status_string(code) not in ("ok", "unknown status")
     assert B.status_string(-99) == "unknown status"
 
