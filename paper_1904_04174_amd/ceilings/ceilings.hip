@@ -176,6 +176,33 @@ __global__ __launch_bounds__(256) void lds_pattern_loop(unsigned* out, int iters
   clocks_end(c);
 }
 
+// Transposing 8-byte reads (ds_read_b64_tr_b16) at host-given per-lane byte offsets, eight in
+// flight per wave: offsets of read u are lane_offset[(u % 2) * 64 + lane] (the two reads that
+// make up one MFMA operand) plus (u / 2) * `step` bytes.
+__global__ __launch_bounds__(256) void lds_tr_pattern_loop(unsigned* out, int iters, Clocks* c,
+                                                           const int* lane_offset, int step) {
+  __shared__ __align__(16) unsigned char buf[65536];
+  for (int i = threadIdx.x; i < 16384; i += 256) reinterpret_cast<unsigned*>(buf)[i] = i;
+  __syncthreads();
+  clocks_begin(c);
+  typedef __attribute__((address_space(3))) shortx4* lds_ptr;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const unsigned char* b0 = buf + wave * 16384 + lane_offset[lane];
+  const unsigned char* b1 = buf + wave * 16384 + lane_offset[64 + lane];
+  unsigned acc = 0;
+  for (int it = 0; it < iters; ++it) {
+    shortx4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      v[u] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)((u % 2 ? b1 : b0) + (u / 2) * step));
+    asm volatile("" ::"v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "v"(v[4]), "v"(v[5]),
+                 "v"(v[6]), "v"(v[7]));
+    acc += static_cast<unsigned>(v[0].x);
+  }
+  out[blockIdx.x * 256 + threadIdx.x] = acc;
+  clocks_end(c);
+}
+
 // ---- streaming: 16 bytes per lane, grid-stride
 template <int KIND>  // 0 copy, 1 read, 2 write, 3 copy with non-temporal stores
 __global__ __launch_bounds__(256) void stream_loop(const uintx4* __restrict__ a,
@@ -318,7 +345,15 @@ __attribute__((visibility("default"))) int conv2d_ceilings_measure(void* out, in
         {"lds frag 128B rows, 32-row blk, swz r&7", 128, 32, 0},
         {"lds frag 128B rows, 16-row blk, swz (r>>1)&7", 128, 16, 1},
         {"lds frag 128B rows, 16-row blk, swz r&7", 128, 16, 0},
+        {"lds frag planes, 32-row blk, plane stride 1024", 0, 32, 1024},
+        {"lds frag planes, 32-row blk, plane stride 1024+256", 0, 32, 1024 + 256},
+        {"lds frag planes, 16-row blk, plane stride 512", 0, 16, 512},
+        {"lds frag planes, 16-row blk, plane stride 512+64", 0, 16, 512 + 64},
+        {"lds frag planes, 16-row blk, plane stride 512+128", 0, 16, 512 + 128},
     };
+    // (rowb == 0: "planes": consecutive 16-byte entries per k chunk, chunk c of every entry
+    // `shift` bytes after chunk c - 1: the patch layout of the 3x3 kernels, where the plane
+    // stride is a multiple of 256 bytes, or that plus a pad)
     int* d_off = nullptr;
     CHECK(hipMalloc(&d_off, 64 * sizeof(int)));
     for (const P& q : ps) {
@@ -326,7 +361,10 @@ __attribute__((visibility("default"))) int conv2d_ceilings_measure(void* out, in
       const int cpr = q.rowb / 16;
       for (int l = 0; l < 64; ++l) {
         const int row = l % q.rows, chunk = l / q.rows;
-        off[l] = (row * q.rowb + ((chunk ^ ((row >> q.shift) & (cpr - 1))) * 16)) % 2048;
+        if (q.rowb == 0)
+          off[l] = row * 16 + chunk * q.shift;
+        else
+          off[l] = (row * q.rowb + ((chunk ^ ((row >> q.shift) & (cpr - 1))) * 16)) % 2048;
       }
       CHECK(hipMemcpy(d_off, off, sizeof(off), hipMemcpyHostToDevice));
       const int lw = cus * 2, li = 4000;
@@ -336,6 +374,52 @@ __attribute__((visibility("default"))) int conv2d_ceilings_measure(void* out, in
         return -1;
       CHECK(hipMemcpy(&h, clk, sizeof(h), hipMemcpyDeviceToHost));
       const double bytes = 1.0 * lw * 256 * li * 8 * 16;
+      const double mhz = core_mhz(h);
+      col.add(q.name, mhz > 0 ? bytes / (ms * 1e-3) / cus / (mhz * 1e6) : 0.0, "B/clk/CU");
+    }
+    CHECK(hipFree(d_off));
+  }
+  // transposing reads of an MFMA operand whose 8 k values per lane lie in 8 different LDS rows
+  // (the filter as it lies in memory: a row = one k, features contiguous).  A 16-lane group
+  // reads 4 rows x 32 bytes; piece j of row k is stored at piece position j ^ swizzle(k).
+  {
+    struct Q { const char* name; int row_bytes, blk, swz; };
+    const Q qs[] = {
+        {"lds tr-read, 256B rows, 16-row blk, no swizzle", 256, 16, 0},
+        {"lds tr-read, 256B rows, 16-row blk, swz k&3|k>>3&1<<2", 256, 16, 1},
+        {"lds tr-read, 128B rows, 16-row blk, swz k>>1&1|k>>3&1<<1", 128, 16, 2},
+        {"lds tr-read, 512B rows, 16-row blk, swz k&3|k>>3&1<<2", 512, 16, 1},
+        {"lds tr-read, 256B rows, 32-row blk, swz (k&3)<<1", 256, 32, 3},
+        {"lds tr-read, 512B rows, 32-row blk, swz (k&3)<<1", 512, 32, 3},
+        {"lds tr-read, 128B rows, 32-row blk, swz (k>>1&1)<<1", 128, 32, 4},
+    };
+    int* d_off = nullptr;
+    CHECK(hipMalloc(&d_off, 128 * sizeof(int)));
+    for (const Q& q : qs) {
+      int off[128];
+      for (int r = 0; r < 2; ++r)
+        for (int l = 0; l < 64; ++l) {
+          const int a = l % 16;
+          int k, piece;
+          if (q.blk == 16) { k = 8 * (l / 16) + 4 * r + a / 4; piece = 0; }
+          else { k = 8 * (l / 32) + 4 * r + a / 4; piece = (l / 16) % 2; }
+          int sw = 0;
+          if (q.swz == 1) sw = (k & 3) | (((k >> 3) & 1) << 2);
+          if (q.swz == 2) sw = ((k >> 1) & 1) | (((k >> 3) & 1) << 1);
+          if (q.swz == 3) sw = (k & 3) << 1;
+          if (q.swz == 4) sw = ((k >> 1) & 1) << 1;
+          off[r * 64 + l] = k * q.row_bytes + 32 * (piece ^ sw) + 8 * (a % 4);
+        }
+      CHECK(hipMemcpy(d_off, off, sizeof(off), hipMemcpyHostToDevice));
+      // (further reads of the loop: the next feature block, 2 pieces on for 32-row blocks)
+      const int step = q.row_bytes >= 256 ? 64 : 0;
+      const int lw = cus * 2, li = 4000;
+      lds_tr_pattern_loop<<<lw, 256>>>(reinterpret_cast<unsigned*>(fout), 10, clk, d_off, step);
+      CHECK(hipDeviceSynchronize());
+      if (timed([&] { lds_tr_pattern_loop<<<lw, 256>>>(reinterpret_cast<unsigned*>(fout), li, clk, d_off, step); }, &ms))
+        return -1;
+      CHECK(hipMemcpy(&h, clk, sizeof(h), hipMemcpyDeviceToHost));
+      const double bytes = 1.0 * lw * 256 * li * 8 * 8;
       const double mhz = core_mhz(h);
       col.add(q.name, mhz > 0 ? bytes / (ms * 1e-3) / cus / (mhz * 1e6) : 0.0, "B/clk/CU");
     }

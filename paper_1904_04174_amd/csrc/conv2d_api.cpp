@@ -401,7 +401,7 @@ double model_cost(const Variant& v, const Problem& q) {
   const double stream =
       (es * (1.0 * q.N * q.H * q.W * q.C + 1.0 * q.Kg * q.K) + 4.0 * q.M * q.K) / kChipBytesPerClock;
   double cost = (compute > stream ? compute : stream) + rounds * (g.pro + g.epi * area) + extra;
-  if (v.family == kDma) {
+  if (v.family == kDma && !igemm_dma_tile_native(v.bf16, v.tile)) {
     ++kernels;
     cost += kRepackPerByte * es * q.Kg * q.K;
   }

@@ -114,6 +114,9 @@ bool igemm_dma_tile_fits(const Problem& p, int bf16, int tile);  // extra shape 
 // activation after the maximum: both are monotone) and stores the pooled
 // tensor only.
 bool igemm_dma_tile_pools(int bf16, int tile);
+// Tiles that read the filter as it lies in memory (no repacked copy, no launch before the
+// convolution); their packed filter is a plain copy.
+bool igemm_dma_tile_native(int bf16, int tile);
 // The repacked filter of a tile (slice-major, k contiguous, zero padded to whole slices) as a
 // tensor of its own: its size and the kernel that writes it from p.filt.  A launch with
 // Problem::packed_filt set to it skips its own repack.

@@ -1015,9 +1015,27 @@ size_t workspace_bytes(const Problem& p, int splits) {
 // 77 % full against 87.5 %).  The blocks are computed transposed (filter
 // fragment as the first operand), so a lane ends up with four consecutive
 // features of one pixel and stores them as one 16-byte vector.
+//
+// Native filter (NATIVE, bf16 16-row tiles): the filter slice is loaded as it lies in memory,
+// BK rows (one per k) of BN consecutive features, and the MFMA operand (8 consecutive k of one
+// feature per lane) is formed by two transposing LDS reads (ds_read_b64_tr_b16: the 16 lanes of
+// a group hand in 4 rows x 16 features and each gets the 4 rows of its feature).  No repacked
+// copy of the filter, no workspace and no launch before the convolution.  A group's read
+// touches 4 rows at one feature offset, 16 row pieces of 32 bytes per wavefront, which would all
+// start at the same bank (the rows are a multiple of 256 bytes apart), so the 32-byte piece j
+// of row k is stored at piece position j ^ native_swizzle(k): measured 200 bytes per clock and
+// compute unit against 32 unswizzled.
 template <bool BF16_, int BM_, int BN_, int WAVES_M_, int WAVES_N_, int PATCH_ROWS_,
-          bool TWO_LEVEL_, int OCC_, int BW_ = 0, bool MF16_ = false>
+          bool TWO_LEVEL_, int OCC_, int BW_ = 0, bool MF16_ = false, bool NATIVE_ = false>
 struct PatchTile {
+  static constexpr bool NATIVE = NATIVE_;
+  static_assert(!NATIVE_ || (BF16_ && MF16_ && BN_ % 64 == 0), "native filter: bf16 16-row tiles");
+  static constexpr int B_ROW_BYTES = BN_ * 2;      // NATIVE: a filter row (one k) in LDS
+  // NATIVE: XOR of the 32-byte piece index of filter row k (rows of at least 8 pieces: the 4
+  // rows of a lane group and the group 8 rows on get 8 different positions; 4 pieces: 2 bits)
+  static constexpr int native_swizzle(int k) {
+    return BN_ >= 128 ? ((k & 3) | (((k >> 3) & 1) << 2)) : (((k >> 1) & 1) | (((k >> 3) & 1) << 1));
+  }
   static constexpr bool BF16 = BF16_;
   static constexpr int BM = BM_, BN = BN_;
   static constexpr int BW = BW_;                       // 0: BM consecutive output pixels
@@ -1161,12 +1179,15 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
 #pragma unroll
   for (int i = 0; i < T::A_PASSES; ++i) {
     if constexpr (T::BW == 0) {
-      const long long v = v0 + (T::BY_PLANE ? i : i * T::NW + wave) * 64 + lane;
-      const int w = static_cast<int>(v % Wp) - p.pl;
-      const long long t = v / Wp;
-      const int h = static_cast<int>(t % Hp) - p.pt;
-      const long long n = t / Hp;
-      const bool ok = n < p.N && static_cast<unsigned>(h) < static_cast<unsigned>(p.H) &&
+      // (32-bit arithmetic: padded pixel indices stay far below 2^31 for tensors that the
+      // host accepts, and 64-bit divisions here were a third of a workgroup's start-up time)
+      const unsigned v = static_cast<unsigned>(v0) + (T::BY_PLANE ? i : i * T::NW + wave) * 64 + lane;
+      const unsigned t = v / static_cast<unsigned>(Wp);
+      const int w = static_cast<int>(v - t * Wp) - p.pl;
+      const unsigned n = t / static_cast<unsigned>(Hp);
+      const int h = static_cast<int>(t - n * Hp) - p.pt;
+      const bool ok = n < static_cast<unsigned>(p.N) &&
+                      static_cast<unsigned>(h) < static_cast<unsigned>(p.H) &&
                       static_cast<unsigned>(w) < static_cast<unsigned>(p.W);
       a_voff[i] = ok ? static_cast<int>(((n * p.H + h) * p.W + w) * p.C * ES) : kOutOfRange;
     }
@@ -1178,14 +1199,42 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   auto filter_offsets = [&](int col0, int (&voff)[T::B_ITERS]) {
 #pragma unroll
     for (int i = 0; i < T::B_ITERS; ++i) {
-      const int n = col0 + ld_row0 + i * T::B_ROWS_PER_PASS;
-      voff[i] = (n < p.K) ? (n * BK + ld_chunk * VEC) * ES : kOutOfRange;
+      if constexpr (T::NATIVE) {
+        // 16-byte chunk q of the stage: row k = q / chunks per row, position q % chunks per
+        // row, which holds the chunk of features [8c, 8c + 8) with c = position ^ swizzle
+        constexpr int CH = BN / 8;
+        const int q = i * T::NT + tid;
+        const int k = q / CH;
+        const int c = (q % CH) ^ (T::native_swizzle(k) << 1);
+        const int n = col0 + 8 * c;
+        voff[i] = (n + 8 <= p.K) ? (k * p.K + n) * ES : kOutOfRange;
+      } else {
+        const int n = col0 + ld_row0 + i * T::B_ROWS_PER_PASS;
+        voff[i] = (n < p.K) ? (n * BK + ld_chunk * VEC) * ES : kOutOfRange;
+      }
     }
   };
   filter_offsets(n0, b_voff);
   const int k_slice_bytes = p.K * ROWB;
   const int k_last_bytes = (nblocks * taps - 1) * k_slice_bytes;
   int k_next_bytes = 0;         // filter slice to load next; wraps into the next tile's
+  // NATIVE: the slices are visited channel block by channel block, all taps of a block; slice
+  // (block, tap) starts at filter row tap * C + block * BK
+  int nat_tap = 0, nat_block_bytes = 0;
+  const int nat_tap_bytes = p.C * p.K * ES;
+  // Moves the filter load position one slice on (past the last slice: to the first again).
+  auto next_filter_slice = [&]() {
+    if constexpr (T::NATIVE) {
+      // (selects, not branches: the position stays in scalar registers)
+      const bool wrap = ++nat_tap == taps;
+      nat_tap = wrap ? 0 : nat_tap;
+      const int next_block = nat_block_bytes + BK * p.K * ES;
+      nat_block_bytes = wrap ? (next_block >= nat_tap_bytes ? 0 : next_block) : nat_block_bytes;
+      k_next_bytes = wrap ? nat_block_bytes : k_next_bytes + nat_tap_bytes;
+    } else {
+      k_next_bytes = k_next_bytes >= k_last_bytes ? 0 : k_next_bytes + k_slice_bytes;
+    }
+  };
   int a_next_block_bytes = 0;   // channel offset (bytes) of the patch being loaded
   // Persistent tiles: the loads of a tile's last channel block (patch) and last SB slices
   // (filter) fetch the workgroup's next tile's (or nothing: out-of-range offsets); the loader
@@ -1196,7 +1245,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
 
   auto load_b = [&](int stage, int i) {
     dma16(bt_rsrc, ring_base + B_REGION + stage * T::B_STAGE_BYTES + i * T::B_ROWS_PER_PASS * ROWB,
-          b_voff[i], k_next_bytes);
+          b_voff[i], T::NATIVE ? __builtin_amdgcn_readfirstlane(k_next_bytes) : k_next_bytes);
   };
   // patch load number j (pass j / CPR, plane j % CPR) into patch buffer `buf`
   auto load_a = [&](int buf, int j) {
@@ -1236,6 +1285,17 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
 #pragma unroll
   for (int kk = 0; kk < KSTEPS; ++kk) chunk_bytes[kk] = ((2 * kk + lk) ^ frag_swz) * 16;
 
+  // NATIVE: lane (feature lr of a block, k group lk) hands in the address of row
+  // 8 * lk + lr / 4 (+ 4 for the second read), features 4 * (lr % 4) ... of the block
+  int nat_row_off = 0, nat_piece_off[T::NATIVE ? TN : 1] = {};
+  if constexpr (T::NATIVE) {
+    const int k = 8 * lk + lr / 4;
+    nat_row_off = k * T::B_ROW_BYTES + 8 * (lr % 4);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      nat_piece_off[j] = 32 * ((wn * TN + j) ^ T::native_swizzle(k));
+  }
+
   uintx4 af[2][TM], bf[2][TN];
   int a_buf_off = 0;  // byte offset of the patch buffer being read (0 or PATCH_BYTES)
 
@@ -1244,12 +1304,24 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   auto read_frag = [&](auto buf_c, int a_off, int bstage, int kk, int r) {
     constexpr int buf = decltype(buf_c)::value;
     // (16-row blocks: one buffer for the A fragments, two only for the last)
-    if (r < TM)
+    if (r < TM) {
       af[T::MF16 && r < TM - 1 ? 0 : buf][r] = *reinterpret_cast<const uintx4*>(
           ring + a_frag[r] + a_off + 2 * kk * T::PLANE_BYTES);
-    else
+    } else if constexpr (T::NATIVE) {
+      typedef short shortx4 __attribute__((ext_vector_type(4)));
+      typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+      typedef __attribute__((address_space(3))) shortx4* lds_ptr;
+      const unsigned char* src = ring + B_REGION + bstage * T::B_STAGE_BYTES + nat_row_off +
+                                 nat_piece_off[r - TM];
+      const uintx2 lo = __builtin_bit_cast(
+          uintx2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(src)));
+      const uintx2 hi = __builtin_bit_cast(
+          uintx2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(src + 4 * T::B_ROW_BYTES)));
+      bf[buf][r - TM] = uintx4{lo.x, lo.y, hi.x, hi.y};
+    } else {
       bf[buf][r - TM] = *reinterpret_cast<const uintx4*>(
           b_frag + bstage * T::B_STAGE_BYTES + (r - TM) * BLK * ROWB + chunk_bytes[kk]);
+    }
   };
   auto mfma = [&](auto buf_c, int m) {
     constexpr int buf = decltype(buf_c)::value;
@@ -1358,7 +1430,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
             } else if (item <= 1 + TN + T::B_ITERS + a_n) {
               load_a(a_load_buf, a_from + item - TN - T::B_ITERS - 2);
             } else {
-              k_next_bytes = k_next_bytes >= k_last_bytes ? 0 : k_next_bytes + k_slice_bytes;
+              next_filter_slice();
             }
           },
           [&](int i) { read_frag(Nxt{}, a_nxt, (bstage + 1) % SB, 0, i); });
@@ -1377,7 +1449,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
       } else if (item <= NR + T::B_ITERS + a_n) {
         load_a(a_load_buf, a_from + item - NR - T::B_ITERS - 1);
       } else {
-        k_next_bytes = k_next_bytes >= k_last_bytes ? 0 : k_next_bytes + k_slice_bytes;
+        next_filter_slice();
       }
     });
     }
@@ -1418,7 +1490,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   for (int s = 0; s < SB; ++s) {
 #pragma unroll
     for (int i = 0; i < T::B_ITERS; ++i) load_b(s, i);
-    k_next_bytes = k_next_bytes >= k_last_bytes ? 0 : k_next_bytes + k_slice_bytes;
+    next_filter_slice();
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm((SB - 1) * T::B_ITERS));
   __builtin_amdgcn_s_barrier();
@@ -1760,7 +1832,10 @@ long long patch_rows_needed(const Problem& p) {
 template <class T>
 bool patch_fits(const Problem& p) {
   if (!(p.R == 3 && p.S == 3 && p.sr == 1 && p.sc == 1 && p.C % T::BK == 0)) return false;
+  if (T::NATIVE && p.K % 8 != 0) return false;  // 16-byte chunks of a filter row
   if (T::BW > 0) return true;  // a block's patch always fits
+  // (the kernel indexes the padded images' pixels with 32 bits)
+  if (1LL * p.N * (p.P + p.R - 1) * (p.Q + p.S - 1) + T::PATCH_ROWS >= (1LL << 31)) return false;
   return patch_rows_needed<T>(p) <= T::PATCH_ROWS;
 }
 
@@ -1774,9 +1849,10 @@ int patch_tiles_m(const Problem& p) {
 template <class T, bool OUT_BF16>
 hipError_t launch_patch_one(const Problem& p, hipStream_t stream) {
   // 1. filter -> Bt[slice][K][BK], channel block by channel block, unless packed before
-  const void* bt = p.packed_filt ? p.packed_filt : p.workspace;
+  // (native tiles read the filter as it is; their "packed" filter is a plain copy)
+  const void* bt = p.packed_filt ? p.packed_filt : (T::NATIVE ? p.filt : p.workspace);
   hipError_t e = hipSuccess;
-  if (!p.packed_filt) {
+  if (!p.packed_filt && !T::NATIVE) {
     dim3 rgrid(p.Kg / T::BK, (p.K + 63) / 64);
     if (T::BF16)
       hipLaunchKernelGGL((repack_filter_kernel<unsigned short>), rgrid, dim3(256), 0, stream,
@@ -1813,6 +1889,7 @@ hipError_t launch_patch(const Problem& p, int, hipStream_t stream) {
 
 template <class T>
 size_t workspace_bytes_patch(const Problem& p, int) {
+  if (T::NATIVE) return 0;
   return (static_cast<size_t>(p.Kg) * p.K * T::ES + 255) / 256 * 256;
 }
 
@@ -1825,6 +1902,7 @@ struct TileEntry {
   bool (*fits)(const Problem&);  // extra shape condition of a tile, or null
   hipError_t (*wino)(const Problem&, hipStream_t);  // fused Winograd products, or null
   bool pools = false;                               // 2x2 pooling in the epilogue
+  bool native = false;                              // reads the filter as it lies: no repack
 };
 
 #define CONV2D_PATCH_TILE(dt, isbf, bm, bn, wm, wn, rows, two, occ)                              \
@@ -1848,6 +1926,16 @@ struct TileEntry {
     &launch_patch<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true>>,                  \
     &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true>>,         \
     &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true>>, nullptr }
+
+// 16-row tiles that read the filter as it lies in memory (transposing LDS reads): bw = 0 for
+// consecutive pixels
+#define CONV2D_PATCH_TILE_M16N(dt, isbf, bm, bn, wm, wn, rows, occ, bw, tag)                     \
+  { "igemm_patch_" dt "_" #bm "x" #bn "_w" #wm "x" #wn "_p" #rows tag "_m16_nat", bm, bn,        \
+    PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true, true>::BK, occ, 3,               \
+    &launch_patch<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true, true>>,            \
+    &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true, true>>,   \
+    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true, true>>, nullptr,     \
+    false, true }
 
 // blocked patch tiles: bm / bw x bw output pixels of one image
 #define CONV2D_PATCH_TILE_B(dt, isbf, bm, bn, wm, wn, rows, two, occ, bw)                        \
@@ -1894,6 +1982,8 @@ const TileEntry kTilesBf16[] = {
     CONV2D_PATCH_TILE("bf16", true, 224, 256, 1, 4, 512, false, 1),
     CONV2D_PATCH_TILE_M16("bf16", true, 224, 128, 2, 2, 384, 2),
     CONV2D_PATCH_TILE_M16B("bf16", true, 224, 128, 2, 2, 384, 2, 16),
+    CONV2D_PATCH_TILE_M16N("bf16", true, 224, 128, 2, 2, 384, 2, 0, ""),
+    CONV2D_PATCH_TILE_M16N("bf16", true, 224, 128, 2, 2, 384, 2, 16, "_b16"),
     CONV2D_PATCH_TILE_B("bf16", true, 256, 256, 4, 2, 512, false, 1, 16),
     CONV2D_PATCH_TILE_B("bf16", true, 256, 128, 4, 2, 512, false, 1, 16),
     CONV2D_PATCH_TILE_B("bf16", true, 256, 64, 4, 1, 512, false, 2, 16),
@@ -1936,14 +2026,20 @@ bool igemm_dma_tile_fits(const Problem& p, int bf16, int tile) {
 }
 bool igemm_dma_tile_has_wino(int bf16, int tile) { return entry(bf16, tile).wino != nullptr; }
 bool igemm_dma_tile_pools(int bf16, int tile) { return entry(bf16, tile).pools; }
+bool igemm_dma_tile_native(int bf16, int tile) { return entry(bf16, tile).native; }
 size_t igemm_dma_packed_filter_bytes(const Problem& p, int bf16, int tile) {
   const TileEntry& t = entry(bf16, tile);
+  if (t.native)  // a plain copy of the filter
+    return (static_cast<size_t>(p.Kg) * p.K * (bf16 ? 2 : 4) + 255) / 256 * 256;
   const size_t kg_p = static_cast<size_t>((p.Kg + t.bk - 1) / t.bk) * t.bk;
   return (kg_p * p.K * (bf16 ? 2 : 4) + 255) / 256 * 256 * (p.batches > 1 ? p.batches : 1);
 }
 hipError_t igemm_dma_pack_filter(const Problem& p, int bf16, int tile, void* packed,
                                  hipStream_t stream) {
   const TileEntry& t = entry(bf16, tile);
+  if (t.native)
+    return hipMemcpyAsync(packed, p.filt, static_cast<size_t>(p.Kg) * p.K * (bf16 ? 2 : 4),
+                          hipMemcpyDeviceToDevice, stream);
   const int Kg_p = (p.Kg + t.bk - 1) / t.bk * t.bk;
   // uniform and patch tiles walk the reduction channel block by channel block
   const int block = (t.addr == kUniform || t.addr == 3) ? t.bk : 0;
