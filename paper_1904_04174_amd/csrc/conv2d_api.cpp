@@ -203,6 +203,7 @@ bool supports(const Variant& v, const Problem& q) {
   if (igemm_dma_tile_addressing(v.bf16, v.tile) == 3 &&
       (v.split != kWhole || !igemm_dma_tile_fits(q, v.bf16, v.tile)))
     return false;
+  if (igemm_dma_tile_native(v.bf16, v.tile) && !igemm_dma_tile_fits(q, v.bf16, v.tile)) return false;
   if (v.split == kSplit && (q.Kg + bk - 1) / bk < 2) return false;
   if (v.split == kTail) {
     // A balanced tail needs tiles left over after whole rounds of the 256

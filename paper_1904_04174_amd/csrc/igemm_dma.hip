@@ -128,9 +128,20 @@ __device__ __forceinline__ void dma4(const uintx4& rsrc, unsigned lds_base, int 
 //   kElement  any C (fp32 only): 4-byte loads, (r,s,c) per lane and element
 constexpr int kUniform = 0, kVector = 1, kElement = 2;
 
+// NATIVE (bf16 uniform tiles): the filter slice is loaded as it lies in memory, BK rows (one
+// per k) of BN consecutive features, and the B fragments are formed by transposing LDS reads
+// (see the patch tiles below): no repacked filter, no launch before the convolution.
 template <bool BF16_, int BM_, int BN_, int ROWB_, int WAVES_M_, int WAVES_N_, int STAGES_,
-          bool TWO_LEVEL_, int OCC_, int ADDR_>
+          bool TWO_LEVEL_, int OCC_, int ADDR_, bool NATIVE_ = false>
 struct DmaTile {
+  static constexpr bool NATIVE = NATIVE_;
+  static_assert(!NATIVE_ || (BF16_ && ADDR_ == 0 && BN_ % 64 == 0), "native filter: bf16 uniform tiles");
+  static constexpr int B_ROW_BYTES = BN_ * 2;   // NATIVE: a filter row (one k) in LDS
+  // NATIVE: XOR of the 32-byte piece index of filter row k.  A 32-row block's read takes, per
+  // half wavefront, 4 rows x 2 adjacent pieces: the XOR moves pairs of pieces (bit 0 clear).
+  static constexpr int native_swizzle(int k) {
+    return BN_ >= 128 ? ((k & 3) << 1) : (((k >> 1) & 1) << 1);
+  }
   static constexpr bool BF16 = BF16_;
   static constexpr int BM = BM_, BN = BN_;
   static constexpr int ROWB = ROWB_;             // bytes of k per LDS row = one slice
@@ -408,8 +419,19 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   int b_voff[T::B_ITERS];
 #pragma unroll
   for (int i = 0; i < T::B_ITERS; ++i) {
-    const int n = n0 + ld_row0 + i * T::ROWS_PER_PASS;
-    b_voff[i] = (n < p.K) ? (n * BK + ld_chunk * VEC) * ES : kOutOfRange;
+    if constexpr (T::NATIVE) {
+      // 16-byte chunk q of the stage's filter part: row k = q / chunks per row; its position
+      // q % chunks per row holds the features [8c, 8c + 8) with c = position ^ swizzle
+      constexpr int CH = BN / 8;
+      const int q = i * T::NT + tid;
+      const int k = q / CH;
+      const int c = (q % CH) ^ (T::native_swizzle(k) << 1);
+      const int n = n0 + 8 * c;
+      b_voff[i] = (n + 8 <= p.K) ? (k * p.K + n) * ES : kOutOfRange;
+    } else {
+      const int n = n0 + ld_row0 + i * T::ROWS_PER_PASS;
+      b_voff[i] = (n < p.K) ? (n * BK + ld_chunk * VEC) * ES : kOutOfRange;
+    }
   }
   // Position of the next slice to load.  UNIFORM: scalar tap index and channel
   // offset.  Otherwise (r, s, c) of this lane's chunk, stepped without division.
@@ -442,6 +464,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   const int k_slice_bytes = p.K * ROWB;
   const int k_last_bytes = (nslices_all - 1) * k_slice_bytes;
   int k_next_bytes = min(slice_begin * k_slice_bytes, k_last_bytes);
+  // NATIVE: slice (channel block, tap) starts at filter row tap * C + channel offset
+  if constexpr (T::NATIVE)
+    k_next_bytes = tap_c < p.C ? (tap_idx * p.C + tap_c) * p.K * ES : 0;
 
   // One A load (row pass i) of the slice at the current position into `stage`.
   auto load_a = [&](int stage, int i) {
@@ -465,7 +490,8 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   };
   auto load_b = [&](int stage, int i) {
     const unsigned dst = ring_base + stage * T::STAGE_BYTES + (BM + i * T::ROWS_PER_PASS) * ROWB;
-    dma16(bt_rsrc, dst, b_voff[i], k_next_bytes);
+    dma16(bt_rsrc, dst, b_voff[i],
+          T::NATIVE ? __builtin_amdgcn_readfirstlane(k_next_bytes) : k_next_bytes);
   };
   // Moves the load position one slice on.
   auto advance = [&]() {
@@ -487,6 +513,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
       // windows have at most 31 taps here, so bit 31 is clear in every mask:
       // past the last channel block every row reads as out of range
       tap_bit = tap_c < p.C ? tap_idx : 31;
+      // (past the end: the first slice again, into a stage nobody reads)
+      if constexpr (T::NATIVE)
+        k_next_bytes = tap_c < p.C ? (tap_idx * p.C + tap_c) * p.K * ES : 0;
     } else {
       kc += step_c;
       const int carry_c = kc >= p.C;
@@ -538,16 +567,39 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   for (int kk = 0; kk < KSTEPS; ++kk) chunk_bytes[kk] = ((2 * kk + lk) ^ frag_swz) * 16;
 
   uintx4 af[2][TM], bf[2][TN];  // double-buffered MFMA fragments
+  // NATIVE: lane (feature lane % 16 of half block (lane / 16) % 2, k group lk) hands in the
+  // address of row 16 * kk + 8 * lk + (lane % 16) / 4 (+ 4 for the second read), features
+  // 4 * (lane % 4) ... of its 16-feature piece
+  int nat_row_off = 0, nat_piece_off[T::NATIVE ? TN : 1] = {};
+  if constexpr (T::NATIVE) {
+    const int a = lane & 15, k = 8 * lk + a / 4;
+    nat_row_off = BM * ROWB + k * T::B_ROW_BYTES + 8 * (a % 4);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      nat_piece_off[j] = 32 * ((2 * (wn * TN + j) + ((lane >> 4) & 1)) ^ T::native_swizzle(k));
+  }
 
   // Fragment read number r (A blocks first, then B blocks) of step kk of `stage`.
   auto read_frag = [&](auto buf_c, int stage, int kk, int r) {
     constexpr int buf = decltype(buf_c)::value;
-    if (r < TM)
+    if (r < TM) {
       af[buf][r] = *reinterpret_cast<const uintx4*>(a_frag + stage * T::STAGE_BYTES +
                                                     r * 32 * ROWB + chunk_bytes[kk]);
-    else
+    } else if constexpr (T::NATIVE) {
+      typedef short shortx4 __attribute__((ext_vector_type(4)));
+      typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+      typedef __attribute__((address_space(3))) shortx4* lds_ptr;
+      const unsigned char* src = ring + stage * T::STAGE_BYTES + nat_row_off +
+                                 nat_piece_off[r - TM] + 16 * kk * T::B_ROW_BYTES;
+      const uintx2 lo = __builtin_bit_cast(
+          uintx2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(src)));
+      const uintx2 hi = __builtin_bit_cast(
+          uintx2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(src + 4 * T::B_ROW_BYTES)));
+      bf[buf][r - TM] = uintx4{lo.x, lo.y, hi.x, hi.y};
+    } else {
       bf[buf][r - TM] = *reinterpret_cast<const uintx4*>(b_frag + stage * T::STAGE_BYTES +
                                                          (r - TM) * 32 * ROWB + chunk_bytes[kk]);
+    }
   };
   // MFMA number m of a step.
   auto mfma = [&](auto buf_c, int m) {
@@ -843,6 +895,7 @@ __global__ __launch_bounds__(256) void tail_reduce_kernel(const float* __restric
 // Bytes of the repacked filter at the head of the workspace (a multiple of 256).
 template <class T>
 size_t filter_bytes(const Problem& p) {
+  if (T::NATIVE) return 0;  // no repacked copy
   const size_t kg_p = static_cast<size_t>((p.Kg + T::BK - 1) / T::BK) * T::BK;
   return (kg_p * p.K * T::ES + 255) / 256 * 256;
 }
@@ -890,9 +943,11 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   const int batches = p.batches > 1 ? p.batches : 1;
   if (batches > 1 && splits != 1) return hipErrorInvalidValue;  // batched: whole tiles only
   // 1. filter -> Bt[K][Kg_p] in the workspace (one per batch), unless the caller packed it before
-  const void* bt = p.packed_filt ? p.packed_filt : p.workspace;
+  // (native tiles read the filter as it is; their "packed" filter is a plain copy)
+  if (T::NATIVE && (p.K % 8 != 0 || batches > 1)) return hipErrorInvalidValue;
+  const void* bt = p.packed_filt ? p.packed_filt : (T::NATIVE ? p.filt : p.workspace);
   hipError_t e = hipSuccess;
-  if (!p.packed_filt) {
+  if (!p.packed_filt && !T::NATIVE) {
     dim3 rgrid(Kg_p / T::BK, (p.K + 63) / 64, batches);
     const long long bt_stride = static_cast<long long>(filter_bytes<T>(p) / T::ES);
     if (T::BF16)
@@ -1893,6 +1948,9 @@ size_t workspace_bytes_patch(const Problem& p, int) {
   return (static_cast<size_t>(p.Kg) * p.K * T::ES + 255) / 256 * 256;
 }
 
+// Extra shape condition of the native gather tiles: 16-byte chunks of a filter row.
+bool native_fits(const Problem& p) { return p.K % 8 == 0 && p.batches <= 1; }
+
 struct TileEntry {
   const char* name;
   int bm, bn, bk, occ;
@@ -1946,6 +2004,14 @@ struct TileEntry {
     &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw>>, nullptr,                   \
     PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw>::POOLS }
 
+// bf16 uniform tiles that read the filter as it lies in memory
+#define CONV2D_DMA_TILE_N(dt, bm, bn, rowb, wm, wn, st, occ)                                    \
+  { "igemm_dma_" dt "_" #bm "x" #bn "_r" #rowb "_w" #wm "x" #wn "_s" #st "_nat", bm, bn,        \
+    DmaTile<true, bm, bn, rowb, wm, wn, st, false, occ, kUniform, true>::BK, occ, kUniform,     \
+    &launch<DmaTile<true, bm, bn, rowb, wm, wn, st, false, occ, kUniform, true>>,               \
+    &workspace_bytes<DmaTile<true, bm, bn, rowb, wm, wn, st, false, occ, kUniform, true>>,      \
+    &native_fits, nullptr, false, true }
+
 #define CONV2D_DMA_TILE(dt, isbf, bm, bn, rowb, wm, wn, st, two, occ, addr, tag)                \
   { "igemm_dma_" dt "_" #bm "x" #bn "_r" #rowb "_w" #wm "x" #wn "_s" #st tag, bm, bn,           \
     DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, addr>::BK, occ, addr,                     \
@@ -1998,6 +2064,12 @@ const TileEntry kTilesBf16[] = {
     CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 4, false, 4, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 3, false, 6, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 64, 64, 128, 2, 2, 4, false, 2, kUniform, ""),
+    CONV2D_DMA_TILE_N("bf16", 256, 128, 64, 4, 2, 3, 2),
+    CONV2D_DMA_TILE_N("bf16", 128, 128, 64, 2, 2, 4, 2),
+    CONV2D_DMA_TILE_N("bf16", 128, 64, 64, 2, 2, 4, 3),
+    CONV2D_DMA_TILE_N("bf16", 64, 64, 64, 2, 2, 4, 4),
+    CONV2D_DMA_TILE_N("bf16", 64, 64, 64, 2, 2, 3, 6),
+    CONV2D_DMA_TILE_N("bf16", 64, 64, 128, 2, 2, 4, 2),
     CONV2D_DMA_TILE("bf16", true, 128, 128, 64, 2, 2, 4, false, 2, kVector, "_g"),
     CONV2D_DMA_TILE("bf16", true, 128, 64, 64, 2, 2, 4, false, 3, kVector, "_g"),
     CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 4, false, 4, kVector, "_g"),
