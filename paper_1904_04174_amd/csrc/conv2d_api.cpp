@@ -74,6 +74,7 @@ struct Table {
     for (int t = 0; t < igemm_dma_num_tiles(0); ++t) {
       const int addressing = igemm_dma_tile_addressing(0, t);
       if (addressing != 0 && addressing != 1) continue;
+      if (igemm_dma_tile_native(0, t)) continue;  // the batched products repack per point
       char base[80];
       // "igemm_dma_f32_64x64_..." -> "winograd2x2_f32_64x64_..."
       std::snprintf(base, sizeof(base), "winograd2x2_%s", igemm_dma_tile_name(0, t) + 10);

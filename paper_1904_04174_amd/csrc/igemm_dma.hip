@@ -135,11 +135,15 @@ template <bool BF16_, int BM_, int BN_, int ROWB_, int WAVES_M_, int WAVES_N_, i
           bool TWO_LEVEL_, int OCC_, int ADDR_, bool NATIVE_ = false>
 struct DmaTile {
   static constexpr bool NATIVE = NATIVE_;
-  static_assert(!NATIVE_ || (BF16_ && ADDR_ == 0 && BN_ % 64 == 0), "native filter: bf16 uniform tiles");
-  static constexpr int B_ROW_BYTES = BN_ * 2;   // NATIVE: a filter row (one k) in LDS
-  // NATIVE: XOR of the 32-byte piece index of filter row k.  A 32-row block's read takes, per
-  // half wavefront, 4 rows x 2 adjacent pieces: the XOR moves pairs of pieces (bit 0 clear).
+  static_assert(!NATIVE_ || (ADDR_ == 0 && BN_ % 64 == 0), "native filter: uniform tiles");
+  static constexpr int B_ROW_BYTES = BN_ * (BF16_ ? 2 : 4);   // NATIVE: a filter row (one k) in LDS
+  // NATIVE, bf16: XOR of the 32-byte piece index of filter row k.  A 32-row block's read takes,
+  // per half wavefront, 4 rows x 2 adjacent pieces: the XOR moves pairs of pieces (bit 0 clear).
+  // NATIVE, fp32 (a lane reads single values, 32 consecutive features of row k per lane half,
+  // the other half 4 rows on): XOR of the 128-byte half index, so that the two halves of a
+  // wavefront read different banks.
   static constexpr int native_swizzle(int k) {
+    if (!BF16_) return (k >> 2) & 1;
     return BN_ >= 128 ? ((k & 3) << 1) : (((k >> 1) & 1) << 1);
   }
   static constexpr bool BF16 = BF16_;
@@ -422,12 +426,13 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
     if constexpr (T::NATIVE) {
       // 16-byte chunk q of the stage's filter part: row k = q / chunks per row; its position
       // q % chunks per row holds the features [8c, 8c + 8) with c = position ^ swizzle
-      constexpr int CH = BN / 8;
+      constexpr int CH = BN / VEC;
       const int q = i * T::NT + tid;
       const int k = q / CH;
-      const int c = (q % CH) ^ (T::native_swizzle(k) << 1);
-      const int n = n0 + 8 * c;
-      b_voff[i] = (n + 8 <= p.K) ? (k * p.K + n) * ES : kOutOfRange;
+      // (bf16: pieces of 2 chunks; fp32: halves of 8 chunks)
+      const int c = (q % CH) ^ (T::native_swizzle(k) << (T::BF16 ? 1 : 3));
+      const int n = n0 + VEC * c;
+      b_voff[i] = (n + VEC <= p.K) ? (k * p.K + n) * ES : kOutOfRange;
     } else {
       const int n = n0 + ld_row0 + i * T::ROWS_PER_PASS;
       b_voff[i] = (n < p.K) ? (n * BK + ld_chunk * VEC) * ES : kOutOfRange;
@@ -571,12 +576,19 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   // address of row 16 * kk + 8 * lk + (lane % 16) / 4 (+ 4 for the second read), features
   // 4 * (lane % 4) ... of its 16-feature piece
   int nat_row_off = 0, nat_piece_off[T::NATIVE ? TN : 1] = {};
-  if constexpr (T::NATIVE) {
+  if constexpr (T::NATIVE && T::BF16) {
     const int a = lane & 15, k = 8 * lk + a / 4;
     nat_row_off = BM * ROWB + k * T::B_ROW_BYTES + 8 * (a % 4);
 #pragma unroll
     for (int j = 0; j < TN; ++j)
       nat_piece_off[j] = 32 * ((2 * (wn * TN + j) + ((lane >> 4) & 1)) ^ T::native_swizzle(k));
+  }
+  // NATIVE, fp32: lane (feature lr of a block, half lk) reads rows 8 * kk + 4 * lk + t, t = 0..3
+  // (the four MFMAs of a step), feature lr of the block's 128-byte half
+  if constexpr (T::NATIVE && !T::BF16) {
+    nat_row_off = BM * ROWB + 4 * lk * T::B_ROW_BYTES + 4 * lr;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) nat_piece_off[j] = 128 * ((wn * TN + j) ^ lk);
   }
 
   // Fragment read number r (A blocks first, then B blocks) of step kk of `stage`.
@@ -585,6 +597,14 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
     if (r < TM) {
       af[buf][r] = *reinterpret_cast<const uintx4*>(a_frag + stage * T::STAGE_BYTES +
                                                     r * 32 * ROWB + chunk_bytes[kk]);
+    } else if constexpr (T::NATIVE && !T::BF16) {
+      const unsigned char* src = ring + stage * T::STAGE_BYTES + nat_row_off +
+                                 nat_piece_off[r - TM] + 8 * kk * T::B_ROW_BYTES;
+      uintx4 v;
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        v[t] = *reinterpret_cast<const unsigned*>(src + t * T::B_ROW_BYTES);
+      bf[buf][r - TM] = v;
     } else if constexpr (T::NATIVE) {
       typedef short shortx4 __attribute__((ext_vector_type(4)));
       typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
@@ -944,7 +964,7 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   if (batches > 1 && splits != 1) return hipErrorInvalidValue;  // batched: whole tiles only
   // 1. filter -> Bt[K][Kg_p] in the workspace (one per batch), unless the caller packed it before
   // (native tiles read the filter as it is; their "packed" filter is a plain copy)
-  if (T::NATIVE && (p.K % 8 != 0 || batches > 1)) return hipErrorInvalidValue;
+  if (T::NATIVE && (p.K % T::VEC != 0 || batches > 1)) return hipErrorInvalidValue;
   const void* bt = p.packed_filt ? p.packed_filt : (T::NATIVE ? p.filt : p.workspace);
   hipError_t e = hipSuccess;
   if (!p.packed_filt && !T::NATIVE) {
@@ -1949,7 +1969,7 @@ size_t workspace_bytes_patch(const Problem& p, int) {
 }
 
 // Extra shape condition of the native gather tiles: 16-byte chunks of a filter row.
-bool native_fits(const Problem& p) { return p.K % 8 == 0 && p.batches <= 1; }
+bool native_fits(const Problem& p) { return p.K % (p.in_bf16 ? 8 : 4) == 0 && p.batches <= 1; }
 
 struct TileEntry {
   const char* name;
@@ -2004,12 +2024,12 @@ struct TileEntry {
     &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw>>, nullptr,                   \
     PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw>::POOLS }
 
-// bf16 uniform tiles that read the filter as it lies in memory
-#define CONV2D_DMA_TILE_N(dt, bm, bn, rowb, wm, wn, st, occ)                                    \
+// uniform tiles that read the filter as it lies in memory
+#define CONV2D_DMA_TILE_N(dt, isbf, bm, bn, rowb, wm, wn, st, two, occ)                         \
   { "igemm_dma_" dt "_" #bm "x" #bn "_r" #rowb "_w" #wm "x" #wn "_s" #st "_nat", bm, bn,        \
-    DmaTile<true, bm, bn, rowb, wm, wn, st, false, occ, kUniform, true>::BK, occ, kUniform,     \
-    &launch<DmaTile<true, bm, bn, rowb, wm, wn, st, false, occ, kUniform, true>>,               \
-    &workspace_bytes<DmaTile<true, bm, bn, rowb, wm, wn, st, false, occ, kUniform, true>>,      \
+    DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, kUniform, true>::BK, occ, kUniform,       \
+    &launch<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, kUniform, true>>,                 \
+    &workspace_bytes<DmaTile<isbf, bm, bn, rowb, wm, wn, st, two, occ, kUniform, true>>,        \
     &native_fits, nullptr, false, true }
 
 #define CONV2D_DMA_TILE(dt, isbf, bm, bn, rowb, wm, wn, st, two, occ, addr, tag)                \
@@ -2035,6 +2055,10 @@ const TileEntry kTilesF32[] = {
     CONV2D_DMA_TILE("f32", false, 256, 128, 64, 4, 2, 4, true, 2, kUniform, ""),
     CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 4, true, 4, kUniform, ""),
     CONV2D_DMA_TILE("f32", false, 64, 64, 64, 2, 2, 3, true, 6, kUniform, ""),
+    CONV2D_DMA_TILE_N("f32", false, 128, 128, 64, 2, 2, 4, true, 2),
+    CONV2D_DMA_TILE_N("f32", false, 128, 64, 64, 2, 2, 4, true, 3),
+    CONV2D_DMA_TILE_N("f32", false, 64, 64, 64, 2, 2, 4, true, 4),
+    CONV2D_DMA_TILE_N("f32", false, 64, 64, 64, 2, 2, 3, true, 6),
     CONV2D_DMA_TILE("f32", false, 128, 128, 64, 2, 2, 4, true, 2, kVector, "_g"),
     CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, kVector, "_g"),
     CONV2D_DMA_TILE_W("f32", false, 64, 64, 64, 2, 2, 4, true, 4, kVector, "_g"),
@@ -2064,12 +2088,12 @@ const TileEntry kTilesBf16[] = {
     CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 4, false, 4, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 3, false, 6, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 64, 64, 128, 2, 2, 4, false, 2, kUniform, ""),
-    CONV2D_DMA_TILE_N("bf16", 256, 128, 64, 4, 2, 3, 2),
-    CONV2D_DMA_TILE_N("bf16", 128, 128, 64, 2, 2, 4, 2),
-    CONV2D_DMA_TILE_N("bf16", 128, 64, 64, 2, 2, 4, 3),
-    CONV2D_DMA_TILE_N("bf16", 64, 64, 64, 2, 2, 4, 4),
-    CONV2D_DMA_TILE_N("bf16", 64, 64, 64, 2, 2, 3, 6),
-    CONV2D_DMA_TILE_N("bf16", 64, 64, 128, 2, 2, 4, 2),
+    CONV2D_DMA_TILE_N("bf16", true, 256, 128, 64, 4, 2, 3, false, 2),
+    CONV2D_DMA_TILE_N("bf16", true, 128, 128, 64, 2, 2, 4, false, 2),
+    CONV2D_DMA_TILE_N("bf16", true, 128, 64, 64, 2, 2, 4, false, 3),
+    CONV2D_DMA_TILE_N("bf16", true, 64, 64, 64, 2, 2, 4, false, 4),
+    CONV2D_DMA_TILE_N("bf16", true, 64, 64, 64, 2, 2, 3, false, 6),
+    CONV2D_DMA_TILE_N("bf16", true, 64, 64, 128, 2, 2, 4, false, 2),
     CONV2D_DMA_TILE("bf16", true, 128, 128, 64, 2, 2, 4, false, 2, kVector, "_g"),
     CONV2D_DMA_TILE("bf16", true, 128, 64, 64, 2, 2, 4, false, 3, kVector, "_g"),
     CONV2D_DMA_TILE("bf16", true, 64, 64, 64, 2, 2, 4, false, 4, kVector, "_g"),
