@@ -38,21 +38,17 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2516.6}   # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of a layer's selected variant (convolution kernel plus its reduce kernel),
-# from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB, factors calibrated on a
-# 256 MiB copy); source: profiles/igemm_dma_counters_per_layer.md.  Not measurable inside this
-# process; keyed by the variant as well, so that another selection reports null, not a wrong figure.
-MEASURED_TRAFFIC_MB = {
-    ("f32", "V224-N16", "igemm_patch_f32_128x64_w2x2_p256_b16"): 223.6 + 205.5,
-    ("f32", "V112-N16", "igemm_dma_f32_64x64_r64_w2x2_s3_tail"): 109.3 + 104.9 + 4.3 + 2.1,
-    ("f32", "V56-N16", "igemm_dma_f32_64x64_r64_w2x2_s3_tail"): 78.2 + 54.5 + 4.3 + 1.0,
-    ("f32", "V28-N16", "igemm_dma_f32_64x64_r64_w2x2_s3_tail"): 388.0 + 29.4 + 4.3 + 0.5,
-    ("f32", "V14-N16", "igemm_dma_f32_64x64_r64_w2x2_s4_splitk"): 106.2 + 19.3 + 19.3 + 6.4,
-    ("bf16", "V224-N16", "igemm_patch_bf16_256x64_w4x1_p512_b16"): 105.0 + 205.5,
-    ("bf16", "V112-N16", "igemm_patch_bf16_224x128_w2x2_p384_b16_m16"): 54.1 + 102.8,
-    ("bf16", "V56-N16", "igemm_patch_bf16_224x128_w2x2_p384_b16_m16"): 35.4 + 51.4,
-    ("bf16", "V28-N16", "igemm_patch_bf16_224x128_w2x2_p384_m16"): 52.2 + 25.7,
-}
+def measured_traffic():
+    """HBM bytes per launch (all kernels of a call) per "dtype|layer|variant", as written by
+    `python -m paper_1904_04174_amd.profile_summary --json` from two rocprofv3 --pmc runs
+    (FETCH_SIZE, WRITE_SIZE, scaled on a copy of known size).  Not measurable inside this
+    process; keyed by the variant as well, so that another selection reports null, not a wrong
+    figure."""
+    path = os.path.join(ROOT, "paper_1904_04174_amd", "measured_traffic.json")
+    if not os.path.exists(path):
+        return {}
+    with open(path) as fh:
+        return json.load(fh)
 
 
 def layer_flops(B, p):
@@ -392,9 +388,9 @@ def main():
     roofline = {"bound": "hbm" if hbm_bound else "mfma", "achieved": round(achieved, 3),
                 "peak": peak, "unit": "GB/s" if hbm_bound else "TFLOP/s",
                 "frac": round(achieved / peak, 4),
-                "traffic": (round(MEASURED_TRAFFIC_MB[(args.dtype, dom["name"], dom["variant"])] * 1e6)
-                            if (args.dtype, dom["name"], dom["variant"]) in MEASURED_TRAFFIC_MB
-                            else None),
+                "traffic": measured_traffic().get(
+                    "%s|%s|%s" % (args.dtype, dom["name"], dom["variant"]),
+                    {}).get("hbm_bytes_per_launch"),
                 "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled)",
                 "algorithmic_bytes_per_launch": dom["bytes"],
                 "kernel": dom["variant"], "layer": dom["name"],

@@ -92,8 +92,10 @@ typedef struct {
   int32_t out_rows, out_cols, pad_top, pad_bottom, pad_left, pad_right;
 } conv2d_geometry;
 
-/* Output size and padding for `params` (host only, touches no GPU).
- * INVALID_ARGUMENT if the tuple has no valid output. */
+/* Output size and padding for `params` (host only, touches no GPU): the
+ * parameter tuple is the one of Figure 1's caption; the paper gives no padding
+ * rule, the output size and padding follow the conventions at the top of this
+ * file.  INVALID_ARGUMENT if the tuple has no valid output. */
 CONV2D_API int conv2d_get_geometry(const conv2d_params* params, conv2d_geometry* geometry);
 
 /* Bytes of device scratch that conv2d_forward may use for `params` (section 3:
@@ -107,7 +109,8 @@ CONV2D_API int conv2d_get_geometry(const conv2d_params* params, conv2d_geometry*
  * needs none), so a workspace of this size is always enough.  Host only. */
 CONV2D_API int conv2d_workspace_size(const conv2d_params* params, size_t* bytes);
 
-/* Same, for a forced variant.  UNSUPPORTED if the variant cannot run `params`. */
+/* Same, for a forced variant (Figure 1's caption: not every algorithm supports
+ * every parameter set).  UNSUPPORTED if the variant cannot run `params`. */
 CONV2D_API int conv2d_workspace_size_variant(const conv2d_params* params, int variant_id, size_t* bytes);
 
 /* Forward convolution with the variant the selector picks for the layer
@@ -148,7 +151,8 @@ CONV2D_API int conv2d_forward_static_scratch(const conv2d_params* params, const 
                                              const void* filt, void* out, void* hip_stream);
 
 /* Same, with the variant forced (0 <= variant_id < conv2d_num_variants()).
- * Every variant that supports `params` produces the same result up to the
+ * Section 3: the library's algorithms all give the same numeric result; here:
+ * every variant that supports `params` produces the same result up to the
  * order of floating-point summation (the Winograd variants: up to the
  * rounding of their transforms, within the same tolerance).  UNSUPPORTED if it cannot run them. */
 CONV2D_API int conv2d_forward_variant(const conv2d_params* params, const void* in, const void* filt,
@@ -205,7 +209,11 @@ CONV2D_API int conv2d_forward_bias_act_pool(const conv2d_params* params, const v
                                  const void* filt, const float* bias, int activation, void* out,
                                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Filters packed ahead of time.  The matrix-core kernels read the filter in a
+/* Filters packed ahead of time.  (These three calls follow no passage of the
+ * paper: they serve inference loops whose filters do not change.  The tiles
+ * whose names end in "_nat" and the conv1x1_* variants read the filter as it
+ * lies in memory and need none of this: their packed filter is a plain copy.)
+ * The other matrix-core kernels read the filter in a
  * layout of their own (reduction index contiguous, cut into the tile's
  * slices), which conv2d_forward writes into the workspace on every call: a
  * small kernel of its own, ~5 us, a tenth to a third of a whole call on the
@@ -238,10 +246,12 @@ CONV2D_API int conv2d_forward_packed(const conv2d_params* params, int variant_id
 
 /* The runtime's description of the error behind the calling thread's last
  * CONV2D_STATUS_LAUNCH_FAILED ("" if there was none).  The string is the
- * runtime's and stays valid. */
+ * runtime's and stays valid.  (Follows no passage of the paper.) */
 CONV2D_API const char* conv2d_last_launch_error(void);
 
-/* Variant introspection (host only). */
+/* Variant introspection (host only): the "algorithms and their parameters" of
+ * section 3 by number and name, and Figure 1's compatibility rule as a
+ * predicate. */
 CONV2D_API int conv2d_num_variants(void);
 CONV2D_API const char* conv2d_variant_name(int variant_id);            /* NULL if out of range */
 CONV2D_API int conv2d_variant_supports(const conv2d_params* params, int variant_id); /* 1, 0, or <0 status */
@@ -271,6 +281,8 @@ CONV2D_API int conv2d_selected_variant(const conv2d_params* params, int* variant
 #define CONV2D_SELECT_DIRECT_SUM_ONLY 1u
 CONV2D_API int conv2d_select_variant(const conv2d_params* params, uint32_t flags, int* variant_id);
 
+/* Text of a status code; the library's version (100 * major + minor).  (Follow
+ * no passage of the paper.) */
 CONV2D_API const char* conv2d_status_string(int status);
 CONV2D_API int conv2d_version(void);
 

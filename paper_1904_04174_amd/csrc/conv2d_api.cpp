@@ -21,7 +21,7 @@ namespace {
 
 constexpr long long kMaxElems = (1LL << 31) - 1;
 
-enum Family { kDirect = 0, kIgemm = 1, kDma = 2, kWinograd = 3, kPadded = 4, kRowGather = 5 };
+enum Family { kDirect = 0, kIgemm = 1, kDma = 2, kWinograd = 3, kPadded = 4, kRowGather = 5, kConv1x1 = 6 };
 enum Split { kWhole = 0, kSplit = 1, kTail = 2, kFused = 3 };
 
 struct Variant {
@@ -87,6 +87,9 @@ struct Table {
       }
     }
     add(kRowGather, 0, 0, kWhole, "rowgather_f32_128x64");
+    // the streaming kernel for 1x1 windows
+    for (int t = 0; t < conv1x1_num_tiles(); ++t)
+      add(kConv1x1, conv1x1_tile_bf16(t), t, kWhole, conv1x1_tile_name(t));
   }
 };
 const Table& table() {
@@ -183,6 +186,7 @@ bool supports(const Variant& v, const Problem& q) {
   if (1LL * es * q.N * q.H * q.W * q.C >= (1LL << 31)) return false;
   if (v.family == kWinograd) return winograd_supports(q, v.tile, v.split == kFused);
   if (v.family == kRowGather) return row_gather_supports(q);
+  if (v.family == kConv1x1) return conv1x1_supports(q, v.tile);
   if (v.family == kPadded) {
     if (v.bf16 != q.in_bf16 || (!q.in_bf16 && q.out_bf16)) return false;
     return padded_supports(q, v.tile);
@@ -331,6 +335,19 @@ double winograd_cost(const Variant& v, const Problem& q) {
 double model_cost(const Variant& v, const Problem& q) {
   if (v.family == kWinograd) return winograd_cost(v, q);
   if (v.family == kRowGather) return row_gather_cost(q);
+  if (v.family == kConv1x1) {
+    // a stream: the larger of the products' time and the tensors' bytes at the chip's streaming
+    // rate (the input is read once per slab of features), one launch, a persistent pipeline
+    const double es = q.in_bf16 ? 2.0 : 4.0;
+    const int bn = conv1x1_tile_features(v.tile);
+    const double slabs = static_cast<double>(ceil_div_ll(q.K, bn));
+    const double mfma = 1.0 * q.M * q.K * q.C / ((q.in_bf16 ? 2048.0 : 128.0) * 256.0) /
+                        (q.in_bf16 ? 0.5 : 0.8);
+    const double bytes = es * q.M * q.C * (slabs > 1 ? 1.3 : 1.0) + es * q.C * q.K * 256.0 +
+                         (q.out_bf16 ? 2.0 : 4.0) * q.M * q.K;
+    const double stream = bytes / 1900.0;
+    return (mfma > stream ? mfma : stream) * 1.1 + 4000.0 + kLaunchCycles;
+  }
   if (v.family == kPadded) {
     // the gather tile on the padded problem, the padding passes' traffic, two more launches
     const int vec = q.in_bf16 ? 8 : 4;
@@ -527,7 +544,8 @@ size_t packed_filter_bytes_for(const Variant& v, const Problem& q, bool* ok) {
   *ok = true;
   if (v.family == kPadded) return padded_packed_filter_bytes(q, v.tile);
   if (v.family == kDma) return igemm_dma_packed_filter_bytes(q, v.bf16, v.tile);
-  if (v.family == kDirect || v.family == kIgemm || v.family == kRowGather)  // these read the filter as it is: a copy
+  if (v.family == kDirect || v.family == kIgemm || v.family == kRowGather ||
+      v.family == kConv1x1)  // these read the filter as it is: a copy
     return align256(static_cast<size_t>(q.Kg) * q.K * (q.in_bf16 ? 2 : 4));
   if (v.family == kWinograd) return winograd_packed_filter_bytes(q, v.tile, v.split == kFused);
   *ok = false;
@@ -658,6 +676,7 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
       break;
     case kPadded: e = launch_padded(q, tb.v[id].tile, stream); break;
     case kRowGather: e = launch_row_gather(q, stream); break;
+    case kConv1x1: e = launch_conv1x1(q, tb.v[id].tile, stream); break;
     case kWinograd:
       e = launch_winograd(q, tb.v[id].tile, tb.v[id].split == kFused, stream);
       break;

@@ -68,6 +68,16 @@ bool row_gather_supports(const Problem& p);
 double row_gather_cost(const Problem& p);
 hipError_t launch_row_gather(const Problem& p, hipStream_t stream);
 
+// Streaming kernel for 1x1 windows (conv1x1.hip): persistent workgroups, the filter slab of
+// `features` output features resident in LDS as it lies in memory, loads and stores issued by
+// different wavefronts.  No workspace.
+int conv1x1_num_tiles();
+const char* conv1x1_tile_name(int tile);
+int conv1x1_tile_bf16(int tile);
+int conv1x1_tile_features(int tile);
+bool conv1x1_supports(const Problem& p, int tile);
+hipError_t launch_conv1x1(const Problem& p, int tile, hipStream_t stream);
+
 // Launchers (one per kernel family).  Each returns hipSuccess or the launch
 // error; none synchronises.  `tile` selects a compiled tile configuration.
 hipError_t launch_direct(const Problem& p, hipStream_t stream);

@@ -90,6 +90,7 @@ FAMILIES = (
     ("LDS-resident patch", lambda n: n.startswith("igemm_patch_")),
     ("Winograd F(2x2,3x3)", lambda n: n.startswith("winograd2x2_")),
     ("window-row gather", lambda n: n.startswith("rowgather_")),
+    ("1x1 streaming", lambda n: n.startswith("conv1x1_")),
 )
 
 

@@ -91,6 +91,8 @@ SMALL = [
     (8, 48, 48, 16, 64, 3, 3, 1, 1, wl.PAD_SAME),      # 288 tiles of 64x64: whole rounds + a tail
     (5, 10, 10, 32, 64, 3, 3, 1, 1, wl.PAD_SAME),      # tiles span several small images (patch tiles)
     (3, 12, 13, 32, 40, 3, 3, 1, 1, wl.PAD_VALID),     # the same without padding, H != W
+    (2, 19, 17, 64, 136, 1, 1, 2, 2, wl.PAD_SAME),     # 1x1, stride 2, a ragged second slab of features
+    (3, 23, 11, 32, 256, 1, 1, 1, 1, wl.PAD_VALID),    # 1x1, many tiles of 64 pixels per workgroup
 ]
 
 

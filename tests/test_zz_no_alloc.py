@@ -25,8 +25,21 @@ def _case(shape_in, shape_f, stride, padding, dtype, seed):
     return p, xd, fd, (n, g.out_rows, g.out_cols, k)
 
 
-def _reference(p, xd, fd, out_shape):
-    vid = B.conv2d_select_variant(p, B.SELECT_DIRECT_SUM_ONLY)
+def _scratch_variant(p):
+    """A variant that uses scratch memory for `p` (repacked filter and, by preference, the
+    partial sums of a split reduction), within the static array's size."""
+    fits = []
+    for v in range(B.conv2d_num_variants()):
+        name = B.conv2d_variant_name(v)
+        if name.startswith("winograd") or not B.conv2d_variant_supports(p, v):
+            continue
+        if 0 < B.conv2d_workspace_size(p, v) <= B.STATIC_SCRATCH_BYTES:
+            fits.append((0 if name.endswith("_splitk") else 1, v))
+    assert fits, "no variant of this case uses scratch memory"
+    return min(fits)[1]
+
+
+def _reference(p, xd, fd, out_shape, vid):
     need = B.conv2d_workspace_size(p, vid)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
     out = torch.full(out_shape, float("nan"), dtype=torch.float32, device="cuda")
@@ -37,8 +50,9 @@ def _reference(p, xd, fd, out_shape):
     return out, need
 
 
-# (first call, second and smaller call): a layer whose pick repacks the filter and splits the
-# reduction (scratch: filter + partial sums), then a small layer on the same array
+# (first call, second and smaller call), each run twice: with the selector's own pick, and with
+# a variant forced that keeps a repacked filter and the partial sums of a split reduction in
+# the scratch array
 CASES = [
     ("f32", ((2, 14, 14, 256), (3, 3, 256, 256), 1, wl.PAD_SAME),
             ((1, 9, 11, 32), (3, 3, 32, 48), 1, wl.PAD_SAME)),
@@ -49,29 +63,35 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("forced", [False, True])
 @pytest.mark.parametrize("dtype,first,second", CASES)
-def test_static_scratch_matches_workspace_entry_point(dtype, first, second):
+def test_static_scratch_matches_workspace_entry_point(dtype, first, second, forced):
     stream = torch.cuda.current_stream().cuda_stream
     prepared = []
-    some_scratch = False
     for i, (shape_in, shape_f, stride, padding) in enumerate((first, second)):
         p, xd, fd, out_shape = _case(shape_in, shape_f, stride, padding, dtype, 4242 + i)
-        want, need = _reference(p, xd, fd, out_shape)
-        some_scratch = some_scratch or need > 0
+        vid = (_scratch_variant(p) if forced
+               else B.conv2d_select_variant(p, B.SELECT_DIRECT_SUM_ONLY))
+        want, need = _reference(p, xd, fd, out_shape, vid)
         assert need <= B.STATIC_SCRATCH_BYTES
-        prepared.append((p, xd, fd, want))
-    assert some_scratch, "the cases are meant to use scratch memory"
+        assert need > 0 or not forced
+        prepared.append((p, xd, fd, want, vid))
     torch.cuda.synchronize()
     # the two calls in a row, outputs allocated beforehand: nothing is allocated in between
     outs = [torch.full(tuple(w.shape), float("nan"), dtype=torch.float32, device="cuda")
-            for _, _, _, w in prepared]
+            for _, _, _, w, _ in prepared]
     torch.cuda.synchronize()
-    for (p, xd, fd, _), out in zip(prepared, outs):
-        rc = B.conv2d_forward_static_scratch_raw(p, xd.data_ptr(), fd.data_ptr(), out.data_ptr(),
-                                                 stream)
-        assert rc == 0, B.status_string(rc)
+    try:
+        for (p, xd, fd, _, vid), out in zip(prepared, outs):
+            if forced:
+                B.conv2d_debug_force_variant(vid)
+            rc = B.conv2d_forward_static_scratch_raw(p, xd.data_ptr(), fd.data_ptr(),
+                                                     out.data_ptr(), stream)
+            assert rc == 0, B.status_string(rc)
+    finally:
+        B.conv2d_debug_force_variant(None)
     torch.cuda.synchronize()
-    for (_, _, _, want), out in zip(prepared, outs):
+    for (_, _, _, want, _), out in zip(prepared, outs):
         got, ref = out.cpu().numpy(), want.cpu().numpy()
         assert not np.isnan(got).any()
         assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
