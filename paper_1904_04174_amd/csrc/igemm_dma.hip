@@ -1104,11 +1104,14 @@ template <bool BF16_, int BM_, int BN_, int WAVES_M_, int WAVES_N_, int PATCH_RO
           bool TWO_LEVEL_, int OCC_, int BW_ = 0, bool MF16_ = false, bool NATIVE_ = false>
 struct PatchTile {
   static constexpr bool NATIVE = NATIVE_;
-  static_assert(!NATIVE_ || (BF16_ && MF16_ && BN_ % 64 == 0), "native filter: bf16 16-row tiles");
-  static constexpr int B_ROW_BYTES = BN_ * 2;      // NATIVE: a filter row (one k) in LDS
-  // NATIVE: XOR of the 32-byte piece index of filter row k (rows of at least 8 pieces: the 4
-  // rows of a lane group and the group 8 rows on get 8 different positions; 4 pieces: 2 bits)
+  static_assert(!NATIVE_ || BN_ % 64 == 0, "native filter: whole 64-feature groups");
+  static constexpr int B_ROW_BYTES = BN_ * (BF16_ ? 2 : 4);   // NATIVE: a filter row (one k) in LDS
+  // NATIVE, bf16 16-row blocks: XOR of the 32-byte piece index of filter row k (rows of at
+  // least 8 pieces: the 4 rows of a lane group and the group 8 rows on get 8 different
+  // positions; 4 pieces: 2 bits).  32-row blocks (bf16 and fp32): as DmaTile::native_swizzle.
   static constexpr int native_swizzle(int k) {
+    if (!BF16_) return (k >> 2) & 1;
+    if (!MF16_) return BN_ >= 128 ? ((k & 3) << 1) : (((k >> 1) & 1) << 1);
     return BN_ >= 128 ? ((k & 3) | (((k >> 3) & 1) << 2)) : (((k >> 1) & 1) | (((k >> 3) & 1) << 1));
   }
   static constexpr bool BF16 = BF16_;
@@ -1277,12 +1280,13 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
       if constexpr (T::NATIVE) {
         // 16-byte chunk q of the stage: row k = q / chunks per row, position q % chunks per
         // row, which holds the chunk of features [8c, 8c + 8) with c = position ^ swizzle
-        constexpr int CH = BN / 8;
+        constexpr int CH = BN / VEC;
         const int q = i * T::NT + tid;
         const int k = q / CH;
-        const int c = (q % CH) ^ (T::native_swizzle(k) << 1);
-        const int n = col0 + 8 * c;
-        voff[i] = (n + 8 <= p.K) ? (k * p.K + n) * ES : kOutOfRange;
+        // (bf16: pieces of 2 chunks; fp32: halves of 8 chunks)
+        const int c = (q % CH) ^ (T::native_swizzle(k) << (T::BF16 ? 1 : 3));
+        const int n = col0 + VEC * c;
+        voff[i] = (n + VEC <= p.K) ? (k * p.K + n) * ES : kOutOfRange;
       } else {
         const int n = col0 + ld_row0 + i * T::B_ROWS_PER_PASS;
         voff[i] = (n < p.K) ? (n * BK + ld_chunk * VEC) * ES : kOutOfRange;
@@ -1363,12 +1367,26 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   // NATIVE: lane (feature lr of a block, k group lk) hands in the address of row
   // 8 * lk + lr / 4 (+ 4 for the second read), features 4 * (lr % 4) ... of the block
   int nat_row_off = 0, nat_piece_off[T::NATIVE ? TN : 1] = {};
-  if constexpr (T::NATIVE) {
+  if constexpr (T::NATIVE && T::MF16) {
     const int k = 8 * lk + lr / 4;
     nat_row_off = k * T::B_ROW_BYTES + 8 * (lr % 4);
 #pragma unroll
     for (int j = 0; j < TN; ++j)
       nat_piece_off[j] = 32 * ((wn * TN + j) ^ T::native_swizzle(k));
+  }
+  // 32-row blocks (as in the gather kernel): bf16 lanes hand in row 16 kk + 8 lk +
+  // (lane % 16) / 4 of their half block; fp32 lanes read rows 8 kk + 4 lk + t of their feature
+  if constexpr (T::NATIVE && !T::MF16 && T::BF16) {
+    const int a = lane & 15, k = 8 * lk + a / 4;
+    nat_row_off = k * T::B_ROW_BYTES + 8 * (a % 4);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      nat_piece_off[j] = 32 * ((2 * (wn * TN + j) + ((lane >> 4) & 1)) ^ T::native_swizzle(k));
+  }
+  if constexpr (T::NATIVE && !T::BF16) {
+    nat_row_off = 4 * lk * T::B_ROW_BYTES + 4 * lr;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) nat_piece_off[j] = 128 * ((wn * TN + j) ^ lk);
   }
 
   uintx4 af[2][TM], bf[2][TN];
@@ -1382,12 +1400,21 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
     if (r < TM) {
       af[T::MF16 && r < TM - 1 ? 0 : buf][r] = *reinterpret_cast<const uintx4*>(
           ring + a_frag[r] + a_off + 2 * kk * T::PLANE_BYTES);
+    } else if constexpr (T::NATIVE && !T::BF16) {
+      const unsigned char* src = ring + B_REGION + bstage * T::B_STAGE_BYTES + nat_row_off +
+                                 nat_piece_off[r - TM] + 8 * kk * T::B_ROW_BYTES;
+      uintx4 v;
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        v[t] = *reinterpret_cast<const unsigned*>(src + t * T::B_ROW_BYTES);
+      bf[buf][r - TM] = v;
     } else if constexpr (T::NATIVE) {
       typedef short shortx4 __attribute__((ext_vector_type(4)));
       typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
       typedef __attribute__((address_space(3))) shortx4* lds_ptr;
+      // (16-row blocks have one step per slice: kk = 0)
       const unsigned char* src = ring + B_REGION + bstage * T::B_STAGE_BYTES + nat_row_off +
-                                 nat_piece_off[r - TM];
+                                 nat_piece_off[r - TM] + 16 * kk * T::B_ROW_BYTES;
       const uintx2 lo = __builtin_bit_cast(
           uintx2, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(src)));
       const uintx2 hi = __builtin_bit_cast(
@@ -1907,7 +1934,7 @@ long long patch_rows_needed(const Problem& p) {
 template <class T>
 bool patch_fits(const Problem& p) {
   if (!(p.R == 3 && p.S == 3 && p.sr == 1 && p.sc == 1 && p.C % T::BK == 0)) return false;
-  if (T::NATIVE && p.K % 8 != 0) return false;  // 16-byte chunks of a filter row
+  if (T::NATIVE && p.K % T::VEC != 0) return false;  // 16-byte chunks of a filter row
   if (T::BW > 0) return true;  // a block's patch always fits
   // (the kernel indexes the padded images' pixels with 32 bits)
   if (1LL * p.N * (p.P + p.R - 1) * (p.Q + p.S - 1) + T::PATCH_ROWS >= (1LL << 31)) return false;
@@ -2015,6 +2042,15 @@ struct TileEntry {
     &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true, true>>, nullptr,     \
     false, true }
 
+// blocked patch tiles of 32-row blocks that read the filter as it lies in memory
+#define CONV2D_PATCH_TILE_BN(dt, isbf, bm, bn, wm, wn, rows, two, occ, bw)                       \
+  { "igemm_patch_" dt "_" #bm "x" #bn "_w" #wm "x" #wn "_p" #rows "_b" #bw "_nat", bm, bn,       \
+    PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw, false, true>::BK, occ, 3,                \
+    &launch_patch<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw, false, true>>,             \
+    &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw, false, true>>,    \
+    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw, false, true>>, nullptr,      \
+    PatchTile<isbf, bm, bn, wm, wn, rows, two, occ, bw, false, true>::POOLS, true }
+
 // blocked patch tiles: bm / bw x bw output pixels of one image
 #define CONV2D_PATCH_TILE_B(dt, isbf, bm, bn, wm, wn, rows, two, occ, bw)                        \
   { "igemm_patch_" dt "_" #bm "x" #bn "_w" #wm "x" #wn "_p" #rows "_b" #bw, bm, bn,              \
@@ -2050,6 +2086,8 @@ const TileEntry kTilesF32[] = {
     CONV2D_PATCH_TILE("f32", false, 128, 128, 2, 2, 512, true, 1),
     CONV2D_PATCH_TILE_B("f32", false, 128, 128, 2, 2, 256, true, 2, 16),
     CONV2D_PATCH_TILE_B("f32", false, 128, 64, 2, 2, 256, true, 3, 16),
+    CONV2D_PATCH_TILE_BN("f32", false, 128, 128, 2, 2, 256, true, 2, 16),
+    CONV2D_PATCH_TILE_BN("f32", false, 128, 64, 2, 2, 256, true, 3, 16),
     CONV2D_DMA_TILE("f32", false, 128, 128, 64, 2, 2, 4, true, 2, kUniform, ""),
     CONV2D_DMA_TILE("f32", false, 128, 64, 64, 2, 2, 4, true, 3, kUniform, ""),
     CONV2D_DMA_TILE("f32", false, 256, 128, 64, 4, 2, 4, true, 2, kUniform, ""),
@@ -2079,6 +2117,9 @@ const TileEntry kTilesBf16[] = {
     CONV2D_PATCH_TILE_B("bf16", true, 256, 64, 4, 1, 512, false, 2, 16),
     CONV2D_PATCH_TILE_B("bf16", true, 128, 64, 2, 2, 256, false, 3, 16),
     CONV2D_PATCH_TILE_B("bf16", true, 128, 128, 2, 2, 256, false, 2, 16),
+    CONV2D_PATCH_TILE_BN("bf16", true, 256, 64, 4, 1, 512, false, 2, 16),
+    CONV2D_PATCH_TILE_BN("bf16", true, 128, 64, 2, 2, 256, false, 3, 16),
+    CONV2D_PATCH_TILE_BN("bf16", true, 128, 128, 2, 2, 256, false, 2, 16),
     CONV2D_DMA_TILE("bf16", true, 256, 256, 64, 4, 2, 4, false, 1, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 256, 256, 128, 4, 2, 2, false, 1, kUniform, ""),
     CONV2D_DMA_TILE("bf16", true, 256, 128, 64, 4, 2, 4, false, 1, kUniform, ""),
