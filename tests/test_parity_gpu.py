@@ -696,7 +696,7 @@ def test_pool_in_the_epilogue_of_blocked_tiles(torch_cuda, oracle, shape):
         p = B.make_params(n, h, w, c, k, 3, 3, 1, 1, wl.PAD_SAME, dt, B.F32)
         for v in range(B.conv2d_num_variants()):
             name = B.conv2d_variant_name(v)
-            if not (name.startswith("igemm_patch_") and name.endswith("_b16")):
+            if not (name.startswith("igemm_patch_") and name.endswith(("_b16", "_b16_nat"))):
                 continue
             if not B.conv2d_variant_supports(p, v):
                 continue
