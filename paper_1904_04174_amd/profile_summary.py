@@ -19,6 +19,8 @@ and produces
 
     python -m paper_1904_04174_amd.profile_summary --dir gpurun_out/prof \\
         --md profiles/counters_per_layer.md --json paper_1904_04174_amd/measured_traffic.json
+
+`--stats DIR` prints the per-kernel table of a `rocprofv3 --kernel-trace --stats` run.
 """
 import argparse
 import collections
@@ -101,10 +103,26 @@ def variant_of(layer_dir):
 
 
 def tile_label(kernel_name):
+    """`kernel Tile<...>` without namespaces, return type and argument list."""
+    m = re.search(r"(\w+_kernel)", kernel_name)
+    name = m.group(1) if m else kernel_name.split("(")[0][-60:]
     i = kernel_name.find("Tile<")
     if i < 0:
-        return kernel_name.split("(")[0][-60:]
-    return kernel_name[i:kernel_name.find(">", i) + 1]
+        return name
+    return "%s %s" % (name, kernel_name[i:kernel_name.find(">", i) + 1])
+
+
+def kernel_stats(stats_dir):
+    """Markdown table of a `rocprofv3 --kernel-trace --stats` run (its *_kernel_stats.csv)."""
+    lines = ["kernel | calls | average us | min us | max us | % of GPU time", "---|---|---|---|---|---"]
+    for fn in sorted(glob.glob(os.path.join(stats_dir, "**", "*kernel_stats.csv"), recursive=True)):
+        for r in csv.DictReader(open(fn)):
+            name = r["Name"]
+            label = tile_label(name) if "conv2d::" in name else name.split("(")[0][:70]
+            lines.append("%s | %s | %.1f | %.1f | %.1f | %.2f" % (
+                label.replace("|", "/"), r["Calls"], float(r["AverageNs"]) / 1e3,
+                float(r["MinNs"]) / 1e3, float(r["MaxNs"]) / 1e3, float(r["Percentage"])))
+    return "\n".join(lines) + "\n"
 
 
 def main(argv=None):
@@ -113,7 +131,13 @@ def main(argv=None):
     ap.add_argument("--dir", default="gpurun_out/prof")
     ap.add_argument("--md")
     ap.add_argument("--json")
+    ap.add_argument("--stats", metavar="DIR",
+                    help="print the kernel table of a `rocprofv3 --kernel-trace --stats "
+                         "--output-format csv -d DIR` run instead")
     args = ap.parse_args(argv)
+    if args.stats:
+        sys.stdout.write(kernel_stats(args.stats))
+        return
     if args.print_commands:
         print("\n".join(commands(args.print_commands, args.dir)))
         return
