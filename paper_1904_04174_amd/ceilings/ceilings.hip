@@ -75,6 +75,19 @@ __global__ __launch_bounds__(256) void mfma_loop(float* out, int iters, Clocks* 
           acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
     for (int i = 0; i < NACC; ++i)
       for (int v = 0; v < 16; ++v) s += acc[i][v];
+  } else if constexpr (KIND == 3) {
+    floatx4 acc[NACC];
+    for (int i = 0; i < NACC; ++i)
+      for (int v = 0; v < 4; ++v) acc[i][v] = 0.f;
+    const float a = 1.f + threadIdx.x, b = 0.5f;
+    for (int it = 0; it < iters; ++it)
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int i = 0; i < NACC; ++i)
+          acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[i], 0, 0, 0);
+    for (int i = 0; i < NACC; ++i)
+      for (int v = 0; v < 4; ++v) s += acc[i][v];
   } else {
     floatx4 acc[NACC];
     for (int i = 0; i < NACC; ++i)
@@ -289,6 +302,7 @@ __attribute__((visibility("default"))) int conv2d_ceilings_measure(void* out, in
       {"mfma_f32_32x32x2 x4acc", 4096, mfma_loop<0, 4>, 4},
       {"mfma_bf16_32x32x16 x4acc", 32768, mfma_loop<1, 4>, 4},
       {"mfma_bf16_16x16x32 x8acc", 16384, mfma_loop<2, 8>, 8},
+      {"mfma_f32_16x16x4 x8acc", 2048, mfma_loop<3, 8>, 8},
   };
   for (const M& m : ms_) {
     double best = 0.0, best_mhz = 0.0;

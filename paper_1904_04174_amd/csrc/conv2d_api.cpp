@@ -21,7 +21,10 @@ namespace {
 
 constexpr long long kMaxElems = (1LL << 31) - 1;
 
-enum Family { kDirect = 0, kIgemm = 1, kDma = 2, kWinograd = 3, kPadded = 4, kRowGather = 5, kConv1x1 = 6 };
+enum Family { kDirect = 0, kIgemm = 1, kDma = 2, kWinograd = 3, kPadded = 4, kRowGather = 5, kConv1x1 = 6,
+              kWinogradLds = 7 };
+// (kWinograd: transform passes around the products; kWinogradLds: everything in one launch)
+inline bool is_winograd(int family) { return family == kWinograd || family == kWinogradLds; }
 enum Split { kWhole = 0, kSplit = 1, kTail = 2, kFused = 3 };
 
 struct Variant {
@@ -86,6 +89,7 @@ struct Table {
         v[n - 1].split = kFused;
       }
     }
+    add(kWinogradLds, 0, 0, kWhole, "winograd2x2_lds_f32_32x64");
     add(kRowGather, 0, 0, kWhole, "rowgather_f32_128x64");
     // the streaming kernel for 1x1 windows
     for (int t = 0; t < conv1x1_num_tiles(); ++t)
@@ -186,6 +190,7 @@ bool supports(const Variant& v, const Problem& q) {
   if (1LL * es * q.N * q.H * q.W * q.C >= (1LL << 31)) return false;
   if (v.family == kWinograd) return winograd_supports(q, v.tile, v.split == kFused);
   if (v.family == kRowGather) return row_gather_supports(q);
+  if (v.family == kWinogradLds) return winograd_lds_supports(q);
   if (v.family == kConv1x1) return conv1x1_supports(q, v.tile);
   if (v.family == kPadded) {
     if (v.bf16 != q.in_bf16 || (!q.in_bf16 && q.out_bf16)) return false;
@@ -280,6 +285,7 @@ constexpr double kVectorGatherFactor = 0.8502;  // efficiency of the per-lane ad
 constexpr double kElementFactor = 0.75;        // ... of the element-wise tiles
 constexpr double kKSplitFactor = 0.9858;          // ... of the tiles whose waves split the k range
 constexpr double kKSplitLatency = 0.3428;        // extra exposed latency per further k group (their slices are deeper)
+constexpr double kWinogradLdsEff = 0.70;       // MFMA rate of the one-launch Winograd kernel's loop
 constexpr double kPatchFactor = 1.246;         // ... of the LDS-resident patch tiles
 
 // The balanced tail's plan as the launcher makes it: tiles computed whole,
@@ -335,6 +341,17 @@ double winograd_cost(const Variant& v, const Problem& q) {
 double model_cost(const Variant& v, const Problem& q) {
   if (v.family == kWinograd) return winograd_cost(v, q);
   if (v.family == kRowGather) return row_gather_cost(q);
+  if (v.family == kWinogradLds) {
+    // 16 point products per 2x2 outputs on the matrix cores (16 / 36 of the direct sum's
+    // multiplications) at the kernel's sustained rate, whole workgroups of 32 tiles x 64
+    // features in rounds of two per compute unit; the filter transform is a launch of its own
+    const long long tiles = 1LL * q.N * ((q.P + 1) / 2) * ((q.Q + 1) / 2);
+    const long long wgs = ceil_div_ll(tiles, 32) * ceil_div_ll(q.K, 64);
+    const double per_wg = 16.0 * 32 * 64 * q.C / 128.0 / kWinogradLdsEff + 6000.0;
+    const double rounds = static_cast<double>(ceil_div_ll(wgs, 256));
+    const double filter = 4.0 * q.C * q.K * (9.0 + 16.0) / kChipBytesPerClock;
+    return rounds * per_wg + filter + 2 * kLaunchCycles;
+  }
   if (v.family == kConv1x1) {
     // a stream: the larger of the products' time and the tensors' bytes at the chip's streaming
     // rate (the input is read once per slab of features), one launch, a persistent pipeline
@@ -508,7 +525,7 @@ int select_uncached(const Problem& q, int padding, bool aligned, int mode) {
         t.padding == padding) {
       for (int i = 0; i < tb.n; ++i)
         if (std::strcmp(tb.v[i].name, t.variant) == 0 && usable(tb.v[i], q, aligned) &&
-            !(direct_sum_only && tb.v[i].family == kWinograd))
+            !(direct_sum_only && is_winograd(tb.v[i].family)))
           return i;
     }
   }
@@ -518,7 +535,7 @@ int select_uncached(const Problem& q, int padding, bool aligned, int mode) {
   for (int i = 1; i < tb.n; ++i) {
     const Variant& v = tb.v[i];
     if (!usable(v, q, aligned)) continue;
-    if (direct_sum_only && v.family == kWinograd) continue;
+    if (direct_sum_only && is_winograd(v.family)) continue;
     // element-wise tiles only where the vector tiles cannot run
     if (v.family == kRowGather && q.C % vec == 0) continue;
     if (is_scalar(v) && aligned && q.C % vec == 0 && q.K % vec == 0) continue;
@@ -530,6 +547,7 @@ int select_uncached(const Problem& q, int padding, bool aligned, int mode) {
 
 size_t workspace_bytes_for(const Variant& v, const Problem& q) {
   if (v.family == kWinograd) return winograd_workspace_bytes(q, v.tile, v.split == kFused);
+  if (v.family == kWinogradLds) return winograd_lds_workspace_bytes(q);
   if (v.family == kPadded) return padded_workspace_bytes(q, v.tile);
   if (v.family == kDma) return igemm_dma_workspace_bytes(q, v.bf16, v.tile, split_factor(v, q));
   if (v.family == kIgemm && v.split)
@@ -548,6 +566,7 @@ size_t packed_filter_bytes_for(const Variant& v, const Problem& q, bool* ok) {
       v.family == kConv1x1)  // these read the filter as it is: a copy
     return align256(static_cast<size_t>(q.Kg) * q.K * (q.in_bf16 ? 2 : 4));
   if (v.family == kWinograd) return winograd_packed_filter_bytes(q, v.tile, v.split == kFused);
+  if (v.family == kWinogradLds) return winograd_lds_packed_filter_bytes(q);
   *ok = false;
   return 0;
 }
@@ -559,7 +578,7 @@ thread_local hipError_t last_launch_error = hipSuccess;
 bool pools_in_epilogue(const Variant& v) {
   // (the four outputs of a Winograd F(2x2, 3x3) tile are one pooling window: the output
   // transform, or the fused variant's epilogue, takes their maximum)
-  if (v.family == kWinograd) return true;
+  if (is_winograd(v.family)) return true;
   return v.family == kDma && v.split == kWhole && igemm_dma_tile_pools(v.bf16, v.tile);
 }
 
@@ -627,7 +646,7 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
         double best_cost = 0;
         for (int i = 0; i < tb.n; ++i) {
           if (!usable(tb.v[i], q, false)) continue;
-          if (mode == kDirectSumOnly && tb.v[i].family == kWinograd) continue;
+          if (mode == kDirectSumOnly && is_winograd(tb.v[i].family)) continue;
           const size_t n = pool ? pooled_workspace_bytes_for(tb.v[i], q) : workspace_bytes_for(tb.v[i], q);
           if (n > 0 && (!workspace || workspace_bytes < n)) continue;
           const double c = tb.v[i].family == kDirect ? 1e300 : model_cost(tb.v[i], q);
@@ -649,7 +668,7 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
   }
   q.in = in; q.filt = filt; q.out = out; q.workspace = workspace;
   // (a packed filter of the direct and register-staged variants is a plain copy)
-  if (filt_is_packed && (tb.v[id].family == kDma || tb.v[id].family == kWinograd ||
+  if (filt_is_packed && (tb.v[id].family == kDma || is_winograd(tb.v[id].family) ||
                          tb.v[id].family == kPadded))
     q.packed_filt = filt;
   q.bias = bias;
@@ -680,6 +699,7 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     case kWinograd:
       e = launch_winograd(q, tb.v[id].tile, tb.v[id].split == kFused, stream);
       break;
+    case kWinogradLds: e = launch_winograd_lds(q, stream); break;
   }
   if (e == hipSuccess && unpooled)
     e = launch_max_pool_2x2(unpooled, out, q.N, q.P, q.Q, q.K, q.out_bf16 != 0, stream);
@@ -875,6 +895,9 @@ int conv2d_pack_filter(const conv2d_params* params, int variant_id, const void* 
   } else if (v.family == kWinograd) {
     q.filt = filt;
     e = winograd_pack_filter(q, v.tile, v.split == kFused, packed, stream);
+  } else if (v.family == kWinogradLds) {
+    q.filt = filt;
+    e = winograd_lds_pack_filter(q, packed, stream);
   } else if (v.family == kPadded) {
     q.filt = filt;
     e = padded_pack_filter(q, v.tile, packed, stream);

@@ -165,6 +165,15 @@ size_t winograd_packed_filter_bytes(const Problem& p, int gemm_tile, bool fused)
 hipError_t winograd_pack_filter(const Problem& p, int gemm_tile, bool fused, void* packed,
                                 hipStream_t stream);
 
+// Winograd F(2x2, 3x3), fp32, stride 1, in one launch (winograd_lds.hip): input transform,
+// point products and output transform inside one workgroup; only the transformed filter goes
+// through memory (the workspace, or a filter packed ahead of time).  Pools in its epilogue.
+bool winograd_lds_supports(const Problem& p);
+size_t winograd_lds_workspace_bytes(const Problem& p);
+size_t winograd_lds_packed_filter_bytes(const Problem& p);
+hipError_t winograd_lds_pack_filter(const Problem& p, void* packed, hipStream_t stream);
+hipError_t launch_winograd_lds(const Problem& p, hipStream_t stream);
+
 // 2x2 max pooling, stride 2, of the NHWC tensor `in` [N][P][Q][K] (fp32 or bf16)
 // into `out` [N][P/2][Q/2][K] of the same type: the second step of the pooled
 // entry point for variants that cannot pool in their epilogue.

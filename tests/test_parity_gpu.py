@@ -475,18 +475,20 @@ def test_winograd_variants_are_among_the_small_cases():
 @pytest.mark.parametrize("name", ["V112-N16", "V56-N16", "V28-N16", "V14-N16", "V14-N1", "R3x3"])
 def test_winograd_full_size_fp32(torch_cuda, oracle, name):
     """Forced Winograd variants (one with scalar-offset addressing, one with per-lane addressing
-    of the batched products, one with products and output transform fused) at full layer size
-    against the whole oracle output, to the same fp32 tolerance as the direct-sum variants."""
+    of the batched products, one with products and output transform fused, and the one-launch
+    kernel that also transforms the input inside the workgroup) at full layer size against the
+    whole oracle output, to the same fp32 tolerance as the direct-sum variants."""
     L = wl.LAYERS[name]
     x, f = wl.make_inputs(L)
     p = B.params_of_layer(L)
     want = oracle.forward_f32(x, f, (1, 1), L.padding)
     ids = _winograd_variants(p)
     names = [B.conv2d_variant_name(v) for v in ids]
-    plain = [(v, n) for v, n in zip(ids, names) if "_fused_" not in n]
+    plain = [(v, n) for v, n in zip(ids, names) if "_fused_" not in n and "_lds_" not in n]
     fused = [v for v, n in zip(ids, names) if "_fused_" in n]
-    picks = [plain[0][0]] + [v for v, n in plain if n.endswith("_g")][:1] + fused[:1]
-    assert len(picks) == 3, names
+    one_launch = [v for v, n in zip(ids, names) if "_lds_" in n]
+    picks = [plain[0][0]] + [v for v, n in plain if n.endswith("_g")][:1] + fused[:1] + one_launch
+    assert len(picks) == 4, names
     for vid in picks:
         _say("winograd %s variant %s" % (name, B.conv2d_variant_name(vid)))
         err = rel_err(run_gpu(torch_cuda, p, x, f, vid), want)
