@@ -12,25 +12,29 @@
 //
 //   1. direct global->LDS loads bring the 16 input pixels x 4 channels of each tile (16 bytes
 //      per pixel; pixels outside the image arrive as zeros through out-of-range offsets) and
-//      the slice of U for the 64 features: U'[feature tile][slice][point][64 features][4 k],
-//      16 KB that lie contiguously in memory, written that way by winograd_lds_pack_kernel;
-//   2. every thread transforms one (tile, channel) patch in registers (B^T d B: 32 additions,
-//      half of the 16 points written by each of the two threads that share a patch) into
-//      V[point][tile][4 k] in LDS;
+//      the slice of U for the 64 features: U'[feature tile][slice][row a][64 features][4 k]
+//      [column b] (point 4a + b), 16 KB that lie contiguously in memory, written that way by
+//      winograd_lds_pack_kernel;
+//   2. every thread transforms one (tile, channel) patch in registers (B^T d B), two of the
+//      four rows of the transformed patch each (wavefronts 0, 1 the upper, 2, 3 the lower
+//      rows), and writes V[row a][tile][4 k][column b] in LDS, 16 bytes per row;
 //   3. per point, v_mfma_f32_16x16x4_f32 multiplies U (16 features x 4 k) by V (4 k x 16
 //      tiles): a wavefront owns 16 tiles x 32 features, i.e. 16 points x 2 blocks of
-//      accumulators (128 registers), and reads one 4-byte value per lane and operand.
+//      accumulators (128 registers), and one 16-byte LDS read per operand block gives a lane
+//      its values for the four points of a row a.
 //
-// The input loads run three slices ahead of the products (three buffers), U one slice (two
-// buffers) and the transform one slice (two buffers of V): 72 KB of LDS, two workgroups per
-// compute unit, one barrier per slice, placed before the slice's last four points so that
-// their MFMAs cover the barrier and the first fragment reads of the next slice.  After the last
-// slice each lane holds, for one tile and 2 x 4 consecutive features, all 16 points: it applies
-// A^T . A in registers, then bias, activation and, when asked, the 2x2 maximum (a tile is one
-// pooling window), and stores 16 bytes per pixel.
+// U, the input pixels and V are double buffered (64 KB of LDS, two workgroups per compute
+// unit): loads run one slice ahead (U) or two (input), the transform one slice ahead; one
+// barrier per slice, placed before the slice's last four points so that their MFMAs cover the
+// barrier and the first fragment reads of the next slice.  After the last slice each lane
+// holds, for one tile and 2 x 4 consecutive features, all 16 points: it applies A^T . A in
+// registers, then bias, activation and, when asked, the 2x2 maximum (a tile is one pooling
+// window), and stores 16 bytes per pixel.
 //
 // All transform entries are 0, +-1 or +-1/2: integer-valued tensors give exact results, as with
 // the separate-pass Winograd variants.
+#include <type_traits>
+
 #include "conv2d_internal.h"
 
 namespace conv2d {
@@ -47,8 +51,8 @@ constexpr int kPoints = 16;
 constexpr int kUBytes = kPoints * kFeatures * kBK * 4;  // a slice of U: 16 KB
 constexpr int kRawBytes = 16 * kTiles * kBK * 4;        // the tiles' input pixels: 8 KB
 constexpr int kVBytes = kPoints * kTiles * kBK * 4;     // their transform: 8 KB
-constexpr int kU0 = 0, kRaw0 = 2 * kUBytes, kV0 = kRaw0 + 3 * kRawBytes;  // U x2, input x3, V x2
-constexpr int kLdsBytes = kV0 + 2 * kVBytes;  // 72 KB
+constexpr int kU0 = 0, kRaw0 = 2 * kUBytes, kV0 = kRaw0 + 2 * kRawBytes;  // all double buffered
+constexpr int kLdsBytes = kV0 + 2 * kVBytes;  // 64 KB
 constexpr unsigned kRsrcFlags = 0x00020000u;
 constexpr int kOutOfRange = static_cast<int>(0x80000000u);
 
@@ -77,8 +81,10 @@ __device__ __forceinline__ void dma16(const uintx4& rsrc, unsigned lds_base, int
                : "memory", "m0");
 }
 
-// U'[nt][s][t = a*4 + b][f][j] = sum_{r,q} G[a][r] G[b][q] filt[r][q][4s + j][64 nt + f]
-// (0 for features past K).  One thread per (feature, slice).
+// U'[nt][s][a][f][j][b] = sum_{r,q} G[a][r] G[b][q] filt[r][q][4s + j][64 nt + f] (0 for
+// features past K): point t = 4a + b of the transformed filter; the four points of a row a lie
+// together, and the 16-byte chunk j of feature f sits at position j ^ ((f >> 1) & 3) of the
+// feature's 64 bytes (the bank swizzle of the fragment reads).  One thread per (feature, slice).
 __global__ __launch_bounds__(256) void winograd_lds_pack_kernel(const float* __restrict__ filt,
                                                                 float* __restrict__ u, int C,
                                                                 int K, int nslices) {
@@ -87,9 +93,11 @@ __global__ __launch_bounds__(256) void winograd_lds_pack_kernel(const float* __r
   if (idx >= static_cast<long long>(kpad) * nslices) return;
   const int k = static_cast<int>(idx % kpad), s = static_cast<int>(idx / kpad);
   const size_t ck = static_cast<size_t>(C) * K;
-  floatx4 out[kPoints];
+  floatx4 out[4][kBK];  // [row a][channel j] -> the four columns b
 #pragma unroll
-  for (int t = 0; t < kPoints; ++t) out[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int j = 0; j < kBK; ++j) out[a][j] = floatx4{0.f, 0.f, 0.f, 0.f};
   if (k < K) {
 #pragma unroll
     for (int j = 0; j < kBK; ++j) {
@@ -113,18 +121,17 @@ __global__ __launch_bounds__(256) void winograd_lds_pack_kernel(const float* __r
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
         const float sum02 = t[a][0] + t[a][2];
-        out[a * 4 + 0][j] = t[a][0];
-        out[a * 4 + 1][j] = 0.5f * (sum02 + t[a][1]);
-        out[a * 4 + 2][j] = 0.5f * (sum02 - t[a][1]);
-        out[a * 4 + 3][j] = t[a][2];
+        out[a][j] = floatx4{t[a][0], 0.5f * (sum02 + t[a][1]), 0.5f * (sum02 - t[a][1]), t[a][2]};
       }
     }
   }
   const int nt = k / kFeatures, f = k % kFeatures;
-  float* dst = u + ((static_cast<size_t>(nt) * nslices + s) * kPoints * kFeatures + f) * kBK;
+  float* dst = u + (static_cast<size_t>(nt) * nslices + s) * (kUBytes / 4) + f * 16;
 #pragma unroll
-  for (int t = 0; t < kPoints; ++t)
-    *reinterpret_cast<floatx4*>(dst + static_cast<size_t>(t) * kFeatures * kBK) = out[t];
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int j = 0; j < kBK; ++j)
+      *reinterpret_cast<floatx4*>(dst + a * (kFeatures * 16) + (j ^ ((f >> 1) & 3)) * 4) = out[a][j];
 }
 
 __global__ __launch_bounds__(256, 2) void winograd_lds_kernel(const Problem p,
@@ -192,26 +199,36 @@ __global__ __launch_bounds__(256, 2) void winograd_lds_kernel(const Problem p,
             soff + (wave * 4 + i) * 1024);
   };
 
-  // ---- transform role: thread -> patch (tile, channel) = tid % 128 and half of its points
+  // ---- transform role: thread -> patch (tile, channel) = tid % 128; wavefronts 0 and 1 compute
+  // rows 0, 1 of the transformed patch (from pixel rows 0..2), wavefronts 2 and 3 rows 2, 3 (from
+  // pixel rows 1..3).  V[row a = group of 4 points][tile][channel][column b]: a thread writes
+  // the four points of a row with one 16-byte store, the multipliers read them with one load.
   const int item = tid & 127;
-  const int half = tid >> 7;  // points a = 2 half, 2 half + 1
-  float d[4][4], tr[2][4];
-  auto raw_read = [&](int buf, int px) {
-    d[px >> 2][px & 3] =
-        *reinterpret_cast<const float*>(lds + kRaw0 + buf * kRawBytes + px * (kTiles * 16) + item * 4);
+  const bool lower = wave >= 2;  // (wave-uniform)
+  // B^T rows: (1,0,-1,0), (0,1,1,0) need pixel rows 0..2; (0,-1,1,0), (0,1,0,-1) rows 1..3.  With
+  // x0, x1, x2 = pixel rows 0, 1, 2 (upper) or 2, 3, 1 (lower) both pairs are
+  // x0 - x2 and sign * x1 + x2 with sign = +1 (upper), -1 (lower): no per-lane selects.
+  const int x_row0 = lower ? 2 : 0, x_row1 = lower ? 3 : 1, x_row2 = lower ? 1 : 2;
+  const float x_sign = lower ? -1.f : 1.f;
+  const unsigned char* raw_item = lds + kRaw0 + item * 4;
+  float d[3][4], tr[2][4];
+  auto raw_read = [&](int buf, int e) {  // e = 0..11: x(e / 4), column e % 4
+    const int row = (e >> 2) == 0 ? x_row0 : (e >> 2) == 1 ? x_row1 : x_row2;
+    d[e >> 2][e & 3] = *reinterpret_cast<const float*>(raw_item + buf * kRawBytes +
+                                                       (row * 4 + (e & 3)) * (kTiles * 16));
   };
-  // rows a = 2 half, 2 half + 1 of B^T d, column j
   auto row_transform = [&](int j) {
-    // B^T rows: (1,0,-1,0), (0,1,1,0), (0,-1,1,0), (0,1,0,-1)
-    tr[0][j] = half ? d[2][j] - d[1][j] : d[0][j] - d[2][j];
-    tr[1][j] = half ? d[1][j] - d[3][j] : d[1][j] + d[2][j];
+    tr[0][j] = d[0][j] - d[2][j];
+    tr[1][j] = x_sign * d[1][j] + d[2][j];
   };
-  auto point_write = [&](int buf, int e) {  // e = 0..7: row e / 4 of this half, column e % 4
-    const int a = e >> 2, b = e & 3;
-    const float* t = tr[a];
-    const float o = b == 0 ? t[0] - t[2] : b == 1 ? t[1] + t[2] : b == 2 ? t[2] - t[1] : t[1] - t[3];
-    const int point = (2 * half + a) * 4 + b;
-    *reinterpret_cast<float*>(lds + kV0 + buf * kVBytes + point * (kTiles * 16) + item * 4) = o;
+  // (16-byte chunk `channel` of a tile's 64-byte row sits at position channel ^ swizzle(tile),
+  // see the fragment reads)
+  const int v_write_off = (item >> 2) * 64 + (((item & 3) ^ ((item >> 3) & 3)) * 16);
+  auto row_write = [&](int buf, int a) {
+    const floatx4 o = {tr[a][0] - tr[a][2], tr[a][1] + tr[a][2], tr[a][2] - tr[a][1],
+                       tr[a][1] - tr[a][3]};
+    *reinterpret_cast<floatx4*>(lds + kV0 + buf * kVBytes + ((lower ? 2 : 0) + a) * (kTiles * 64) +
+                                v_write_off) = o;
   };
 
   // ---- multiplier role
@@ -220,20 +237,19 @@ __global__ __launch_bounds__(256, 2) void winograd_lds_kernel(const Problem p,
   for (int t = 0; t < kPoints; ++t)
 #pragma unroll
     for (int b = 0; b < 2; ++b) acc[t][b] = floatx4{0.f, 0.f, 0.f, 0.f};
-  const int a_off = (32 * fg + lr) * 16 + lk * 4;  // + point * 1024 + block * 256
-  const int b_off = (16 * tg + lr) * 16 + lk * 4;  // + point * 512
+  // U[group][feature][k][4 points], V[group][tile][k][4 points]: 64 bytes per row
+  // A wavefront's 16-byte reads (row = lane % 16, chunk k = lane / 16) hit all banks only if the
+  // chunks of a row are permuted: chunk k of row r sits at position k ^ ((r >> 1) & 3).
+  const int frag_pos = (lk ^ ((lr >> 1) & 3)) * 16;
+  const int a_off = (32 * fg + lr) * 64 + frag_pos;  // + group * 4096 + block * 1024
+  const int b_off = (16 * tg + lr) * 64 + frag_pos;  // + group * 2048
   // fragments of a group of 4 points, two sets (one being used, one being read)
-  float fa[2][4][2], fb[2][4];
+  floatx4 fa[2][2], fb[2];
   auto read_group = [&](int set, int buf, int group) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int point = 4 * group + i;
-      const unsigned char* ub = lds + kU0 + buf * kUBytes + point * (kFeatures * 16) + a_off;
-      fa[set][i][0] = *reinterpret_cast<const float*>(ub);
-      fa[set][i][1] = *reinterpret_cast<const float*>(ub + 256);
-      fb[set][i] =
-          *reinterpret_cast<const float*>(lds + kV0 + buf * kVBytes + point * (kTiles * 16) + b_off);
-    }
+    const unsigned char* ub = lds + kU0 + buf * kUBytes + group * (kFeatures * 64) + a_off;
+    fa[set][0] = *reinterpret_cast<const floatx4*>(ub);
+    fa[set][1] = *reinterpret_cast<const floatx4*>(ub + 1024);
+    fb[set] = *reinterpret_cast<const floatx4*>(lds + kV0 + buf * kVBytes + group * (kTiles * 64) + b_off);
   };
   // the 8 MFMAs of a group with `side(m)` after MFMA m, pinned in that order
   auto multiply_group = [&](int set, int group, auto side) {
@@ -241,50 +257,47 @@ __global__ __launch_bounds__(256, 2) void winograd_lds_kernel(const Problem p,
     for (int m = 0; m < 8; ++m) {
       const int i = m >> 1, b = m & 1, point = 4 * group + i;
       acc[point][b] =
-          __builtin_amdgcn_mfma_f32_16x16x4f32(fa[set][i][b], fb[set][i], acc[point][b], 0, 0, 0);
+          __builtin_amdgcn_mfma_f32_16x16x4f32(fa[set][b][i], fb[set][i], acc[point][b], 0, 0, 0);
       side(m);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  // ---- prologue: U(0) and input(0..2) in flight; transform(0); fragments of group 0
+  // ---- prologue: U(0), input(0) and input(1) in flight; transform(0); fragments of group 0
   load_u(0, 0);
   load_raw(0, 0);
   load_raw(1, 1);
-  load_raw(2, 2);
   __builtin_amdgcn_s_waitcnt(kWaitLoadsAndLds);
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 #pragma unroll
-  for (int px = 0; px < 16; ++px) raw_read(0, px);
+  for (int e = 0; e < 12; ++e) raw_read(0, e);
 #pragma unroll
   for (int j = 0; j < 4; ++j) row_transform(j);
-#pragma unroll
-  for (int e = 0; e < 8; ++e) point_write(0, e);
+  row_write(0, 0);
+  row_write(0, 1);
   __builtin_amdgcn_s_waitcnt(kWaitLds);
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   read_group(0, 0, 0);
   __builtin_amdgcn_sched_barrier(0);
 
-  // Slice s: U and V in buffer s % 2, its input pixels in buffer s % 3.  Loads past the last
-  // slice are issued all the same (the last slice again, into buffers nobody reads): the counts
-  // that the waits rely on stay the same in every slice.
-  int rb = 0;  // s % 3
-  for (int s = 0; s < nslices; ++s) {
-    const int cur = s & 1, nxt = cur ^ 1;
-    const int rb1 = rb == 2 ? 0 : rb + 1;
-    // U(s + 1) into the buffer that slice s - 1 read; input(s + 3) into the buffer that the
+  // Slice s: U, V and its input pixels in buffer s % 2 (`cur`, a compile-time constant: the
+  // loop body is a pair of slices).  Loads past the last slice are issued all the same (the
+  // last slice again, into buffers nobody reads).
+  auto slice = [&](int s, auto cur_c) {
+    constexpr int cur = decltype(cur_c)::value, nxt = cur ^ 1;
+    // U(s + 1) into the buffer that slice s - 1 read; input(s + 2) into the buffer that the
     // transform read during slice s - 1
     load_u(s + 1, nxt);
-    load_raw(s + 3, rb);
+    load_raw(s + 2, cur);
     // groups 0..2: the next group's fragments, then 8 MFMAs with the transform of input(s + 1)
-    // into V(s + 1) between them: 16 reads, 4 row steps, 8 writes
+    // into V(s + 1) between them: 12 reads, 4 row steps, 2 writes
     read_group(1, cur, 1);
     __builtin_amdgcn_sched_barrier(0);
     multiply_group(0, 0, [&](int m) {
-      raw_read(rb1, 2 * m);
-      raw_read(rb1, 2 * m + 1);
+      raw_read(nxt, m);
+      if (m >= 4) raw_read(nxt, m + 4);
     });
     read_group(0, cur, 2);
     __builtin_amdgcn_sched_barrier(0);
@@ -293,18 +306,26 @@ __global__ __launch_bounds__(256, 2) void winograd_lds_kernel(const Problem p,
     });
     read_group(1, cur, 3);
     __builtin_amdgcn_sched_barrier(0);
-    multiply_group(0, 2, [&](int m) { point_write(nxt, m); });
-    // U(s + 1) has landed (only the two input loads of this slice may still be in flight), this
-    // wavefront's part of V(s + 1) is written and its reads of slice s are done
-    __builtin_amdgcn_s_waitcnt(0x0072);  // vmcnt(2) lgkmcnt(0)
+    multiply_group(0, 2, [&](int m) {
+      if (m == 2) row_write(nxt, 0);
+      if (m == 5) row_write(nxt, 1);
+    });
+    // U(s + 1) and input(s + 2) have landed, this wavefront's part of V(s + 1) is written and
+    // its reads of slice s are done
+    __builtin_amdgcn_s_waitcnt(kWaitLoadsAndLds);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     // the last group runs from registers while the next slice's first fragments arrive
     read_group(0, nxt, 0);
     __builtin_amdgcn_sched_barrier(0);
     multiply_group(1, 3, [&](int) {});
-    rb = rb1;
+  };
+  int s = 0;
+  for (; s + 1 < nslices; s += 2) {
+    slice(s, std::integral_constant<int, 0>{});
+    slice(s + 1, std::integral_constant<int, 1>{});
   }
+  if (s < nslices) slice(s, std::integral_constant<int, 0>{});
   __builtin_amdgcn_s_waitcnt(kWaitLoadsAndLds);  // drain the loads issued past the end
 
   // ---- output transform and stores: lane = tile 16 tg + lr, features 4 lk .. 4 lk + 3 of the
