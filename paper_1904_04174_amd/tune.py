@@ -88,7 +88,8 @@ FAMILIES = (
         ("igemm_dma_", "igemm_patch_"))),
     ("direct-to-LDS implicit GEMM", lambda n: n.startswith(("igemm_dma_", "padc_"))),
     ("LDS-resident patch", lambda n: n.startswith("igemm_patch_")),
-    ("Winograd F(2x2,3x3)", lambda n: n.startswith("winograd2x2_")),
+    ("Winograd F(2x2,3x3), transform passes", lambda n: n.startswith("winograd2x2_") and "_lds_" not in n),
+    ("Winograd F(2x2,3x3), one launch", lambda n: n.startswith("winograd2x2_lds_")),
     ("window-row gather", lambda n: n.startswith("rowgather_")),
     ("1x1 streaming", lambda n: n.startswith("conv1x1_")),
 )
