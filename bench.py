@@ -213,6 +213,8 @@ def main():
                          "input/output buffers (the cold-cache figures in `layers`)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="lower bound on the CPU oracle's timed work")
+    ap.add_argument("--variant", default=None,
+                    help="with --only: run this variant (by name) instead of the selector's pick")
     ap.add_argument("--only", default=None,
                     help="profile mode: launch only this layer (any name in workloads.LAYERS) "
                          "--steps times, plus one device-to-device copy of --copy-mb MiB as the "
@@ -266,6 +268,8 @@ def main():
                           device=dev)
         vid = B.conv2d_select_variant(
             p, B.SELECT_DIRECT_SUM_ONLY if args.algorithms == "direct" else 0)
+        if args.only and args.variant:
+            vid = B.variant_id_by_name(args.variant)
         ws_bytes = B.conv2d_workspace_size(p, vid)
         ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev)
         layers.append(dict(name=name, layer=L, p=p, x=xd, f=fd, out=out, ws=ws, ws_bytes=ws_bytes,
