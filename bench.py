@@ -450,6 +450,7 @@ def main():
         for l in layers:
             vid = B.conv2d_select_variant(l["p"], 0)
             l["direct_vid"], l["direct_variant"] = l["vid"], l["variant"]
+            l["direct_ws"], l["direct_ws_bytes"] = l["ws"], l["ws_bytes"]
             if vid != l["vid"]:
                 changed = True
                 l["vid"], l["variant"] = vid, B.conv2d_variant_name(vid)
@@ -479,6 +480,7 @@ def main():
             with_transforms["packed_filters_ms_per_step"] = round(ms_all_packed, 4)
         for l in layers:
             l["vid"], l["variant"] = l["direct_vid"], l["direct_variant"]
+            l["ws"], l["ws_bytes"] = l["direct_ws"], l["direct_ws_bytes"]
 
     # ---- the same sweep (direct-sum selection) with the filters packed ahead of time
     # (conv2d_pack_filter once, outside the timed region; conv2d_forward_packed in it): what an
