@@ -42,6 +42,7 @@ COPY_MIB = 256
 # kernels of the library by a substring of their name, in launch order
 KINDS = (
     ("filter_transform", "filter_transform"), ("input_transform", "input_transform"),
+    ("filter_transform", "winograd_lds_pack_kernel"), ("convolution", "winograd_lds_kernel"),
     ("pad_channels", "pad_channels"), ("repack", "repack_filter_kernel"),
     ("convolution", "igemm_dma_kernel"), ("convolution", "igemm_patch_kernel"),
     ("convolution", "igemm_kernel"), ("convolution", "conv1x1_kernel"),
@@ -118,7 +119,9 @@ def kernel_stats(stats_dir):
     for fn in sorted(glob.glob(os.path.join(stats_dir, "**", "*kernel_stats.csv"), recursive=True)):
         for r in csv.DictReader(open(fn)):
             name = r["Name"]
-            label = tile_label(name) if "conv2d::" in name else name.split("(")[0][:70]
+            # (kernels of other libraries: their name without return type and arguments)
+            label = tile_label(name) if "conv2d::" in name else re.sub(
+                r"^void ", "", name).replace("(anonymous namespace)::", "").split("(")[0][:70]
             lines.append("%s | %s | %.1f | %.1f | %.1f | %.2f" % (
                 label.replace("|", "/"), r["Calls"], float(r["AverageNs"]) / 1e3,
                 float(r["MinNs"]) / 1e3, float(r["MaxNs"]) / 1e3, float(r["Percentage"])))
