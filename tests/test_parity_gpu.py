@@ -495,11 +495,14 @@ def test_winograd_full_size_fp32(torch_cuda, oracle, name):
         assert err <= TOL_F32, (name, B.conv2d_variant_name(vid), err)
 
 
+@pytest.mark.parametrize("shape", [(4, 19, 23, 64, 32), (8, 61, 69, 8, 128)])
 @pytest.mark.parametrize("pad", [wl.PAD_SAME, wl.PAD_VALID])
-def test_winograd_integer_inputs_bit_exact(torch_cuda, oracle, pad):
+def test_winograd_integer_inputs_bit_exact(torch_cuda, oracle, pad, shape):
     """The transform matrices hold only 0, +-1 and +-1/2: with small integer inputs every
-    intermediate is a multiple of 1/4 below 2^22, so the result is exact."""
-    case = (4, 19, 23, 64, 32, 3, 3, 1, 1, pad)
+    intermediate is a multiple of 1/4 below 2^22, so the result is exact.  The second shape has
+    544 (SAME) workgroup tiles for the one-launch kernel, more than the 512 that are resident
+    at a time, the last one ragged."""
+    case = shape + (3, 3, 1, 1, pad)
     n, h, w, c, k, r, s, sr, sc, _ = case
     x, f = wl.make_case((n, h, w, c), (r, s, c, k), "ints", 9100 + pad)
     want = oracle.forward_f32(x, f, (1, 1), pad)
