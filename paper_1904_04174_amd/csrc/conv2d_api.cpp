@@ -91,6 +91,7 @@ struct Table {
     }
     add(kWinogradLds, 0, 0, kWhole, "winograd2x2_lds_f32_32x64");
     add(kRowGather, 0, 0, kWhole, "rowgather_f32_128x64");
+    add(kRowGather, 1, 0, kWhole, "rowgather_bf16_128x64");
     // the streaming kernel for 1x1 windows
     for (int t = 0; t < conv1x1_num_tiles(); ++t)
       add(kConv1x1, conv1x1_tile_bf16(t), t, kWhole, conv1x1_tile_name(t));

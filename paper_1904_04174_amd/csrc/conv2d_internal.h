@@ -62,7 +62,8 @@ __device__ __forceinline__ float finish(float v, float bias_value, int relu) {
   return v;
 }
 
-// Window-row gather kernel for fp32 layers of at most 4 channels (row_gather.hip): supported
+// Window-row gather kernels for layers of at most 4 channels (row_gather.hip; fp32, and bf16
+// where the pixels of a row are an even number of values apart): supported
 // problems, modelled cost in clock cycles, launch.  No workspace; reads the filter as it is.
 bool row_gather_supports(const Problem& p);
 double row_gather_cost(const Problem& p);

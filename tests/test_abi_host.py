@@ -378,3 +378,13 @@ def test_window_row_gather_kernel_support_rules():
     # a single channel, a 1x1 window: supported (one padded reduction step)
     assert B.conv2d_variant_supports(
         B.make_params(2, 19, 23, 1, 5, 1, 1, 1, 1, wl.PAD_SAME, B.F32, B.F32), vid)
+    # the bf16 twin: bf16 input only, pixels of a row an even number of values apart
+    vb = names.index("rowgather_bf16_128x64")
+    for out in (B.F32, B.BF16):
+        assert B.conv2d_variant_supports(
+            B.make_params(32, 224, 224, 3, 64, 7, 7, 2, 2, wl.PAD_SAME, B.BF16, out), vb)
+    assert B.conv2d_workspace_size(
+        B.make_params(32, 224, 224, 3, 64, 7, 7, 2, 2, wl.PAD_SAME, B.BF16, B.F32), vb) == 0
+    assert not B.conv2d_variant_supports(stem, vb)
+    assert not B.conv2d_variant_supports(
+        B.make_params(5, 30, 17, 3, 64, 5, 5, 3, 1, wl.PAD_SAME, B.BF16, B.F32), vb)

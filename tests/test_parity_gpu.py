@@ -782,6 +782,56 @@ def test_window_row_gather_kernel(torch_cuda, oracle, case):
     assert np.array_equal(got, want_pool)
 
 
+ROW_GATHER_BF16_CASES = [c for c in ROW_GATHER_CASES if (c[8] * c[3]) % 2 == 0]
+
+
+@pytest.mark.parametrize("case", ROW_GATHER_BF16_CASES)
+def test_window_row_gather_kernel_bf16(torch_cuda, oracle, case):
+    """The bf16 twin (pixels of a row an even number of values apart): random bf16-rounded
+    inputs against the oracle on the same rounded values (products of bf16 values are exact in
+    fp32, so the fp32 tolerance holds with fp32 output), bf16 output, integer inputs bit-exact,
+    bias + ReLU, packed filter, pooled entry point.  A NaN in one input pixel must reach exactly
+    the outputs whose windows hold it (values past the end of a window row are masked)."""
+    n, h, w, c, k, r, s, sr, sc, pad = case
+    names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
+    vid = names.index("rowgather_bf16_128x64")
+    p = _params(case, B.BF16, B.F32)
+    assert B.conv2d_variant_supports(p, vid)
+    x, f = wl.make_case((n, h, w, c), (r, s, c, k), "uniform", 41 + sum(case))
+    x, _ = wl.round_to_bf16(x)
+    f, _ = wl.round_to_bf16(f)
+    want = oracle.forward_f32(x, f, (sr, sc), pad)
+    _say("row gather bf16 %s uniform" % (case,))
+    err = rel_err(run_gpu(torch_cuda, p, x, f, vid), want)
+    assert err <= TOL_F32, (case, err)
+    err = rel_err(run_gpu(torch_cuda, _params(case, B.BF16, B.BF16), x, f, vid), want)
+    assert err <= TOL_BF16, (case, err)
+    xi, fi = wl.make_case((n, h, w, c), (r, s, c, k), "ints", 42 + sum(case))
+    bias = np.random.default_rng(43).integers(-4, 5, size=k).astype(np.float32)
+    _say("row gather bf16 %s ints" % (case,))
+    assert np.array_equal(run_gpu(torch_cuda, p, xi, fi, vid), oracle.forward_f32(xi, fi, (sr, sc), pad))
+    want_b = oracle.forward_bias_act_f32(xi, fi, bias, True, (sr, sc), pad)
+    assert np.array_equal(run_gpu_fused(torch_cuda, p, xi, fi, bias, B.ACT_RELU, force=vid), want_b)
+    torch = torch_cuda
+    xd, fd = (torch.from_numpy(a).cuda().to(torch.bfloat16) for a in (xi, fi))
+    bd = torch.from_numpy(bias).cuda()
+    packed = B.conv2d_pack_filter(p, vid, fd)
+    got = B.conv2d_forward_packed(p, vid, xd, packed, bd, B.ACT_RELU)
+    assert np.array_equal(got.cpu().numpy(), want_b)
+    want_pool = oracle.forward_bias_act_pool_f32(xi, fi, bias, True, (sr, sc), pad)
+    assert np.array_equal(run_gpu_pooled(torch_cuda, p, xi, fi, bias, B.ACT_RELU, force=vid), want_pool)
+    # one NaN pixel value: NaN exactly where the oracle has it
+    xn = xi.copy()
+    xn[n - 1, h // 2, w // 2, c - 1] = np.nan
+    want_n = oracle.forward_f32(xn, fi, (sr, sc), pad)
+    xnd = torch.from_numpy(xn).cuda().to(torch.bfloat16)
+    got_n = B.conv2d_forward(p, xnd, fd, variant_id=vid)
+    torch.cuda.synchronize()
+    got_n = got_n.float().cpu().numpy()
+    assert np.array_equal(np.isnan(got_n), np.isnan(want_n)), case
+    assert np.array_equal(got_n[~np.isnan(want_n)], want_n[~np.isnan(want_n)]), case
+
+
 # ------------------------------------------------------------------ filters packed ahead of time
 
 PACKED_CASES = [SMALL[1], SMALL[3], SMALL[5], SMALL[7], SMALL[13], SMALL[14], SMALL[16]]
