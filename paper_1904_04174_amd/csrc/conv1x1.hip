@@ -36,46 +36,23 @@
 // (16 fp32 / 32 bf16 values), K a multiple of the 16-byte vector, 16-byte
 // aligned pointers, the filter slab C x BN within 64 KiB, tensors below 2^31
 // bytes.
+#include "buffer_lds.h"
 #include "conv2d_internal.h"
 
 namespace conv2d {
 namespace c1 {  // named namespace: the kernels' host stubs need external linkage
 
+using namespace buf;
+
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-constexpr unsigned kRsrcFlags = 0x00020000u;
-constexpr int kOutOfRange = static_cast<int>(0x80000000u);
 constexpr int kComputeUnits = 256;
 constexpr int kBM = 64;            // output pixels per tile
 constexpr int kRowB = 64;          // bytes of k per ring row = one slice
 constexpr int kMaxSlabBytes = 64 * 1024;
-
-// s_waitcnt immediate: vmcnt <= n only (gfx9 encoding)
-constexpr int vmcnt_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4) | (0xf << 8); }
-
-__device__ __forceinline__ uintx4 make_rsrc(const void* base, long long bytes) {
-  const size_t a = reinterpret_cast<size_t>(base);
-  uintx4 r;
-  r[0] = static_cast<unsigned>(a);
-  r[1] = static_cast<unsigned>(a >> 32) & 0xffffu;
-  r[2] = static_cast<unsigned>(bytes);
-  r[3] = kRsrcFlags;
-  return r;
-}
-
-// One wavefront-wide 16-byte-per-lane load from a buffer straight into LDS: lane l's bytes
-// land at lds_base + 16 * l; an out-of-range voffset writes zeros.
-__device__ __forceinline__ void dma16(const uintx4& rsrc, unsigned lds_base, int voffset,
-                                      int soffset) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :
-               : "s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset)
-               : "memory", "m0");
-}
 
 __device__ __forceinline__ unsigned short to_bf16_bits(float x) {
   unsigned int u = __float_as_uint(x);

@@ -63,64 +63,20 @@
 // the blocked tiles, 16-row MFMA tiles, pooling epilogue); see there.
 #include <type_traits>
 
+#include "buffer_lds.h"
 #include "conv2d_internal.h"
 
 namespace conv2d {
 namespace dma {  // named namespace: the kernels' host stubs need external linkage
 
+using namespace buf;
+
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kXcds = 8;
 constexpr int kComputeUnits = 256;
-constexpr unsigned kRsrcFlags = 0x00020000u;
-constexpr int kOutOfRange = static_cast<int>(0x80000000u);
-
-// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding:
-// vmcnt in bits 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "no wait").
-constexpr int vmcnt_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4) | (0xf << 8); }
-// the same, and all of this wave's LDS reads complete as well (lgkmcnt == 0)
-constexpr int vmcnt_lds_imm(int n) { return (n & 0xf) | ((n >> 4) << 14) | (0x7 << 4); }
-
-// Raw buffer descriptor (base moved back by shift_back bytes, stride 0, bytes,
-// flags) as four scalars.
-__device__ __forceinline__ uintx4 make_rsrc(const void* base, int shift_back, int bytes) {
-  const size_t a = reinterpret_cast<size_t>(base) - static_cast<size_t>(shift_back);
-  uintx4 r;
-  r[0] = static_cast<unsigned>(a);
-  r[1] = static_cast<unsigned>(a >> 32) & 0xffffu;
-  r[2] = static_cast<unsigned>(bytes);
-  r[3] = kRsrcFlags;
-  return r;
-}
-
-// LDS byte address of a pointer into a __shared__ array (the low half of its flat address).
-__device__ __forceinline__ unsigned lds_address(const void* p) {
-  return static_cast<unsigned>(reinterpret_cast<size_t>(p));
-}
-
-// One wavefront-wide 16-byte-per-lane load from a buffer straight into LDS:
-// lane l's 16 bytes land at lds_base + 16*l (lds_base is wave-uniform and goes
-// through M0); an out-of-range voffset writes zeros.
-__device__ __forceinline__ void dma16(const uintx4& rsrc, unsigned lds_base, int voffset,
-                                      int soffset) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :
-               : "s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset)
-               : "memory", "m0");
-}
-
-// The same with 4 bytes per lane: lane l's dword lands at lds_base + 4*l.
-__device__ __forceinline__ void dma4(const uintx4& rsrc, unsigned lds_base, int voffset,
-                                     int soffset) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
-               :
-               : "s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset)
-               : "memory", "m0");
-}
-
 // ADDR: how the gathered A rows are addressed.
 //   kUniform  a slice lies inside one tap (C a multiple of the slice width, at
 //             most 31 taps): scalar tap offset + per-row tap masks, 16-byte loads

@@ -35,13 +35,15 @@
 // the separate-pass Winograd variants.
 #include <type_traits>
 
+#include "buffer_lds.h"
 #include "conv2d_internal.h"
 
 namespace conv2d {
 namespace wlds {  // named namespace: the kernels' host stubs need external linkage
 
+using namespace buf;
+
 typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kXcds = 8;
 constexpr int kTiles = 32;     // tiles of a workgroup
@@ -53,33 +55,8 @@ constexpr int kRawBytes = 16 * kTiles * kBK * 4;        // the tiles' input pixe
 constexpr int kVBytes = kPoints * kTiles * kBK * 4;     // their transform: 8 KB
 constexpr int kU0 = 0, kRaw0 = 2 * kUBytes, kV0 = kRaw0 + 2 * kRawBytes;  // all double buffered
 constexpr int kLdsBytes = kV0 + 2 * kVBytes;  // 64 KB
-constexpr unsigned kRsrcFlags = 0x00020000u;
-constexpr int kOutOfRange = static_cast<int>(0x80000000u);
-
-// s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
+// s_waitcnt immediate (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8)
 constexpr int kWaitLoadsAndLds = 0x0070;  // vmcnt(0) lgkmcnt(0)
-constexpr int kWaitLds = 0xc07f;          // lgkmcnt(0)
-
-__device__ __forceinline__ uintx4 make_rsrc(const void* base, long long bytes) {
-  const size_t a = reinterpret_cast<size_t>(base);
-  uintx4 r;
-  r[0] = static_cast<unsigned>(a);
-  r[1] = static_cast<unsigned>(a >> 32) & 0xffffu;
-  r[2] = static_cast<unsigned>(bytes);
-  r[3] = kRsrcFlags;
-  return r;
-}
-
-// One wavefront-wide 16-byte-per-lane load from a buffer straight into LDS: lane l's 16 bytes
-// land at lds_base + 16 * l (lds_base is wave-uniform and goes through M0); an out-of-range
-// offset writes zeros.
-__device__ __forceinline__ void dma16(const uintx4& rsrc, unsigned lds_base, int voffset,
-                                      int soffset) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :
-               : "s"(lds_base), "v"(voffset), "s"(rsrc), "s"(soffset)
-               : "memory", "m0");
-}
 
 // U'[nt][s][a][f][j][b] = sum_{r,q} G[a][r] G[b][q] filt[r][q][4s + j][64 nt + f] (0 for
 // features past K): point t = 4a + b of the transformed filter; the four points of a row a lie
