@@ -259,15 +259,25 @@ __global__ __launch_bounds__(256, 2) void winograd_lds_kernel(const Problem p,
   read_group(0, 0, 0);
   __builtin_amdgcn_sched_barrier(0);
 
+  // The lane's output tile and bias values, worked out here (the divisions and loads overlap the
+  // first slice's waits; at the end they would delay the stores).
+  const int t = t0 + 16 * tg + lr;
+  const int tw = t % TW, th = (t / TW) % TH, n = t / (TW * TH);
+  floatx4 bias2[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) bias2[b][v] = bias_of(p.bias, n0 + 32 * fg + 16 * b + 4 * lk + v, p.K);
+
   // Slice s: U, V and its input pixels in buffer s % 2 (`cur`, a compile-time constant: the
-  // loop body is a pair of slices).  Loads past the last slice are issued all the same (the
-  // last slice again, into buffers nobody reads).
+  // loop body is a pair of slices).
   auto slice = [&](int s, auto cur_c) {
     constexpr int cur = decltype(cur_c)::value, nxt = cur ^ 1;
     // U(s + 1) into the buffer that slice s - 1 read; input(s + 2) into the buffer that the
     // transform read during slice s - 1
-    load_u(s + 1, nxt);
-    load_raw(s + 2, cur);
+    // (nothing past the last slice: the epilogue would wait for those loads)
+    if (s + 1 < nslices) load_u(s + 1, nxt);
+    if (s + 2 < nslices) load_raw(s + 2, cur);
     // groups 0..2: the next group's fragments, then 8 MFMAs with the transform of input(s + 1)
     // into V(s + 1) between them: 12 reads, 4 row steps, 2 writes
     read_group(1, cur, 1);
@@ -303,21 +313,17 @@ __global__ __launch_bounds__(256, 2) void winograd_lds_kernel(const Problem p,
     slice(s + 1, std::integral_constant<int, 1>{});
   }
   if (s < nslices) slice(s, std::integral_constant<int, 0>{});
-  __builtin_amdgcn_s_waitcnt(kWaitLoadsAndLds);  // drain the loads issued past the end
+  __builtin_amdgcn_s_waitcnt(kWaitLoadsAndLds);
 
   // ---- output transform and stores: lane = tile 16 tg + lr, features 4 lk .. 4 lk + 3 of the
   // two 16-feature blocks
-  const int t = t0 + 16 * tg + lr;
   if (t >= tiles) return;
-  const int tw = t % TW, th = (t / TW) % TH, n = t / (TW * TH);
   float* out = static_cast<float*>(p.out);
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
     const int k = n0 + 32 * fg + 16 * b + 4 * lk;
     if (k >= p.K) continue;  // (K is a multiple of 4)
-    floatx4 bias;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) bias[v] = bias_of(p.bias, k + v, p.K);
+    const floatx4 bias = bias2[b];
     // rows: r[i][c] = sum_a A^T[i][a] m[a][c], A^T = (1,1,1,0), (0,1,-1,-1)
     floatx4 r[2][4];
 #pragma unroll
