@@ -266,6 +266,17 @@ CONV2D_API int conv2d_variant_supports(const conv2d_params* params, int variant_
  * algorithm gives the same result through these entry points too.
  * INVALID_ARGUMENT for an id outside [-1, conv2d_num_variants()). */
 CONV2D_API int conv2d_debug_force_variant(int variant_id);
+/* Debugging aid for the "_splitk" variants of the direct-to-LDS gather tiles (the reduction of
+ * an output tile split over several workgroups, for layers with few output pixels).  They add a
+ * tile's partial sums inside the convolution launch, by the last of the tile's workgroups to
+ * finish, wherever they can: an output of at most 4096 tiles with a feature count that is a
+ * multiple of 4, a stream that is not being captured into a graph, one of the 32 streams per
+ * process that such launches have been seen on.  Everything else takes a second launch that adds
+ * the partial sums.  on = 1 makes every launch of the process take the second launch, 0 (the
+ * start value) returns to the rule above; both give the sum of the partial sums in split order.
+ * It is how the tests run both paths.  INVALID_ARGUMENT for other values.  (Follows no passage
+ * of the paper.) */
+CONV2D_API int conv2d_debug_split_reduce_separate(int on);
 /* The variant conv2d_forward would use, assuming 16-byte-aligned pointers. */
 CONV2D_API int conv2d_selected_variant(const conv2d_params* params, int* variant_id);
 

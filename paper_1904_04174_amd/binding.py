@@ -29,6 +29,7 @@ EXPORTS = (
     "conv2d_forward_bias_act_pool", "conv2d_pool_workspace_size",
     "conv2d_pool_workspace_size_variant", "conv2d_packed_filter_size", "conv2d_pack_filter",
     "conv2d_forward_packed", "conv2d_last_launch_error", "conv2d_debug_force_variant",
+    "conv2d_debug_split_reduce_separate",
     "conv2d_num_variants",
     "conv2d_variant_name",
     "conv2d_variant_supports", "conv2d_selected_variant", "conv2d_select_variant",
@@ -88,6 +89,7 @@ def lib():
         l.conv2d_forward_variant.argtypes = [pp, vp, vp, vp, vp, sz, vp, ctypes.c_int]
         l.conv2d_forward_static_scratch.argtypes = [pp, vp, vp, vp, vp]
         l.conv2d_debug_force_variant.argtypes = [ctypes.c_int]
+        l.conv2d_debug_split_reduce_separate.argtypes = [ctypes.c_int]
         l.conv2d_num_variants.argtypes = []
         l.conv2d_variant_name.argtypes = [ctypes.c_int]
         l.conv2d_variant_name.restype = ctypes.c_char_p
@@ -220,6 +222,13 @@ def conv2d_debug_force_variant(variant_id):
     rc = lib().conv2d_debug_force_variant(-1 if variant_id is None else int(variant_id))
     if rc:
         raise Conv2dError(rc, "conv2d_debug_force_variant")
+
+
+def conv2d_debug_split_reduce_separate(on):
+    """True: the split-reduction variants add their partial sums in a second launch, always."""
+    rc = lib().conv2d_debug_split_reduce_separate(1 if on else 0)
+    if rc:
+        raise Conv2dError(rc, "conv2d_debug_split_reduce_separate")
 
 
 STATIC_SCRATCH_BYTES = 32 << 20   # CONV2D_STATIC_SCRATCH_BYTES

@@ -937,6 +937,12 @@ int conv2d_debug_force_variant(int variant_id) {
   return CONV2D_STATUS_OK;
 }
 
+int conv2d_debug_split_reduce_separate(int on) {
+  if (on != 0 && on != 1) return CONV2D_STATUS_INVALID_ARGUMENT;
+  igemm_dma_split_reduce_separate(on != 0);
+  return CONV2D_STATUS_OK;
+}
+
 int conv2d_num_variants(void) { return table().n; }
 
 const char* conv2d_variant_name(int variant_id) {

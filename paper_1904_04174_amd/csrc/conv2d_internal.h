@@ -100,6 +100,10 @@ hipError_t launch_igemm(const Problem& p, int bf16, int tile, int splits, hipStr
 hipError_t launch_split_reduce(const float* partial, void* out, int total, int splits,
                                bool out_bf16, const float* bias, int relu, int K,
                                hipStream_t stream);
+// The order of its additions: `groups` sums, group g over the splits g, g + groups, ... from
+// zero, then group 0's sum + group 1's + ...  (The reduction inside a launch adds in the same
+// order, so both give the same bits.)
+int split_reduce_groups(int total, int splits);
 
 // Value of `splits` that asks the direct-to-LDS kernels for whole tiles plus
 // a balanced tail instead of a uniform split.
@@ -137,6 +141,11 @@ hipError_t igemm_dma_pack_filter(const Problem& p, int bf16, int tile, void* pac
 // (a batched problem holds one repacked filter per batch and takes whole tiles only)
 size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile, int splits);
 hipError_t launch_igemm_dma(const Problem& p, int bf16, int tile, int splits, hipStream_t stream);
+// A uniform split of the reduction (splits > 1) adds its partial sums inside the convolution
+// launch where it can (the last workgroup of a tile to arrive adds them; counters in a device
+// array of the library, one bank per stream).  `on`: always use the second launch instead
+// (split_reduce_kernel), as streams under graph capture and outputs of too many tiles do anyway.
+void igemm_dma_split_reduce_separate(bool on);
 
 // The Winograd F(2x2, 3x3) point products with the output transform folded
 // in, on a direct-to-LDS tile that has such an instantiation

@@ -623,14 +623,20 @@ constexpr int kNumBf16 = sizeof(kTilesBf16) / sizeof(kTilesBf16[0]);
 
 }  // namespace
 
-hipError_t launch_split_reduce(const float* partial, void* out, int total, int splits,
-                               bool out_bf16, const float* bias, int relu, int K,
-                               hipStream_t stream) {
-  // more groups while the grid would stay under two workgroups per compute unit
+// more groups while the grid would stay under two workgroups per compute unit
+int split_reduce_groups(int total, int splits) {
   const int vecs = (total + 3) / 4;
   int groups = 1;
   while (groups < 16 && groups * 2 <= splits && (vecs + 256 / groups - 1) / (256 / groups) < 512)
     groups *= 2;
+  return groups;
+}
+
+hipError_t launch_split_reduce(const float* partial, void* out, int total, int splits,
+                               bool out_bf16, const float* bias, int relu, int K,
+                               hipStream_t stream) {
+  const int vecs = (total + 3) / 4;
+  const int groups = split_reduce_groups(total, splits);
   const int per_wg = 256 / groups;
   const dim3 grid((vecs + per_wg - 1) / per_wg), block(256);
   if (out_bf16)

@@ -61,6 +61,8 @@
 // The second half of the file is the LDS-resident patch kernel for 3x3,
 // stride-1 layers (consecutive-pixel and blocked tiles, persistent launch of
 // the blocked tiles, 16-row MFMA tiles, pooling epilogue); see there.
+#include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "buffer_lds.h"
@@ -268,7 +270,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
                                                                   const int flush_slices,
                                                                   const void* bt,
                                                                   float* partial,
-                                                                  const TailPlan tail) {
+                                                                  const TailPlan tail,
+                                                                  unsigned* split_counters,
+                                                                  const int reduce_groups) {
   constexpr int BM = T::BM, BN = T::BN, BK = T::BK, S = T::STAGES, ROWB = T::ROWB, CPR = T::CPR;
   constexpr int ES = T::ES, VEC = T::VEC, KSTEPS = T::KSTEPS;
   constexpr int TM = T::TM, TN = T::TN, NM = T::NM, NR = T::NR, MPF = T::MPF;
@@ -806,6 +810,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
     return;
   }
   const bool to_partial = gridDim.y > 1;
+  // split_counters: the workgroup of a tile that stores its partial sums last adds them all
+  // (below); the partial sums then go through memory with device-coherent stores and loads.
+  const bool in_launch = to_partial && split_counters != nullptr;
   float* part = partial + static_cast<size_t>(blockIdx.y) * static_cast<size_t>(p.M) * p.K;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -819,7 +826,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
         const int row = rbase + 8 * (v / 4) + (v % 4);
         if (row < p.M && col < p.K) {
           const size_t idx = static_cast<size_t>(row) * p.K + col;
-          if (to_partial)
+          if (in_launch)
+            __hip_atomic_store(part + idx, acc[i][j][v], __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+          else if (to_partial)
             part[idx] = acc[i][j][v];
           else if (OUT_BF16)
             store_out(static_cast<unsigned short*>(p.out) + bz * p.out_stride + idx,
@@ -834,6 +844,117 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
       }
     }
   }
+  if (!in_launch) return;
+
+  // ---- split reduction inside the launch.  Every workgroup of a tile counts itself in after
+  // its partial sums have been written; the one that finds all others counted adds the tile's
+  // partial sums in split order (so the result does not depend on which one it is), applies the
+  // epilogue and stores the output.  Nobody waits for anybody.  The workgroups of a tile run
+  // on different XCDs, whose L2 caches do not see each other's lines: the partial sums are
+  // written and read with device-scope coherent accesses (sc1), and a workgroup counts itself
+  // in only after all of its stores have been acknowledged.  The counter is left at zero for
+  // the next launch.
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wave's partial sums (and loads past the end)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  unsigned* arrived = reinterpret_cast<unsigned*>(ring);  // the ring is free from here on
+  const unsigned nsplits = gridDim.y;
+  if (tid == 0) {
+    unsigned* counter = split_counters + tile;
+    const unsigned before =
+        __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (before == nsplits - 1)
+      __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *arrived = before;
+  }
+  __syncthreads();
+  if (*arrived != nsplits - 1) return;
+
+  // Only tiles of up to 128x64 get here (the host keeps larger ones on the second launch: one
+  // workgroup would read too much), so the registers below stay under what the main loop needs.
+  if constexpr (BM * BN <= 128 * 64) {
+  // 16-byte pieces of the tile, row by row: piece f = row * (BN / 4) + column quad
+  constexpr int PER = BM * BN / 4 / T::NT;  // pieces per thread
+  // splits whose loads are in flight together (fewer where six workgroups share a unit's registers)
+  constexpr int AHEAD = PER <= 4 && T::OCC <= 4 ? 3 : 2;
+  static_assert(BM * BN / 4 % T::NT == 0, "tile pieces over the threads");
+  const __amdgpu_buffer_rsrc_t part_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      partial, 0, static_cast<int>(nsplits * static_cast<unsigned>(p.M) * p.K * 4u), kRsrcFlags);
+  const int plane_bytes = p.M * p.K * 4;
+  int piece_off[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    const int f = e * T::NT + tid;
+    const int row = m0 + f / (BN / 4), col = n0 + 4 * (f % (BN / 4));
+    piece_off[e] = (row < p.M && col < p.K) ? (row * p.K + col) * 4 : kOutOfRange;
+  }
+  // The order of the additions is split_reduce_kernel's, so that both ways give the same bits:
+  // `reduce_groups` sums, group g over the splits g, g + groups, ... from zero, then group 0's
+  // sum + group 1's + ...  The splits are visited in that order, AHEAD loads at a time.
+  floatx4 acc[PER], total[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) acc[e] = total[e] = floatx4{0.f, 0.f, 0.f, 0.f};
+  bool have_total = false;
+  int next_group = 0, next_split = 0;
+  for (unsigned done = 0; done < nsplits; done += AHEAD) {
+    uintx4 got[AHEAD][PER];
+    unsigned starts_group = 0;
+#pragma unroll
+    for (int a = 0; a < AHEAD; ++a) {
+      // (a visit past the last, like a piece outside the output, reads out of range: zeros;
+      // the range check covers the vector offset only, so the split's plane is part of it)
+      const bool live = done + a < nsplits;
+      const int plane = next_split * plane_bytes;
+      if (live) {
+        if (next_split == next_group) starts_group |= 1u << a;
+        next_split += reduce_groups;
+        if (next_split >= static_cast<int>(nsplits)) next_split = ++next_group;
+      }
+#pragma unroll
+      for (int e = 0; e < PER; ++e)
+        got[a][e] = __builtin_amdgcn_raw_buffer_load_b128(
+            part_rsrc, (live && piece_off[e] != kOutOfRange) ? piece_off[e] + plane : kOutOfRange,
+            0, 16 /* sc1 */);
+    }
+#pragma unroll
+    for (int a = 0; a < AHEAD; ++a) {
+      if (done + a >= nsplits) break;
+      if (((starts_group >> a) & 1u) && done + a > 0) {
+        // a group's sum is complete: fold it into the total
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+          total[e] = have_total ? total[e] + acc[e] : acc[e];
+          acc[e] = floatx4{0.f, 0.f, 0.f, 0.f};
+        }
+        have_total = true;
+      }
+#pragma unroll
+      for (int e = 0; e < PER; ++e)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[e][c] += __uint_as_float(got[a][e][c]);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    if (piece_off[e] == kOutOfRange) continue;
+    const floatx4 sum = have_total ? total[e] + acc[e] : acc[e];
+    const int f = e * T::NT + tid;
+    const int col = n0 + 4 * (f % (BN / 4));
+    const size_t idx = static_cast<size_t>(piece_off[e]) / 4;
+    floatx4 r;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) r[c] = finish(sum[c], bias_of(p.bias, col + c, p.K), p.relu);
+    if (OUT_BF16) {
+      typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+      uintx2 packed;
+      packed.x = to_bf16_bits(r[0]) | (static_cast<unsigned>(to_bf16_bits(r[1])) << 16);
+      packed.y = to_bf16_bits(r[2]) | (static_cast<unsigned>(to_bf16_bits(r[3])) << 16);
+      store_out(reinterpret_cast<uintx2*>(static_cast<unsigned short*>(p.out) + idx), packed);
+    } else {
+      store_out(reinterpret_cast<floatx4*>(static_cast<float*>(p.out) + idx), r);
+    }
+  }
+  }  // tiles of up to 128x64
 }
 
 // Sum of the pieces of each tail tile, in slice order, to the output.
@@ -878,6 +999,64 @@ __global__ __launch_bounds__(256) void tail_reduce_kernel(const float* __restric
         static_cast<float*>(out)[idx] = r;
     }
   }
+}
+
+// ---- counters of the split reduction inside the launch.  One counter per output tile, in banks;
+// a stream gets a bank of its own the first time it runs such a launch (launches of one stream
+// never overlap, and every launch leaves its counters at zero, which is also how the array
+// starts), so launches that run at the same time on different streams never share a counter.
+// A stream that is being captured into a graph gets none (the graph may be replayed on any
+// stream), nor does a stream that comes when all banks are taken: those launches add their
+// partial sums in a second launch, as do outputs of more tiles than a bank has counters.
+constexpr int kCounterBanks = 32;
+constexpr int kCountersPerBank = 4096;
+constexpr int kCounterDevices = 64;
+}  // namespace dma
+}  // namespace conv2d
+static __device__ unsigned split_counter_array[conv2d::dma::kCounterBanks *
+                                               conv2d::dma::kCountersPerBank];
+namespace conv2d {
+namespace dma {
+std::mutex counter_mutex;
+unsigned* counter_base[kCounterDevices] = {};
+struct BankOwner {
+  int device;
+  hipStream_t stream;
+};
+BankOwner bank_owner[kCounterBanks];
+int banks_taken = 0;
+std::atomic<int> split_reduce_separate{0};  // 1: always add the partial sums in a second launch
+
+// The stream's counter bank on the current device, or null.
+unsigned* split_counters_for(hipStream_t stream, int tiles) {
+  if (split_reduce_separate.load(std::memory_order_relaxed) || tiles > kCountersPerBank)
+    return nullptr;
+  hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &capture) != hipSuccess) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  if (capture != hipStreamCaptureStatusNone) return nullptr;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kCounterDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(counter_mutex);
+  if (!counter_base[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(split_counter_array)) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    counter_base[dev] = static_cast<unsigned*>(ptr);
+  }
+  int bank = -1;
+  for (int b = 0; b < banks_taken; ++b)
+    if (bank_owner[b].device == dev && bank_owner[b].stream == stream) bank = b;
+  if (bank < 0) {
+    if (banks_taken == kCounterBanks) return nullptr;
+    bank = banks_taken++;
+    bank_owner[bank] = BankOwner{dev, stream};
+  }
+  return counter_base[dev] + bank * kCountersPerBank;
 }
 
 // Bytes of the repacked filter at the head of the workspace (a multiple of 256).
@@ -962,11 +1141,26 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   while (flush * flush < per_split) ++flush;
   float* partial = reinterpret_cast<float*>(static_cast<unsigned char*>(p.workspace) +
                                             filter_bytes<T>(p));
+  // A uniform split adds its partial sums inside the launch where it can (whole 16-byte pieces
+  // of output rows: K a multiple of 4, an aligned output; partial sums within 2^31 bytes; a
+  // counter bank for the stream) and where it pays: the one workgroup that adds a tile's
+  // partial sums reads them at ~36 GB/s (device-coherent loads of a single compute unit,
+  // measured), so up to 96 KiB per tile cost less than the second launch's ~5 us (a 56x56x256
+  // -> 256 layer at batch 1 with 6 splits of 64x64 tiles: 45.2 -> 42.3 us; 14x14x512 -> 512 at
+  // batch 1 with 18 splits: 22.0 -> 25.3 us, so that one keeps the second launch).
+  unsigned* counters = nullptr;
+  if (splits > 1 && tail.wgs == 0 && p.K % 4 == 0 && T::BM * T::BN <= 128 * 64 &&
+      splits * T::BM * T::BN * 4 <= 96 * 1024 &&
+      reinterpret_cast<uintptr_t>(p.out) % (OUT_BF16 ? 8 : 16) == 0 &&
+      static_cast<unsigned long long>(splits) * p.M * p.K * 4ull < (1ull << 31))
+    counters = split_counters_for(stream, tail.n_main);
   hipLaunchKernelGGL((igemm_dma_kernel<T, OUT_BF16>),
                      dim3(tail.n_main + 2 * tail.wgs, splits, batches), dim3(T::NT), 0, stream, p,
-                     Kg_p, per_split, flush, bt, partial, tail);
+                     Kg_p, per_split, flush, bt, partial, tail, counters,
+                     split_reduce_groups(p.M * p.K, splits));
   e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (counters) return hipSuccess;
   // 3. sum of the partial outputs
   if (tail.wgs > 0) {
     const int rest = ((p.M + T::BM - 1) / T::BM) * ((p.K + T::BN - 1) / T::BN) - tail.n_main;
@@ -1006,7 +1200,8 @@ hipError_t launch_wino(const Problem& p, hipStream_t stream) {
   const int tiles = ((p.M + T::BM - 1) / T::BM) * ((p.K + T::BN - 1) / T::BN);
   const TailPlan none = {tiles, 0, 0, 0, 0};
   hipLaunchKernelGGL((igemm_dma_kernel<T, false, true>), dim3(tiles, 1, 1), dim3(T::NT), 0, stream,
-                     p, Kg_p, Kg_p / T::BK, p.C / T::BK, bt, static_cast<float*>(nullptr), none);
+                     p, Kg_p, Kg_p / T::BK, p.C / T::BK, bt, static_cast<float*>(nullptr), none,
+                     static_cast<unsigned*>(nullptr), 1);
   return hipGetLastError();
 }
 
@@ -2176,6 +2371,9 @@ size_t igemm_dma_workspace_bytes(const Problem& p, int bf16, int tile, int split
 }
 hipError_t launch_igemm_dma(const Problem& p, int bf16, int tile, int splits, hipStream_t stream) {
   return entry(bf16, tile).fn(p, splits, stream);
+}
+void igemm_dma_split_reduce_separate(bool on) {
+  split_reduce_separate.store(on ? 1 : 0, std::memory_order_relaxed);
 }
 
 }  // namespace conv2d

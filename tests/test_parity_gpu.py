@@ -899,6 +899,104 @@ def test_packed_filter_full_size(torch_cuda, oracle, name, in_dtype):
     assert err <= (TOL_F32 if in_dtype == B.F32 else TOL_BF16), (name, err)
 
 
+# Shapes whose "_splitk" gather variants add their partial sums inside the convolution launch
+# (64x64 tiles, 196 of them or more, so at most 6 splits: 96 KiB of partial sums per tile), with
+# ragged tiles in M and in K, and a feature count that is a multiple of 4 but not of 32.
+SPLIT_IN_LAUNCH = [
+    (4, 28, 28, 64, 256, 3, 3, 1, 1, wl.PAD_SAME),     # 49 x 4 whole tiles, 6 splits
+    (3, 30, 31, 32, 260, 3, 3, 1, 1, wl.PAD_SAME),     # ragged in M and K, K % 32 = 4
+    (5, 27, 27, 48, 200, 3, 3, 2, 2, wl.PAD_VALID),    # stride 2, two splits
+]
+
+
+def _gather_split_variants(p):
+    return [i for i in supported_variants(p)
+            if B.conv2d_variant_name(i).startswith("igemm_dma_")
+            and B.conv2d_variant_name(i).endswith("_splitk")]
+
+
+@pytest.mark.parametrize("case", SPLIT_IN_LAUNCH)
+@pytest.mark.parametrize("in_dtype,out_dtype", [(B.F32, B.F32), (B.BF16, B.F32), (B.BF16, B.BF16)])
+def test_split_reduction_inside_the_launch(torch_cuda, oracle, case, in_dtype, out_dtype):
+    """The split-reduction gather variants with the sum of the partial tiles inside the launch
+    and in a second launch: both match the oracle and give the same bits (the additions run in
+    the same order), with a fused bias and ReLU as well, on calls that reuse one workspace with
+    fresh inputs (a stale partial tile would show)."""
+    torch = torch_cuda
+    dev = torch.device("cuda:0")
+    n, h, w, c, k, r, s, sr, sc, pad = case
+    p = _params(case, in_dtype, out_dtype)
+    ids = _gather_split_variants(p)
+    assert ids, "no split-reduction gather variant supports %s" % (case,)
+    tol = TOL_F32 if in_dtype == B.F32 else TOL_BF16
+    in_dt = torch.float32 if in_dtype == B.F32 else torch.bfloat16
+    out_dt = torch.float32 if out_dtype == B.F32 else torch.bfloat16
+    g = B.conv2d_get_geometry(p)
+    bias = np.linspace(-2.0, 2.0, k).astype(np.float32)
+    bd = torch.from_numpy(bias).to(dev)
+    inputs = []
+    for rep in range(3):
+        x, f = wl.make_case((n, h, w, c), (r, s, c, k), "uniform", 5100 + 17 * rep + sum(case))
+        if in_dtype == B.BF16:
+            x, f = wl.round_to_bf16(x)[0], wl.round_to_bf16(f)[0]
+        inputs.append((x, f, oracle.forward_bias_act_f32(x, f, bias, True, (sr, sc), pad)))
+    try:
+        for vid in ids:
+            _say("split reduction %s %s" % (case, B.conv2d_variant_name(vid)))
+            ws = torch.empty(max(B.conv2d_workspace_size(p, vid), 16), dtype=torch.uint8, device=dev)
+            got = {}
+            for separate in (1, 0):
+                B.conv2d_debug_split_reduce_separate(separate)
+                B.conv2d_debug_force_variant(vid)
+                for rep, (x, f, want) in enumerate(inputs):
+                    xd = torch.from_numpy(x).to(dev).to(in_dt)
+                    fd = torch.from_numpy(f).to(dev).to(in_dt)
+                    out = torch.full((n, g.out_rows, g.out_cols, k), float("nan"), dtype=out_dt,
+                                     device=dev)
+                    B.conv2d_forward_bias_act(p, xd, fd, bd, B.ACT_RELU, out=out, workspace=ws)
+                    torch.cuda.synchronize()
+                    res = out.float().cpu().numpy()
+                    assert not np.isnan(res).any(), (B.conv2d_variant_name(vid), separate, rep)
+                    assert rel_err(res, want) <= tol, (B.conv2d_variant_name(vid), separate, rep)
+                    got[(separate, rep)] = res
+            for rep in range(len(inputs)):
+                assert np.array_equal(got[(0, rep)], got[(1, rep)]), (B.conv2d_variant_name(vid), rep)
+    finally:
+        B.conv2d_debug_force_variant(None)
+        B.conv2d_debug_split_reduce_separate(0)
+
+
+def test_split_reduction_inside_the_launch_on_two_streams(torch_cuda, oracle):
+    """Launches with the reduction inside run at the same time on two streams (each stream has
+    its own counters) and are repeated back to back on each: every output matches the oracle."""
+    torch = torch_cuda
+    dev = torch.device("cuda:0")
+    case = SPLIT_IN_LAUNCH[0]
+    n, h, w, c, k, r, s, sr, sc, pad = case
+    p = _params(case)
+    vid = B.variant_id_by_name("igemm_dma_f32_64x64_r64_w2x2_s4_nat_splitk")
+    assert B.conv2d_variant_supports(p, vid)
+    g = B.conv2d_get_geometry(p)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    jobs = []
+    for i, st in enumerate(streams):
+        x, f = wl.make_case((n, h, w, c), (r, s, c, k), "uniform", 6200 + i)
+        want = oracle.forward_f32(x, f, (sr, sc), pad)
+        xd, fd = torch.from_numpy(x).to(dev), torch.from_numpy(f).to(dev)
+        ws = torch.empty(max(B.conv2d_workspace_size(p, vid), 16), dtype=torch.uint8, device=dev)
+        outs = [torch.full((n, g.out_rows, g.out_cols, k), float("nan"), device=dev) for _ in range(8)]
+        jobs.append((st, xd, fd, ws, outs, want))
+    torch.cuda.synchronize()
+    for rep in range(8):
+        for st, xd, fd, ws, outs, _ in jobs:
+            B.conv2d_forward(p, xd, fd, out=outs[rep], workspace=ws, stream=st, variant_id=vid)
+    torch.cuda.synchronize()
+    for _, _, _, _, outs, want in jobs:
+        for o in outs:
+            assert rel_err(o.cpu().numpy(), want) <= TOL_F32
+            assert torch.equal(o, outs[0])
+
+
 def test_library_loaded_before_torch(torch_cuda):
     """A process that touches the library before it imports torch must not end up with two HIP
     runtimes (torch ships its own): the binding loads torch's first.  Run in a child process,
