@@ -22,7 +22,7 @@ namespace {
 constexpr long long kMaxElems = (1LL << 31) - 1;
 
 enum Family { kDirect = 0, kIgemm = 1, kDma = 2, kWinograd = 3, kPadded = 4, kRowGather = 5, kConv1x1 = 6,
-              kWinogradLds = 7 };
+              kWinogradLds = 7, kRegFilter = 8 };
 // (kWinograd: transform passes around the products; kWinogradLds: everything in one launch)
 inline bool is_winograd(int family) { return family == kWinograd || family == kWinogradLds; }
 enum Split { kWhole = 0, kSplit = 1, kTail = 2, kFused = 3 };
@@ -95,6 +95,8 @@ struct Table {
     // the streaming kernel for 1x1 windows
     for (int t = 0; t < conv1x1_num_tiles(); ++t)
       add(kConv1x1, conv1x1_tile_bf16(t), t, kWhole, conv1x1_tile_name(t));
+    // 3x3 bf16 layers of 64 channels and features: the filter in registers
+    add(kRegFilter, 1, 0, kWhole, "conv3x3_bf16_regfilter_256x64");
   }
 };
 const Table& table() {
@@ -193,6 +195,7 @@ bool supports(const Variant& v, const Problem& q) {
   if (v.family == kRowGather) return row_gather_supports(q);
   if (v.family == kWinogradLds) return winograd_lds_supports(q);
   if (v.family == kConv1x1) return conv1x1_supports(q, v.tile);
+  if (v.family == kRegFilter) return conv3x3_regfilter_supports(q);
   if (v.family == kPadded) {
     if (v.bf16 != q.in_bf16 || (!q.in_bf16 && q.out_bf16)) return false;
     return padded_supports(q, v.tile);
@@ -365,6 +368,17 @@ double model_cost(const Variant& v, const Problem& q) {
                          (q.out_bf16 ? 2.0 : 4.0) * q.M * q.K;
     const double stream = bytes / 1900.0;
     return (mfma > stream ? mfma : stream) * 1.1 + 4000.0 + kLaunchCycles;
+  }
+  if (v.family == kRegFilter) {
+    // a stream like the 1x1 kernel: the products at about half the MFMA rate or the tensors'
+    // bytes at the chip's streaming rate, whichever is larger, one launch, tiles of 16x16
+    // pixels (ragged blocks at the image edge are computed whole), 256 persistent workgroups
+    const double blocks = 1.0 * q.N * ceil_div_ll(q.P, 16) * ceil_div_ll(q.Q, 16);
+    const double rounds = static_cast<double>(ceil_div_ll(static_cast<long long>(blocks), 256));
+    const double mfma = rounds * 256.0 * 64.0 * q.Kg / 2048.0 / 0.5;
+    const double bytes = 2.0 * q.N * q.H * q.W * q.C * 1.27 + (q.out_bf16 ? 2.0 : 4.0) * q.M * q.K;
+    const double stream = bytes / 1900.0;
+    return (mfma > stream ? mfma : stream) * 1.05 + 6000.0 + kLaunchCycles;
   }
   if (v.family == kPadded) {
     // the gather tile on the padded problem, the padding passes' traffic, two more launches
@@ -564,7 +578,7 @@ size_t packed_filter_bytes_for(const Variant& v, const Problem& q, bool* ok) {
   if (v.family == kPadded) return padded_packed_filter_bytes(q, v.tile);
   if (v.family == kDma) return igemm_dma_packed_filter_bytes(q, v.bf16, v.tile);
   if (v.family == kDirect || v.family == kIgemm || v.family == kRowGather ||
-      v.family == kConv1x1)  // these read the filter as it is: a copy
+      v.family == kConv1x1 || v.family == kRegFilter)  // these read the filter as it is: a copy
     return align256(static_cast<size_t>(q.Kg) * q.K * (q.in_bf16 ? 2 : 4));
   if (v.family == kWinograd) return winograd_packed_filter_bytes(q, v.tile, v.split == kFused);
   if (v.family == kWinogradLds) return winograd_lds_packed_filter_bytes(q);
@@ -697,6 +711,7 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     case kPadded: e = launch_padded(q, tb.v[id].tile, stream); break;
     case kRowGather: e = launch_row_gather(q, stream); break;
     case kConv1x1: e = launch_conv1x1(q, tb.v[id].tile, stream); break;
+    case kRegFilter: e = launch_conv3x3_regfilter(q, stream); break;
     case kWinograd:
       e = launch_winograd(q, tb.v[id].tile, tb.v[id].split == kFused, stream);
       break;

@@ -997,6 +997,49 @@ def test_split_reduction_inside_the_launch_on_two_streams(torch_cuda, oracle):
             assert torch.equal(o, outs[0])
 
 
+# 3x3, stride 1, 64 channels, 64 features: the shapes of the kernel that keeps the filter in
+# registers.  Ragged 16x16 blocks at the right and lower edge, blocks that are all padding but
+# one row, more tiles than workgroups (so a workgroup walks several), VALID padding, one block.
+REGFILTER_CASES = [
+    (2, 37, 29, 64, 64, 3, 3, 1, 1, wl.PAD_SAME),
+    (1, 18, 50, 64, 64, 3, 3, 1, 1, wl.PAD_VALID),
+    (3, 160, 176, 64, 64, 3, 3, 1, 1, wl.PAD_SAME),    # 330 blocks on 256 workgroups
+    (1, 5, 7, 64, 64, 3, 3, 1, 1, wl.PAD_SAME),
+]
+
+
+@pytest.mark.parametrize("case", REGFILTER_CASES)
+def test_filter_in_registers_kernel_bf16(torch_cuda, oracle, case):
+    """conv3x3_bf16_regfilter_256x64 against the oracle: fp32 and bf16 output, integer inputs
+    bit-exact, bias + ReLU through the fused entry point, twice in a row with the same bits."""
+    n, h, w, c, k, r, s, sr, sc, pad = case
+    vid = B.variant_id_by_name("conv3x3_bf16_regfilter_256x64")
+    x, f = wl.make_case((n, h, w, c), (r, s, c, k), "uniform", 8300 + sum(case))
+    x, f = wl.round_to_bf16(x)[0], wl.round_to_bf16(f)[0]
+    want = oracle.forward_f32(x, f, (sr, sc), pad)
+    xi, fi = wl.make_case((n, h, w, c), (r, s, c, k), "ints", 8400 + sum(case))
+    want_i = oracle.forward_f32(xi, fi, (sr, sc), pad)
+    for out_dtype in (B.F32, B.BF16):
+        p = _params(case, B.BF16, out_dtype)
+        assert B.conv2d_variant_supports(p, vid)
+        _say("filter in registers %s out %d" % (case, out_dtype))
+        got = run_gpu(torch_cuda, p, x, f, vid)
+        assert got.shape == want.shape
+        assert rel_err(got, want) <= TOL_BF16, (case, out_dtype, rel_err(got, want))
+        assert np.array_equal(got, run_gpu(torch_cuda, p, x, f, vid))
+        if out_dtype == B.F32:
+            assert np.array_equal(run_gpu(torch_cuda, p, xi, fi, vid), want_i), case
+    p = _params(case, B.BF16, B.F32)
+    bias = np.linspace(-3.0, 3.0, k).astype(np.float32)
+    want_b = oracle.forward_bias_act_f32(x, f, bias, True, (sr, sc), pad)
+    got_b = run_gpu_fused(torch_cuda, p, x, f, bias, B.ACT_RELU, force=vid)
+    assert rel_err(got_b, want_b) <= TOL_BF16
+    # not for other shapes or types
+    assert not B.conv2d_variant_supports(_params(case, B.F32, B.F32), vid)
+    assert not B.conv2d_variant_supports(
+        B.make_params(n, h, w, c, 128, r, s, sr, sc, pad, B.BF16, B.F32), vid)
+
+
 def test_library_loaded_before_torch(torch_cuda):
     """A process that touches the library before it imports torch must not end up with two HIP
     runtimes (torch ships its own): the binding loads torch's first.  Run in a child process,
