@@ -92,6 +92,7 @@ FAMILIES = (
     ("Winograd F(2x2,3x3), one launch", lambda n: n.startswith("winograd2x2_lds_")),
     ("window-row gather", lambda n: n.startswith("rowgather_")),
     ("1x1 streaming", lambda n: n.startswith("conv1x1_")),
+    ("3x3, filter in registers", lambda n: n.startswith("conv3x3_")),
 )
 
 
