@@ -96,7 +96,8 @@ struct Table {
     for (int t = 0; t < conv1x1_num_tiles(); ++t)
       add(kConv1x1, conv1x1_tile_bf16(t), t, kWhole, conv1x1_tile_name(t));
     // 3x3 bf16 layers of 64 channels and features: the filter in registers
-    add(kRegFilter, 1, 0, kWhole, "conv3x3_bf16_regfilter_256x64");
+    for (int t = 0; t < conv3x3_regfilter_num_tiles(); ++t)
+      add(kRegFilter, 1, t, kWhole, conv3x3_regfilter_tile_name(t));
   }
 };
 const Table& table() {
@@ -195,7 +196,7 @@ bool supports(const Variant& v, const Problem& q) {
   if (v.family == kRowGather) return row_gather_supports(q);
   if (v.family == kWinogradLds) return winograd_lds_supports(q);
   if (v.family == kConv1x1) return conv1x1_supports(q, v.tile);
-  if (v.family == kRegFilter) return conv3x3_regfilter_supports(q);
+  if (v.family == kRegFilter) return conv3x3_regfilter_supports(q, v.tile);
   if (v.family == kPadded) {
     if (v.bf16 != q.in_bf16 || (!q.in_bf16 && q.out_bf16)) return false;
     return padded_supports(q, v.tile);
@@ -373,12 +374,16 @@ double model_cost(const Variant& v, const Problem& q) {
     // a stream like the 1x1 kernel: the products at about half the MFMA rate or the tensors'
     // bytes at the chip's streaming rate, whichever is larger, one launch, tiles of 16x16
     // pixels (ragged blocks at the image edge are computed whole), 256 persistent workgroups
-    const double blocks = 1.0 * q.N * ceil_div_ll(q.P, 16) * ceil_div_ll(q.Q, 16);
+    const int rows = conv3x3_regfilter_tile_rows(v.tile);
+    const double blocks = 1.0 * q.N * ceil_div_ll(q.P, rows) * ceil_div_ll(q.Q, 16);
     const double rounds = static_cast<double>(ceil_div_ll(static_cast<long long>(blocks), 256));
-    const double mfma = rounds * 256.0 * 64.0 * q.Kg / 2048.0 / 0.5;
-    const double bytes = 2.0 * q.N * q.H * q.W * q.C * 1.27 + (q.out_bf16 ? 2.0 : 4.0) * q.M * q.K;
+    const double mfma = rounds * rows * 16.0 * q.K * q.Kg / 2048.0 / 0.6;
+    const double halo = (rows + 2.0) * 18.0 / (rows * 16.0);
+    const double bytes = 2.0 * q.N * q.H * q.W * q.C * halo + (q.out_bf16 ? 2.0 : 4.0) * q.M * q.K;
     const double stream = bytes / 1900.0;
-    return (mfma > stream ? mfma : stream) * 1.05 + 6000.0 + kLaunchCycles;
+    // (the start: the filter through LDS into the registers of every workgroup)
+    return (mfma > stream ? mfma : stream) * 1.05 + 4000.0 + 2.0 * q.Kg * q.K / 64.0 +
+           kLaunchCycles;
   }
   if (v.family == kPadded) {
     // the gather tile on the padded problem, the padding passes' traffic, two more launches
@@ -711,7 +716,7 @@ int run(const conv2d_params* params, const void* in, const void* filt, void* out
     case kPadded: e = launch_padded(q, tb.v[id].tile, stream); break;
     case kRowGather: e = launch_row_gather(q, stream); break;
     case kConv1x1: e = launch_conv1x1(q, tb.v[id].tile, stream); break;
-    case kRegFilter: e = launch_conv3x3_regfilter(q, stream); break;
+    case kRegFilter: e = launch_conv3x3_regfilter(q, tb.v[id].tile, stream); break;
     case kWinograd:
       e = launch_winograd(q, tb.v[id].tile, tb.v[id].split == kFused, stream);
       break;

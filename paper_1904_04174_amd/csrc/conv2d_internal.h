@@ -79,11 +79,15 @@ int conv1x1_tile_features(int tile);
 bool conv1x1_supports(const Problem& p, int tile);
 hipError_t launch_conv1x1(const Problem& p, int tile, hipStream_t stream);
 
-// 3x3, stride-1 bf16 layers with 64 channels and 64 features (conv3x3_regfilter.hip): persistent
-// workgroups that keep the whole filter in registers and stream 16x16-pixel tiles through a
-// double-buffered LDS patch.  No workspace; reads the filter as it is.
-bool conv3x3_regfilter_supports(const Problem& p);
-hipError_t launch_conv3x3_regfilter(const Problem& p, hipStream_t stream);
+// 3x3, stride-1 bf16 layers with 64 channels and 64 features, or 128 and 128
+// (conv3x3_regfilter.hip): persistent workgroups that keep the whole filter in registers and
+// stream tiles of `rows` x 16 pixels through a double-buffered LDS patch.  No workspace; reads
+// the filter as it is.
+int conv3x3_regfilter_num_tiles();
+const char* conv3x3_regfilter_tile_name(int tile);
+int conv3x3_regfilter_tile_rows(int tile);
+bool conv3x3_regfilter_supports(const Problem& p, int tile);
+hipError_t launch_conv3x3_regfilter(const Problem& p, int tile, hipStream_t stream);
 
 // Launchers (one per kernel family).  Each returns hipSuccess or the launch
 // error; none synchronises.  `tile` selects a compiled tile configuration.

@@ -1005,12 +1005,14 @@ REGFILTER_CASES = [
     (1, 18, 50, 64, 64, 3, 3, 1, 1, wl.PAD_VALID),
     (3, 160, 176, 64, 64, 3, 3, 1, 1, wl.PAD_SAME),    # 330 blocks on 256 workgroups
     (1, 5, 7, 64, 64, 3, 3, 1, 1, wl.PAD_SAME),
+    (1, 200, 200, 64, 64, 3, 3, 1, 1, wl.PAD_SAME),    # 169 blocks: one per workgroup, ragged edges
+    (6, 160, 176, 64, 64, 3, 3, 1, 1, wl.PAD_VALID),   # 660 blocks: three buffers in rotation
 ]
 
 
 @pytest.mark.parametrize("case", REGFILTER_CASES)
 def test_filter_in_registers_kernel_bf16(torch_cuda, oracle, case):
-    """conv3x3_bf16_regfilter_256x64 against the oracle: fp32 and bf16 output, integer inputs
+    """The filter-in-registers kernel against the oracle: fp32 and bf16 output, integer inputs
     bit-exact, bias + ReLU through the fused entry point, twice in a row with the same bits."""
     n, h, w, c, k, r, s, sr, sc, pad = case
     vid = B.variant_id_by_name("conv3x3_bf16_regfilter_256x64")
@@ -1037,7 +1039,7 @@ def test_filter_in_registers_kernel_bf16(torch_cuda, oracle, case):
     # not for other shapes or types
     assert not B.conv2d_variant_supports(_params(case, B.F32, B.F32), vid)
     assert not B.conv2d_variant_supports(
-        B.make_params(n, h, w, c, 128, r, s, sr, sc, pad, B.BF16, B.F32), vid)
+        B.make_params(n, h, w, c, 192 - c, r, s, sr, sc, pad, B.BF16, B.F32), vid)
 
 
 def test_library_loaded_before_torch(torch_cuda):
