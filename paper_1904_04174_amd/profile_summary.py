@@ -46,6 +46,7 @@ KINDS = (
     ("pad_channels", "pad_channels"), ("repack", "repack_filter_kernel"),
     ("convolution", "igemm_dma_kernel"), ("convolution", "igemm_patch_kernel"),
     ("convolution", "igemm_kernel"), ("convolution", "conv1x1_kernel"),
+    ("convolution", "conv3x3_regfilter_kernel"),
     ("convolution", "row_gather_kernel"), ("convolution", "direct_kernel"),
     ("tail_reduce", "tail_reduce_kernel"), ("split_reduce", "split_reduce_kernel"),
     ("output_transform", "output_transform"), ("max_pool", "max_pool_2x2_kernel"),
