@@ -1071,7 +1071,10 @@ def test_calls_can_be_captured_in_a_hip_graph(torch_cuda, oracle):
     torch = torch_cuda
     dev = torch.device("cuda:0")
     cases = [(1, 14, 14, 512, 512, 3, 3), (16, 28, 28, 128, 128, 3, 3), (4, 56, 56, 64, 64, 3, 3),
-             (8, 28, 28, 64, 256, 1, 1)]
+             (8, 28, 28, 64, 256, 1, 1),
+             # a split reduction that adds its partial sums inside the launch when called
+             # directly and in a second launch under capture: the same bits either way
+             (1, 56, 56, 256, 256, 3, 3)]
     jobs = []
     for i, (n, hw, _, c, k, r, s) in enumerate(cases):
         p = B.make_params(n, hw, hw, c, k, r, s)
