@@ -14,11 +14,13 @@
 //    reduction indices in Kg / 4 = 144 registers per lane (steps of 16 indices x 4 registers),
 //    read once from the HWCF filter as it lies (through LDS and transposing reads);
 //  * a tile is a block of 16 x 16 output pixels of one image; its 18 x 18 x 64 input patch is
-//    fetched by direct global->LDS loads, whole pixels per load instruction, into one of three
+//    fetched by direct global->LDS loads, whole pixels per load instruction, into one of two
 //    buffers (entry by entry, the 16-byte chunks XOR-swizzled so that a fragment read is
-//    conflict free), two tiles ahead of its use: the loop reads only the pixel operand from LDS;
+//    conflict free), the next tile's during the current tile's first steps: the loop reads only
+//    the pixel operand from LDS;
 //  * a finished pass's sums are held in registers and stored one by one during the next pass's
-//    steps, at the rate the memory system takes them, never in a burst;
+//    steps, at the rate the memory system takes them, never in a burst; the wait for the next
+//    patch at a tile's end counts the stores issued since its loads and leaves them in flight;
 //  * one barrier per tile;
 //  * workgroup i runs on XCD i % 8; every XCD walks a contiguous range of tiles, its 32
 //    workgroups on neighbouring blocks, so that the halo rows of a block come from its L2.
@@ -75,9 +77,8 @@ struct Cfg {
   static constexpr int PASS_ROWS = KG * ROW_BYTES <= 96 * 1024 ? KG : 96 * 1024 / ROW_BYTES;
   static constexpr int FPASSES = KG / PASS_ROWS;
   static constexpr int PASS_BYTES = PASS_ROWS * ROW_BYTES;
-  // three patch buffers; the staging copy overlies the second and third
-  static constexpr int LDS_BYTES = 3 * PATCH_BYTES;
-  static_assert(PASS_BYTES <= 2 * PATCH_BYTES, "staging copy behind the first buffer");
+  // two patch buffers; the staging copy overlies the second and what lies behind it
+  static constexpr int LDS_BYTES = PATCH_BYTES + (PASS_BYTES > PATCH_BYTES ? PASS_BYTES : PATCH_BYTES);
   // bank swizzle of the staged filter rows, in 32-byte pieces (as the native gather tiles)
   static constexpr int swizzle(int k) { return K >= 128 ? ((k & 3) << 1) : (((k >> 1) & 1) << 1); }
   // bf16 output only where the registers allow it: with 128 channels the conversion's
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(T::NT) void conv3x3_regfilter_kernel(const Problem 
                                                                   const int blocks_x,
                                                                   const int blocks_y) {
   constexpr int C = T::C, K = T::K, BH = T::BH, TM = T::TM;
-  // [patch buffer 0 | 1 | 2]; the filter's staging copy overlies buffers 1 and 2
+  // [patch buffer 0 | 1]; the filter's staging copy overlies buffer 1 and beyond
   __shared__ __align__(1024) unsigned char lds[T::LDS_BYTES];
   unsigned char* const patch = lds;
 
@@ -262,38 +263,39 @@ __global__ __launch_bounds__(T::NT) void conv3x3_regfilter_kernel(const Problem 
     const int i = k / 16, v = k % 16;
     const int r = i * 32 + 8 * (v / 4) + (v % 4);   // pixel of the pass's, without 4 lk
     const int py = r / kBW, px = r % kBW;
-    if (py < held_rows) {
-      const int voff = px < held_cols ? lane_off : kOutOfRange;
-      const int soff = ((held_row0 + py) * p.Q + px) * K * OES;
-      const float x = finish(hold[i][v], bias_col, p.relu);
-      if (OUT_BF16)
-        __builtin_amdgcn_raw_buffer_store_b16(to_bf16_bits(x), out_rsrc, voff, soff, 2 /* nt */);
-      else
-        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(x), out_rsrc, voff, soff, 2);
-    }
+    // (always issued: a pixel outside the image has an out-of-range vector offset, and a scalar
+    // offset of zero so that the sum of the two is out of range as well)
+    const bool row_ok = py < held_rows;
+    const int voff = (row_ok && px < held_cols) ? lane_off : kOutOfRange;
+    const int soff = row_ok ? ((held_row0 + py) * p.Q + px) * K * OES : 0;
+    const float x = finish(hold[i][v], bias_col, p.relu);
+    if (OUT_BF16)
+      __builtin_amdgcn_raw_buffer_store_b16(to_bf16_bits(x), out_rsrc, voff, soff, 2 /* nt */);
+    else
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(x), out_rsrc, voff, soff, 2);
   };
   constexpr int STORES = TMU * 16;
   constexpr int STORE_EVERY = UNIT_STEPS / STORES >= 2 ? 2 : 1;
-  constexpr int LOAD_EVERY = TILE_STEPS / T::LOADS;
-  static_assert(STORES * STORE_EVERY <= UNIT_STEPS && LOAD_EVERY >= 1, "stores over a pass");
+  static_assert(T::LOADS + STORES <= UNIT_STEPS && STORES * STORE_EVERY <= UNIT_STEPS,
+                "loads, then stores, over a pass");
 
-  // Three patch buffers: tile t is read from buffer t % 3 while the loads of tile t + 2 are
-  // issued and tile t + 1's, issued a tile ago, have time to land.
+  // Two patch buffers.  During a tile's first steps the wave issues its loads of the next
+  // tile's patch (one per step), then the held stores, one per step or every other step; at the
+  // tile's end it waits until no more operations are outstanding than it has issued since the
+  // last of those loads (a wave's memory operations retire in the order issued, loads and
+  // stores alike: what the compiler's own wait counts rely on), so the patch has landed and the
+  // stores just issued are not waited for.  Every store of a tile is issued, those outside the
+  // image with an out-of-range offset, so that the count is known.
+  constexpr int AFTER_LOADS = T::PASSES * STORES < 63 ? T::PASSES * STORES : 63;
+  constexpr int AFTER_LOADS_FIRST = (T::PASSES - 1) * STORES < 63 ? (T::PASSES - 1) * STORES : 63;
   int next_tile = tile + tile_step;
-  int nn = 0, np = 0, nq = 0;
-  if (next_tile < range_end) {
-    block_of(next_tile, nn, np, nq);
-#pragma unroll
-    for (int j = 0; j < T::LOADS; ++j) load_chunk(1, j, nn, np, nq);
-  }
   int buf = 0;
   for (;;) {
-    const int tile2 = tile + 2 * tile_step;
-    const bool has2 = tile2 < range_end;
-    int n2 = 0, p2 = 0, q2 = 0;
-    if (has2) block_of(tile2, n2, p2, q2);
-    const int buf2 = buf >= 1 ? buf - 1 : 2;   // (buf + 2) % 3
+    const bool has_next = next_tile < range_end;
+    int nn = 0, np = 0, nq = 0;
+    if (has_next) block_of(next_tile, nn, np, nq);
     const int buf_off = buf * T::PATCH_BYTES;
+    const bool first_tile = !have_hold;
 
     floatx16 acc[TMU];
 #pragma unroll
@@ -332,26 +334,22 @@ __global__ __launch_bounds__(T::NT) void conv3x3_regfilter_kernel(const Problem 
         }
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (s % STORE_EVERY == 0 && s / STORE_EVERY < STORES) {
-        if (have_hold) store_held(s / STORE_EVERY);
+      if (S < T::LOADS) {
+        // (every wave passed the barrier before this tile, so nobody still reads that buffer)
+        if (has_next) load_chunk(buf ^ 1, S, nn, np, nq);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (S % LOAD_EVERY == LOAD_EVERY / 2 && S / LOAD_EVERY < T::LOADS) {
-        // (every wave passed the barrier before this tile, so nobody still reads that buffer)
-        if (has2) load_chunk(buf2, S / LOAD_EVERY, n2, p2, q2);
+      const int ks = pass == 0 ? s - T::LOADS : (s % STORE_EVERY == 0 ? s / STORE_EVERY : -1);
+      if (ks >= 0 && ks < STORES) {
+        if (have_hold) store_held(ks);
         __builtin_amdgcn_sched_barrier(0);
       }
       if (s == UNIT_STEPS - 1) {
-        if (pass == T::PASSES - 1) {
-          // This wave's loads of the next tile's patch have landed: they are older than the
-          // LOADS loads issued above, and loads complete in order, so with one of them
-          // outstanding all of those are as well and the count is above LOADS (stores, which
-          // may complete in any order relative to loads, can only make the wait longer).
-          // Without loads above: everything.
-          if (has2)
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(T::LOADS));
+        if (pass == T::PASSES - 1 && has_next) {
+          if (first_tile)
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(AFTER_LOADS_FIRST));
           else
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(AFTER_LOADS));
         }
         hold_pass(acc, pass, bn, bp, bq);
 #pragma unroll
@@ -361,7 +359,7 @@ __global__ __launch_bounds__(T::NT) void conv3x3_regfilter_kernel(const Problem 
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-    if (next_tile >= range_end) break;
+    if (!has_next) break;
     __builtin_amdgcn_s_barrier();   // the next patch is whole; this tile's buffer is free
     asm volatile("" ::: "memory");
     tile = next_tile;
@@ -369,10 +367,7 @@ __global__ __launch_bounds__(T::NT) void conv3x3_regfilter_kernel(const Problem 
     bn = nn;
     bp = np;
     bq = nq;
-    nn = n2;
-    np = p2;
-    nq = q2;
-    buf = buf == 2 ? 0 : buf + 1;
+    buf ^= 1;
   }
   // the last pass's sums
 #pragma unroll
@@ -418,8 +413,8 @@ struct Entry {
 using Cfg64 = Cfg<64, 16, 4, 2, 2, 1>;
 // (Cfg<128, 8, 1, 4, 2, 2>, 128 channels -> 128 features on 8 x 16 tiles with 4 waves of 288
 // operand registers each, passes the same tests and is not compiled in: a 112x112 layer at batch
-// 16 takes it 68 us against 56 us on the 16-row patch tile, 59 us with its stores switched off:
-// with one wave per SIMD nothing covers a wave's waits.)
+// 16 takes it 67-68 us against 56-59 us on the 16-row patch tile, 30 us with its stores and loads
+// switched off: four waves do not keep enough stores in flight to fill the chip's store rate.)
 const Entry kEntries[] = {
     {"conv3x3_bf16_regfilter_256x64", 16, &supports<Cfg64>, &launch<Cfg64>},
 };

@@ -1006,7 +1006,7 @@ REGFILTER_CASES = [
     (3, 160, 176, 64, 64, 3, 3, 1, 1, wl.PAD_SAME),    # 330 blocks on 256 workgroups
     (1, 5, 7, 64, 64, 3, 3, 1, 1, wl.PAD_SAME),
     (1, 200, 200, 64, 64, 3, 3, 1, 1, wl.PAD_SAME),    # 169 blocks: one per workgroup, ragged edges
-    (6, 160, 176, 64, 64, 3, 3, 1, 1, wl.PAD_VALID),   # 660 blocks: three buffers in rotation
+    (6, 160, 176, 64, 64, 3, 3, 1, 1, wl.PAD_VALID),   # 660 blocks: both buffers in rotation
 ]
 
 
