@@ -156,6 +156,10 @@ hipError_t launch_igemm_dma(const Problem& p, int bf16, int tile, int splits, hi
 // array of the library, one bank per stream).  `on`: always use the second launch instead
 // (split_reduce_kernel), as streams under graph capture and outputs of too many tiles do anyway.
 void igemm_dma_split_reduce_separate(bool on);
+// The calling stream's bank of per-tile arrival counters for a split reduction inside the
+// launch (one counter per output tile, all zero between launches), or null: a stream under
+// graph capture, more tiles than a bank has counters, all banks taken, or the switch above.
+unsigned* split_counters_for_stream(hipStream_t stream, int tiles);
 
 // The Winograd F(2x2, 3x3) point products with the output transform folded
 // in, on a direct-to-LDS tile that has such an instantiation

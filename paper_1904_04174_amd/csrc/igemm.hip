@@ -39,6 +39,7 @@
 #include <type_traits>
 
 #include "conv2d_internal.h"
+#include "split_in_launch.h"
 
 namespace conv2d {
 namespace {
@@ -178,7 +179,9 @@ __global__ __launch_bounds__(256) void split_reduce_kernel(const float* __restri
 template <class T, bool OUT_BF16>
 __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
                                                               const int slices_per_split,
-                                                              const int flush_slices) {
+                                                              const int flush_slices,
+                                                              unsigned* split_counters,
+                                                              const int reduce_groups) {
   constexpr int BM = T::BM, BN = T::BN, BK = T::BK, LD = T::LD, NT = T::NT;
   constexpr int ES = T::ES, VEC = T::VEC, AV = T::AV;
   constexpr bool SCALAR = T::SCALAR;
@@ -486,17 +489,20 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
                 slot] = acc[i][j][v];
     }
     __syncthreads();
-    if (wk > 0) return;
+    // (with the sum of the splits inside the launch, the other groups' waves come back for it)
+    if (wk > 0 && split_counters == nullptr) return;
+    if (wk == 0) {
 #pragma unroll
-    for (int g = 0; g < T::WAVES_K - 1; ++g)
+      for (int g = 0; g < T::WAVES_K - 1; ++g)
 #pragma unroll
-      for (int i = 0; i < T::TM; ++i)
+        for (int i = 0; i < T::TM; ++i)
 #pragma unroll
-        for (int j = 0; j < T::TN; ++j)
+          for (int j = 0; j < T::TN; ++j)
 #pragma unroll
-          for (int v = 0; v < 16; ++v)
-            acc[i][j][v] += red[g * PER_GROUP + ((i * T::TN + j) * 16 + v) *
-                                                    (T::WAVES_M * T::WAVES_N * 64) + slot];
+            for (int v = 0; v < 16; ++v)
+              acc[i][j][v] += red[g * PER_GROUP + ((i * T::TN + j) * 16 + v) *
+                                                      (T::WAVES_M * T::WAVES_N * 64) + slot];
+    }
   }
 
   // ---- epilogue: D tile -> NHWC output (or the fp32 partial of this split).
@@ -514,8 +520,10 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
 #pragma unroll
   for (int j = 0; j < T::TN; ++j) asm volatile("" : "+v"(bias_col[j]));
   const bool to_partial = gridDim.y > 1;
+  const bool in_launch = split_counters != nullptr;
   float* part = static_cast<float*>(p.workspace) +
                 static_cast<size_t>(blockIdx.y) * static_cast<size_t>(p.M) * p.K;
+  if (wk == 0) {
 #pragma unroll
   for (int i = 0; i < T::TM; ++i) {
 #pragma unroll
@@ -528,7 +536,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
         const int row = rbase + 8 * (v / 4) + (v % 4);
         if (row < p.M && col < p.K) {
           const size_t idx = static_cast<size_t>(row) * p.K + col;
-          if (to_partial)
+          if (in_launch)
+            splitk::split_store(part + idx, acc[i][j][v]);
+          else if (to_partial)
             part[idx] = acc[i][j][v];
           else if (OUT_BF16)
             static_cast<unsigned short*>(p.out)[idx] =
@@ -538,6 +548,20 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_kernel(const Problem p,
         }
       }
     }
+  }
+  }  // waves of k group 0
+  if (!in_launch) return;
+
+  // ---- split reduction inside the launch (split_in_launch.h), by all waves of the workgroup;
+  // the tile buffers are free (the call's first step is a barrier)
+  if constexpr (BM * BN <= 128 * 64 && BM * BN / 4 % NT == 0) {
+    // (loads in flight per thread: up to 8 vectors of 16 bytes, the chain of dependent round
+    // trips to the other XCDs' data is what the last workgroup spends its time on)
+    constexpr int PER = BM * BN / 4 / NT;
+    constexpr int AHEAD = PER == 1 ? 8 : PER == 2 ? 4 : PER <= 4 ? 3 : 2;
+    splitk::split_reduce_in_launch<BM, BN, NT, OUT_BF16, AHEAD>(
+        p, static_cast<const float*>(p.workspace), split_counters + tile, gridDim.y,
+        reduce_groups, m0, n0, reinterpret_cast<unsigned*>(lds), tid);
   }
 }
 
@@ -560,10 +584,17 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   // flush interval of the two-level summation: about sqrt(#slices)
   int flush = 1;
   while (flush * flush < per_split) ++flush;
+  // A split adds its partial sums inside the launch where it can and where it pays
+  // (split_in_launch.h), given a counter bank for the stream.
+  unsigned* counters = nullptr;
+  if (T::BM * T::BN / 4 % T::NT == 0 &&
+      splitk::split_in_launch_pays(p, T::BM, T::BN, splits, OUT_BF16))
+    counters = split_counters_for_stream(stream, tiles_m * tiles_n);
   hipLaunchKernelGGL((igemm_kernel<T, OUT_BF16>), dim3(tiles_m * tiles_n, splits), dim3(T::NT),
-                     lds_bytes, stream, p, per_split, flush);
+                     lds_bytes, stream, p, per_split, flush, counters,
+                     split_reduce_groups(p.M * p.K, splits));
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || splits == 1) return e;
+  if (e != hipSuccess || splits == 1 || counters) return e;
   return launch_split_reduce(static_cast<const float*>(p.workspace), p.out, p.M * p.K, splits,
                              OUT_BF16, p.bias, p.relu, p.K, stream);
 }

@@ -67,6 +67,7 @@
 
 #include "buffer_lds.h"
 #include "conv2d_internal.h"
+#include "split_in_launch.h"
 
 namespace conv2d {
 namespace dma {  // named namespace: the kernels' host stubs need external linkage
@@ -827,8 +828,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
         if (row < p.M && col < p.K) {
           const size_t idx = static_cast<size_t>(row) * p.K + col;
           if (in_launch)
-            __hip_atomic_store(part + idx, acc[i][j][v], __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
+            splitk::split_store(part + idx, acc[i][j][v]);
           else if (to_partial)
             part[idx] = acc[i][j][v];
           else if (OUT_BF16)
@@ -846,115 +846,13 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_dma_kernel(const Problem 
   }
   if (!in_launch) return;
 
-  // ---- split reduction inside the launch.  Every workgroup of a tile counts itself in after
-  // its partial sums have been written; the one that finds all others counted adds the tile's
-  // partial sums in split order (so the result does not depend on which one it is), applies the
-  // epilogue and stores the output.  Nobody waits for anybody.  The workgroups of a tile run
-  // on different XCDs, whose L2 caches do not see each other's lines: the partial sums are
-  // written and read with device-scope coherent accesses (sc1), and a workgroup counts itself
-  // in only after all of its stores have been acknowledged.  The counter is left at zero for
-  // the next launch.
-  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // this wave's partial sums (and loads past the end)
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-  unsigned* arrived = reinterpret_cast<unsigned*>(ring);  // the ring is free from here on
-  const unsigned nsplits = gridDim.y;
-  if (tid == 0) {
-    unsigned* counter = split_counters + tile;
-    const unsigned before =
-        __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (before == nsplits - 1)
-      __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    *arrived = before;
-  }
-  __syncthreads();
-  if (*arrived != nsplits - 1) return;
-
-  // Only tiles of up to 128x64 get here (the host keeps larger ones on the second launch: one
-  // workgroup would read too much), so the registers below stay under what the main loop needs.
-  if constexpr (BM * BN <= 128 * 64) {
-  // 16-byte pieces of the tile, row by row: piece f = row * (BN / 4) + column quad
-  constexpr int PER = BM * BN / 4 / T::NT;  // pieces per thread
-  // splits whose loads are in flight together (fewer where six workgroups share a unit's registers)
-  constexpr int AHEAD = PER <= 4 && T::OCC <= 4 ? 3 : 2;
-  static_assert(BM * BN / 4 % T::NT == 0, "tile pieces over the threads");
-  const __amdgpu_buffer_rsrc_t part_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      partial, 0, static_cast<int>(nsplits * static_cast<unsigned>(p.M) * p.K * 4u), kRsrcFlags);
-  const int plane_bytes = p.M * p.K * 4;
-  int piece_off[PER];
-#pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    const int f = e * T::NT + tid;
-    const int row = m0 + f / (BN / 4), col = n0 + 4 * (f % (BN / 4));
-    piece_off[e] = (row < p.M && col < p.K) ? (row * p.K + col) * 4 : kOutOfRange;
-  }
-  // The order of the additions is split_reduce_kernel's, so that both ways give the same bits:
-  // `reduce_groups` sums, group g over the splits g, g + groups, ... from zero, then group 0's
-  // sum + group 1's + ...  The splits are visited in that order, AHEAD loads at a time.
-  floatx4 acc[PER], total[PER];
-#pragma unroll
-  for (int e = 0; e < PER; ++e) acc[e] = total[e] = floatx4{0.f, 0.f, 0.f, 0.f};
-  bool have_total = false;
-  int next_group = 0, next_split = 0;
-  for (unsigned done = 0; done < nsplits; done += AHEAD) {
-    uintx4 got[AHEAD][PER];
-    unsigned starts_group = 0;
-#pragma unroll
-    for (int a = 0; a < AHEAD; ++a) {
-      // (a visit past the last, like a piece outside the output, reads out of range: zeros;
-      // the range check covers the vector offset only, so the split's plane is part of it)
-      const bool live = done + a < nsplits;
-      const int plane = next_split * plane_bytes;
-      if (live) {
-        if (next_split == next_group) starts_group |= 1u << a;
-        next_split += reduce_groups;
-        if (next_split >= static_cast<int>(nsplits)) next_split = ++next_group;
-      }
-#pragma unroll
-      for (int e = 0; e < PER; ++e)
-        got[a][e] = __builtin_amdgcn_raw_buffer_load_b128(
-            part_rsrc, (live && piece_off[e] != kOutOfRange) ? piece_off[e] + plane : kOutOfRange,
-            0, 16 /* sc1 */);
-    }
-#pragma unroll
-    for (int a = 0; a < AHEAD; ++a) {
-      if (done + a >= nsplits) break;
-      if (((starts_group >> a) & 1u) && done + a > 0) {
-        // a group's sum is complete: fold it into the total
-#pragma unroll
-        for (int e = 0; e < PER; ++e) {
-          total[e] = have_total ? total[e] + acc[e] : acc[e];
-          acc[e] = floatx4{0.f, 0.f, 0.f, 0.f};
-        }
-        have_total = true;
-      }
-#pragma unroll
-      for (int e = 0; e < PER; ++e)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) acc[e][c] += __uint_as_float(got[a][e][c]);
-    }
-  }
-#pragma unroll
-  for (int e = 0; e < PER; ++e) {
-    if (piece_off[e] == kOutOfRange) continue;
-    const floatx4 sum = have_total ? total[e] + acc[e] : acc[e];
-    const int f = e * T::NT + tid;
-    const int col = n0 + 4 * (f % (BN / 4));
-    const size_t idx = static_cast<size_t>(piece_off[e]) / 4;
-    floatx4 r;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) r[c] = finish(sum[c], bias_of(p.bias, col + c, p.K), p.relu);
-    if (OUT_BF16) {
-      typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
-      uintx2 packed;
-      packed.x = to_bf16_bits(r[0]) | (static_cast<unsigned>(to_bf16_bits(r[1])) << 16);
-      packed.y = to_bf16_bits(r[2]) | (static_cast<unsigned>(to_bf16_bits(r[3])) << 16);
-      store_out(reinterpret_cast<uintx2*>(static_cast<unsigned short*>(p.out) + idx), packed);
-    } else {
-      store_out(reinterpret_cast<floatx4*>(static_cast<float*>(p.out) + idx), r);
-    }
-  }
-  }  // tiles of up to 128x64
+  // ---- split reduction inside the launch (split_in_launch.h): the ring is free from here on
+  // (the call's first step is a wait for this wave's loads past the end and a barrier)
+  constexpr int AHEAD = BM * BN / 4 / T::NT <= 4 && T::OCC <= 4 ? 3 : 2;
+  if constexpr (BM * BN <= 128 * 64)
+    splitk::split_reduce_in_launch<BM, BN, T::NT, OUT_BF16, AHEAD>(
+        p, partial, split_counters + tile, gridDim.y, reduce_groups, m0, n0,
+        reinterpret_cast<unsigned*>(ring), tid);
 }
 
 // Sum of the pieces of each tail tile, in slice order, to the output.
@@ -1028,7 +926,9 @@ int banks_taken = 0;
 std::atomic<int> split_reduce_separate{0};  // 1: always add the partial sums in a second launch
 
 // The stream's counter bank on the current device, or null.
-unsigned* split_counters_for(hipStream_t stream, int tiles) {
+}  // namespace dma
+unsigned* split_counters_for_stream(hipStream_t stream, int tiles) {
+  using namespace dma;
   if (split_reduce_separate.load(std::memory_order_relaxed) || tiles > kCountersPerBank)
     return nullptr;
   hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
@@ -1058,6 +958,7 @@ unsigned* split_counters_for(hipStream_t stream, int tiles) {
   }
   return counter_base[dev] + bank * kCountersPerBank;
 }
+namespace dma {
 
 // Bytes of the repacked filter at the head of the workspace (a multiple of 256).
 template <class T>
@@ -1141,19 +1042,13 @@ hipError_t launch_one(const Problem& p, int splits, hipStream_t stream) {
   while (flush * flush < per_split) ++flush;
   float* partial = reinterpret_cast<float*>(static_cast<unsigned char*>(p.workspace) +
                                             filter_bytes<T>(p));
-  // A uniform split adds its partial sums inside the launch where it can (whole 16-byte pieces
-  // of output rows: K a multiple of 4, an aligned output; partial sums within 2^31 bytes; a
-  // counter bank for the stream) and where it pays: the one workgroup that adds a tile's
-  // partial sums reads them at ~36 GB/s (device-coherent loads of a single compute unit,
-  // measured), so up to 96 KiB per tile cost less than the second launch's ~5 us (a 56x56x256
-  // -> 256 layer at batch 1 with 6 splits of 64x64 tiles: 45.2 -> 42.3 us; 14x14x512 -> 512 at
-  // batch 1 with 18 splits: 22.0 -> 25.3 us, so that one keeps the second launch).
+  // A uniform split adds its partial sums inside the launch where it can and where it pays
+  // (split_in_launch.h; a 56x56x256 -> 256 layer at batch 1 with 6 splits of 64x64 tiles: 45.2 ->
+  // 42.3 us; 14x14x512 -> 512 at batch 1 with 18 splits: 22.0 -> 25.3 us, so that one keeps the
+  // second launch), given a counter bank for the stream.
   unsigned* counters = nullptr;
-  if (splits > 1 && tail.wgs == 0 && p.K % 4 == 0 && T::BM * T::BN <= 128 * 64 &&
-      splits * T::BM * T::BN * 4 <= 96 * 1024 &&
-      reinterpret_cast<uintptr_t>(p.out) % (OUT_BF16 ? 8 : 16) == 0 &&
-      static_cast<unsigned long long>(splits) * p.M * p.K * 4ull < (1ull << 31))
-    counters = split_counters_for(stream, tail.n_main);
+  if (tail.wgs == 0 && splitk::split_in_launch_pays(p, T::BM, T::BN, splits, OUT_BF16))
+    counters = split_counters_for_stream(stream, tail.n_main);
   hipLaunchKernelGGL((igemm_dma_kernel<T, OUT_BF16>),
                      dim3(tail.n_main + 2 * tail.wgs, splits, batches), dim3(T::NT), 0, stream, p,
                      Kg_p, per_split, flush, bt, partial, tail, counters,

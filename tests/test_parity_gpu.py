@@ -910,8 +910,10 @@ SPLIT_IN_LAUNCH = [
 
 
 def _gather_split_variants(p):
+    """The split-reduction variants of both implicit-GEMM kernels (direct loads to LDS, and
+    loads staged through registers)."""
     return [i for i in supported_variants(p)
-            if B.conv2d_variant_name(i).startswith("igemm_dma_")
+            if B.conv2d_variant_name(i).startswith(("igemm_dma_", "igemm_f32_", "igemm_bf16_"))
             and B.conv2d_variant_name(i).endswith("_splitk")]
 
 
