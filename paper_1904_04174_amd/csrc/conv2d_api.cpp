@@ -215,9 +215,12 @@ bool supports(const Variant& v, const Problem& q) {
   if ((!is_scalar(v) && q.C % vec != 0) || 1LL * es * (q.Kg + bk) * q.K >= (1LL << 31)) return false;
   if (1LL * es * (1LL * q.N * q.H * q.W + 1LL * q.R * q.W + q.S) * q.C >= (1LL << 31)) return false;
   if (igemm_dma_tile_addressing(v.bf16, v.tile) == 0 && (q.C % bk != 0 || q.R * q.S > 31)) return false;
-  if (igemm_dma_tile_addressing(v.bf16, v.tile) == 3 &&
-      (v.split != kWhole || !igemm_dma_tile_fits(q, v.bf16, v.tile)))
-    return false;
+  if (igemm_dma_tile_addressing(v.bf16, v.tile) == 3) {
+    // patch tiles: whole tiles, or a split over the channel blocks where there are several
+    if (!igemm_dma_tile_fits(q, v.bf16, v.tile) || v.split == kTail) return false;
+    if (v.split == kSplit) return igemm_dma_tile_splits_channels(v.bf16, v.tile) && q.C / bk >= 2;
+    return true;
+  }
   if (igemm_dma_tile_native(v.bf16, v.tile) && !igemm_dma_tile_fits(q, v.bf16, v.tile)) return false;
   if (v.split == kSplit && (q.Kg + bk - 1) / bk < 2) return false;
   if (v.split == kTail) {
@@ -244,9 +247,21 @@ int split_factor(const Variant& v, const Problem& q) {
   int bm, bn, bk;
   tile_shape(v, &bm, &bn, &bk);
   const long long tiles = ceil_div_ll(q.M, bm) * ceil_div_ll(q.K, bn);
+  if (tiles == 0) return 1;  // empty batch
+  if (v.family == kDma && igemm_dma_tile_addressing(v.bf16, v.tile) == 3) {
+    // Patch tiles split their channel blocks (nine slices each): one workgroup per compute
+    // unit, no split shorter than four blocks unless that leaves a single one (a workgroup's
+    // start and its burst of partial sums cost about two blocks' time).
+    const int nblocks = q.C / bk;
+    long long s = ceil_div_ll(256, tiles);
+    const long long cap = nblocks / 4 > 2 ? nblocks / 4 : 2;
+    if (s > cap) s = cap;
+    if (s < 2) s = 2;
+    if (s > nblocks) s = nblocks;
+    return static_cast<int>(s);
+  }
   const int nslices = (q.Kg + bk - 1) / bk;
   const long long target = 256LL * occupancy(v);
-  if (tiles == 0) return 1;  // empty batch
   long long s = ceil_div_ll(target, tiles);
   const long long cap = nslices / 4 > 2 ? nslices / 4 : 2;
   if (s > cap) s = cap;

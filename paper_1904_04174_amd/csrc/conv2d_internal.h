@@ -142,6 +142,10 @@ bool igemm_dma_tile_pools(int bf16, int tile);
 // Tiles that read the filter as it lies in memory (no repacked copy, no launch before the
 // convolution); their packed filter is a plain copy.
 bool igemm_dma_tile_native(int bf16, int tile);
+// Patch tiles (kind 3) that can split the channel blocks of a tile over several workgroups (a
+// split reduction: splits * M * K fp32 partial sums in the workspace behind the repacked
+// filter): one tile per workgroup, wave tiles of up to 128 x 64.
+bool igemm_dma_tile_splits_channels(int bf16, int tile);
 // The repacked filter of a tile (slice-major, k contiguous, zero padded to whole slices) as a
 // tensor of its own: its size and the kernel that writes it from p.filt.  A launch with
 // Problem::packed_filt set to it skips its own repack.

@@ -1200,6 +1200,9 @@ struct PatchTile {
   // blocked tiles of 32-row blocks: a workgroup takes several tiles, one after the other (the
   // 16-row tiles were slower that way: 71.9 -> 81.0 us on a 112x112x128 layer at batch 16)
   static constexpr bool PERSIST = BW_ > 0 && !MF16_;
+  // A split reduction over the channel blocks (several workgroups per tile, fp32 partial sums):
+  // for tiles of one tile per workgroup whose wave tiles leave registers for it
+  static constexpr bool SPLITS = !PERSIST && (BM_ / WAVES_M_) * (BN_ / WAVES_N_) <= 128 * 64;
   // 2x2 pooling in the epilogue: blocks of 16 columns and an even number of rows, 32-row blocks
   static constexpr bool POOLS = BW_ == 16 && !MF16_ && (BM_ / 16) % 2 == 0;
   static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
@@ -1245,7 +1248,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
                                                                     const int Wp,
                                                                     const int flush_slices,
                                                                     const void* bt,
-                                                                    const int ntiles) {
+                                                                    const int ntiles,
+                                                                    const int blocks_per_split,
+                                                                    float* partial) {
   constexpr int BM = T::BM, BN = T::BN, BK = T::BK, ROWB = T::ROWB, CPR = T::CPR, SB = T::SB;
   constexpr int ES = T::ES, VEC = T::VEC, KSTEPS = T::KSTEPS;
   constexpr int TM = T::TM, TN = T::TN, NM = T::NM, NR = T::NR, MPF = T::MPF;
@@ -1291,11 +1296,22 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   };
   if constexpr (T::BW > 0) block_of(tile, blk_n, blk_p, blk_q);
   constexpr int taps = 9;
-  const int nblocks = p.C / BK;      // channel blocks
   const int Kg_p = p.Kg;             // C is a multiple of BK
-
-  const uintx4 in_rsrc = make_rsrc(p.in, 0, p.N * p.H * p.W * p.C * ES);
-  const uintx4 bt_rsrc = make_rsrc(bt, 0, p.K * Kg_p * ES);
+  // Channel blocks of this workgroup: all of them, or (gridDim.y > 1: a split reduction over
+  // the channels) those from blockIdx.y * blocks_per_split on, whose sum goes to plane
+  // blockIdx.y of `partial`.  Input and filter are then seen from the first of these channels
+  // on (channel c of a pixel is c * ES bytes into the pixel, filter row (tap, c) c rows into the
+  // tap, repacked slice (block, tap) 9 * block + tap slices in), so that nothing below changes.
+  const int first_block = T::SPLITS ? blockIdx.y * blocks_per_split : 0;
+  const int nblocks = T::SPLITS ? min(blocks_per_split, p.C / BK - first_block) : p.C / BK;
+  const bool to_partial = T::SPLITS && gridDim.y > 1;
+  const long long in_shift = 1LL * first_block * ROWB;
+  const long long bt_shift =
+      T::NATIVE ? 1LL * first_block * BK * p.K * ES : 1LL * first_block * taps * p.K * ROWB;
+  const uintx4 in_rsrc = make_rsrc(static_cast<const unsigned char*>(p.in) + in_shift, 0,
+                                   1LL * p.N * p.H * p.W * p.C * ES - in_shift);
+  const uintx4 bt_rsrc = make_rsrc(static_cast<const unsigned char*>(bt) + bt_shift, 0,
+                                   1LL * p.K * Kg_p * ES - bt_shift);
   const unsigned ring_base = __builtin_amdgcn_readfirstlane(lds_address(ring) + wave * 1024);
 
   // ---- patch loader role: entries (pass*NW + wave)*64 + lane of the patch
@@ -1362,6 +1378,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
   // (block, tap) starts at filter row tap * C + block * BK
   int nat_tap = 0, nat_block_bytes = 0;
   const int nat_tap_bytes = p.C * p.K * ES;
+  const int nat_blocks_bytes = nblocks * BK * p.K * ES;  // this workgroup's channels of a tap
   // Moves the filter load position one slice on (past the last slice: to the first again).
   auto next_filter_slice = [&]() {
     if constexpr (T::NATIVE) {
@@ -1369,7 +1386,7 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
       const bool wrap = ++nat_tap == taps;
       nat_tap = wrap ? 0 : nat_tap;
       const int next_block = nat_block_bytes + BK * p.K * ES;
-      nat_block_bytes = wrap ? (next_block >= nat_tap_bytes ? 0 : next_block) : nat_block_bytes;
+      nat_block_bytes = wrap ? (next_block >= nat_blocks_bytes ? 0 : next_block) : nat_block_bytes;
       k_next_bytes = wrap ? nat_block_bytes : k_next_bytes + nat_tap_bytes;
     } else {
       k_next_bytes = k_next_bytes >= k_last_bytes ? 0 : k_next_bytes + k_slice_bytes;
@@ -1786,7 +1803,28 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
     // the row of 16 lanes); then the first store covers the pixels with px & 8 == 0, the second
     // the others.
     constexpr int kStageRow = T::WN * 2 + 16;  // bytes of a staged pixel: its features + a pad
-    if (OUT_BF16 && T::WN == 64 && (p.K & 7) == 0 &&
+    if (to_partial) {
+      // a split over the channels: the sums as they are, to this split's plane of `partial`
+      // (ordinary stores: the kernel that adds the planes reads them next)
+      float* part = partial + static_cast<size_t>(blockIdx.y) * p.M * p.K;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = out_row(i, lr);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int col = n0 + wn * T::WN + j * BLK + lk * 4;
+          if (row < 0) continue;
+          const size_t idx = static_cast<size_t>(row) * p.K + col;
+          if (vec_ok && col + 3 < p.K) {
+            *reinterpret_cast<floatx4*>(part + idx) = acc[i][j];
+          } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              if (col + v < p.K) part[idx + v] = acc[i][j][v];
+          }
+        }
+      }
+    } else if (OUT_BF16 && T::WN == 64 && (p.K & 7) == 0 &&
         T::NW * T::WM * kStageRow <= T::LDS_BYTES) {
       // bf16 output: a lane's 8-byte pieces (four features of a pixel) are gathered through LDS
       // into whole 128-byte lines (64 features of a pixel), 8 pixels per store instruction.  The
@@ -1954,7 +1992,9 @@ __global__ __launch_bounds__(T::NT, T::OCC) void igemm_patch_kernel(const Proble
         }
         if (row_ok && col < p.K) {
           const size_t idx = static_cast<size_t>(row) * p.K + col;
-          if (OUT_BF16)
+          if (to_partial)  // a split over the channels: the sum as it is, to its plane
+            partial[static_cast<size_t>(blockIdx.y) * p.M * p.K + idx] = acc[i][j][v];
+          else if (OUT_BF16)
             store_out(static_cast<unsigned short*>(p.out) + idx,
                       to_bf16_bits(finish(acc[i][j][v], bcol, p.relu)));
           else
@@ -2009,8 +2049,29 @@ int patch_tiles_m(const Problem& p) {
   return (p.M + T::BM - 1) / T::BM;
 }
 
+// Repacked filter (none for native tiles), then the partial sums of a split over the channels.
+template <class T>
+size_t workspace_bytes_patch(const Problem& p, int splits) {
+  const size_t filter =
+      T::NATIVE ? 0 : (static_cast<size_t>(p.Kg) * p.K * T::ES + 255) / 256 * 256;
+  if (splits <= 1 || !T::SPLITS) return filter;
+  return filter + static_cast<size_t>(splits) * p.M * p.K * sizeof(float);
+}
+
+// Split of the channel blocks of a patch tile over `splits` workgroups per tile: blocks per
+// split, and the number of splits that leaves none empty (1 for tiles that do not split).
+template <class T>
+int patch_blocks_per_split(const Problem& p, int* splits) {
+  const int nblocks = p.C / T::BK;
+  int s = !T::SPLITS || *splits < 1 ? 1 : *splits;
+  if (s > nblocks) s = nblocks;
+  const int per = (nblocks + s - 1) / s;
+  *splits = (nblocks + per - 1) / per;
+  return per;
+}
+
 template <class T, bool OUT_BF16>
-hipError_t launch_patch_one(const Problem& p, hipStream_t stream) {
+hipError_t launch_patch_one(const Problem& p, int splits, hipStream_t stream) {
   // 1. filter -> Bt[slice][K][BK], channel block by channel block, unless packed before
   // (native tiles read the filter as it is; their "packed" filter is a plain copy)
   const void* bt = p.packed_filt ? p.packed_filt : (T::NATIVE ? p.filt : p.workspace);
@@ -2038,22 +2099,24 @@ hipError_t launch_patch_one(const Problem& p, hipStream_t stream) {
   const int patch_width = T::BW > 0 ? T::PW : p.Q + p.S - 1;
   const int resident = kComputeUnits * T::OCC;
   const int grid = T::PERSIST && tiles > resident ? resident : tiles;
-  hipLaunchKernelGGL((igemm_patch_kernel<T, OUT_BF16>), dim3(grid), dim3(T::NT), 0, stream, p,
-                     p.P + p.R - 1, patch_width, flush, bt, tiles);
-  return hipGetLastError();
+  // 3. with a split over the channels: fp32 partial sums behind the repacked filter, added by
+  // split_reduce_kernel
+  const int per_split = patch_blocks_per_split<T>(p, &splits);
+  float* partial = reinterpret_cast<float*>(static_cast<unsigned char*>(p.workspace) +
+                                            workspace_bytes_patch<T>(p, 1));
+  hipLaunchKernelGGL((igemm_patch_kernel<T, OUT_BF16>), dim3(grid, splits), dim3(T::NT), 0, stream,
+                     p, p.P + p.R - 1, patch_width, flush, bt, tiles, per_split, partial);
+  e = hipGetLastError();
+  if (e != hipSuccess || splits == 1) return e;
+  return launch_split_reduce(partial, p.out, p.M * p.K, splits, OUT_BF16, p.bias, p.relu, p.K,
+                             stream);
 }
 
 template <class T>
-hipError_t launch_patch(const Problem& p, int, hipStream_t stream) {
+hipError_t launch_patch(const Problem& p, int splits, hipStream_t stream) {
   if (!patch_fits<T>(p)) return hipErrorInvalidValue;
-  if (T::BF16 && p.out_bf16) return launch_patch_one<T, T::BF16>(p, stream);
-  return launch_patch_one<T, false>(p, stream);
-}
-
-template <class T>
-size_t workspace_bytes_patch(const Problem& p, int) {
-  if (T::NATIVE) return 0;
-  return (static_cast<size_t>(p.Kg) * p.K * T::ES + 255) / 256 * 256;
+  if (T::BF16 && p.out_bf16) return launch_patch_one<T, T::BF16>(p, splits, stream);
+  return launch_patch_one<T, false>(p, splits, stream);
 }
 
 // Extra shape condition of the native gather tiles: 16-byte chunks of a filter row.
@@ -2069,6 +2132,7 @@ struct TileEntry {
   hipError_t (*wino)(const Problem&, hipStream_t);  // fused Winograd products, or null
   bool pools = false;                               // 2x2 pooling in the epilogue
   bool native = false;                              // reads the filter as it lies: no repack
+  bool splits_channels = false;                     // patch tiles: PatchTile::SPLITS
 };
 
 #define CONV2D_PATCH_TILE(dt, isbf, bm, bn, wm, wn, rows, two, occ)                              \
@@ -2076,7 +2140,8 @@ struct TileEntry {
     PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>::BK, occ, 3,                                 \
     &launch_patch<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>>,                              \
     &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>>,                     \
-    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>>, nullptr }
+    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>>, nullptr, false, false,         \
+    PatchTile<isbf, bm, bn, wm, wn, rows, two, occ>::SPLITS }
 
 // 16-row MFMA blocks (tile heights that are multiples of 7 * 32)
 #define CONV2D_PATCH_TILE_M16(dt, isbf, bm, bn, wm, wn, rows, occ)                               \
@@ -2084,14 +2149,16 @@ struct TileEntry {
     PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, 0, true>::BK, occ, 3,                      \
     &launch_patch<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, 0, true>>,                   \
     &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, 0, true>>,          \
-    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, 0, true>>, nullptr }
+    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, 0, true>>, nullptr, false,     \
+    false, PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, 0, true>::SPLITS }
 
 #define CONV2D_PATCH_TILE_M16B(dt, isbf, bm, bn, wm, wn, rows, occ, bw)                          \
   { "igemm_patch_" dt "_" #bm "x" #bn "_w" #wm "x" #wn "_p" #rows "_b" #bw "_m16", bm, bn,      \
     PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true>::BK, occ, 3,                     \
     &launch_patch<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true>>,                  \
     &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true>>,         \
-    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true>>, nullptr }
+    &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true>>, nullptr, false,    \
+    false, PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true>::SPLITS }
 
 // 16-row tiles that read the filter as it lies in memory (transposing LDS reads): bw = 0 for
 // consecutive pixels
@@ -2101,7 +2168,7 @@ struct TileEntry {
     &launch_patch<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true, true>>,            \
     &workspace_bytes_patch<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true, true>>,   \
     &patch_fits<PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true, true>>, nullptr,     \
-    false, true }
+    false, true, PatchTile<isbf, bm, bn, wm, wn, rows, false, occ, bw, true, true>::SPLITS }
 
 // blocked patch tiles of 32-row blocks that read the filter as it lies in memory
 #define CONV2D_PATCH_TILE_BN(dt, isbf, bm, bn, wm, wn, rows, two, occ, bw)                       \
@@ -2228,6 +2295,9 @@ bool igemm_dma_tile_fits(const Problem& p, int bf16, int tile) {
 bool igemm_dma_tile_has_wino(int bf16, int tile) { return entry(bf16, tile).wino != nullptr; }
 bool igemm_dma_tile_pools(int bf16, int tile) { return entry(bf16, tile).pools; }
 bool igemm_dma_tile_native(int bf16, int tile) { return entry(bf16, tile).native; }
+bool igemm_dma_tile_splits_channels(int bf16, int tile) {
+  return entry(bf16, tile).splits_channels;
+}
 size_t igemm_dma_packed_filter_bytes(const Problem& p, int bf16, int tile) {
   const TileEntry& t = entry(bf16, tile);
   if (t.native)  // a plain copy of the filter

@@ -968,6 +968,58 @@ def test_split_reduction_inside_the_launch(torch_cuda, oracle, case, in_dtype, o
         B.conv2d_debug_split_reduce_separate(0)
 
 
+PATCH_CHANNEL_SPLIT = [
+    (2, 14, 14, 512, 136, 3, 3, 1, 1, wl.PAD_SAME),    # 16 / 32 channel blocks, ragged K tile
+    (1, 33, 31, 96, 64, 3, 3, 1, 1, wl.PAD_VALID),     # 3 / 6 blocks: an uneven last split
+    (3, 12, 13, 64, 40, 3, 3, 1, 1, wl.PAD_SAME),      # tiles span images, K % 8 == 0 only
+]
+
+
+@pytest.mark.parametrize("case", PATCH_CHANNEL_SPLIT)
+@pytest.mark.parametrize("in_dtype,out_dtype", [(B.F32, B.F32), (B.BF16, B.F32), (B.BF16, B.BF16)])
+def test_patch_tiles_split_over_channels(torch_cuda, oracle, case, in_dtype, out_dtype):
+    """The patch tiles with the channel blocks of a tile split over several workgroups (fp32
+    partial sums, added in a fixed order): against the oracle with a fused bias and ReLU, twice
+    on one workspace with the same bits."""
+    torch = torch_cuda
+    dev = torch.device("cuda:0")
+    n, h, w, c, k, r, s, sr, sc, pad = case
+    p = _params(case, in_dtype, out_dtype)
+    ids = [i for i in supported_variants(p)
+           if B.conv2d_variant_name(i).startswith("igemm_patch_")
+           and B.conv2d_variant_name(i).endswith("_splitk")]
+    assert ids, "no split patch variant supports %s" % (case,)
+    tol = TOL_F32 if in_dtype == B.F32 else TOL_BF16
+    in_dt = torch.float32 if in_dtype == B.F32 else torch.bfloat16
+    out_dt = torch.float32 if out_dtype == B.F32 else torch.bfloat16
+    g = B.conv2d_get_geometry(p)
+    x, f = wl.make_case((n, h, w, c), (r, s, c, k), "uniform", 7300 + sum(case))
+    if in_dtype == B.BF16:
+        x, f = wl.round_to_bf16(x)[0], wl.round_to_bf16(f)[0]
+    bias = np.linspace(-3.0, 3.0, k).astype(np.float32)
+    want = oracle.forward_bias_act_f32(x, f, bias, True, (sr, sc), pad)
+    xd = torch.from_numpy(x).to(dev).to(in_dt)
+    fd = torch.from_numpy(f).to(dev).to(in_dt)
+    bd = torch.from_numpy(bias).to(dev)
+    try:
+        for vid in ids:
+            _say("channel split %s %s" % (case, B.conv2d_variant_name(vid)))
+            ws = torch.empty(max(B.conv2d_workspace_size(p, vid), 16), dtype=torch.uint8, device=dev)
+            B.conv2d_debug_force_variant(vid)
+            res = []
+            for rep in range(2):
+                out = torch.full((n, g.out_rows, g.out_cols, k), float("nan"), dtype=out_dt,
+                                 device=dev)
+                B.conv2d_forward_bias_act(p, xd, fd, bd, B.ACT_RELU, out=out, workspace=ws)
+                torch.cuda.synchronize()
+                res.append(out.float().cpu().numpy())
+                assert not np.isnan(res[-1]).any(), B.conv2d_variant_name(vid)
+                assert rel_err(res[-1], want) <= tol, B.conv2d_variant_name(vid)
+            assert np.array_equal(res[0], res[1]), B.conv2d_variant_name(vid)
+    finally:
+        B.conv2d_debug_force_variant(None)
+
+
 def test_split_reduction_inside_the_launch_on_two_streams(torch_cuda, oracle):
     """Launches with the reduction inside run at the same time on two streams (each stream has
     its own counters) and are repeated back to back on each: every output matches the oracle."""
