@@ -200,6 +200,26 @@ def test_split_reduction_variants_state_their_workspace():
             assert not B.conv2d_variant_supports(p1, v)
 
 
+def test_patch_tiles_split_their_channel_blocks():
+    """A patch tile's split reduction runs over its channel blocks: at most one split per four
+    blocks, the partial sums behind the repacked filter (none for a filter read as it lies);
+    tiles that walk several tiles per workgroup, and shapes with a single block, do not split."""
+    names = [B.conv2d_variant_name(v) for v in range(B.conv2d_num_variants())]
+    p = B.params_of_layer(wl.LAYERS["V14-N16"], B.BF16, B.F32)       # C = 512: 16 blocks of 32
+    plane = 4 * 16 * 14 * 14 * 512
+    nat = names.index("igemm_patch_bf16_224x128_w2x2_p384_m16_nat_splitk")
+    assert B.conv2d_variant_supports(p, nat)
+    assert B.conv2d_workspace_size(p, nat) == 4 * plane
+    packed = names.index("igemm_patch_bf16_224x128_w2x2_p384_m16_splitk")
+    assert B.conv2d_workspace_size(p, packed) == 4 * plane + 2 * 9 * 512 * 512
+    assert not B.conv2d_variant_supports(
+        p, names.index("igemm_patch_bf16_128x64_w2x2_p256_b16_nat_splitk"))
+    one_block = B.make_params(2, 14, 14, 32, 64, 3, 3, 1, 1, wl.PAD_SAME, B.BF16, B.F32)
+    assert B.conv2d_variant_supports(
+        one_block, names.index("igemm_patch_bf16_224x128_w2x2_p384_m16_nat"))
+    assert not B.conv2d_variant_supports(one_block, nat)
+
+
 def test_workspace_is_checked_before_any_launch():
     # a variant that needs scratch: too little of it, or a misaligned pointer, is an error status
     p = B.params_of_layer(wl.LAYERS["V14-N1"])
