@@ -21,7 +21,7 @@
 // 2w + 1 (32 pixels) and all 64 features: two 32x32x2 fp32 MFMA accumulators.
 // Per step of two reduction indices (both in one window row) a lane reads one
 // patch value (its pixel, value 2 * jj + lane / 32 of the row) and two filter
-// values; fragments are fetched one step ahead.  The patch's row pitch is chosen so that the 32 pixels of a wave
+// values; fragments are fetched two steps ahead.  The patch's row pitch is chosen so that the 32 pixels of a wave
 // fall into distinct LDS banks.
 #include "conv2d_internal.h"
 
@@ -57,15 +57,15 @@ RowPlan make_plan(const Problem& p) {
     while ((1LL * p.sr * pl.pitch) % 64 != 32 && pl.pitch < pl.PWE + 64) ++pl.pitch;
   if ((1LL * p.sr * pl.pitch) % 64 != 32) pl.pitch = pl.PWE | 1;
   pl.steps = p.R * ((p.S * p.C + 1) / 2);  // window rows padded to an even length
-  pl.frows = 2 * pl.steps + 2;
+  pl.frows = 2 * pl.steps + 4;   // fragments are fetched up to two steps past the end
   pl.tiles_x = (p.Q + kBW - 1) / kBW;
   pl.tiles_y = (p.P + kBH - 1) / kBH;
   pl.tiles_n = (p.K + kBN - 1) / kBN;
   pl.tiles_m = p.N * pl.tiles_y * pl.tiles_x;
   pl.tiles = 1LL * pl.tiles_m * pl.tiles_n;
-  // (one more patch row: the fragment fetched after the last step lies in the row after the
+  // (three more patch rows: the fragments fetched after the last step lie in the rows after the
   // window; +4: the pad value of an odd window row may lie one past the last value of a row)
-  const long long lds = 4LL * (1LL * pl.frows * kBN + 1LL * (pl.PH + 1) * pl.pitch + 4);
+  const long long lds = 4LL * (1LL * pl.frows * kBN + 1LL * (pl.PH + 3) * pl.pitch + 4);
   pl.lds_bytes = lds > (1LL << 30) ? (1 << 30) : static_cast<int>(lds);
   int occ = pl.lds_bytes > 0 ? (160 * 1024) / pl.lds_bytes : 1;
   occ = occ < 1 ? 1 : (occ > 3 ? 3 : occ);
@@ -235,24 +235,42 @@ __global__ __launch_bounds__(kThreads, 2) void row_gather_kernel(const Problem p
     // length the upper half's last value of a row is a pad: zero filter row, value forced to 0.
     // (The scalar bookkeeping of a step is kept to a few dependent instructions: a wave issues
     // them one after the other between its products.)
+    // Fragments are fetched two steps ahead, into three sets of registers that take turns (X, Y,
+    // Z: the step loop is unrolled by three, so no set is copied): with a single step ahead, or
+    // with copies from set to set, the reads' latency lies on a wave's path from one step to
+    // the next.  A pad value is forced to zero when its set is multiplied, a step or two after
+    // it was read.  The fragments read past the last step are never multiplied.
     int jj = 0, off = 0;
-    float a_cur = (odd_pad && row_steps == 1) ? 0.f : lds_p[a_lane];
-    float b0_cur = lds_f[b_base], b1_cur = lds_f[b_base + 64];
-    for (int s = 0; s < pl.steps; ++s) {
-      // fragments of the next step (past the end: zero rows of the filter and the patch row
-      // after the window, which LDS has room for)
+    struct Frag { float a, b0, b1; bool pad; };
+    auto read_frag = [&](int step, Frag& f) {
+      f.pad = odd_pad && jj == row_steps - 1;
+      f.a = lds_p[a_lane + off];
+      f.b0 = lds_f[b_base + step * 128];
+      f.b1 = lds_f[b_base + step * 128 + 64];
       ++jj; off += 2;
       if (jj == row_steps) { jj = 0; off += row_skip; }
-      const bool pad = odd_pad && jj == row_steps - 1;
-      const float a_ld = lds_p[a_lane + off];
-      const float b0_nxt = lds_f[b_base + (s + 1) * 128];
-      const float b1_nxt = lds_f[b_base + (s + 1) * 128 + 64];
-      __builtin_amdgcn_sched_barrier(0);  // the reads above are issued before this step's products
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur, b0_cur, acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur, b1_cur, acc1, 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);  // and waited for only after them
-      a_cur = pad ? 0.f : a_ld; b0_cur = b0_nxt; b1_cur = b1_nxt;
+    };
+    auto multiply = [&](const Frag& f) {
+      const float a = f.pad ? 0.f : f.a;
+      __builtin_amdgcn_sched_barrier(0);  // the reads before are issued ahead of the products
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, f.b0, acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, f.b1, acc1, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    Frag X, Y, Z;
+    read_frag(0, X);
+    read_frag(1, Y);
+    const int whole = pl.steps / 3 * 3;
+    for (int s = 0; s < whole; s += 3) {
+      read_frag(s + 2, Z);
+      multiply(X);
+      read_frag(s + 3, X);
+      multiply(Y);
+      read_frag(s + 4, Y);
+      multiply(Z);
     }
+    if (pl.steps - whole >= 1) multiply(X);
+    if (pl.steps - whole == 2) multiply(Y);
 
     lds_barrier();  // every wave has read this tile's patch and filter
     if (has_next) {
@@ -329,7 +347,7 @@ RowPlanB make_plan_b(const Problem& p) {
   pl.row2 = (row_len + 7) / 8 * 8;
   pl.row_steps = pl.row2 / 8;
   pl.steps = p.R * pl.row_steps;
-  pl.kpad = p.R * pl.row2 + 8;  // (+ the step fetched after the last one)
+  pl.kpad = p.R * pl.row2 + 16;  // (+ the two steps fetched after the last one)
   pl.wrow = pl.kpad / 2;
   while (pl.wrow % 32 != 2) ++pl.wrow;
   pl.tiles_x = (p.Q + kBW - 1) / kBW;
@@ -339,7 +357,7 @@ RowPlanB make_plan_b(const Problem& p) {
   pl.tiles = 1LL * pl.tiles_m * pl.tiles_n;
   // (one more patch row and 16 values: the fragment fetched after the last step lies in the row
   // after the window, a padded window row may reach past the end of a patch row)
-  const long long lds = 4LL * kBN * pl.wrow + 2LL * ((pl.PH + 1LL) * pl.pitch + 16);
+  const long long lds = 4LL * kBN * pl.wrow + 2LL * ((pl.PH + 3LL) * pl.pitch + 16);
   pl.lds_bytes = lds > (1LL << 30) ? (1 << 30) : static_cast<int>((lds + 15) / 16 * 16);
   int occ = pl.lds_bytes > 0 ? (160 * 1024) / pl.lds_bytes : 1;
   occ = occ < 1 ? 1 : (occ > 3 ? 3 : occ);
@@ -490,26 +508,43 @@ __global__ __launch_bounds__(kThreads, 2) void row_gather_bf16_kernel(const Prob
     }
 
     floatx16 acc0 = {}, acc1 = {};
+    // Fragments two steps ahead in three sets of registers that take turns, as in the fp32
+    // kernel; the values past the end of a window row are masked when the set is multiplied.
     int jj = 0, off = 0;
-    uintx2 a_cur = read_a(0);
-    if (row_steps == 1) { a_cur.x &= mask0; a_cur.y &= mask1; }
-    uintx2 b0_cur = read_b(b_base0, 0), b1_cur = read_b(b_base1, 0);
-    for (int s = 0; s < pl.steps; ++s) {
+    struct Frag { uintx2 a, b0, b1; bool last; };
+    auto read_frag = [&](int step, Frag& f) {
+      f.last = jj == row_steps - 1;
+      f.a = read_a(off);
+      f.b0 = read_b(b_base0, step);
+      f.b1 = read_b(b_base1, step);
       ++jj; off += 8;
       if (jj == row_steps) { jj = 0; off += pl.pitch - row2; }
-      const bool last = jj == row_steps - 1;
-      uintx2 a_ld = read_a(off);
-      const uintx2 b0_nxt = read_b(b_base0, s + 1), b1_nxt = read_b(b_base1, s + 1);
+    };
+    auto multiply = [&](const Frag& f) {
+      uintx2 a = f.a;
+      a.x &= f.last ? mask0 : 0xffffffffu;
+      a.y &= f.last ? mask1 : 0xffffffffu;
       __builtin_amdgcn_sched_barrier(0);
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(shortx4, a_cur),
-                                                      __builtin_bit_cast(shortx4, b0_cur), acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(shortx4, a_cur),
-                                                      __builtin_bit_cast(shortx4, b1_cur), acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(shortx4, a),
+                                                      __builtin_bit_cast(shortx4, f.b0), acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(shortx4, a),
+                                                      __builtin_bit_cast(shortx4, f.b1), acc1, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      a_ld.x &= last ? mask0 : 0xffffffffu;
-      a_ld.y &= last ? mask1 : 0xffffffffu;
-      a_cur = a_ld; b0_cur = b0_nxt; b1_cur = b1_nxt;
+    };
+    Frag X, Y, Z;
+    read_frag(0, X);
+    read_frag(1, Y);
+    const int whole = pl.steps / 3 * 3;
+    for (int s = 0; s < whole; s += 3) {
+      read_frag(s + 2, Z);
+      multiply(X);
+      read_frag(s + 3, X);
+      multiply(Y);
+      read_frag(s + 4, Y);
+      multiply(Z);
     }
+    if (pl.steps - whole >= 1) multiply(X);
+    if (pl.steps - whole == 2) multiply(Y);
 
     lds_barrier();
     if (has_next) {
