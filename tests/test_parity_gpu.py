@@ -1096,6 +1096,69 @@ def test_filter_in_registers_kernel_bf16(torch_cuda, oracle, case):
         B.make_params(n, h, w, c, 192 - c, r, s, sr, sc, pad, B.BF16, B.F32), vid)
 
 
+def _random_shape(rng):
+    """A layer shape drawn over the ranges the workloads span (1x1 to 7x7 windows, strides up to
+    3, 1 to 640 channels and features with and without the 16-byte alignment, small and wide
+    images), sized so that the oracle takes milliseconds."""
+    r = int(rng.choice([1, 1, 3, 3, 3, 5, 7]))
+    s = r if rng.random() < 0.8 else int(rng.choice([1, 3, 5]))
+    c = int(rng.choice([1, 3, 4, 8, 16, 24, 32, 64, 96, 128, 200, 256, 512, 640]))
+    k = int(rng.choice([1, 8, 16, 24, 40, 64, 100, 128, 192, 256, 512, 640]))
+    budget = 2.5e8 / (2.0 * r * s * c * k)          # output pixels the oracle can afford
+    hw_max = int(min(70, max(r + 1, (budget ** 0.5))))
+    h = int(rng.integers(max(1, min(r, hw_max)), hw_max + 1))
+    w = int(rng.integers(max(1, min(s, hw_max)), hw_max + 1))
+    n = int(max(1, min(9, budget // max(1, h * w))))
+    n = int(rng.integers(1, n + 1))
+    sr = int(rng.choice([1, 1, 1, 2, 2, 3]))
+    sc = sr if rng.random() < 0.85 else int(rng.choice([1, 2]))
+    pad = wl.PAD_SAME if rng.random() < 0.6 or h < r or w < s else wl.PAD_VALID
+    return (n, h, w, c, k, r, s, sr, sc, pad)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_shapes_through_the_selector_and_forced_variants(torch_cuda, oracle, seed):
+    """Shapes that no other test names: the selector's pick and three supported variants drawn
+    at random, fp32 and bf16 input, against the oracle with a fused bias and ReLU."""
+    torch = torch_cuda
+    rng = np.random.default_rng(9100 + seed)
+    for trial in range(8):
+        case = _random_shape(rng)
+        n, h, w, c, k, r, s, sr, sc, pad = case
+        in_dtype = B.BF16 if rng.random() < 0.4 else B.F32
+        out_dtype = B.BF16 if in_dtype == B.BF16 and rng.random() < 0.3 else B.F32
+        p = _params(case, in_dtype, out_dtype)
+        x, f = wl.make_case((n, h, w, c), (r, s, c, k), "uniform", 9200 + 31 * seed + trial)
+        if in_dtype == B.BF16:
+            x, f = wl.round_to_bf16(x)[0], wl.round_to_bf16(f)[0]
+        bias = np.linspace(-1.5, 1.5, k).astype(np.float32)
+        want = oracle.forward_bias_act_f32(x, f, bias, True, (sr, sc), pad)
+        tol = TOL_F32 if in_dtype == B.F32 else TOL_BF16
+        ids = supported_variants(p)
+        picks = [None] + [int(v) for v in rng.choice(ids, size=min(3, len(ids)), replace=False)]
+        dev = torch.device("cuda:0")
+        in_dt = torch.float32 if in_dtype == B.F32 else torch.bfloat16
+        out_dt = torch.float32 if out_dtype == B.F32 else torch.bfloat16
+        xd = torch.from_numpy(x).to(dev).to(in_dt)
+        fd = torch.from_numpy(f).to(dev).to(in_dt)
+        bd = torch.from_numpy(bias).to(dev)
+        g = B.conv2d_get_geometry(p)
+        try:
+            for vid in picks:
+                name = "selector" if vid is None else B.conv2d_variant_name(vid)
+                _say("random shape %s dtype %d/%d %s" % (case, in_dtype, out_dtype, name))
+                B.conv2d_debug_force_variant(vid)
+                out = torch.full((n, g.out_rows, g.out_cols, k), float("nan"), dtype=out_dt,
+                                      device=dev)
+                B.conv2d_forward_bias_act(p, xd, fd, bd, B.ACT_RELU, out=out)
+                torch.cuda.synchronize()
+                res = out.float().cpu().numpy()
+                assert not np.isnan(res).any(), (case, name)
+                assert rel_err(res, want) <= tol, (case, name, rel_err(res, want))
+        finally:
+            B.conv2d_debug_force_variant(None)
+
+
 def test_library_loaded_before_torch(torch_cuda):
     """A process that touches the library before it imports torch must not end up with two HIP
     runtimes (torch ships its own): the binding loads torch's first.  Run in a child process,
