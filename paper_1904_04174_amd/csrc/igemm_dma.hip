@@ -925,8 +925,8 @@ BankOwner bank_owner[kCounterBanks];
 int banks_taken = 0;
 std::atomic<int> split_reduce_separate{0};  // 1: always add the partial sums in a second launch
 
-// The stream's counter bank on the current device, or null.
 }  // namespace dma
+// The stream's counter bank on the current device, or null.
 unsigned* split_counters_for_stream(hipStream_t stream, int tiles) {
   using namespace dma;
   if (split_reduce_separate.load(std::memory_order_relaxed) || tiles > kCountersPerBank)
