@@ -93,6 +93,8 @@ SMALL = [
     (3, 12, 13, 32, 40, 3, 3, 1, 1, wl.PAD_VALID),     # the same without padding, H != W
     (2, 19, 17, 64, 136, 1, 1, 2, 2, wl.PAD_SAME),     # 1x1, stride 2, a ragged second slab of features
     (3, 23, 11, 32, 256, 1, 1, 1, 1, wl.PAD_VALID),    # 1x1, many tiles of 64 pixels per workgroup
+    (2, 13, 14, 256, 72, 1, 1, 1, 1, wl.PAD_SAME),     # 1x1, many channels (wide slices), ragged slab
+    (3, 17, 9, 384, 64, 1, 1, 2, 2, wl.PAD_VALID),     # the same at stride 2, three slices of 128
 ]
 
 
